@@ -1,0 +1,381 @@
+"""Pins for the CPU checker's whole-model code and AMP simulator (no GPU).
+
+  * whole-model gradients: central finite differences of the instance loss;
+  * the message-passing simulator at max_active_keys = 1 with one update per
+    instance equals plain per-instance SGD (Section 3 and its footnote), and
+    for the MLP with min_update_frequency = m equals minibatch-m SGD;
+  * with learning rate 0 any schedule gives the losses of a plain forward;
+  * sparse GGNN propagation equals the dense (N H) x (N H) formulation
+    (Section 5, results);
+  * invariants of Section 3 / 4 under asynchronous schedules;
+  * the replay driver reproduces a recorded run and refuses illegal orders.
+"""
+import copy
+
+import numpy as np
+import pytest
+
+from oracle import amp, direct
+from paper_1705_09786_amd import synth
+
+TINY = {
+    "mlp": dict(d_in=5, hidden=4, n_class=3),
+    "rnn": dict(vocab=6, emb=3, hidden=4, n_class=3),
+    "tree": dict(vocab=11, emb=4, hidden=3, n_class=3),
+    "ggnn": dict(n_node_types=4, hidden=3, n_edge_types=4, n_steps=2),
+}
+
+
+def tiny_data(model, n, seed=3):
+    d = TINY[model]
+    if model == "mlp":
+        return synth.make_mlp(n, seed, d)
+    if model == "rnn":
+        return synth.make_rnn(n, seed, d, min_len=1, max_len=5)
+    if model == "tree":
+        return synth.make_tree(n, seed, d, min_leaves=2, max_leaves=5, teacher=False)
+    return synth.make_ggnn(n, seed, d, min_nodes=3, max_nodes=6)[0]
+
+
+def tiny_params(model, seed=11, scale=3.0):
+    fp = synth.init_params(model, TINY[model], seed)
+    rng = np.random.default_rng(seed)
+    # larger weights and non-zero biases so that every term matters
+    return [(scale * v + 0.1 * rng.standard_normal(v.shape)).astype(np.float32) for v in fp]
+
+
+MODELS = ["mlp", "rnn", "tree", "ggnn"]
+
+
+@pytest.mark.parametrize("model", MODELS)
+def test_direct_gradients_by_finite_differences(model):
+    dims = TINY[model]
+    P = direct.unpack(model, dims, tiny_params(model))
+    for inst in tiny_data(model, 3):
+        res = direct.MODELS[model](P, inst, dims)
+        eps = 1e-6
+        for k, node in enumerate(P):
+            for name, w in node.items():
+                num = np.zeros_like(w)
+                flat, nflat = w.reshape(-1), num.reshape(-1)
+                for i in range(flat.size):
+                    old = flat[i]
+                    flat[i] = old + eps
+                    lp = direct.MODELS[model](P, inst, dims, want_grad=False)["loss"]
+                    flat[i] = old - eps
+                    lm = direct.MODELS[model](P, inst, dims, want_grad=False)["loss"]
+                    flat[i] = old
+                    nflat[i] = (lp - lm) / (2 * eps)
+                scale = max(np.abs(num).max(), 1e-8)
+                assert np.abs(num - res["grads"][k][name]).max() / scale < 1e-6, (model, k, name)
+
+
+def test_direct_counts_match_message_counts():
+    """The number of gradient messages per node that the direct code assumes
+    is the number of backward events the simulator produces."""
+    for model in MODELS:
+        dims = TINY[model]
+        fp = tiny_params(model)
+        P = direct.unpack(model, dims, fp)
+        for inst in tiny_data(model, 3):
+            rt = amp.Runtime(model, dims, fp)
+            rt.set_muf(10 ** 9)
+            rt.run([inst], mak=1)
+            got = [sum(1 for e in rt.events if e[0] == n.name and e[1] == "B") for n in rt.ppt]
+            assert got == direct.MODELS[model](P, inst, dims)["counts"], model
+
+
+@pytest.mark.parametrize("model", MODELS)
+def test_amp_mak1_update_at_retirement_equals_per_instance_sgd(model):
+    dims = TINY[model]
+    fp = tiny_params(model, scale=1.0)
+    data = tiny_data(model, 6)
+    lr = 0.05
+    P = direct.unpack(model, dims, fp)
+    ref_losses = direct.train(model, dims, P, data, lr)
+    rt = amp.Runtime(model, dims, fp)
+    rt.set_optimizer(kind="sgd", lr=lr)
+    Pc = direct.unpack(model, dims, fp)
+    losses = []
+    for i, inst in enumerate(data):
+        counts = direct.MODELS[model](Pc, inst, dims)["counts"]
+        for node, c in zip(rt.ppt, counts):
+            node.muf = max(c, 1)
+        losses += rt.run([inst], mak=1, first_seq=i)
+        for node, c in zip(rt.ppt, counts):
+            assert node.count == 0 or c == 0
+    assert np.allclose(losses, ref_losses, rtol=1e-12, atol=1e-13)
+    for node, ref in zip(rt.ppt, P):
+        for name in ref:
+            assert np.allclose(node.P[name], ref[name], rtol=1e-11, atol=1e-13), (model, node.name, name)
+
+
+@pytest.mark.parametrize("muf", [1, 4])
+def test_amp_mlp_mak1_equals_minibatch_sgd(muf):
+    dims = TINY["mlp"]
+    fp = tiny_params("mlp", scale=1.0)
+    data = tiny_data("mlp", 12)
+    P = direct.unpack("mlp", dims, fp)
+    ref = direct.train("mlp", dims, P, data, lr=0.1, batch=muf)
+    rt = amp.Runtime("mlp", dims, fp)
+    rt.set_optimizer(kind="sgd", lr=0.1)
+    rt.set_muf(muf)
+    losses = rt.run(data, mak=1)
+    assert np.allclose(losses, ref, rtol=1e-12)
+    for node, r in zip(rt.ppt, P):
+        assert np.allclose(node.P["W"], r["W"], rtol=1e-11, atol=1e-13)
+        assert np.allclose(node.P["b"], r["b"], rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("model", MODELS)
+@pytest.mark.parametrize("mak", [1, 3, 8])
+def test_lr_zero_any_schedule_gives_plain_forward_losses(model, mak):
+    dims = TINY[model]
+    fp = tiny_params(model)
+    data = tiny_data(model, 9)
+    P = direct.unpack(model, dims, fp)
+    ref = [direct.MODELS[model](P, inst, dims, want_grad=False)["loss"] for inst in data]
+    rt = amp.Runtime(model, dims, fp)
+    rt.set_optimizer(kind="sgd", lr=0.0)
+    rt.set_muf(3)
+    losses = rt.run(data, mak=mak)
+    assert np.allclose(losses, ref, rtol=1e-12, atol=1e-14)
+    assert rt.max_active_seen == min(mak, len(data))
+
+
+def test_ggnn_sparse_equals_dense_propagation():
+    """One propagation step written as a dense (N H) x (N H) matrix acting on
+    the stacked node states must give the same aggregated messages."""
+    dims = TINY["ggnn"]
+    H = dims["hidden"]
+    fp = tiny_params("ggnn")
+    P = direct.unpack("ggnn", dims, fp)
+    for g in tiny_data("ggnn", 4):
+        N = g["n_nodes"]
+        h0 = P[0]["W"][g["node_type"]]
+        big = np.zeros((N * H, N * H))
+        bias = np.zeros(N * H)
+        for e in range(len(g["src"])):
+            s, t, c = g["src"][e], g["dst"][e], g["etype"][e]
+            big[t * H:(t + 1) * H, s * H:(s + 1) * H] += P[1 + c]["W"]
+            bias[t * H:(t + 1) * H] += P[1 + c]["b"]
+        a_dense = (big @ h0.reshape(-1) + bias).reshape(N, H)
+        # run the simulator for this instance and read the aggregated messages
+        # that reached the GRU in step 0
+        rt = amp.Runtime("ggnn", dims, fp)
+        rt.set_muf(10 ** 9)
+        seen = {}
+        node = next(n for n in rt.nodes if n.name == "bcast_a")
+        orig = node.forward
+
+        def spy(rt_, port, msg, orig=orig):
+            seen[msg.state] = msg.payload.copy()
+            orig(rt_, port, msg)
+        node.forward = spy
+        rt.run([g], mak=1)
+        assert np.allclose(seen[(0, 0)], a_dense, rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- control nodes
+class FakeRT:
+    def __init__(self):
+        self.f, self.b = [], []
+
+    def emit_fwd(self, node, port, msg):
+        self.f.append((port, msg.payload, msg.state))
+
+    def emit_bwd(self, node, port, msg):
+        self.b.append((port, msg.payload, msg.state))
+
+
+def test_isu_inverse_and_phi_origin():
+    rt = FakeRT()
+    isu = amp.Isu("i", lambda r, s: (s[0], s[1] + 1), lambda r, s: (s[0], s[1] - 1))
+    isu.forward(rt, 0, amp.Msg(1.0, (7, 3)))
+    assert rt.f[-1][2] == (7, 4)
+    isu.backward(rt, 0, amp.Msg(2.0, rt.f[-1][2]))
+    assert rt.b[-1][2] == (7, 3)
+    phi = amp.Phi("p")
+    phi.forward(rt, 1, amp.Msg("x", (7, 1)))
+    phi.forward(rt, 0, amp.Msg("y", (7, 0)))
+    phi.backward(rt, 0, amp.Msg("gy", (7, 0)))
+    assert rt.b[-1][0] == 0
+    phi.backward(rt, 0, amp.Msg("gx", (7, 1)))
+    assert rt.b[-1][0] == 1 and not phi.origin
+
+
+def test_flatmap_sums_and_restores_state():
+    rt = FakeRT()
+    fm = amp.Flatmap("f", lambda r, s: [(s[0], "e", k) for k in range(3)])
+    fm.forward(rt, 0, amp.Msg(np.array([1.0, 2.0]), (5,)))
+    assert [m[2] for m in rt.f] == [(5, "e", 0), (5, "e", 1), (5, "e", 2)]
+    assert all(np.array_equal(m[1], [1.0, 2.0]) for m in rt.f)
+    for k in (2, 0):
+        fm.backward(rt, 0, amp.Msg(np.array([k, 1.0]), (5, "e", k)))
+        assert not rt.b
+    fm.backward(rt, 0, amp.Msg(np.array([1.0, 1.0]), (5, "e", 1)))
+    assert rt.b[-1][2] == (5,) and np.array_equal(rt.b[-1][1], [3.0, 3.0])
+
+
+def test_group_ungroup_concat_restore_states():
+    rt = FakeRT()
+    g = amp.Group("g", lambda r, s: (s[0], "all"), lambda r, k: 3, lambda r, s: s[1])
+    for v in (2, 0, 1):
+        g.forward(rt, 0, amp.Msg(np.array([float(v)]), (9, v)))
+    assert len(rt.f) == 1 and rt.f[0][2] == (9, "all")
+    assert np.array_equal(rt.f[0][1], [[0.0], [1.0], [2.0]])
+    g.backward(rt, 0, amp.Msg(np.array([[10.0], [11.0], [12.0]]), (9, "all")))
+    assert [(b[2], float(b[1][0])) for b in rt.b] == [((9, 0), 10.0), ((9, 1), 11.0), ((9, 2), 12.0)]
+    rt = FakeRT()
+    u = amp.Ungroup("u", lambda r, s: [(s[0], k) for k in range(2)])
+    u.forward(rt, 0, amp.Msg(np.array([[1.0], [2.0]]), (4,)))
+    assert [m[2] for m in rt.f] == [(4, 0), (4, 1)]
+    u.backward(rt, 0, amp.Msg(np.array([7.0]), (4, 1)))
+    u.backward(rt, 0, amp.Msg(np.array([6.0]), (4, 0)))
+    assert rt.b[-1][2] == (4,) and np.array_equal(rt.b[-1][1], [[6.0], [7.0]])
+    rt = FakeRT()
+    kc = amp.KeyedConcat("c", 2, lambda s: (s[0], s[1]), lambda s: s[2])
+    kc.forward(rt, 0, amp.Msg(np.array([3.0]), (1, 8, 1)))
+    kc.forward(rt, 0, amp.Msg(np.array([2.0, 2.5]), (1, 8, 0)))
+    assert rt.f[-1][2] == (1, 8) and np.array_equal(rt.f[-1][1], [2.0, 2.5, 3.0])
+    kc.backward(rt, 0, amp.Msg(np.array([1.0, 2.0, 3.0]), (1, 8)))
+    assert rt.b[0][2] == (1, 8, 0) and np.array_equal(rt.b[0][1], [1.0, 2.0])
+    assert rt.b[1][2] == (1, 8, 1) and np.array_equal(rt.b[1][1], [3.0])
+
+
+def test_bcast_sums_in_port_order():
+    rt = FakeRT()
+    b = amp.Bcast("b", 3)
+    b.forward(rt, 0, amp.Msg(np.array([1.0]), (0,)))
+    assert [m[0] for m in rt.f] == [0, 1, 2]
+    b.backward(rt, 2, amp.Msg(np.array([4.0]), (0,)))
+    b.backward(rt, 0, amp.Msg(np.array([1.0]), (0,)))
+    assert not rt.b
+    b.backward(rt, 1, amp.Msg(np.array([2.0]), (0,)))
+    assert np.array_equal(rt.b[0][1], [7.0])
+
+
+# ---------------------------------------------------------------- invariants
+@pytest.mark.parametrize("model", MODELS)
+def test_invariants_under_asynchrony(model):
+    dims = TINY[model]
+    fp = tiny_params(model, scale=1.0)
+    data = tiny_data(model, 20)
+    mak, muf = 4, 3
+    rt = amp.Runtime(model, dims, fp)
+    rt.set_optimizer(kind="sgd", lr=0.05)
+    rt.set_muf(muf)
+    rt.run(data, mak=mak)           # asserts every forward was answered and caches are empty
+    assert rt.max_active_seen == mak
+    for n in rt.ppt:
+        ev = [e for e in rt.events if e[0] == n.name]
+        nf = sum(1 for e in ev if e[1] == "F")
+        nb = sum(1 for e in ev if e[1] == "B")
+        nu = sum(1 for e in ev if e[1] == "U")
+        assert nf == nb
+        assert sorted(e[2] for e in ev if e[1] == "F") == sorted(e[2] for e in ev if e[1] == "B")
+        assert nu == nb // muf and n.count == nb - nu * muf
+        cnt = 0
+        for e in ev:
+            if e[1] == "B":
+                cnt += 1
+            elif e[1] == "U":
+                assert cnt >= muf
+                cnt = 0
+    # active count from the controller's admit / retire events never exceeds mak
+    active = 0
+    for e in rt.events:
+        if e[0] == "controller":
+            active += 1 if e[1] == "A" else -1
+            assert 0 <= active <= mak
+
+
+@pytest.mark.parametrize("mak", [1, 2, 4, 7])
+def test_mlp_staleness_bounded_by_mak_minus_one(mak):
+    """Section 3: staleness = number of updates at a node between the forward
+    and the backward pass of a message.  For the MLP with an update after every
+    gradient, only the other mak - 1 active instances can update in between."""
+    dims = TINY["mlp"]
+    rt = amp.Runtime("mlp", dims, tiny_params("mlp", scale=1.0))
+    rt.set_optimizer(kind="sgd", lr=0.05)
+    rt.run(tiny_data("mlp", 40), mak=mak)
+    st = rt.staleness()
+    worst = max(max(v) for v in st.values())
+    assert worst <= mak - 1
+    if mak == 1:
+        assert worst == 0
+    else:
+        assert worst > 0
+
+
+# ---------------------------------------------------------------- replay
+def split_log(events, workers):
+    logs = [[] for _ in workers]
+    where = {name: w for w, names in enumerate(workers) for name in names}
+    for name, kind, key in events:
+        if name == "controller":
+            continue
+        seq, local = key if key is not None else (0, 0)
+        logs[where[name]].append((name, kind, seq, local))
+    return logs
+
+
+@pytest.mark.parametrize("model", MODELS)
+def test_replay_reproduces_a_recorded_run(model):
+    dims = TINY[model]
+    fp = tiny_params(model, scale=1.0)
+    data = tiny_data(model, 15)
+    rt = amp.Runtime(model, dims, fp)
+    rt.set_optimizer(kind="adam", lr=0.01)
+    rt.set_muf(2)
+    losses = rt.run(data, mak=4)
+    names = [n.name for n in rt.ppt]
+    # workers: first two nodes share a worker, every other node has its own
+    workers = [names[:2]] + [[n] for n in names[2:]]
+    logs = split_log(rt.events, workers)
+    rp = amp.Runtime(model, dims, fp)
+    rp.set_optimizer(kind="adam", lr=0.01)
+    rp.set_muf(2)
+    rp.replay(data, logs)
+    assert [rp.loss[s] for s in range(len(data))] == losses
+    for a, b in zip(rt.ppt, rp.ppt):
+        for k in a.P:
+            assert np.array_equal(a.P[k], b.P[k])
+
+
+def test_replay_refuses_illegal_logs():
+    dims = TINY["mlp"]
+    fp = tiny_params("mlp", scale=1.0)
+    data = tiny_data("mlp", 6)
+    rt = amp.Runtime("mlp", dims, fp)
+    rt.set_muf(2)
+    rt.run(data, mak=2)
+    logs = split_log(rt.events, [["lin1"], ["lin2"], ["lin3"]])
+
+    def fresh():
+        r = amp.Runtime("mlp", dims, fp)
+        r.set_muf(2)
+        return r
+    fresh().replay(data, copy.deepcopy(logs))
+    # an update dropped
+    bad = copy.deepcopy(logs)
+    bad[1].remove(next(e for e in bad[1] if e[1] == "U"))
+    with pytest.raises(RuntimeError):
+        fresh().replay(data, bad)
+    # an update before enough gradients were accumulated
+    bad = copy.deepcopy(logs)
+    i = next(k for k, e in enumerate(bad[2]) if e[1] == "U")
+    bad[2].insert(i - 1, bad[2].pop(i))
+    with pytest.raises(RuntimeError):
+        fresh().replay(data, bad)
+    # a backward event before its forward
+    bad = copy.deepcopy(logs)
+    i = next(k for k, e in enumerate(bad[0]) if e[1] == "B")
+    bad[0].insert(0, bad[0].pop(i))
+    with pytest.raises(RuntimeError):
+        fresh().replay(data, bad)
+    # a forward event lost
+    bad = copy.deepcopy(logs)
+    bad[2] = [e for e in bad[2] if not (e[1] in "FB" and e[2] == 5)]
+    with pytest.raises(RuntimeError):
+        fresh().replay(data, bad)
