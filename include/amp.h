@@ -1,0 +1,199 @@
+/*
+ * amp.h -- C boundary of the MI355X implementation of asynchronous
+ * model-parallel (AMP) training (AMPNet, arXiv 1705.09786).
+ *
+ * The library runs the paper's training method -- per-instance forward and
+ * backward messages through a static graph of small dense cells, each
+ * parameterized cell accumulating its own gradients and updating its own
+ * parameters once enough have arrived (Section 3) -- as one persistent GPU
+ * kernel in which workgroups play the role of the paper's workers
+ * (Appendix A) and keep their cells' weights in LDS.
+ *
+ * Conventions
+ *   - Every call returns 0 (AMP_OK) or a negative amp_status.  After an
+ *     error amp_last_error(ctx) returns a message owned by the ctx.
+ *   - All pointer arguments are HOST pointers unless the parameter is
+ *     documented as a device pointer.  The caller owns every buffer it
+ *     passes; the library copies what it needs during the call and writes
+ *     results into caller-provided buffers of stated capacity.
+ *   - The library never allocates device memory: it works inside the device
+ *     arena handed to amp_create and launches on the HIP stream given there.
+ *   - A ctx is not thread-safe.  Call order: create -> build_* -> finalize
+ *     -> (set_* | submit | train | eval | get_*)* -> destroy.  Calls made in
+ *     the wrong phase return AMP_ESTATE.
+ */
+#ifndef AMP_H
+#define AMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct amp_ctx amp_ctx;
+
+enum amp_status {
+  AMP_OK = 0,
+  AMP_EINVAL = -1,       /* bad argument (message says which) */
+  AMP_ESTATE = -2,       /* call made in the wrong phase */
+  AMP_ENOMEM = -3,       /* arena or a caller buffer too small */
+  AMP_EFULL = -4,        /* instance store full */
+  AMP_EDEVICE = -5,      /* HIP error, or the kernel stopped itself (stall watchdog) */
+  AMP_EUNSUPPORTED = -6  /* valid request that this build cannot run */
+};
+
+/* The four model graphs of Sections 2 and 5 (Figures 2 and 4a). */
+enum amp_model { AMP_MODEL_MLP = 1, AMP_MODEL_RNN = 2, AMP_MODEL_TREE = 3, AMP_MODEL_GGNN = 4 };
+
+/* Sizes of a model; fields a model does not use are ignored.
+ *   MLP : d_in -> hidden (ReLU) -> hidden (ReLU) -> n_class, softmax loss
+ *   RNN : vocab x emb lookup, tanh cell (emb+hidden -> hidden), n_class
+ *   TREE: vocab x emb lookup, leaf cell (emb -> 3*hidden), branch cell
+ *         (2*hidden -> 5*hidden), n_class softmax at every tree node
+ *   GGNN: n_node_types x hidden lookup, n_edge_types linear (hidden ->
+ *         hidden), three GRU linears (2*hidden -> hidden), n_steps
+ *         propagation steps, linear readout of the node sum, squared error */
+typedef struct amp_model_dims {
+  int32_t d_in, hidden, n_class, vocab, emb;
+  int32_t n_node_types, n_edge_types, n_steps;
+} amp_model_dims;
+
+/* Parameterized nodes (PPT nodes, Section 4) are numbered per model:
+ *   MLP : 0 lin1, 1 lin2, 2 lin3
+ *   RNN : 0 lookup, 1 cell, 2 out
+ *   TREE: 0 lookup, 1 leaf, 2 branch, 3 out
+ *   GGNN: 0 lookup, 1..n_edge_types edge linears, then gz, gr, gh, readout
+ * A node's parameters are one flat float vector: W (rows x cols, row-major)
+ * followed by b (rows) -- lookups have no b.  Gate row blocks of `hidden`
+ * rows each: leaf [i; o; u], branch [i; f_left; f_right; o; u]; branch
+ * columns are [h_left; h_right]; rnn cell columns [embedding; h];
+ * GRU columns [a; h] (gz, gr) and [a; r*h] (gh). */
+
+/* One training or evaluation instance.  Unused fields are 0 / NULL.
+ *   MLP : x[n_x], labels[1]
+ *   RNN : tokens[n_tokens], labels[1]
+ *   TREE: n_tokens = L leaves with tokens[L]; n_nodes = 2L-1; leaves are
+ *         nodes 0..L-1, internal nodes L..2L-2 with children left[n],
+ *         right[n] < n (left/right are -1 for leaves), root = 2L-2;
+ *         labels[n_nodes]
+ *   GGNN: n_nodes graph nodes with tokens[n_nodes] = node types; n_edges
+ *         directed edges src[e] -> dst[e] of type etype[e]; every node must
+ *         have at least one incoming edge; target */
+typedef struct amp_instance {
+  int32_t n_x;       const float *x;
+  int32_t n_tokens;  const int32_t *tokens;
+  int32_t n_labels;  const int32_t *labels;
+  int32_t n_nodes;   const int32_t *left, *right;
+  int32_t n_edges;   const int32_t *src, *dst, *etype;
+  float target;
+} amp_instance;
+
+enum amp_opt { AMP_OPT_SGD = 0, AMP_OPT_MOMENTUM = 1, AMP_OPT_ADAM = 2 };
+typedef struct amp_opt_params { float lr, momentum, beta1, beta2, eps; } amp_opt_params;
+
+/* One entry of a worker's ordered event record: the worker executed the
+ * forward (F) or backward (B) transform of `node` for the message keyed
+ * (seq, local), or applied the node's accumulated update (U).  `seq` is the
+ * instance's admission number (epoch * n_instances + index); `local` is the
+ * position inside the instance: 0 for the MLP, the time step for the RNN
+ * cell and lookup, the tree node for TREE nodes, the propagation step for
+ * GGNN edge and GRU nodes.  Worker 0 is the controller: it records A
+ * (admitted) and R (retired). */
+enum amp_event_kind { AMP_EV_F = 0, AMP_EV_B = 1, AMP_EV_U = 2, AMP_EV_A = 3, AMP_EV_R = 4 };
+typedef struct amp_event {
+  uint16_t worker;
+  uint8_t node;
+  uint8_t kind;
+  uint32_t seq;
+  uint32_t local;
+} amp_event;
+
+typedef struct amp_eval_result {
+  double mean_loss;     /* per instance */
+  double accuracy;      /* correct / predictions (0 for GGNN) */
+  uint64_t n_instances;
+  uint64_t n_predictions;
+  double seconds;       /* device time of the evaluation kernel */
+} amp_eval_result;
+
+/* Creates a context that works inside [dev_arena, dev_arena + arena_bytes)
+ * (DEVICE pointer, 256-byte aligned, caller keeps it alive until
+ * amp_destroy) and launches on hip_stream (a hipStream_t passed as void*;
+ * NULL = the default stream).  Model = IR graph + controller, Section 4. */
+int amp_create(amp_ctx **out, void *dev_arena, size_t arena_bytes, void *hip_stream);
+void amp_destroy(amp_ctx *ctx);
+
+/* Builds one of the paper's model graphs.  One model per ctx. */
+int amp_build_mlp(amp_ctx *ctx, const amp_model_dims *dims);
+int amp_build_rnn(amp_ctx *ctx, const amp_model_dims *dims);
+int amp_build_treelstm(amp_ctx *ctx, const amp_model_dims *dims);
+int amp_build_ggnn(amp_ctx *ctx, const amp_model_dims *dims);
+
+/* Splits a heavy node's rows over `n_tiles` workgroups that run in lockstep
+ * (Section 5.1: a linear layer can be split into tiles computed in
+ * parallel).  Only before amp_finalize; TREE leaf / branch nodes only. */
+int amp_set_tiles(amp_ctx *ctx, int node_id, int n_tiles);
+
+/* Validates the graph, places nodes on workgroups and lays out the arena for
+ * at most max_active_keys instances in flight, each at most max_instance_len
+ * long (time steps, tree leaves, or graph nodes) with at most max_edges
+ * directed edges, and room for max_instances stored instances per set. */
+int amp_finalize(amp_ctx *ctx, int max_active_keys, int max_instance_len, int max_edges,
+                 size_t max_instances);
+
+/* max_active_keys: number of instances in flight (Section 3); 1..the value
+ * given to amp_finalize. */
+int amp_set_max_active_keys(amp_ctx *ctx, int mak);
+/* min_update_frequency of a node (-1 = all): the node updates as soon as it
+ * has accumulated this many gradients (Section 3); >= 1. */
+int amp_set_min_update_frequency(amp_ctx *ctx, int node_id, int muf);
+/* Optimizer of a node (-1 = all), Appendix A.  Lookup nodes support SGD only. */
+int amp_set_optimizer(amp_ctx *ctx, int node_id, int kind, const amp_opt_params *p);
+/* 1 (default): the applied gradient is the mean of the accumulated ones; 0: their sum. */
+int amp_set_gradient_mean(amp_ctx *ctx, int mean);
+
+int amp_num_nodes(amp_ctx *ctx);
+int amp_param_count(amp_ctx *ctx, int node_id, size_t *n);
+int amp_set_params(amp_ctx *ctx, int node_id, const float *host, size_t n);
+int amp_get_params(amp_ctx *ctx, int node_id, float *host, size_t cap, size_t *n);
+
+/* Appends an instance to the training set (which = 0) or the evaluation set
+ * (which = 1).  `key` is kept for the caller's bookkeeping.  Instances are
+ * copied; they reach the device at the next amp_train / amp_eval. */
+int amp_submit(amp_ctx *ctx, int which, uint64_t key, const amp_instance *inst);
+int amp_clear_instances(amp_ctx *ctx, int which);
+
+/* Record up to events_per_worker events per worker during the next
+ * amp_train calls (0 = off, the default).  Costs arena space. */
+int amp_set_event_log(amp_ctx *ctx, size_t events_per_worker);
+/* Seconds a worker may wait for a message before the kernel stops itself
+ * and amp_train returns AMP_EDEVICE (default 20). */
+int amp_set_watchdog(amp_ctx *ctx, double seconds);
+
+/* Blocking: trains `epochs` passes over the training set in submit order. */
+int amp_train(amp_ctx *ctx, int epochs);
+/* Blocking: forward-only pass over the evaluation set with the present
+ * parameters; nothing is recorded or updated. */
+int amp_eval(amp_ctx *ctx, amp_eval_result *out);
+
+/* Results of the last amp_train: mean loss per instance, accuracy over all
+ * predictions, instances trained, device seconds from first admission to
+ * last retirement.  Any out pointer may be NULL. */
+int amp_get_loss(amp_ctx *ctx, double *mean_loss, double *accuracy, uint64_t *n_instances,
+                 double *seconds);
+/* Per-admission losses of the last amp_train, in admission order. */
+int amp_get_instance_losses(amp_ctx *ctx, float *host, size_t cap, size_t *n);
+/* Events of the last amp_train, worker by worker, each worker's in execution order. */
+int amp_get_event_log(amp_ctx *ctx, amp_event *buf, size_t cap, size_t *n);
+/* bins[k] = gradients whose node was updated k times between their forward
+ * and backward pass (last bin = that many or more), from the event log. */
+int amp_get_staleness_hist(amp_ctx *ctx, uint64_t *bins, size_t nbins);
+int amp_num_workers(amp_ctx *ctx);
+const char *amp_last_error(amp_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AMP_H */

@@ -1,0 +1,307 @@
+// Device-side building blocks of the persistent AMP kernel: message rings,
+// watchdog-bounded waits, LDS-resident matrix-vector products, gradient
+// accumulation, local optimizer steps and the event record.
+#pragma once
+#include <hip/hip_runtime.h>
+#include "amp_dev.h"
+
+#define AGENT __HIP_MEMORY_SCOPE_AGENT
+
+__device__ __forceinline__ unsigned ld_u32(const unsigned* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, AGENT);
+}
+__device__ __forceinline__ void fence_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
+__device__ __forceinline__ void fence_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
+
+// ---------------------------------------------------------------- rings
+// Called by ONE thread, after a release fence that covers the payload.
+__device__ __forceinline__ void ring_post(const RingDev& r, unsigned code) {
+  unsigned t = __hip_atomic_fetch_add(r.tail, 1u, __ATOMIC_RELAXED, AGENT);
+  unsigned long long e = ((unsigned long long)(t + 1u) << 32) | code;
+  __hip_atomic_store(&r.ent[t & r.mask], e, __ATOMIC_RELAXED, AGENT);
+}
+
+// Reserves n consecutive tickets; entry i is published with ring_put.
+__device__ __forceinline__ unsigned ring_reserve(const RingDev& r, unsigned n) {
+  return __hip_atomic_fetch_add(r.tail, n, __ATOMIC_RELAXED, AGENT);
+}
+__device__ __forceinline__ void ring_put(const RingDev& r, unsigned ticket, unsigned code) {
+  unsigned long long e = ((unsigned long long)(ticket + 1u) << 32) | code;
+  __hip_atomic_store(&r.ent[ticket & r.mask], e, __ATOMIC_RELAXED, AGENT);
+}
+
+__device__ __forceinline__ void raise_abort(const AmpDev* D, unsigned code, unsigned detail) {
+  unsigned expected = 0;
+  if (__hip_atomic_compare_exchange_strong(&D->ctl[0], &expected, code, __ATOMIC_RELAXED, __ATOMIC_RELAXED, AGENT))
+    __hip_atomic_store(&D->ctl[2], detail, __ATOMIC_RELAXED, AGENT);
+}
+
+// Whole workgroup.  Waits for the entry with ticket `head` of ring r; returns
+// false when the run is over (done flag, abort flag, or this wait exceeded
+// the watchdog, which raises the abort flag so that every workgroup leaves).
+// s_ctl: two words of LDS.
+__device__ bool wait_msg(const AmpDev* D, const RingDev& r, unsigned& head, unsigned* s_ctl, unsigned& code) {
+  if (threadIdx.x == 0) {
+    const unsigned want = head + 1u;
+    unsigned long long* slot = &r.ent[head & r.mask];
+    const long long t0 = wall_clock64();
+    unsigned stop = 0, spins = 0;
+    unsigned long long e;
+    for (;;) {
+      e = __hip_atomic_load(slot, __ATOMIC_RELAXED, AGENT);
+      if ((unsigned)(e >> 32) == want) break;
+      if ((++spins & 7u) == 0u) {
+        if (ld_u32(&D->ctl[0]) | ld_u32(&D->ctl[1])) {
+          // done is only raised once nothing is in flight; re-check the slot once
+          e = __hip_atomic_load(slot, __ATOMIC_RELAXED, AGENT);
+          if ((unsigned)(e >> 32) == want && ld_u32(&D->ctl[0]) == 0u) break;
+          stop = 1;
+          break;
+        }
+        if (wall_clock64() - t0 > D->watchdog_ticks) {
+          raise_abort(D, ABORT_WATCHDOG, blockIdx.x);
+          stop = 1;
+          break;
+        }
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
+    if (!stop) fence_acquire();
+    s_ctl[0] = (unsigned)e;
+    s_ctl[1] = stop;
+  }
+  __syncthreads();
+  code = s_ctl[0];
+  const bool ok = s_ctl[1] == 0u;
+  __syncthreads();
+  if (ok) head++;
+  return ok;
+}
+
+// ---------------------------------------------------------------- event record
+__device__ __forceinline__ void log_event(const AmpDev* D, const WorkerDev* W, unsigned* s_logn, int node, int kind,
+                                          unsigned seq, unsigned local) {
+  if (W->log_cap == 0) return;
+  unsigned n = *s_logn;
+  if (n >= W->log_cap) {
+    raise_abort(D, ABORT_LOG_FULL, blockIdx.x);
+    return;
+  }
+  W->log[n] = ((unsigned long long)seq << 32) | ((unsigned)kind << 28) | ((unsigned)node << 20) | (local & 0xfffffu);
+  *s_logn = n + 1;
+}
+
+// ---------------------------------------------------------------- LDS matvec
+// Weights of a tile live in LDS as Wl[R][ldw] with ldw odd, so that threads
+// walking down a column (stride ldw) and threads walking along a row both hit
+// distinct banks.
+
+// y[r] = b[r] + sum_c Wl[r][c] * x[c].  Thread (p, r) sums the p-th column
+// chunk of row r; partials meet in `part` (>= P * R floats).  All threads.
+__device__ void gemv_rows(const float* Wl, int ldw, int R, int C, const float* bl, const float* x, float* part,
+                          float* y) {
+  int P = AMP_THREADS / R;
+  if (P < 1) P = 1;
+  if (P > 8) P = 8;
+  const int chunk = (C + P - 1) / P;
+  for (int idx = threadIdx.x; idx < R * P; idx += AMP_THREADS) {
+    const int p = idx / R, r = idx - p * R;
+    const int c0 = p * chunk;
+    int c1 = c0 + chunk;
+    if (c1 > C) c1 = C;
+    const float* w = Wl + r * ldw;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int c = c0;
+    for (; c + 3 < c1; c += 4) {
+      s0 = fmaf(w[c], x[c], s0);
+      s1 = fmaf(w[c + 1], x[c + 1], s1);
+      s2 = fmaf(w[c + 2], x[c + 2], s2);
+      s3 = fmaf(w[c + 3], x[c + 3], s3);
+    }
+    for (; c < c1; ++c) s0 = fmaf(w[c], x[c], s0);
+    part[p * R + r] = (s0 + s1) + (s2 + s3);
+  }
+  __syncthreads();
+  for (int r = threadIdx.x; r < R; r += AMP_THREADS) {
+    float s = bl ? bl[r] : 0.f;
+    for (int p = 0; p < P; ++p) s += part[p * R + r];
+    y[r] = s;
+  }
+  __syncthreads();
+}
+
+// dx[c] = sum_r Wl[r][c] * d[r].  Thread (p, c) sums the p-th row chunk of
+// column c.  `part` >= P * C floats.  All threads.
+__device__ void gemv_cols(const float* Wl, int ldw, int R, int C, const float* d, float* part, float* dx) {
+  int P = AMP_THREADS / C;
+  if (P < 1) P = 1;
+  if (P > 8) P = 8;
+  const int chunk = (R + P - 1) / P;
+  for (int idx = threadIdx.x; idx < C * P; idx += AMP_THREADS) {
+    const int p = idx / C, c = idx - p * C;
+    const int r0 = p * chunk;
+    int r1 = r0 + chunk;
+    if (r1 > R) r1 = R;
+    const float* w = Wl + c;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int r = r0;
+    for (; r + 3 < r1; r += 4) {
+      s0 = fmaf(w[r * ldw], d[r], s0);
+      s1 = fmaf(w[(r + 1) * ldw], d[r + 1], s1);
+      s2 = fmaf(w[(r + 2) * ldw], d[r + 2], s2);
+      s3 = fmaf(w[(r + 3) * ldw], d[r + 3], s3);
+    }
+    for (; r < r1; ++r) s0 = fmaf(w[r * ldw], d[r], s0);
+    part[p * C + c] = (s0 + s1) + (s2 + s3);
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < C; c += AMP_THREADS) {
+    float s = 0.f;
+    for (int p = 0; p < P; ++p) s += part[p * C + c];
+    dx[c] = s;
+  }
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------- tiles
+// A tile owns units [u0, u0+nu) of each of the node's gate blocks.  Local row
+// lr = g * nu + j  <->  node row g * block + u0 + j.
+struct Tile {
+  int R, C, ldw, nu, u0, block, nblocks;
+  __device__ __forceinline__ int grow(int lr) const {
+    const int g = lr / nu;
+    return g * block + u0 + (lr - g * nu);
+  }
+};
+
+__device__ __forceinline__ Tile make_tile(const NodeDev& nd, const WorkerDev* W) {
+  Tile t;
+  t.nu = W->nu;
+  t.u0 = W->u0;
+  t.block = nd.block;
+  t.nblocks = nd.nblocks;
+  t.R = nd.nblocks * W->nu;
+  t.C = nd.cols;
+  t.ldw = nd.cols | 1;
+  return t;
+}
+
+__device__ void tile_load(const NodeDev& nd, const Tile& t, float* Wl, float* bl) {
+  for (int i = threadIdx.x; i < t.R * t.C; i += AMP_THREADS) {
+    const int lr = i / t.C, c = i - lr * t.C;
+    Wl[lr * t.ldw + c] = nd.P[(long long)t.grow(lr) * t.C + c];
+  }
+  if (nd.has_bias)
+    for (int lr = threadIdx.x; lr < t.R; lr += AMP_THREADS) bl[lr] = nd.P[(long long)nd.rows * t.C + t.grow(lr)];
+  __syncthreads();
+}
+
+__device__ void tile_store(const NodeDev& nd, const Tile& t, const float* Wl, const float* bl) {
+  __syncthreads();
+  for (int i = threadIdx.x; i < t.R * t.C; i += AMP_THREADS) {
+    const int lr = i / t.C, c = i - lr * t.C;
+    nd.P[(long long)t.grow(lr) * t.C + c] = Wl[lr * t.ldw + c];
+  }
+  if (nd.has_bias)
+    for (int lr = threadIdx.x; lr < t.R; lr += AMP_THREADS) nd.P[(long long)nd.rows * t.C + t.grow(lr)] = bl[lr];
+}
+
+// G[row][c] += d[lr] * x[c] over the tile's rows; bias gradient alike.
+__device__ void tile_accumulate(const NodeDev& nd, const Tile& t, const float* d, const float* x) {
+  for (int i = threadIdx.x; i < t.R * t.C; i += AMP_THREADS) {
+    const int lr = i / t.C, c = i - lr * t.C;
+    float* g = nd.G + (long long)t.grow(lr) * t.C + c;
+    *g = fmaf(d[lr], x[c], *g);
+  }
+  if (nd.has_bias)
+    for (int lr = threadIdx.x; lr < t.R; lr += AMP_THREADS) nd.G[(long long)nd.rows * t.C + t.grow(lr)] += d[lr];
+}
+
+// One optimizer step on a value held in LDS (w) with slots in HBM.
+struct OptCoef {
+  float lr, mom, b1, b2, eps, c1, c2;  // c1 = 1/(1-b1^t), c2 = 1/(1-b2^t)
+  int kind;
+};
+
+__device__ __forceinline__ OptCoef opt_coef(const NodeDev& nd, unsigned tstep) {
+  OptCoef o;
+  o.kind = nd.opt;
+  o.lr = nd.lr;
+  o.mom = nd.mom;
+  o.b1 = nd.b1;
+  o.b2 = nd.b2;
+  o.eps = nd.eps;
+  o.c1 = o.c2 = 1.f;
+  if (nd.opt == 2) {
+    o.c1 = (float)(1.0 / (1.0 - pow((double)nd.b1, (double)tstep)));
+    o.c2 = (float)(1.0 / (1.0 - pow((double)nd.b2, (double)tstep)));
+  }
+  return o;
+}
+
+__device__ __forceinline__ float opt_apply(const OptCoef& o, float w, float g, float* M, float* V, long long gi) {
+  if (o.kind == 0) return w - o.lr * g;
+  if (o.kind == 1) {
+    const float m = fmaf(o.mom, M[gi], g);
+    M[gi] = m;
+    return w - o.lr * m;
+  }
+  const float m = fmaf(o.b1, M[gi], (1.f - o.b1) * g);
+  const float v = fmaf(o.b2, V[gi], (1.f - o.b2) * g * g);
+  M[gi] = m;
+  V[gi] = v;
+  return w - o.lr * (m * o.c1) / (sqrtf(v * o.c2) + o.eps);
+}
+
+// Applies the node's optimizer to the tile with the accumulated gradient
+// (mean over `count` gradients unless the node sums), clears the accumulator.
+// tstep is the 1-based number of this update.
+__device__ void tile_update(const NodeDev& nd, const Tile& t, float* Wl, float* bl, unsigned count, unsigned tstep) {
+  __syncthreads();
+  const OptCoef o = opt_coef(nd, tstep);
+  const float inv = nd.mean ? 1.f / (float)count : 1.f;
+  for (int i = threadIdx.x; i < t.R * t.C; i += AMP_THREADS) {
+    const int lr = i / t.C, c = i - lr * t.C;
+    const long long gi = (long long)t.grow(lr) * t.C + c;
+    const float g = nd.G[gi] * inv;
+    nd.G[gi] = 0.f;
+    Wl[lr * t.ldw + c] = opt_apply(o, Wl[lr * t.ldw + c], g, nd.M, nd.V, gi);
+  }
+  if (nd.has_bias)
+    for (int lr = threadIdx.x; lr < t.R; lr += AMP_THREADS) {
+      const long long gi = (long long)nd.rows * t.C + t.grow(lr);
+      const float g = nd.G[gi] * inv;
+      nd.G[gi] = 0.f;
+      bl[lr] = opt_apply(o, bl[lr], g, nd.M, nd.V, gi);
+    }
+  __syncthreads();
+}
+
+// softmax cross-entropy over n <= 64 logits held in LDS, by wave 0.
+// Writes dz[k] = p_k - [k == label]; returns loss and argmax through LDS words.
+__device__ void softmax_xent_wave0(const float* z, int n, int label, float* dz, float* s_loss, int* s_pred) {
+  if (threadIdx.x < 64) {
+    const int k = threadIdx.x;
+    float v = k < n ? z[k] : -3.0e38f;
+    float m = v;
+    int am = k < n ? k : 0x7fffffff;
+    for (int off = 32; off; off >>= 1) {
+      const float om = __shfl_xor(m, off);
+      const int oa = __shfl_xor(am, off);
+      if (om > m || (om == m && oa < am)) {
+        m = om;
+        am = oa;
+      }
+    }
+    float e = k < n ? expf(v - m) : 0.f;
+    float s = e;
+    for (int off = 32; off; off >>= 1) s += __shfl_xor(s, off);
+    if (k < n) dz[k] = e / s - (k == label ? 1.f : 0.f);
+    const float zl = __shfl(v, label);
+    if (k == 0) {
+      *s_loss = -(zl - m - logf(s));
+      *s_pred = am;
+    }
+  }
+  __syncthreads();
+}

@@ -1,0 +1,113 @@
+// Device-visible descriptors shared by the host library and the kernels.
+// Plain structs only: the host fills one AmpDev, copies it to the arena, and
+// passes its device address to the persistent kernel.
+#pragma once
+#include <stdint.h>
+
+#define AMP_MAX_NODES 16
+#define AMP_MAX_WORKERS 64
+#define AMP_MAX_BUFS 24
+#define AMP_THREADS 512
+#define AMP_LDS_BYTES 163840   // 160 KB per workgroup on gfx950
+
+// Message code carried by a ring entry: [31] direction, [30:20] slot,
+// [19:0] position inside the instance.
+#define MSG_DIR_B 0x80000000u
+#define MSG_SLOT(c) (((c) >> 20) & 0x7ffu)
+#define MSG_LOCAL(c) ((c) & 0xfffffu)
+#define MSG_MAKE(dirb, slot, local) (((dirb) ? MSG_DIR_B : 0u) | ((unsigned)(slot) << 20) | (unsigned)(local))
+#define AMP_MAX_MAK 2047
+
+// Values of ctl[0] when the kernel stopped itself.
+#define ABORT_WATCHDOG 1u
+#define ABORT_LOG_FULL 2u
+#define ABORT_BAD_STATE 3u
+
+enum AmpRole {
+  ROLE_CTRL = 0,
+  ROLE_MLP_LIN = 1,      // aux = layer index (0..2)
+  ROLE_RNN_CELL = 2,     // hosts lookup + cell
+  ROLE_RNN_OUT = 3,
+  ROLE_TREE_LOOKUP = 4,
+  ROLE_TREE_LEAF = 5,
+  ROLE_TREE_BRANCH = 6,
+  ROLE_TREE_OUT = 7,
+  ROLE_G_LOOKUP = 8,
+  ROLE_G_EDGE = 9,       // aux = edge type
+  ROLE_G_GATE = 10,      // aux = 0 (z) / 1 (r)
+  ROLE_G_CAND = 11,
+  ROLE_G_READOUT = 12,
+};
+
+// Multi-producer ring of 64-bit entries: high word = ticket + 1 (ready tag),
+// low word = message code.  Every consumer keeps a private head; capacity is
+// sized by the host so that unconsumed entries never wrap.
+struct RingDev {
+  unsigned long long* ent;
+  unsigned* tail;
+  unsigned mask;
+  unsigned pad;
+};
+
+// One parameterized node.  P = [W rows x cols row-major; b rows] is the master
+// copy in HBM (loaded into LDS by the owning workgroups at kernel start,
+// written back at exit); G, M, V have the same layout.
+struct NodeDev {
+  float* P;
+  float* G;
+  float* M;
+  float* V;
+  int rows, cols, has_bias, muf;
+  int opt, mean, nblocks, block;   // rows = nblocks * block (gate blocks)
+  float lr, mom, b1, b2, eps;
+  int pad;
+};
+
+struct WorkerDev {
+  int role, node, tile, ntiles;
+  int u0, nu;          // units [u0, u0+nu) of every gate block belong to this tile
+  int ring, aux;
+  unsigned* wstate;    // persistent per-worker words: [0] count, [1] opt step (node), [2] count, [3] step (hosted lookup)
+  unsigned long long* log;
+  unsigned* log_n;
+  unsigned log_cap, pad;
+};
+
+// One stored instance set (training or evaluation), flattened.
+struct DataDev {
+  int n_inst, n_x;
+  const float* x;          // [n_inst][n_x]
+  const float* target;     // [n_inst]
+  const int* tok_off;      // [n_inst+1] into tok
+  const int* tok;
+  const int* lab_off;      // [n_inst+1] into lab
+  const int* lab;
+  const int* node_off;     // [n_inst+1] into left/right/parent
+  const int* left;
+  const int* right;
+  const int* parent;       // parent*2 + side, -1 for the root
+  const int* edge_off;     // [n_inst+1] into src/dst/etype
+  const int* src;
+  const int* dst;
+  const int* etype;
+};
+
+struct AmpDev {
+  RingDev ring[AMP_MAX_WORKERS];
+  NodeDev node[AMP_MAX_NODES];
+  WorkerDev worker[AMP_MAX_WORKERS];
+  DataDev data;
+  int model, n_workers, n_nodes, mak;
+  int d_in, hidden, n_class, vocab, emb, n_node_types, n_edge_types, n_steps;
+  int max_len, max_edges, train, pad0;
+  unsigned n_total, first_seq;
+  unsigned* ctl;              // [0] abort code, [1] done, [2] abort detail
+  unsigned* slot_seq;         // [mak] admission number held by each slot
+  float* loss_out;            // [n_total] summed loss of each admission
+  int* correct_out;           // [n_total]
+  float* yhat_out;            // [n_total] (GGNN prediction)
+  unsigned long long* clock;  // [0] first admission, [1] last retirement (wall_clock64 ticks)
+  long long watchdog_ticks;
+  void* buf[AMP_MAX_BUFS];    // model-specific per-slot storage
+  long long stride[AMP_MAX_BUFS];
+};

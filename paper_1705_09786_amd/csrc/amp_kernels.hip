@@ -1,0 +1,421 @@
+// Persistent AMP training kernel for gfx950.
+//
+// One launch = one amp_train / amp_eval call.  Workgroup w plays worker w
+// (Appendix A of the paper: a worker hosts one or more IR nodes and is fed by
+// a multi-producer queue): it keeps its nodes' weights in LDS, takes keyed
+// messages from its ring, runs the node's forward or backward transform,
+// accumulates the gradient, applies the node's own update once
+// min_update_frequency gradients have arrived (Section 3), and posts the
+// resulting messages.  Worker 0 is the controller (Section 4): it admits
+// instances while fewer than max_active_keys are active and retires them when
+// their last backward message has come back.
+//
+// Control-flow nodes of the IR (Cond, Phi, Isu, Concat, Bcast, Group,
+// Ungroup, Flatmap) are pure functions of the message state; here they are
+// the index arithmetic a producer performs when it decides where a result
+// goes, plus arrival counters where several messages must meet.
+#include <hip/hip_runtime.h>
+#include "amp_common.hip.h"
+
+struct Lds {
+  float* p;
+  __device__ __forceinline__ float* take(int n) {
+    float* r = p;
+    p += (n + 3) & ~3;
+    return r;
+  }
+};
+
+__shared__ unsigned s_ctl[4];
+__shared__ unsigned s_logn;
+__shared__ float s_loss;
+__shared__ int s_pred;
+
+#define LOG(node, kind, seq, local)                                         \
+  do {                                                                      \
+    if (threadIdx.x == 0 && W->tile == 0) log_event(D, W, &s_logn, node, kind, seq, local); \
+  } while (0)
+
+// ============================================================ controller
+// Single-thread wait on the controller's ring.
+__device__ bool ctrl_wait(const AmpDev* D, const RingDev& r, unsigned& head, unsigned& code) {
+  const unsigned want = head + 1u;
+  unsigned long long* slot = &r.ent[head & r.mask];
+  const long long t0 = wall_clock64();
+  unsigned spins = 0;
+  for (;;) {
+    const unsigned long long e = __hip_atomic_load(slot, __ATOMIC_RELAXED, AGENT);
+    if ((unsigned)(e >> 32) == want) {
+      fence_acquire();
+      code = (unsigned)e;
+      head++;
+      return true;
+    }
+    if ((++spins & 7u) == 0u) {
+      if (ld_u32(&D->ctl[0])) return false;
+      if (wall_clock64() - t0 > D->watchdog_ticks) {
+        raise_abort(D, ABORT_WATCHDOG, 0);
+        return false;
+      }
+    }
+    __builtin_amdgcn_s_sleep(1);
+  }
+}
+
+__device__ void role_ctrl(const AmpDev* D, const WorkerDev* W, float* lds) {
+  if (threadIdx.x == 0) {
+    int* freelist = (int*)lds;
+    const int mak = D->mak;
+    int nfree = mak;
+    for (int i = 0; i < mak; ++i) freelist[i] = mak - 1 - i;
+    unsigned next = 0, retired = 0, head = 0;
+    int active = 0;
+    const unsigned n_total = D->n_total;
+    const RingDev& mine = D->ring[W->ring];
+    D->clock[0] = wall_clock64();
+    bool ok = true;
+    while (retired < n_total && ok) {
+      while (active < mak && next < n_total) {
+        const int s = freelist[--nfree];
+        const unsigned seq = D->first_seq + next;
+        D->slot_seq[s] = seq;
+        log_event(D, W, &s_logn, 0, 3, seq, 0);
+        fence_release();
+        if (D->model == 3) {
+          // tree: one token message per leaf goes to the lookup (worker 1)
+          const int inst = seq % D->data.n_inst;
+          const int L = D->data.tok_off[inst + 1] - D->data.tok_off[inst];
+          const unsigned t = ring_reserve(D->ring[1], L);
+          for (int l = 0; l < L; ++l) ring_put(D->ring[1], t + l, MSG_MAKE(0, s, l));
+        } else {
+          ring_post(D->ring[1], MSG_MAKE(0, s, 0));
+        }
+        next++;
+        active++;
+      }
+      unsigned code;
+      ok = ctrl_wait(D, mine, head, code);
+      if (ok) {
+        const int s = MSG_SLOT(code);
+        log_event(D, W, &s_logn, 0, 4, D->slot_seq[s], 0);
+        freelist[nfree++] = s;
+        active--;
+        retired++;
+      }
+    }
+    D->clock[1] = wall_clock64();
+    fence_release();
+    __hip_atomic_store(&D->ctl[1], 1u, __ATOMIC_RELAXED, AGENT);
+  }
+}
+
+// ============================================================ shared tail of a dense backward
+// Counts the gradient, updates when min_update_frequency is reached.
+__device__ __forceinline__ void count_and_update(const AmpDev* D, const WorkerDev* W, const NodeDev& nd, const Tile& t,
+                                                 float* Wl, float* bl, unsigned& count, unsigned& tstep) {
+  count++;
+  if ((int)count >= nd.muf) {
+    tstep++;
+    tile_update(nd, t, Wl, bl, count, tstep);
+    count = 0;
+    LOG(W->node, 2, 0, 0);
+  }
+}
+
+// ============================================================ MLP
+// Worker for linear layer `aux` (0..2) with its ReLU fused; the last layer
+// also hosts the softmax loss, which turns the forward message round.
+// Slot storage: buf[0]=act1, buf[1]=act2 (post-ReLU outputs), buf[2]=grad
+// w.r.t. act1, buf[3]=grad w.r.t. act2.
+__device__ void role_mlp_lin(const AmpDev* D, const WorkerDev* W, float* lds) {
+  const NodeDev& nd = D->node[W->node];
+  const Tile t = make_tile(nd, W);
+  const int R = t.R, C = t.C, li = W->aux;
+  const bool first = li == 0, last = li == 2;
+  Lds L{lds};
+  float* Wl = L.take(R * t.ldw);
+  float* bl = L.take(R);
+  float* xs = L.take(C);
+  float* ys = L.take(R);
+  float* ds = L.take(R);
+  float* dx = L.take(C);
+  float* part = L.take(8 * (R > C ? R : C));
+  tile_load(nd, t, Wl, bl);
+  const float* act_in = first ? nullptr : (const float*)D->buf[li - 1];
+  float* act_out = last ? nullptr : (float*)D->buf[li];
+  const float* g_in = last ? nullptr : (const float*)D->buf[2 + li];
+  float* g_out = first ? nullptr : (float*)D->buf[2 + li - 1];
+  const RingDev& mine = D->ring[W->ring];
+  const RingDev& next = D->ring[W->ring + 1];   // unused by the last layer
+  const RingDev& prev = D->ring[W->ring - 1];   // the controller for the first layer
+  unsigned head = 0, code;
+  unsigned count = W->wstate[0], tstep = W->wstate[1];
+  while (wait_msg(D, mine, head, s_ctl, code)) {
+    const int s = MSG_SLOT(code);
+    const unsigned seq = D->slot_seq[s];
+    const int inst = seq % D->data.n_inst;
+    const float* x = first ? D->data.x + (long long)inst * C : act_in + (long long)s * C;
+    bool backward = (code & MSG_DIR_B) != 0;
+    for (int c = threadIdx.x; c < C; c += AMP_THREADS) xs[c] = x[c];
+    __syncthreads();
+    if (!backward) {
+      gemv_rows(Wl, t.ldw, R, C, bl, xs, part, ys);
+      LOG(W->node, 0, seq, 0);
+      if (!last) {
+        for (int r = threadIdx.x; r < R; r += AMP_THREADS) act_out[(long long)s * R + r] = fmaxf(ys[r], 0.f);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+          fence_release();
+          ring_post(next, MSG_MAKE(0, s, 0));
+        }
+        continue;
+      }
+      const int label = D->data.lab[D->data.lab_off[inst]];
+      softmax_xent_wave0(ys, R, label, ds, &s_loss, &s_pred);
+      if (threadIdx.x == 0) {
+        D->loss_out[seq - D->first_seq] = s_loss;
+        D->correct_out[seq - D->first_seq] = s_pred == label;
+      }
+      if (!D->train) {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+          fence_release();
+          ring_post(D->ring[0], MSG_MAKE(1, s, 0));
+        }
+        continue;
+      }
+      backward = true;   // the loss layer starts backpropagation
+    } else {
+      for (int r = threadIdx.x; r < R; r += AMP_THREADS)
+        ds[r] = act_out[(long long)s * R + r] > 0.f ? g_in[(long long)s * R + r] : 0.f;
+      __syncthreads();
+    }
+    LOG(W->node, 1, seq, 0);
+    if (!first) {
+      gemv_cols(Wl, t.ldw, R, C, ds, part, dx);
+      for (int c = threadIdx.x; c < C; c += AMP_THREADS) g_out[(long long)s * C + c] = dx[c];
+    }
+    tile_accumulate(nd, t, ds, xs);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      fence_release();
+      ring_post(prev, MSG_MAKE(1, s, 0));
+    }
+    count_and_update(D, W, nd, t, Wl, bl, count, tstep);
+  }
+  tile_store(nd, t, Wl, bl);
+  if (threadIdx.x == 0) {
+    W->wstate[0] = count;
+    W->wstate[1] = tstep;
+  }
+}
+
+// ============================================================ RNN
+// The cell worker hosts the lookup table and the recurrent cell (Figure 2):
+// Concat(embedding, h) -> Linear-1 -> tanh -> Isu(t+1) -> Cond(end?) is one
+// forward event; the loop edge is a message to itself.
+// Slot storage: buf[0]=hs[mak][max_len][H] cell outputs, buf[1]=es[mak][max_len][E]
+// embeddings recorded at forward time, buf[2]=dh[mak][H] gradient w.r.t. the
+// hidden state travelling down the loop.
+__device__ void role_rnn_cell(const AmpDev* D, const WorkerDev* W, float* lds) {
+  const NodeDev& nd = D->node[1];
+  const NodeDev& lk = D->node[0];
+  const Tile t = make_tile(nd, W);
+  const int H = t.R, C = t.C, E = D->emb, V = D->vocab, TM = D->max_len;
+  Lds L{lds};
+  float* Wl = L.take(H * t.ldw);
+  float* bl = L.take(H);
+  float* El = L.take(V * E);
+  float* xs = L.take(C);
+  float* ys = L.take(H);
+  float* ds = L.take(H);
+  float* dx = L.take(C);
+  float* part = L.take(8 * (H > C ? H : C));
+  tile_load(nd, t, Wl, bl);
+  for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) El[i] = lk.P[i];
+  __syncthreads();
+  float* hs = (float*)D->buf[0];
+  float* es = (float*)D->buf[1];
+  float* dh = (float*)D->buf[2];
+  const RingDev& mine = D->ring[W->ring];
+  const RingDev& out = D->ring[W->ring + 1];
+  unsigned head = 0, code;
+  unsigned count = W->wstate[0], tstep = W->wstate[1], lcount = W->wstate[2], lstep = W->wstate[3];
+  while (wait_msg(D, mine, head, s_ctl, code)) {
+    const int s = MSG_SLOT(code), tt = MSG_LOCAL(code);
+    const unsigned seq = D->slot_seq[s];
+    const int inst = seq % D->data.n_inst;
+    const int toff = D->data.tok_off[inst];
+    const int T = D->data.tok_off[inst + 1] - toff;
+    const int tok = D->data.tok[toff + tt];
+    float* h_t = hs + ((long long)s * TM + tt) * H;
+    float* e_t = es + ((long long)s * TM + tt) * E;
+    if (!(code & MSG_DIR_B)) {
+      for (int c = threadIdx.x; c < C; c += AMP_THREADS) {
+        float v;
+        if (c < E) {
+          v = El[tok * E + c];
+          e_t[c] = v;
+        } else {
+          v = tt == 0 ? 0.f : h_t[c - E - H];   // previous step's output
+        }
+        xs[c] = v;
+      }
+      __syncthreads();
+      gemv_rows(Wl, t.ldw, H, C, bl, xs, part, ys);
+      for (int r = threadIdx.x; r < H; r += AMP_THREADS) h_t[r] = tanhf(ys[r]);
+      LOG(0, 0, seq, tt);
+      LOG(1, 0, seq, tt);
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        fence_release();
+        if (tt + 1 < T)
+          ring_post(mine, MSG_MAKE(0, s, tt + 1));
+        else
+          ring_post(out, MSG_MAKE(0, s, 0));
+      }
+      continue;
+    }
+    // backward through step tt
+    for (int c = threadIdx.x; c < C; c += AMP_THREADS) xs[c] = c < E ? e_t[c] : (tt == 0 ? 0.f : h_t[c - E - H]);
+    for (int r = threadIdx.x; r < H; r += AMP_THREADS) {
+      const float y = h_t[r];
+      ds[r] = dh[(long long)s * H + r] * (1.f - y * y);
+    }
+    __syncthreads();
+    LOG(1, 1, seq, tt);
+    gemv_cols(Wl, t.ldw, H, C, ds, part, dx);
+    for (int c = threadIdx.x; c < C; c += AMP_THREADS) {
+      if (c < E) {
+        float* g = lk.G + (long long)tok * E + c;
+        *g += dx[c];
+      } else {
+        dh[(long long)s * H + c - E] = dx[c];
+      }
+    }
+    tile_accumulate(nd, t, ds, xs);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      fence_release();
+      if (tt > 0)
+        ring_post(mine, MSG_MAKE(1, s, tt - 1));
+      else
+        ring_post(D->ring[0], MSG_MAKE(1, s, 0));
+    }
+    count_and_update(D, W, nd, t, Wl, bl, count, tstep);
+    LOG(0, 1, seq, tt);
+    lcount++;
+    if ((int)lcount >= lk.muf) {
+      // lookup update: plain SGD over the whole (small) table
+      lstep++;
+      __syncthreads();
+      const float sc = lk.lr * (lk.mean ? 1.f / (float)lcount : 1.f);
+      for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) {
+        El[i] -= sc * lk.G[i];
+        lk.G[i] = 0.f;
+      }
+      __syncthreads();
+      lcount = 0;
+      LOG(0, 2, 0, 0);
+    }
+  }
+  tile_store(nd, t, Wl, bl);
+  for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) lk.P[i] = El[i];
+  if (threadIdx.x == 0) {
+    W->wstate[0] = count;
+    W->wstate[1] = tstep;
+    W->wstate[2] = lcount;
+    W->wstate[3] = lstep;
+  }
+}
+
+// Output layer + softmax loss of the RNN: forward and backward in one event.
+__device__ void role_rnn_out(const AmpDev* D, const WorkerDev* W, float* lds) {
+  const NodeDev& nd = D->node[2];
+  const Tile t = make_tile(nd, W);
+  const int R = t.R, C = t.C, TM = D->max_len;
+  Lds L{lds};
+  float* Wl = L.take(R * t.ldw);
+  float* bl = L.take(R);
+  float* xs = L.take(C);
+  float* ys = L.take(R);
+  float* ds = L.take(R);
+  float* dx = L.take(C);
+  float* part = L.take(8 * (R > C ? R : C));
+  tile_load(nd, t, Wl, bl);
+  const float* hs = (const float*)D->buf[0];
+  float* dh = (float*)D->buf[2];
+  const RingDev& mine = D->ring[W->ring];
+  const RingDev& cell = D->ring[W->ring - 1];
+  unsigned head = 0, code;
+  unsigned count = W->wstate[0], tstep = W->wstate[1];
+  while (wait_msg(D, mine, head, s_ctl, code)) {
+    const int s = MSG_SLOT(code);
+    const unsigned seq = D->slot_seq[s];
+    const int inst = seq % D->data.n_inst;
+    const int T = D->data.tok_off[inst + 1] - D->data.tok_off[inst];
+    const float* x = hs + ((long long)s * TM + (T - 1)) * C;
+    for (int c = threadIdx.x; c < C; c += AMP_THREADS) xs[c] = x[c];
+    __syncthreads();
+    gemv_rows(Wl, t.ldw, R, C, bl, xs, part, ys);
+    LOG(2, 0, seq, 0);
+    const int label = D->data.lab[D->data.lab_off[inst]];
+    softmax_xent_wave0(ys, R, label, ds, &s_loss, &s_pred);
+    if (threadIdx.x == 0) {
+      D->loss_out[seq - D->first_seq] = s_loss;
+      D->correct_out[seq - D->first_seq] = s_pred == label;
+    }
+    if (!D->train) {
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        fence_release();
+        ring_post(D->ring[0], MSG_MAKE(1, s, 0));
+      }
+      continue;
+    }
+    LOG(2, 1, seq, 0);
+    gemv_cols(Wl, t.ldw, R, C, ds, part, dx);
+    for (int c = threadIdx.x; c < C; c += AMP_THREADS) dh[(long long)s * C + c] = dx[c];
+    tile_accumulate(nd, t, ds, xs);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      fence_release();
+      ring_post(cell, MSG_MAKE(1, s, T - 1));
+    }
+    count_and_update(D, W, nd, t, Wl, bl, count, tstep);
+  }
+  tile_store(nd, t, Wl, bl);
+  if (threadIdx.x == 0) {
+    W->wstate[0] = count;
+    W->wstate[1] = tstep;
+  }
+}
+
+// ============================================================ entry
+extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const AmpDev* D) {
+  extern __shared__ float lds[];
+  const WorkerDev* W = &D->worker[blockIdx.x];
+  if (threadIdx.x == 0) s_logn = 0;
+  __syncthreads();
+  switch (W->role) {
+    case ROLE_CTRL: role_ctrl(D, W, lds); break;
+    case ROLE_MLP_LIN: role_mlp_lin(D, W, lds); break;
+    case ROLE_RNN_CELL: role_rnn_cell(D, W, lds); break;
+    case ROLE_RNN_OUT: role_rnn_out(D, W, lds); break;
+    default: break;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0 && W->log_cap) *W->log_n = s_logn;
+}
+
+extern "C" hipError_t amp_launch(const AmpDev* dev, int n_workers, hipStream_t stream) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)amp_persistent, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       AMP_LDS_BYTES - 256);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(amp_persistent, dim3(n_workers), dim3(AMP_THREADS), AMP_LDS_BYTES - 256, stream, dev);
+  return hipGetLastError();
+}

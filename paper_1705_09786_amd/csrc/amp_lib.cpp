@@ -1,0 +1,859 @@
+// Host side of the C boundary declared in include/amp.h: graph construction
+// and validation, arena layout, instance staging, kernel launch, results.
+// No step of the training path runs here: every forward, backward and update
+// happens in the persistent kernel.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/amp.h"
+#include "amp_dev.h"
+
+extern "C" hipError_t amp_launch(const AmpDev* dev, int n_workers, hipStream_t stream);
+
+namespace {
+
+struct HostNode {
+  std::string name;
+  int rows = 0, cols = 0, has_bias = 0, nblocks = 1, block = 0;
+  int muf = 1, opt = AMP_OPT_SGD, tiles = 1;
+  amp_opt_params op{0.1f, 0.9f, 0.9f, 0.999f, 1e-8f};
+  std::vector<float> params;
+  bool dirty = true;        // host copy newer than device copy
+  size_t off_P = 0, off_G = 0, off_M = 0, off_V = 0;
+  size_t count() const { return (size_t)rows * cols + (has_bias ? rows : 0); }
+};
+
+struct HostWorker {
+  int role, node, tile, ntiles, u0, nu, ring, aux;
+  size_t off_state;
+};
+
+struct InstSet {
+  std::vector<uint64_t> keys;
+  std::vector<float> x, target;
+  std::vector<int> tok_off{0}, tok, lab_off{0}, lab, node_off{0}, left, right, parent, edge_off{0}, src, dst, etype;
+  bool dirty = true;
+  size_t n() const { return keys.size(); }
+  void clear() { *this = InstSet(); }
+};
+
+}  // namespace
+
+struct amp_ctx {
+  char* arena = nullptr;
+  size_t arena_bytes = 0;
+  hipStream_t stream = nullptr;
+  int model = 0;
+  amp_model_dims dims{};
+  std::vector<HostNode> nodes;
+  std::vector<HostWorker> workers;
+  bool finalized = false;
+  int max_mak = 0, mak = 1, max_len = 0, max_edges = 0, mean = 1;
+  size_t max_instances = 0, log_cap = 0;
+  double watchdog_s = 20.0;
+  InstSet sets[2];
+  // arena layout
+  size_t static_end = 0;   // everything below is laid out at finalize
+  size_t off_dev = 0, off_ctl = 0, off_slot_seq = 0, off_clock = 0;
+  std::vector<size_t> off_ring_ent, off_ring_tail;
+  unsigned ring_cap = 0;
+  size_t off_buf[AMP_MAX_BUFS] = {0};
+  size_t buf_bytes[AMP_MAX_BUFS] = {0};
+  long long buf_stride[AMP_MAX_BUFS] = {0};
+  bool state_zeroed = false;
+  // results of the last train
+  std::vector<float> last_loss;
+  std::vector<int> last_correct;
+  std::vector<amp_event> last_events;
+  double last_seconds = 0;
+  uint64_t last_npred = 0;
+  unsigned total_admitted = 0;
+  std::string err;
+};
+
+namespace {
+
+int fail(amp_ctx* c, int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  if (c) c->err = buf;
+  return code;
+}
+
+#define HIPCHK(c, call)                                                                      \
+  do {                                                                                       \
+    hipError_t e_ = (call);                                                                  \
+    if (e_ != hipSuccess) return fail(c, AMP_EDEVICE, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+HostNode make_node(const char* name, int rows, int cols, int has_bias, int nblocks = 1) {
+  HostNode n;
+  n.name = name;
+  n.rows = rows;
+  n.cols = cols;
+  n.has_bias = has_bias;
+  n.nblocks = nblocks;
+  n.block = rows / nblocks;
+  n.params.assign(n.count(), 0.f);
+  return n;
+}
+
+int check_build(amp_ctx* c, const amp_model_dims* d) {
+  if (!c || !d) return fail(c, AMP_EINVAL, "null argument");
+  if (c->model) return fail(c, AMP_ESTATE, "a model graph was already built");
+  return AMP_OK;
+}
+
+bool positive(std::initializer_list<int> v) {
+  for (int x : v)
+    if (x < 1) return false;
+  return true;
+}
+
+unsigned next_pow2(size_t v) {
+  unsigned p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+
+// LDS floats a worker needs (mirrors the carving in the kernels).
+size_t lds_floats(const amp_ctx* c, const HostWorker& w) {
+  auto r4 = [](size_t n) { return (n + 3) & ~(size_t)3; };
+  if (w.role == ROLE_CTRL) return r4(c->max_mak);
+  const HostNode& n = c->nodes[w.node];
+  const size_t R = (size_t)n.nblocks * w.nu, C = n.cols, ldw = C | 1;
+  size_t f = r4(R * ldw) + r4(R) + r4(C) + r4(R) + r4(R) + r4(C) + r4(8 * std::max(R, C));
+  if (w.role == ROLE_RNN_CELL) f += r4((size_t)c->dims.vocab * c->dims.emb);
+  return f;
+}
+
+}  // namespace
+
+extern "C" {
+
+int amp_create(amp_ctx** out, void* dev_arena, size_t arena_bytes, void* hip_stream) {
+  if (!out) return AMP_EINVAL;
+  *out = nullptr;
+  if (!dev_arena || arena_bytes < (1u << 20) || ((uintptr_t)dev_arena & 255)) return AMP_EINVAL;
+  amp_ctx* c = new amp_ctx();
+  c->arena = (char*)dev_arena;
+  c->arena_bytes = arena_bytes;
+  c->stream = (hipStream_t)hip_stream;
+  *out = c;
+  return AMP_OK;
+}
+
+void amp_destroy(amp_ctx* ctx) { delete ctx; }
+
+const char* amp_last_error(amp_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int amp_build_mlp(amp_ctx* c, const amp_model_dims* d) {
+  if (int r = check_build(c, d)) return r;
+  if (!positive({d->d_in, d->hidden, d->n_class})) return fail(c, AMP_EINVAL, "mlp: sizes must be >= 1");
+  if (d->n_class > 64) return fail(c, AMP_EUNSUPPORTED, "mlp: n_class > 64");
+  c->model = AMP_MODEL_MLP;
+  c->dims = *d;
+  c->nodes = {make_node("lin1", d->hidden, d->d_in, 1), make_node("lin2", d->hidden, d->hidden, 1),
+              make_node("lin3", d->n_class, d->hidden, 1)};
+  return AMP_OK;
+}
+
+int amp_build_rnn(amp_ctx* c, const amp_model_dims* d) {
+  if (int r = check_build(c, d)) return r;
+  if (!positive({d->vocab, d->emb, d->hidden, d->n_class})) return fail(c, AMP_EINVAL, "rnn: sizes must be >= 1");
+  if (d->n_class > 64) return fail(c, AMP_EUNSUPPORTED, "rnn: n_class > 64");
+  c->model = AMP_MODEL_RNN;
+  c->dims = *d;
+  c->nodes = {make_node("lookup", d->vocab, d->emb, 0), make_node("cell", d->hidden, d->emb + d->hidden, 1),
+              make_node("out", d->n_class, d->hidden, 1)};
+  return AMP_OK;
+}
+
+int amp_build_treelstm(amp_ctx* c, const amp_model_dims* d) {
+  if (int r = check_build(c, d)) return r;
+  if (!positive({d->vocab, d->emb, d->hidden, d->n_class})) return fail(c, AMP_EINVAL, "tree: sizes must be >= 1");
+  if (d->n_class > 64) return fail(c, AMP_EUNSUPPORTED, "tree: n_class > 64");
+  c->model = AMP_MODEL_TREE;
+  c->dims = *d;
+  c->nodes = {make_node("lookup", d->vocab, d->emb, 0), make_node("leaf", 3 * d->hidden, d->emb, 1, 3),
+              make_node("branch", 5 * d->hidden, 2 * d->hidden, 1, 5), make_node("out", d->n_class, d->hidden, 1)};
+  c->nodes[1].tiles = 4;
+  c->nodes[2].tiles = 8;
+  return AMP_OK;
+}
+
+int amp_build_ggnn(amp_ctx* c, const amp_model_dims* d) {
+  if (int r = check_build(c, d)) return r;
+  if (!positive({d->n_node_types, d->hidden, d->n_edge_types, d->n_steps}))
+    return fail(c, AMP_EINVAL, "ggnn: sizes must be >= 1");
+  if (d->n_edge_types > 8) return fail(c, AMP_EUNSUPPORTED, "ggnn: more than 8 edge types");
+  c->model = AMP_MODEL_GGNN;
+  c->dims = *d;
+  c->nodes.clear();
+  c->nodes.push_back(make_node("lookup", d->n_node_types, d->hidden, 0));
+  for (int k = 0; k < d->n_edge_types; ++k) {
+    char nm[16];
+    snprintf(nm, sizeof nm, "edge%d", k);
+    c->nodes.push_back(make_node(nm, d->hidden, d->hidden, 1));
+  }
+  for (const char* nm : {"gz", "gr", "gh"}) c->nodes.push_back(make_node(nm, d->hidden, 2 * d->hidden, 1));
+  c->nodes.push_back(make_node("readout", 1, d->hidden, 1));
+  return AMP_OK;
+}
+
+int amp_set_tiles(amp_ctx* c, int node_id, int n_tiles) {
+  if (!c) return AMP_EINVAL;
+  if (!c->model || c->finalized) return fail(c, AMP_ESTATE, "set_tiles: only between build and finalize");
+  if (node_id < 0 || node_id >= (int)c->nodes.size()) return fail(c, AMP_EINVAL, "set_tiles: no node %d", node_id);
+  if (c->model != AMP_MODEL_TREE || (node_id != 1 && node_id != 2))
+    return fail(c, AMP_EUNSUPPORTED, "set_tiles: only the tree model's leaf and branch nodes can be tiled");
+  if (n_tiles < 1 || n_tiles > 16 || n_tiles > c->nodes[node_id].block)
+    return fail(c, AMP_EINVAL, "set_tiles: n_tiles must be in 1..min(16, hidden)");
+  c->nodes[node_id].tiles = n_tiles;
+  return AMP_OK;
+}
+
+int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_edges, size_t max_instances) {
+  if (!c) return AMP_EINVAL;
+  if (!c->model) return fail(c, AMP_ESTATE, "finalize: no model graph built");
+  if (c->finalized) return fail(c, AMP_ESTATE, "finalize: already finalized");
+  if (max_active_keys < 1 || max_active_keys > AMP_MAX_MAK)
+    return fail(c, AMP_EINVAL, "finalize: max_active_keys must be in 1..%d", AMP_MAX_MAK);
+  if (max_instance_len < 1 || max_instances < 1) return fail(c, AMP_EINVAL, "finalize: sizes must be >= 1");
+  if (c->model == AMP_MODEL_GGNN && max_edges < 1) return fail(c, AMP_EINVAL, "finalize: ggnn needs max_edges >= 1");
+  const int NN = c->model == AMP_MODEL_TREE ? 2 * max_instance_len - 1 : max_instance_len;
+  if (NN >= (1 << 20)) return fail(c, AMP_EINVAL, "finalize: max_instance_len too large");
+  c->max_mak = c->mak = max_active_keys;
+  c->max_len = max_instance_len;
+  c->max_edges = max_edges;
+  c->max_instances = max_instances;
+
+  // ---- workers: one workgroup per node tile, worker 0 = controller
+  c->workers.clear();
+  auto add_worker = [&](int role, int node, int tile, int ntiles, int aux) {
+    HostWorker w{};
+    w.role = role;
+    w.node = node;
+    w.tile = tile;
+    w.ntiles = ntiles;
+    w.aux = aux;
+    if (node >= 0) {
+      const int blk = c->nodes[node].block;
+      const int base = blk / ntiles, rem = blk % ntiles;
+      w.u0 = tile * base + std::min(tile, rem);
+      w.nu = base + (tile < rem ? 1 : 0);
+    }
+    c->workers.push_back(w);
+  };
+  add_worker(ROLE_CTRL, -1, 0, 1, 0);
+  int nrings = 0;
+  if (c->model == AMP_MODEL_MLP) {
+    for (int l = 0; l < 3; ++l) add_worker(ROLE_MLP_LIN, l, 0, 1, l);
+    for (size_t i = 0; i < c->workers.size(); ++i) c->workers[i].ring = (int)i;
+    nrings = 4;
+  } else if (c->model == AMP_MODEL_RNN) {
+    add_worker(ROLE_RNN_CELL, 1, 0, 1, 0);
+    add_worker(ROLE_RNN_OUT, 2, 0, 1, 0);
+    for (size_t i = 0; i < c->workers.size(); ++i) c->workers[i].ring = (int)i;
+    nrings = 3;
+  } else if (c->model == AMP_MODEL_TREE) {
+    // rings: 0 controller, 1 lookup, 2 leaf (all leaf tiles), 3 branch (all branch tiles), 4 out
+    add_worker(ROLE_TREE_LOOKUP, 0, 0, 1, 0);
+    c->workers.back().ring = 1;
+    for (int t = 0; t < c->nodes[1].tiles; ++t) {
+      add_worker(ROLE_TREE_LEAF, 1, t, c->nodes[1].tiles, 0);
+      c->workers.back().ring = 2;
+    }
+    for (int t = 0; t < c->nodes[2].tiles; ++t) {
+      add_worker(ROLE_TREE_BRANCH, 2, t, c->nodes[2].tiles, 0);
+      c->workers.back().ring = 3;
+    }
+    add_worker(ROLE_TREE_OUT, 3, 0, 1, 0);
+    c->workers.back().ring = 4;
+    nrings = 5;
+  } else {
+    // rings: 0 controller, 1 lookup, 2.. edge types, then gz, gr, gh, readout
+    const int ne = c->dims.n_edge_types;
+    add_worker(ROLE_G_LOOKUP, 0, 0, 1, 0);
+    for (int k = 0; k < ne; ++k) add_worker(ROLE_G_EDGE, 1 + k, 0, 1, k);
+    add_worker(ROLE_G_GATE, 1 + ne, 0, 1, 0);
+    add_worker(ROLE_G_GATE, 2 + ne, 0, 1, 1);
+    add_worker(ROLE_G_CAND, 3 + ne, 0, 1, 0);
+    add_worker(ROLE_G_READOUT, 4 + ne, 0, 1, 0);
+    for (size_t i = 0; i < c->workers.size(); ++i) c->workers[i].ring = (int)i;
+    nrings = (int)c->workers.size();
+  }
+  if (c->workers.size() > AMP_MAX_WORKERS) return fail(c, AMP_EUNSUPPORTED, "finalize: too many workers");
+  for (const HostWorker& w : c->workers) {
+    const size_t need = lds_floats(c, w) * 4 + 256;
+    if (need > AMP_LDS_BYTES)
+      return fail(c, AMP_EUNSUPPORTED, "finalize: worker for node %d tile %d needs %zu bytes of LDS (limit %d); use more tiles",
+                  w.node, w.tile, need, AMP_LDS_BYTES);
+  }
+
+  // ---- arena layout
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off = align_up(off + bytes);
+    return o;
+  };
+  c->off_dev = take(sizeof(AmpDev));
+  c->off_ctl = take(64);
+  c->off_clock = take(64);
+  c->off_slot_seq = take(sizeof(unsigned) * c->max_mak);
+  const size_t per_inst_msgs = 4 * (size_t)NN + 8;
+  c->ring_cap = next_pow2(per_inst_msgs * c->max_mak);
+  c->off_ring_ent.assign(nrings, 0);
+  c->off_ring_tail.assign(nrings, 0);
+  for (int r = 0; r < nrings; ++r) {
+    c->off_ring_ent[r] = take(8 * (size_t)c->ring_cap);
+    c->off_ring_tail[r] = take(64);
+  }
+  for (HostNode& n : c->nodes) {
+    const size_t b = n.count() * 4;
+    n.off_P = take(b);
+    n.off_G = take(b);
+    n.off_M = take(b);
+    n.off_V = take(b);
+  }
+  for (HostWorker& w : c->workers) w.off_state = take(64);
+  // model-specific per-slot storage
+  const size_t mak = c->max_mak, H = c->dims.hidden;
+  auto buf = [&](int i, size_t floats_per_slot) {
+    c->buf_stride[i] = (long long)floats_per_slot;
+    c->buf_bytes[i] = floats_per_slot * 4 * mak;
+    c->off_buf[i] = take(c->buf_bytes[i]);
+  };
+  if (c->model == AMP_MODEL_MLP) {
+    for (int i = 0; i < 4; ++i) buf(i, H);
+  } else if (c->model == AMP_MODEL_RNN) {
+    buf(0, (size_t)c->max_len * H);
+    buf(1, (size_t)c->max_len * c->dims.emb);
+    buf(2, H);
+  }
+  c->static_end = off;
+  if (off > c->arena_bytes)
+    return fail(c, AMP_ENOMEM, "finalize: arena of %zu bytes is too small, %zu needed before instances", c->arena_bytes, off);
+  c->finalized = true;
+  c->state_zeroed = false;
+  return AMP_OK;
+}
+
+int amp_set_max_active_keys(amp_ctx* c, int mak) {
+  if (!c) return AMP_EINVAL;
+  if (!c->finalized) return fail(c, AMP_ESTATE, "set_max_active_keys: finalize first");
+  if (mak < 1 || mak > c->max_mak) return fail(c, AMP_EINVAL, "max_active_keys must be in 1..%d", c->max_mak);
+  c->mak = mak;
+  return AMP_OK;
+}
+
+int amp_set_min_update_frequency(amp_ctx* c, int node_id, int muf) {
+  if (!c) return AMP_EINVAL;
+  if (!c->model) return fail(c, AMP_ESTATE, "set_min_update_frequency: build a model first");
+  if (muf < 1) return fail(c, AMP_EINVAL, "min_update_frequency must be >= 1");
+  if (node_id < -1 || node_id >= (int)c->nodes.size()) return fail(c, AMP_EINVAL, "no node %d", node_id);
+  for (int i = 0; i < (int)c->nodes.size(); ++i)
+    if (node_id < 0 || node_id == i) c->nodes[i].muf = muf;
+  return AMP_OK;
+}
+
+int amp_set_optimizer(amp_ctx* c, int node_id, int kind, const amp_opt_params* p) {
+  if (!c || !p) return fail(c, AMP_EINVAL, "null argument");
+  if (!c->model) return fail(c, AMP_ESTATE, "set_optimizer: build a model first");
+  if (kind < AMP_OPT_SGD || kind > AMP_OPT_ADAM) return fail(c, AMP_EINVAL, "unknown optimizer %d", kind);
+  if (node_id < -1 || node_id >= (int)c->nodes.size()) return fail(c, AMP_EINVAL, "no node %d", node_id);
+  for (int i = 0; i < (int)c->nodes.size(); ++i) {
+    if (node_id >= 0 && node_id != i) continue;
+    const bool lookup = c->nodes[i].name == "lookup";
+    if (lookup && kind != AMP_OPT_SGD) {
+      if (node_id >= 0) return fail(c, AMP_EUNSUPPORTED, "lookup nodes support SGD only");
+      c->nodes[i].opt = AMP_OPT_SGD;   // "all nodes": the lookup keeps SGD with the given rate
+      c->nodes[i].op = *p;
+      continue;
+    }
+    c->nodes[i].opt = kind;
+    c->nodes[i].op = *p;
+  }
+  return AMP_OK;
+}
+
+int amp_set_gradient_mean(amp_ctx* c, int mean) {
+  if (!c) return AMP_EINVAL;
+  c->mean = mean ? 1 : 0;
+  return AMP_OK;
+}
+
+int amp_num_nodes(amp_ctx* c) { return c ? (int)c->nodes.size() : AMP_EINVAL; }
+int amp_num_workers(amp_ctx* c) { return c ? (int)c->workers.size() : AMP_EINVAL; }
+
+int amp_param_count(amp_ctx* c, int node_id, size_t* n) {
+  if (!c || !n) return fail(c, AMP_EINVAL, "null argument");
+  if (node_id < 0 || node_id >= (int)c->nodes.size()) return fail(c, AMP_EINVAL, "no node %d", node_id);
+  *n = c->nodes[node_id].count();
+  return AMP_OK;
+}
+
+int amp_set_params(amp_ctx* c, int node_id, const float* host, size_t n) {
+  if (!c || !host) return fail(c, AMP_EINVAL, "null argument");
+  if (node_id < 0 || node_id >= (int)c->nodes.size()) return fail(c, AMP_EINVAL, "no node %d", node_id);
+  HostNode& nd = c->nodes[node_id];
+  if (n != nd.count())
+    return fail(c, AMP_EINVAL, "set_params: node %d (%s) has %zu parameters, got %zu", node_id, nd.name.c_str(), nd.count(), n);
+  std::memcpy(nd.params.data(), host, n * 4);
+  nd.dirty = true;
+  return AMP_OK;
+}
+
+int amp_get_params(amp_ctx* c, int node_id, float* host, size_t cap, size_t* n) {
+  if (!c || !host) return fail(c, AMP_EINVAL, "null argument");
+  if (node_id < 0 || node_id >= (int)c->nodes.size()) return fail(c, AMP_EINVAL, "no node %d", node_id);
+  HostNode& nd = c->nodes[node_id];
+  if (n) *n = nd.count();
+  if (cap < nd.count()) return fail(c, AMP_ENOMEM, "get_params: buffer holds %zu floats, %zu needed", cap, nd.count());
+  if (c->finalized && !nd.dirty) {
+    HIPCHK(c, hipMemcpyAsync(nd.params.data(), c->arena + nd.off_P, nd.count() * 4, hipMemcpyDeviceToHost, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+  }
+  std::memcpy(host, nd.params.data(), nd.count() * 4);
+  return AMP_OK;
+}
+
+int amp_submit(amp_ctx* c, int which, uint64_t key, const amp_instance* in) {
+  if (!c || !in) return fail(c, AMP_EINVAL, "null argument");
+  if (!c->finalized) return fail(c, AMP_ESTATE, "submit: finalize first");
+  if (which < 0 || which > 1) return fail(c, AMP_EINVAL, "submit: which must be 0 (train) or 1 (eval)");
+  InstSet& S = c->sets[which];
+  if (S.n() >= c->max_instances) return fail(c, AMP_EFULL, "submit: instance store holds %zu", c->max_instances);
+  const amp_model_dims& d = c->dims;
+  auto bad_label = [&](int l) { return l < 0 || l >= d.n_class; };
+  switch (c->model) {
+    case AMP_MODEL_MLP:
+      if (in->n_x != d.d_in || !in->x) return fail(c, AMP_EINVAL, "submit: mlp instance needs x[%d]", d.d_in);
+      if (in->n_labels != 1 || !in->labels || bad_label(in->labels[0])) return fail(c, AMP_EINVAL, "submit: bad label");
+      S.x.insert(S.x.end(), in->x, in->x + d.d_in);
+      S.lab.push_back(in->labels[0]);
+      break;
+    case AMP_MODEL_RNN:
+      if (in->n_tokens < 1 || in->n_tokens > c->max_len || !in->tokens)
+        return fail(c, AMP_EINVAL, "submit: sequence length must be in 1..%d", c->max_len);
+      for (int t = 0; t < in->n_tokens; ++t)
+        if (in->tokens[t] < 0 || in->tokens[t] >= d.vocab) return fail(c, AMP_EINVAL, "submit: token %d out of range", t);
+      if (in->n_labels != 1 || !in->labels || bad_label(in->labels[0])) return fail(c, AMP_EINVAL, "submit: bad label");
+      S.tok.insert(S.tok.end(), in->tokens, in->tokens + in->n_tokens);
+      S.lab.push_back(in->labels[0]);
+      break;
+    case AMP_MODEL_TREE: {
+      const int L = in->n_tokens, NN = 2 * L - 1;
+      if (L < 1 || L > c->max_len || !in->tokens) return fail(c, AMP_EINVAL, "submit: leaves must be in 1..%d", c->max_len);
+      if (in->n_nodes != NN || in->n_labels != NN || !in->labels || (L > 1 && (!in->left || !in->right)))
+        return fail(c, AMP_EINVAL, "submit: a tree with %d leaves needs %d nodes and labels", L, NN);
+      for (int l = 0; l < L; ++l)
+        if (in->tokens[l] < 0 || in->tokens[l] >= d.vocab) return fail(c, AMP_EINVAL, "submit: token %d out of range", l);
+      std::vector<int> par(NN, -1);
+      for (int n = 0; n < NN; ++n) {
+        if (bad_label(in->labels[n])) return fail(c, AMP_EINVAL, "submit: label of node %d out of range", n);
+        if (n < L) {
+          if (L > 1 && (in->left[n] != -1 || in->right[n] != -1))
+            return fail(c, AMP_EINVAL, "submit: leaf %d has children", n);
+          continue;
+        }
+        const int a = in->left[n], b = in->right[n];
+        if (a < 0 || b < 0 || a >= n || b >= n || a == b)
+          return fail(c, AMP_EINVAL, "submit: node %d needs two distinct children with smaller ids", n);
+        if (par[a] != -1 || par[b] != -1) return fail(c, AMP_EINVAL, "submit: a child of node %d has two parents", n);
+        par[a] = 2 * n;
+        par[b] = 2 * n + 1;
+      }
+      for (int n = 0; n < NN - 1; ++n)
+        if (par[n] == -1) return fail(c, AMP_EINVAL, "submit: node %d is not reachable from the root", n);
+      S.tok.insert(S.tok.end(), in->tokens, in->tokens + L);
+      S.lab.insert(S.lab.end(), in->labels, in->labels + NN);
+      for (int n = 0; n < NN; ++n) {
+        S.left.push_back(n < L ? -1 : in->left[n]);
+        S.right.push_back(n < L ? -1 : in->right[n]);
+        S.parent.push_back(par[n]);
+      }
+      break;
+    }
+    case AMP_MODEL_GGNN: {
+      const int N = in->n_nodes, E = in->n_edges;
+      if (N < 1 || N > c->max_len || in->n_tokens != N || !in->tokens)
+        return fail(c, AMP_EINVAL, "submit: graph nodes must be in 1..%d with one type each", c->max_len);
+      if (E < 1 || E > c->max_edges || !in->src || !in->dst || !in->etype)
+        return fail(c, AMP_EINVAL, "submit: directed edges must be in 1..%d", c->max_edges);
+      std::vector<int> indeg(N, 0);
+      for (int v = 0; v < N; ++v)
+        if (in->tokens[v] < 0 || in->tokens[v] >= d.n_node_types) return fail(c, AMP_EINVAL, "submit: node type %d out of range", v);
+      for (int e = 0; e < E; ++e) {
+        if (in->src[e] < 0 || in->src[e] >= N || in->dst[e] < 0 || in->dst[e] >= N)
+          return fail(c, AMP_EINVAL, "submit: edge %d has an endpoint outside 0..%d", e, N - 1);
+        if (in->etype[e] < 0 || in->etype[e] >= d.n_edge_types) return fail(c, AMP_EINVAL, "submit: edge %d has a bad type", e);
+        indeg[in->dst[e]]++;
+      }
+      for (int v = 0; v < N; ++v)
+        if (!indeg[v]) return fail(c, AMP_EINVAL, "submit: node %d has no incoming edge", v);
+      if (!std::isfinite(in->target)) return fail(c, AMP_EINVAL, "submit: target is not finite");
+      S.tok.insert(S.tok.end(), in->tokens, in->tokens + N);
+      S.src.insert(S.src.end(), in->src, in->src + E);
+      S.dst.insert(S.dst.end(), in->dst, in->dst + E);
+      S.etype.insert(S.etype.end(), in->etype, in->etype + E);
+      S.target.push_back(in->target);
+      break;
+    }
+    default: return fail(c, AMP_ESTATE, "submit: no model");
+  }
+  if (c->model != AMP_MODEL_GGNN) S.target.push_back(0.f);
+  S.tok_off.push_back((int)S.tok.size());
+  S.lab_off.push_back((int)S.lab.size());
+  S.node_off.push_back((int)S.left.size());
+  S.edge_off.push_back((int)S.src.size());
+  S.keys.push_back(key);
+  S.dirty = true;
+  return AMP_OK;
+}
+
+int amp_clear_instances(amp_ctx* c, int which) {
+  if (!c || which < 0 || which > 1) return fail(c, AMP_EINVAL, "bad argument");
+  c->sets[which].clear();
+  return AMP_OK;
+}
+
+int amp_set_event_log(amp_ctx* c, size_t events_per_worker) {
+  if (!c) return AMP_EINVAL;
+  c->log_cap = events_per_worker;
+  return AMP_OK;
+}
+
+int amp_set_watchdog(amp_ctx* c, double seconds) {
+  if (!c) return AMP_EINVAL;
+  if (!(seconds > 0) || seconds > 600) return fail(c, AMP_EINVAL, "watchdog must be in (0, 600] seconds");
+  c->watchdog_s = seconds;
+  return AMP_OK;
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------- running
+namespace {
+
+template <class T>
+int upload(amp_ctx* c, size_t& off, const std::vector<T>& v, const void** dst) {
+  const size_t bytes = std::max<size_t>(v.size() * sizeof(T), 4);
+  if (off + bytes > c->arena_bytes) return fail(c, AMP_ENOMEM, "arena too small for the instance set (%zu bytes more needed)", bytes);
+  *dst = c->arena + off;
+  if (!v.empty()) HIPCHK(c, hipMemcpyAsync(c->arena + off, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice, c->stream));
+  off = align_up(off + bytes);
+  return AMP_OK;
+}
+
+int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
+  InstSet& S = c->sets[which];
+  if (S.n() == 0) return fail(c, AMP_ESTATE, "no instances submitted");
+  const size_t n_total = S.n() * (size_t)epochs;
+  if (n_total >= 0xffffffffull) return fail(c, AMP_EINVAL, "too many admissions for one call");
+  int dev_id = 0;
+  HIPCHK(c, hipGetDevice(&dev_id));
+  hipDeviceProp_t prop;
+  HIPCHK(c, hipGetDeviceProperties(&prop, dev_id));
+  if ((int)c->workers.size() > prop.multiProcessorCount)
+    return fail(c, AMP_EUNSUPPORTED, "%zu workers do not fit %d compute units", c->workers.size(), prop.multiProcessorCount);
+
+  if (!c->state_zeroed) {
+    // accumulators, optimizer slots, per-worker counters start at zero
+    for (HostNode& n : c->nodes) {
+      HIPCHK(c, hipMemsetAsync(c->arena + n.off_G, 0, n.count() * 4, c->stream));
+      HIPCHK(c, hipMemsetAsync(c->arena + n.off_M, 0, n.count() * 4, c->stream));
+      HIPCHK(c, hipMemsetAsync(c->arena + n.off_V, 0, n.count() * 4, c->stream));
+    }
+    for (HostWorker& w : c->workers) HIPCHK(c, hipMemsetAsync(c->arena + w.off_state, 0, 64, c->stream));
+    for (int i = 0; i < AMP_MAX_BUFS; ++i)
+      if (c->buf_bytes[i]) HIPCHK(c, hipMemsetAsync(c->arena + c->off_buf[i], 0, c->buf_bytes[i], c->stream));
+    c->state_zeroed = true;
+  }
+  for (HostNode& n : c->nodes)
+    if (n.dirty) {
+      HIPCHK(c, hipMemcpyAsync(c->arena + n.off_P, n.params.data(), n.count() * 4, hipMemcpyHostToDevice, c->stream));
+      n.dirty = false;
+    }
+
+  // ---- per-call region: instance set, results, event record
+  AmpDev D;
+  std::memset(&D, 0, sizeof D);
+  size_t off = c->static_end;
+  DataDev& dd = D.data;
+  dd.n_inst = (int)S.n();
+  dd.n_x = c->dims.d_in;
+  int r;
+  if ((r = upload(c, off, S.x, (const void**)&dd.x))) return r;
+  if ((r = upload(c, off, S.target, (const void**)&dd.target))) return r;
+  if ((r = upload(c, off, S.tok_off, (const void**)&dd.tok_off))) return r;
+  if ((r = upload(c, off, S.tok, (const void**)&dd.tok))) return r;
+  if ((r = upload(c, off, S.lab_off, (const void**)&dd.lab_off))) return r;
+  if ((r = upload(c, off, S.lab, (const void**)&dd.lab))) return r;
+  if ((r = upload(c, off, S.node_off, (const void**)&dd.node_off))) return r;
+  if ((r = upload(c, off, S.left, (const void**)&dd.left))) return r;
+  if ((r = upload(c, off, S.right, (const void**)&dd.right))) return r;
+  if ((r = upload(c, off, S.parent, (const void**)&dd.parent))) return r;
+  if ((r = upload(c, off, S.edge_off, (const void**)&dd.edge_off))) return r;
+  if ((r = upload(c, off, S.src, (const void**)&dd.src))) return r;
+  if ((r = upload(c, off, S.dst, (const void**)&dd.dst))) return r;
+  if ((r = upload(c, off, S.etype, (const void**)&dd.etype))) return r;
+  auto take = [&](size_t bytes) -> size_t {
+    size_t o = off;
+    off = align_up(off + bytes);
+    return o;
+  };
+  const size_t off_loss = take(n_total * 4), off_correct = take(n_total * 4), off_yhat = take(n_total * 4);
+  const size_t log_cap = train ? c->log_cap : 0;
+  std::vector<size_t> off_log(c->workers.size()), off_logn(c->workers.size());
+  for (size_t w = 0; w < c->workers.size(); ++w) {
+    off_log[w] = take(8 * std::max<size_t>(log_cap, 1));
+    off_logn[w] = take(64);
+  }
+  if (off > c->arena_bytes) return fail(c, AMP_ENOMEM, "arena of %zu bytes is too small, %zu needed", c->arena_bytes, off);
+  HIPCHK(c, hipMemsetAsync(c->arena + off_loss, 0, off - off_loss, c->stream));
+
+  // ---- device descriptor
+  for (size_t i = 0; i < c->off_ring_ent.size(); ++i) {
+    D.ring[i].ent = (unsigned long long*)(c->arena + c->off_ring_ent[i]);
+    D.ring[i].tail = (unsigned*)(c->arena + c->off_ring_tail[i]);
+    D.ring[i].mask = c->ring_cap - 1;
+    HIPCHK(c, hipMemsetAsync(D.ring[i].ent, 0, 8 * (size_t)c->ring_cap, c->stream));
+    HIPCHK(c, hipMemsetAsync(D.ring[i].tail, 0, 64, c->stream));
+  }
+  for (size_t i = 0; i < c->nodes.size(); ++i) {
+    const HostNode& n = c->nodes[i];
+    NodeDev& nd = D.node[i];
+    nd.P = (float*)(c->arena + n.off_P);
+    nd.G = (float*)(c->arena + n.off_G);
+    nd.M = (float*)(c->arena + n.off_M);
+    nd.V = (float*)(c->arena + n.off_V);
+    nd.rows = n.rows;
+    nd.cols = n.cols;
+    nd.has_bias = n.has_bias;
+    nd.muf = n.muf;
+    nd.opt = n.opt;
+    nd.mean = c->mean;
+    nd.nblocks = n.nblocks;
+    nd.block = n.block;
+    nd.lr = n.op.lr;
+    nd.mom = n.op.momentum;
+    nd.b1 = n.op.beta1;
+    nd.b2 = n.op.beta2;
+    nd.eps = n.op.eps;
+  }
+  for (size_t i = 0; i < c->workers.size(); ++i) {
+    const HostWorker& w = c->workers[i];
+    WorkerDev& wd = D.worker[i];
+    wd.role = w.role;
+    wd.node = w.node;
+    wd.tile = w.tile;
+    wd.ntiles = w.ntiles;
+    wd.u0 = w.u0;
+    wd.nu = w.nu;
+    wd.ring = w.ring;
+    wd.aux = w.aux;
+    wd.wstate = (unsigned*)(c->arena + w.off_state);
+    wd.log = (unsigned long long*)(c->arena + off_log[i]);
+    wd.log_n = (unsigned*)(c->arena + off_logn[i]);
+    wd.log_cap = (unsigned)log_cap;
+  }
+  D.model = c->model;
+  D.n_workers = (int)c->workers.size();
+  D.n_nodes = (int)c->nodes.size();
+  D.mak = c->mak;
+  D.d_in = c->dims.d_in;
+  D.hidden = c->dims.hidden;
+  D.n_class = c->dims.n_class;
+  D.vocab = c->dims.vocab;
+  D.emb = c->dims.emb;
+  D.n_node_types = c->dims.n_node_types;
+  D.n_edge_types = c->dims.n_edge_types;
+  D.n_steps = c->dims.n_steps;
+  D.max_len = c->max_len;
+  D.max_edges = c->max_edges;
+  D.train = train ? 1 : 0;
+  D.n_total = (unsigned)n_total;
+  D.first_seq = train ? c->total_admitted : 0;
+  D.ctl = (unsigned*)(c->arena + c->off_ctl);
+  D.slot_seq = (unsigned*)(c->arena + c->off_slot_seq);
+  D.loss_out = (float*)(c->arena + off_loss);
+  D.correct_out = (int*)(c->arena + off_correct);
+  D.yhat_out = (float*)(c->arena + off_yhat);
+  D.clock = (unsigned long long*)(c->arena + c->off_clock);
+  D.watchdog_ticks = (long long)(c->watchdog_s * 1.0e8);   // wall_clock64 counts at 100 MHz
+  for (int i = 0; i < AMP_MAX_BUFS; ++i) {
+    D.buf[i] = c->buf_bytes[i] ? c->arena + c->off_buf[i] : nullptr;
+    D.stride[i] = c->buf_stride[i];
+  }
+  HIPCHK(c, hipMemsetAsync(D.ctl, 0, 64, c->stream));
+  HIPCHK(c, hipMemsetAsync(D.clock, 0, 64, c->stream));
+  HIPCHK(c, hipMemcpyAsync(c->arena + c->off_dev, &D, sizeof D, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+
+  hipEvent_t e0, e1;
+  HIPCHK(c, hipEventCreate(&e0));
+  HIPCHK(c, hipEventCreate(&e1));
+  HIPCHK(c, hipEventRecord(e0, c->stream));
+  HIPCHK(c, amp_launch((const AmpDev*)(c->arena + c->off_dev), (int)c->workers.size(), c->stream));
+  HIPCHK(c, hipEventRecord(e1, c->stream));
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  float ms = 0;
+  HIPCHK(c, hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+
+  unsigned ctl[4] = {0, 0, 0, 0};
+  HIPCHK(c, hipMemcpy(ctl, D.ctl, sizeof ctl, hipMemcpyDeviceToHost));
+  if (ctl[0]) {
+    const char* why = ctl[0] == ABORT_WATCHDOG ? "a worker waited longer than the watchdog allows"
+                      : ctl[0] == ABORT_LOG_FULL ? "event record full"
+                                                 : "inconsistent state";
+    c->state_zeroed = false;   // device state is unreliable after an aborted run
+    for (HostNode& n : c->nodes) n.dirty = true;
+    return fail(c, AMP_EDEVICE, "kernel stopped itself: %s (worker %u)", why, ctl[2]);
+  }
+  std::vector<float> loss(n_total);
+  std::vector<int> correct(n_total);
+  HIPCHK(c, hipMemcpy(loss.data(), D.loss_out, n_total * 4, hipMemcpyDeviceToHost));
+  HIPCHK(c, hipMemcpy(correct.data(), D.correct_out, n_total * 4, hipMemcpyDeviceToHost));
+  uint64_t npred = 0;
+  if (c->model == AMP_MODEL_TREE)
+    for (int e = 0; e < epochs; ++e) npred += S.lab.size();
+  else
+    npred = n_total;
+  if (train) {
+    c->last_loss.swap(loss);
+    c->last_correct.swap(correct);
+    c->last_seconds = ms * 1e-3;
+    c->last_npred = npred;
+    c->total_admitted += (unsigned)n_total;
+    c->last_events.clear();
+    if (log_cap) {
+      std::vector<unsigned long long> raw(log_cap);
+      for (size_t w = 0; w < c->workers.size(); ++w) {
+        unsigned n = 0;
+        HIPCHK(c, hipMemcpy(&n, c->arena + off_logn[w], 4, hipMemcpyDeviceToHost));
+        if (n > log_cap) n = (unsigned)log_cap;
+        if (n) HIPCHK(c, hipMemcpy(raw.data(), c->arena + off_log[w], 8 * (size_t)n, hipMemcpyDeviceToHost));
+        for (unsigned i = 0; i < n; ++i) {
+          amp_event e;
+          e.worker = (uint16_t)w;
+          e.kind = (uint8_t)((raw[i] >> 28) & 0xf);
+          e.node = (uint8_t)((raw[i] >> 20) & 0xff);
+          e.local = (uint32_t)(raw[i] & 0xfffff);
+          e.seq = (uint32_t)(raw[i] >> 32);
+          c->last_events.push_back(e);
+        }
+      }
+    }
+  } else if (ev) {
+    double sl = 0;
+    uint64_t sc = 0;
+    for (size_t i = 0; i < n_total; ++i) {
+      sl += loss[i];
+      sc += correct[i];
+    }
+    ev->mean_loss = sl / (double)n_total;
+    ev->accuracy = c->model == AMP_MODEL_GGNN ? 0.0 : (double)sc / (double)npred;
+    ev->n_instances = n_total;
+    ev->n_predictions = npred;
+    ev->seconds = ms * 1e-3;
+  }
+  return AMP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int amp_train(amp_ctx* c, int epochs) {
+  if (!c) return AMP_EINVAL;
+  if (!c->finalized) return fail(c, AMP_ESTATE, "train: finalize first");
+  if (epochs < 1) return fail(c, AMP_EINVAL, "train: epochs must be >= 1");
+  return run(c, 0, epochs, true, nullptr);
+}
+
+int amp_eval(amp_ctx* c, amp_eval_result* out) {
+  if (!c || !out) return fail(c, AMP_EINVAL, "null argument");
+  if (!c->finalized) return fail(c, AMP_ESTATE, "eval: finalize first");
+  return run(c, 1, 1, false, out);
+}
+
+int amp_get_loss(amp_ctx* c, double* mean_loss, double* accuracy, uint64_t* n_instances, double* seconds) {
+  if (!c) return AMP_EINVAL;
+  if (c->last_loss.empty()) return fail(c, AMP_ESTATE, "get_loss: nothing trained yet");
+  double sl = 0;
+  uint64_t sc = 0;
+  for (size_t i = 0; i < c->last_loss.size(); ++i) {
+    sl += c->last_loss[i];
+    sc += c->last_correct[i];
+  }
+  if (mean_loss) *mean_loss = sl / (double)c->last_loss.size();
+  if (accuracy) *accuracy = c->model == AMP_MODEL_GGNN ? 0.0 : (double)sc / (double)c->last_npred;
+  if (n_instances) *n_instances = c->last_loss.size();
+  if (seconds) *seconds = c->last_seconds;
+  return AMP_OK;
+}
+
+int amp_get_instance_losses(amp_ctx* c, float* host, size_t cap, size_t* n) {
+  if (!c || !host) return fail(c, AMP_EINVAL, "null argument");
+  if (n) *n = c->last_loss.size();
+  if (cap < c->last_loss.size()) return fail(c, AMP_ENOMEM, "get_instance_losses: %zu floats needed", c->last_loss.size());
+  std::memcpy(host, c->last_loss.data(), c->last_loss.size() * 4);
+  return AMP_OK;
+}
+
+int amp_get_event_log(amp_ctx* c, amp_event* buf, size_t cap, size_t* n) {
+  if (!c) return AMP_EINVAL;
+  if (n) *n = c->last_events.size();
+  if (!buf) return AMP_OK;   // size query
+  if (cap < c->last_events.size()) return fail(c, AMP_ENOMEM, "get_event_log: %zu events needed", c->last_events.size());
+  std::memcpy(buf, c->last_events.data(), c->last_events.size() * sizeof(amp_event));
+  return AMP_OK;
+}
+
+int amp_get_staleness_hist(amp_ctx* c, uint64_t* bins, size_t nbins) {
+  if (!c || !bins || nbins < 1) return fail(c, AMP_EINVAL, "bad argument");
+  if (c->last_events.empty()) return fail(c, AMP_ESTATE, "get_staleness_hist: no event record (amp_set_event_log)");
+  std::fill(bins, bins + nbins, 0);
+  // per node: updates so far, and the value at each pending forward
+  const size_t nn = c->nodes.size();
+  std::vector<uint64_t> updates(nn, 0);
+  std::vector<std::vector<std::pair<uint64_t, uint64_t>>> pending(nn);   // (key, updates at forward)
+  for (const amp_event& e : c->last_events) {
+    if (e.worker == 0 || e.node >= nn) continue;
+    const uint64_t key = ((uint64_t)e.seq << 20) | e.local;
+    if (e.kind == AMP_EV_U) {
+      updates[e.node]++;
+    } else if (e.kind == AMP_EV_F) {
+      pending[e.node].push_back({key, updates[e.node]});
+    } else if (e.kind == AMP_EV_B) {
+      auto& p = pending[e.node];
+      for (size_t i = 0; i < p.size(); ++i)
+        if (p[i].first == key) {
+          const uint64_t st = updates[e.node] - p[i].second;
+          bins[std::min<uint64_t>(st, nbins - 1)]++;
+          p[i] = p.back();
+          p.pop_back();
+          break;
+        }
+    }
+  }
+  return AMP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,88 @@
+"""Shared helpers of the GPU parity tests: run the HIP path through the C
+boundary, replay its event record in the CPU checker, compare."""
+import numpy as np
+
+from oracle import amp as oamp
+from oracle import direct
+from paper_1705_09786_amd import binding as B
+from paper_1705_09786_amd import runner, synth
+
+# Tolerance (relative), as the benchmark spec fixes it for fp32 against the
+# float64 checker: parameters per tensor in the 2-norm, losses per instance.
+RTOL = 1e-5
+
+OPT_KIND = {"sgd": B.OPT_SGD, "momentum": B.OPT_MOMENTUM, "adam": B.OPT_ADAM}
+
+
+def f32(x):
+    return float(np.float32(x))
+
+
+def gpu_train(model, dims, fp, data, mak, muf, opt, epochs=1, log=True, tiles=None, watchdog=5.0,
+              arena_bytes=1 << 30, lookup_muf=None):
+    ml, me = runner.max_len_of(model, data)
+    tr = runner.Trainer(model, dims, fp, mak, ml, me, len(data), arena_bytes=arena_bytes, tiles=tiles)
+    a = tr.amp
+    a.set_watchdog(watchdog)
+    a.set_min_update_frequency(-1, muf)
+    if lookup_muf is not None:
+        a.set_min_update_frequency(0, lookup_muf)
+    kw = dict(opt)
+    kind = OPT_KIND[kw.pop("kind")]
+    a.set_optimizer(-1, kind, **kw)
+    if log:
+        per_inst = 8 * (2 * ml + 2) * max(1, dims.get("n_steps", 1))
+        a.set_event_log(per_inst * len(data) * epochs + 1024)
+    tr.submit_all(data)
+    a.train(epochs)
+    out = dict(params=tr.params(), losses=a.get_instance_losses().astype(np.float64), stats=a.get_loss(),
+               logs=a.get_event_log() if log else None, trainer=tr)
+    return out
+
+
+def oracle_replay(model, dims, fp, data, logs, muf, opt, lookup_muf=None):
+    names = synth.NODE_NAMES[model]
+    rt = oamp.Runtime(model, dims, fp)
+    rt.set_muf(muf)
+    if lookup_muf is not None:
+        rt.set_muf(lookup_muf, "lookup")
+    kw = {k: (f32(v) if isinstance(v, float) else v) for k, v in opt.items()}
+    rt.set_optimizer(**kw)
+    if "lookup" in names:
+        rt.set_optimizer("lookup", kind="sgd", lr=kw["lr"])
+    wl = [[(names[n], k, s, l) for (n, k, s, l) in w] for w in logs[1:]]
+    rt.replay(data, wl)
+    return rt
+
+
+def rel_err(a, b):
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def compare(gpu, rt, n_adm, tol=RTOL):
+    worst = 0.0
+    for k, node in enumerate(rt.ppt):
+        ref = oamp.C.pack_node(node.P)
+        e = rel_err(gpu["params"][k], ref)
+        worst = max(worst, e)
+        assert e <= tol, ("params", node.name, e)
+    ref_loss = np.array([rt.loss[s] for s in range(n_adm)])
+    le = np.abs(gpu["losses"] - ref_loss) / np.maximum(np.abs(ref_loss), 1.0)
+    assert le.max() <= tol, ("loss", int(le.argmax()), float(le.max()))
+    return worst, float(le.max())
+
+
+def check_controller_log(logs, mak, n_adm):
+    active = 0
+    adm = []
+    for (_, kind, seq, _) in logs[0]:
+        if kind == "A":
+            active += 1
+            adm.append(seq)
+        else:
+            assert kind == "R"
+            active -= 1
+        assert 0 <= active <= mak
+    assert adm == list(range(n_adm))
+    assert active == 0
