@@ -99,7 +99,10 @@ class PPT(Node):
         if self.acc is None:
             self.acc = {k: np.zeros_like(v) for k, v in self.P.items()}
         for k in g:
-            self.acc[k] += g[k]
+            if isinstance(g[k], C.RowGradient):
+                g[k].add_to(self.acc[k])
+            else:
+                self.acc[k] += g[k]
         self.count += 1
         rt.log(self, "B", msg.state)
         rt.emit_bwd(self, 0, Msg(dx, msg.state))

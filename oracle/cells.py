@@ -46,13 +46,28 @@ def lookup_fwd(P, idx):
     return P["W"][idx].copy(), idx
 
 
+class RowGradient:
+    """Gradient of a table that is zero except in the listed rows (repeated
+    indices add up): a dense gradient in sparse clothing, so that large
+    tables do not cost a full-size array per message."""
+
+    def __init__(self, shape, idx, rows):
+        self.shape = shape
+        self.idx = np.atleast_1d(np.asarray(idx))
+        self.rows = np.atleast_2d(np.asarray(rows, np.float64))
+
+    def add_to(self, dense):
+        np.add.at(dense, self.idx, self.rows)
+
+    def dense(self):
+        g = np.zeros(self.shape)
+        self.add_to(g)
+        return g
+
+
 def lookup_bwd(P, idx, dy):
-    g = np.zeros_like(P["W"])
-    if np.ndim(idx) == 0:
-        g[idx] += dy
-    else:
-        np.add.at(g, idx, dy)
-    return None, {"W": g}
+    """The gradient of a gather is a scatter-add of the incoming rows."""
+    return None, {"W": RowGradient(P["W"].shape, idx, dy)}
 
 
 # ---------------------------------------------------------------- NPTs

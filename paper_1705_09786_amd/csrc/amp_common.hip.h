@@ -305,3 +305,19 @@ __device__ void softmax_xent_wave0(const float* z, int n, int label, float* dz, 
   }
   __syncthreads();
 }
+
+__device__ __forceinline__ void fence_acq_rel() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "agent"); }
+
+// Arrival counter of a join: returns true for the arrival that completes
+// `expect` parts; that caller resets the counter (the slot is not reused
+// before the instance has retired) and may then post.  ONE thread, after a
+// release fence covering its own part.
+__device__ __forceinline__ bool join_arrive(int* counter, int expect) {
+  const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, AGENT);
+  if (old + 1 != expect) return false;
+  __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, AGENT);
+  fence_acq_rel();
+  return true;
+}
+
+__device__ __forceinline__ float sigmoidf_(float x) { return 1.f / (1.f + expf(-x)); }

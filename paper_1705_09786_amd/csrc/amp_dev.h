@@ -9,6 +9,7 @@
 #define AMP_MAX_BUFS 24
 #define AMP_THREADS 512
 #define AMP_LDS_BYTES 163840   // 160 KB per workgroup on gfx950
+#define AMP_TREE_LOOKUP_MAX_MUF 16384
 
 // Message code carried by a ring entry: [31] direction, [30:20] slot,
 // [19:0] position inside the instance.
@@ -100,6 +101,7 @@ struct AmpDev {
   int model, n_workers, n_nodes, mak;
   int d_in, hidden, n_class, vocab, emb, n_node_types, n_edge_types, n_steps;
   int max_len, max_edges, train, pad0;
+  int tiles_leaf, tiles_branch;
   unsigned n_total, first_seq;
   unsigned* ctl;              // [0] abort code, [1] done, [2] abort detail
   unsigned* slot_seq;         // [mak] admission number held by each slot

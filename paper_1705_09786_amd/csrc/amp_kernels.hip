@@ -391,6 +391,8 @@ __device__ void role_rnn_out(const AmpDev* D, const WorkerDev* W, float* lds) {
   }
 }
 
+#include "amp_tree.hip.h"
+
 // ============================================================ entry
 extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const AmpDev* D) {
   extern __shared__ float lds[];
@@ -402,6 +404,10 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
     case ROLE_MLP_LIN: role_mlp_lin(D, W, lds); break;
     case ROLE_RNN_CELL: role_rnn_cell(D, W, lds); break;
     case ROLE_RNN_OUT: role_rnn_out(D, W, lds); break;
+    case ROLE_TREE_LOOKUP: role_tree_lookup(D, W, lds); break;
+    case ROLE_TREE_LEAF: role_tree_cell<false>(D, W, lds); break;
+    case ROLE_TREE_BRANCH: role_tree_cell<true>(D, W, lds); break;
+    case ROLE_TREE_OUT: role_tree_out(D, W, lds); break;
     default: break;
   }
   __syncthreads();

@@ -132,10 +132,12 @@ unsigned next_pow2(size_t v) {
 size_t lds_floats(const amp_ctx* c, const HostWorker& w) {
   auto r4 = [](size_t n) { return (n + 3) & ~(size_t)3; };
   if (w.role == ROLE_CTRL) return r4(c->max_mak);
+  if (w.role == ROLE_TREE_LOOKUP) return r4(c->max_mak) + AMP_TREE_LOOKUP_MAX_MUF;
   const HostNode& n = c->nodes[w.node];
   const size_t R = (size_t)n.nblocks * w.nu, C = n.cols, ldw = C | 1;
   size_t f = r4(R * ldw) + r4(R) + r4(C) + r4(R) + r4(R) + r4(C) + r4(8 * std::max(R, C));
   if (w.role == ROLE_RNN_CELL) f += r4((size_t)c->dims.vocab * c->dims.emb);
+  if (w.role == ROLE_TREE_OUT) f += r4(c->max_mak);
   return f;
 }
 
@@ -343,6 +345,20 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     buf(0, (size_t)c->max_len * H);
     buf(1, (size_t)c->max_len * c->dims.emb);
     buf(2, H);
+  } else if (c->model == AMP_MODEL_TREE) {
+    const size_t L = c->max_len, N2 = 2 * L - 1, E = c->dims.emb;
+    const size_t TL = c->nodes[1].tiles, TB = c->nodes[2].tiles;
+    buf(0, L * E);
+    buf(1, N2 * 2 * H);
+    buf(2, N2 * 6 * H);
+    buf(3, N2 * H);
+    buf(4, N2 * TB * H);
+    buf(5, N2 * H);
+    buf(6, L * TL * E);
+    buf(7, N2 * 4);
+    c->buf_stride[10] = 0;
+    c->buf_bytes[10] = 4 * (size_t)AMP_TREE_LOOKUP_MAX_MUF;
+    c->off_buf[10] = take(c->buf_bytes[10]);
   }
   c->static_end = off;
   if (off > c->arena_bytes)
@@ -562,6 +578,8 @@ int upload(amp_ctx* c, size_t& off, const std::vector<T>& v, const void** dst) {
 int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   InstSet& S = c->sets[which];
   if (S.n() == 0) return fail(c, AMP_ESTATE, "no instances submitted");
+  if (c->model == AMP_MODEL_TREE && c->nodes[0].muf > AMP_TREE_LOOKUP_MAX_MUF)
+    return fail(c, AMP_EUNSUPPORTED, "the tree lookup supports min_update_frequency up to %d", AMP_TREE_LOOKUP_MAX_MUF);
   const size_t n_total = S.n() * (size_t)epochs;
   if (n_total >= 0xffffffffull) return fail(c, AMP_EINVAL, "too many admissions for one call");
   int dev_id = 0;
@@ -686,6 +704,10 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   D.max_len = c->max_len;
   D.max_edges = c->max_edges;
   D.train = train ? 1 : 0;
+  if (c->model == AMP_MODEL_TREE) {
+    D.tiles_leaf = c->nodes[1].tiles;
+    D.tiles_branch = c->nodes[2].tiles;
+  }
   D.n_total = (unsigned)n_total;
   D.first_seq = train ? c->total_admitted : 0;
   D.ctl = (unsigned*)(c->arena + c->off_ctl);

@@ -58,3 +58,42 @@ def test_rnn_edge_lengths():
     g = gpu_train("rnn", dims, fp, data, 5, 2, SGD)
     rt = oracle_replay("rnn", dims, fp, data, g["logs"], 2, SGD)
     compare(g, rt, len(data))
+
+
+TREE_SMALLVOCAB = dict(vocab=64, emb=300, hidden=150, n_class=5)
+TREE_ODD = dict(vocab=97, emb=50, hidden=37, n_class=5)
+
+
+@pytest.mark.parametrize("dims,tiles,mak,muf,lmuf,opt,n", [
+    (TREE_SMALLVOCAB, None, 1, 1, 1, SGD, 16),
+    (synth.DEFAULT_DIMS["tree"], None, 16, 50, 1000, SGD, 96),
+    (synth.DEFAULT_DIMS["tree"], None, 64, 7, 333, ADAM, 96),
+    (TREE_ODD, {1: 3, 2: 5}, 8, 3, 5, SGD, 64),
+    (TREE_ODD, {1: 1, 2: 1}, 8, 3, 5, ADAM, 64),
+])
+def test_tree_replay_parity(dims, tiles, mak, muf, lmuf, opt, n):
+    data = synth.make_tree(n, 21, dims)
+    fp = synth.init_params("tree", dims, 8)
+    g = gpu_train("tree", dims, fp, data, mak, muf, opt, tiles=tiles, lookup_muf=lmuf)
+    check_controller_log(g["logs"], mak, len(data))
+    rt = oracle_replay("tree", dims, fp, data, g["logs"], muf, opt, lookup_muf=lmuf)
+    compare(g, rt, len(data))
+
+
+def test_tree_edge_shapes():
+    """Single-leaf trees (the root is a leaf), two leaves, the maximum size,
+    left and right combs, with repeated tokens inside a tree."""
+    dims = TREE_ODD
+    data = synth.make_tree(6, 1, dims, min_leaves=1, max_leaves=1) + synth.make_tree(6, 2, dims, min_leaves=2, max_leaves=2) \
+        + synth.make_tree(4, 3, dims, min_leaves=60, max_leaves=60)
+    L = 9
+    comb_l = dict(n_leaves=L, tokens=np.full(L, 5, np.int32),
+                  left=np.array([-1] * L + [0] + list(range(L, 2 * L - 2)), np.int32),
+                  right=np.array([-1] * L + list(range(1, L)), np.int32),
+                  labels=np.arange(2 * L - 1, dtype=np.int32) % 5)
+    comb_r = dict(comb_l, left=comb_l["right"], right=comb_l["left"])
+    data += [comb_l, comb_r]
+    fp = synth.init_params("tree", dims, 8)
+    g = gpu_train("tree", dims, fp, data, 4, 2, SGD, tiles={1: 2, 2: 3}, lookup_muf=3)
+    rt = oracle_replay("tree", dims, fp, data, g["logs"], 2, SGD, lookup_muf=3)
+    compare(g, rt, len(data))
