@@ -1,0 +1,160 @@
+#!/usr/bin/env python3
+"""Benchmark of the AMP training hot path on one MI355X.
+
+A step is one pass of the whole path (admission, lookup, cell forward and
+backward, loss, local updates, retirement) over the full synthetic workload:
+one amp_train epoch.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--mak 64]
+
+The default workload is BASELINE config 3 (binary Tree-LSTM, 8,544 random
+trees, hidden 150, 300-d embeddings, max_active_keys 64), the configuration
+the metric names first; --config 1, 2 select the MLP and RNN workloads.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_1705_09786_amd import costmodel, synth  # noqa: E402
+
+CLOCK_HZ = 2.4e9
+LDS_BYTES_PER_CLK_PER_CU = 128
+N_CU = 256
+
+DEFAULTS = {
+    # cfg: mak, muf, lookup muf, optimizer
+    1: dict(mak=4, muf=1, lmuf=None, opt=("sgd", dict(lr=0.05))),
+    2: dict(mak=16, muf=16, lmuf=16, opt=("sgd", dict(lr=0.05))),
+    3: dict(mak=64, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.05))),
+    4: dict(mak=32, muf=20, lmuf=20, opt=("adam", dict(lr=0.001))),
+}
+NAMES = {1: "mlp_64-128-128-10_1024inst", 2: "rnn_h128_len4-32_10000seq",
+         3: "treelstm_h150_e300_2-60leaves_8544trees", 4: "ggnn_h100_4steps_9-29nodes_20000graphs"}
+
+
+def visits(model, data):
+    """Message visits per node for one pass over `data` (forward = backward)."""
+    if model == "mlp":
+        n = len(data)
+        return dict(lin1=n, lin2=n, lin3=n)
+    if model == "rnn":
+        return dict(cell=sum(len(d["tokens"]) for d in data), out=len(data))
+    if model == "tree":
+        nl = sum(d["n_leaves"] for d in data)
+        return dict(leaf=nl, branch=nl - len(data), out=2 * nl - len(data))
+    raise ValueError(model)
+
+
+def cpu_baseline(model, dims, fp, data, cfg, budget_s=15.0):
+    """The CPU checker's own-schedule AMP driver, as it stands, on a prefix of
+    the same workload; one thread."""
+    from threadpoolctl import threadpool_limits
+    from oracle import amp as oamp
+    n = min(len(data), 16)
+    with threadpool_limits(limits=1):
+        while True:
+            rt = oamp.Runtime(model, dims, fp)
+            rt.set_muf(cfg["muf"])
+            if cfg["lmuf"]:
+                rt.set_muf(cfg["lmuf"], "lookup")
+            rt.set_optimizer(kind=cfg["opt"][0], **cfg["opt"][1])
+            t0 = time.perf_counter()
+            rt.run(data[:n], mak=cfg["mak"])
+            dt = time.perf_counter() - t0
+            if dt > budget_s / 4 or n >= len(data):
+                break
+            n = min(len(data), max(n * 2, int(n * budget_s / 2 / max(dt, 1e-3))))
+    return dict(value=n / dt, unit="instances/s", cores=1, kind="oracle",
+                sample="first %d instances of the workload, 1 epoch, same mak/muf, %.1f s" % (n, dt))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--mak", type=int, default=None)
+    ap.add_argument("--muf", type=int, default=None)
+    ap.add_argument("--n", type=int, default=None, help="instances (default: the config's full set)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_1705_09786_amd import binding as B
+    from paper_1705_09786_amd import runner
+
+    cfg = dict(DEFAULTS[args.config])
+    if args.mak:
+        cfg["mak"] = args.mak
+    if args.muf:
+        cfg["muf"] = args.muf
+    model, dims, data = synth.workload(args.config, n=args.n)
+    fp = synth.init_params(model, dims, 100 + args.config)
+    ml, me = runner.max_len_of(model, data)
+    tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=4 << 30)
+    a = tr.amp
+    a.set_min_update_frequency(-1, cfg["muf"])
+    if cfg["lmuf"]:
+        a.set_min_update_frequency(0, cfg["lmuf"])
+    kind = {"sgd": B.OPT_SGD, "momentum": B.OPT_MOMENTUM, "adam": B.OPT_ADAM}[cfg["opt"][0]]
+    a.set_optimizer(-1, kind, **cfg["opt"][1])
+    tr.submit_all(data)
+
+    for _ in range(args.warmup):
+        a.train(1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    kern_s = []
+    for _ in range(args.steps):
+        a.train(1)
+        kern_s.append(a.get_loss()["seconds"])     # HIP events around the kernel, on its stream
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    stats = a.get_loss()
+
+    n = len(data)
+    value = n * args.steps / wall
+    kern = float(np.mean(kern_s))
+    # algorithmic LDS traffic of one launch: every visit reads the node's weights once forward, once backward
+    W = costmodel.cell_weights(model, dims)
+    v = visits(model, data)
+    lds_bytes = sum(costmodel.visit_cost(W[k])["weight_bytes"] * v[k] for k in v)
+    flops = sum(costmodel.visit_cost(W[k])["flops"] * v[k] for k in v)
+    n_workers = a.num_workers()
+    peak = n_workers * LDS_BYTES_PER_CLK_PER_CU * CLOCK_HZ / 1e9
+    achieved = lds_bytes / kern / 1e9
+    out = {
+        "metric": "trained instances/sec", "value": value, "unit": "instances/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * wall / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": NAMES[args.config], "model": model, "instances": n, "max_active_keys": cfg["mak"],
+                   "min_update_frequency": cfg["muf"], "lookup_min_update_frequency": cfg["lmuf"],
+                   "optimizer": cfg["opt"][0], "workgroups": n_workers},
+        "kernel_ms_per_step": 1e3 * kern,
+        "kernel_instances_per_s": n / kern,
+        "train_loss": stats["mean_loss"], "train_accuracy": stats["accuracy"],
+        "roofline": {"bound": "lds", "achieved": achieved, "peak": peak, "unit": "GB/s", "frac": achieved / peak,
+                     "traffic": None, "occupied_cus": n_workers,
+                     "peak_whole_chip": N_CU * LDS_BYTES_PER_CLK_PER_CU * CLOCK_HZ / 1e9,
+                     "frac_whole_chip": achieved / (N_CU * LDS_BYTES_PER_CLK_PER_CU * CLOCK_HZ / 1e9),
+                     "algorithmic_flops_per_s": flops / kern},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(model, dims, fp, data, cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
