@@ -91,6 +91,7 @@ struct DataDev {
   const int* src;
   const int* dst;
   const int* etype;
+  const int* tcount;       // [n_inst][8] directed edges per edge type
 };
 
 struct AmpDev {

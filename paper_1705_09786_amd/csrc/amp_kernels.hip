@@ -392,6 +392,7 @@ __device__ void role_rnn_out(const AmpDev* D, const WorkerDev* W, float* lds) {
 }
 
 #include "amp_tree.hip.h"
+#include "amp_ggnn.hip.h"
 
 // ============================================================ entry
 extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const AmpDev* D) {
@@ -408,6 +409,11 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
     case ROLE_TREE_LEAF: role_tree_cell<false>(D, W, lds); break;
     case ROLE_TREE_BRANCH: role_tree_cell<true>(D, W, lds); break;
     case ROLE_TREE_OUT: role_tree_out(D, W, lds); break;
+    case ROLE_G_LOOKUP: role_g_lookup(D, W, lds); break;
+    case ROLE_G_EDGE: role_g_edge(D, W, lds); break;
+    case ROLE_G_GATE: role_g_gate(D, W, lds); break;
+    case ROLE_G_CAND: role_g_cand(D, W, lds); break;
+    case ROLE_G_READOUT: role_g_readout(D, W, lds); break;
     default: break;
   }
   __syncthreads();

@@ -38,7 +38,7 @@ struct HostWorker {
 struct InstSet {
   std::vector<uint64_t> keys;
   std::vector<float> x, target;
-  std::vector<int> tok_off{0}, tok, lab_off{0}, lab, node_off{0}, left, right, parent, edge_off{0}, src, dst, etype;
+  std::vector<int> tok_off{0}, tok, lab_off{0}, lab, node_off{0}, left, right, parent, edge_off{0}, src, dst, etype, tcount;
   bool dirty = true;
   size_t n() const { return keys.size(); }
   void clear() { *this = InstSet(); }
@@ -133,6 +133,14 @@ size_t lds_floats(const amp_ctx* c, const HostWorker& w) {
   auto r4 = [](size_t n) { return (n + 3) & ~(size_t)3; };
   if (w.role == ROLE_CTRL) return r4(c->max_mak);
   if (w.role == ROLE_TREE_LOOKUP) return r4(c->max_mak) + AMP_TREE_LOOKUP_MAX_MUF;
+  if (w.role >= ROLE_G_LOOKUP) {
+    const size_t H = c->dims.hidden, N = c->max_len, Ep = (c->max_edges + 3) & ~3, Np = (N + 3) & ~3;
+    if (w.role == ROLE_G_LOOKUP) return r4((size_t)c->dims.n_node_types * H);
+    if (w.role == ROLE_G_EDGE)
+      return r4(H * (H | 1)) + r4(H) + 3 * r4(Ep * H) + r4(N * H) + r4(2048 + 4 * H) + r4(c->max_edges);
+    if (w.role == ROLE_G_READOUT) return r4(H | 1) + 4 + r4(H) + AMP_THREADS;
+    return r4(H * (2 * H | 1)) + r4(H) + 2 * r4(Np * 2 * H) + r4(Np * H) + r4(2048 + 8 * H);
+  }
   const HostNode& n = c->nodes[w.node];
   const size_t R = (size_t)n.nblocks * w.nu, C = n.cols, ldw = C | 1;
   size_t f = r4(R * ldw) + r4(R) + r4(C) + r4(R) + r4(R) + r4(C) + r4(8 * std::max(R, C));
@@ -359,6 +367,19 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     c->buf_stride[10] = 0;
     c->buf_bytes[10] = 4 * (size_t)AMP_TREE_LOOKUP_MAX_MUF;
     c->off_buf[10] = take(c->buf_bytes[10]);
+  } else if (c->model == AMP_MODEL_GGNN) {
+    const size_t N = c->max_len, E = c->max_edges, S = c->dims.n_steps, T = c->dims.n_edge_types;
+    buf(0, (S + 1) * N * H);
+    for (int i = 1; i <= 4; ++i) buf(i, S * N * H);
+    buf(5, E * H);
+    buf(6, N * H);
+    buf(7, N * H);
+    buf(8, N * H);
+    buf(9, 3 * N * H);
+    buf(10, 3 * N * H);
+    buf(11, T * N * H);
+    buf(12, N * H);
+    buf(13, 8);
   }
   c->static_end = off;
   if (off > c->arena_bytes)
@@ -526,6 +547,11 @@ int amp_submit(amp_ctx* c, int which, uint64_t key, const amp_instance* in) {
       S.src.insert(S.src.end(), in->src, in->src + E);
       S.dst.insert(S.dst.end(), in->dst, in->dst + E);
       S.etype.insert(S.etype.end(), in->etype, in->etype + E);
+      {
+        int tc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        for (int e = 0; e < E; ++e) tc[in->etype[e]]++;
+        S.tcount.insert(S.tcount.end(), tc, tc + 8);
+      }
       S.target.push_back(in->target);
       break;
     }
@@ -629,6 +655,7 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   if ((r = upload(c, off, S.src, (const void**)&dd.src))) return r;
   if ((r = upload(c, off, S.dst, (const void**)&dd.dst))) return r;
   if ((r = upload(c, off, S.etype, (const void**)&dd.etype))) return r;
+  if ((r = upload(c, off, S.tcount, (const void**)&dd.tcount))) return r;
   auto take = [&](size_t bytes) -> size_t {
     size_t o = off;
     off = align_up(off + bytes);

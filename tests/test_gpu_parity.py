@@ -97,3 +97,65 @@ def test_tree_edge_shapes():
     g = gpu_train("tree", dims, fp, data, 4, 2, SGD, tiles={1: 2, 2: 3}, lookup_muf=3)
     rt = oracle_replay("tree", dims, fp, data, g["logs"], 2, SGD, lookup_muf=3)
     compare(g, rt, len(data))
+
+
+MOM = dict(kind="momentum", lr=0.0005, momentum=0.9)
+GG_ODD = dict(n_node_types=5, hidden=37, n_edge_types=3, n_steps=3)
+
+
+@pytest.mark.parametrize("mak,muf,opt,n", [(1, 1, dict(kind="sgd", lr=0.01), 40), (32, 20, ADAM, 300), (8, 3, MOM, 150)])
+def test_ggnn_replay_parity(mak, muf, opt, n):
+    model, dims, data = synth.workload(4, n=n)
+    fp = synth.init_params(model, dims, 9)
+    g = gpu_train(model, dims, fp, data, mak, muf, opt)
+    check_controller_log(g["logs"], mak, len(data))
+    rt = oracle_replay(model, dims, fp, data, g["logs"], muf, opt)
+    compare(g, rt, len(data))
+
+
+def test_ggnn_odd_sizes_and_tiny_graphs():
+    """Hidden size not a multiple of anything, three edge types of which some
+    graphs use only one, graphs of two nodes next to the largest ones."""
+    dims = GG_ODD
+    data = synth.make_ggnn(30, 5, dims, min_nodes=2, max_nodes=3)[0] + synth.make_ggnn(30, 6, dims, min_nodes=29, max_nodes=29)[0]
+    pair = dict(n_nodes=2, node_type=np.array([0, 4], np.int32), src=np.array([0, 1], np.int32),
+                dst=np.array([1, 0], np.int32), etype=np.array([2, 2], np.int32), target=0.25)
+    data += [pair, pair]
+    fp = synth.init_params("ggnn", dims, 9)
+    g = gpu_train("ggnn", dims, fp, data, 6, 4, ADAM)
+    rt = oracle_replay("ggnn", dims, fp, data, g["logs"], 4, ADAM)
+    compare(g, rt, len(data))
+
+
+@pytest.mark.parametrize("cfg,n,nv", [(1, 256, 128), (2, 200, 100), (3, 48, 32), (4, 100, 50)])
+def test_eval_matches_direct_forward(cfg, n, nv):
+    """Forward-only pass (Section 1: training and inference through the same
+    graph): after some training, evaluation of a held-out set must equal the
+    checker's plain forward with the trained parameters."""
+    from paper_1705_09786_amd import runner
+    model, dims, data = synth.workload(cfg, n=n)
+    _, _, valid = synth.workload(cfg, n=nv, valid=True)
+    fp = synth.init_params(model, dims, 10 + cfg)
+    ml, me = runner.max_len_of(model, data + valid)
+    tr = runner.Trainer(model, dims, fp, 8, ml, me, len(data))
+    a = tr.amp
+    a.set_watchdog(5.0)
+    a.set_min_update_frequency(-1, 4)
+    a.set_optimizer(-1, 0, lr=0.02)
+    tr.submit_all(data)
+    tr.submit_all(valid, which=1)
+    a.train(1)
+    ev = a.eval()
+    P = direct.unpack(model, dims, tr.params())
+    ref_loss, ref_acc = direct.evaluate(model, dims, P, valid)
+    assert ev["n_instances"] == len(valid)
+    assert abs(ev["mean_loss"] - ref_loss) <= 1e-5 * max(1.0, abs(ref_loss))
+    if model != "ggnn":
+        assert abs(ev["accuracy"] - ref_acc) < 1e-9
+    # evaluation changes nothing: a second call gives the same numbers (a tree's loss is
+    # summed over its nodes in arrival order, hence fp32 rounding differences)
+    ev2 = a.eval()
+    assert abs(ev2["mean_loss"] - ev["mean_loss"]) <= 1e-6 * abs(ev["mean_loss"])
+    assert ev2["accuracy"] == ev["accuracy"]
+    # and training can continue afterwards
+    a.train(1)

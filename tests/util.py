@@ -41,7 +41,7 @@ def gpu_train(model, dims, fp, data, mak, muf, opt, epochs=1, log=True, tiles=No
 
 
 def oracle_replay(model, dims, fp, data, logs, muf, opt, lookup_muf=None):
-    names = synth.NODE_NAMES[model]
+    names = [sh[0] for sh in synth.param_shapes(model, dims)]
     rt = oamp.Runtime(model, dims, fp)
     rt.set_muf(muf)
     if lookup_muf is not None:
