@@ -54,6 +54,26 @@ def visits(model, data):
     raise ValueError(model)
 
 
+def ggnn_cost(dims, data):
+    """(weight bytes, flops) of one pass: each node is visited once per step
+    with k grouped rows (edges of its type, or all graph nodes)."""
+    W = costmodel.cell_weights("ggnn", dims)
+    S, ne = dims["n_steps"], dims["n_edge_types"]
+    nbytes = nflops = 0
+    for g in data:
+        for c in range(ne):
+            k = int((g["etype"] == c).sum())
+            if k:
+                vc = costmodel.visit_cost(W["edge%d" % c], rows=k)
+                nbytes += S * vc["weight_bytes"]
+                nflops += S * vc["flops"]
+        for name in ("gz", "gr", "gh"):
+            vc = costmodel.visit_cost(W[name], rows=g["n_nodes"])
+            nbytes += S * vc["weight_bytes"]
+            nflops += S * vc["flops"]
+    return nbytes, nflops
+
+
 def cpu_baseline(model, dims, fp, data, cfg, budget_s=15.0):
     """The CPU checker's own-schedule AMP driver, as it stands, on a prefix of
     the same workload; one thread."""
@@ -128,10 +148,13 @@ def main():
     value = n * args.steps / wall
     kern = float(np.mean(kern_s))
     # algorithmic LDS traffic of one launch: every visit reads the node's weights once forward, once backward
-    W = costmodel.cell_weights(model, dims)
-    v = visits(model, data)
-    lds_bytes = sum(costmodel.visit_cost(W[k])["weight_bytes"] * v[k] for k in v)
-    flops = sum(costmodel.visit_cost(W[k])["flops"] * v[k] for k in v)
+    if model == "ggnn":
+        lds_bytes, flops = ggnn_cost(dims, data)
+    else:
+        W = costmodel.cell_weights(model, dims)
+        v = visits(model, data)
+        lds_bytes = sum(costmodel.visit_cost(W[k])["weight_bytes"] * v[k] for k in v)
+        flops = sum(costmodel.visit_cost(W[k])["flops"] * v[k] for k in v)
     n_workers = a.num_workers()
     peak = n_workers * LDS_BYTES_PER_CLK_PER_CU * CLOCK_HZ / 1e9
     achieved = lds_bytes / kern / 1e9

@@ -191,6 +191,13 @@ int amp_get_event_log(amp_ctx *ctx, amp_event *buf, size_t cap, size_t *n);
  * and backward pass (last bin = that many or more), from the event log. */
 int amp_get_staleness_hist(amp_ctx *ctx, uint64_t *bins, size_t nbins);
 int amp_num_workers(amp_ctx *ctx);
+/* Utilisation of the last amp_train / amp_eval, one entry per worker
+ * (workgroup): fraction of the kernel's life spent waiting for a message,
+ * messages taken, and the node the worker hosts (-1 = controller).  Workers
+ * correspond to the paper's Appendix A workers; a node whose workers never
+ * wait is the pipeline's bottleneck.  Any out pointer may be NULL. */
+int amp_get_worker_stats(amp_ctx *ctx, double *wait_fraction, uint64_t *messages, int32_t *node_of_worker,
+                         size_t cap, size_t *n);
 const char *amp_last_error(amp_ctx *ctx);
 
 #ifdef __cplusplus

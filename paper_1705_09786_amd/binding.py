@@ -82,6 +82,8 @@ SIGNATURES = {
     "amp_get_instance_losses": (ct.c_int, [_ctxp, _f32p, ct.c_size_t, ct.POINTER(ct.c_size_t)]),
     "amp_get_event_log": (ct.c_int, [_ctxp, ct.POINTER(Event), ct.c_size_t, ct.POINTER(ct.c_size_t)]),
     "amp_get_staleness_hist": (ct.c_int, [_ctxp, ct.POINTER(ct.c_uint64), ct.c_size_t]),
+    "amp_get_worker_stats": (ct.c_int, [_ctxp, ct.POINTER(ct.c_double), ct.POINTER(ct.c_uint64), _i32p,
+                                        ct.c_size_t, ct.POINTER(ct.c_size_t)]),
     "amp_last_error": (ct.c_char_p, [_ctxp]),
 }
 
@@ -260,6 +262,14 @@ class Amp:
         for e in buf[:n.value]:
             logs[e.worker].append((e.node, EV_NAMES[e.kind], e.seq, e.local))
         return logs
+
+    def get_worker_stats(self):
+        """List per worker of dict(node, wait_fraction, messages)."""
+        nw = self.num_workers()
+        wf, ms, nd = (ct.c_double * nw)(), (ct.c_uint64 * nw)(), (ct.c_int32 * nw)()
+        n = ct.c_size_t()
+        self._chk(self.L.amp_get_worker_stats(self.h, wf, ms, nd, nw, ct.byref(n)))
+        return [dict(node=nd[i], wait_fraction=wf[i], messages=ms[i]) for i in range(nw)]
 
     def get_staleness_hist(self, nbins=16):
         bins = (ct.c_uint64 * nbins)()

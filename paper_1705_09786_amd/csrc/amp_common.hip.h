@@ -36,6 +36,9 @@ __device__ __forceinline__ void raise_abort(const AmpDev* D, unsigned code, unsi
     __hip_atomic_store(&D->ctl[2], detail, __ATOMIC_RELAXED, AGENT);
 }
 
+// Per-workgroup utilisation counters: [0] ticks spent waiting for messages, [1] messages taken.
+__shared__ unsigned long long s_stat[2];
+
 // Whole workgroup.  Waits for the entry with ticket `head` of ring r; returns
 // false when the run is over (done flag, abort flag, or this wait exceeded
 // the watchdog, which raises the abort flag so that every workgroup leaves).
@@ -67,6 +70,8 @@ __device__ bool wait_msg(const AmpDev* D, const RingDev& r, unsigned& head, unsi
       __builtin_amdgcn_s_sleep(1);
     }
     if (!stop) fence_acquire();
+    s_stat[0] += (unsigned long long)(wall_clock64() - t0);
+    s_stat[1] += 1ull - stop;
     s_ctl[0] = (unsigned)e;
     s_ctl[1] = stop;
   }

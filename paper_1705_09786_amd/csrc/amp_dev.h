@@ -71,6 +71,7 @@ struct WorkerDev {
   unsigned* wstate;    // persistent per-worker words: [0] count, [1] opt step (node), [2] count, [3] step (hosted lookup)
   unsigned long long* log;
   unsigned* log_n;
+  unsigned long long* stats;   // [0] ticks waiting, [1] messages taken, [2] ticks alive (100 MHz)
   unsigned log_cap, pad;
 };
 

@@ -398,7 +398,12 @@ __device__ void role_rnn_out(const AmpDev* D, const WorkerDev* W, float* lds) {
 extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const AmpDev* D) {
   extern __shared__ float lds[];
   const WorkerDev* W = &D->worker[blockIdx.x];
-  if (threadIdx.x == 0) s_logn = 0;
+  long long t_begin = 0;
+  if (threadIdx.x == 0) {
+    s_logn = 0;
+    s_stat[0] = s_stat[1] = 0;
+    t_begin = wall_clock64();
+  }
   __syncthreads();
   switch (W->role) {
     case ROLE_CTRL: role_ctrl(D, W, lds); break;
@@ -417,7 +422,12 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
     default: break;
   }
   __syncthreads();
-  if (threadIdx.x == 0 && W->log_cap) *W->log_n = s_logn;
+  if (threadIdx.x == 0) {
+    if (W->log_cap) *W->log_n = s_logn;
+    W->stats[0] = s_stat[0];
+    W->stats[1] = s_stat[1];
+    W->stats[2] = (unsigned long long)(wall_clock64() - t_begin);
+  }
 }
 
 extern "C" hipError_t amp_launch(const AmpDev* dev, int n_workers, hipStream_t stream) {

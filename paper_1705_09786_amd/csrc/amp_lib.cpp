@@ -73,6 +73,7 @@ struct amp_ctx {
   std::vector<int> last_correct;
   std::vector<amp_event> last_events;
   double last_seconds = 0;
+  std::vector<unsigned long long> last_stats;   // 3 per worker
   uint64_t last_npred = 0;
   unsigned total_admitted = 0;
   std::string err;
@@ -436,6 +437,21 @@ int amp_set_gradient_mean(amp_ctx* c, int mean) {
 int amp_num_nodes(amp_ctx* c) { return c ? (int)c->nodes.size() : AMP_EINVAL; }
 int amp_num_workers(amp_ctx* c) { return c ? (int)c->workers.size() : AMP_EINVAL; }
 
+int amp_get_worker_stats(amp_ctx* c, double* wait_fraction, uint64_t* messages, int32_t* node_of_worker, size_t cap,
+                         size_t* n) {
+  if (!c) return AMP_EINVAL;
+  if (n) *n = c->workers.size();
+  if (c->last_stats.empty()) return fail(c, AMP_ESTATE, "get_worker_stats: nothing run yet");
+  if (cap < c->workers.size()) return fail(c, AMP_ENOMEM, "get_worker_stats: %zu entries needed", c->workers.size());
+  for (size_t w = 0; w < c->workers.size(); ++w) {
+    const unsigned long long* s = &c->last_stats[3 * w];
+    if (wait_fraction) wait_fraction[w] = s[2] ? (double)s[0] / (double)s[2] : 0.0;
+    if (messages) messages[w] = s[1];
+    if (node_of_worker) node_of_worker[w] = c->workers[w].node;
+  }
+  return AMP_OK;
+}
+
 int amp_param_count(amp_ctx* c, int node_id, size_t* n) {
   if (!c || !n) return fail(c, AMP_EINVAL, "null argument");
   if (node_id < 0 || node_id >= (int)c->nodes.size()) return fail(c, AMP_EINVAL, "no node %d", node_id);
@@ -668,6 +684,7 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
     off_log[w] = take(8 * std::max<size_t>(log_cap, 1));
     off_logn[w] = take(64);
   }
+  const size_t off_stats = take(24 * c->workers.size());
   if (off > c->arena_bytes) return fail(c, AMP_ENOMEM, "arena of %zu bytes is too small, %zu needed", c->arena_bytes, off);
   HIPCHK(c, hipMemsetAsync(c->arena + off_loss, 0, off - off_loss, c->stream));
 
@@ -715,6 +732,7 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
     wd.log = (unsigned long long*)(c->arena + off_log[i]);
     wd.log_n = (unsigned*)(c->arena + off_logn[i]);
     wd.log_cap = (unsigned)log_cap;
+    wd.stats = (unsigned long long*)(c->arena + off_stats) + 3 * i;
   }
   D.model = c->model;
   D.n_workers = (int)c->workers.size();
@@ -775,6 +793,8 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
     for (HostNode& n : c->nodes) n.dirty = true;
     return fail(c, AMP_EDEVICE, "kernel stopped itself: %s (worker %u)", why, ctl[2]);
   }
+  c->last_stats.assign(3 * c->workers.size(), 0);
+  HIPCHK(c, hipMemcpy(c->last_stats.data(), c->arena + off_stats, 24 * c->workers.size(), hipMemcpyDeviceToHost));
   std::vector<float> loss(n_total);
   std::vector<int> correct(n_total);
   HIPCHK(c, hipMemcpy(loss.data(), D.loss_out, n_total * 4, hipMemcpyDeviceToHost));
