@@ -9,7 +9,9 @@
 #define AMP_MAX_BUFS 24
 #define AMP_THREADS 512
 #define AMP_LDS_BYTES 163840   // 160 KB per workgroup on gfx950
+#define AMP_DYN_LDS_BYTES (AMP_LDS_BYTES - 2048)   // dynamic part; the rest is for static __shared__
 #define AMP_TREE_LOOKUP_MAX_MUF 16384
+#define AMP_DENSE_MAX_MUF 1024        // pending-gradient list of a dense node
 
 // Message code carried by a ring entry: [31] direction, [30:20] slot,
 // [19:0] position inside the instance.
@@ -72,7 +74,9 @@ struct WorkerDev {
   unsigned long long* log;
   unsigned* log_n;
   unsigned long long* stats;   // [0] ticks waiting, [1] messages taken, [2] ticks alive (100 MHz)
-  unsigned log_cap, pad;
+  float* pend;                 // pending (delta, input) pairs of the hosted dense node
+  unsigned log_cap;
+  int kb;                      // largest batch this worker takes at once
 };
 
 // One stored instance set (training or evaluation), flattened.

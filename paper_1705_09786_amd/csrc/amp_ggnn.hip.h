@@ -100,105 +100,19 @@ __device__ void g_post_edges(const AmpDev* D, const GView& v, int s, int it, boo
     if (v.tcount[c] > 0) ring_post(D->ring[GR_EDGE0 + c], MSG_MAKE(backward, s, it));
 }
 
-// ---------------------------------------------------------------- grouped-row products
-// Y[k][r] = b[r] + sum_c Wl[r][c] X[k][c] for k < K.  X, Y are LDS row blocks
-// whose row count is K rounded up to 4 (padding rows of X must be finite).
-// Thread (p, g, r) handles row r, k-rows 4g..4g+3 and the p-th column chunk.
-__device__ void gemm_rows(const float* Wl, int ldw, int R, int C, const float* bl, const float* X, int K, float* part,
-                          float* Y) {
-  const int nkg = (K + 3) >> 2;
-  int P = AMP_THREADS / (R * nkg);
-  if (P < 1) P = 1;
-  if (P > 8) P = 8;
-  const int chunk = (C + P - 1) / P;
-  const int total = R * nkg * P;
-  for (int idx = threadIdx.x; idx < total; idx += AMP_THREADS) {
-    const int p = idx / (R * nkg);
-    const int rem = idx - p * R * nkg;
-    const int g = rem / R, r = rem - g * R;
-    const int c0 = p * chunk;
-    int c1 = c0 + chunk;
-    if (c1 > C) c1 = C;
-    const float* w = Wl + r * ldw;
-    const float* x0 = X + (4 * g) * C;
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-    for (int c = c0; c < c1; ++c) {
-      const float wv = w[c];
-      a0 = fmaf(wv, x0[c], a0);
-      a1 = fmaf(wv, x0[C + c], a1);
-      a2 = fmaf(wv, x0[2 * C + c], a2);
-      a3 = fmaf(wv, x0[3 * C + c], a3);
-    }
-    float* o = (P == 1 ? Y : part + (long long)p * nkg * 4 * R) + (4 * g) * R + r;
-    o[0] = a0;
-    o[R] = a1;
-    o[2 * R] = a2;
-    o[3 * R] = a3;
-  }
-  __syncthreads();
-  for (int i = threadIdx.x; i < nkg * 4 * R; i += AMP_THREADS) {
-    const int r = i % R;
-    float s = P == 1 ? Y[i] : 0.f;
-    if (P > 1)
-      for (int p = 0; p < P; ++p) s += part[(long long)p * nkg * 4 * R + i];
-    Y[i] = s + (bl ? bl[r] : 0.f);
-  }
-  __syncthreads();
-}
-
-// DX[k][c] = sum_r Wl[r][c] Dl[k][r] for k < K (row blocks padded to 4).
-__device__ void gemm_cols(const float* Wl, int ldw, int R, int C, const float* Dl, int K, float* part, float* DX) {
-  const int nkg = (K + 3) >> 2;
-  int P = AMP_THREADS / (C * nkg);
-  if (P < 1) P = 1;
-  if (P > 8) P = 8;
-  const int chunk = (R + P - 1) / P;
-  const int total = C * nkg * P;
-  for (int idx = threadIdx.x; idx < total; idx += AMP_THREADS) {
-    const int p = idx / (C * nkg);
-    const int rem = idx - p * C * nkg;
-    const int g = rem / C, c = rem - g * C;
-    const int r0 = p * chunk;
-    int r1 = r0 + chunk;
-    if (r1 > R) r1 = R;
-    const float* d0 = Dl + (4 * g) * R;
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-    for (int r = r0; r < r1; ++r) {
-      const float wv = Wl[r * ldw + c];
-      a0 = fmaf(wv, d0[r], a0);
-      a1 = fmaf(wv, d0[R + r], a1);
-      a2 = fmaf(wv, d0[2 * R + r], a2);
-      a3 = fmaf(wv, d0[3 * R + r], a3);
-    }
-    float* o = (P == 1 ? DX : part + (long long)p * nkg * 4 * C) + (4 * g) * C + c;
-    o[0] = a0;
-    o[C] = a1;
-    o[2 * C] = a2;
-    o[3 * C] = a3;
-  }
-  __syncthreads();
-  if (P > 1) {
-    for (int i = threadIdx.x; i < nkg * 4 * C; i += AMP_THREADS) {
-      float s = 0.f;
-      for (int p = 0; p < P; ++p) s += part[(long long)p * nkg * 4 * C + i];
-      DX[i] = s;
-    }
-    __syncthreads();
-  }
-}
-
 // G += sum_k Dl[k] (x) X[k]; bias gradient alike.  One gradient per message.
-__device__ void rows_accumulate(const NodeDev& nd, int R, int C, const float* Dl, const float* X, int K) {
+__device__ void rows_accumulate(const NodeDev& nd, int R, int C, const float* Dl, int ldd, const float* X, int ldx,
+                                int K) {
   for (int i = threadIdx.x; i < R * C; i += AMP_THREADS) {
     const int r = i / C, c = i - r * C;
     float a = 0.f;
-    for (int k = 0; k < K; ++k) a = fmaf(Dl[k * R + r], X[k * C + c], a);
+    for (int k = 0; k < K; ++k) a = fmaf(Dl[k * ldd + r], X[k * ldx + c], a);
     nd.G[i] += a;
   }
   if (nd.has_bias)
     for (int r = threadIdx.x; r < R; r += AMP_THREADS) {
       float a = 0.f;
-      for (int k = 0; k < K; ++k) a += Dl[k * R + r];
+      for (int k = 0; k < K; ++k) a += Dl[k * ldd + r];
       nd.G[(long long)R * C + r] += a;
     }
 }
@@ -268,18 +182,18 @@ __device__ void role_g_edge(const AmpDev* D, const WorkerDev* W, float* lds) {
   const NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
-  const int H = B.H, ctype = W->aux, Ep = (B.Em + 3) & ~3;
+  const int H = B.H, ctype = W->aux, Ep = (B.Em + 3) & ~3, Hs = (H + 3) & ~3;
   Lds L{lds};
   float* Wl = L.take(H * t.ldw);
   float* bl = L.take(H);
-  float* X = L.take(Ep * H);
-  float* Y = L.take(Ep * H);
-  float* DX = L.take(Ep * H);
+  float* X = L.take(Ep * Hs);
+  float* Y = L.take(Ep * Hs);
+  float* DX = L.take(Ep * Hs);
   float* acc = L.take(B.N * H);
   float* part = L.take(2048 + 4 * H);
   int* elist = (int*)L.take(B.Em);
   tile_load(nd, t, Wl, bl);
-  for (int i = threadIdx.x; i < Ep * H; i += AMP_THREADS) X[i] = Y[i] = 0.f;
+  for (int i = threadIdx.x; i < Ep * Hs; i += AMP_THREADS) X[i] = Y[i] = 0.f;
   __syncthreads();
   const RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
@@ -301,16 +215,16 @@ __device__ void role_g_edge(const AmpDev* D, const WorkerDev* W, float* lds) {
     const float* h = B.Hm + B.hm(s, it);
     for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
       const int k = i / H, j = i - k * H;
-      X[i] = h[v.src[elist[k]] * H + j];
+      X[k * Hs + j] = h[v.src[elist[k]] * H + j];
     }
     __syncthreads();
     const int nact = g_active_types(v, B.T);
     if (!(code & MSG_DIR_B)) {
-      gemm_rows(Wl, t.ldw, H, H, bl, X, K, part, Y);
+      gemm_rows(Wl, t.ldw, H, H, bl, X, Hs, K, part, Y, Hs);
       float* msg = B.Msg + (long long)s * B.Em * H;
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
         const int k = i / H, j = i - k * H;
-        msg[elist[k] * H + j] = Y[i];
+        msg[elist[k] * H + j] = Y[k * Hs + j];
       }
       LOG(W->node, 0, seq, it);
       __syncthreads();
@@ -343,14 +257,14 @@ __device__ void role_g_edge(const AmpDev* D, const WorkerDev* W, float* lds) {
     const float* dAs = B.dAs + B.sl(s);
     for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
       const int k = i / H, j = i - k * H;
-      Y[i] = dAs[v.dst[elist[k]] * H + j];
+      Y[k * Hs + j] = dAs[v.dst[elist[k]] * H + j];
     }
     for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) acc[i] = 0.f;
     __syncthreads();
     LOG(W->node, 1, seq, it);
-    gemm_cols(Wl, t.ldw, H, H, Y, K, part, DX);
+    gemm_cols(Wl, t.ldw, H, H, Y, Hs, K, part, DX, Hs);
     for (int j = threadIdx.x; j < H; j += AMP_THREADS)
-      for (int k = 0; k < K; ++k) acc[v.src[elist[k]] * H + j] += DX[k * H + j];
+      for (int k = 0; k < K; ++k) acc[v.src[elist[k]] * H + j] += DX[k * Hs + j];
     __syncthreads();
     float* dHe = B.dHe + ((long long)s * B.T + ctype) * B.N * H;
     for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) dHe[i] = acc[i];
@@ -383,7 +297,7 @@ __device__ void role_g_edge(const AmpDev* D, const WorkerDev* W, float* lds) {
           ring_post(D->ring[GR_LOOKUP], MSG_MAKE(1, s, 0));
       }
     }
-    rows_accumulate(nd, H, H, Y, X, K);
+    rows_accumulate(nd, H, H, Y, Hs, X, Hs, K);
     count_and_update(D, W, nd, t, Wl, bl, count, tstep);
   }
   tile_store(nd, t, Wl, bl);
@@ -398,17 +312,17 @@ __device__ void role_g_gate(const AmpDev* D, const WorkerDev* W, float* lds) {
   const NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
-  const int H = B.H, C = 2 * H, Np = (B.N + 3) & ~3, which = W->aux;
+  const int H = B.H, C = 2 * H, Np = (B.N + 3) & ~3, which = W->aux, Hs = (H + 3) & ~3, Cs = (C + 3) & ~3;
   Lds L{lds};
   float* Wl = L.take(H * t.ldw);
   float* bl = L.take(H);
-  float* X = L.take(Np * C);
-  float* Y = L.take(Np * H);
-  float* DX = L.take(Np * C);
+  float* X = L.take(Np * Cs);
+  float* Y = L.take(Np * Hs);
+  float* DX = L.take(Np * Cs);
   float* part = L.take(2048 + 4 * C);
   tile_load(nd, t, Wl, bl);
-  for (int i = threadIdx.x; i < Np * C; i += AMP_THREADS) X[i] = 0.f;
-  for (int i = threadIdx.x; i < Np * H; i += AMP_THREADS) Y[i] = 0.f;
+  for (int i = threadIdx.x; i < Np * Cs; i += AMP_THREADS) X[i] = 0.f;
+  for (int i = threadIdx.x; i < Np * Hs; i += AMP_THREADS) Y[i] = 0.f;
   __syncthreads();
   const RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
@@ -423,13 +337,13 @@ __device__ void role_g_gate(const AmpDev* D, const WorkerDev* W, float* lds) {
     const float* h = B.Hm + B.hm(s, it);
     for (int i = threadIdx.x; i < K * C; i += AMP_THREADS) {
       const int k = i / C, c = i - k * C;
-      X[i] = c < H ? A[k * H + c] : h[k * H + c - H];
+      X[k * Cs + c] = c < H ? A[k * H + c] : h[k * H + c - H];
     }
     __syncthreads();
     float* outp = (which == 0 ? B.Z : B.Rr) + B.st(s, it);
     if (!(code & MSG_DIR_B)) {
-      gemm_rows(Wl, t.ldw, H, C, bl, X, K, part, Y);
-      for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) outp[i] = sigmoidf_(Y[i]);
+      gemm_rows(Wl, t.ldw, H, C, bl, X, Cs, K, part, Y, Hs);
+      for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) outp[i] = sigmoidf_(Y[(i / H) * Hs + i % H]);
       LOG(W->node, 0, seq, it);
       __syncthreads();
       if (threadIdx.x == 0) {
@@ -439,18 +353,18 @@ __device__ void role_g_gate(const AmpDev* D, const WorkerDev* W, float* lds) {
       continue;
     }
     const float* dpre = (which == 0 ? B.dZ : B.dR) + B.sl(s);
-    for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) Y[i] = dpre[i];
+    for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) Y[(i / H) * Hs + i % H] = dpre[i];
     __syncthreads();
     LOG(W->node, 1, seq, it);
-    gemm_cols(Wl, t.ldw, H, C, Y, K, part, DX);
+    gemm_cols(Wl, t.ldw, H, C, Y, Hs, K, part, DX, Cs);
     float* dA = B.dA + ((long long)s * 3 + 1 + which) * B.N * H;
     float* dHp = B.dHp + ((long long)s * 3 + 1 + which) * B.N * H;
     for (int i = threadIdx.x; i < K * C; i += AMP_THREADS) {
       const int k = i / C, c = i - k * C;
       if (c < H)
-        dA[k * H + c] = DX[i];
+        dA[k * H + c] = DX[k * Cs + c];
       else
-        dHp[k * H + c - H] = DX[i];
+        dHp[k * H + c - H] = DX[k * Cs + c];
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -470,7 +384,7 @@ __device__ void role_g_gate(const AmpDev* D, const WorkerDev* W, float* lds) {
         g_post_edges(D, v, s, it, true);
       }
     }
-    rows_accumulate(nd, H, C, Y, X, K);
+    rows_accumulate(nd, H, C, Y, Hs, X, Cs, K);
     count_and_update(D, W, nd, t, Wl, bl, count, tstep);
   }
   tile_store(nd, t, Wl, bl);
@@ -485,17 +399,17 @@ __device__ void role_g_cand(const AmpDev* D, const WorkerDev* W, float* lds) {
   const NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
-  const int H = B.H, C = 2 * H, Np = (B.N + 3) & ~3;
+  const int H = B.H, C = 2 * H, Np = (B.N + 3) & ~3, Hs = (H + 3) & ~3, Cs = (C + 3) & ~3;
   Lds L{lds};
   float* Wl = L.take(H * t.ldw);
   float* bl = L.take(H);
-  float* X = L.take(Np * C);
-  float* Y = L.take(Np * H);
-  float* DX = L.take(Np * C);
+  float* X = L.take(Np * Cs);
+  float* Y = L.take(Np * Hs);
+  float* DX = L.take(Np * Cs);
   float* part = L.take(2048 + 4 * C);
   tile_load(nd, t, Wl, bl);
-  for (int i = threadIdx.x; i < Np * C; i += AMP_THREADS) X[i] = 0.f;
-  for (int i = threadIdx.x; i < Np * H; i += AMP_THREADS) Y[i] = 0.f;
+  for (int i = threadIdx.x; i < Np * Cs; i += AMP_THREADS) X[i] = 0.f;
+  for (int i = threadIdx.x; i < Np * Hs; i += AMP_THREADS) Y[i] = 0.f;
   __syncthreads();
   const RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
@@ -512,14 +426,14 @@ __device__ void role_g_cand(const AmpDev* D, const WorkerDev* W, float* lds) {
     float* Ht = B.Ht + B.st(s, it);
     for (int i = threadIdx.x; i < K * C; i += AMP_THREADS) {
       const int k = i / C, c = i - k * C;
-      X[i] = c < H ? A[k * H + c] : Rr[k * H + c - H] * h[k * H + c - H];
+      X[k * Cs + c] = c < H ? A[k * H + c] : Rr[k * H + c - H] * h[k * H + c - H];
     }
     __syncthreads();
     if (!(code & MSG_DIR_B)) {
-      gemm_rows(Wl, t.ldw, H, C, bl, X, K, part, Y);
+      gemm_rows(Wl, t.ldw, H, C, bl, X, Cs, K, part, Y, Hs);
       float* hn = B.Hm + B.hm(s, it + 1);
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
-        const float ht = tanhf(Y[i]), z = Z[i];
+        const float ht = tanhf(Y[(i / H) * Hs + i % H]), z = Z[i];
         Ht[i] = ht;
         hn[i] = (1.f - z) * h[i] + z * ht;
       }
@@ -541,17 +455,17 @@ __device__ void role_g_cand(const AmpDev* D, const WorkerDev* W, float* lds) {
     for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
       const float g = gH[i], z = Z[i], ht = Ht[i];
       dZ[i] = g * (ht - h[i]) * z * (1.f - z);
-      Y[i] = g * z * (1.f - ht * ht);
+      Y[(i / H) * Hs + i % H] = g * z * (1.f - ht * ht);
     }
     __syncthreads();
     LOG(W->node, 1, seq, it);
-    gemm_cols(Wl, t.ldw, H, C, Y, K, part, DX);
+    gemm_cols(Wl, t.ldw, H, C, Y, Hs, K, part, DX, Cs);
     float* dA = B.dA + (long long)s * 3 * B.N * H;
     float* dHp = B.dHp + (long long)s * 3 * B.N * H;
     for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
       const int k = i / H, j = i - k * H;
-      const float drh = DX[k * C + H + j], r = Rr[i], z = Z[i];
-      dA[i] = DX[k * C + j];
+      const float drh = DX[k * Cs + H + j], r = Rr[i], z = Z[i];
+      dA[i] = DX[k * Cs + j];
       dR[i] = drh * h[i] * r * (1.f - r);
       dHp[i] = drh * r + gH[i] * (1.f - z);
     }
@@ -561,7 +475,7 @@ __device__ void role_g_cand(const AmpDev* D, const WorkerDev* W, float* lds) {
       ring_post(D->ring[GR_GZ(D)], MSG_MAKE(1, s, it));
       ring_post(D->ring[GR_GR(D)], MSG_MAKE(1, s, it));
     }
-    rows_accumulate(nd, H, C, Y, X, K);
+    rows_accumulate(nd, H, C, Y, Hs, X, Cs, K);
     count_and_update(D, W, nd, t, Wl, bl, count, tstep);
   }
   tile_store(nd, t, Wl, bl);

@@ -391,6 +391,7 @@ __device__ void role_rnn_out(const AmpDev* D, const WorkerDev* W, float* lds) {
   }
 }
 
+#include "amp_batch.hip.h"
 #include "amp_tree.hip.h"
 #include "amp_ggnn.hip.h"
 
@@ -434,10 +435,10 @@ extern "C" hipError_t amp_launch(const AmpDev* dev, int n_workers, hipStream_t s
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)amp_persistent, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       AMP_LDS_BYTES - 256);
+                                       AMP_DYN_LDS_BYTES);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(amp_persistent, dim3(n_workers), dim3(AMP_THREADS), AMP_LDS_BYTES - 256, stream, dev);
+  hipLaunchKernelGGL(amp_persistent, dim3(n_workers), dim3(AMP_THREADS), AMP_DYN_LDS_BYTES, stream, dev);
   return hipGetLastError();
 }

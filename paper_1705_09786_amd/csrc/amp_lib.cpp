@@ -32,7 +32,8 @@ struct HostNode {
 
 struct HostWorker {
   int role, node, tile, ntiles, u0, nu, ring, aux;
-  size_t off_state;
+  int kb = 1;
+  size_t off_state, off_pend = 0, pend_bytes = 0;
 };
 
 struct InstSet {
@@ -129,24 +130,49 @@ unsigned next_pow2(size_t v) {
   return p;
 }
 
-// LDS floats a worker needs (mirrors the carving in the kernels).
-size_t lds_floats(const amp_ctx* c, const HostWorker& w) {
-  auto r4 = [](size_t n) { return (n + 3) & ~(size_t)3; };
+size_t r4(size_t n) { return (n + 3) & ~(size_t)3; }
+size_t r8(size_t n) { return (n + 7) & ~(size_t)7; }
+
+// LDS floats a worker needs (mirrors the carving in the kernels); sets w.kb.
+// Returns 0 when the worker cannot fit.
+size_t lds_floats(const amp_ctx* c, HostWorker& w) {
+  const size_t avail = AMP_DYN_LDS_BYTES / 4;
+  w.kb = 1;
   if (w.role == ROLE_CTRL) return r4(c->max_mak);
-  if (w.role == ROLE_TREE_LOOKUP) return r4(c->max_mak) + AMP_TREE_LOOKUP_MAX_MUF;
+  if (w.role == ROLE_TREE_LOOKUP) {
+    w.kb = 32;
+    return r4(c->max_mak) + AMP_TREE_LOOKUP_MAX_MUF;
+  }
   if (w.role >= ROLE_G_LOOKUP) {
     const size_t H = c->dims.hidden, N = c->max_len, Ep = (c->max_edges + 3) & ~3, Np = (N + 3) & ~3;
+    const size_t Hs = r4(H), Cs = r4(2 * H);
     if (w.role == ROLE_G_LOOKUP) return r4((size_t)c->dims.n_node_types * H);
     if (w.role == ROLE_G_EDGE)
-      return r4(H * (H | 1)) + r4(H) + 3 * r4(Ep * H) + r4(N * H) + r4(2048 + 4 * H) + r4(c->max_edges);
+      return r4(H * (H | 1)) + r4(H) + 3 * r4(Ep * Hs) + r4(N * H) + r4(2048 + 4 * H) + r4(c->max_edges);
     if (w.role == ROLE_G_READOUT) return r4(H | 1) + 4 + r4(H) + AMP_THREADS;
-    return r4(H * (2 * H | 1)) + r4(H) + 2 * r4(Np * 2 * H) + r4(Np * H) + r4(2048 + 8 * H);
+    return r4(H * (2 * H | 1)) + r4(H) + 2 * r4(Np * Cs) + r4(Np * Hs) + r4(2048 + 8 * H);
   }
   const HostNode& n = c->nodes[w.node];
   const size_t R = (size_t)n.nblocks * w.nu, C = n.cols, ldw = C | 1;
+  const size_t stride = r8(R) + r8(C);
+  if (w.role == ROLE_TREE_LEAF || w.role == ROLE_TREE_BRANCH) {
+    const size_t fixed = r4(R * ldw) + r4(R) + r4(2048 + 512);
+    const size_t ldx = r4(C), ldy = r4(R);
+    if (fixed + 8 * stride + 4 * ldy > avail) return 0;
+    size_t kb = (avail - fixed) / (ldx + ldy);
+    kb = std::min<size_t>(kb, 16) & ~(size_t)3;
+    while (kb >= 4 && fixed + std::max(kb * ldx, 8 * stride) + kb * ldy > avail) kb -= 4;
+    if (kb < 4) return 0;
+    w.kb = (int)kb;
+    return fixed + std::max(kb * ldx, 8 * stride) + kb * ldy;
+  }
+  if (w.role == ROLE_TREE_OUT) {
+    w.kb = 32;
+    const size_t NW = AMP_THREADS / 64;
+    return r4(R * ldw) + r4(R) + r4(NW * C) + r4(NW * 64) + r4(8 * stride) + r4(c->max_mak);
+  }
   size_t f = r4(R * ldw) + r4(R) + r4(C) + r4(R) + r4(R) + r4(C) + r4(8 * std::max(R, C));
   if (w.role == ROLE_RNN_CELL) f += r4((size_t)c->dims.vocab * c->dims.emb);
-  if (w.role == ROLE_TREE_OUT) f += r4(c->max_mak);
   return f;
 }
 
@@ -200,7 +226,7 @@ int amp_build_treelstm(amp_ctx* c, const amp_model_dims* d) {
   c->dims = *d;
   c->nodes = {make_node("lookup", d->vocab, d->emb, 0), make_node("leaf", 3 * d->hidden, d->emb, 1, 3),
               make_node("branch", 5 * d->hidden, 2 * d->hidden, 1, 5), make_node("out", d->n_class, d->hidden, 1)};
-  c->nodes[1].tiles = 4;
+  c->nodes[1].tiles = 5;
   c->nodes[2].tiles = 8;
   return AMP_OK;
 }
@@ -307,11 +333,11 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     nrings = (int)c->workers.size();
   }
   if (c->workers.size() > AMP_MAX_WORKERS) return fail(c, AMP_EUNSUPPORTED, "finalize: too many workers");
-  for (const HostWorker& w : c->workers) {
-    const size_t need = lds_floats(c, w) * 4 + 256;
-    if (need > AMP_LDS_BYTES)
-      return fail(c, AMP_EUNSUPPORTED, "finalize: worker for node %d tile %d needs %zu bytes of LDS (limit %d); use more tiles",
-                  w.node, w.tile, need, AMP_LDS_BYTES);
+  for (HostWorker& w : c->workers) {
+    const size_t need = lds_floats(c, w) * 4;
+    if (need == 0 || need > AMP_DYN_LDS_BYTES)
+      return fail(c, AMP_EUNSUPPORTED, "finalize: the worker for node %d tile %d does not fit %d bytes of LDS; use more tiles",
+                  w.node, w.tile, AMP_DYN_LDS_BYTES);
   }
 
   // ---- arena layout
@@ -340,7 +366,15 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     n.off_M = take(b);
     n.off_V = take(b);
   }
-  for (HostWorker& w : c->workers) w.off_state = take(64);
+  for (HostWorker& w : c->workers) {
+    w.off_state = take(64);
+    if (w.node >= 0 && c->nodes[w.node].name != "lookup") {
+      const HostNode& n = c->nodes[w.node];
+      const size_t stride = r8((size_t)n.nblocks * w.nu) + r8(n.cols);
+      w.pend_bytes = stride * 4 * AMP_DENSE_MAX_MUF;
+      w.off_pend = take(w.pend_bytes);
+    }
+  }
   // model-specific per-slot storage
   const size_t mak = c->max_mak, H = c->dims.hidden;
   auto buf = [&](int i, size_t floats_per_slot) {
@@ -368,6 +402,9 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     c->buf_stride[10] = 0;
     c->buf_bytes[10] = 4 * (size_t)AMP_TREE_LOOKUP_MAX_MUF;
     c->off_buf[10] = take(c->buf_bytes[10]);
+    c->buf_stride[11] = 0;
+    c->buf_bytes[11] = 4 * (size_t)AMP_TREE_LOOKUP_MAX_MUF * E;
+    c->off_buf[11] = take(c->buf_bytes[11]);
   } else if (c->model == AMP_MODEL_GGNN) {
     const size_t N = c->max_len, E = c->max_edges, S = c->dims.n_steps, T = c->dims.n_edge_types;
     buf(0, (S + 1) * N * H);
@@ -622,6 +659,9 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   if (S.n() == 0) return fail(c, AMP_ESTATE, "no instances submitted");
   if (c->model == AMP_MODEL_TREE && c->nodes[0].muf > AMP_TREE_LOOKUP_MAX_MUF)
     return fail(c, AMP_EUNSUPPORTED, "the tree lookup supports min_update_frequency up to %d", AMP_TREE_LOOKUP_MAX_MUF);
+  for (const HostNode& n : c->nodes)
+    if (n.name != "lookup" && n.muf > AMP_DENSE_MAX_MUF)
+      return fail(c, AMP_EUNSUPPORTED, "dense nodes support min_update_frequency up to %d", AMP_DENSE_MAX_MUF);
   const size_t n_total = S.n() * (size_t)epochs;
   if (n_total >= 0xffffffffull) return fail(c, AMP_EINVAL, "too many admissions for one call");
   int dev_id = 0;
@@ -733,6 +773,8 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
     wd.log_n = (unsigned*)(c->arena + off_logn[i]);
     wd.log_cap = (unsigned)log_cap;
     wd.stats = (unsigned long long*)(c->arena + off_stats) + 3 * i;
+    wd.pend = w.pend_bytes ? (float*)(c->arena + w.off_pend) : nullptr;
+    wd.kb = w.kb;
   }
   D.model = c->model;
   D.n_workers = (int)c->workers.size();

@@ -2,10 +2,11 @@
 // branch cell, output layer with a softmax loss at every tree node.
 //
 // Leaf and branch cells are split over several workgroups ("tiles", Section
-// 5.1); the tiles of a cell read the same ring in the same order, so they act
-// as one node with one event order.  Tile t owns hidden units [u0, u0+nu) of
-// every gate, computes those units' h and c entirely, and contributes a
-// partial W^T delta over all input columns on the way back.
+// 5.1); the tiles of a cell read the same ring in the same order and cut
+// their batches at the same places, so they act as one node with one event
+// order.  Tile t owns hidden units [u0, u0+nu) of every gate, computes those
+// units' h and c entirely, and contributes a partial W^T delta over all
+// input columns on the way back.
 //
 // Slot storage (s = slot, n = tree node, l = leaf):
 //   buf[0] xin  [s][l][D]        embedding recorded by the lookup's forward
@@ -17,6 +18,8 @@
 //   buf[6] gx   [s][l][TL][D]    dx partials from the leaf tiles
 //   buf[7] cnt  [s][n][4] (int)  arrival counters: tiles done / children done /
 //                                gradient parts / leaf-tile dx parts
+//   buf[10] lookup: tokens of the gradients waiting for the next update
+//   buf[11] lookup: their gradient rows [AMP_TREE_LOOKUP_MAX_MUF][D]
 #pragma once
 
 struct TreeView {
@@ -73,164 +76,252 @@ __device__ __forceinline__ TreeBufs tree_bufs(const AmpDev* D) {
 #define TR_BRANCH 3
 #define TR_OUT 4
 
+__device__ __forceinline__ bool code_is_b(unsigned c) { return (c & MSG_DIR_B) != 0; }
+
 // A tile has finished its units of node n: when all tiles have, the node's
 // [h; c] goes to the output layer and, through Isu / Concat, to its parent,
-// which fires once both children are there.  ONE thread.
-__device__ void tree_node_part_done(const AmpDev* D, const TreeBufs& B, const TreeView& v, int s, int n, int ntiles) {
-  fence_release();
+// which fires once both children are there.  One lane, after a release fence.
+__device__ void tree_node_part_done(const AmpDev* D, const TreeBufs& B, int s, int n, int parent_code, int ntiles) {
   int* c = B.cnt + B.node(s, n) * 4;
   if (!join_arrive(c + 0, ntiles)) return;
   ring_post(D->ring[TR_OUT], MSG_MAKE(0, s, n));
-  const int pp = v.parent[n];
-  if (pp < 0) return;
-  const int p = pp >> 1;
+  if (parent_code < 0) return;
+  const int p = parent_code >> 1;
   if (join_arrive(B.cnt + B.node(s, p) * 4 + 1, 2)) ring_post(D->ring[TR_BRANCH], MSG_MAKE(0, s, p));
 }
 
 // One gradient part for node n has been written: Bcast's backward waits for
 // the output layer's part and (unless n is the root) every parent tile's.
-__device__ void tree_grad_part_done(const AmpDev* D, const TreeBufs& B, const TreeView& v, int s, int n) {
-  const int expect = v.parent[n] < 0 ? 1 : 1 + B.TB;
+__device__ void tree_grad_part_done(const AmpDev* D, const TreeBufs& B, int s, int n, bool is_root, bool is_leaf) {
+  const int expect = is_root ? 1 : 1 + B.TB;
   if (join_arrive(B.cnt + B.node(s, n) * 4 + 2, expect))
-    ring_post(D->ring[n < v.L ? TR_LEAF : TR_BRANCH], MSG_MAKE(1, s, n));
+    ring_post(D->ring[is_leaf ? TR_LEAF : TR_BRANCH], MSG_MAKE(1, s, n));
 }
 
 // ------------------------------------------------------------ lookup
+// Thread c owns column c of every row it touches, so the messages of a batch
+// need no barriers between them.
 __device__ void role_tree_lookup(const AmpDev* D, const WorkerDev* W, float* lds) {
   const NodeDev& lk = D->node[0];
   const TreeBufs B = tree_bufs(D);
-  const int E = B.D;
-  int* left_cnt = (int*)lds;                 // [mak] leaves not yet answered
-  int* pend = left_cnt + ((D->mak + 3) & ~3); // tokens touched since the last update
+  const int E = B.D, KB = W->kb;
+  int* left_cnt = (int*)lds;                  // [mak] leaves not yet answered
+  int* pend_tok = left_cnt + ((D->mak + 3) & ~3);
   for (int i = threadIdx.x; i < D->mak; i += AMP_THREADS) left_cnt[i] = 0;
-  __syncthreads();
+  BatchMsg& M = s_M;
   const RingDev& mine = D->ring[W->ring];
-  unsigned head = 0, code;
+  unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
-  // tokens whose gradients were still waiting for an update when the previous call ended
   int* keep = (int*)D->buf[10];
-  for (unsigned k = threadIdx.x; k < count; k += AMP_THREADS) pend[k] = keep[k];
+  float* prow = (float*)D->buf[11];
+  for (unsigned k = threadIdx.x; k < count; k += AMP_THREADS) pend_tok[k] = keep[k];
   __syncthreads();
-  while (wait_msg(D, mine, head, s_ctl, code)) {
-    const int s = MSG_SLOT(code), l = MSG_LOCAL(code);
-    const unsigned seq = D->slot_seq[s];
-    const TreeView v = tree_view(D, seq);
-    const int tok = v.tok[l];
-    if (!(code & MSG_DIR_B)) {
-      const float* row = lk.P + (long long)tok * E;
-      float* x = B.xin + B.leaf(s, l) * E;
-      for (int c = threadIdx.x; c < E; c += AMP_THREADS) x[c] = row[c];
-      LOG(0, 0, seq, l);
-      __syncthreads();
-      if (threadIdx.x == 0) {
-        if (l == 0) left_cnt[s] = v.L;
-        fence_release();
-        ring_post(D->ring[TR_LEAF], MSG_MAKE(0, s, l));
-      }
-      continue;
+  for (;;) {
+    const int n = wait_batch(D, mine, head, KB, lk.muf - (int)count, s_codes, &s_n, code_is_b);
+    if (n == 0) break;
+    if ((int)threadIdx.x < n) {
+      const int k = threadIdx.x;
+      const unsigned code = s_codes[k];
+      const int s = MSG_SLOT(code), l = MSG_LOCAL(code);
+      const unsigned seq = D->slot_seq[s];
+      const TreeView v = tree_view(D, seq);
+      M.s[k] = s;
+      M.n[k] = l;
+      M.seq[k] = seq;
+      M.a[k] = v.tok[l];
+      M.aux[k] = code_is_b(code);
+      if (!code_is_b(code) && l == 0) left_cnt[s] = v.L;
     }
-    // backward: sum the leaf tiles' partials in tile order, add to the table's accumulator
-    const float* gx = B.gx + B.leaf(s, l) * B.TL * E;
-    float* g = lk.G + (long long)tok * E;
-    for (int c = threadIdx.x; c < E; c += AMP_THREADS) {
-      float a = 0.f;
-      for (int t = 0; t < B.TL; ++t) a += gx[t * E + c];
-      g[c] += a;
-    }
-    LOG(0, 1, seq, l);
-    if (threadIdx.x == 0) pend[count] = tok;
-    count++;
     __syncthreads();
+    // ordinal of each backward message inside the batch
     if (threadIdx.x == 0) {
-      if (--left_cnt[s] == 0) {
-        fence_release();
-        ring_post(D->ring[0], MSG_MAKE(1, s, 0));
+      int nb = 0;
+      for (int k = 0; k < n; ++k) {
+        M.b[k] = nb;
+        if (M.aux[k]) pend_tok[count + nb++] = M.a[k];
+      }
+      M.nB = nb;
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < E; c += AMP_THREADS) {
+      float v[KB_MAX];
+#pragma unroll
+      for (int k = 0; k < KB_MAX; ++k) {
+        v[k] = 0.f;
+        if (k < n) {
+          if (!M.aux[k]) {
+            v[k] = lk.P[(long long)M.a[k] * E + c];
+          } else {
+            const float* gx = B.gx + B.leaf(M.s[k], M.n[k]) * B.TL * E + c;
+            float a = 0.f;
+            for (int t = 0; t < B.TL; ++t) a += gx[t * E];
+            v[k] = a;
+          }
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < KB_MAX; ++k) {
+        if (k < n) {
+          if (!M.aux[k])
+            B.xin[B.leaf(M.s[k], M.n[k]) * E + c] = v[k];
+          else
+            prow[(long long)(count + M.b[k]) * E + c] = v[k];
+        }
       }
     }
+    if (threadIdx.x == 0 && W->log_cap)
+      for (int k = 0; k < n; ++k) log_event(D, W, &s_logn, 0, M.aux[k], M.seq[k], M.n[k]);
+    __syncthreads();
+    if (threadIdx.x < 64) {
+      fence_release();
+      const int k = threadIdx.x;
+      if (k < n) {
+        if (!M.aux[k]) {
+          ring_post(D->ring[TR_LEAF], MSG_MAKE(0, M.s[k], M.n[k]));
+        } else if (D->train) {
+          if (atomicSub(&left_cnt[M.s[k]], 1) == 1) ring_post(D->ring[0], MSG_MAKE(1, M.s[k], 0));
+        }
+      }
+    }
+    count += M.nB;
     if ((int)count >= lk.muf) {
-      // SGD on the touched rows only: an untouched row has a zero gradient
+      // SGD on the touched rows: each waiting gradient row is subtracted from its
+      // token's row, in arrival order (rows never touched have a zero gradient)
       tstep++;
       const float sc = lk.lr * (lk.mean ? 1.f / (float)count : 1.f);
-      for (unsigned k = 0; k < count; ++k) {
-        float* row = lk.P + (long long)pend[k] * E;
-        float* gr = lk.G + (long long)pend[k] * E;
-        for (int c = threadIdx.x; c < E; c += AMP_THREADS) {
-          row[c] -= sc * gr[c];
-          gr[c] = 0.f;
+      __syncthreads();
+      for (int c = threadIdx.x; c < E; c += AMP_THREADS) {
+        for (unsigned k0 = 0; k0 < count; k0 += 16) {
+          const int kc = count - k0 < 16u ? (int)(count - k0) : 16;
+          float w[16], g[16];
+#pragma unroll
+          for (int k = 0; k < 16; ++k)
+            if (k < kc) {
+              w[k] = lk.P[(long long)pend_tok[k0 + k] * E + c];
+              g[k] = prow[(long long)(k0 + k) * E + c];
+            }
+#pragma unroll
+          for (int k = 0; k < 16; ++k)
+            if (k < kc) {
+              // a token seen earlier in this chunk: continue from that result
+              float base = w[k];
+#pragma unroll
+              for (int j = 0; j < 16; ++j)
+                if (j < k && pend_tok[k0 + j] == pend_tok[k0 + k]) base = w[j];
+              w[k] = base - sc * g[k];
+            }
+#pragma unroll
+          for (int k = 0; k < 16; ++k)
+            if (k < kc) lk.P[(long long)pend_tok[k0 + k] * E + c] = w[k];
         }
-        __syncthreads();   // a token may occur twice: its row must be finished before it is seen again
       }
       count = 0;
-      LOG(0, 2, 0, 0);
+      if (threadIdx.x == 0) log_event(D, W, &s_logn, 0, 2, 0, 0);
     }
+    __syncthreads();
   }
-  // gradients still pending stay in G; remember their tokens for the next call
   __syncthreads();
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;
   }
-  for (unsigned k = threadIdx.x; k < count; k += AMP_THREADS) keep[k] = pend[k];
+  for (unsigned k = threadIdx.x; k < count; k += AMP_THREADS) keep[k] = pend_tok[k];
 }
 
 // ------------------------------------------------------------ leaf / branch cells
-// is_branch = false: rows [i; o; u] over the embedding.
-// is_branch = true : rows [i; f_l; f_r; o; u] over [h_l; h_r].
+// BR = false: rows [i; o; u] over the embedding.
+// BR = true : rows [i; f_l; f_r; o; u] over [h_l; h_r].
 template <bool BR>
 __device__ void role_tree_cell(const AmpDev* D, const WorkerDev* W, float* lds) {
   const NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const TreeBufs B = tree_bufs(D);
-  const int R = t.R, C = t.C, H = B.H, nu = t.nu, u0 = t.u0;
-  constexpr int NG = BR ? 5 : 3;
+  const Pend pd = make_pend(W, t);
+  const int R = t.R, C = t.C, H = B.H, nu = t.nu, u0 = t.u0, KB = W->kb;
+  const int ldx = (C + 3) & ~3, ldy = (R + 3) & ~3, KBp = (KB + 3) & ~3;
   Lds L{lds};
   float* Wl = L.take(R * t.ldw);
   float* bl = L.take(R);
-  float* xs = L.take(C);
-  float* ys = L.take(R);
-  float* ds = L.take(R);
-  float* dx = L.take(C);
-  float* part = L.take(8 * (R > C ? R : C));
+  const int xfloats = KBp * ldx > 8 * pd.stride ? KBp * ldx : 8 * pd.stride;
+  float* X = L.take(xfloats);
+  float* Y = L.take(KBp * ldy);
+  float* part = L.take(2048 + 512);
   tile_load(nd, t, Wl, bl);
+  for (int i = threadIdx.x; i < xfloats; i += AMP_THREADS) X[i] = 0.f;
+  for (int i = threadIdx.x; i < KBp * ldy; i += AMP_THREADS) Y[i] = 0.f;
+  BatchMsg& M = s_M;
+  __syncthreads();
   const RingDev& mine = D->ring[W->ring];
-  unsigned head = 0, code;
+  unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
-  while (wait_msg(D, mine, head, s_ctl, code)) {
-    const int s = MSG_SLOT(code), n = MSG_LOCAL(code);
-    const unsigned seq = D->slot_seq[s];
-    const TreeView v = tree_view(D, seq);
-    const int a = BR ? v.left[n] : 0, b = BR ? v.right[n] : 0;
-    const float* hca = B.hc + B.node(s, a) * 2 * H;
-    const float* hcb = B.hc + B.node(s, b) * 2 * H;
-    float* hcn = B.hc + B.node(s, n) * 2 * H;
-    float* gt = B.gate + B.node(s, n) * 6 * H;
-    // input columns: the embedding, or the children's hidden states
-    if (BR) {
-      for (int c = threadIdx.x; c < C; c += AMP_THREADS) xs[c] = c < H ? hca[c] : hcb[c - H];
-    } else {
-      const float* x = B.xin + B.leaf(s, n) * C;
-      for (int c = threadIdx.x; c < C; c += AMP_THREADS) xs[c] = x[c];
+  for (;;) {
+    const int n = wait_batch(D, mine, head, KB, nd.muf - (int)count, s_codes, &s_n, code_is_b);
+    if (n == 0) break;
+    if ((int)threadIdx.x < n) {
+      const int k = threadIdx.x;
+      const unsigned code = s_codes[k];
+      const int s = MSG_SLOT(code), nn = MSG_LOCAL(code);
+      const unsigned seq = D->slot_seq[s];
+      const TreeView v = tree_view(D, seq);
+      M.s[k] = s;
+      M.n[k] = nn;
+      M.seq[k] = seq;
+      M.a[k] = BR ? v.left[nn] : 0;
+      M.b[k] = BR ? v.right[nn] : 0;
+      M.par[k] = v.parent[nn];
+      M.L[k] = v.L;
+      M.aux[k] = code_is_b(code);
     }
     __syncthreads();
-    if (!(code & MSG_DIR_B)) {
-      gemv_rows(Wl, t.ldw, R, C, bl, xs, part, ys);
-      for (int j = threadIdx.x; j < nu; j += AMP_THREADS) {
-        const int u = u0 + j;
+    if (threadIdx.x == 0) {
+      int nf = 0, nb = 0;
+      for (int k = 0; k < n; ++k) {
+        if (M.aux[k])
+          M.bidx[nb++] = k;
+        else
+          M.fidx[nf++] = k;
+        if (W->tile == 0) log_event(D, W, &s_logn, W->node, M.aux[k], M.seq[k], M.n[k]);
+      }
+      M.nF = nf;
+      M.nB = nb;
+    }
+    __syncthreads();
+    const int nF = M.nF, nB = M.nB;
+    // ---------------- forward messages of the batch
+    if (nF > 0) {
+      for (int i = threadIdx.x; i < nF * C; i += AMP_THREADS) {
+        const int k = i / C, c = i - k * C, m = M.fidx[k];
+        float v;
+        if (BR)
+          v = c < H ? B.hc[B.node(M.s[m], M.a[m]) * 2 * H + c] : B.hc[B.node(M.s[m], M.b[m]) * 2 * H + c - H];
+        else
+          v = B.xin[B.leaf(M.s[m], M.n[m]) * C + c];
+        X[k * ldx + c] = v;
+      }
+      __syncthreads();
+      gemm_rows(Wl, t.ldw, R, C, bl, X, ldx, nF, part, Y, ldy);
+      for (int i = threadIdx.x; i < nF * nu; i += AMP_THREADS) {
+        const int k = i / nu, j = i - k * nu, m = M.fidx[k], u = u0 + j;
+        const float* y = Y + k * ldy;
+        float* hcn = B.hc + B.node(M.s[m], M.n[m]) * 2 * H;
+        float* gt = B.gate + B.node(M.s[m], M.n[m]) * 6 * H;
         float c_, o_;
         if (BR) {
-          const float i_ = sigmoidf_(ys[j]), fl = sigmoidf_(ys[nu + j]), fr = sigmoidf_(ys[2 * nu + j]);
-          o_ = sigmoidf_(ys[3 * nu + j]);
-          const float g_ = tanhf(ys[4 * nu + j]);
-          c_ = i_ * g_ + fl * hca[H + u] + fr * hcb[H + u];
+          const float cl = B.hc[B.node(M.s[m], M.a[m]) * 2 * H + H + u];
+          const float cr = B.hc[B.node(M.s[m], M.b[m]) * 2 * H + H + u];
+          const float i_ = sigmoidf_(y[j]), fl = sigmoidf_(y[nu + j]), fr = sigmoidf_(y[2 * nu + j]);
+          o_ = sigmoidf_(y[3 * nu + j]);
+          const float g_ = tanhf(y[4 * nu + j]);
+          c_ = i_ * g_ + fl * cl + fr * cr;
           gt[u] = i_;
           gt[H + u] = fl;
           gt[2 * H + u] = fr;
           gt[3 * H + u] = o_;
           gt[4 * H + u] = g_;
         } else {
-          const float i_ = sigmoidf_(ys[j]);
-          o_ = sigmoidf_(ys[nu + j]);
-          const float g_ = tanhf(ys[2 * nu + j]);
+          const float i_ = sigmoidf_(y[j]);
+          o_ = sigmoidf_(y[nu + j]);
+          const float g_ = tanhf(y[2 * nu + j]);
           c_ = i_ * g_;
           gt[u] = i_;
           gt[3 * H + u] = o_;
@@ -241,137 +332,228 @@ __device__ void role_tree_cell(const AmpDev* D, const WorkerDev* W, float* lds) 
         hcn[u] = o_ * tc;
         hcn[H + u] = c_;
       }
-      LOG(W->node, 0, seq, n);
       __syncthreads();
-      if (threadIdx.x == 0) tree_node_part_done(D, B, v, s, n, W->ntiles);
-      continue;
     }
-    // ---- backward
-    const bool root = v.parent[n] < 0;
-    const float* gout = B.gout + B.node(s, n) * H;
-    const float* gpar = B.gpar + B.node(s, n) * B.TB * H;
-    const float* gcn = B.gc + B.node(s, n) * H;
-    for (int j = threadIdx.x; j < nu; j += AMP_THREADS) {
-      const int u = u0 + j;
-      float dh = gout[u], dc = 0.f;
-      if (!root) {
-        float p = 0.f;
-        for (int k = 0; k < B.TB; ++k) p += gpar[k * H + u];
-        dh += p;
-        dc = gcn[u];
-      }
-      const float i_ = gt[u], o_ = gt[3 * H + u], g_ = gt[4 * H + u], tc = gt[5 * H + u];
-      const float dct = dc + dh * o_ * (1.f - tc * tc);
-      const float d_o = dh * tc * o_ * (1.f - o_);
-      const float d_i = dct * g_ * i_ * (1.f - i_);
-      const float d_g = dct * i_ * (1.f - g_ * g_);
-      if (BR) {
-        const float fl = gt[H + u], fr = gt[2 * H + u];
-        ds[j] = d_i;
-        ds[nu + j] = dct * hca[H + u] * fl * (1.f - fl);
-        ds[2 * nu + j] = dct * hcb[H + u] * fr * (1.f - fr);
-        ds[3 * nu + j] = d_o;
-        ds[4 * nu + j] = d_g;
-        B.gc[B.node(s, a) * H + u] = dct * fl;
-        B.gc[B.node(s, b) * H + u] = dct * fr;
-      } else {
-        ds[j] = d_i;
-        ds[nu + j] = d_o;
-        ds[2 * nu + j] = d_g;
-      }
-    }
-    __syncthreads();
-    LOG(W->node, 1, seq, n);
-    gemv_cols(Wl, t.ldw, R, C, ds, part, dx);
-    if (BR) {
-      float* pa = B.gpar + (B.node(s, a) * B.TB + W->tile) * H;
-      float* pb = B.gpar + (B.node(s, b) * B.TB + W->tile) * H;
-      for (int c = threadIdx.x; c < C; c += AMP_THREADS) {
-        if (c < H)
-          pa[c] = dx[c];
+    // ---------------- backward messages of the batch
+    if (nB > 0) {
+      for (int i = threadIdx.x; i < nB * C; i += AMP_THREADS) {
+        const int k = i / C, c = i - k * C, m = M.bidx[k];
+        float v;
+        if (BR)
+          v = c < H ? B.hc[B.node(M.s[m], M.a[m]) * 2 * H + c] : B.hc[B.node(M.s[m], M.b[m]) * 2 * H + c - H];
         else
-          pb[c - H] = dx[c];
+          v = B.xin[B.leaf(M.s[m], M.n[m]) * C + c];
+        X[k * ldx + c] = v;
       }
-    } else {
-      float* px = B.gx + (B.leaf(s, n) * B.TL + W->tile) * C;
-      for (int c = threadIdx.x; c < C; c += AMP_THREADS) px[c] = dx[c];
+      for (int i = threadIdx.x; i < nB * nu; i += AMP_THREADS) {
+        const int k = i / nu, j = i - k * nu, m = M.bidx[k], u = u0 + j;
+        const long long nn = B.node(M.s[m], M.n[m]);
+        const float* gt = B.gate + nn * 6 * H;
+        float dh = B.gout[nn * H + u], dc = 0.f;
+        if (M.par[m] >= 0) {
+          const float* gp = B.gpar + nn * B.TB * H + u;
+          float p = 0.f;
+          for (int q = 0; q < B.TB; ++q) p += gp[q * H];
+          dh += p;
+          dc = B.gc[nn * H + u];
+        }
+        const float i_ = gt[u], o_ = gt[3 * H + u], g_ = gt[4 * H + u], tc = gt[5 * H + u];
+        const float dct = dc + dh * o_ * (1.f - tc * tc);
+        const float d_o = dh * tc * o_ * (1.f - o_);
+        const float d_i = dct * g_ * i_ * (1.f - i_);
+        const float d_g = dct * i_ * (1.f - g_ * g_);
+        float* ds = Y + k * ldy;
+        if (BR) {
+          const long long na = B.node(M.s[m], M.a[m]), nb = B.node(M.s[m], M.b[m]);
+          const float fl = gt[H + u], fr = gt[2 * H + u];
+          ds[j] = d_i;
+          ds[nu + j] = dct * B.hc[na * 2 * H + H + u] * fl * (1.f - fl);
+          ds[2 * nu + j] = dct * B.hc[nb * 2 * H + H + u] * fr * (1.f - fr);
+          ds[3 * nu + j] = d_o;
+          ds[4 * nu + j] = d_g;
+          B.gc[na * H + u] = dct * fl;
+          B.gc[nb * H + u] = dct * fr;
+        } else {
+          ds[j] = d_i;
+          ds[nu + j] = d_o;
+          ds[2 * nu + j] = d_g;
+        }
+      }
+      __syncthreads();
+      pend_append(pd, count, Y, ldy, R, X, ldx, C, nB);
+      __syncthreads();
+      gemm_cols(Wl, t.ldw, R, C, Y, ldy, nB, part, X, ldx);
+      for (int i = threadIdx.x; i < nB * C; i += AMP_THREADS) {
+        const int k = i / C, c = i - k * C, m = M.bidx[k];
+        const float v = X[k * ldx + c];
+        if (BR) {
+          if (c < H)
+            B.gpar[(B.node(M.s[m], M.a[m]) * B.TB + W->tile) * H + c] = v;
+          else
+            B.gpar[(B.node(M.s[m], M.b[m]) * B.TB + W->tile) * H + c - H] = v;
+        } else {
+          B.gx[(B.leaf(M.s[m], M.n[m]) * B.TL + W->tile) * C + c] = v;
+        }
+      }
+      __syncthreads();
+    }
+    // ---------------- joins and posts, one lane per message
+    if (threadIdx.x < 64) {
+      fence_release();
+      const int k = threadIdx.x;
+      if (k < n) {
+        const int s = M.s[k], nn = M.n[k];
+        if (!M.aux[k]) {
+          tree_node_part_done(D, B, s, nn, M.par[k], W->ntiles);
+        } else if (BR) {
+          tree_grad_part_done(D, B, s, M.a[k], false, M.a[k] < M.L[k]);
+          tree_grad_part_done(D, B, s, M.b[k], false, M.b[k] < M.L[k]);
+        } else {
+          if (join_arrive(B.cnt + B.node(s, nn) * 4 + 3, B.TL)) ring_post(D->ring[TR_LOOKUP], MSG_MAKE(1, s, nn));
+        }
+      }
+    }
+    count += nB;
+    if ((int)count >= nd.muf) {
+      tstep++;
+      tile_update_deferred(nd, t, Wl, bl, pd, count, tstep, X);
+      count = 0;
+      LOG(W->node, 2, 0, 0);
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-      fence_release();
-      if (BR) {
-        tree_grad_part_done(D, B, v, s, a);
-        tree_grad_part_done(D, B, v, s, b);
-      } else {
-        if (join_arrive(B.cnt + B.node(s, n) * 4 + 3, B.TL)) ring_post(D->ring[TR_LOOKUP], MSG_MAKE(1, s, n));
-      }
-    }
-    tile_accumulate(nd, t, ds, xs);
-    count_and_update(D, W, nd, t, Wl, bl, count, tstep);
   }
   tile_store(nd, t, Wl, bl);
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;
   }
-  (void)NG;
 }
 
 // ------------------------------------------------------------ output layer + loss at every node
+// One wave per message: forward, softmax loss and backward in one event.
 __device__ void role_tree_out(const AmpDev* D, const WorkerDev* W, float* lds) {
   const NodeDev& nd = D->node[3];
   const Tile t = make_tile(nd, W);
   const TreeBufs B = tree_bufs(D);
-  const int R = t.R, C = t.C, H = B.H;
+  const Pend pd = make_pend(W, t);
+  const int R = t.R, C = t.C, H = B.H, KB = W->kb;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, NW = AMP_THREADS >> 6;
   Lds L{lds};
   float* Wl = L.take(R * t.ldw);
   float* bl = L.take(R);
-  float* xs = L.take(C);
-  float* ys = L.take(R);
-  float* ds = L.take(R);
-  float* dx = L.take(C);
-  float* part = L.take(8 * (R > C ? R : C));
-  int* done_cnt = (int*)L.take(D->mak);     // eval: nodes scored per slot
+  float* hbuf = L.take(NW * C);            // per wave: the node's h
+  float* zbuf = L.take(NW * 64);           // per wave: logits, then dz
+  float* stage = L.take(8 * pd.stride);
+  int* done_cnt = (int*)L.take(D->mak);    // eval: nodes scored per slot
   tile_load(nd, t, Wl, bl);
   for (int i = threadIdx.x; i < D->mak; i += AMP_THREADS) done_cnt[i] = 0;
+  BatchMsg& M = s_M;
   __syncthreads();
   const RingDev& mine = D->ring[W->ring];
-  unsigned head = 0, code;
+  unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
-  while (wait_msg(D, mine, head, s_ctl, code)) {
-    const int s = MSG_SLOT(code), n = MSG_LOCAL(code);
-    const unsigned seq = D->slot_seq[s];
-    const TreeView v = tree_view(D, seq);
-    const float* h = B.hc + B.node(s, n) * 2 * H;
-    for (int c = threadIdx.x; c < C; c += AMP_THREADS) xs[c] = h[c];
-    __syncthreads();
-    gemv_rows(Wl, t.ldw, R, C, bl, xs, part, ys);
-    LOG(3, 0, seq, n);
-    const int label = v.lab[n];
-    softmax_xent_wave0(ys, R, label, ds, &s_loss, &s_pred);
-    if (threadIdx.x == 0) {
-      D->loss_out[seq - D->first_seq] += s_loss;
-      D->correct_out[seq - D->first_seq] += s_pred == label;
+  for (;;) {
+    const int room = D->train ? nd.muf - (int)count : KB_MAX;
+    const int n = wait_batch(D, mine, head, KB, room, s_codes, &s_n, [](unsigned) { return true; });
+    if (n == 0) break;
+    if ((int)threadIdx.x < n) {
+      const int k = threadIdx.x;
+      const unsigned code = s_codes[k];
+      const int s = MSG_SLOT(code), nn = MSG_LOCAL(code);
+      const unsigned seq = D->slot_seq[s];
+      const TreeView v = tree_view(D, seq);
+      M.s[k] = s;
+      M.n[k] = nn;
+      M.seq[k] = seq;
+      M.a[k] = v.lab[nn];
+      M.par[k] = v.parent[nn];
+      M.L[k] = v.L;
     }
-    if (!D->train) {
-      if (threadIdx.x == 0 && ++done_cnt[s] == v.NN) {
-        done_cnt[s] = 0;
-        fence_release();
-        ring_post(D->ring[0], MSG_MAKE(1, s, 0));
+    __syncthreads();
+    float* hw = hbuf + wave * C;
+    float* zw = zbuf + wave * 64;
+    for (int k = wave; k < n; k += NW) {
+      const int s = M.s[k], nn = M.n[k], label = M.a[k];
+      const float* h = B.hc + B.node(s, nn) * 2 * H;
+      for (int c = lane; c < C; c += 64) hw[c] = h[c];
+      // logits: lane r keeps z_r
+      float zmine = -3.0e38f;
+      for (int r = 0; r < R; ++r) {
+        float a = 0.f;
+        for (int c = lane; c < C; c += 64) a = fmaf(Wl[r * t.ldw + c], hw[c], a);
+        for (int off = 32; off; off >>= 1) a += __shfl_xor(a, off);
+        if (lane == r) zmine = a + bl[r];
       }
-      continue;
+      float m = zmine;
+      int am = lane < R ? lane : 0x7fffffff;
+      for (int off = 32; off; off >>= 1) {
+        const float om = __shfl_xor(m, off);
+        const int oa = __shfl_xor(am, off);
+        if (om > m || (om == m && oa < am)) {
+          m = om;
+          am = oa;
+        }
+      }
+      const float e = lane < R ? expf(zmine - m) : 0.f;
+      float se = e;
+      for (int off = 32; off; off >>= 1) se += __shfl_xor(se, off);
+      const float zl = __shfl(zmine, label);
+      const float dz = e / se - (lane == label ? 1.f : 0.f);
+      if (lane < 64) zw[lane] = lane < R ? dz : 0.f;
+      if (lane == 0) {
+        const unsigned idx = M.seq[k] - D->first_seq;
+        atomicAdd(&D->loss_out[idx], -(zl - m - logf(se)));
+        if (am == label) atomicAdd(&D->correct_out[idx], 1);
+      }
+      if (!D->train) continue;
+      // dh = W^T dz, and the (dz, h) pair joins the pending gradients
+      float* go = B.gout + B.node(s, nn) * H;
+      for (int c = lane; c < C; c += 64) {
+        float a = 0.f;
+        for (int r = 0; r < R; ++r) a = fmaf(Wl[r * t.ldw + c], zw[r], a);
+        go[c] = a;
+      }
+      float* pe = pd.base + (long long)(count + k) * pd.stride;
+      for (int j = lane; j < pd.stride; j += 64) {
+        float v = 0.f;
+        if (j < pd.R8) {
+          if (j < R) v = zw[j];
+        } else if (j - pd.R8 < C) {
+          v = hw[j - pd.R8];
+        }
+        pe[j] = v;
+      }
     }
-    LOG(3, 1, seq, n);
-    gemv_cols(Wl, t.ldw, R, C, ds, part, dx);
-    float* go = B.gout + B.node(s, n) * H;
-    for (int c = threadIdx.x; c < C; c += AMP_THREADS) go[c] = dx[c];
+    if (threadIdx.x == 0 && W->log_cap)
+      for (int k = 0; k < n; ++k) {
+        log_event(D, W, &s_logn, 3, 0, M.seq[k], M.n[k]);
+        if (D->train) log_event(D, W, &s_logn, 3, 1, M.seq[k], M.n[k]);
+      }
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (threadIdx.x < 64) {
       fence_release();
-      tree_grad_part_done(D, B, v, s, n);
+      const int k = threadIdx.x;
+      if (k < n) {
+        if (!D->train) {
+          if (atomicAdd(&done_cnt[M.s[k]], 1) + 1 == 2 * M.L[k] - 1) {
+            done_cnt[M.s[k]] = 0;
+            ring_post(D->ring[0], MSG_MAKE(1, M.s[k], 0));
+          }
+        } else {
+          tree_grad_part_done(D, B, M.s[k], M.n[k], M.par[k] < 0, M.n[k] < M.L[k]);
+        }
+      }
     }
-    tile_accumulate(nd, t, ds, xs);
-    count_and_update(D, W, nd, t, Wl, bl, count, tstep);
+    if (D->train) {
+      count += n;
+      if ((int)count >= nd.muf) {
+        tstep++;
+        tile_update_deferred(nd, t, Wl, bl, pd, count, tstep, stage);
+        count = 0;
+        LOG(3, 2, 0, 0);
+      }
+    }
+    __syncthreads();
   }
   tile_store(nd, t, Wl, bl);
   if (threadIdx.x == 0) {
