@@ -193,11 +193,13 @@ int amp_get_staleness_hist(amp_ctx *ctx, uint64_t *bins, size_t nbins);
 int amp_num_workers(amp_ctx *ctx);
 /* Utilisation of the last amp_train / amp_eval, one entry per worker
  * (workgroup): fraction of the kernel's life spent waiting for a message,
- * messages taken, and the node the worker hosts (-1 = controller).  Workers
- * correspond to the paper's Appendix A workers; a node whose workers never
- * wait is the pipeline's bottleneck.  Any out pointer may be NULL. */
+ * messages taken, the node the worker hosts (-1 = controller), batches of
+ * messages taken, and (8 per worker) the fraction of time spent in each of
+ * the worker's processing phases.  Workers correspond to the paper's
+ * Appendix A workers; a node whose workers never wait is the pipeline's
+ * bottleneck.  Any out pointer may be NULL. */
 int amp_get_worker_stats(amp_ctx *ctx, double *wait_fraction, uint64_t *messages, int32_t *node_of_worker,
-                         size_t cap, size_t *n);
+                         size_t cap, size_t *n, uint64_t *batches, double *phase_fraction);
 const char *amp_last_error(amp_ctx *ctx);
 
 #ifdef __cplusplus

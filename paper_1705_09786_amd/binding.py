@@ -83,7 +83,8 @@ SIGNATURES = {
     "amp_get_event_log": (ct.c_int, [_ctxp, ct.POINTER(Event), ct.c_size_t, ct.POINTER(ct.c_size_t)]),
     "amp_get_staleness_hist": (ct.c_int, [_ctxp, ct.POINTER(ct.c_uint64), ct.c_size_t]),
     "amp_get_worker_stats": (ct.c_int, [_ctxp, ct.POINTER(ct.c_double), ct.POINTER(ct.c_uint64), _i32p,
-                                        ct.c_size_t, ct.POINTER(ct.c_size_t)]),
+                                        ct.c_size_t, ct.POINTER(ct.c_size_t), ct.POINTER(ct.c_uint64),
+                                        ct.POINTER(ct.c_double)]),
     "amp_last_error": (ct.c_char_p, [_ctxp]),
 }
 
@@ -267,9 +268,11 @@ class Amp:
         """List per worker of dict(node, wait_fraction, messages)."""
         nw = self.num_workers()
         wf, ms, nd = (ct.c_double * nw)(), (ct.c_uint64 * nw)(), (ct.c_int32 * nw)()
+        bt, ph = (ct.c_uint64 * nw)(), (ct.c_double * (8 * nw))()
         n = ct.c_size_t()
-        self._chk(self.L.amp_get_worker_stats(self.h, wf, ms, nd, nw, ct.byref(n)))
-        return [dict(node=nd[i], wait_fraction=wf[i], messages=ms[i]) for i in range(nw)]
+        self._chk(self.L.amp_get_worker_stats(self.h, wf, ms, nd, nw, ct.byref(n), bt, ph))
+        return [dict(node=nd[i], wait_fraction=wf[i], messages=ms[i], batches=bt[i],
+                     phases=[ph[8 * i + j] for j in range(8)]) for i in range(nw)]
 
     def get_staleness_hist(self, nbins=16):
         bins = (ct.c_uint64 * nbins)()

@@ -37,7 +37,7 @@ __shared__ int s_n;
 // (those for which is_b(code) holds) are in it.  Returns the batch size, 0
 // when the run is over.  s_codes / s_n are LDS.
 template <class IsB>
-__device__ int wait_batch(const AmpDev* D, const RingDev& r, unsigned& head, int kmax, int room, unsigned* s_codes,
+__device__ __forceinline__ int wait_batch(const AmpDev* D, const RingDev& r, unsigned& head, int kmax, int room, unsigned* s_codes,
                           int* s_n, IsB is_b) {
   if (threadIdx.x < 64) {
     const int lane = threadIdx.x;
@@ -93,8 +93,11 @@ __device__ int wait_batch(const AmpDev* D, const RingDev& r, unsigned& head, int
     }
     if (lane == 0) {
       *s_n = n;
-      s_stat[0] += (unsigned long long)(wall_clock64() - t0);
+      const unsigned long long now = wall_clock64();
+      s_stat[0] += now - (unsigned long long)t0;
       s_stat[1] += (unsigned long long)n;
+      s_stat[2] += 1;
+      s_stat[3] = now;
     }
   }
   __syncthreads();
@@ -103,217 +106,174 @@ __device__ int wait_batch(const AmpDev* D, const RingDev& r, unsigned& head, int
   return n;
 }
 
-// ---------------------------------------------------------------- grouped-row products
-// Y[k][r] = b[r] + sum_c Wl[r][c] X[k][c], k < K.  X rows have stride ldx, Y
-// rows stride ldy (both multiples of 4, buffers 16-byte aligned, row count
-// rounded up to 4; padding rows of X must hold finite values).
-// Thread (p, g, r): output row r, k-rows 4g..4g+3, p-th column chunk.
-__device__ void gemm_rows(const float* Wl, int ldw, int R, int C, const float* bl, const float* X, int ldx, int K,
-                          float* part, float* Y, int ldy) {
-  const int nkg = (K + 3) >> 2;
-  int P = AMP_THREADS / (R * nkg);
-  if (P < 1) P = 1;
-  if (P > 8) P = 8;
-  const int chunk = (((C + P - 1) / P) + 3) & ~3;
-  const int total = R * nkg * P;
-  for (int idx = threadIdx.x; idx < total; idx += AMP_THREADS) {
-    const int p = idx / (R * nkg);
-    const int rem = idx - p * R * nkg;
-    const int g = rem / R, r = rem - g * R;
-    const int c0 = p * chunk;
-    int c1 = c0 + chunk;
-    if (c1 > C) c1 = C;
-    const float* w = Wl + r * ldw;
-    const float* x0 = X + (4 * g) * ldx;
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-    int c = c0;
-    for (; c + 3 < c1; c += 4) {
-      const float w0 = w[c], w1 = w[c + 1], w2 = w[c + 2], w3 = w[c + 3];
-      const float4 xa = *(const float4*)(x0 + c);
-      const float4 xb = *(const float4*)(x0 + ldx + c);
-      const float4 xc = *(const float4*)(x0 + 2 * ldx + c);
-      const float4 xd = *(const float4*)(x0 + 3 * ldx + c);
-      a0 = fmaf(w0, xa.x, a0); a0 = fmaf(w1, xa.y, a0); a0 = fmaf(w2, xa.z, a0); a0 = fmaf(w3, xa.w, a0);
-      a1 = fmaf(w0, xb.x, a1); a1 = fmaf(w1, xb.y, a1); a1 = fmaf(w2, xb.z, a1); a1 = fmaf(w3, xb.w, a1);
-      a2 = fmaf(w0, xc.x, a2); a2 = fmaf(w1, xc.y, a2); a2 = fmaf(w2, xc.z, a2); a2 = fmaf(w3, xc.w, a2);
-      a3 = fmaf(w0, xd.x, a3); a3 = fmaf(w1, xd.y, a3); a3 = fmaf(w2, xd.z, a3); a3 = fmaf(w3, xd.w, a3);
+// ---------------------------------------------------------------- grouped-row products on the matrix cores
+// All operands live in LDS.  Weight tile Wl: Rp x ldw (Rp = 16 * NRB rows, ldw
+// from amp_ldrow, zero outside R x C).  Row blocks X / Y / D hold 16 * NB rows
+// each (one row per message or grouped row) with strides from amp_ldrow, so
+// every 16-byte read below is aligned and bank-friendly.  Rows are independent
+// of each other, so rows that carry no message may hold anything; but in a row
+// that carries one, the padding columns (beyond C in X, beyond R in D) must be
+// zero: they meet the weight tile's zero padding, and 0 x inf would be NaN.
+//
+// v_mfma_f32_16x16x4_f32: lane l supplies A[l%16][l/16] and B[l/16][l%16] and
+// receives D[4*(l/16)+v][l%16], v = 0..3.  fp32 in, fp32 accumulate.
+typedef float v4f __attribute__((ext_vector_type(4)));
+#define LDSQ __attribute__((address_space(3)))
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x4f32((a), (b), (c), 0, 0, 0)
+
+// Y[j][r] = b[r] + sum_c W[r][c] X[j][c]   (M = weight rows, N = messages, K = columns)
+__device__ __noinline__ void mfma_rows(const LDSQ float* Wl, int ldw, int NRB, int NCG, const LDSQ float* bl,
+                                       const LDSQ float* X, int ldx, int NB, LDSQ float* Y, int ldy) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  for (int item = wave; item < NRB * NB; item += AMP_THREADS / 64) {
+    const int rb = item % NRB, nb = item / NRB;
+    const LDSQ float* wp = Wl + (rb * 16 + i) * ldw + 4 * q;
+    const LDSQ float* xp = X + (nb * 16 + i) * ldx + 4 * q;
+    v4f acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    int g = 0;
+    for (; g + 1 < NCG; g += 2) {
+      const v4f w0 = *(const LDSQ v4f*)(wp + 16 * g), x0 = *(const LDSQ v4f*)(xp + 16 * g);
+      const v4f w1 = *(const LDSQ v4f*)(wp + 16 * g + 16), x1 = *(const LDSQ v4f*)(xp + 16 * g + 16);
+      acc0 = MFMA(w0.x, x0.x, acc0);
+      acc1 = MFMA(w1.x, x1.x, acc1);
+      acc0 = MFMA(w0.y, x0.y, acc0);
+      acc1 = MFMA(w1.y, x1.y, acc1);
+      acc0 = MFMA(w0.z, x0.z, acc0);
+      acc1 = MFMA(w1.z, x1.z, acc1);
+      acc0 = MFMA(w0.w, x0.w, acc0);
+      acc1 = MFMA(w1.w, x1.w, acc1);
     }
-    for (; c < c1; ++c) {
-      const float wv = w[c];
-      a0 = fmaf(wv, x0[c], a0);
-      a1 = fmaf(wv, x0[ldx + c], a1);
-      a2 = fmaf(wv, x0[2 * ldx + c], a2);
-      a3 = fmaf(wv, x0[3 * ldx + c], a3);
+    if (g < NCG) {
+      const v4f w0 = *(const LDSQ v4f*)(wp + 16 * g), x0 = *(const LDSQ v4f*)(xp + 16 * g);
+      acc0 = MFMA(w0.x, x0.x, acc0);
+      acc0 = MFMA(w0.y, x0.y, acc0);
+      acc0 = MFMA(w0.z, x0.z, acc0);
+      acc0 = MFMA(w0.w, x0.w, acc0);
     }
-    float* o = (P == 1 ? Y : part + p * nkg * 4 * ldy) + (4 * g) * ldy + r;
-    o[0] = a0;
-    o[ldy] = a1;
-    o[2 * ldy] = a2;
-    o[3 * ldy] = a3;
-  }
-  __syncthreads();
-  for (int i = threadIdx.x; i < nkg * 4 * R; i += AMP_THREADS) {
-    const int k = i / R, r = i - k * R;
-    const int at = k * ldy + r;
-    float s = P == 1 ? Y[at] : 0.f;
-    if (P > 1)
-      for (int p = 0; p < P; ++p) s += part[p * nkg * 4 * ldy + at];
-    Y[at] = s + (bl ? bl[r] : 0.f);
+    const v4f b4 = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
+    *(LDSQ v4f*)(Y + (nb * 16 + i) * ldy + rb * 16 + 4 * q) = acc0 + acc1 + b4;
   }
   __syncthreads();
 }
 
-// DX[k][c] = sum_r Wl[r][c] Dl[k][r], k < K.  Dl rows stride ldd, DX rows
-// stride ldx (multiples of 4).  Thread (p, g, c): column c, k-rows 4g..4g+3,
-// p-th row chunk.
-__device__ void gemm_cols(const float* Wl, int ldw, int R, int C, const float* Dl, int ldd, int K, float* part,
-                          float* DX, int ldx) {
-  const int nkg = (K + 3) >> 2;
-  int P = AMP_THREADS / (C * nkg);
-  if (P < 1) P = 1;
-  if (P > 8) P = 8;
-  const int chunk = (((R + P - 1) / P) + 3) & ~3;
-  const int total = C * nkg * P;
-  for (int idx = threadIdx.x; idx < total; idx += AMP_THREADS) {
-    const int p = idx / (C * nkg);
-    const int rem = idx - p * C * nkg;
-    const int g = rem / C, c = rem - g * C;
-    const int r0 = p * chunk;
-    int r1 = r0 + chunk;
-    if (r1 > R) r1 = R;
-    const float* d0 = Dl + (4 * g) * ldd;
-    const float* w = Wl + c;
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-    int r = r0;
-    for (; r + 3 < r1; r += 4) {
-      const float w0 = w[r * ldw], w1 = w[(r + 1) * ldw], w2 = w[(r + 2) * ldw], w3 = w[(r + 3) * ldw];
-      const float4 da = *(const float4*)(d0 + r);
-      const float4 db = *(const float4*)(d0 + ldd + r);
-      const float4 dc = *(const float4*)(d0 + 2 * ldd + r);
-      const float4 dd = *(const float4*)(d0 + 3 * ldd + r);
-      a0 = fmaf(w0, da.x, a0); a0 = fmaf(w1, da.y, a0); a0 = fmaf(w2, da.z, a0); a0 = fmaf(w3, da.w, a0);
-      a1 = fmaf(w0, db.x, a1); a1 = fmaf(w1, db.y, a1); a1 = fmaf(w2, db.z, a1); a1 = fmaf(w3, db.w, a1);
-      a2 = fmaf(w0, dc.x, a2); a2 = fmaf(w1, dc.y, a2); a2 = fmaf(w2, dc.z, a2); a2 = fmaf(w3, dc.w, a2);
-      a3 = fmaf(w0, dd.x, a3); a3 = fmaf(w1, dd.y, a3); a3 = fmaf(w2, dd.z, a3); a3 = fmaf(w3, dd.w, a3);
+// DX[j][c] = sum_r W[r][c] D[j][r]   (M = weight columns, N = messages, K = weight rows)
+__device__ __noinline__ void mfma_cols(const LDSQ float* Wl, int ldw, int NRB, int NCG, const LDSQ float* Dl, int ldd,
+                                       int NB, LDSQ float* DX, int ldx) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  for (int item = wave; item < NCG * NB; item += AMP_THREADS / 64) {
+    const int cb = item % NCG, nb = item / NCG;
+    const LDSQ float* wp = Wl + (4 * q) * ldw + cb * 16 + i;
+    const LDSQ float* dp = Dl + (nb * 16 + i) * ldd + 4 * q;
+    v4f acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < NRB; ++g) {
+      const v4f d0 = *(const LDSQ v4f*)(dp + 16 * g);
+      const LDSQ float* w = wp + 16 * g * ldw;
+      const float w0 = w[0], w1 = w[ldw], w2 = w[2 * ldw], w3 = w[3 * ldw];
+      acc0 = MFMA(w0, d0.x, acc0);
+      acc1 = MFMA(w1, d0.y, acc1);
+      acc0 = MFMA(w2, d0.z, acc0);
+      acc1 = MFMA(w3, d0.w, acc1);
     }
-    for (; r < r1; ++r) {
-      const float wv = w[r * ldw];
-      a0 = fmaf(wv, d0[r], a0);
-      a1 = fmaf(wv, d0[ldd + r], a1);
-      a2 = fmaf(wv, d0[2 * ldd + r], a2);
-      a3 = fmaf(wv, d0[3 * ldd + r], a3);
-    }
-    float* o = (P == 1 ? DX : part + p * nkg * 4 * ldx) + (4 * g) * ldx + c;
-    o[0] = a0;
-    o[ldx] = a1;
-    o[2 * ldx] = a2;
-    o[3 * ldx] = a3;
+    *(LDSQ v4f*)(DX + (nb * 16 + i) * ldx + cb * 16 + 4 * q) = acc0 + acc1;
   }
   __syncthreads();
-  if (P > 1) {
-    for (int i = threadIdx.x; i < nkg * 4 * C; i += AMP_THREADS) {
-      const int k = i / C, c = i - k * C;
-      const int at = k * ldx + c;
-      float s = 0.f;
-      for (int p = 0; p < P; ++p) s += part[p * nkg * 4 * ldx + at];
-      DX[at] = s;
-    }
-    __syncthreads();
-  }
 }
 
 // ---------------------------------------------------------------- pending gradients
-// Entry e of a worker's list: pend + e * stride, [delta (R8 floats) | input (C8 floats)],
-// R8 / C8 = tile rows / cols rounded up to 8, stride = R8 + C8.
+// Entry e of a worker's list in HBM: pend + e * stride, [delta (Rp floats) |
+// input (Cp floats)], Rp / Cp = tile rows / cols rounded up to 16, zero padded.
 struct Pend {
   float* base;
-  int R8, C8, stride;
+  int Rp, Cp, stride;
 };
 
 __device__ __forceinline__ Pend make_pend(const WorkerDev* W, const Tile& t) {
   Pend p;
   p.base = W->pend;
-  p.R8 = round8(t.R);
-  p.C8 = round8(t.C);
-  p.stride = p.R8 + p.C8;
+  p.Rp = t.Rp;
+  p.Cp = amp_round16(t.C);
+  p.stride = p.Rp + p.Cp;
   return p;
 }
 
 // Appends K pairs held in LDS (delta rows stride ldd, input rows stride ldx) as entries first..first+K-1.
-__device__ void pend_append(const Pend& p, unsigned first, const float* Dl, int ldd, int R, const float* X, int ldx,
-                            int C, int K) {
+__device__ __forceinline__ void pend_append(const Pend& p, unsigned first, const float* Dl, int ldd, int R,
+                                            const float* X, int ldx, int C, int K) {
   for (int i = threadIdx.x; i < K * p.stride; i += AMP_THREADS) {
     const int k = i / p.stride, j = i - k * p.stride;
     float v = 0.f;
-    if (j < p.R8) {
+    if (j < p.Rp) {
       if (j < R) v = Dl[k * ldd + j];
-    } else if (j - p.R8 < C) {
-      v = X[k * ldx + j - p.R8];
+    } else if (j - p.Rp < C) {
+      v = X[k * ldx + j - p.Rp];
     }
-    p.base[(long long)(first + k) * p.stride + i - k * p.stride] = v;
+    p.base[(long long)(first + k) * p.stride + j] = v;
   }
 }
 
-// The node's update from `count` pending pairs.  Thread blocks of 8 rows x 8
-// columns (columns 4*bj..4*bj+3 and C8/2 + 4*bj..+3, so that the lanes of a
-// wave read consecutive 16-byte pieces of an input row).  `stage` is LDS for
-// 8 entries (8 * stride floats, 16-byte aligned).  tstep: 1-based update number.
-__device__ void tile_update_deferred(const NodeDev& nd, const Tile& t, float* Wl, float* bl, const Pend& p,
-                                     unsigned count, unsigned tstep, float* stage) {
-  __syncthreads();
+// The node's update from `count` pending pairs: G = sum_k delta_k (x) input_k
+// formed in 16 x 16 register tiles on the matrix cores (M = rows, N = columns,
+// K = pending index, in arrival order), then the optimizer step on the LDS
+// weights.  `stage` is LDS for UPD_STAGE entries.  Wave w owns tiles w, w+8, ...
+#define UPD_STAGE 8
+#define UPD_TILES 16
+__device__ __noinline__ void mfma_update(LDSQ float* Wl, LDSQ float* bl, const NodeDev* ndp, Tile t, const float* pend,
+                                         int stride, unsigned n_grad, unsigned count, unsigned tstep,
+                                         LDSQ float* stage) {
+  // n_grad = gradients (messages) accumulated, count = pending rows (a grouped message has several)
+  const NodeDev& nd = *ndp;
   const OptCoef o = opt_coef(nd, tstep);
-  const float inv = nd.mean ? 1.f / (float)count : 1.f;
-  const int nbr = p.R8 >> 3, nbc = p.C8 >> 3, nblk = nbr * nbc, half = p.C8 >> 1;
-  for (int base = 0; base < nblk; base += AMP_THREADS) {
-    const int blk = base + threadIdx.x;
-    const bool act = blk < nblk;
-    const int bi = act ? blk / nbc : 0, bj = act ? blk - bi * nbc : 0;
-    float acc[64];
-    float accb[8];
+  const float inv = nd.mean ? 1.f / (float)n_grad : 1.f;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  const int NRB = t.Rp >> 4, NCB = (stride - t.Rp) >> 4, T = NRB * NCB;
+  __syncthreads();
+  for (int pass0 = 0; pass0 < T; pass0 += 8 * UPD_TILES) {
+    v4f acc[UPD_TILES];
 #pragma unroll
-    for (int i = 0; i < 64; ++i) acc[i] = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) accb[i] = 0.f;
-    for (unsigned k0 = 0; k0 < count; k0 += 8) {
-      const int kc = count - k0 < 8u ? (int)(count - k0) : 8;
+    for (int ti = 0; ti < UPD_TILES; ++ti) acc[ti] = (v4f){0.f, 0.f, 0.f, 0.f};
+    float accb = 0.f;   // bias gradient of row threadIdx.x (first pass only)
+    for (unsigned k0 = 0; k0 < count; k0 += UPD_STAGE) {
+      const int kc = count - k0 < (unsigned)UPD_STAGE ? (int)(count - k0) : UPD_STAGE;
+      const v4f* src = (const v4f*)(pend + (long long)k0 * stride);
+      for (int j = threadIdx.x; j < (UPD_STAGE * stride) >> 2; j += AMP_THREADS)
+        ((LDSQ v4f*)stage)[j] = j < (kc * stride) >> 2 ? src[j] : (v4f){0.f, 0.f, 0.f, 0.f};
       __syncthreads();
-      const float4* src = (const float4*)(p.base + (long long)k0 * p.stride);
-      for (int i = threadIdx.x; i < (kc * p.stride) >> 2; i += AMP_THREADS) ((float4*)stage)[i] = src[i];
+#pragma unroll
+      for (int ti = 0; ti < UPD_TILES; ++ti) {
+        const int tl = pass0 + wave + 8 * ti;
+        if (tl < T) {
+          const int rb = tl / NCB, cb = tl - rb * NCB;
+#pragma unroll
+          for (int k4 = 0; k4 < UPD_STAGE / 4; ++k4) {
+            const LDSQ float* e = stage + (4 * k4 + q) * stride;
+            acc[ti] = MFMA(e[rb * 16 + i], e[t.Rp + cb * 16 + i], acc[ti]);
+          }
+        }
+      }
+      if (pass0 == 0 && (int)threadIdx.x < t.R)
+        for (int k = 0; k < kc; ++k) accb += stage[k * stride + threadIdx.x];
       __syncthreads();
-      if (act) {
-        for (int kk = 0; kk < kc; ++kk) {
-          const float* e = stage + kk * p.stride;
-          const float4 d0 = *(const float4*)(e + 8 * bi), d1 = *(const float4*)(e + 8 * bi + 4);
-          const float4 x0 = *(const float4*)(e + p.R8 + 4 * bj), x1 = *(const float4*)(e + p.R8 + half + 4 * bj);
-          const float d[8] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
-          const float x[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+    }
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
+    for (int ti = 0; ti < UPD_TILES; ++ti) {
+      const int tl = pass0 + wave + 8 * ti;
+      if (tl < T) {
+        const int rb = tl / NCB, cb = tl - rb * NCB;
+        const int c = cb * 16 + i;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[i * 8 + j] = fmaf(d[i], x[j], acc[i * 8 + j]);
-            accb[i] += d[i];
+        for (int v = 0; v < 4; ++v) {
+          const int r = rb * 16 + 4 * q + v;
+          if (r < t.R && c < t.C) {
+            const long long gi = (long long)t.grow(r) * t.C + c;
+            Wl[r * t.ldw + c] = opt_apply(o, Wl[r * t.ldw + c], acc[ti][v] * inv, nd.M, nd.V, gi);
           }
         }
       }
     }
-    if (act) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int r = 8 * bi + i;
-        if (r >= t.R) continue;
-        const long long grow = t.grow(r);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const int c = (j < 4 ? 4 * bj + j : half + 4 * bj + j - 4);
-          if (c >= t.C) continue;
-          const long long gi = grow * t.C + c;
-          Wl[r * t.ldw + c] = opt_apply(o, Wl[r * t.ldw + c], acc[i * 8 + j] * inv, nd.M, nd.V, gi);
-        }
-        if (bj == 0 && nd.has_bias) {
-          const long long gi = (long long)nd.rows * t.C + grow;
-          bl[r] = opt_apply(o, bl[r], accb[i] * inv, nd.M, nd.V, gi);
-        }
-      }
+    if (pass0 == 0 && nd.has_bias && (int)threadIdx.x < t.R) {
+      const int r = threadIdx.x;
+      const long long gi = (long long)nd.rows * t.C + t.grow(r);
+      bl[r] = opt_apply(o, bl[r], accb * inv, nd.M, nd.V, gi);
     }
   }
   __syncthreads();

@@ -7,6 +7,9 @@
 
 #define AGENT __HIP_MEMORY_SCOPE_AGENT
 
+// The workgroup's dynamic LDS; every role carves its buffers out of it.
+extern __shared__ float amp_lds[];
+
 __device__ __forceinline__ unsigned ld_u32(const unsigned* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, AGENT);
 }
@@ -36,14 +39,25 @@ __device__ __forceinline__ void raise_abort(const AmpDev* D, unsigned code, unsi
     __hip_atomic_store(&D->ctl[2], detail, __ATOMIC_RELAXED, AGENT);
 }
 
-// Per-workgroup utilisation counters: [0] ticks spent waiting for messages, [1] messages taken.
-__shared__ unsigned long long s_stat[2];
+// Per-workgroup utilisation counters: [0] ticks spent waiting for messages, [1] messages taken,
+// [2] batches taken, [3] last phase boundary, [4..11] ticks per phase (role-specific).
+#define AMP_NSTAT 12
+__shared__ unsigned long long s_stat[AMP_NSTAT];
+// Thread 0 charges the time since the previous boundary to phase i.
+#define PHASE(i)                                             \
+  do {                                                       \
+    if (threadIdx.x == 0) {                                  \
+      const unsigned long long now_ = wall_clock64();        \
+      s_stat[4 + (i)] += now_ - s_stat[3];                   \
+      s_stat[3] = now_;                                      \
+    }                                                        \
+  } while (0)
 
 // Whole workgroup.  Waits for the entry with ticket `head` of ring r; returns
 // false when the run is over (done flag, abort flag, or this wait exceeded
 // the watchdog, which raises the abort flag so that every workgroup leaves).
 // s_ctl: two words of LDS.
-__device__ bool wait_msg(const AmpDev* D, const RingDev& r, unsigned& head, unsigned* s_ctl, unsigned& code) {
+__device__ __forceinline__ bool wait_msg(const AmpDev* D, const RingDev& r, unsigned& head, unsigned* s_ctl, unsigned& code) {
   if (threadIdx.x == 0) {
     const unsigned want = head + 1u;
     unsigned long long* slot = &r.ent[head & r.mask];
@@ -103,7 +117,7 @@ __device__ __forceinline__ void log_event(const AmpDev* D, const WorkerDev* W, u
 
 // y[r] = b[r] + sum_c Wl[r][c] * x[c].  Thread (p, r) sums the p-th column
 // chunk of row r; partials meet in `part` (>= P * R floats).  All threads.
-__device__ void gemv_rows(const float* Wl, int ldw, int R, int C, const float* bl, const float* x, float* part,
+__device__ __forceinline__ void gemv_rows(const float* Wl, int ldw, int R, int C, const float* bl, const float* x, float* part,
                           float* y) {
   int P = AMP_THREADS / R;
   if (P < 1) P = 1;
@@ -137,7 +151,7 @@ __device__ void gemv_rows(const float* Wl, int ldw, int R, int C, const float* b
 
 // dx[c] = sum_r Wl[r][c] * d[r].  Thread (p, c) sums the p-th row chunk of
 // column c.  `part` >= P * C floats.  All threads.
-__device__ void gemv_cols(const float* Wl, int ldw, int R, int C, const float* d, float* part, float* dx) {
+__device__ __forceinline__ void gemv_cols(const float* Wl, int ldw, int R, int C, const float* d, float* part, float* dx) {
   int P = AMP_THREADS / C;
   if (P < 1) P = 1;
   if (P > 8) P = 8;
@@ -172,7 +186,7 @@ __device__ void gemv_cols(const float* Wl, int ldw, int R, int C, const float* d
 // A tile owns units [u0, u0+nu) of each of the node's gate blocks.  Local row
 // lr = g * nu + j  <->  node row g * block + u0 + j.
 struct Tile {
-  int R, C, ldw, nu, u0, block, nblocks;
+  int R, C, ldw, nu, u0, block, nblocks, Rp;
   __device__ __forceinline__ int grow(int lr) const {
     const int g = lr / nu;
     return g * block + u0 + (lr - g * nu);
@@ -187,11 +201,16 @@ __device__ __forceinline__ Tile make_tile(const NodeDev& nd, const WorkerDev* W)
   t.nblocks = nd.nblocks;
   t.R = nd.nblocks * W->nu;
   t.C = nd.cols;
-  t.ldw = nd.cols | 1;
+  t.ldw = amp_ldrow(nd.cols);
+  t.Rp = amp_round16(t.R);
   return t;
 }
 
-__device__ void tile_load(const NodeDev& nd, const Tile& t, float* Wl, float* bl) {
+// Wl holds Rp x ldw floats, bl holds Rp; everything outside R x C is zero.
+__device__ __forceinline__ void tile_load(const NodeDev& nd, const Tile& t, float* Wl, float* bl) {
+  for (int i = threadIdx.x; i < t.Rp * t.ldw; i += AMP_THREADS) Wl[i] = 0.f;
+  for (int i = threadIdx.x; i < t.Rp; i += AMP_THREADS) bl[i] = 0.f;
+  __syncthreads();
   for (int i = threadIdx.x; i < t.R * t.C; i += AMP_THREADS) {
     const int lr = i / t.C, c = i - lr * t.C;
     Wl[lr * t.ldw + c] = nd.P[(long long)t.grow(lr) * t.C + c];
@@ -201,7 +220,7 @@ __device__ void tile_load(const NodeDev& nd, const Tile& t, float* Wl, float* bl
   __syncthreads();
 }
 
-__device__ void tile_store(const NodeDev& nd, const Tile& t, const float* Wl, const float* bl) {
+__device__ __forceinline__ void tile_store(const NodeDev& nd, const Tile& t, const float* Wl, const float* bl) {
   __syncthreads();
   for (int i = threadIdx.x; i < t.R * t.C; i += AMP_THREADS) {
     const int lr = i / t.C, c = i - lr * t.C;
@@ -212,7 +231,7 @@ __device__ void tile_store(const NodeDev& nd, const Tile& t, const float* Wl, co
 }
 
 // G[row][c] += d[lr] * x[c] over the tile's rows; bias gradient alike.
-__device__ void tile_accumulate(const NodeDev& nd, const Tile& t, const float* d, const float* x) {
+__device__ __forceinline__ void tile_accumulate(const NodeDev& nd, const Tile& t, const float* d, const float* x) {
   for (int i = threadIdx.x; i < t.R * t.C; i += AMP_THREADS) {
     const int lr = i / t.C, c = i - lr * t.C;
     float* g = nd.G + (long long)t.grow(lr) * t.C + c;
@@ -261,7 +280,7 @@ __device__ __forceinline__ float opt_apply(const OptCoef& o, float w, float g, f
 // Applies the node's optimizer to the tile with the accumulated gradient
 // (mean over `count` gradients unless the node sums), clears the accumulator.
 // tstep is the 1-based number of this update.
-__device__ void tile_update(const NodeDev& nd, const Tile& t, float* Wl, float* bl, unsigned count, unsigned tstep) {
+__device__ __forceinline__ void tile_update(const NodeDev& nd, const Tile& t, float* Wl, float* bl, unsigned count, unsigned tstep) {
   __syncthreads();
   const OptCoef o = opt_coef(nd, tstep);
   const float inv = nd.mean ? 1.f / (float)count : 1.f;
@@ -284,7 +303,7 @@ __device__ void tile_update(const NodeDev& nd, const Tile& t, float* Wl, float* 
 
 // softmax cross-entropy over n <= 64 logits held in LDS, by wave 0.
 // Writes dz[k] = p_k - [k == label]; returns loss and argmax through LDS words.
-__device__ void softmax_xent_wave0(const float* z, int n, int label, float* dz, float* s_loss, int* s_pred) {
+__device__ __forceinline__ void softmax_xent_wave0(const float* z, int n, int label, float* dz, float* s_loss, int* s_pred) {
   if (threadIdx.x < 64) {
     const int k = threadIdx.x;
     float v = k < n ? z[k] : -3.0e38f;

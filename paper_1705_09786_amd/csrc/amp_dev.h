@@ -11,7 +11,23 @@
 #define AMP_LDS_BYTES 163840   // 160 KB per workgroup on gfx950
 #define AMP_DYN_LDS_BYTES (AMP_LDS_BYTES - 2048)   // dynamic part; the rest is for static __shared__
 #define AMP_TREE_LOOKUP_MAX_MUF 16384
-#define AMP_DENSE_MAX_MUF 1024        // pending-gradient list of a dense node
+#define AMP_DENSE_MAX_MUF 256         // longest pending-gradient list of a dense node (messages)
+
+// LDS layout of a weight tile: rows padded to a multiple of 16, row stride a
+// multiple of 16 floats plus, if needed, 4 more so that stride/4 is odd: rows
+// are then 16-byte aligned and both row-wise 16-byte reads and column-wise
+// 4-byte reads spread evenly over the LDS banks.
+#if defined(__HIPCC__) || defined(__CUDACC__)
+#define AMP_HD __host__ __device__
+#else
+#define AMP_HD
+#endif
+AMP_HD static inline int amp_round16(int v) { return (v + 15) & ~15; }
+AMP_HD static inline int amp_ldrow(int cols) {
+  int l = amp_round16(cols);
+  if (((l >> 2) & 1) == 0) l += 4;
+  return l;
+}
 
 // Message code carried by a ring entry: [31] direction, [30:20] slot,
 // [19:0] position inside the instance.
@@ -73,7 +89,7 @@ struct WorkerDev {
   unsigned* wstate;    // persistent per-worker words: [0] count, [1] opt step (node), [2] count, [3] step (hosted lookup)
   unsigned long long* log;
   unsigned* log_n;
-  unsigned long long* stats;   // [0] ticks waiting, [1] messages taken, [2] ticks alive (100 MHz)
+  unsigned long long* stats;   // [0] ticks waiting, [1] messages, [2] batches, [3] ticks alive (100 MHz), [4..11] phases
   float* pend;                 // pending (delta, input) pairs of the hosted dense node
   unsigned log_cap;
   int kb;                      // largest batch this worker takes at once

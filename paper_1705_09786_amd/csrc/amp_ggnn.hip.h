@@ -95,30 +95,30 @@ __device__ __forceinline__ int g_active_types(const GView& v, int T) {
 }
 
 // Sends one message per edge type that occurs in the graph.  ONE thread, after a release fence.
-__device__ void g_post_edges(const AmpDev* D, const GView& v, int s, int it, bool backward) {
+__device__ __forceinline__ void g_post_edges(const AmpDev* D, const GView& v, int s, int it, bool backward) {
   for (int c = 0; c < D->n_edge_types; ++c)
     if (v.tcount[c] > 0) ring_post(D->ring[GR_EDGE0 + c], MSG_MAKE(backward, s, it));
 }
 
-// G += sum_k Dl[k] (x) X[k]; bias gradient alike.  One gradient per message.
-__device__ void rows_accumulate(const NodeDev& nd, int R, int C, const float* Dl, int ldd, const float* X, int ldx,
-                                int K) {
-  for (int i = threadIdx.x; i < R * C; i += AMP_THREADS) {
-    const int r = i / C, c = i - r * C;
-    float a = 0.f;
-    for (int k = 0; k < K; ++k) a = fmaf(Dl[k * ldd + r], X[k * ldx + c], a);
-    nd.G[i] += a;
+// Counts one gradient (a grouped message of K rows already appended to the
+// pending list) and updates when min_update_frequency is reached.
+__device__ __forceinline__ void g_count_and_update(const AmpDev* D, const WorkerDev* W, const NodeDev& nd, const Tile& t,
+                                                   float* Wl, float* bl, const Pend& pd, unsigned& count,
+                                                   unsigned& nrows, unsigned& tstep, int K, float* stage) {
+  count++;
+  nrows += K;
+  if ((int)count >= nd.muf) {
+    tstep++;
+    mfma_update((LDSQ float*)Wl, (LDSQ float*)bl, &nd, t, pd.base, pd.stride, count, nrows, tstep, (LDSQ float*)stage);
+    count = 0;
+    nrows = 0;
+    LOG(W->node, 2, 0, 0);
   }
-  if (nd.has_bias)
-    for (int r = threadIdx.x; r < R; r += AMP_THREADS) {
-      float a = 0.f;
-      for (int k = 0; k < K; ++k) a += Dl[k * ldd + r];
-      nd.G[(long long)R * C + r] += a;
-    }
 }
 
 // ---------------------------------------------------------------- lookup
-__device__ void role_g_lookup(const AmpDev* D, const WorkerDev* W, float* lds) {
+__device__ __noinline__ void role_g_lookup(const AmpDev* D, const WorkerDev* W) {
+  float* lds = amp_lds;
   const NodeDev& lk = D->node[0];
   const GBufs B = g_bufs(D);
   const int H = B.H, V = D->n_node_types;
@@ -178,27 +178,30 @@ __device__ void role_g_lookup(const AmpDev* D, const WorkerDev* W, float* lds) {
 }
 
 // ---------------------------------------------------------------- edge linear of type c
-__device__ void role_g_edge(const AmpDev* D, const WorkerDev* W, float* lds) {
+__device__ __noinline__ void role_g_edge(const AmpDev* D, const WorkerDev* W) {
+  float* lds = amp_lds;
   const NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
-  const int H = B.H, ctype = W->aux, Ep = (B.Em + 3) & ~3, Hs = (H + 3) & ~3;
+  const Pend pd = make_pend(W, t);
+  const int H = B.H, ctype = W->aux, Ep = amp_round16(B.Em), Hs = amp_ldrow(H);
+  const int NRB = t.Rp >> 4, NCG = amp_round16(H) >> 4;
   Lds L{lds};
-  float* Wl = L.take(H * t.ldw);
-  float* bl = L.take(H);
-  float* X = L.take(Ep * Hs);
-  float* Y = L.take(Ep * Hs);
-  float* DX = L.take(Ep * Hs);
+  float* Wl = L.take(t.Rp * t.ldw);
+  float* bl = L.take(t.Rp);
+  const int xfloats = Ep * Hs > UPD_STAGE * pd.stride ? Ep * Hs : UPD_STAGE * pd.stride;
+  float* X = L.take(xfloats);     // inputs h_src; later the products W^T delta; staging at updates
+  float* Y = L.take(Ep * Hs);     // outputs / deltas
   float* acc = L.take(B.N * H);
-  float* part = L.take(2048 + 4 * H);
   int* elist = (int*)L.take(B.Em);
   tile_load(nd, t, Wl, bl);
-  for (int i = threadIdx.x; i < Ep * Hs; i += AMP_THREADS) X[i] = Y[i] = 0.f;
+  for (int i = threadIdx.x; i < xfloats; i += AMP_THREADS) X[i] = 0.f;
+  for (int i = threadIdx.x; i < Ep * Hs; i += AMP_THREADS) Y[i] = 0.f;
   __syncthreads();
   const RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
-  unsigned count = W->wstate[0], tstep = W->wstate[1];
-  __shared__ int s_k;
+  unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
+  __shared__ int s_k, s_last, s_lastb;
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
     const unsigned seq = D->slot_seq[s];
@@ -211,16 +214,16 @@ __device__ void role_g_edge(const AmpDev* D, const WorkerDev* W, float* lds) {
       s_k = k;
     }
     __syncthreads();
-    const int K = s_k;
+    const int K = s_k, NB = (K + 15) >> 4;
     const float* h = B.Hm + B.hm(s, it);
-    for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
-      const int k = i / H, j = i - k * H;
-      X[k * Hs + j] = h[v.src[elist[k]] * H + j];
+    for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
+      const int k = i / Hs, j = i - k * Hs;
+      X[i] = j < H ? h[v.src[elist[k]] * H + j] : 0.f;   // padding columns of a used row are zero
     }
     __syncthreads();
     const int nact = g_active_types(v, B.T);
     if (!(code & MSG_DIR_B)) {
-      gemm_rows(Wl, t.ldw, H, H, bl, X, Hs, K, part, Y, Hs);
+      mfma_rows((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)bl, (LDSQ float*)X, Hs, NB, (LDSQ float*)Y, Hs);
       float* msg = B.Msg + (long long)s * B.Em * H;
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
         const int k = i / H, j = i - k * H;
@@ -228,7 +231,6 @@ __device__ void role_g_edge(const AmpDev* D, const WorkerDev* W, float* lds) {
       }
       LOG(W->node, 0, seq, it);
       __syncthreads();
-      __shared__ int s_last;
       if (threadIdx.x == 0) {
         fence_release();
         s_last = join_arrive(B.cnt + s * 8 + 0, nact);
@@ -255,21 +257,22 @@ __device__ void role_g_edge(const AmpDev* D, const WorkerDev* W, float* lds) {
     }
     // ---- backward: delta_e = dA[dst(e)]; dh_src(e) += W^T delta_e; one gradient for the group
     const float* dAs = B.dAs + B.sl(s);
-    for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
-      const int k = i / H, j = i - k * H;
-      Y[k * Hs + j] = dAs[v.dst[elist[k]] * H + j];
+    for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
+      const int k = i / Hs, j = i - k * Hs;
+      Y[i] = j < H ? dAs[v.dst[elist[k]] * H + j] : 0.f;
     }
     for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) acc[i] = 0.f;
     __syncthreads();
     LOG(W->node, 1, seq, it);
-    gemm_cols(Wl, t.ldw, H, H, Y, Hs, K, part, DX, Hs);
+    pend_append(pd, nrows, Y, Hs, H, X, Hs, H, K);
+    __syncthreads();
+    mfma_cols((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)Y, Hs, NB, (LDSQ float*)X, Hs);
     for (int j = threadIdx.x; j < H; j += AMP_THREADS)
-      for (int k = 0; k < K; ++k) acc[v.src[elist[k]] * H + j] += DX[k * Hs + j];
+      for (int k = 0; k < K; ++k) acc[v.src[elist[k]] * H + j] += X[k * Hs + j];
     __syncthreads();
     float* dHe = B.dHe + ((long long)s * B.T + ctype) * B.N * H;
     for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) dHe[i] = acc[i];
     __syncthreads();
-    __shared__ int s_lastb;
     if (threadIdx.x == 0) {
       fence_release();
       s_lastb = join_arrive(B.cnt + s * 8 + 3, nact);
@@ -297,36 +300,39 @@ __device__ void role_g_edge(const AmpDev* D, const WorkerDev* W, float* lds) {
           ring_post(D->ring[GR_LOOKUP], MSG_MAKE(1, s, 0));
       }
     }
-    rows_accumulate(nd, H, H, Y, Hs, X, Hs, K);
-    count_and_update(D, W, nd, t, Wl, bl, count, tstep);
+    g_count_and_update(D, W, nd, t, Wl, bl, pd, count, nrows, tstep, K, X);
   }
   tile_store(nd, t, Wl, bl);
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;
+    W->wstate[4] = nrows;
   }
 }
 
 // ---------------------------------------------------------------- GRU gate nodes (aux 0: update z, aux 1: reset r)
-__device__ void role_g_gate(const AmpDev* D, const WorkerDev* W, float* lds) {
+__device__ __noinline__ void role_g_gate(const AmpDev* D, const WorkerDev* W) {
+  float* lds = amp_lds;
   const NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
-  const int H = B.H, C = 2 * H, Np = (B.N + 3) & ~3, which = W->aux, Hs = (H + 3) & ~3, Cs = (C + 3) & ~3;
+  const Pend pd = make_pend(W, t);
+  const int H = B.H, C = 2 * H, Np = amp_round16(B.N), which = W->aux, Hs = amp_ldrow(H), Cs = amp_ldrow(C);
+  const int NRB = t.Rp >> 4, NCG = amp_round16(C) >> 4;
   Lds L{lds};
-  float* Wl = L.take(H * t.ldw);
-  float* bl = L.take(H);
-  float* X = L.take(Np * Cs);
+  float* Wl = L.take(t.Rp * t.ldw);
+  float* bl = L.take(t.Rp);
+  const int xfloats = Np * Cs > UPD_STAGE * pd.stride ? Np * Cs : UPD_STAGE * pd.stride;
+  float* X = L.take(xfloats);     // inputs; later W^T delta; staging at updates
   float* Y = L.take(Np * Hs);
-  float* DX = L.take(Np * Cs);
-  float* part = L.take(2048 + 4 * C);
+  float* DX = X;
   tile_load(nd, t, Wl, bl);
-  for (int i = threadIdx.x; i < Np * Cs; i += AMP_THREADS) X[i] = 0.f;
+  for (int i = threadIdx.x; i < xfloats; i += AMP_THREADS) X[i] = 0.f;
   for (int i = threadIdx.x; i < Np * Hs; i += AMP_THREADS) Y[i] = 0.f;
   __syncthreads();
   const RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
-  unsigned count = W->wstate[0], tstep = W->wstate[1];
+  unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
   __shared__ int s_last;
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
@@ -335,14 +341,14 @@ __device__ void role_g_gate(const AmpDev* D, const WorkerDev* W, float* lds) {
     const int K = v.N;
     const float* A = B.A + B.st(s, it);
     const float* h = B.Hm + B.hm(s, it);
-    for (int i = threadIdx.x; i < K * C; i += AMP_THREADS) {
-      const int k = i / C, c = i - k * C;
-      X[k * Cs + c] = c < H ? A[k * H + c] : h[k * H + c - H];
+    for (int i = threadIdx.x; i < K * Cs; i += AMP_THREADS) {
+      const int k = i / Cs, c = i - k * Cs;
+      X[i] = c < H ? A[k * H + c] : c < C ? h[k * H + c - H] : 0.f;   // padding columns of a used row are zero
     }
     __syncthreads();
     float* outp = (which == 0 ? B.Z : B.Rr) + B.st(s, it);
     if (!(code & MSG_DIR_B)) {
-      gemm_rows(Wl, t.ldw, H, C, bl, X, Cs, K, part, Y, Hs);
+      mfma_rows((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)bl, (LDSQ float*)X, Cs, (K + 15) >> 4, (LDSQ float*)Y, Hs);
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) outp[i] = sigmoidf_(Y[(i / H) * Hs + i % H]);
       LOG(W->node, 0, seq, it);
       __syncthreads();
@@ -353,10 +359,15 @@ __device__ void role_g_gate(const AmpDev* D, const WorkerDev* W, float* lds) {
       continue;
     }
     const float* dpre = (which == 0 ? B.dZ : B.dR) + B.sl(s);
-    for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) Y[(i / H) * Hs + i % H] = dpre[i];
+    for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
+      const int k = i / Hs, j = i - k * Hs;
+      Y[i] = j < H ? dpre[k * H + j] : 0.f;
+    }
     __syncthreads();
     LOG(W->node, 1, seq, it);
-    gemm_cols(Wl, t.ldw, H, C, Y, Hs, K, part, DX, Cs);
+    pend_append(pd, nrows, Y, Hs, H, X, Cs, C, K);
+    __syncthreads();
+    mfma_cols((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)Y, Hs, (K + 15) >> 4, (LDSQ float*)DX, Cs);
     float* dA = B.dA + ((long long)s * 3 + 1 + which) * B.N * H;
     float* dHp = B.dHp + ((long long)s * 3 + 1 + which) * B.N * H;
     for (int i = threadIdx.x; i < K * C; i += AMP_THREADS) {
@@ -384,36 +395,39 @@ __device__ void role_g_gate(const AmpDev* D, const WorkerDev* W, float* lds) {
         g_post_edges(D, v, s, it, true);
       }
     }
-    rows_accumulate(nd, H, C, Y, Hs, X, Cs, K);
-    count_and_update(D, W, nd, t, Wl, bl, count, tstep);
+    g_count_and_update(D, W, nd, t, Wl, bl, pd, count, nrows, tstep, K, X);
   }
   tile_store(nd, t, Wl, bl);
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;
+    W->wstate[4] = nrows;
   }
 }
 
 // ---------------------------------------------------------------- GRU candidate node + blend + loop control
-__device__ void role_g_cand(const AmpDev* D, const WorkerDev* W, float* lds) {
+__device__ __noinline__ void role_g_cand(const AmpDev* D, const WorkerDev* W) {
+  float* lds = amp_lds;
   const NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
-  const int H = B.H, C = 2 * H, Np = (B.N + 3) & ~3, Hs = (H + 3) & ~3, Cs = (C + 3) & ~3;
+  const Pend pd = make_pend(W, t);
+  const int H = B.H, C = 2 * H, Np = amp_round16(B.N), Hs = amp_ldrow(H), Cs = amp_ldrow(C);
+  const int NRB = t.Rp >> 4, NCG = amp_round16(C) >> 4;
   Lds L{lds};
-  float* Wl = L.take(H * t.ldw);
-  float* bl = L.take(H);
-  float* X = L.take(Np * Cs);
+  float* Wl = L.take(t.Rp * t.ldw);
+  float* bl = L.take(t.Rp);
+  const int xfloats = Np * Cs > UPD_STAGE * pd.stride ? Np * Cs : UPD_STAGE * pd.stride;
+  float* X = L.take(xfloats);     // inputs; later W^T delta; staging at updates
   float* Y = L.take(Np * Hs);
-  float* DX = L.take(Np * Cs);
-  float* part = L.take(2048 + 4 * C);
+  float* DX = X;
   tile_load(nd, t, Wl, bl);
-  for (int i = threadIdx.x; i < Np * Cs; i += AMP_THREADS) X[i] = 0.f;
+  for (int i = threadIdx.x; i < xfloats; i += AMP_THREADS) X[i] = 0.f;
   for (int i = threadIdx.x; i < Np * Hs; i += AMP_THREADS) Y[i] = 0.f;
   __syncthreads();
   const RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
-  unsigned count = W->wstate[0], tstep = W->wstate[1];
+  unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
     const unsigned seq = D->slot_seq[s];
@@ -424,13 +438,13 @@ __device__ void role_g_cand(const AmpDev* D, const WorkerDev* W, float* lds) {
     const float* Z = B.Z + B.st(s, it);
     const float* Rr = B.Rr + B.st(s, it);
     float* Ht = B.Ht + B.st(s, it);
-    for (int i = threadIdx.x; i < K * C; i += AMP_THREADS) {
-      const int k = i / C, c = i - k * C;
-      X[k * Cs + c] = c < H ? A[k * H + c] : Rr[k * H + c - H] * h[k * H + c - H];
+    for (int i = threadIdx.x; i < K * Cs; i += AMP_THREADS) {
+      const int k = i / Cs, c = i - k * Cs;
+      X[i] = c < H ? A[k * H + c] : c < C ? Rr[k * H + c - H] * h[k * H + c - H] : 0.f;
     }
     __syncthreads();
     if (!(code & MSG_DIR_B)) {
-      gemm_rows(Wl, t.ldw, H, C, bl, X, Cs, K, part, Y, Hs);
+      mfma_rows((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)bl, (LDSQ float*)X, Cs, (K + 15) >> 4, (LDSQ float*)Y, Hs);
       float* hn = B.Hm + B.hm(s, it + 1);
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
         const float ht = tanhf(Y[(i / H) * Hs + i % H]), z = Z[i];
@@ -457,9 +471,12 @@ __device__ void role_g_cand(const AmpDev* D, const WorkerDev* W, float* lds) {
       dZ[i] = g * (ht - h[i]) * z * (1.f - z);
       Y[(i / H) * Hs + i % H] = g * z * (1.f - ht * ht);
     }
+    for (int i = threadIdx.x; i < K * (Hs - H); i += AMP_THREADS) Y[(i / (Hs - H)) * Hs + H + i % (Hs - H)] = 0.f;
     __syncthreads();
     LOG(W->node, 1, seq, it);
-    gemm_cols(Wl, t.ldw, H, C, Y, Hs, K, part, DX, Cs);
+    pend_append(pd, nrows, Y, Hs, H, X, Cs, C, K);
+    __syncthreads();
+    mfma_cols((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)Y, Hs, (K + 15) >> 4, (LDSQ float*)DX, Cs);
     float* dA = B.dA + (long long)s * 3 * B.N * H;
     float* dHp = B.dHp + (long long)s * 3 * B.N * H;
     for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
@@ -475,25 +492,26 @@ __device__ void role_g_cand(const AmpDev* D, const WorkerDev* W, float* lds) {
       ring_post(D->ring[GR_GZ(D)], MSG_MAKE(1, s, it));
       ring_post(D->ring[GR_GR(D)], MSG_MAKE(1, s, it));
     }
-    rows_accumulate(nd, H, C, Y, Hs, X, Cs, K);
-    count_and_update(D, W, nd, t, Wl, bl, count, tstep);
+    g_count_and_update(D, W, nd, t, Wl, bl, pd, count, nrows, tstep, K, X);
   }
   tile_store(nd, t, Wl, bl);
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;
+    W->wstate[4] = nrows;
   }
 }
 
 // ---------------------------------------------------------------- readout: sum over nodes -> linear -> squared error
-__device__ void role_g_readout(const AmpDev* D, const WorkerDev* W, float* lds) {
+__device__ __noinline__ void role_g_readout(const AmpDev* D, const WorkerDev* W) {
+  float* lds = amp_lds;
   const NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
   const int H = B.H;
   Lds L{lds};
-  float* Wl = L.take(t.ldw);
-  float* bl = L.take(4);
+  float* Wl = L.take(t.Rp * t.ldw);
+  float* bl = L.take(t.Rp);
   float* pooled = L.take(H);
   float* red = L.take(AMP_THREADS);
   tile_load(nd, t, Wl, bl);

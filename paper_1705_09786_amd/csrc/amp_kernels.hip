@@ -38,7 +38,7 @@ __shared__ int s_pred;
 
 // ============================================================ controller
 // Single-thread wait on the controller's ring.
-__device__ bool ctrl_wait(const AmpDev* D, const RingDev& r, unsigned& head, unsigned& code) {
+__device__ __forceinline__ bool ctrl_wait(const AmpDev* D, const RingDev& r, unsigned& head, unsigned& code) {
   const unsigned want = head + 1u;
   unsigned long long* slot = &r.ent[head & r.mask];
   const long long t0 = wall_clock64();
@@ -62,7 +62,8 @@ __device__ bool ctrl_wait(const AmpDev* D, const RingDev& r, unsigned& head, uns
   }
 }
 
-__device__ void role_ctrl(const AmpDev* D, const WorkerDev* W, float* lds) {
+__device__ __noinline__ void role_ctrl(const AmpDev* D, const WorkerDev* W) {
+  float* lds = amp_lds;
   if (threadIdx.x == 0) {
     int* freelist = (int*)lds;
     const int mak = D->mak;
@@ -127,14 +128,15 @@ __device__ __forceinline__ void count_and_update(const AmpDev* D, const WorkerDe
 // also hosts the softmax loss, which turns the forward message round.
 // Slot storage: buf[0]=act1, buf[1]=act2 (post-ReLU outputs), buf[2]=grad
 // w.r.t. act1, buf[3]=grad w.r.t. act2.
-__device__ void role_mlp_lin(const AmpDev* D, const WorkerDev* W, float* lds) {
+__device__ __noinline__ void role_mlp_lin(const AmpDev* D, const WorkerDev* W) {
+  float* lds = amp_lds;
   const NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const int R = t.R, C = t.C, li = W->aux;
   const bool first = li == 0, last = li == 2;
   Lds L{lds};
-  float* Wl = L.take(R * t.ldw);
-  float* bl = L.take(R);
+  float* Wl = L.take(t.Rp * t.ldw);
+  float* bl = L.take(t.Rp);
   float* xs = L.take(C);
   float* ys = L.take(R);
   float* ds = L.take(R);
@@ -217,14 +219,15 @@ __device__ void role_mlp_lin(const AmpDev* D, const WorkerDev* W, float* lds) {
 // Slot storage: buf[0]=hs[mak][max_len][H] cell outputs, buf[1]=es[mak][max_len][E]
 // embeddings recorded at forward time, buf[2]=dh[mak][H] gradient w.r.t. the
 // hidden state travelling down the loop.
-__device__ void role_rnn_cell(const AmpDev* D, const WorkerDev* W, float* lds) {
+__device__ __noinline__ void role_rnn_cell(const AmpDev* D, const WorkerDev* W) {
+  float* lds = amp_lds;
   const NodeDev& nd = D->node[1];
   const NodeDev& lk = D->node[0];
   const Tile t = make_tile(nd, W);
   const int H = t.R, C = t.C, E = D->emb, V = D->vocab, TM = D->max_len;
   Lds L{lds};
-  float* Wl = L.take(H * t.ldw);
-  float* bl = L.take(H);
+  float* Wl = L.take(t.Rp * t.ldw);
+  float* bl = L.take(t.Rp);
   float* El = L.take(V * E);
   float* xs = L.take(C);
   float* ys = L.take(H);
@@ -330,13 +333,14 @@ __device__ void role_rnn_cell(const AmpDev* D, const WorkerDev* W, float* lds) {
 }
 
 // Output layer + softmax loss of the RNN: forward and backward in one event.
-__device__ void role_rnn_out(const AmpDev* D, const WorkerDev* W, float* lds) {
+__device__ __noinline__ void role_rnn_out(const AmpDev* D, const WorkerDev* W) {
+  float* lds = amp_lds;
   const NodeDev& nd = D->node[2];
   const Tile t = make_tile(nd, W);
   const int R = t.R, C = t.C, TM = D->max_len;
   Lds L{lds};
-  float* Wl = L.take(R * t.ldw);
-  float* bl = L.take(R);
+  float* Wl = L.take(t.Rp * t.ldw);
+  float* bl = L.take(t.Rp);
   float* xs = L.take(C);
   float* ys = L.take(R);
   float* ds = L.take(R);
@@ -397,37 +401,35 @@ __device__ void role_rnn_out(const AmpDev* D, const WorkerDev* W, float* lds) {
 
 // ============================================================ entry
 extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const AmpDev* D) {
-  extern __shared__ float lds[];
   const WorkerDev* W = &D->worker[blockIdx.x];
   long long t_begin = 0;
   if (threadIdx.x == 0) {
     s_logn = 0;
-    s_stat[0] = s_stat[1] = 0;
+    for (int i = 0; i < AMP_NSTAT; ++i) s_stat[i] = 0;
     t_begin = wall_clock64();
   }
   __syncthreads();
   switch (W->role) {
-    case ROLE_CTRL: role_ctrl(D, W, lds); break;
-    case ROLE_MLP_LIN: role_mlp_lin(D, W, lds); break;
-    case ROLE_RNN_CELL: role_rnn_cell(D, W, lds); break;
-    case ROLE_RNN_OUT: role_rnn_out(D, W, lds); break;
-    case ROLE_TREE_LOOKUP: role_tree_lookup(D, W, lds); break;
-    case ROLE_TREE_LEAF: role_tree_cell<false>(D, W, lds); break;
-    case ROLE_TREE_BRANCH: role_tree_cell<true>(D, W, lds); break;
-    case ROLE_TREE_OUT: role_tree_out(D, W, lds); break;
-    case ROLE_G_LOOKUP: role_g_lookup(D, W, lds); break;
-    case ROLE_G_EDGE: role_g_edge(D, W, lds); break;
-    case ROLE_G_GATE: role_g_gate(D, W, lds); break;
-    case ROLE_G_CAND: role_g_cand(D, W, lds); break;
-    case ROLE_G_READOUT: role_g_readout(D, W, lds); break;
+    case ROLE_CTRL: role_ctrl(D, W); break;
+    case ROLE_MLP_LIN: role_mlp_lin(D, W); break;
+    case ROLE_RNN_CELL: role_rnn_cell(D, W); break;
+    case ROLE_RNN_OUT: role_rnn_out(D, W); break;
+    case ROLE_TREE_LOOKUP: role_tree_lookup(D, W); break;
+    case ROLE_TREE_LEAF: role_tree_cell<false>(D, W); break;
+    case ROLE_TREE_BRANCH: role_tree_cell<true>(D, W); break;
+    case ROLE_TREE_OUT: role_tree_out(D, W); break;
+    case ROLE_G_LOOKUP: role_g_lookup(D, W); break;
+    case ROLE_G_EDGE: role_g_edge(D, W); break;
+    case ROLE_G_GATE: role_g_gate(D, W); break;
+    case ROLE_G_CAND: role_g_cand(D, W); break;
+    case ROLE_G_READOUT: role_g_readout(D, W); break;
     default: break;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
     if (W->log_cap) *W->log_n = s_logn;
-    W->stats[0] = s_stat[0];
-    W->stats[1] = s_stat[1];
-    W->stats[2] = (unsigned long long)(wall_clock64() - t_begin);
+    for (int i = 0; i < AMP_NSTAT; ++i) W->stats[i] = s_stat[i];
+    W->stats[3] = (unsigned long long)(wall_clock64() - t_begin);
   }
 }
 

@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <string>
 #include <vector>
 
@@ -18,6 +19,9 @@
 extern "C" hipError_t amp_launch(const AmpDev* dev, int n_workers, hipStream_t stream);
 
 namespace {
+
+constexpr size_t NSTAT = 12;
+constexpr size_t UPD_STAGE_HOST = 8;   // entries staged per step of an update (UPD_STAGE in the kernels)
 
 struct HostNode {
   std::string name;
@@ -74,7 +78,7 @@ struct amp_ctx {
   std::vector<int> last_correct;
   std::vector<amp_event> last_events;
   double last_seconds = 0;
-  std::vector<unsigned long long> last_stats;   // 3 per worker
+  std::vector<unsigned long long> last_stats;   // NSTAT per worker
   uint64_t last_npred = 0;
   unsigned total_admitted = 0;
   std::string err;
@@ -131,7 +135,17 @@ unsigned next_pow2(size_t v) {
 }
 
 size_t r4(size_t n) { return (n + 3) & ~(size_t)3; }
-size_t r8(size_t n) { return (n + 7) & ~(size_t)7; }
+
+size_t tile_rows(const amp_ctx* c, const HostWorker& w) { return (size_t)c->nodes[w.node].nblocks * w.nu; }
+size_t pend_stride(const amp_ctx* c, const HostWorker& w) {
+  return (size_t)amp_round16((int)tile_rows(c, w)) + (size_t)amp_round16(c->nodes[w.node].cols);
+}
+// Rows one gradient message can carry (grouped rows of the graph model).
+size_t rows_per_message(const amp_ctx* c, const HostWorker& w) {
+  if (w.role == ROLE_G_EDGE) return (size_t)c->max_edges;
+  if (w.role == ROLE_G_GATE || w.role == ROLE_G_CAND) return (size_t)c->max_len;
+  return 1;
+}
 
 // LDS floats a worker needs (mirrors the carving in the kernels); sets w.kb.
 // Returns 0 when the worker cannot fit.
@@ -143,37 +157,45 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
     w.kb = 32;
     return r4(c->max_mak) + AMP_TREE_LOOKUP_MAX_MUF;
   }
-  if (w.role >= ROLE_G_LOOKUP) {
-    const size_t H = c->dims.hidden, N = c->max_len, Ep = (c->max_edges + 3) & ~3, Np = (N + 3) & ~3;
-    const size_t Hs = r4(H), Cs = r4(2 * H);
-    if (w.role == ROLE_G_LOOKUP) return r4((size_t)c->dims.n_node_types * H);
-    if (w.role == ROLE_G_EDGE)
-      return r4(H * (H | 1)) + r4(H) + 3 * r4(Ep * Hs) + r4(N * H) + r4(2048 + 4 * H) + r4(c->max_edges);
-    if (w.role == ROLE_G_READOUT) return r4(H | 1) + 4 + r4(H) + AMP_THREADS;
-    return r4(H * (2 * H | 1)) + r4(H) + 2 * r4(Np * Cs) + r4(Np * Hs) + r4(2048 + 8 * H);
-  }
+  if (w.role == ROLE_G_LOOKUP) return r4((size_t)c->dims.n_node_types * c->dims.hidden);
   const HostNode& n = c->nodes[w.node];
-  const size_t R = (size_t)n.nblocks * w.nu, C = n.cols, ldw = C | 1;
-  const size_t stride = r8(R) + r8(C);
-  if (w.role == ROLE_TREE_LEAF || w.role == ROLE_TREE_BRANCH) {
-    const size_t fixed = r4(R * ldw) + r4(R) + r4(2048 + 512);
-    const size_t ldx = r4(C), ldy = r4(R);
-    if (fixed + 8 * stride + 4 * ldy > avail) return 0;
-    size_t kb = (avail - fixed) / (ldx + ldy);
-    kb = std::min<size_t>(kb, 16) & ~(size_t)3;
-    while (kb >= 4 && fixed + std::max(kb * ldx, 8 * stride) + kb * ldy > avail) kb -= 4;
-    if (kb < 4) return 0;
-    w.kb = (int)kb;
-    return fixed + std::max(kb * ldx, 8 * stride) + kb * ldy;
+  const size_t R = tile_rows(c, w), C = n.cols, Rp = amp_round16((int)R), ldw = amp_ldrow((int)C);
+  const size_t stride = pend_stride(c, w), wfl = r4(Rp * ldw) + r4(Rp);
+  if (R > AMP_THREADS) return 0;
+  size_t f = 0;
+  switch (w.role) {
+    case ROLE_TREE_LEAF:
+    case ROLE_TREE_BRANCH: {
+      const size_t ldx = amp_ldrow((int)C), ldy = amp_ldrow((int)R);
+      w.kb = 16;
+      f = wfl + r4(std::max(16 * ldx, UPD_STAGE_HOST * stride)) + r4(16 * ldy);
+      break;
+    }
+    case ROLE_TREE_OUT: {
+      const size_t NW = AMP_THREADS / 64;
+      w.kb = 32;
+      f = wfl + r4(NW * C) + r4(NW * 64) + r4(UPD_STAGE_HOST * stride) + r4(c->max_mak);
+      break;
+    }
+    case ROLE_G_EDGE: {
+      const size_t H = c->dims.hidden, Ep = amp_round16(c->max_edges), Hs = amp_ldrow((int)H);
+      f = wfl + r4(std::max(Ep * Hs, UPD_STAGE_HOST * stride)) + r4(Ep * Hs) + r4((size_t)c->max_len * H) + r4(c->max_edges);
+      break;
+    }
+    case ROLE_G_GATE:
+    case ROLE_G_CAND: {
+      const size_t H = c->dims.hidden, Np = amp_round16(c->max_len), Hs = amp_ldrow((int)H), Cs = amp_ldrow((int)(2 * H));
+      f = wfl + r4(std::max(Np * Cs, UPD_STAGE_HOST * stride)) + r4(Np * Hs);
+      break;
+    }
+    case ROLE_G_READOUT:
+      f = wfl + r4(c->dims.hidden) + AMP_THREADS;
+      break;
+    default:   // MLP / RNN workers
+      f = wfl + r4(C) + r4(R) + r4(R) + r4(C) + r4(8 * std::max(R, C));
+      if (w.role == ROLE_RNN_CELL) f += r4((size_t)c->dims.vocab * c->dims.emb);
   }
-  if (w.role == ROLE_TREE_OUT) {
-    w.kb = 32;
-    const size_t NW = AMP_THREADS / 64;
-    return r4(R * ldw) + r4(R) + r4(NW * C) + r4(NW * 64) + r4(8 * stride) + r4(c->max_mak);
-  }
-  size_t f = r4(R * ldw) + r4(R) + r4(C) + r4(R) + r4(R) + r4(C) + r4(8 * std::max(R, C));
-  if (w.role == ROLE_RNN_CELL) f += r4((size_t)c->dims.vocab * c->dims.emb);
-  return f;
+  return f <= avail ? f : 0;
 }
 
 }  // namespace
@@ -369,9 +391,7 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
   for (HostWorker& w : c->workers) {
     w.off_state = take(64);
     if (w.node >= 0 && c->nodes[w.node].name != "lookup") {
-      const HostNode& n = c->nodes[w.node];
-      const size_t stride = r8((size_t)n.nblocks * w.nu) + r8(n.cols);
-      w.pend_bytes = stride * 4 * AMP_DENSE_MAX_MUF;
+      w.pend_bytes = pend_stride(c, w) * 4 * AMP_DENSE_MAX_MUF * rows_per_message(c, w);
       w.off_pend = take(w.pend_bytes);
     }
   }
@@ -475,15 +495,18 @@ int amp_num_nodes(amp_ctx* c) { return c ? (int)c->nodes.size() : AMP_EINVAL; }
 int amp_num_workers(amp_ctx* c) { return c ? (int)c->workers.size() : AMP_EINVAL; }
 
 int amp_get_worker_stats(amp_ctx* c, double* wait_fraction, uint64_t* messages, int32_t* node_of_worker, size_t cap,
-                         size_t* n) {
+                         size_t* n, uint64_t* batches, double* phase_fraction) {
   if (!c) return AMP_EINVAL;
   if (n) *n = c->workers.size();
   if (c->last_stats.empty()) return fail(c, AMP_ESTATE, "get_worker_stats: nothing run yet");
   if (cap < c->workers.size()) return fail(c, AMP_ENOMEM, "get_worker_stats: %zu entries needed", c->workers.size());
   for (size_t w = 0; w < c->workers.size(); ++w) {
-    const unsigned long long* s = &c->last_stats[3 * w];
-    if (wait_fraction) wait_fraction[w] = s[2] ? (double)s[0] / (double)s[2] : 0.0;
+    const unsigned long long* s = &c->last_stats[NSTAT * w];
+    if (wait_fraction) wait_fraction[w] = s[3] ? (double)s[0] / (double)s[3] : 0.0;
     if (messages) messages[w] = s[1];
+    if (batches) batches[w] = s[2];
+    if (phase_fraction)
+      for (int i = 0; i < 8; ++i) phase_fraction[8 * w + i] = getenv("AMP_RAW_PHASES") ? (double)s[4 + i] : s[3] ? (double)s[4 + i] / (double)s[3] : 0.0;
     if (node_of_worker) node_of_worker[w] = c->workers[w].node;
   }
   return AMP_OK;
@@ -724,7 +747,7 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
     off_log[w] = take(8 * std::max<size_t>(log_cap, 1));
     off_logn[w] = take(64);
   }
-  const size_t off_stats = take(24 * c->workers.size());
+  const size_t off_stats = take(8 * NSTAT * c->workers.size());
   if (off > c->arena_bytes) return fail(c, AMP_ENOMEM, "arena of %zu bytes is too small, %zu needed", c->arena_bytes, off);
   HIPCHK(c, hipMemsetAsync(c->arena + off_loss, 0, off - off_loss, c->stream));
 
@@ -772,7 +795,7 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
     wd.log = (unsigned long long*)(c->arena + off_log[i]);
     wd.log_n = (unsigned*)(c->arena + off_logn[i]);
     wd.log_cap = (unsigned)log_cap;
-    wd.stats = (unsigned long long*)(c->arena + off_stats) + 3 * i;
+    wd.stats = (unsigned long long*)(c->arena + off_stats) + NSTAT * i;
     wd.pend = w.pend_bytes ? (float*)(c->arena + w.off_pend) : nullptr;
     wd.kb = w.kb;
   }
@@ -835,8 +858,8 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
     for (HostNode& n : c->nodes) n.dirty = true;
     return fail(c, AMP_EDEVICE, "kernel stopped itself: %s (worker %u)", why, ctl[2]);
   }
-  c->last_stats.assign(3 * c->workers.size(), 0);
-  HIPCHK(c, hipMemcpy(c->last_stats.data(), c->arena + off_stats, 24 * c->workers.size(), hipMemcpyDeviceToHost));
+  c->last_stats.assign(NSTAT * c->workers.size(), 0);
+  HIPCHK(c, hipMemcpy(c->last_stats.data(), c->arena + off_stats, 8 * NSTAT * c->workers.size(), hipMemcpyDeviceToHost));
   std::vector<float> loss(n_total);
   std::vector<int> correct(n_total);
   HIPCHK(c, hipMemcpy(loss.data(), D.loss_out, n_total * 4, hipMemcpyDeviceToHost));

@@ -81,7 +81,7 @@ __device__ __forceinline__ bool code_is_b(unsigned c) { return (c & MSG_DIR_B) !
 // A tile has finished its units of node n: when all tiles have, the node's
 // [h; c] goes to the output layer and, through Isu / Concat, to its parent,
 // which fires once both children are there.  One lane, after a release fence.
-__device__ void tree_node_part_done(const AmpDev* D, const TreeBufs& B, int s, int n, int parent_code, int ntiles) {
+__device__ __forceinline__ void tree_node_part_done(const AmpDev* D, const TreeBufs& B, int s, int n, int parent_code, int ntiles) {
   int* c = B.cnt + B.node(s, n) * 4;
   if (!join_arrive(c + 0, ntiles)) return;
   ring_post(D->ring[TR_OUT], MSG_MAKE(0, s, n));
@@ -92,7 +92,7 @@ __device__ void tree_node_part_done(const AmpDev* D, const TreeBufs& B, int s, i
 
 // One gradient part for node n has been written: Bcast's backward waits for
 // the output layer's part and (unless n is the root) every parent tile's.
-__device__ void tree_grad_part_done(const AmpDev* D, const TreeBufs& B, int s, int n, bool is_root, bool is_leaf) {
+__device__ __forceinline__ void tree_grad_part_done(const AmpDev* D, const TreeBufs& B, int s, int n, bool is_root, bool is_leaf) {
   const int expect = is_root ? 1 : 1 + B.TB;
   if (join_arrive(B.cnt + B.node(s, n) * 4 + 2, expect))
     ring_post(D->ring[is_leaf ? TR_LEAF : TR_BRANCH], MSG_MAKE(1, s, n));
@@ -101,7 +101,8 @@ __device__ void tree_grad_part_done(const AmpDev* D, const TreeBufs& B, int s, i
 // ------------------------------------------------------------ lookup
 // Thread c owns column c of every row it touches, so the messages of a batch
 // need no barriers between them.
-__device__ void role_tree_lookup(const AmpDev* D, const WorkerDev* W, float* lds) {
+__device__ __noinline__ void role_tree_lookup(const AmpDev* D, const WorkerDev* W) {
+  float* lds = amp_lds;
   const NodeDev& lk = D->node[0];
   const TreeBufs B = tree_bufs(D);
   const int E = B.D, KB = W->kb;
@@ -232,23 +233,23 @@ __device__ void role_tree_lookup(const AmpDev* D, const WorkerDev* W, float* lds
 // BR = false: rows [i; o; u] over the embedding.
 // BR = true : rows [i; f_l; f_r; o; u] over [h_l; h_r].
 template <bool BR>
-__device__ void role_tree_cell(const AmpDev* D, const WorkerDev* W, float* lds) {
+__device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W) {
+  float* lds = amp_lds;
   const NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const TreeBufs B = tree_bufs(D);
   const Pend pd = make_pend(W, t);
   const int R = t.R, C = t.C, H = B.H, nu = t.nu, u0 = t.u0, KB = W->kb;
-  const int ldx = (C + 3) & ~3, ldy = (R + 3) & ~3, KBp = (KB + 3) & ~3;
+  const int ldx = amp_ldrow(C), ldy = amp_ldrow(R), NRB = t.Rp >> 4, NCG = amp_round16(C) >> 4;
   Lds L{lds};
-  float* Wl = L.take(R * t.ldw);
-  float* bl = L.take(R);
-  const int xfloats = KBp * ldx > 8 * pd.stride ? KBp * ldx : 8 * pd.stride;
+  float* Wl = L.take(t.Rp * t.ldw);
+  float* bl = L.take(t.Rp);
+  const int xfloats = 16 * ldx > UPD_STAGE * pd.stride ? 16 * ldx : UPD_STAGE * pd.stride;
   float* X = L.take(xfloats);
-  float* Y = L.take(KBp * ldy);
-  float* part = L.take(2048 + 512);
+  float* Y = L.take(16 * ldy);
   tile_load(nd, t, Wl, bl);
   for (int i = threadIdx.x; i < xfloats; i += AMP_THREADS) X[i] = 0.f;
-  for (int i = threadIdx.x; i < KBp * ldy; i += AMP_THREADS) Y[i] = 0.f;
+  for (int i = threadIdx.x; i < 16 * ldy; i += AMP_THREADS) Y[i] = 0.f;
   BatchMsg& M = s_M;
   __syncthreads();
   const RingDev& mine = D->ring[W->ring];
@@ -287,19 +288,24 @@ __device__ void role_tree_cell(const AmpDev* D, const WorkerDev* W, float* lds) 
     }
     __syncthreads();
     const int nF = M.nF, nB = M.nB;
+    PHASE(0);
     // ---------------- forward messages of the batch
     if (nF > 0) {
-      for (int i = threadIdx.x; i < nF * C; i += AMP_THREADS) {
-        const int k = i / C, c = i - k * C, m = M.fidx[k];
-        float v;
-        if (BR)
-          v = c < H ? B.hc[B.node(M.s[m], M.a[m]) * 2 * H + c] : B.hc[B.node(M.s[m], M.b[m]) * 2 * H + c - H];
-        else
-          v = B.xin[B.leaf(M.s[m], M.n[m]) * C + c];
-        X[k * ldx + c] = v;
+      for (int i = threadIdx.x; i < nF * ldx; i += AMP_THREADS) {
+        const int k = i / ldx, c = i - k * ldx, m = M.fidx[k];
+        float v = 0.f;   // padding columns of a used row are zero
+        if (c < C) {
+          if (BR)
+            v = c < H ? B.hc[B.node(M.s[m], M.a[m]) * 2 * H + c] : B.hc[B.node(M.s[m], M.b[m]) * 2 * H + c - H];
+          else
+            v = B.xin[B.leaf(M.s[m], M.n[m]) * C + c];
+        }
+        X[i] = v;
       }
       __syncthreads();
-      gemm_rows(Wl, t.ldw, R, C, bl, X, ldx, nF, part, Y, ldy);
+      PHASE(1);
+      mfma_rows((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)bl, (LDSQ float*)X, ldx, 1, (LDSQ float*)Y, ldy);
+      PHASE(2);
       for (int i = threadIdx.x; i < nF * nu; i += AMP_THREADS) {
         const int k = i / nu, j = i - k * nu, m = M.fidx[k], u = u0 + j;
         const float* y = Y + k * ldy;
@@ -333,17 +339,24 @@ __device__ void role_tree_cell(const AmpDev* D, const WorkerDev* W, float* lds) 
         hcn[H + u] = c_;
       }
       __syncthreads();
+      PHASE(3);
     }
     // ---------------- backward messages of the batch
     if (nB > 0) {
-      for (int i = threadIdx.x; i < nB * C; i += AMP_THREADS) {
-        const int k = i / C, c = i - k * C, m = M.bidx[k];
-        float v;
-        if (BR)
-          v = c < H ? B.hc[B.node(M.s[m], M.a[m]) * 2 * H + c] : B.hc[B.node(M.s[m], M.b[m]) * 2 * H + c - H];
-        else
-          v = B.xin[B.leaf(M.s[m], M.n[m]) * C + c];
-        X[k * ldx + c] = v;
+      for (int i = threadIdx.x; i < nB * ldx; i += AMP_THREADS) {
+        const int k = i / ldx, c = i - k * ldx, m = M.bidx[k];
+        float v = 0.f;   // padding columns of a used row are zero
+        if (c < C) {
+          if (BR)
+            v = c < H ? B.hc[B.node(M.s[m], M.a[m]) * 2 * H + c] : B.hc[B.node(M.s[m], M.b[m]) * 2 * H + c - H];
+          else
+            v = B.xin[B.leaf(M.s[m], M.n[m]) * C + c];
+        }
+        X[i] = v;
+      }
+      for (int i = threadIdx.x; i < nB * (ldy - R); i += AMP_THREADS) {
+        const int k = i / (ldy - R), r = R + i - k * (ldy - R);
+        Y[k * ldy + r] = 0.f;
       }
       for (int i = threadIdx.x; i < nB * nu; i += AMP_THREADS) {
         const int k = i / nu, j = i - k * nu, m = M.bidx[k], u = u0 + j;
@@ -380,9 +393,11 @@ __device__ void role_tree_cell(const AmpDev* D, const WorkerDev* W, float* lds) 
         }
       }
       __syncthreads();
+      PHASE(4);
       pend_append(pd, count, Y, ldy, R, X, ldx, C, nB);
       __syncthreads();
-      gemm_cols(Wl, t.ldw, R, C, Y, ldy, nB, part, X, ldx);
+      mfma_cols((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)Y, ldy, 1, (LDSQ float*)X, ldx);
+      PHASE(5);
       for (int i = threadIdx.x; i < nB * C; i += AMP_THREADS) {
         const int k = i / C, c = i - k * C, m = M.bidx[k];
         const float v = X[k * ldx + c];
@@ -413,14 +428,16 @@ __device__ void role_tree_cell(const AmpDev* D, const WorkerDev* W, float* lds) 
         }
       }
     }
+    PHASE(6);
     count += nB;
     if ((int)count >= nd.muf) {
       tstep++;
-      tile_update_deferred(nd, t, Wl, bl, pd, count, tstep, X);
+      mfma_update((LDSQ float*)Wl, (LDSQ float*)bl, &nd, t, pd.base, pd.stride, count, count, tstep, (LDSQ float*)X);
       count = 0;
       LOG(W->node, 2, 0, 0);
     }
     __syncthreads();
+    PHASE(7);
   }
   tile_store(nd, t, Wl, bl);
   if (threadIdx.x == 0) {
@@ -431,7 +448,8 @@ __device__ void role_tree_cell(const AmpDev* D, const WorkerDev* W, float* lds) 
 
 // ------------------------------------------------------------ output layer + loss at every node
 // One wave per message: forward, softmax loss and backward in one event.
-__device__ void role_tree_out(const AmpDev* D, const WorkerDev* W, float* lds) {
+__device__ __noinline__ void role_tree_out(const AmpDev* D, const WorkerDev* W) {
+  float* lds = amp_lds;
   const NodeDev& nd = D->node[3];
   const Tile t = make_tile(nd, W);
   const TreeBufs B = tree_bufs(D);
@@ -439,11 +457,11 @@ __device__ void role_tree_out(const AmpDev* D, const WorkerDev* W, float* lds) {
   const int R = t.R, C = t.C, H = B.H, KB = W->kb;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, NW = AMP_THREADS >> 6;
   Lds L{lds};
-  float* Wl = L.take(R * t.ldw);
-  float* bl = L.take(R);
+  float* Wl = L.take(t.Rp * t.ldw);
+  float* bl = L.take(t.Rp);
   float* hbuf = L.take(NW * C);            // per wave: the node's h
   float* zbuf = L.take(NW * 64);           // per wave: logits, then dz
-  float* stage = L.take(8 * pd.stride);
+  float* stage = L.take(UPD_STAGE * pd.stride);
   int* done_cnt = (int*)L.take(D->mak);    // eval: nodes scored per slot
   tile_load(nd, t, Wl, bl);
   for (int i = threadIdx.x; i < D->mak; i += AMP_THREADS) done_cnt[i] = 0;
@@ -516,10 +534,10 @@ __device__ void role_tree_out(const AmpDev* D, const WorkerDev* W, float* lds) {
       float* pe = pd.base + (long long)(count + k) * pd.stride;
       for (int j = lane; j < pd.stride; j += 64) {
         float v = 0.f;
-        if (j < pd.R8) {
+        if (j < pd.Rp) {
           if (j < R) v = zw[j];
-        } else if (j - pd.R8 < C) {
-          v = hw[j - pd.R8];
+        } else if (j - pd.Rp < C) {
+          v = hw[j - pd.Rp];
         }
         pe[j] = v;
       }
@@ -548,7 +566,7 @@ __device__ void role_tree_out(const AmpDev* D, const WorkerDev* W, float* lds) {
       count += n;
       if ((int)count >= nd.muf) {
         tstep++;
-        tile_update_deferred(nd, t, Wl, bl, pd, count, tstep, stage);
+        mfma_update((LDSQ float*)Wl, (LDSQ float*)bl, &nd, t, pd.base, pd.stride, count, count, tstep, (LDSQ float*)stage);
         count = 0;
         LOG(3, 2, 0, 0);
       }
