@@ -17,7 +17,7 @@
 // step on the LDS-resident weights.
 #pragma once
 
-#define KB_MAX 32
+#define KB_MAX 64
 
 __device__ __forceinline__ int round8(int v) { return (v + 7) & ~7; }
 
@@ -26,6 +26,8 @@ struct BatchMsg {
   int s[KB_MAX], n[KB_MAX], a[KB_MAX], b[KB_MAX], par[KB_MAX], L[KB_MAX], aux[KB_MAX];
   unsigned seq[KB_MAX];
   int fidx[KB_MAX], bidx[KB_MAX];
+  int off0[KB_MAX], off1[KB_MAX];   // float offsets of the input segments
+  int dst0[KB_MAX], dst1[KB_MAX];   // float offsets where the input gradient's segments go
   int nF, nB;
 };
 __shared__ BatchMsg s_M;
@@ -52,7 +54,7 @@ __device__ __forceinline__ int wait_batch(const AmpDev* D, const RingDev& r, uns
       if (lane < kmax) e = __hip_atomic_load(slot, __ATOMIC_RELAXED, AGENT);
       const bool ready = lane < kmax && (unsigned)(e >> 32) == ticket + 1u;
       const unsigned long long m = __ballot(ready);
-      n = __builtin_ctzll(~m);   // leading run of ready entries (m has at most kmax <= 32 bits set)
+      n = ~m ? __builtin_ctzll(~m) : 64;   // leading run of ready entries
       code = (unsigned)e;
       if (n > 0) break;
       int stop = 0;
@@ -69,7 +71,7 @@ __device__ __forceinline__ int wait_batch(const AmpDev* D, const RingDev& r, uns
         // done is raised only when nothing is in flight; a last look avoids losing a message
         e = lane < kmax ? __hip_atomic_load(slot, __ATOMIC_RELAXED, AGENT) : 0ull;
         const unsigned long long m2 = __ballot(lane < kmax && (unsigned)(e >> 32) == ticket + 1u);
-        n = __builtin_ctzll(~m2);
+        n = ~m2 ? __builtin_ctzll(~m2) : 64;
         code = (unsigned)e;
         if (n == 0 || ld_u32(&D->ctl[0]) != 0u) {
           n = 0;
@@ -83,7 +85,7 @@ __device__ __forceinline__ int wait_batch(const AmpDev* D, const RingDev& r, uns
       // cut after the room-th backward message
       const bool b = lane < n && is_b(code);
       const unsigned long long mb = __ballot(b);
-      const int before = __popcll(mb & ((1ull << lane) - 1ull));
+      const int before = __popcll(mb & ((1ull << lane) - 1ull));   // lane < 64
       const unsigned long long cutm = __ballot(b && before + 1 == room);
       if (cutm) {
         const int cut = __builtin_ctzll(cutm) + 1;
@@ -191,7 +193,7 @@ __device__ __forceinline__ Pend make_pend(const WorkerDev* W, const Tile& t) {
   Pend p;
   p.base = W->pend;
   p.Rp = t.Rp;
-  p.Cp = amp_round16(t.C);
+  p.Cp = amp_round16(t.Cl);
   p.stride = p.Rp + p.Cp;
   return p;
 }
@@ -259,13 +261,13 @@ __device__ __noinline__ void mfma_update(LDSQ float* Wl, LDSQ float* bl, const N
       const int tl = pass0 + wave + 8 * ti;
       if (tl < T) {
         const int rb = tl / NCB, cb = tl - rb * NCB;
-        const int c = cb * 16 + i;
+        const int lc = cb * 16 + i, c = t.ncol(lc);
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int r = rb * 16 + 4 * q + v;
-          if (r < t.R && c < t.C) {
+          if (r < t.R && c >= 0) {
             const long long gi = (long long)t.grow(r) * t.C + c;
-            Wl[r * t.ldw + c] = opt_apply(o, Wl[r * t.ldw + c], acc[ti][v] * inv, nd.M, nd.V, gi);
+            Wl[r * t.ldw + lc] = opt_apply(o, Wl[r * t.ldw + lc], acc[ti][v] * inv, nd.M, nd.V, gi);
           }
         }
       }

@@ -187,9 +187,20 @@ __device__ __forceinline__ void gemv_cols(const float* Wl, int ldw, int R, int C
 // lr = g * nu + j  <->  node row g * block + u0 + j.
 struct Tile {
   int R, C, ldw, nu, u0, block, nblocks, Rp;
+  int seg, segp, Cl;   // column segments (see NodeDev); Cl = padded column count
   __device__ __forceinline__ int grow(int lr) const {
     const int g = lr / nu;
     return g * block + u0 + (lr - g * nu);
+  }
+  // LDS column of node column c
+  __device__ __forceinline__ int lcol(int c) const {
+    const int sg = c / seg;
+    return sg * segp + (c - sg * seg);
+  }
+  // node column of LDS column lc, -1 for a padding column
+  __device__ __forceinline__ int ncol(int lc) const {
+    const int sg = lc / segp, o = lc - sg * segp;
+    return (lc < Cl && o < seg) ? sg * seg + o : -1;
   }
 };
 
@@ -201,7 +212,10 @@ __device__ __forceinline__ Tile make_tile(const NodeDev& nd, const WorkerDev* W)
   t.nblocks = nd.nblocks;
   t.R = nd.nblocks * W->nu;
   t.C = nd.cols;
-  t.ldw = amp_ldrow(nd.cols);
+  t.seg = nd.seg;
+  t.segp = nd.segp;
+  t.Cl = (nd.cols / nd.seg) * nd.segp;
+  t.ldw = amp_ldrow(t.Cl);
   t.Rp = amp_round16(t.R);
   return t;
 }
@@ -213,7 +227,7 @@ __device__ __forceinline__ void tile_load(const NodeDev& nd, const Tile& t, floa
   __syncthreads();
   for (int i = threadIdx.x; i < t.R * t.C; i += AMP_THREADS) {
     const int lr = i / t.C, c = i - lr * t.C;
-    Wl[lr * t.ldw + c] = nd.P[(long long)t.grow(lr) * t.C + c];
+    Wl[lr * t.ldw + t.lcol(c)] = nd.P[(long long)t.grow(lr) * t.C + c];
   }
   if (nd.has_bias)
     for (int lr = threadIdx.x; lr < t.R; lr += AMP_THREADS) bl[lr] = nd.P[(long long)nd.rows * t.C + t.grow(lr)];
@@ -224,7 +238,7 @@ __device__ __forceinline__ void tile_store(const NodeDev& nd, const Tile& t, con
   __syncthreads();
   for (int i = threadIdx.x; i < t.R * t.C; i += AMP_THREADS) {
     const int lr = i / t.C, c = i - lr * t.C;
-    nd.P[(long long)t.grow(lr) * t.C + c] = Wl[lr * t.ldw + c];
+    nd.P[(long long)t.grow(lr) * t.C + c] = Wl[lr * t.ldw + t.lcol(c)];
   }
   if (nd.has_bias)
     for (int lr = threadIdx.x; lr < t.R; lr += AMP_THREADS) nd.P[(long long)nd.rows * t.C + t.grow(lr)] = bl[lr];
@@ -289,7 +303,7 @@ __device__ __forceinline__ void tile_update(const NodeDev& nd, const Tile& t, fl
     const long long gi = (long long)t.grow(lr) * t.C + c;
     const float g = nd.G[gi] * inv;
     nd.G[gi] = 0.f;
-    Wl[lr * t.ldw + c] = opt_apply(o, Wl[lr * t.ldw + c], g, nd.M, nd.V, gi);
+    Wl[lr * t.ldw + t.lcol(c)] = opt_apply(o, Wl[lr * t.ldw + t.lcol(c)], g, nd.M, nd.V, gi);
   }
   if (nd.has_bias)
     for (int lr = threadIdx.x; lr < t.R; lr += AMP_THREADS) {

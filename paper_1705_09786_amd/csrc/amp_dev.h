@@ -9,7 +9,7 @@
 #define AMP_MAX_BUFS 24
 #define AMP_THREADS 512
 #define AMP_LDS_BYTES 163840   // 160 KB per workgroup on gfx950
-#define AMP_DYN_LDS_BYTES (AMP_LDS_BYTES - 2048)   // dynamic part; the rest is for static __shared__
+#define AMP_DYN_LDS_BYTES (AMP_LDS_BYTES - 6144)   // dynamic part; the rest is for static __shared__
 #define AMP_TREE_LOOKUP_MAX_MUF 16384
 #define AMP_DENSE_MAX_MUF 256         // longest pending-gradient list of a dense node (messages)
 
@@ -23,6 +23,7 @@
 #define AMP_HD
 #endif
 AMP_HD static inline int amp_round16(int v) { return (v + 15) & ~15; }
+AMP_HD static inline int amp_round4(int v) { return (v + 3) & ~3; }
 AMP_HD static inline int amp_ldrow(int cols) {
   int l = amp_round16(cols);
   if (((l >> 2) & 1) == 0) l += 4;
@@ -79,7 +80,10 @@ struct NodeDev {
   int rows, cols, has_bias, muf;
   int opt, mean, nblocks, block;   // rows = nblocks * block (gate blocks)
   float lr, mom, b1, b2, eps;
-  int pad;
+  // Column layout of the node's LDS tile and pending inputs: the cols columns
+  // form cols / seg segments of seg columns, each padded to segp (a multiple
+  // of 4) so that a segment can be fetched from its own 16-byte aligned row.
+  int seg, segp, pad;
 };
 
 struct WorkerDev {
@@ -113,6 +117,7 @@ struct DataDev {
   const int* dst;
   const int* etype;
   const int* tcount;       // [n_inst][8] directed edges per edge type
+  const int* tnode;        // tree: [nodes][4] = left, right, parent*2+side (-1 root), label; indexed like left
 };
 
 struct AmpDev {
@@ -127,6 +132,7 @@ struct AmpDev {
   unsigned n_total, first_seq;
   unsigned* ctl;              // [0] abort code, [1] done, [2] abort detail
   unsigned* slot_seq;         // [mak] admission number held by each slot
+  int* smeta;                 // [mak][4] written at admission: admission number, length, node offset, token offset
   float* loss_out;            // [n_total] summed loss of each admission
   int* correct_out;           // [n_total]
   float* yhat_out;            // [n_total] (GGNN prediction)

@@ -81,14 +81,20 @@ __device__ __noinline__ void role_ctrl(const AmpDev* D, const WorkerDev* W) {
         const unsigned seq = D->first_seq + next;
         D->slot_seq[s] = seq;
         log_event(D, W, &s_logn, 0, 3, seq, 0);
-        fence_release();
         if (D->model == 3) {
-          // tree: one token message per leaf goes to the lookup (worker 1)
+          // tree: the slot's instance facts for the workers, then one token message per leaf to the lookup (worker 1)
           const int inst = seq % D->data.n_inst;
-          const int L = D->data.tok_off[inst + 1] - D->data.tok_off[inst];
+          const int toff = D->data.tok_off[inst], L = D->data.tok_off[inst + 1] - toff;
+          int* sm = D->smeta + 4 * s;
+          sm[0] = (int)seq;
+          sm[1] = L;
+          sm[2] = D->data.node_off[inst];
+          sm[3] = toff;
+          fence_release();
           const unsigned t = ring_reserve(D->ring[1], L);
           for (int l = 0; l < L; ++l) ring_put(D->ring[1], t + l, MSG_MAKE(0, s, l));
         } else {
+          fence_release();
           ring_post(D->ring[1], MSG_MAKE(0, s, 0));
         }
         next++;

@@ -27,6 +27,8 @@ struct HostNode {
   std::string name;
   int rows = 0, cols = 0, has_bias = 0, nblocks = 1, block = 0;
   int muf = 1, opt = AMP_OPT_SGD, tiles = 1;
+  int seg = 0, segp = 0;    // column segments of the LDS layout (0 = one unpadded segment)
+  int cl() const { return seg ? (cols / seg) * segp : cols; }
   amp_opt_params op{0.1f, 0.9f, 0.9f, 0.999f, 1e-8f};
   std::vector<float> params;
   bool dirty = true;        // host copy newer than device copy
@@ -44,6 +46,7 @@ struct InstSet {
   std::vector<uint64_t> keys;
   std::vector<float> x, target;
   std::vector<int> tok_off{0}, tok, lab_off{0}, lab, node_off{0}, left, right, parent, edge_off{0}, src, dst, etype, tcount;
+  std::vector<int> tnode;   // tree: left, right, parent code, label per node
   bool dirty = true;
   size_t n() const { return keys.size(); }
   void clear() { *this = InstSet(); }
@@ -66,7 +69,7 @@ struct amp_ctx {
   InstSet sets[2];
   // arena layout
   size_t static_end = 0;   // everything below is laid out at finalize
-  size_t off_dev = 0, off_ctl = 0, off_slot_seq = 0, off_clock = 0;
+  size_t off_dev = 0, off_ctl = 0, off_slot_seq = 0, off_clock = 0, off_smeta = 0;
   std::vector<size_t> off_ring_ent, off_ring_tail;
   unsigned ring_cap = 0;
   size_t off_buf[AMP_MAX_BUFS] = {0};
@@ -138,7 +141,7 @@ size_t r4(size_t n) { return (n + 3) & ~(size_t)3; }
 
 size_t tile_rows(const amp_ctx* c, const HostWorker& w) { return (size_t)c->nodes[w.node].nblocks * w.nu; }
 size_t pend_stride(const amp_ctx* c, const HostWorker& w) {
-  return (size_t)amp_round16((int)tile_rows(c, w)) + (size_t)amp_round16(c->nodes[w.node].cols);
+  return (size_t)amp_round16((int)tile_rows(c, w)) + (size_t)amp_round16(c->nodes[w.node].cl());
 }
 // Rows one gradient message can carry (grouped rows of the graph model).
 size_t rows_per_message(const amp_ctx* c, const HostWorker& w) {
@@ -154,27 +157,31 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
   w.kb = 1;
   if (w.role == ROLE_CTRL) return r4(c->max_mak);
   if (w.role == ROLE_TREE_LOOKUP) {
-    w.kb = 32;
+    w.kb = 64;
     return r4(c->max_mak) + AMP_TREE_LOOKUP_MAX_MUF;
   }
   if (w.role == ROLE_G_LOOKUP) return r4((size_t)c->dims.n_node_types * c->dims.hidden);
   const HostNode& n = c->nodes[w.node];
-  const size_t R = tile_rows(c, w), C = n.cols, Rp = amp_round16((int)R), ldw = amp_ldrow((int)C);
+  const size_t R = tile_rows(c, w), C = n.cols, Rp = amp_round16((int)R), ldw = amp_ldrow(n.cl());
   const size_t stride = pend_stride(c, w), wfl = r4(Rp * ldw) + r4(Rp);
   if (R > AMP_THREADS) return 0;
   size_t f = 0;
   switch (w.role) {
     case ROLE_TREE_LEAF:
     case ROLE_TREE_BRANCH: {
-      const size_t ldx = amp_ldrow((int)C), ldy = amp_ldrow((int)R);
-      w.kb = 16;
-      f = wfl + r4(std::max(16 * ldx, UPD_STAGE_HOST * stride)) + r4(16 * ldy);
+      // the largest batch (a multiple of 16 messages) whose pre-activation rows fit beside the weights
+      const size_t ldy = amp_ldrow((int)R);
+      for (w.kb = 64; w.kb >= 16; w.kb -= 16) {
+        f = wfl + r4(std::max((size_t)w.kb * ldy, UPD_STAGE_HOST * stride));
+        if (f <= avail) break;
+      }
+      if (w.kb < 16) return 0;
       break;
     }
     case ROLE_TREE_OUT: {
       const size_t NW = AMP_THREADS / 64;
-      w.kb = 32;
-      f = wfl + r4(NW * C) + r4(NW * 64) + r4(UPD_STAGE_HOST * stride) + r4(c->max_mak);
+      w.kb = 64;
+      f = wfl + r4((size_t)w.kb * amp_round4(c->dims.hidden)) + r4(NW * 64) + r4(UPD_STAGE_HOST * stride) + r4(c->max_mak);
       break;
     }
     case ROLE_G_EDGE: {
@@ -250,6 +257,10 @@ int amp_build_treelstm(amp_ctx* c, const amp_model_dims* d) {
               make_node("branch", 5 * d->hidden, 2 * d->hidden, 1, 5), make_node("out", d->n_class, d->hidden, 1)};
   c->nodes[1].tiles = 5;
   c->nodes[2].tiles = 8;
+  c->nodes[1].seg = d->emb;
+  c->nodes[1].segp = amp_round4(d->emb);
+  c->nodes[2].seg = d->hidden;
+  c->nodes[2].segp = amp_round4(d->hidden);
   return AMP_OK;
 }
 
@@ -373,6 +384,7 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
   c->off_ctl = take(64);
   c->off_clock = take(64);
   c->off_slot_seq = take(sizeof(unsigned) * c->max_mak);
+  c->off_smeta = take(16 * (size_t)c->max_mak);
   const size_t per_inst_msgs = 4 * (size_t)NN + 8;
   c->ring_cap = next_pow2(per_inst_msgs * c->max_mak);
   c->off_ring_ent.assign(nrings, 0);
@@ -409,15 +421,15 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     buf(1, (size_t)c->max_len * c->dims.emb);
     buf(2, H);
   } else if (c->model == AMP_MODEL_TREE) {
-    const size_t L = c->max_len, N2 = 2 * L - 1, E = c->dims.emb;
+    const size_t L = c->max_len, N2 = 2 * L - 1, E = c->dims.emb, Ep = amp_round4(c->dims.emb), Hp = amp_round4(c->dims.hidden);
     const size_t TL = c->nodes[1].tiles, TB = c->nodes[2].tiles;
-    buf(0, L * E);
-    buf(1, N2 * 2 * H);
+    buf(0, L * Ep);
+    buf(1, N2 * 2 * Hp);
     buf(2, N2 * 6 * H);
     buf(3, N2 * H);
-    buf(4, N2 * TB * H);
+    buf(4, N2 * TB * Hp);
     buf(5, N2 * H);
-    buf(6, L * TL * E);
+    buf(6, L * TL * Ep);
     buf(7, N2 * 4);
     c->buf_stride[10] = 0;
     c->buf_bytes[10] = 4 * (size_t)AMP_TREE_LOOKUP_MAX_MUF;
@@ -598,6 +610,8 @@ int amp_submit(amp_ctx* c, int which, uint64_t key, const amp_instance* in) {
         S.left.push_back(n < L ? -1 : in->left[n]);
         S.right.push_back(n < L ? -1 : in->right[n]);
         S.parent.push_back(par[n]);
+        const int tn[4] = {n < L ? -1 : in->left[n], n < L ? -1 : in->right[n], par[n], in->labels[n]};
+        S.tnode.insert(S.tnode.end(), tn, tn + 4);
       }
       break;
     }
@@ -735,6 +749,7 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   if ((r = upload(c, off, S.dst, (const void**)&dd.dst))) return r;
   if ((r = upload(c, off, S.etype, (const void**)&dd.etype))) return r;
   if ((r = upload(c, off, S.tcount, (const void**)&dd.tcount))) return r;
+  if ((r = upload(c, off, S.tnode, (const void**)&dd.tnode))) return r;
   auto take = [&](size_t bytes) -> size_t {
     size_t o = off;
     off = align_up(off + bytes);
@@ -779,6 +794,8 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
     nd.b1 = n.op.beta1;
     nd.b2 = n.op.beta2;
     nd.eps = n.op.eps;
+    nd.seg = n.seg ? n.seg : n.cols;
+    nd.segp = n.seg ? n.segp : n.cols;
   }
   for (size_t i = 0; i < c->workers.size(); ++i) {
     const HostWorker& w = c->workers[i];
@@ -822,6 +839,7 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   D.first_seq = train ? c->total_admitted : 0;
   D.ctl = (unsigned*)(c->arena + c->off_ctl);
   D.slot_seq = (unsigned*)(c->arena + c->off_slot_seq);
+  D.smeta = (int*)(c->arena + c->off_smeta);
   D.loss_out = (float*)(c->arena + off_loss);
   D.correct_out = (int*)(c->arena + off_correct);
   D.yhat_out = (float*)(c->arena + off_yhat);

@@ -3,50 +3,36 @@
 //
 // Leaf and branch cells are split over several workgroups ("tiles", Section
 // 5.1); the tiles of a cell read the same ring in the same order and cut
-// their batches at the same places, so they act as one node with one event
+// their batches at the same updates, so they act as one node with one event
 // order.  Tile t owns hidden units [u0, u0+nu) of every gate, computes those
 // units' h and c entirely, and contributes a partial W^T delta over all
 // input columns on the way back.
 //
-// Slot storage (s = slot, n = tree node, l = leaf):
-//   buf[0] xin  [s][l][D]        embedding recorded by the lookup's forward
-//   buf[1] hc   [s][n][2H]       node output: h then c
-//   buf[2] gate [s][n][6H]       gate activations and tanh(c) recorded at forward
+// A worker takes up to 64 waiting messages at once.  The inputs of the
+// forward product go from the slot storage in HBM straight into the matrix
+// cores' operand registers (rows there are padded to multiples of 4 floats so
+// that every 16-byte fetch is aligned); the input gradient goes from the
+// accumulators straight back to HBM.
+//
+// Slot storage (s = slot, n = tree node, l = leaf; Hp, Ep = H, E rounded up to 4;
+// padding entries stay zero):
+//   buf[0] xin  [s][l][Ep]       embedding recorded by the lookup's forward
+//   buf[1] hc   [s][n][2][Hp]    node output: h then c
+//   buf[2] gate [s][n][6][H]     gate activations and tanh(c) recorded at forward
 //   buf[3] gout [s][n][H]        dh from the output layer
-//   buf[4] gpar [s][n][TB][H]    dh partials from the parent's tiles
+//   buf[4] gpar [s][n][TB][Hp]   dh partials from the parent's tiles
 //   buf[5] gc   [s][n][H]        dc from the parent
-//   buf[6] gx   [s][l][TL][D]    dx partials from the leaf tiles
+//   buf[6] gx   [s][l][TL][Ep]   dx partials from the leaf tiles
 //   buf[7] cnt  [s][n][4] (int)  arrival counters: tiles done / children done /
 //                                gradient parts / leaf-tile dx parts
 //   buf[10] lookup: tokens of the gradients waiting for the next update
-//   buf[11] lookup: their gradient rows [AMP_TREE_LOOKUP_MAX_MUF][D]
+//   buf[11] lookup: their gradient rows [AMP_TREE_LOOKUP_MAX_MUF][E]
 #pragma once
-
-struct TreeView {
-  int inst, L, NN, toff, noff, loff;
-  const int *left, *right, *parent, *tok, *lab;
-};
-
-__device__ __forceinline__ TreeView tree_view(const AmpDev* D, unsigned seq) {
-  TreeView v;
-  v.inst = seq % D->data.n_inst;
-  v.toff = D->data.tok_off[v.inst];
-  v.L = D->data.tok_off[v.inst + 1] - v.toff;
-  v.NN = 2 * v.L - 1;
-  v.noff = D->data.node_off[v.inst];
-  v.loff = D->data.lab_off[v.inst];
-  v.left = D->data.left + v.noff;
-  v.right = D->data.right + v.noff;
-  v.parent = D->data.parent + v.noff;
-  v.tok = D->data.tok + v.toff;
-  v.lab = D->data.lab + v.loff;
-  return v;
-}
 
 struct TreeBufs {
   float *xin, *hc, *gate, *gout, *gpar, *gc, *gx;
   int* cnt;
-  int H, D, NNmax, Lmax, TL, TB;
+  int H, Hp, E, Ep, NNmax, Lmax, TL, TB;
   __device__ __forceinline__ long long node(int s, int n) const { return (long long)s * NNmax + n; }
   __device__ __forceinline__ long long leaf(int s, int l) const { return (long long)s * Lmax + l; }
 };
@@ -62,7 +48,9 @@ __device__ __forceinline__ TreeBufs tree_bufs(const AmpDev* D) {
   b.gx = (float*)D->buf[6];
   b.cnt = (int*)D->buf[7];
   b.H = D->hidden;
-  b.D = D->emb;
+  b.Hp = amp_round4(D->hidden);
+  b.E = D->emb;
+  b.Ep = amp_round4(D->emb);
   b.Lmax = D->max_len;
   b.NNmax = 2 * D->max_len - 1;
   b.TL = D->tiles_leaf;
@@ -77,6 +65,49 @@ __device__ __forceinline__ TreeBufs tree_bufs(const AmpDev* D) {
 #define TR_OUT 4
 
 __device__ __forceinline__ bool code_is_b(unsigned c) { return (c & MSG_DIR_B) != 0; }
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// What the controller wrote for slot s at admission: admission number, leaves, node offset, token offset.
+__device__ __forceinline__ v4i tree_slot(const AmpDev* D, int s) { return *(const v4i*)(D->smeta + 4 * s); }
+// left, right, parent * 2 + side (-1 for the root), label of node n of the instance whose nodes start at noff
+__device__ __forceinline__ v4i tree_node(const AmpDev* D, int noff, int n) {
+  return *(const v4i*)(D->data.tnode + 4 * (long long)(noff + n));
+}
+
+// Wave 0, all 64 lanes, after lanes k < n have written M.aux[k]: positions of
+// the batch's forward and backward messages, and the event record (tile 0 only).
+__device__ __forceinline__ void batch_split_and_log(const AmpDev* D, const WorkerDev* W, BatchMsg& M, int n, int node,
+                                                    bool both_kinds) {
+  const int k = threadIdx.x;   // < 64
+  const bool in = k < n, isb = in && M.aux[k] != 0;
+  const unsigned long long mb = __ballot(isb), mf = __ballot(in && !isb);
+  const unsigned long long lt = (1ull << k) - 1ull;
+  if (isb) M.bidx[__popcll(mb & lt)] = k;
+  if (in && !isb) M.fidx[__popcll(mf & lt)] = k;
+  if (k == 0) {
+    M.nF = __popcll(mf);
+    M.nB = __popcll(mb);
+  }
+  if (W->log_cap && W->tile == 0) {
+    // both_kinds: every message is a forward event followed by a backward event (output layer in training)
+    const unsigned per = both_kinds ? 2u : 1u, base = s_logn;
+    if (base + per * (unsigned)n > W->log_cap) {
+      if (k == 0) raise_abort(D, ABORT_LOG_FULL, blockIdx.x);
+    } else {
+      if (in) {
+        const unsigned long long tail = ((unsigned long long)M.seq[k] << 32) | ((unsigned)node << 20) | ((unsigned)M.n[k] & 0xfffffu);
+        if (both_kinds) {
+          W->log[base + 2 * k] = tail;
+          W->log[base + 2 * k + 1] = tail | (1ull << 28);
+        } else {
+          W->log[base + k] = tail | ((unsigned long long)(isb ? 1 : 0) << 28);
+        }
+      }
+      if (k == 0) s_logn = base + per * (unsigned)n;
+    }
+  }
+}
 
 // A tile has finished its units of node n: when all tiles have, the node's
 // [h; c] goes to the output layer and, through Isu / Concat, to its parent,
@@ -99,13 +130,11 @@ __device__ __forceinline__ void tree_grad_part_done(const AmpDev* D, const TreeB
 }
 
 // ------------------------------------------------------------ lookup
-// Thread c owns column c of every row it touches, so the messages of a batch
-// need no barriers between them.
 __device__ __noinline__ void role_tree_lookup(const AmpDev* D, const WorkerDev* W) {
   float* lds = amp_lds;
   const NodeDev& lk = D->node[0];
   const TreeBufs B = tree_bufs(D);
-  const int E = B.D, KB = W->kb;
+  const int E = B.E, Ep = B.Ep, KB = W->kb, E4 = E >> 2;
   int* left_cnt = (int*)lds;                  // [mak] leaves not yet answered
   int* pend_tok = left_cnt + ((D->mak + 3) & ~3);
   for (int i = threadIdx.x; i < D->mak; i += AMP_THREADS) left_cnt[i] = 0;
@@ -120,58 +149,56 @@ __device__ __noinline__ void role_tree_lookup(const AmpDev* D, const WorkerDev* 
   for (;;) {
     const int n = wait_batch(D, mine, head, KB, lk.muf - (int)count, s_codes, &s_n, code_is_b);
     if (n == 0) break;
-    if ((int)threadIdx.x < n) {
+    if (threadIdx.x < 64) {
       const int k = threadIdx.x;
-      const unsigned code = s_codes[k];
-      const int s = MSG_SLOT(code), l = MSG_LOCAL(code);
-      const unsigned seq = D->slot_seq[s];
-      const TreeView v = tree_view(D, seq);
-      M.s[k] = s;
-      M.n[k] = l;
-      M.seq[k] = seq;
-      M.a[k] = v.tok[l];
-      M.aux[k] = code_is_b(code);
-      if (!code_is_b(code) && l == 0) left_cnt[s] = v.L;
+      if (k < n) {
+        const unsigned code = s_codes[k];
+        const int s = MSG_SLOT(code), l = MSG_LOCAL(code);
+        const v4i sm = tree_slot(D, s);
+        M.s[k] = s;
+        M.n[k] = l;
+        M.seq[k] = (unsigned)sm.x;
+        M.a[k] = D->data.tok[sm.w + l];
+        M.aux[k] = code_is_b(code);
+        if (!code_is_b(code) && l == 0) left_cnt[s] = sm.y;
+      }
+      batch_split_and_log(D, W, M, n, 0, false);
+      // backward message k is the b-th gradient of the batch: remember its token
+      const bool isb = k < n && M.aux[k] != 0;
+      const unsigned long long mb = __ballot(isb);
+      if (isb) {
+        const int b = __popcll(mb & ((1ull << k) - 1ull));
+        M.b[k] = b;
+        pend_tok[count + b] = M.a[k];
+      }
     }
     __syncthreads();
-    // ordinal of each backward message inside the batch
-    if (threadIdx.x == 0) {
-      int nb = 0;
-      for (int k = 0; k < n; ++k) {
-        M.b[k] = nb;
-        if (M.aux[k]) pend_tok[count + nb++] = M.a[k];
-      }
-      M.nB = nb;
-    }
-    __syncthreads();
-    for (int c = threadIdx.x; c < E; c += AMP_THREADS) {
-      float v[KB_MAX];
-#pragma unroll
-      for (int k = 0; k < KB_MAX; ++k) {
-        v[k] = 0.f;
-        if (k < n) {
-          if (!M.aux[k]) {
-            v[k] = lk.P[(long long)M.a[k] * E + c];
-          } else {
-            const float* gx = B.gx + B.leaf(M.s[k], M.n[k]) * B.TL * E + c;
-            float a = 0.f;
-            for (int t = 0; t < B.TL; ++t) a += gx[t * E];
-            v[k] = a;
-          }
+    if ((E & 3) == 0) {
+      // forward: table row -> xin; backward: sum of the leaf tiles' partials -> pending gradient row
+      for (int idx = threadIdx.x; idx < n * E4; idx += AMP_THREADS) {
+        const int k = idx / E4, c = (idx - k * E4) << 2;
+        if (!M.aux[k]) {
+          *(v4f*)(B.xin + B.leaf(M.s[k], M.n[k]) * Ep + c) = *(const v4f*)(lk.P + (long long)M.a[k] * E + c);
+        } else {
+          const float* gx = B.gx + B.leaf(M.s[k], M.n[k]) * B.TL * Ep + c;
+          v4f a = {0.f, 0.f, 0.f, 0.f};
+          for (int t = 0; t < B.TL; ++t) a += *(const v4f*)(gx + t * Ep);
+          *(v4f*)(prow + (long long)(count + M.b[k]) * E + c) = a;
         }
       }
-#pragma unroll
-      for (int k = 0; k < KB_MAX; ++k) {
-        if (k < n) {
-          if (!M.aux[k])
-            B.xin[B.leaf(M.s[k], M.n[k]) * E + c] = v[k];
-          else
-            prow[(long long)(count + M.b[k]) * E + c] = v[k];
+    } else {
+      for (int idx = threadIdx.x; idx < n * E; idx += AMP_THREADS) {
+        const int k = idx / E, c = idx - k * E;
+        if (!M.aux[k]) {
+          B.xin[B.leaf(M.s[k], M.n[k]) * Ep + c] = lk.P[(long long)M.a[k] * E + c];
+        } else {
+          const float* gx = B.gx + B.leaf(M.s[k], M.n[k]) * B.TL * Ep + c;
+          float a = 0.f;
+          for (int t = 0; t < B.TL; ++t) a += gx[t * Ep];
+          prow[(long long)(count + M.b[k]) * E + c] = a;
         }
       }
     }
-    if (threadIdx.x == 0 && W->log_cap)
-      for (int k = 0; k < n; ++k) log_event(D, W, &s_logn, 0, M.aux[k], M.seq[k], M.n[k]);
     __syncthreads();
     if (threadIdx.x < 64) {
       fence_release();
@@ -229,6 +256,94 @@ __device__ __noinline__ void role_tree_lookup(const AmpDev* D, const WorkerDev* 
   for (unsigned k = threadIdx.x; k < count; k += AMP_THREADS) keep[k] = pend_tok[k];
 }
 
+// ------------------------------------------------------------ matrix-core products of a cell tile
+// Y[j][r] = b[r] + sum_c W[r][c] x_j[c] for the nF forward messages of the batch.
+// Wave item = (16 messages, 16 weight rows); the messages' inputs are fetched
+// from HBM (xbase + M.off0 / off1 for the first / second column segment)
+// eight 16-column groups ahead of their use.
+template <bool BR>
+__device__ __forceinline__ void tree_fwd_mfma(const LDSQ float* Wl, const Tile& t, const LDSQ float* bl, const float* xbase,
+                                              const BatchMsg& M, int nF, LDSQ float* Y, int ldy) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  const int NRB = t.Rp >> 4, NCG = amp_round16(t.Cl) >> 4, NBF = (nF + 15) >> 4;
+  const v4f zero = {0.f, 0.f, 0.f, 0.f};
+  for (int item = wave; item < NBF * NRB; item += AMP_THREADS / 64) {
+    const int rb = item % NRB, nb = item / NRB;
+    int mi = nb * 16 + i;
+    if (mi > nF - 1) mi = nF - 1;   // rows beyond the batch repeat its last message; their results are dropped
+    const int m = M.fidx[mi];
+    const float* p0 = xbase + M.off0[m] + 4 * q;
+    const float* p1 = xbase + M.off1[m] + 4 * q - t.segp;
+    const LDSQ float* wp = Wl + (rb * 16 + i) * t.ldw + 4 * q;
+    auto fetch = [&](int kg) -> v4f {
+      const int lc = kg * 16 + 4 * q;
+      if (lc >= t.Cl) return zero;
+      return *(const v4f*)((BR && lc >= t.segp ? p1 : p0) + kg * 16);
+    };
+    v4f acc0 = zero, acc1 = zero, xa[8], xb[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) xa[j] = fetch(j);
+    for (int kc = 0; kc < NCG; kc += 16) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) xb[j] = fetch(kc + 8 + j);
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (kc + j < NCG) {
+          const v4f w = *(const LDSQ v4f*)(wp + 16 * (kc + j));
+          acc0 = MFMA(w.x, xa[j].x, acc0);
+          acc1 = MFMA(w.y, xa[j].y, acc1);
+          acc0 = MFMA(w.z, xa[j].z, acc0);
+          acc1 = MFMA(w.w, xa[j].w, acc1);
+        }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) xa[j] = fetch(kc + 16 + j);
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (kc + 8 + j < NCG) {
+          const v4f w = *(const LDSQ v4f*)(wp + 16 * (kc + 8 + j));
+          acc0 = MFMA(w.x, xb[j].x, acc0);
+          acc1 = MFMA(w.y, xb[j].y, acc1);
+          acc0 = MFMA(w.z, xb[j].z, acc0);
+          acc1 = MFMA(w.w, xb[j].w, acc1);
+        }
+    }
+    const v4f b4 = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
+    *(LDSQ v4f*)(Y + (nb * 16 + i) * ldy + rb * 16 + 4 * q) = acc0 + acc1 + b4;
+  }
+}
+
+// dx_j[c] = sum_r W[r][c] delta_j[r] for the nB backward messages; delta rows
+// in LDS (Dl, stride ldd, zero beyond the tile's rows); the result goes from
+// the accumulators to HBM at obase + M.dst0 / dst1 (+ column inside the segment).
+template <bool BR>
+__device__ __forceinline__ void tree_bwd_mfma(const LDSQ float* Wl, const Tile& t, const LDSQ float* Dl, int ldd,
+                                              const BatchMsg& M, int nB, float* obase) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  const int NRB = t.Rp >> 4, NCG = amp_round16(t.Cl) >> 4, NBB = (nB + 15) >> 4;
+  const v4f zero = {0.f, 0.f, 0.f, 0.f};
+  for (int item = wave; item < NCG * NBB; item += AMP_THREADS / 64) {
+    const int cb = item % NCG, nb = item / NCG;
+    const LDSQ float* wp = Wl + (4 * q) * t.ldw + cb * 16 + i;
+    const LDSQ float* dp = Dl + (nb * 16 + i) * ldd + 4 * q;
+    v4f acc0 = zero, acc1 = zero;
+    for (int g = 0; g < NRB; ++g) {
+      const v4f d0 = *(const LDSQ v4f*)(dp + 16 * g);
+      const LDSQ float* w = wp + 16 * g * t.ldw;
+      const float w0 = w[0], w1 = w[t.ldw], w2 = w[2 * t.ldw], w3 = w[3 * t.ldw];
+      acc0 = MFMA(w0, d0.x, acc0);
+      acc1 = MFMA(w1, d0.y, acc1);
+      acc0 = MFMA(w2, d0.z, acc0);
+      acc1 = MFMA(w3, d0.w, acc1);
+    }
+    const int mi = nb * 16 + i, lc = cb * 16 + 4 * q;
+    if (mi < nB && lc < t.Cl) {
+      const int m = M.bidx[mi];
+      float* o = (BR && lc >= t.segp) ? obase + M.dst1[m] + (lc - t.segp) : obase + M.dst0[m] + lc;
+      *(v4f*)o = acc0 + acc1;
+    }
+  }
+}
+
 // ------------------------------------------------------------ leaf / branch cells
 // BR = false: rows [i; o; u] over the embedding.
 // BR = true : rows [i; f_l; f_r; o; u] over [h_l; h_r].
@@ -239,82 +354,70 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
   const Tile t = make_tile(nd, W);
   const TreeBufs B = tree_bufs(D);
   const Pend pd = make_pend(W, t);
-  const int R = t.R, C = t.C, H = B.H, nu = t.nu, u0 = t.u0, KB = W->kb;
-  const int ldx = amp_ldrow(C), ldy = amp_ldrow(R), NRB = t.Rp >> 4, NCG = amp_round16(C) >> 4;
+  const int R = t.R, H = B.H, Hp = B.Hp, nu = t.nu, u0 = t.u0, KB = W->kb;
+  const int ldy = amp_ldrow(R);
   Lds L{lds};
   float* Wl = L.take(t.Rp * t.ldw);
   float* bl = L.take(t.Rp);
-  const int xfloats = 16 * ldx > UPD_STAGE * pd.stride ? 16 * ldx : UPD_STAGE * pd.stride;
-  float* X = L.take(xfloats);
-  float* Y = L.take(16 * ldy);
+  const int yfloats = KB * ldy > UPD_STAGE * pd.stride ? KB * ldy : UPD_STAGE * pd.stride;
+  float* Y = L.take(yfloats);   // forward: pre-activations; backward: deltas; staging at updates
   tile_load(nd, t, Wl, bl);
-  for (int i = threadIdx.x; i < xfloats; i += AMP_THREADS) X[i] = 0.f;
-  for (int i = threadIdx.x; i < 16 * ldy; i += AMP_THREADS) Y[i] = 0.f;
+  for (int i = threadIdx.x; i < yfloats; i += AMP_THREADS) Y[i] = 0.f;
   BatchMsg& M = s_M;
   __syncthreads();
   const RingDev& mine = D->ring[W->ring];
+  const float* xbase = BR ? B.hc : B.xin;
+  float* obase = BR ? B.gpar : B.gx;
   unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   for (;;) {
     const int n = wait_batch(D, mine, head, KB, nd.muf - (int)count, s_codes, &s_n, code_is_b);
     if (n == 0) break;
-    if ((int)threadIdx.x < n) {
+    if (threadIdx.x < 64) {
       const int k = threadIdx.x;
-      const unsigned code = s_codes[k];
-      const int s = MSG_SLOT(code), nn = MSG_LOCAL(code);
-      const unsigned seq = D->slot_seq[s];
-      const TreeView v = tree_view(D, seq);
-      M.s[k] = s;
-      M.n[k] = nn;
-      M.seq[k] = seq;
-      M.a[k] = BR ? v.left[nn] : 0;
-      M.b[k] = BR ? v.right[nn] : 0;
-      M.par[k] = v.parent[nn];
-      M.L[k] = v.L;
-      M.aux[k] = code_is_b(code);
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      int nf = 0, nb = 0;
-      for (int k = 0; k < n; ++k) {
-        if (M.aux[k])
-          M.bidx[nb++] = k;
-        else
-          M.fidx[nf++] = k;
-        if (W->tile == 0) log_event(D, W, &s_logn, W->node, M.aux[k], M.seq[k], M.n[k]);
+      if (k < n) {
+        const unsigned code = s_codes[k];
+        const int s = MSG_SLOT(code), nn = MSG_LOCAL(code);
+        const v4i sm = tree_slot(D, s);
+        const v4i tn = tree_node(D, sm.z, nn);
+        M.s[k] = s;
+        M.n[k] = nn;
+        M.seq[k] = (unsigned)sm.x;
+        M.a[k] = tn.x;
+        M.b[k] = tn.y;
+        M.par[k] = tn.z;
+        M.L[k] = sm.y;
+        M.aux[k] = code_is_b(code);
+        if (BR) {
+          M.off0[k] = (int)(B.node(s, tn.x) * 2 * Hp);
+          M.off1[k] = (int)(B.node(s, tn.y) * 2 * Hp);
+          M.dst0[k] = (int)((B.node(s, tn.x) * B.TB + W->tile) * Hp);
+          M.dst1[k] = (int)((B.node(s, tn.y) * B.TB + W->tile) * Hp);
+        } else {
+          M.off0[k] = M.off1[k] = (int)(B.leaf(s, nn) * B.Ep);
+          M.dst0[k] = M.dst1[k] = (int)((B.leaf(s, nn) * B.TL + W->tile) * B.Ep);
+        }
       }
-      M.nF = nf;
-      M.nB = nb;
+      batch_split_and_log(D, W, M, n, W->node, false);
     }
     __syncthreads();
     const int nF = M.nF, nB = M.nB;
     PHASE(0);
     // ---------------- forward messages of the batch
     if (nF > 0) {
-      for (int i = threadIdx.x; i < nF * ldx; i += AMP_THREADS) {
-        const int k = i / ldx, c = i - k * ldx, m = M.fidx[k];
-        float v = 0.f;   // padding columns of a used row are zero
-        if (c < C) {
-          if (BR)
-            v = c < H ? B.hc[B.node(M.s[m], M.a[m]) * 2 * H + c] : B.hc[B.node(M.s[m], M.b[m]) * 2 * H + c - H];
-          else
-            v = B.xin[B.leaf(M.s[m], M.n[m]) * C + c];
-        }
-        X[i] = v;
-      }
+      tree_fwd_mfma<BR>((const LDSQ float*)Wl, t, (const LDSQ float*)bl, xbase, M, nF, (LDSQ float*)Y, ldy);
       __syncthreads();
       PHASE(1);
-      mfma_rows((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)bl, (LDSQ float*)X, ldx, 1, (LDSQ float*)Y, ldy);
-      PHASE(2);
       for (int i = threadIdx.x; i < nF * nu; i += AMP_THREADS) {
         const int k = i / nu, j = i - k * nu, m = M.fidx[k], u = u0 + j;
         const float* y = Y + k * ldy;
-        float* hcn = B.hc + B.node(M.s[m], M.n[m]) * 2 * H;
-        float* gt = B.gate + B.node(M.s[m], M.n[m]) * 6 * H;
+        const long long nn = B.node(M.s[m], M.n[m]);
+        float* hcn = B.hc + nn * 2 * Hp;
+        float* gt = B.gate + nn * 6 * H;
         float c_, o_;
         if (BR) {
-          const float cl = B.hc[B.node(M.s[m], M.a[m]) * 2 * H + H + u];
-          const float cr = B.hc[B.node(M.s[m], M.b[m]) * 2 * H + H + u];
+          const float cl = xbase[M.off0[m] + Hp + u];
+          const float cr = xbase[M.off1[m] + Hp + u];
           const float i_ = sigmoidf_(y[j]), fl = sigmoidf_(y[nu + j]), fr = sigmoidf_(y[2 * nu + j]);
           o_ = sigmoidf_(y[3 * nu + j]);
           const float g_ = tanhf(y[4 * nu + j]);
@@ -336,24 +439,14 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
         const float tc = tanhf(c_);
         gt[5 * H + u] = tc;
         hcn[u] = o_ * tc;
-        hcn[H + u] = c_;
+        hcn[Hp + u] = c_;
       }
       __syncthreads();
-      PHASE(3);
+      PHASE(2);
     }
     // ---------------- backward messages of the batch
     if (nB > 0) {
-      for (int i = threadIdx.x; i < nB * ldx; i += AMP_THREADS) {
-        const int k = i / ldx, c = i - k * ldx, m = M.bidx[k];
-        float v = 0.f;   // padding columns of a used row are zero
-        if (c < C) {
-          if (BR)
-            v = c < H ? B.hc[B.node(M.s[m], M.a[m]) * 2 * H + c] : B.hc[B.node(M.s[m], M.b[m]) * 2 * H + c - H];
-          else
-            v = B.xin[B.leaf(M.s[m], M.n[m]) * C + c];
-        }
-        X[i] = v;
-      }
+      // delta rows (tile order [gate][unit], zero beyond R) into Y
       for (int i = threadIdx.x; i < nB * (ldy - R); i += AMP_THREADS) {
         const int k = i / (ldy - R), r = R + i - k * (ldy - R);
         Y[k * ldy + r] = 0.f;
@@ -364,9 +457,9 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
         const float* gt = B.gate + nn * 6 * H;
         float dh = B.gout[nn * H + u], dc = 0.f;
         if (M.par[m] >= 0) {
-          const float* gp = B.gpar + nn * B.TB * H + u;
+          const float* gp = B.gpar + nn * B.TB * Hp + u;
           float p = 0.f;
-          for (int q = 0; q < B.TB; ++q) p += gp[q * H];
+          for (int q = 0; q < B.TB; ++q) p += gp[q * Hp];
           dh += p;
           dc = B.gc[nn * H + u];
         }
@@ -380,8 +473,8 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
           const long long na = B.node(M.s[m], M.a[m]), nb = B.node(M.s[m], M.b[m]);
           const float fl = gt[H + u], fr = gt[2 * H + u];
           ds[j] = d_i;
-          ds[nu + j] = dct * B.hc[na * 2 * H + H + u] * fl * (1.f - fl);
-          ds[2 * nu + j] = dct * B.hc[nb * 2 * H + H + u] * fr * (1.f - fr);
+          ds[nu + j] = dct * xbase[M.off0[m] + Hp + u] * fl * (1.f - fl);
+          ds[2 * nu + j] = dct * xbase[M.off1[m] + Hp + u] * fr * (1.f - fr);
           ds[3 * nu + j] = d_o;
           ds[4 * nu + j] = d_g;
           B.gc[na * H + u] = dct * fl;
@@ -393,24 +486,23 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
         }
       }
       __syncthreads();
-      PHASE(4);
-      pend_append(pd, count, Y, ldy, R, X, ldx, C, nB);
-      __syncthreads();
-      mfma_cols((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)Y, ldy, 1, (LDSQ float*)X, ldx);
-      PHASE(5);
-      for (int i = threadIdx.x; i < nB * C; i += AMP_THREADS) {
-        const int k = i / C, c = i - k * C, m = M.bidx[k];
-        const float v = X[k * ldx + c];
-        if (BR) {
-          if (c < H)
-            B.gpar[(B.node(M.s[m], M.a[m]) * B.TB + W->tile) * H + c] = v;
-          else
-            B.gpar[(B.node(M.s[m], M.b[m]) * B.TB + W->tile) * H + c - H] = v;
+      PHASE(3);
+      // the (delta, input) pairs join the pending gradients: entry = [delta (Rp) | input in LDS column layout (Cp)]
+      for (int i = threadIdx.x; i < nB * (pd.stride >> 2); i += AMP_THREADS) {
+        const int k = i / (pd.stride >> 2), j = (i - k * (pd.stride >> 2)) << 2, m = M.bidx[k];
+        v4f v = {0.f, 0.f, 0.f, 0.f};
+        if (j < pd.Rp) {
+          if (j < ldy) v = *(const v4f*)(Y + k * ldy + j);   // ldy >= R, zero beyond R
         } else {
-          B.gx[(B.leaf(M.s[m], M.n[m]) * B.TL + W->tile) * C + c] = v;
+          const int lc = j - pd.Rp;
+          if (lc < t.Cl) v = *(const v4f*)(xbase + ((BR && lc >= t.segp) ? M.off1[m] + lc - t.segp : M.off0[m] + lc));
         }
+        *(v4f*)(pd.base + (long long)(count + k) * pd.stride + j) = v;
       }
+      PHASE(4);
+      tree_bwd_mfma<BR>((const LDSQ float*)Wl, t, (const LDSQ float*)Y, ldy, M, nB, obase);
       __syncthreads();
+      PHASE(5);
     }
     // ---------------- joins and posts, one lane per message
     if (threadIdx.x < 64) {
@@ -432,7 +524,7 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
     count += nB;
     if ((int)count >= nd.muf) {
       tstep++;
-      mfma_update((LDSQ float*)Wl, (LDSQ float*)bl, &nd, t, pd.base, pd.stride, count, count, tstep, (LDSQ float*)X);
+      mfma_update((LDSQ float*)Wl, (LDSQ float*)bl, &nd, t, pd.base, pd.stride, count, count, tstep, (LDSQ float*)Y);
       count = 0;
       LOG(W->node, 2, 0, 0);
     }
@@ -447,20 +539,23 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
 }
 
 // ------------------------------------------------------------ output layer + loss at every node
-// One wave per message: forward, softmax loss and backward in one event.
+// The node where a forward message turns round (Section 4: the loss layer
+// initiates backpropagation).  The batch's h vectors are fetched into LDS
+// together; then one wave per message: logits, loss, d logits, W^T d logits,
+// and the (d logits, h) pair joins the node's pending gradients.
 __device__ __noinline__ void role_tree_out(const AmpDev* D, const WorkerDev* W) {
   float* lds = amp_lds;
   const NodeDev& nd = D->node[3];
   const Tile t = make_tile(nd, W);
   const TreeBufs B = tree_bufs(D);
   const Pend pd = make_pend(W, t);
-  const int R = t.R, C = t.C, H = B.H, KB = W->kb;
+  const int R = t.R, C = t.C, H = B.H, Hp = B.Hp, KB = W->kb;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, NW = AMP_THREADS >> 6;
   Lds L{lds};
   float* Wl = L.take(t.Rp * t.ldw);
   float* bl = L.take(t.Rp);
-  float* hbuf = L.take(NW * C);            // per wave: the node's h
-  float* zbuf = L.take(NW * 64);           // per wave: logits, then dz
+  float* hbuf = L.take(KB * Hp);           // per message: the node's h
+  float* zbuf = L.take(NW * 64);           // per wave: d logits
   float* stage = L.take(UPD_STAGE * pd.stride);
   int* done_cnt = (int*)L.take(D->mak);    // eval: nodes scored per slot
   tile_load(nd, t, Wl, bl);
@@ -474,26 +569,34 @@ __device__ __noinline__ void role_tree_out(const AmpDev* D, const WorkerDev* W) 
     const int room = D->train ? nd.muf - (int)count : KB_MAX;
     const int n = wait_batch(D, mine, head, KB, room, s_codes, &s_n, [](unsigned) { return true; });
     if (n == 0) break;
-    if ((int)threadIdx.x < n) {
+    if (threadIdx.x < 64) {
       const int k = threadIdx.x;
-      const unsigned code = s_codes[k];
-      const int s = MSG_SLOT(code), nn = MSG_LOCAL(code);
-      const unsigned seq = D->slot_seq[s];
-      const TreeView v = tree_view(D, seq);
-      M.s[k] = s;
-      M.n[k] = nn;
-      M.seq[k] = seq;
-      M.a[k] = v.lab[nn];
-      M.par[k] = v.parent[nn];
-      M.L[k] = v.L;
+      if (k < n) {
+        const unsigned code = s_codes[k];
+        const int s = MSG_SLOT(code), nn = MSG_LOCAL(code);
+        const v4i sm = tree_slot(D, s);
+        const v4i tn = tree_node(D, sm.z, nn);
+        M.s[k] = s;
+        M.n[k] = nn;
+        M.seq[k] = (unsigned)sm.x;
+        M.a[k] = tn.w;
+        M.par[k] = tn.z;
+        M.L[k] = sm.y;
+        M.aux[k] = 0;
+        M.off0[k] = (int)(B.node(s, nn) * 2 * Hp);
+      }
+      batch_split_and_log(D, W, M, n, 3, D->train != 0);
     }
     __syncthreads();
-    float* hw = hbuf + wave * C;
+    for (int idx = threadIdx.x; idx < n * (Hp >> 2); idx += AMP_THREADS) {
+      const int k = idx / (Hp >> 2), c = (idx - k * (Hp >> 2)) << 2;
+      *(v4f*)(hbuf + k * Hp + c) = *(const v4f*)(B.hc + M.off0[k] + c);
+    }
+    __syncthreads();
     float* zw = zbuf + wave * 64;
     for (int k = wave; k < n; k += NW) {
       const int s = M.s[k], nn = M.n[k], label = M.a[k];
-      const float* h = B.hc + B.node(s, nn) * 2 * H;
-      for (int c = lane; c < C; c += 64) hw[c] = h[c];
+      const float* hw = hbuf + k * Hp;
       // logits: lane r keeps z_r
       float zmine = -3.0e38f;
       for (int r = 0; r < R; ++r) {
@@ -517,7 +620,7 @@ __device__ __noinline__ void role_tree_out(const AmpDev* D, const WorkerDev* W) 
       for (int off = 32; off; off >>= 1) se += __shfl_xor(se, off);
       const float zl = __shfl(zmine, label);
       const float dz = e / se - (lane == label ? 1.f : 0.f);
-      if (lane < 64) zw[lane] = lane < R ? dz : 0.f;
+      zw[lane] = lane < R ? dz : 0.f;
       if (lane == 0) {
         const unsigned idx = M.seq[k] - D->first_seq;
         atomicAdd(&D->loss_out[idx], -(zl - m - logf(se)));
@@ -542,11 +645,6 @@ __device__ __noinline__ void role_tree_out(const AmpDev* D, const WorkerDev* W) 
         pe[j] = v;
       }
     }
-    if (threadIdx.x == 0 && W->log_cap)
-      for (int k = 0; k < n; ++k) {
-        log_event(D, W, &s_logn, 3, 0, M.seq[k], M.n[k]);
-        if (D->train) log_event(D, W, &s_logn, 3, 1, M.seq[k], M.n[k]);
-      }
     __syncthreads();
     if (threadIdx.x < 64) {
       fence_release();
