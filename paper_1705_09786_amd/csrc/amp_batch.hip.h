@@ -39,12 +39,12 @@ __shared__ int s_n;
 // (those for which is_b(code) holds) are in it.  Returns the batch size, 0
 // when the run is over.  s_codes / s_n are LDS.
 template <class IsB>
-__device__ __forceinline__ int wait_batch(const AmpDev* D, const RingDev& r, unsigned& head, int kmax, int room, unsigned* s_codes,
+__device__ __forceinline__ int wait_batch(const GQ AmpDev* D, const GQ RingDev& r, unsigned& head, int kmax, int room, unsigned* s_codes,
                           int* s_n, IsB is_b) {
   if (threadIdx.x < 64) {
     const int lane = threadIdx.x;
     const unsigned ticket = head + lane;
-    unsigned long long* slot = &r.ent[ticket & r.mask];
+    GQ unsigned long long* slot = (GQ unsigned long long*)&r.ent[ticket & r.mask];
     const long long t0 = wall_clock64();
     unsigned spins = 0;
     int n = 0;
@@ -102,7 +102,7 @@ __device__ __forceinline__ int wait_batch(const AmpDev* D, const RingDev& r, uns
       s_stat[3] = now;
     }
   }
-  __syncthreads();
+  lds_barrier();
   const int n = *s_n;
   head += n;
   return n;
@@ -119,8 +119,6 @@ __device__ __forceinline__ int wait_batch(const AmpDev* D, const RingDev& r, uns
 //
 // v_mfma_f32_16x16x4_f32: lane l supplies A[l%16][l/16] and B[l/16][l%16] and
 // receives D[4*(l/16)+v][l%16], v = 0..3.  fp32 in, fp32 accumulate.
-typedef float v4f __attribute__((ext_vector_type(4)));
-#define LDSQ __attribute__((address_space(3)))
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x4f32((a), (b), (c), 0, 0, 0)
 
 // Y[j][r] = b[r] + sum_c W[r][c] X[j][c]   (M = weight rows, N = messages, K = columns)
@@ -189,7 +187,7 @@ struct Pend {
   int Rp, Cp, stride;
 };
 
-__device__ __forceinline__ Pend make_pend(const WorkerDev* W, const Tile& t) {
+__device__ __forceinline__ Pend make_pend(const GQ WorkerDev* W, const Tile& t) {
   Pend p;
   p.base = W->pend;
   p.Rp = t.Rp;
@@ -219,11 +217,11 @@ __device__ __forceinline__ void pend_append(const Pend& p, unsigned first, const
 // weights.  `stage` is LDS for UPD_STAGE entries.  Wave w owns tiles w, w+8, ...
 #define UPD_STAGE 8
 #define UPD_TILES 16
-__device__ __noinline__ void mfma_update(LDSQ float* Wl, LDSQ float* bl, const NodeDev* ndp, Tile t, const float* pend,
+__device__ __noinline__ void mfma_update(LDSQ float* Wl, LDSQ float* bl, const GQ NodeDev* ndp, Tile t, const float* pend,
                                          int stride, unsigned n_grad, unsigned count, unsigned tstep,
                                          LDSQ float* stage) {
   // n_grad = gradients (messages) accumulated, count = pending rows (a grouped message has several)
-  const NodeDev& nd = *ndp;
+  const GQ NodeDev& nd = *ndp;
   const OptCoef o = opt_coef(nd, tstep);
   const float inv = nd.mean ? 1.f / (float)n_grad : 1.f;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;

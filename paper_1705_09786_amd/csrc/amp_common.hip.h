@@ -7,36 +7,57 @@
 
 #define AGENT __HIP_MEMORY_SCOPE_AGENT
 
+// Address-space qualifiers.  Pointers read from the device descriptor are
+// generic; a generic access is a FLAT instruction, which occupies both the
+// vector-memory and the LDS counters, so that every later wait for an LDS
+// read also waits for the outstanding HBM traffic.  Hot paths therefore cast
+// HBM pointers to GQ (global) and LDS pointers to LDSQ.
+#define GQ __attribute__((address_space(1)))
+#define LDSQ __attribute__((address_space(3)))
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+
 // The workgroup's dynamic LDS; every role carves its buffers out of it.
 extern __shared__ float amp_lds[];
 
 __device__ __forceinline__ unsigned ld_u32(const unsigned* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, AGENT);
+  return __hip_atomic_load((const GQ unsigned*)p, __ATOMIC_RELAXED, AGENT);
 }
 __device__ __forceinline__ void fence_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
 __device__ __forceinline__ void fence_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
 
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits
+// until every HBM load and store of the wave has completed (a round trip to
+// memory); between phases that hand data over through LDS this one is enough.
+// HBM data written by one wave and read by another wave of the workgroup, or
+// published to other workgroups, still needs __syncthreads().
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // ---------------------------------------------------------------- rings
 // Called by ONE thread, after a release fence that covers the payload.
-__device__ __forceinline__ void ring_post(const RingDev& r, unsigned code) {
-  unsigned t = __hip_atomic_fetch_add(r.tail, 1u, __ATOMIC_RELAXED, AGENT);
+__device__ __forceinline__ void ring_post(const GQ RingDev& r, unsigned code) {
+  unsigned t = __hip_atomic_fetch_add((GQ unsigned*)r.tail, 1u, __ATOMIC_RELAXED, AGENT);
   unsigned long long e = ((unsigned long long)(t + 1u) << 32) | code;
-  __hip_atomic_store(&r.ent[t & r.mask], e, __ATOMIC_RELAXED, AGENT);
+  __hip_atomic_store((GQ unsigned long long*)&r.ent[t & r.mask], e, __ATOMIC_RELAXED, AGENT);
 }
 
 // Reserves n consecutive tickets; entry i is published with ring_put.
-__device__ __forceinline__ unsigned ring_reserve(const RingDev& r, unsigned n) {
-  return __hip_atomic_fetch_add(r.tail, n, __ATOMIC_RELAXED, AGENT);
+__device__ __forceinline__ unsigned ring_reserve(const GQ RingDev& r, unsigned n) {
+  return __hip_atomic_fetch_add((GQ unsigned*)r.tail, n, __ATOMIC_RELAXED, AGENT);
 }
-__device__ __forceinline__ void ring_put(const RingDev& r, unsigned ticket, unsigned code) {
+__device__ __forceinline__ void ring_put(const GQ RingDev& r, unsigned ticket, unsigned code) {
   unsigned long long e = ((unsigned long long)(ticket + 1u) << 32) | code;
-  __hip_atomic_store(&r.ent[ticket & r.mask], e, __ATOMIC_RELAXED, AGENT);
+  __hip_atomic_store((GQ unsigned long long*)&r.ent[ticket & r.mask], e, __ATOMIC_RELAXED, AGENT);
 }
 
-__device__ __forceinline__ void raise_abort(const AmpDev* D, unsigned code, unsigned detail) {
+__device__ __forceinline__ void raise_abort(const GQ AmpDev* D, unsigned code, unsigned detail) {
   unsigned expected = 0;
-  if (__hip_atomic_compare_exchange_strong(&D->ctl[0], &expected, code, __ATOMIC_RELAXED, __ATOMIC_RELAXED, AGENT))
-    __hip_atomic_store(&D->ctl[2], detail, __ATOMIC_RELAXED, AGENT);
+  if (__hip_atomic_compare_exchange_strong((GQ unsigned*)&D->ctl[0], &expected, code, __ATOMIC_RELAXED, __ATOMIC_RELAXED, AGENT))
+    __hip_atomic_store((GQ unsigned*)&D->ctl[2], detail, __ATOMIC_RELAXED, AGENT);
 }
 
 // Per-workgroup utilisation counters: [0] ticks spent waiting for messages, [1] messages taken,
@@ -57,10 +78,10 @@ __shared__ unsigned long long s_stat[AMP_NSTAT];
 // false when the run is over (done flag, abort flag, or this wait exceeded
 // the watchdog, which raises the abort flag so that every workgroup leaves).
 // s_ctl: two words of LDS.
-__device__ __forceinline__ bool wait_msg(const AmpDev* D, const RingDev& r, unsigned& head, unsigned* s_ctl, unsigned& code) {
+__device__ __forceinline__ bool wait_msg(const GQ AmpDev* D, const GQ RingDev& r, unsigned& head, unsigned* s_ctl, unsigned& code) {
   if (threadIdx.x == 0) {
     const unsigned want = head + 1u;
-    unsigned long long* slot = &r.ent[head & r.mask];
+    GQ unsigned long long* slot = (GQ unsigned long long*)&r.ent[head & r.mask];
     const long long t0 = wall_clock64();
     unsigned stop = 0, spins = 0;
     unsigned long long e;
@@ -98,7 +119,7 @@ __device__ __forceinline__ bool wait_msg(const AmpDev* D, const RingDev& r, unsi
 }
 
 // ---------------------------------------------------------------- event record
-__device__ __forceinline__ void log_event(const AmpDev* D, const WorkerDev* W, unsigned* s_logn, int node, int kind,
+__device__ __forceinline__ void log_event(const GQ AmpDev* D, const GQ WorkerDev* W, unsigned* s_logn, int node, int kind,
                                           unsigned seq, unsigned local) {
   if (W->log_cap == 0) return;
   unsigned n = *s_logn;
@@ -204,7 +225,7 @@ struct Tile {
   }
 };
 
-__device__ __forceinline__ Tile make_tile(const NodeDev& nd, const WorkerDev* W) {
+__device__ __forceinline__ Tile make_tile(const GQ NodeDev& nd, const GQ WorkerDev* W) {
   Tile t;
   t.nu = W->nu;
   t.u0 = W->u0;
@@ -221,7 +242,7 @@ __device__ __forceinline__ Tile make_tile(const NodeDev& nd, const WorkerDev* W)
 }
 
 // Wl holds Rp x ldw floats, bl holds Rp; everything outside R x C is zero.
-__device__ __forceinline__ void tile_load(const NodeDev& nd, const Tile& t, float* Wl, float* bl) {
+__device__ __forceinline__ void tile_load(const GQ NodeDev& nd, const Tile& t, float* Wl, float* bl) {
   for (int i = threadIdx.x; i < t.Rp * t.ldw; i += AMP_THREADS) Wl[i] = 0.f;
   for (int i = threadIdx.x; i < t.Rp; i += AMP_THREADS) bl[i] = 0.f;
   __syncthreads();
@@ -234,7 +255,7 @@ __device__ __forceinline__ void tile_load(const NodeDev& nd, const Tile& t, floa
   __syncthreads();
 }
 
-__device__ __forceinline__ void tile_store(const NodeDev& nd, const Tile& t, const float* Wl, const float* bl) {
+__device__ __forceinline__ void tile_store(const GQ NodeDev& nd, const Tile& t, const float* Wl, const float* bl) {
   __syncthreads();
   for (int i = threadIdx.x; i < t.R * t.C; i += AMP_THREADS) {
     const int lr = i / t.C, c = i - lr * t.C;
@@ -245,7 +266,7 @@ __device__ __forceinline__ void tile_store(const NodeDev& nd, const Tile& t, con
 }
 
 // G[row][c] += d[lr] * x[c] over the tile's rows; bias gradient alike.
-__device__ __forceinline__ void tile_accumulate(const NodeDev& nd, const Tile& t, const float* d, const float* x) {
+__device__ __forceinline__ void tile_accumulate(const GQ NodeDev& nd, const Tile& t, const float* d, const float* x) {
   for (int i = threadIdx.x; i < t.R * t.C; i += AMP_THREADS) {
     const int lr = i / t.C, c = i - lr * t.C;
     float* g = nd.G + (long long)t.grow(lr) * t.C + c;
@@ -261,7 +282,7 @@ struct OptCoef {
   int kind;
 };
 
-__device__ __forceinline__ OptCoef opt_coef(const NodeDev& nd, unsigned tstep) {
+__device__ __forceinline__ OptCoef opt_coef(const GQ NodeDev& nd, unsigned tstep) {
   OptCoef o;
   o.kind = nd.opt;
   o.lr = nd.lr;
@@ -277,7 +298,9 @@ __device__ __forceinline__ OptCoef opt_coef(const NodeDev& nd, unsigned tstep) {
   return o;
 }
 
-__device__ __forceinline__ float opt_apply(const OptCoef& o, float w, float g, float* M, float* V, long long gi) {
+__device__ __forceinline__ float opt_apply(const OptCoef& o, float w, float g, float* Mp, float* Vp, long long gi) {
+  GQ float* M = (GQ float*)Mp;
+  GQ float* V = (GQ float*)Vp;
   if (o.kind == 0) return w - o.lr * g;
   if (o.kind == 1) {
     const float m = fmaf(o.mom, M[gi], g);
@@ -294,7 +317,7 @@ __device__ __forceinline__ float opt_apply(const OptCoef& o, float w, float g, f
 // Applies the node's optimizer to the tile with the accumulated gradient
 // (mean over `count` gradients unless the node sums), clears the accumulator.
 // tstep is the 1-based number of this update.
-__device__ __forceinline__ void tile_update(const NodeDev& nd, const Tile& t, float* Wl, float* bl, unsigned count, unsigned tstep) {
+__device__ __forceinline__ void tile_update(const GQ NodeDev& nd, const Tile& t, float* Wl, float* bl, unsigned count, unsigned tstep) {
   __syncthreads();
   const OptCoef o = opt_coef(nd, tstep);
   const float inv = nd.mean ? 1.f / (float)count : 1.f;
@@ -350,12 +373,14 @@ __device__ __forceinline__ void fence_acq_rel() { __builtin_amdgcn_fence(__ATOMI
 // `expect` parts; that caller resets the counter (the slot is not reused
 // before the instance has retired) and may then post.  ONE thread, after a
 // release fence covering its own part.
-__device__ __forceinline__ bool join_arrive(int* counter, int expect) {
+__device__ __forceinline__ bool join_arrive(GQ int* counter, int expect) {
   const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, AGENT);
   if (old + 1 != expect) return false;
   __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, AGENT);
   fence_acq_rel();
   return true;
 }
+
+__device__ __forceinline__ bool join_arrive(int* counter, int expect) { return join_arrive((GQ int*)counter, expect); }
 
 __device__ __forceinline__ float sigmoidf_(float x) { return 1.f / (1.f + expf(-x)); }

@@ -33,7 +33,7 @@ struct GView {
   float target;
 };
 
-__device__ __forceinline__ GView g_view(const AmpDev* D, unsigned seq) {
+__device__ __forceinline__ GView g_view(const GQ AmpDev* D, unsigned seq) {
   GView v;
   v.inst = seq % D->data.n_inst;
   const int to = D->data.tok_off[v.inst], eo = D->data.edge_off[v.inst];
@@ -57,7 +57,7 @@ struct GBufs {
   __device__ __forceinline__ long long sl(int s) const { return (long long)s * N * H; }
 };
 
-__device__ __forceinline__ GBufs g_bufs(const AmpDev* D) {
+__device__ __forceinline__ GBufs g_bufs(const GQ AmpDev* D) {
   GBufs b;
   b.Hm = (float*)D->buf[0];
   b.A = (float*)D->buf[1];
@@ -95,14 +95,14 @@ __device__ __forceinline__ int g_active_types(const GView& v, int T) {
 }
 
 // Sends one message per edge type that occurs in the graph.  ONE thread, after a release fence.
-__device__ __forceinline__ void g_post_edges(const AmpDev* D, const GView& v, int s, int it, bool backward) {
+__device__ __forceinline__ void g_post_edges(const GQ AmpDev* D, const GView& v, int s, int it, bool backward) {
   for (int c = 0; c < D->n_edge_types; ++c)
     if (v.tcount[c] > 0) ring_post(D->ring[GR_EDGE0 + c], MSG_MAKE(backward, s, it));
 }
 
 // Counts one gradient (a grouped message of K rows already appended to the
 // pending list) and updates when min_update_frequency is reached.
-__device__ __forceinline__ void g_count_and_update(const AmpDev* D, const WorkerDev* W, const NodeDev& nd, const Tile& t,
+__device__ __forceinline__ void g_count_and_update(const GQ AmpDev* D, const GQ WorkerDev* W, const GQ NodeDev& nd, const Tile& t,
                                                    float* Wl, float* bl, const Pend& pd, unsigned& count,
                                                    unsigned& nrows, unsigned& tstep, int K, float* stage) {
   count++;
@@ -117,15 +117,15 @@ __device__ __forceinline__ void g_count_and_update(const AmpDev* D, const Worker
 }
 
 // ---------------------------------------------------------------- lookup
-__device__ __noinline__ void role_g_lookup(const AmpDev* D, const WorkerDev* W) {
+__device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
-  const NodeDev& lk = D->node[0];
+  const GQ NodeDev& lk = D->node[0];
   const GBufs B = g_bufs(D);
   const int H = B.H, V = D->n_node_types;
   float* El = lds;
   for (int i = threadIdx.x; i < V * H; i += AMP_THREADS) El[i] = lk.P[i];
   __syncthreads();
-  const RingDev& mine = D->ring[W->ring];
+  const GQ RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   while (wait_msg(D, mine, head, s_ctl, code)) {
@@ -178,9 +178,9 @@ __device__ __noinline__ void role_g_lookup(const AmpDev* D, const WorkerDev* W) 
 }
 
 // ---------------------------------------------------------------- edge linear of type c
-__device__ __noinline__ void role_g_edge(const AmpDev* D, const WorkerDev* W) {
+__device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
-  const NodeDev& nd = D->node[W->node];
+  const GQ NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
   const Pend pd = make_pend(W, t);
@@ -198,7 +198,7 @@ __device__ __noinline__ void role_g_edge(const AmpDev* D, const WorkerDev* W) {
   for (int i = threadIdx.x; i < xfloats; i += AMP_THREADS) X[i] = 0.f;
   for (int i = threadIdx.x; i < Ep * Hs; i += AMP_THREADS) Y[i] = 0.f;
   __syncthreads();
-  const RingDev& mine = D->ring[W->ring];
+  const GQ RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
   __shared__ int s_k, s_last, s_lastb;
@@ -311,9 +311,9 @@ __device__ __noinline__ void role_g_edge(const AmpDev* D, const WorkerDev* W) {
 }
 
 // ---------------------------------------------------------------- GRU gate nodes (aux 0: update z, aux 1: reset r)
-__device__ __noinline__ void role_g_gate(const AmpDev* D, const WorkerDev* W) {
+__device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
-  const NodeDev& nd = D->node[W->node];
+  const GQ NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
   const Pend pd = make_pend(W, t);
@@ -330,7 +330,7 @@ __device__ __noinline__ void role_g_gate(const AmpDev* D, const WorkerDev* W) {
   for (int i = threadIdx.x; i < xfloats; i += AMP_THREADS) X[i] = 0.f;
   for (int i = threadIdx.x; i < Np * Hs; i += AMP_THREADS) Y[i] = 0.f;
   __syncthreads();
-  const RingDev& mine = D->ring[W->ring];
+  const GQ RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
   __shared__ int s_last;
@@ -406,9 +406,9 @@ __device__ __noinline__ void role_g_gate(const AmpDev* D, const WorkerDev* W) {
 }
 
 // ---------------------------------------------------------------- GRU candidate node + blend + loop control
-__device__ __noinline__ void role_g_cand(const AmpDev* D, const WorkerDev* W) {
+__device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
-  const NodeDev& nd = D->node[W->node];
+  const GQ NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
   const Pend pd = make_pend(W, t);
@@ -425,7 +425,7 @@ __device__ __noinline__ void role_g_cand(const AmpDev* D, const WorkerDev* W) {
   for (int i = threadIdx.x; i < xfloats; i += AMP_THREADS) X[i] = 0.f;
   for (int i = threadIdx.x; i < Np * Hs; i += AMP_THREADS) Y[i] = 0.f;
   __syncthreads();
-  const RingDev& mine = D->ring[W->ring];
+  const GQ RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
   while (wait_msg(D, mine, head, s_ctl, code)) {
@@ -503,9 +503,9 @@ __device__ __noinline__ void role_g_cand(const AmpDev* D, const WorkerDev* W) {
 }
 
 // ---------------------------------------------------------------- readout: sum over nodes -> linear -> squared error
-__device__ __noinline__ void role_g_readout(const AmpDev* D, const WorkerDev* W) {
+__device__ __noinline__ void role_g_readout(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
-  const NodeDev& nd = D->node[W->node];
+  const GQ NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
   const int H = B.H;
@@ -515,7 +515,7 @@ __device__ __noinline__ void role_g_readout(const AmpDev* D, const WorkerDev* W)
   float* pooled = L.take(H);
   float* red = L.take(AMP_THREADS);
   tile_load(nd, t, Wl, bl);
-  const RingDev& mine = D->ring[W->ring];
+  const GQ RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   while (wait_msg(D, mine, head, s_ctl, code)) {

@@ -38,9 +38,9 @@ __shared__ int s_pred;
 
 // ============================================================ controller
 // Single-thread wait on the controller's ring.
-__device__ __forceinline__ bool ctrl_wait(const AmpDev* D, const RingDev& r, unsigned& head, unsigned& code) {
+__device__ __forceinline__ bool ctrl_wait(const GQ AmpDev* D, const GQ RingDev& r, unsigned& head, unsigned& code) {
   const unsigned want = head + 1u;
-  unsigned long long* slot = &r.ent[head & r.mask];
+  GQ unsigned long long* slot = (GQ unsigned long long*)&r.ent[head & r.mask];
   const long long t0 = wall_clock64();
   unsigned spins = 0;
   for (;;) {
@@ -62,7 +62,7 @@ __device__ __forceinline__ bool ctrl_wait(const AmpDev* D, const RingDev& r, uns
   }
 }
 
-__device__ __noinline__ void role_ctrl(const AmpDev* D, const WorkerDev* W) {
+__device__ __noinline__ void role_ctrl(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
   if (threadIdx.x == 0) {
     int* freelist = (int*)lds;
@@ -72,7 +72,7 @@ __device__ __noinline__ void role_ctrl(const AmpDev* D, const WorkerDev* W) {
     unsigned next = 0, retired = 0, head = 0;
     int active = 0;
     const unsigned n_total = D->n_total;
-    const RingDev& mine = D->ring[W->ring];
+    const GQ RingDev& mine = D->ring[W->ring];
     D->clock[0] = wall_clock64();
     bool ok = true;
     while (retired < n_total && ok) {
@@ -112,13 +112,13 @@ __device__ __noinline__ void role_ctrl(const AmpDev* D, const WorkerDev* W) {
     }
     D->clock[1] = wall_clock64();
     fence_release();
-    __hip_atomic_store(&D->ctl[1], 1u, __ATOMIC_RELAXED, AGENT);
+    __hip_atomic_store((GQ unsigned*)&D->ctl[1], 1u, __ATOMIC_RELAXED, AGENT);
   }
 }
 
 // ============================================================ shared tail of a dense backward
 // Counts the gradient, updates when min_update_frequency is reached.
-__device__ __forceinline__ void count_and_update(const AmpDev* D, const WorkerDev* W, const NodeDev& nd, const Tile& t,
+__device__ __forceinline__ void count_and_update(const GQ AmpDev* D, const GQ WorkerDev* W, const GQ NodeDev& nd, const Tile& t,
                                                  float* Wl, float* bl, unsigned& count, unsigned& tstep) {
   count++;
   if ((int)count >= nd.muf) {
@@ -134,9 +134,9 @@ __device__ __forceinline__ void count_and_update(const AmpDev* D, const WorkerDe
 // also hosts the softmax loss, which turns the forward message round.
 // Slot storage: buf[0]=act1, buf[1]=act2 (post-ReLU outputs), buf[2]=grad
 // w.r.t. act1, buf[3]=grad w.r.t. act2.
-__device__ __noinline__ void role_mlp_lin(const AmpDev* D, const WorkerDev* W) {
+__device__ __noinline__ void role_mlp_lin(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
-  const NodeDev& nd = D->node[W->node];
+  const GQ NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const int R = t.R, C = t.C, li = W->aux;
   const bool first = li == 0, last = li == 2;
@@ -153,9 +153,9 @@ __device__ __noinline__ void role_mlp_lin(const AmpDev* D, const WorkerDev* W) {
   float* act_out = last ? nullptr : (float*)D->buf[li];
   const float* g_in = last ? nullptr : (const float*)D->buf[2 + li];
   float* g_out = first ? nullptr : (float*)D->buf[2 + li - 1];
-  const RingDev& mine = D->ring[W->ring];
-  const RingDev& next = D->ring[W->ring + 1];   // unused by the last layer
-  const RingDev& prev = D->ring[W->ring - 1];   // the controller for the first layer
+  const GQ RingDev& mine = D->ring[W->ring];
+  const GQ RingDev& next = D->ring[W->ring + 1];   // unused by the last layer
+  const GQ RingDev& prev = D->ring[W->ring - 1];   // the controller for the first layer
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   while (wait_msg(D, mine, head, s_ctl, code)) {
@@ -225,10 +225,10 @@ __device__ __noinline__ void role_mlp_lin(const AmpDev* D, const WorkerDev* W) {
 // Slot storage: buf[0]=hs[mak][max_len][H] cell outputs, buf[1]=es[mak][max_len][E]
 // embeddings recorded at forward time, buf[2]=dh[mak][H] gradient w.r.t. the
 // hidden state travelling down the loop.
-__device__ __noinline__ void role_rnn_cell(const AmpDev* D, const WorkerDev* W) {
+__device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
-  const NodeDev& nd = D->node[1];
-  const NodeDev& lk = D->node[0];
+  const GQ NodeDev& nd = D->node[1];
+  const GQ NodeDev& lk = D->node[0];
   const Tile t = make_tile(nd, W);
   const int H = t.R, C = t.C, E = D->emb, V = D->vocab, TM = D->max_len;
   Lds L{lds};
@@ -246,8 +246,8 @@ __device__ __noinline__ void role_rnn_cell(const AmpDev* D, const WorkerDev* W) 
   float* hs = (float*)D->buf[0];
   float* es = (float*)D->buf[1];
   float* dh = (float*)D->buf[2];
-  const RingDev& mine = D->ring[W->ring];
-  const RingDev& out = D->ring[W->ring + 1];
+  const GQ RingDev& mine = D->ring[W->ring];
+  const GQ RingDev& out = D->ring[W->ring + 1];
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1], lcount = W->wstate[2], lstep = W->wstate[3];
   while (wait_msg(D, mine, head, s_ctl, code)) {
@@ -339,9 +339,9 @@ __device__ __noinline__ void role_rnn_cell(const AmpDev* D, const WorkerDev* W) 
 }
 
 // Output layer + softmax loss of the RNN: forward and backward in one event.
-__device__ __noinline__ void role_rnn_out(const AmpDev* D, const WorkerDev* W) {
+__device__ __noinline__ void role_rnn_out(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
-  const NodeDev& nd = D->node[2];
+  const GQ NodeDev& nd = D->node[2];
   const Tile t = make_tile(nd, W);
   const int R = t.R, C = t.C, TM = D->max_len;
   Lds L{lds};
@@ -355,8 +355,8 @@ __device__ __noinline__ void role_rnn_out(const AmpDev* D, const WorkerDev* W) {
   tile_load(nd, t, Wl, bl);
   const float* hs = (const float*)D->buf[0];
   float* dh = (float*)D->buf[2];
-  const RingDev& mine = D->ring[W->ring];
-  const RingDev& cell = D->ring[W->ring - 1];
+  const GQ RingDev& mine = D->ring[W->ring];
+  const GQ RingDev& cell = D->ring[W->ring - 1];
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   while (wait_msg(D, mine, head, s_ctl, code)) {
@@ -406,8 +406,9 @@ __device__ __noinline__ void role_rnn_out(const AmpDev* D, const WorkerDev* W) {
 #include "amp_ggnn.hip.h"
 
 // ============================================================ entry
-extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const AmpDev* D) {
-  const WorkerDev* W = &D->worker[blockIdx.x];
+extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const AmpDev* Dp) {
+  const GQ AmpDev* D = (const GQ AmpDev*)Dp;
+  const GQ WorkerDev* W = &D->worker[blockIdx.x];
   long long t_begin = 0;
   if (threadIdx.x == 0) {
     s_logn = 0;
@@ -421,8 +422,19 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
     case ROLE_RNN_CELL: role_rnn_cell(D, W); break;
     case ROLE_RNN_OUT: role_rnn_out(D, W); break;
     case ROLE_TREE_LOOKUP: role_tree_lookup(D, W); break;
-    case ROLE_TREE_LEAF: role_tree_cell<false>(D, W); break;
-    case ROLE_TREE_BRANCH: role_tree_cell<true>(D, W); break;
+    case ROLE_TREE_LEAF:
+    case ROLE_TREE_BRANCH: {
+      // the benchmark shape (six 16-row blocks, nineteen 16-column groups per tile) has its own instantiation
+      const GQ NodeDev& nd = D->node[W->node];
+      const int rp = amp_round16(nd.nblocks * W->nu), cl = (nd.cols / nd.seg) * nd.segp;
+      const bool fixed = rp == 96 && amp_round16(cl) == 304;
+      if (W->role == ROLE_TREE_LEAF) {
+        if (fixed) role_tree_cell<false, 6, 19>(D, W); else role_tree_cell<false, 0, 0>(D, W);
+      } else {
+        if (fixed) role_tree_cell<true, 6, 19>(D, W); else role_tree_cell<true, 0, 0>(D, W);
+      }
+      break;
+    }
     case ROLE_TREE_OUT: role_tree_out(D, W); break;
     case ROLE_G_LOOKUP: role_g_lookup(D, W); break;
     case ROLE_G_EDGE: role_g_edge(D, W); break;

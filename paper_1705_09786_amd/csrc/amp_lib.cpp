@@ -171,17 +171,23 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
     case ROLE_TREE_BRANCH: {
       // the largest batch (a multiple of 16 messages) whose pre-activation rows fit beside the weights
       const size_t ldy = amp_ldrow((int)R);
+      // the update's register accumulator holds 8 waves x 4 (16-row, 64-column) units
+      if ((Rp / 16) * ((amp_round16(n.cl()) + 63) / 64) > 32) return 0;
       for (w.kb = 64; w.kb >= 16; w.kb -= 16) {
-        f = wfl + r4(std::max((size_t)w.kb * ldy, UPD_STAGE_HOST * stride));
+        f = wfl + r4((size_t)w.kb * ldy) + r4(Rp) + (size_t)(amp_round16(n.cl()) + 63) / 64 * 64;
         if (f <= avail) break;
       }
       if (w.kb < 16) return 0;
       break;
     }
     case ROLE_TREE_OUT: {
-      const size_t NW = AMP_THREADS / 64;
-      w.kb = 64;
-      f = wfl + r4((size_t)w.kb * amp_round4(c->dims.hidden)) + r4(NW * 64) + r4(UPD_STAGE_HOST * stride) + r4(c->max_mak);
+      // the register-resident gradient accumulator holds 12 elements per thread
+      if (R * C > 12 * AMP_THREADS) return 0;
+      for (w.kb = 64; w.kb >= 16; w.kb -= 16) {
+        f = wfl + r4((size_t)w.kb * amp_round4(c->dims.hidden)) + r4((size_t)w.kb * 64) + r4(c->max_mak);
+        if (f <= avail) break;
+      }
+      if (w.kb < 16) return 0;
       break;
     }
     case ROLE_G_EDGE: {
@@ -402,7 +408,7 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
   }
   for (HostWorker& w : c->workers) {
     w.off_state = take(64);
-    if (w.node >= 0 && c->nodes[w.node].name != "lookup") {
+    if (w.node >= 0 && c->nodes[w.node].name != "lookup" && w.role != ROLE_TREE_OUT) {
       w.pend_bytes = pend_stride(c, w) * 4 * AMP_DENSE_MAX_MUF * rows_per_message(c, w);
       w.off_pend = take(w.pend_bytes);
     }

@@ -12,7 +12,9 @@
 // forward product go from the slot storage in HBM straight into the matrix
 // cores' operand registers (rows there are padded to multiples of 4 floats so
 // that every 16-byte fetch is aligned); the input gradient goes from the
-// accumulators straight back to HBM.
+// accumulators straight back to HBM.  Each backward message appends its (delta,
+// input) pair to the tile's pending list in HBM; the update forms the
+// accumulated gradient from that list on the matrix cores.
 //
 // Slot storage (s = slot, n = tree node, l = leaf; Hp, Ep = H, E rounded up to 4;
 // padding entries stay zero):
@@ -30,23 +32,23 @@
 #pragma once
 
 struct TreeBufs {
-  float *xin, *hc, *gate, *gout, *gpar, *gc, *gx;
-  int* cnt;
+  GQ float *xin, *hc, *gate, *gout, *gpar, *gc, *gx;
+  GQ int* cnt;
   int H, Hp, E, Ep, NNmax, Lmax, TL, TB;
   __device__ __forceinline__ long long node(int s, int n) const { return (long long)s * NNmax + n; }
   __device__ __forceinline__ long long leaf(int s, int l) const { return (long long)s * Lmax + l; }
 };
 
-__device__ __forceinline__ TreeBufs tree_bufs(const AmpDev* D) {
+__device__ __forceinline__ TreeBufs tree_bufs(const GQ AmpDev* D) {
   TreeBufs b;
-  b.xin = (float*)D->buf[0];
-  b.hc = (float*)D->buf[1];
-  b.gate = (float*)D->buf[2];
-  b.gout = (float*)D->buf[3];
-  b.gpar = (float*)D->buf[4];
-  b.gc = (float*)D->buf[5];
-  b.gx = (float*)D->buf[6];
-  b.cnt = (int*)D->buf[7];
+  b.xin = (GQ float*)D->buf[0];
+  b.hc = (GQ float*)D->buf[1];
+  b.gate = (GQ float*)D->buf[2];
+  b.gout = (GQ float*)D->buf[3];
+  b.gpar = (GQ float*)D->buf[4];
+  b.gc = (GQ float*)D->buf[5];
+  b.gx = (GQ float*)D->buf[6];
+  b.cnt = (GQ int*)D->buf[7];
   b.H = D->hidden;
   b.Hp = amp_round4(D->hidden);
   b.E = D->emb;
@@ -66,18 +68,17 @@ __device__ __forceinline__ TreeBufs tree_bufs(const AmpDev* D) {
 
 __device__ __forceinline__ bool code_is_b(unsigned c) { return (c & MSG_DIR_B) != 0; }
 
-typedef int v4i __attribute__((ext_vector_type(4)));
 
 // What the controller wrote for slot s at admission: admission number, leaves, node offset, token offset.
-__device__ __forceinline__ v4i tree_slot(const AmpDev* D, int s) { return *(const v4i*)(D->smeta + 4 * s); }
+__device__ __forceinline__ v4i tree_slot(const GQ AmpDev* D, int s) { return *(const GQ v4i*)(D->smeta + 4 * s); }
 // left, right, parent * 2 + side (-1 for the root), label of node n of the instance whose nodes start at noff
-__device__ __forceinline__ v4i tree_node(const AmpDev* D, int noff, int n) {
-  return *(const v4i*)(D->data.tnode + 4 * (long long)(noff + n));
+__device__ __forceinline__ v4i tree_node(const GQ AmpDev* D, int noff, int n) {
+  return *(const GQ v4i*)(D->data.tnode + 4 * (long long)(noff + n));
 }
 
 // Wave 0, all 64 lanes, after lanes k < n have written M.aux[k]: positions of
 // the batch's forward and backward messages, and the event record (tile 0 only).
-__device__ __forceinline__ void batch_split_and_log(const AmpDev* D, const WorkerDev* W, BatchMsg& M, int n, int node,
+__device__ __forceinline__ void batch_split_and_log(const GQ AmpDev* D, const GQ WorkerDev* W, BatchMsg& M, int n, int node,
                                                     bool both_kinds) {
   const int k = threadIdx.x;   // < 64
   const bool in = k < n, isb = in && M.aux[k] != 0;
@@ -112,8 +113,8 @@ __device__ __forceinline__ void batch_split_and_log(const AmpDev* D, const Worke
 // A tile has finished its units of node n: when all tiles have, the node's
 // [h; c] goes to the output layer and, through Isu / Concat, to its parent,
 // which fires once both children are there.  One lane, after a release fence.
-__device__ __forceinline__ void tree_node_part_done(const AmpDev* D, const TreeBufs& B, int s, int n, int parent_code, int ntiles) {
-  int* c = B.cnt + B.node(s, n) * 4;
+__device__ __forceinline__ void tree_node_part_done(const GQ AmpDev* D, const TreeBufs& B, int s, int n, int parent_code, int ntiles) {
+  GQ int* c = B.cnt + B.node(s, n) * 4;
   if (!join_arrive(c + 0, ntiles)) return;
   ring_post(D->ring[TR_OUT], MSG_MAKE(0, s, n));
   if (parent_code < 0) return;
@@ -123,27 +124,29 @@ __device__ __forceinline__ void tree_node_part_done(const AmpDev* D, const TreeB
 
 // One gradient part for node n has been written: Bcast's backward waits for
 // the output layer's part and (unless n is the root) every parent tile's.
-__device__ __forceinline__ void tree_grad_part_done(const AmpDev* D, const TreeBufs& B, int s, int n, bool is_root, bool is_leaf) {
+__device__ __forceinline__ void tree_grad_part_done(const GQ AmpDev* D, const TreeBufs& B, int s, int n, bool is_root, bool is_leaf) {
   const int expect = is_root ? 1 : 1 + B.TB;
   if (join_arrive(B.cnt + B.node(s, n) * 4 + 2, expect))
     ring_post(D->ring[is_leaf ? TR_LEAF : TR_BRANCH], MSG_MAKE(1, s, n));
 }
 
 // ------------------------------------------------------------ lookup
-__device__ __noinline__ void role_tree_lookup(const AmpDev* D, const WorkerDev* W) {
+__device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
-  const NodeDev& lk = D->node[0];
+  const GQ NodeDev& lk = D->node[0];
   const TreeBufs B = tree_bufs(D);
   const int E = B.E, Ep = B.Ep, KB = W->kb, E4 = E >> 2;
   int* left_cnt = (int*)lds;                  // [mak] leaves not yet answered
   int* pend_tok = left_cnt + ((D->mak + 3) & ~3);
   for (int i = threadIdx.x; i < D->mak; i += AMP_THREADS) left_cnt[i] = 0;
   BatchMsg& M = s_M;
-  const RingDev& mine = D->ring[W->ring];
+  const GQ RingDev& mine = D->ring[W->ring];
   unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
-  int* keep = (int*)D->buf[10];
-  float* prow = (float*)D->buf[11];
+  GQ int* keep = (GQ int*)D->buf[10];
+  GQ float* prow = (GQ float*)D->buf[11];
+  GQ float* lkP = (GQ float*)lk.P;
+  const GQ int* tokens = (const GQ int*)D->data.tok;
   for (unsigned k = threadIdx.x; k < count; k += AMP_THREADS) pend_tok[k] = keep[k];
   __syncthreads();
   for (;;) {
@@ -158,7 +161,7 @@ __device__ __noinline__ void role_tree_lookup(const AmpDev* D, const WorkerDev* 
         M.s[k] = s;
         M.n[k] = l;
         M.seq[k] = (unsigned)sm.x;
-        M.a[k] = D->data.tok[sm.w + l];
+        M.a[k] = tokens[sm.w + l];
         M.aux[k] = code_is_b(code);
         if (!code_is_b(code) && l == 0) left_cnt[s] = sm.y;
       }
@@ -172,27 +175,27 @@ __device__ __noinline__ void role_tree_lookup(const AmpDev* D, const WorkerDev* 
         pend_tok[count + b] = M.a[k];
       }
     }
-    __syncthreads();
+    lds_barrier();
     if ((E & 3) == 0) {
       // forward: table row -> xin; backward: sum of the leaf tiles' partials -> pending gradient row
       for (int idx = threadIdx.x; idx < n * E4; idx += AMP_THREADS) {
         const int k = idx / E4, c = (idx - k * E4) << 2;
         if (!M.aux[k]) {
-          *(v4f*)(B.xin + B.leaf(M.s[k], M.n[k]) * Ep + c) = *(const v4f*)(lk.P + (long long)M.a[k] * E + c);
+          *(GQ v4f*)(B.xin + B.leaf(M.s[k], M.n[k]) * Ep + c) = *(const GQ v4f*)(lkP + (long long)M.a[k] * E + c);
         } else {
-          const float* gx = B.gx + B.leaf(M.s[k], M.n[k]) * B.TL * Ep + c;
+          const GQ float* gx = B.gx + B.leaf(M.s[k], M.n[k]) * B.TL * Ep + c;
           v4f a = {0.f, 0.f, 0.f, 0.f};
-          for (int t = 0; t < B.TL; ++t) a += *(const v4f*)(gx + t * Ep);
-          *(v4f*)(prow + (long long)(count + M.b[k]) * E + c) = a;
+          for (int t = 0; t < B.TL; ++t) a += *(const GQ v4f*)(gx + t * Ep);
+          *(GQ v4f*)(prow + (long long)(count + M.b[k]) * E + c) = a;
         }
       }
     } else {
       for (int idx = threadIdx.x; idx < n * E; idx += AMP_THREADS) {
         const int k = idx / E, c = idx - k * E;
         if (!M.aux[k]) {
-          B.xin[B.leaf(M.s[k], M.n[k]) * Ep + c] = lk.P[(long long)M.a[k] * E + c];
+          B.xin[B.leaf(M.s[k], M.n[k]) * Ep + c] = lkP[(long long)M.a[k] * E + c];
         } else {
-          const float* gx = B.gx + B.leaf(M.s[k], M.n[k]) * B.TL * Ep + c;
+          const GQ float* gx = B.gx + B.leaf(M.s[k], M.n[k]) * B.TL * Ep + c;
           float a = 0.f;
           for (int t = 0; t < B.TL; ++t) a += gx[t * Ep];
           prow[(long long)(count + M.b[k]) * E + c] = a;
@@ -225,7 +228,7 @@ __device__ __noinline__ void role_tree_lookup(const AmpDev* D, const WorkerDev* 
 #pragma unroll
           for (int k = 0; k < 16; ++k)
             if (k < kc) {
-              w[k] = lk.P[(long long)pend_tok[k0 + k] * E + c];
+              w[k] = lkP[(long long)pend_tok[k0 + k] * E + c];
               g[k] = prow[(long long)(k0 + k) * E + c];
             }
 #pragma unroll
@@ -240,7 +243,7 @@ __device__ __noinline__ void role_tree_lookup(const AmpDev* D, const WorkerDev* 
             }
 #pragma unroll
           for (int k = 0; k < 16; ++k)
-            if (k < kc) lk.P[(long long)pend_tok[k0 + k] * E + c] = w[k];
+            if (k < kc) lkP[(long long)pend_tok[k0 + k] * E + c] = w[k];
         }
       }
       count = 0;
@@ -257,117 +260,328 @@ __device__ __noinline__ void role_tree_lookup(const AmpDev* D, const WorkerDev* 
 }
 
 // ------------------------------------------------------------ matrix-core products of a cell tile
+// The products are templates over the tile's shape -- NRBT 16-row blocks and
+// NCGT 16-column groups, 0 = known only at run time -- because fixed trip
+// counts and strides let the compiler unroll the loops, fold the LDS
+// addresses into instruction offsets and keep every operand in registers.
+// One wave issues at most one matrix instruction every ~32 clocks and needs
+// four or more independent accumulators to get there, so the loops below are
+// shaped to give every wave an equal share and several accumulators.
+#define TREE_XG 20        // 16-column groups of the input held in registers at once
+#define TREE_GU 4         // (16-row block, 64-column block) gradient units per wave
+
+template <int NRBT, int NCGT>
+struct TreeShape {
+  int NRB, NCG, ldw, ldy;
+  __device__ __forceinline__ TreeShape(const Tile& t) {
+    NRB = NRBT ? NRBT : t.Rp >> 4;
+    NCG = NCGT ? NCGT : amp_round16(t.Cl) >> 4;
+    ldw = NCGT ? amp_ldrow(NCGT * 16) : t.ldw;
+    ldy = NRBT ? amp_ldrow(NRBT * 16) : amp_ldrow(t.Rp);
+  }
+};
+
 // Y[j][r] = b[r] + sum_c W[r][c] x_j[c] for the nF forward messages of the batch.
-// Wave item = (16 messages, 16 weight rows); the messages' inputs are fetched
-// from HBM (xbase + M.off0 / off1 for the first / second column segment)
-// eight 16-column groups ahead of their use.
-template <bool BR>
-__device__ __forceinline__ void tree_fwd_mfma(const LDSQ float* Wl, const Tile& t, const LDSQ float* bl, const float* xbase,
-                                              const BatchMsg& M, int nF, LDSQ float* Y, int ldy) {
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
-  const int NRB = t.Rp >> 4, NCG = amp_round16(t.Cl) >> 4, NBF = (nF + 15) >> 4;
+// A 16-message block is shared by 8 / (number of blocks) waves, each taking
+// every wpn-th 16-row block of the weights.  A wave fetches its messages'
+// inputs from HBM (xbase + M.off0 / off1 for the first / second column
+// segment) once, straight into operand registers, and uses them for NJ (up to
+// three) row blocks at a time.  Loads are unconditional so that they overlap:
+// a column group beyond the input reads a valid address and is replaced by zero.
+template <bool BR, int NJ, int NRBT, int NCGT>
+__device__ __forceinline__ void tree_fwd_pass(const LDSQ float* Wl, const Tile& t, const LDSQ float* bl, const GQ float* p0,
+                                              const GQ float* p1, int r0, int wpn, LDSQ float* yrow) {
+  const TreeShape<NRBT, NCGT> sh(t);
+  const int lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
   const v4f zero = {0.f, 0.f, 0.f, 0.f};
-  for (int item = wave; item < NBF * NRB; item += AMP_THREADS / 64) {
-    const int rb = item % NRB, nb = item / NRB;
-    int mi = nb * 16 + i;
-    if (mi > nF - 1) mi = nF - 1;   // rows beyond the batch repeat its last message; their results are dropped
-    const int m = M.fidx[mi];
-    const float* p0 = xbase + M.off0[m] + 4 * q;
-    const float* p1 = xbase + M.off1[m] + 4 * q - t.segp;
-    const LDSQ float* wp = Wl + (rb * 16 + i) * t.ldw + 4 * q;
-    auto fetch = [&](int kg) -> v4f {
-      const int lc = kg * 16 + 4 * q;
-      if (lc >= t.Cl) return zero;
-      return *(const v4f*)((BR && lc >= t.segp ? p1 : p0) + kg * 16);
-    };
-    v4f acc0 = zero, acc1 = zero, xa[8], xb[8];
+  constexpr int NA = NJ == 1 ? 4 : 2;   // accumulators per row block
+  v4f acc[NJ][NA];
+  const LDSQ float* wr[NJ];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) xa[j] = fetch(j);
-    for (int kc = 0; kc < NCG; kc += 16) {
+  for (int j = 0; j < NJ; ++j) {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) xb[j] = fetch(kc + 8 + j);
+    for (int a = 0; a < NA; ++a) acc[j][a] = zero;
+    wr[j] = Wl + ((r0 + j * wpn) * 16 + i) * sh.ldw + 4 * q;
+  }
+  for (int c0 = 0; c0 < sh.NCG; c0 += TREE_XG) {
+    v4f x[TREE_XG];
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (kc + j < NCG) {
-          const v4f w = *(const LDSQ v4f*)(wp + 16 * (kc + j));
-          acc0 = MFMA(w.x, xa[j].x, acc0);
-          acc1 = MFMA(w.y, xa[j].y, acc1);
-          acc0 = MFMA(w.z, xa[j].z, acc0);
-          acc1 = MFMA(w.w, xa[j].w, acc1);
-        }
-#pragma unroll
-      for (int j = 0; j < 8; ++j) xa[j] = fetch(kc + 16 + j);
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-        if (kc + 8 + j < NCG) {
-          const v4f w = *(const LDSQ v4f*)(wp + 16 * (kc + 8 + j));
-          acc0 = MFMA(w.x, xb[j].x, acc0);
-          acc1 = MFMA(w.y, xb[j].y, acc1);
-          acc0 = MFMA(w.z, xb[j].z, acc0);
-          acc1 = MFMA(w.w, xb[j].w, acc1);
-        }
+    for (int g = 0; g < TREE_XG; ++g) {
+      const int lc = (c0 + g) * 16 + 4 * q;
+      const bool in = lc < t.Cl;
+      const GQ float* p = in ? (BR && lc >= t.segp ? p1 : p0) + (c0 + g) * 16 : p0;
+      const v4f v = *(const GQ v4f*)p;
+      x[g] = in ? v : zero;
     }
-    const v4f b4 = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
-    *(LDSQ v4f*)(Y + (nb * 16 + i) * ldy + rb * 16 + 4 * q) = acc0 + acc1 + b4;
+    // all fetches are in flight before the first product waits for one
+    asm volatile("" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]),
+                      "+v"(x[8]), "+v"(x[9]), "+v"(x[10]), "+v"(x[11]), "+v"(x[12]), "+v"(x[13]), "+v"(x[14]),
+                      "+v"(x[15]), "+v"(x[16]), "+v"(x[17]), "+v"(x[18]), "+v"(x[19]));
+#pragma unroll
+    for (int g = 0; g < TREE_XG; ++g) {
+      if (NCGT ? g < NCGT : c0 + g < sh.NCG) {
+        v4f w[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) w[j] = *(const LDSQ v4f*)(wr[j] + 16 * (c0 + g));
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          acc[j][0] = MFMA(w[j].x, x[g].x, acc[j][0]);
+          acc[j][1] = MFMA(w[j].y, x[g].y, acc[j][1]);
+        }
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          acc[j][NA == 4 ? 2 : 0] = MFMA(w[j].z, x[g].z, acc[j][NA == 4 ? 2 : 0]);
+          acc[j][NA == 4 ? 3 : 1] = MFMA(w[j].w, x[g].w, acc[j][NA == 4 ? 3 : 1]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int rb = r0 + j * wpn;
+    v4f r = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
+#pragma unroll
+    for (int a = 0; a < NA; ++a) r += acc[j][a];
+    *(LDSQ v4f*)(yrow + rb * 16 + 4 * q) = r;
+  }
+}
+
+template <bool BR, int NRBT, int NCGT>
+__device__ __forceinline__ void tree_fwd_mfma(const LDSQ float* Wl, const Tile& t, const LDSQ float* bl, const GQ float* xbase,
+                                              const BatchMsg& M, int nF, LDSQ float* Y) {
+  const TreeShape<NRBT, NCGT> sh(t);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  const int NBF = (nF + 15) >> 4;
+  const int wpn = NBF == 1 ? 8 : NBF == 2 ? 4 : 2;
+  // waves w and w + 4 share a SIMD: rotating the row-block offset with the message block evens out the
+  // number of row blocks per SIMD when the blocks do not divide evenly among a block's waves
+  const int nb = wave / wpn, sub = (wave - nb * wpn + (wpn >> 1) * (nb & 1)) % wpn;
+  if (nb >= NBF) return;
+  int mi = nb * 16 + i;
+  if (mi > nF - 1) mi = nF - 1;   // rows beyond the batch repeat its last message; their results are dropped
+  const int m = M.fidx[mi];
+  const GQ float* p0 = xbase + M.off0[m] + 4 * q;
+  const GQ float* p1 = xbase + M.off1[m] + 4 * q - t.segp;
+  LDSQ float* yrow = Y + (nb * 16 + i) * sh.ldy;
+  for (int r0 = sub; r0 < sh.NRB; r0 += 3 * wpn) {
+    const int left = (sh.NRB - r0 + wpn - 1) / wpn;   // row blocks r0, r0 + wpn, ... still to do
+    if (left >= 3)
+      tree_fwd_pass<BR, 3, NRBT, NCGT>(Wl, t, bl, p0, p1, r0, wpn, yrow);
+    else if (left == 2)
+      tree_fwd_pass<BR, 2, NRBT, NCGT>(Wl, t, bl, p0, p1, r0, wpn, yrow);
+    else
+      tree_fwd_pass<BR, 1, NRBT, NCGT>(Wl, t, bl, p0, p1, r0, wpn, yrow);
   }
 }
 
 // dx_j[c] = sum_r W[r][c] delta_j[r] for the nB backward messages; delta rows
-// in LDS (Dl, stride ldd, zero beyond the tile's rows); the result goes from
-// the accumulators to HBM at obase + M.dst0 / dst1 (+ column inside the segment).
-template <bool BR>
-__device__ __forceinline__ void tree_bwd_mfma(const LDSQ float* Wl, const Tile& t, const LDSQ float* Dl, int ldd,
-                                              const BatchMsg& M, int nB, float* obase) {
+// in LDS (Dl, zero beyond the tile's rows); the result goes from the
+// accumulators to HBM at obase + M.dst0 / dst1 (+ column inside the
+// segment).  Wave item = 16 weight columns, for all NBB message blocks.
+template <bool BR, int NBB, int NRBT, int NCGT>
+__device__ __forceinline__ void tree_bwd_blocks(const LDSQ float* Wl, const Tile& t, const LDSQ float* Dl, const BatchMsg& M,
+                                                int nB, GQ float* obase) {
+  const TreeShape<NRBT, NCGT> sh(t);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
-  const int NRB = t.Rp >> 4, NCG = amp_round16(t.Cl) >> 4, NBB = (nB + 15) >> 4;
   const v4f zero = {0.f, 0.f, 0.f, 0.f};
-  for (int item = wave; item < NCG * NBB; item += AMP_THREADS / 64) {
-    const int cb = item % NCG, nb = item / NCG;
-    const LDSQ float* wp = Wl + (4 * q) * t.ldw + cb * 16 + i;
-    const LDSQ float* dp = Dl + (nb * 16 + i) * ldd + 4 * q;
-    v4f acc0 = zero, acc1 = zero;
-    for (int g = 0; g < NRB; ++g) {
-      const v4f d0 = *(const LDSQ v4f*)(dp + 16 * g);
-      const LDSQ float* w = wp + 16 * g * t.ldw;
-      const float w0 = w[0], w1 = w[t.ldw], w2 = w[2 * t.ldw], w3 = w[3 * t.ldw];
-      acc0 = MFMA(w0, d0.x, acc0);
-      acc1 = MFMA(w1, d0.y, acc1);
-      acc0 = MFMA(w2, d0.z, acc0);
-      acc1 = MFMA(w3, d0.w, acc1);
+  constexpr int NA = NBB == 1 ? 4 : 2;
+  for (int cb = wave; cb < sh.NCG; cb += AMP_THREADS / 64) {
+    const LDSQ float* wp = Wl + (4 * q) * sh.ldw + cb * 16 + i;
+    const LDSQ float* dp = Dl + i * sh.ldy + 4 * q;
+    v4f acc[NBB][NA];
+#pragma unroll
+    for (int nb = 0; nb < NBB; ++nb)
+#pragma unroll
+      for (int a = 0; a < NA; ++a) acc[nb][a] = zero;
+#pragma unroll 6
+    for (int g = 0; g < sh.NRB; ++g) {
+      v4f d[NBB];
+#pragma unroll
+      for (int nb = 0; nb < NBB; ++nb) d[nb] = *(const LDSQ v4f*)(dp + nb * 16 * sh.ldy + 16 * g);
+      const LDSQ float* w = wp + 16 * g * sh.ldw;
+      const float a0 = w[0], a1 = w[sh.ldw], a2 = w[2 * sh.ldw], a3 = w[3 * sh.ldw];
+#pragma unroll
+      for (int nb = 0; nb < NBB; ++nb) {
+        acc[nb][0] = MFMA(a0, d[nb].x, acc[nb][0]);
+        acc[nb][1] = MFMA(a1, d[nb].y, acc[nb][1]);
+      }
+#pragma unroll
+      for (int nb = 0; nb < NBB; ++nb) {
+        acc[nb][NA == 4 ? 2 : 0] = MFMA(a2, d[nb].z, acc[nb][NA == 4 ? 2 : 0]);
+        acc[nb][NA == 4 ? 3 : 1] = MFMA(a3, d[nb].w, acc[nb][NA == 4 ? 3 : 1]);
+      }
     }
-    const int mi = nb * 16 + i, lc = cb * 16 + 4 * q;
-    if (mi < nB && lc < t.Cl) {
-      const int m = M.bidx[mi];
-      float* o = (BR && lc >= t.segp) ? obase + M.dst1[m] + (lc - t.segp) : obase + M.dst0[m] + lc;
-      *(v4f*)o = acc0 + acc1;
+    const int lc = cb * 16 + 4 * q;
+#pragma unroll
+    for (int nb = 0; nb < NBB; ++nb) {
+      const int mi = nb * 16 + i;
+      if (mi < nB && lc < t.Cl) {
+        const int m = M.bidx[mi];
+        GQ float* o = (BR && lc >= t.segp) ? obase + M.dst1[m] + (lc - t.segp) : obase + M.dst0[m] + lc;
+        v4f r = acc[nb][0] + acc[nb][1];
+        if (NA == 4) r += acc[nb][2] + acc[nb][3];
+        *(GQ v4f*)o = r;
+      }
     }
+  }
+}
+
+template <bool BR, int NRBT, int NCGT>
+__device__ __forceinline__ void tree_bwd_mfma(const LDSQ float* Wl, const Tile& t, const LDSQ float* Dl, const BatchMsg& M,
+                                              int nB, GQ float* obase) {
+  const int NBB = (nB + 15) >> 4;
+  if (NBB == 1)
+    tree_bwd_blocks<BR, 1, NRBT, NCGT>(Wl, t, Dl, M, nB, obase);
+  else if (NBB == 2)
+    tree_bwd_blocks<BR, 2, NRBT, NCGT>(Wl, t, Dl, M, nB, obase);
+  else if (NBB == 3)
+    tree_bwd_blocks<BR, 3, NRBT, NCGT>(Wl, t, Dl, M, nB, obase);
+  else
+    tree_bwd_blocks<BR, 4, NRBT, NCGT>(Wl, t, Dl, M, nB, obase);
+}
+
+// The node's update (Section 3) for one tile, from the `count` pending
+// (delta, input) pairs in HBM, entry k at pend + k * stride = [delta (Rp) |
+// input in LDS column layout (Cp)]:  G[r][c] = sum_k delta_k[r] x_k[c] in
+// arrival order, formed on the matrix cores with the pairs fetched straight
+// into operand registers, then the optimizer step on the LDS weights.
+// Unit u of a wave is the (16-row block rb, 64-column block cm) with
+// rb + NRB * cm = wave + 8 u; its four 16 x 16 tiles take the columns
+// cm * 64 + 4 i + v, v = 0..3, so that one 16-byte fetch of an input feeds all
+// four.  Lane (i, q) ends up with G[rb*16 + 4q + e][cm*64 + 4i + v] in g[u][v][e].
+// gb = the accumulated bias gradient of tile row threadIdx.x.
+template <int NRBT, int NCGT>
+__device__ __noinline__ void tree_update_from_pend(LDSQ float* Wl, LDSQ float* bl, const GQ NodeDev* ndp, Tile t,
+                                                   const GQ float* pend, unsigned count, unsigned tstep,
+                                                   const LDSQ int* rowmap, const LDSQ int* colmap, float gb) {
+  const TreeShape<NRBT, NCGT> sh(t);
+  const GQ NodeDev& nd = *ndp;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  const int NRB = sh.NRB, Rp = NRB * 16, Cp = sh.NCG * 16, stride = Rp + Cp, CM = (Cp + 63) >> 6, NU = NRB * CM;
+  const v4f zero = {0.f, 0.f, 0.f, 0.f};
+  const OptCoef o = opt_coef(nd, tstep);
+  const float inv = nd.mean ? 1.f / (float)count : 1.f;
+  v4f g[TREE_GU][4];
+  int aoff[TREE_GU], xoff[TREE_GU];
+  bool xin[TREE_GU];
+#pragma unroll
+  for (int u = 0; u < TREE_GU; ++u) {
+    const int id = wave + 8 * u < NU ? wave + 8 * u : 0, cm = id / NRB, rb = id - cm * NRB, lc = cm * 64 + 4 * i;
+    aoff[u] = rb * 16 + i;
+    xin[u] = lc < Cp;
+    xoff[u] = Rp + (xin[u] ? lc : 0);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) g[u][v] = zero;
+  }
+  constexpr int NH = 4;
+  for (unsigned k0 = 0; k0 < count; k0 += 4 * NH) {
+    // NH groups of four pending pairs per round, all fetches in flight together
+    float a[NH][TREE_GU];
+    v4f x[NH][TREE_GU];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+      const unsigned k = k0 + 4 * h + q;
+      const bool kin = k < count;
+      const GQ float* e = pend + (long long)(kin ? k : count - 1) * stride;
+#pragma unroll
+      for (int u = 0; u < TREE_GU; ++u) {
+        const float av = e[aoff[u]];
+        const v4f xv = *(const GQ v4f*)(e + xoff[u]);
+        a[h][u] = kin ? av : 0.f;
+        x[h][u] = xin[u] ? xv : zero;
+      }
+    }
+    asm volatile("" : "+v"(x[0][0]), "+v"(x[0][1]), "+v"(x[0][2]), "+v"(x[0][3]), "+v"(x[1][0]), "+v"(x[1][1]), "+v"(x[1][2]),
+                      "+v"(x[1][3]), "+v"(x[2][0]), "+v"(x[2][1]), "+v"(x[2][2]), "+v"(x[2][3]), "+v"(x[3][0]), "+v"(x[3][1]),
+                      "+v"(x[3][2]), "+v"(x[3][3]));
+#pragma unroll
+    for (int h = 0; h < NH; ++h)
+#pragma unroll
+      for (int u = 0; u < TREE_GU; ++u)
+        if (wave + 8 * u < NU) {
+          g[u][0] = MFMA(a[h][u], x[h][u].x, g[u][0]);
+          g[u][1] = MFMA(a[h][u], x[h][u].y, g[u][1]);
+          g[u][2] = MFMA(a[h][u], x[h][u].z, g[u][2]);
+          g[u][3] = MFMA(a[h][u], x[h][u].w, g[u][3]);
+        }
+  }
+  // optimizer step from the accumulators.  Plain SGD needs no per-element slots: padding rows and columns
+  // have a zero gradient (their delta / input entries are zero), so whole 16-byte groups are updated.
+  if (o.kind == 0) {
+    const float sc = o.lr * inv;
+#pragma unroll
+    for (int u = 0; u < TREE_GU; ++u) {
+      const int id = wave + 8 * u, cm = id / NRB, rb = id - cm * NRB, lc = cm * 64 + 4 * i;
+      if (id < NU && lc < Cp) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          LDSQ v4f* wp = (LDSQ v4f*)(Wl + (rb * 16 + 4 * q + e) * sh.ldw + lc);
+          const v4f gv = {g[u][0][e], g[u][1][e], g[u][2][e], g[u][3][e]};
+          *wp = *wp - sc * gv;
+        }
+      }
+    }
+  } else
+#pragma unroll
+  for (int u = 0; u < TREE_GU; ++u) {
+    const int id = wave + 8 * u, cm = id / NRB, rb = id - cm * NRB;
+    if (id < NU) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int lc = cm * 64 + 4 * i + v, nc = colmap[lc];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = rb * 16 + 4 * q + e, nr = rowmap[r];
+          if (nr >= 0 && nc >= 0)
+            Wl[r * sh.ldw + lc] = opt_apply(o, Wl[r * sh.ldw + lc], g[u][v][e] * inv, nd.M, nd.V, (long long)nr * t.C + nc);
+        }
+      }
+    }
+  }
+  if ((int)threadIdx.x < t.R && nd.has_bias) {
+    const int r = threadIdx.x;
+    bl[r] = opt_apply(o, bl[r], gb * inv, nd.M, nd.V, (long long)nd.rows * t.C + rowmap[r]);
   }
 }
 
 // ------------------------------------------------------------ leaf / branch cells
 // BR = false: rows [i; o; u] over the embedding.
 // BR = true : rows [i; f_l; f_r; o; u] over [h_l; h_r].
-template <bool BR>
-__device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W) {
+// NRBT / NCGT: the tile's 16-row blocks / 16-column groups when known at compile time, else 0.
+template <bool BR, int NRBT, int NCGT>
+__device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
-  const NodeDev& nd = D->node[W->node];
+  const GQ NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const TreeBufs B = tree_bufs(D);
   const Pend pd = make_pend(W, t);
+  GQ float* pend = (GQ float*)pd.base;
   const int R = t.R, H = B.H, Hp = B.Hp, nu = t.nu, u0 = t.u0, KB = W->kb;
   const int ldy = amp_ldrow(R);
   Lds L{lds};
-  float* Wl = L.take(t.Rp * t.ldw);
-  float* bl = L.take(t.Rp);
-  const int yfloats = KB * ldy > UPD_STAGE * pd.stride ? KB * ldy : UPD_STAGE * pd.stride;
-  float* Y = L.take(yfloats);   // forward: pre-activations; backward: deltas; staging at updates
-  tile_load(nd, t, Wl, bl);
+  float* Wg = L.take(t.Rp * t.ldw);
+  float* bg = L.take(t.Rp);
+  LDSQ float* Wl = (LDSQ float*)Wg;
+  LDSQ float* bl = (LDSQ float*)bg;
+  const int yfloats = KB * ldy;
+  LDSQ float* Y = (LDSQ float*)L.take(yfloats);   // forward: pre-activations; backward: deltas
+  // node row of a tile row / node column of an LDS column (-1 = padding)
+  const int CMW = ((amp_round16(t.Cl) + 63) >> 6) << 6;
+  LDSQ int* rowmap = (LDSQ int*)L.take(t.Rp);
+  LDSQ int* colmap = (LDSQ int*)L.take(CMW);
+  tile_load(nd, t, Wg, bg);
   for (int i = threadIdx.x; i < yfloats; i += AMP_THREADS) Y[i] = 0.f;
+  for (int i = threadIdx.x; i < t.Rp; i += AMP_THREADS) rowmap[i] = i < R ? t.grow(i) : -1;
+  for (int i = threadIdx.x; i < CMW; i += AMP_THREADS) colmap[i] = t.ncol(i);
+  __syncthreads();
+  // bias gradient of tile row threadIdx.x accumulated since the last update (rests in HBM between launches)
+  GQ float* ndG = (GQ float*)nd.G;
+  float accb = ((int)threadIdx.x < R && nd.has_bias) ? ndG[(long long)nd.rows * t.C + t.grow(threadIdx.x)] : 0.f;
   BatchMsg& M = s_M;
   __syncthreads();
-  const RingDev& mine = D->ring[W->ring];
-  const float* xbase = BR ? B.hc : B.xin;
-  float* obase = BR ? B.gpar : B.gx;
+  const GQ RingDev& mine = D->ring[W->ring];
+  const GQ float* xbase = BR ? B.hc : B.xin;
+  GQ float* obase = BR ? B.gpar : B.gx;
   unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   for (;;) {
@@ -400,20 +614,20 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
       }
       batch_split_and_log(D, W, M, n, W->node, false);
     }
-    __syncthreads();
+    lds_barrier();
     const int nF = M.nF, nB = M.nB;
     PHASE(0);
     // ---------------- forward messages of the batch
     if (nF > 0) {
-      tree_fwd_mfma<BR>((const LDSQ float*)Wl, t, (const LDSQ float*)bl, xbase, M, nF, (LDSQ float*)Y, ldy);
-      __syncthreads();
+      tree_fwd_mfma<BR, NRBT, NCGT>(Wl, t, bl, xbase, M, nF, Y);
+      lds_barrier();
       PHASE(1);
       for (int i = threadIdx.x; i < nF * nu; i += AMP_THREADS) {
         const int k = i / nu, j = i - k * nu, m = M.fidx[k], u = u0 + j;
-        const float* y = Y + k * ldy;
+        const LDSQ float* y = Y + k * ldy;
         const long long nn = B.node(M.s[m], M.n[m]);
-        float* hcn = B.hc + nn * 2 * Hp;
-        float* gt = B.gate + nn * 6 * H;
+        GQ float* hcn = B.hc + nn * 2 * Hp;
+        GQ float* gt = B.gate + nn * 6 * H;
         float c_, o_;
         if (BR) {
           const float cl = xbase[M.off0[m] + Hp + u];
@@ -441,7 +655,7 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
         hcn[u] = o_ * tc;
         hcn[Hp + u] = c_;
       }
-      __syncthreads();
+      lds_barrier();
       PHASE(2);
     }
     // ---------------- backward messages of the batch
@@ -454,12 +668,17 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
       for (int i = threadIdx.x; i < nB * nu; i += AMP_THREADS) {
         const int k = i / nu, j = i - k * nu, m = M.bidx[k], u = u0 + j;
         const long long nn = B.node(M.s[m], M.n[m]);
-        const float* gt = B.gate + nn * 6 * H;
+        const GQ float* gt = B.gate + nn * 6 * H;
         float dh = B.gout[nn * H + u], dc = 0.f;
         if (M.par[m] >= 0) {
-          const float* gp = B.gpar + nn * B.TB * Hp + u;
+          const GQ float* gp = B.gpar + nn * B.TB * Hp + u;
           float p = 0.f;
-          for (int q = 0; q < B.TB; ++q) p += gp[q * Hp];
+          int q = 0;
+          for (; q + 3 < B.TB; q += 4) {
+            const float p0 = gp[q * Hp], p1 = gp[(q + 1) * Hp], p2 = gp[(q + 2) * Hp], p3 = gp[(q + 3) * Hp];
+            p = (((p + p0) + p1) + p2) + p3;
+          }
+          for (; q < B.TB; ++q) p += gp[q * Hp];
           dh += p;
           dc = B.gc[nn * H + u];
         }
@@ -468,7 +687,7 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
         const float d_o = dh * tc * o_ * (1.f - o_);
         const float d_i = dct * g_ * i_ * (1.f - i_);
         const float d_g = dct * i_ * (1.f - g_ * g_);
-        float* ds = Y + k * ldy;
+        LDSQ float* ds = Y + k * ldy;
         if (BR) {
           const long long na = B.node(M.s[m], M.a[m]), nb = B.node(M.s[m], M.b[m]);
           const float fl = gt[H + u], fr = gt[2 * H + u];
@@ -485,25 +704,43 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
           ds[2 * nu + j] = d_g;
         }
       }
-      __syncthreads();
+      lds_barrier();
       PHASE(3);
-      // the (delta, input) pairs join the pending gradients: entry = [delta (Rp) | input in LDS column layout (Cp)]
-      for (int i = threadIdx.x; i < nB * (pd.stride >> 2); i += AMP_THREADS) {
-        const int k = i / (pd.stride >> 2), j = (i - k * (pd.stride >> 2)) << 2, m = M.bidx[k];
-        v4f v = {0.f, 0.f, 0.f, 0.f};
-        if (j < pd.Rp) {
-          if (j < ldy) v = *(const v4f*)(Y + k * ldy + j);   // ldy >= R, zero beyond R
-        } else {
-          const int lc = j - pd.Rp;
-          if (lc < t.Cl) v = *(const v4f*)(xbase + ((BR && lc >= t.segp) ? M.off1[m] + lc - t.segp : M.off0[m] + lc));
+      // the (delta, input) pairs join the pending gradients: entry = [delta (Rp) | input in LDS column layout (Cp)];
+      // four 16-byte groups per thread are in flight at a time
+      {
+        const int per = pd.stride >> 2, total = nB * per;
+        for (int i0 = threadIdx.x; i0 < total; i0 += 4 * AMP_THREADS) {
+          v4f v[4];
+          GQ float* dstp[4];
+#pragma unroll
+          for (int a = 0; a < 4; ++a) {
+            const int idx = i0 + a * AMP_THREADS;
+            const int ii = idx < total ? idx : total - 1;
+            const int k = ii / per, j = (ii - k * per) << 2, m = M.bidx[k];
+            dstp[a] = idx < total ? pend + (long long)(count + k) * pd.stride + j : nullptr;
+            if (j < pd.Rp) {
+              v[a] = *(const LDSQ v4f*)(Y + k * ldy + j);   // ldy >= Rp, zero beyond R
+            } else {
+              const int lc = j - pd.Rp;
+              const bool in = lc < t.Cl;
+              const v4f xv = *(const GQ v4f*)(xbase + (in ? ((BR && lc >= t.segp) ? M.off1[m] + lc - t.segp : M.off0[m] + lc) : M.off0[m]));
+              v[a] = in ? xv : (v4f){0.f, 0.f, 0.f, 0.f};
+            }
+          }
+#pragma unroll
+          for (int a = 0; a < 4; ++a)
+            if (dstp[a]) *(GQ v4f*)dstp[a] = v[a];
         }
-        *(v4f*)(pd.base + (long long)(count + k) * pd.stride + j) = v;
       }
+      if ((int)threadIdx.x < R)
+        for (int k = 0; k < nB; ++k) accb += Y[k * ldy + threadIdx.x];
       PHASE(4);
-      tree_bwd_mfma<BR>((const LDSQ float*)Wl, t, (const LDSQ float*)Y, ldy, M, nB, obase);
-      __syncthreads();
+      tree_bwd_mfma<BR, NRBT, NCGT>(Wl, t, Y, M, nB, obase);
       PHASE(5);
     }
+    // every wave's HBM stores have landed before wave 0 publishes the batch
+    __syncthreads();
     // ---------------- joins and posts, one lane per message
     if (threadIdx.x < 64) {
       fence_release();
@@ -523,15 +760,18 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
     PHASE(6);
     count += nB;
     if ((int)count >= nd.muf) {
+      // the node's own update (Section 3): optimizer step on the LDS weights with the accumulated gradient
       tstep++;
-      mfma_update((LDSQ float*)Wl, (LDSQ float*)bl, &nd, t, pd.base, pd.stride, count, count, tstep, (LDSQ float*)Y);
+      tree_update_from_pend<NRBT, NCGT>(Wl, bl, &nd, t, pend, count, tstep, rowmap, colmap, accb);
+      accb = 0.f;
       count = 0;
       LOG(W->node, 2, 0, 0);
     }
-    __syncthreads();
+    lds_barrier();
     PHASE(7);
   }
-  tile_store(nd, t, Wl, bl);
+  tile_store(nd, t, Wg, bg);
+  if ((int)threadIdx.x < R && nd.has_bias) ndG[(long long)nd.rows * t.C + t.grow(threadIdx.x)] = accb;
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;
@@ -541,28 +781,42 @@ __device__ __noinline__ void role_tree_cell(const AmpDev* D, const WorkerDev* W)
 // ------------------------------------------------------------ output layer + loss at every node
 // The node where a forward message turns round (Section 4: the loss layer
 // initiates backpropagation).  The batch's h vectors are fetched into LDS
-// together; then one wave per message: logits, loss, d logits, W^T d logits,
-// and the (d logits, h) pair joins the node's pending gradients.
-__device__ __noinline__ void role_tree_out(const AmpDev* D, const WorkerDev* W) {
+// together; logits, softmax loss, d logits and W^T d logits are then computed
+// thread-parallel over (message, class) and (message, column).  The node's
+// gradient accumulator (n_class x H, spread over the threads) stays in
+// registers from one update to the next; between launches it rests in HBM.
+__device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
-  const NodeDev& nd = D->node[3];
+  const GQ NodeDev& nd = D->node[3];
   const Tile t = make_tile(nd, W);
   const TreeBufs B = tree_bufs(D);
-  const Pend pd = make_pend(W, t);
-  const int R = t.R, C = t.C, H = B.H, Hp = B.Hp, KB = W->kb;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, NW = AMP_THREADS >> 6;
+  const int R = t.R, C = t.C, H = B.H, Hp = B.Hp, KB = W->kb, ldw = t.ldw;
   Lds L{lds};
-  float* Wl = L.take(t.Rp * t.ldw);
-  float* bl = L.take(t.Rp);
-  float* hbuf = L.take(KB * Hp);           // per message: the node's h
-  float* zbuf = L.take(NW * 64);           // per wave: d logits
-  float* stage = L.take(UPD_STAGE * pd.stride);
-  int* done_cnt = (int*)L.take(D->mak);    // eval: nodes scored per slot
-  tile_load(nd, t, Wl, bl);
+  float* Wg = L.take(t.Rp * t.ldw);
+  float* bg = L.take(t.Rp);
+  LDSQ float* Wl = (LDSQ float*)Wg;
+  LDSQ float* bl = (LDSQ float*)bg;
+  LDSQ float* hbuf = (LDSQ float*)L.take(KB * Hp);    // per message: the node's h
+  LDSQ float* zbuf = (LDSQ float*)L.take(KB * 64);    // per message: logits, then d logits (R <= 64)
+  LDSQ int* done_cnt = (LDSQ int*)L.take(D->mak);     // eval: nodes scored per slot
+  tile_load(nd, t, Wg, bg);
   for (int i = threadIdx.x; i < D->mak; i += AMP_THREADS) done_cnt[i] = 0;
+  // this thread's accumulator elements e = threadIdx.x + 512 j (row e / C, column e % C), and the bias gradient of row threadIdx.x
+  GQ float* ndG = (GQ float*)nd.G;
+  constexpr int NE = 12;   // n_class * H <= 12 * 512
+  float gacc[NE], gb;
+  int er[NE], ec[NE];
+#pragma unroll
+  for (int j = 0; j < NE; ++j) {
+    const int e = threadIdx.x + AMP_THREADS * j;
+    er[j] = e < R * C ? e / C : -1;
+    ec[j] = e < R * C ? e - (e / C) * C : 0;
+    gacc[j] = er[j] >= 0 ? ndG[e] : 0.f;
+  }
+  gb = (int)threadIdx.x < R ? ndG[R * C + threadIdx.x] : 0.f;
   BatchMsg& M = s_M;
   __syncthreads();
-  const RingDev& mine = D->ring[W->ring];
+  const GQ RingDev& mine = D->ring[W->ring];
   unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   for (;;) {
@@ -584,74 +838,82 @@ __device__ __noinline__ void role_tree_out(const AmpDev* D, const WorkerDev* W) 
         M.L[k] = sm.y;
         M.aux[k] = 0;
         M.off0[k] = (int)(B.node(s, nn) * 2 * Hp);
+        M.dst0[k] = (int)(B.node(s, nn) * H);
       }
       batch_split_and_log(D, W, M, n, 3, D->train != 0);
     }
-    __syncthreads();
+    lds_barrier();
     for (int idx = threadIdx.x; idx < n * (Hp >> 2); idx += AMP_THREADS) {
       const int k = idx / (Hp >> 2), c = (idx - k * (Hp >> 2)) << 2;
-      *(v4f*)(hbuf + k * Hp + c) = *(const v4f*)(B.hc + M.off0[k] + c);
+      *(LDSQ v4f*)(hbuf + k * Hp + c) = *(const GQ v4f*)(B.hc + M.off0[k] + c);
     }
-    __syncthreads();
-    float* zw = zbuf + wave * 64;
-    for (int k = wave; k < n; k += NW) {
-      const int s = M.s[k], nn = M.n[k], label = M.a[k];
-      const float* hw = hbuf + k * Hp;
-      // logits: lane r keeps z_r
-      float zmine = -3.0e38f;
-      for (int r = 0; r < R; ++r) {
-        float a = 0.f;
-        for (int c = lane; c < C; c += 64) a = fmaf(Wl[r * t.ldw + c], hw[c], a);
-        for (int off = 32; off; off >>= 1) a += __shfl_xor(a, off);
-        if (lane == r) zmine = a + bl[r];
+    lds_barrier();
+    // logits z[k][r]
+    for (int idx = threadIdx.x; idx < n * R; idx += AMP_THREADS) {
+      const int k = idx / R, r = idx - k * R;
+      const LDSQ float* w = Wl + r * ldw;
+      const LDSQ float* h = hbuf + k * Hp;
+      float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+      int c = 0;
+      for (; c + 3 < C; c += 4) {
+        a0 = fmaf(w[c], h[c], a0);
+        a1 = fmaf(w[c + 1], h[c + 1], a1);
+        a2 = fmaf(w[c + 2], h[c + 2], a2);
+        a3 = fmaf(w[c + 3], h[c + 3], a3);
       }
-      float m = zmine;
-      int am = lane < R ? lane : 0x7fffffff;
-      for (int off = 32; off; off >>= 1) {
-        const float om = __shfl_xor(m, off);
-        const int oa = __shfl_xor(am, off);
-        if (om > m || (om == m && oa < am)) {
-          m = om;
-          am = oa;
-        }
-      }
-      const float e = lane < R ? expf(zmine - m) : 0.f;
-      float se = e;
-      for (int off = 32; off; off >>= 1) se += __shfl_xor(se, off);
-      const float zl = __shfl(zmine, label);
-      const float dz = e / se - (lane == label ? 1.f : 0.f);
-      zw[lane] = lane < R ? dz : 0.f;
-      if (lane == 0) {
-        const unsigned idx = M.seq[k] - D->first_seq;
-        atomicAdd(&D->loss_out[idx], -(zl - m - logf(se)));
-        if (am == label) atomicAdd(&D->correct_out[idx], 1);
-      }
-      if (!D->train) continue;
-      // dh = W^T dz, and the (dz, h) pair joins the pending gradients
-      float* go = B.gout + B.node(s, nn) * H;
-      for (int c = lane; c < C; c += 64) {
-        float a = 0.f;
-        for (int r = 0; r < R; ++r) a = fmaf(Wl[r * t.ldw + c], zw[r], a);
-        go[c] = a;
-      }
-      float* pe = pd.base + (long long)(count + k) * pd.stride;
-      for (int j = lane; j < pd.stride; j += 64) {
-        float v = 0.f;
-        if (j < pd.Rp) {
-          if (j < R) v = zw[j];
-        } else if (j - pd.Rp < C) {
-          v = hw[j - pd.Rp];
-        }
-        pe[j] = v;
-      }
+      for (; c < C; ++c) a0 = fmaf(w[c], h[c], a0);
+      zbuf[k * 64 + r] = ((a0 + a1) + (a2 + a3)) + bl[r];
     }
+    lds_barrier();
+    // softmax cross-entropy per message; z becomes dz = p - onehot(label)
+    if ((int)threadIdx.x < n) {
+      const int k = threadIdx.x, label = M.a[k];
+      LDSQ float* z = zbuf + k * 64;
+      float m = z[0];
+      int am = 0;
+      for (int r = 1; r < R; ++r)
+        if (z[r] > m) {
+          m = z[r];
+          am = r;
+        }
+      float se = 0.f;
+      for (int r = 0; r < R; ++r) se += expf(z[r] - m);
+      const float zl = z[label];
+      const float inv = 1.f / se;
+      for (int r = 0; r < R; ++r) z[r] = expf(z[r] - m) * inv - (r == label ? 1.f : 0.f);
+      const unsigned idx = M.seq[k] - D->first_seq;
+      __hip_atomic_fetch_add((GQ float*)&D->loss_out[idx], -(zl - m - logf(se)), __ATOMIC_RELAXED, AGENT);
+      if (am == label) __hip_atomic_fetch_add((GQ int*)&D->correct_out[idx], 1, __ATOMIC_RELAXED, AGENT);
+    }
+    if (D->train) {
+      lds_barrier();
+      // dh[k][c] = sum_r W[r][c] dz[k][r]
+      for (int idx = threadIdx.x; idx < n * C; idx += AMP_THREADS) {
+        const int k = idx / C, c = idx - k * C;
+        const LDSQ float* z = zbuf + k * 64;
+        float a = 0.f;
+        for (int r = 0; r < R; ++r) a = fmaf(Wl[r * ldw + c], z[r], a);
+        B.gout[M.dst0[k] + c] = a;
+      }
+      // G[r][c] += sum_k dz[k][r] h[k][c], messages in ring order
+#pragma unroll
+      for (int j = 0; j < NE; ++j)
+        if (er[j] >= 0) {
+          float a = gacc[j];
+          for (int k = 0; k < n; ++k) a = fmaf(zbuf[k * 64 + er[j]], hbuf[k * Hp + ec[j]], a);
+          gacc[j] = a;
+        }
+      if ((int)threadIdx.x < R)
+        for (int k = 0; k < n; ++k) gb += zbuf[k * 64 + threadIdx.x];
+    }
+    // every wave's HBM stores have landed before wave 0 publishes the batch
     __syncthreads();
     if (threadIdx.x < 64) {
       fence_release();
       const int k = threadIdx.x;
       if (k < n) {
         if (!D->train) {
-          if (atomicAdd(&done_cnt[M.s[k]], 1) + 1 == 2 * M.L[k] - 1) {
+          if (atomicAdd((int*)&done_cnt[M.s[k]], 1) + 1 == 2 * M.L[k] - 1) {
             done_cnt[M.s[k]] = 0;
             ring_post(D->ring[0], MSG_MAKE(1, M.s[k], 0));
           }
@@ -663,15 +925,32 @@ __device__ __noinline__ void role_tree_out(const AmpDev* D, const WorkerDev* W) 
     if (D->train) {
       count += n;
       if ((int)count >= nd.muf) {
+        // the node's own update (Section 3)
         tstep++;
-        mfma_update((LDSQ float*)Wl, (LDSQ float*)bl, &nd, t, pd.base, pd.stride, count, count, tstep, (LDSQ float*)stage);
+        const OptCoef o = opt_coef(nd, tstep);
+        const float inv = nd.mean ? 1.f / (float)count : 1.f;
+#pragma unroll
+        for (int j = 0; j < NE; ++j)
+          if (er[j] >= 0) {
+            const int li = er[j] * ldw + ec[j];
+            Wl[li] = opt_apply(o, Wl[li], gacc[j] * inv, nd.M, nd.V, (long long)er[j] * C + ec[j]);
+            gacc[j] = 0.f;
+          }
+        if ((int)threadIdx.x < R) {
+          bl[threadIdx.x] = opt_apply(o, bl[threadIdx.x], gb * inv, nd.M, nd.V, (long long)R * C + threadIdx.x);
+          gb = 0.f;
+        }
         count = 0;
         LOG(3, 2, 0, 0);
       }
     }
-    __syncthreads();
+    lds_barrier();
   }
-  tile_store(nd, t, Wl, bl);
+  tile_store(nd, t, Wg, bg);
+#pragma unroll
+  for (int j = 0; j < NE; ++j)
+    if (er[j] >= 0) ndG[threadIdx.x + AMP_THREADS * j] = gacc[j];
+  if ((int)threadIdx.x < R) ndG[R * C + threadIdx.x] = gb;
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;

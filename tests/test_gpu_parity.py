@@ -12,7 +12,12 @@ from util import check_controller_log, compare, gpu_train, oracle_replay
 pytestmark = pytest.mark.gpu
 
 SGD = dict(kind="sgd", lr=0.05)
-ADAM = dict(kind="adam", lr=0.002, beta1=0.9, beta2=0.999, eps=1e-8)
+# Adam's step lr * m / (sqrt(v) + eps) has slope lr / eps at a zero gradient: with the customary eps = 1e-8 an
+# fp32 rounding difference of 1e-9 in one near-zero gradient element moves that parameter by a full step, and a
+# single such element is enough to exceed 1e-5 in the norm.  The replay cases therefore use eps = 1e-6, which keeps
+# the optimizer's own amplification of rounding noise below the tolerance; the checker's Adam is pinned with the
+# customary eps against torch.optim.Adam in the CPU suite.
+ADAM = dict(kind="adam", lr=0.002, beta1=0.9, beta2=0.999, eps=1e-6)
 
 
 @pytest.mark.parametrize("mak,muf,opt", [(1, 1, SGD), (4, 1, SGD), (4, 3, ADAM), (8, 5, dict(kind="momentum", lr=0.02, momentum=0.9))])
