@@ -133,8 +133,17 @@ int amp_build_ggnn(amp_ctx *ctx, const amp_model_dims *dims);
 
 /* Splits a heavy node's rows over `n_tiles` workgroups that run in lockstep
  * (Section 5.1: a linear layer can be split into tiles computed in
- * parallel).  Only before amp_finalize; TREE leaf / branch nodes only. */
+ * parallel).  1..32 tiles.  Only before amp_finalize; TREE leaf / branch
+ * nodes only. */
 int amp_set_tiles(amp_ctx *ctx, int node_id, int n_tiles);
+/* Where a tiled node keeps its weights during a launch.  0 (default): in the
+ * LDS of its workgroups when a tile fits, otherwise in HBM; 1: in HBM always
+ * (the tiles read their rows from the parameter array as they go and update
+ * them in place -- the mode for cells whose weights exceed the CUs' LDS, such
+ * as hidden size 1024).  HBM mode needs emb and hidden to be multiples of 4
+ * and at most 512 rows per tile.  Only before amp_finalize; TREE leaf /
+ * branch nodes only. */
+int amp_set_weights_in_hbm(amp_ctx *ctx, int node_id, int on);
 
 /* Validates the graph, places nodes on workgroups and lays out the arena for
  * at most max_active_keys instances in flight, each at most max_instance_len

@@ -61,6 +61,7 @@ SIGNATURES = {
     "amp_build_treelstm": (ct.c_int, [_ctxp, ct.POINTER(ModelDims)]),
     "amp_build_ggnn": (ct.c_int, [_ctxp, ct.POINTER(ModelDims)]),
     "amp_set_tiles": (ct.c_int, [_ctxp, ct.c_int, ct.c_int]),
+    "amp_set_weights_in_hbm": (ct.c_int, [_ctxp, ct.c_int, ct.c_int]),
     "amp_finalize": (ct.c_int, [_ctxp, ct.c_int, ct.c_int, ct.c_int, ct.c_size_t]),
     "amp_set_max_active_keys": (ct.c_int, [_ctxp, ct.c_int]),
     "amp_set_min_update_frequency": (ct.c_int, [_ctxp, ct.c_int, ct.c_int]),
@@ -185,6 +186,9 @@ class Amp:
 
     def set_tiles(self, node, n):
         self._chk(self.L.amp_set_tiles(self.h, node, n))
+
+    def set_weights_in_hbm(self, node, on=True):
+        self._chk(self.L.amp_set_weights_in_hbm(self.h, node, int(on)))
 
     def finalize(self, max_active_keys, max_instance_len, max_edges, max_instances):
         self._chk(self.L.amp_finalize(self.h, max_active_keys, max_instance_len, max_edges, max_instances))

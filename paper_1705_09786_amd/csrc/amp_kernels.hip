@@ -429,9 +429,13 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
       const int rp = amp_round16(nd.nblocks * W->nu), cl = (nd.cols / nd.seg) * nd.segp;
       const bool fixed = rp == 96 && amp_round16(cl) == 304;
       if (W->role == ROLE_TREE_LEAF) {
-        if (fixed) role_tree_cell<false, 6, 19>(D, W); else role_tree_cell<false, 0, 0>(D, W);
+        if (W->aux) role_tree_cell<false, 0, 0, true>(D, W);
+        else if (fixed) role_tree_cell<false, 6, 19, false>(D, W);
+        else role_tree_cell<false, 0, 0, false>(D, W);
       } else {
-        if (fixed) role_tree_cell<true, 6, 19>(D, W); else role_tree_cell<true, 0, 0>(D, W);
+        if (W->aux) role_tree_cell<true, 0, 0, true>(D, W);
+        else if (fixed) role_tree_cell<true, 6, 19, false>(D, W);
+        else role_tree_cell<true, 0, 0, false>(D, W);
       }
       break;
     }

@@ -27,6 +27,7 @@ struct HostNode {
   std::string name;
   int rows = 0, cols = 0, has_bias = 0, nblocks = 1, block = 0;
   int muf = 1, opt = AMP_OPT_SGD, tiles = 1;
+  int in_hbm = 0;           // tiles read the weights from HBM even if they would fit LDS
   int seg = 0, segp = 0;    // column segments of the LDS layout (0 = one unpadded segment)
   int cl() const { return seg ? (cols / seg) * segp : cols; }
   amp_opt_params op{0.1f, 0.9f, 0.9f, 0.999f, 1e-8f};
@@ -171,6 +172,16 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
     case ROLE_TREE_BRANCH: {
       // the largest batch (a multiple of 16 messages) whose pre-activation rows fit beside the weights
       const size_t ldy = amp_ldrow((int)R);
+      if (w.aux) {
+        // weights stay in HBM: rows must be 16-byte aligned and unpadded
+        if (c->dims.hidden % 4 || c->dims.emb % 4) return 0;
+        for (w.kb = 64; w.kb >= 16; w.kb -= 16) {
+          f = r4(Rp) + r4((size_t)w.kb * ldy) + 2 * r4(Rp);
+          if (f <= avail) break;
+        }
+        if (w.kb < 16) return 0;
+        break;
+      }
       // the update's register accumulator holds 8 waves x 4 (16-row, 64-column) units
       if ((Rp / 16) * ((amp_round16(n.cl()) + 63) / 64) > 32) return 0;
       for (w.kb = 64; w.kb >= 16; w.kb -= 16) {
@@ -295,9 +306,21 @@ int amp_set_tiles(amp_ctx* c, int node_id, int n_tiles) {
   if (node_id < 0 || node_id >= (int)c->nodes.size()) return fail(c, AMP_EINVAL, "set_tiles: no node %d", node_id);
   if (c->model != AMP_MODEL_TREE || (node_id != 1 && node_id != 2))
     return fail(c, AMP_EUNSUPPORTED, "set_tiles: only the tree model's leaf and branch nodes can be tiled");
-  if (n_tiles < 1 || n_tiles > 16 || n_tiles > c->nodes[node_id].block)
-    return fail(c, AMP_EINVAL, "set_tiles: n_tiles must be in 1..min(16, hidden)");
+  if (n_tiles < 1 || n_tiles > 32 || n_tiles > c->nodes[node_id].block)
+    return fail(c, AMP_EINVAL, "set_tiles: n_tiles must be in 1..min(32, hidden)");
   c->nodes[node_id].tiles = n_tiles;
+  return AMP_OK;
+}
+
+int amp_set_weights_in_hbm(amp_ctx* c, int node_id, int on) {
+  if (!c) return AMP_EINVAL;
+  if (!c->model || c->finalized) return fail(c, AMP_ESTATE, "set_weights_in_hbm: only between build and finalize");
+  if (node_id < 0 || node_id >= (int)c->nodes.size()) return fail(c, AMP_EINVAL, "set_weights_in_hbm: no node %d", node_id);
+  if (c->model != AMP_MODEL_TREE || (node_id != 1 && node_id != 2))
+    return fail(c, AMP_EUNSUPPORTED, "set_weights_in_hbm: only the tree model's leaf and branch nodes");
+  if (on && (c->dims.hidden % 4 || c->dims.emb % 4))
+    return fail(c, AMP_EUNSUPPORTED, "set_weights_in_hbm: emb and hidden must be multiples of 4");
+  c->nodes[node_id].in_hbm = on ? 1 : 0;
   return AMP_OK;
 }
 
@@ -373,9 +396,15 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
   }
   if (c->workers.size() > AMP_MAX_WORKERS) return fail(c, AMP_EUNSUPPORTED, "finalize: too many workers");
   for (HostWorker& w : c->workers) {
-    const size_t need = lds_floats(c, w) * 4;
+    if ((w.role == ROLE_TREE_LEAF || w.role == ROLE_TREE_BRANCH) && c->nodes[w.node].in_hbm) w.aux = 1;
+    size_t need = lds_floats(c, w) * 4;
+    if ((need == 0 || need > AMP_DYN_LDS_BYTES) && (w.role == ROLE_TREE_LEAF || w.role == ROLE_TREE_BRANCH)) {
+      // a tile that cannot keep its rows in LDS reads them from HBM instead
+      w.aux = 1;
+      need = lds_floats(c, w) * 4;
+    }
     if (need == 0 || need > AMP_DYN_LDS_BYTES)
-      return fail(c, AMP_EUNSUPPORTED, "finalize: the worker for node %d tile %d does not fit %d bytes of LDS; use more tiles",
+      return fail(c, AMP_EUNSUPPORTED, "finalize: the worker for node %d tile %d fits neither %d bytes of LDS nor the streamed mode (sizes a multiple of 4, at most 512 rows per tile); use more tiles",
                   w.node, w.tile, AMP_DYN_LDS_BYTES);
   }
 

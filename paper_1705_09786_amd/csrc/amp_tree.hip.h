@@ -544,11 +544,208 @@ __device__ __noinline__ void tree_update_from_pend(LDSQ float* Wl, LDSQ float* b
   }
 }
 
+// ------------------------------------------------------------ products of a tile whose weights stay in HBM
+// For cells too large for the CUs' LDS (hidden size 1024: 12.6 MB and 41.9 MB
+// of weights) a tile keeps no copy of its rows: the products read them from
+// the node's parameter array (rows x cols, row-major, cols a multiple of 4) in
+// HBM / L2 as they go, and the update writes them back in place.  rowoff[lr] =
+// (node row of tile row lr) * cols, row 0 for the padding rows of the last
+// 16-row block, whose results are dropped or meet a zero delta.
+#define TREE_SG 10        // 16-column groups of input and weights held in registers at once
+
+// Y[j][r] = b[r] + sum_c W[r][c] x_j[c]; wave item = (16 messages, 16 weight rows).
+template <bool BR>
+__device__ __forceinline__ void tree_fwd_stream(const GQ float* P, const LDSQ int* rowoff, const Tile& t, const LDSQ float* bl,
+                                                const GQ float* xbase, const BatchMsg& M, int nF, LDSQ float* Y, int ldy) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  const int NRB = t.Rp >> 4, NCG = amp_round16(t.Cl) >> 4, NBF = (nF + 15) >> 4;
+  const v4f zero = {0.f, 0.f, 0.f, 0.f};
+  for (int item = wave; item < NBF * NRB; item += AMP_THREADS / 64) {
+    const int rb = item % NRB, nb = item / NRB;
+    int mi = nb * 16 + i;
+    if (mi > nF - 1) mi = nF - 1;
+    const int m = M.fidx[mi];
+    const GQ float* p0 = xbase + M.off0[m] + 4 * q;
+    const GQ float* p1 = xbase + M.off1[m] + 4 * q - t.segp;
+    const GQ float* wrow = P + rowoff[rb * 16 + i] + 4 * q;
+    v4f acc[4] = {zero, zero, zero, zero};
+    for (int c0 = 0; c0 < NCG; c0 += TREE_SG) {
+      v4f x[TREE_SG], w[TREE_SG];
+#pragma unroll
+      for (int g = 0; g < TREE_SG; ++g) {
+        const int lc = (c0 + g) * 16 + 4 * q;
+        const bool in = lc < t.Cl;
+        const v4f xv = *(const GQ v4f*)(in ? (BR && lc >= t.segp ? p1 : p0) + (c0 + g) * 16 : p0);
+        const v4f wv = *(const GQ v4f*)(in ? wrow + (c0 + g) * 16 : wrow);
+        x[g] = in ? xv : zero;
+        w[g] = wv;
+      }
+      asm volatile("" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]),
+                        "+v"(x[8]), "+v"(x[9]), "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]), "+v"(w[4]), "+v"(w[5]),
+                        "+v"(w[6]), "+v"(w[7]), "+v"(w[8]), "+v"(w[9]));
+#pragma unroll
+      for (int g = 0; g < TREE_SG; ++g) {
+        acc[0] = MFMA(w[g].x, x[g].x, acc[0]);
+        acc[1] = MFMA(w[g].y, x[g].y, acc[1]);
+        acc[2] = MFMA(w[g].z, x[g].z, acc[2]);
+        acc[3] = MFMA(w[g].w, x[g].w, acc[3]);
+      }
+    }
+    const v4f b4 = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
+    *(LDSQ v4f*)(Y + (nb * 16 + i) * ldy + rb * 16 + 4 * q) = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + b4;
+  }
+}
+
+// dx_j[c] = sum_r W[r][c] delta_j[r]; wave item = 16 weight columns for all NBB message blocks,
+// the tile's rows taken TREE_SG 16-row blocks at a time.
+template <bool BR, int NBB>
+__device__ __forceinline__ void tree_bwd_stream_blocks(const GQ float* P, const LDSQ int* rowoff, const Tile& t,
+                                                       const LDSQ float* Dl, int ldd, const BatchMsg& M, int nB, GQ float* obase) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  const int NRB = t.Rp >> 4, NCG = amp_round16(t.Cl) >> 4;
+  const v4f zero = {0.f, 0.f, 0.f, 0.f};
+  for (int cb = wave; cb < NCG; cb += AMP_THREADS / 64) {
+    const int lc = cb * 16 + 4 * q;
+    const int col = cb * 16 + i < t.Cl ? cb * 16 + i : 0;
+    const LDSQ float* dp = Dl + i * ldd + 4 * q;
+    v4f acc[NBB][2];
+#pragma unroll
+    for (int nb = 0; nb < NBB; ++nb) acc[nb][0] = acc[nb][1] = zero;
+    for (int g0 = 0; g0 < NRB; g0 += TREE_SG) {
+      float a[TREE_SG][4];
+#pragma unroll
+      for (int g = 0; g < TREE_SG; ++g) {
+        const int gg = g0 + g < NRB ? g0 + g : NRB - 1;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) a[g][v] = P[rowoff[gg * 16 + 4 * q + v] + col];
+      }
+#pragma unroll
+      for (int g = 0; g < TREE_SG; ++g)
+        asm volatile("" : "+v"(a[g][0]), "+v"(a[g][1]), "+v"(a[g][2]), "+v"(a[g][3]));
+#pragma unroll
+      for (int g = 0; g < TREE_SG; ++g)
+        if (g0 + g < NRB) {
+#pragma unroll
+          for (int nb = 0; nb < NBB; ++nb) {
+            const v4f d = *(const LDSQ v4f*)(dp + nb * 16 * ldd + 16 * (g0 + g));
+            acc[nb][0] = MFMA(a[g][0], d.x, acc[nb][0]);
+            acc[nb][1] = MFMA(a[g][1], d.y, acc[nb][1]);
+            acc[nb][0] = MFMA(a[g][2], d.z, acc[nb][0]);
+            acc[nb][1] = MFMA(a[g][3], d.w, acc[nb][1]);
+          }
+        }
+    }
+#pragma unroll
+    for (int nb = 0; nb < NBB; ++nb) {
+      const int mi = nb * 16 + i;
+      if (mi < nB && lc < t.Cl) {
+        const int m = M.bidx[mi];
+        GQ float* o = (BR && lc >= t.segp) ? obase + M.dst1[m] + (lc - t.segp) : obase + M.dst0[m] + lc;
+        *(GQ v4f*)o = acc[nb][0] + acc[nb][1];
+      }
+    }
+  }
+}
+
+template <bool BR>
+__device__ __forceinline__ void tree_bwd_stream(const GQ float* P, const LDSQ int* rowoff, const Tile& t, const LDSQ float* Dl,
+                                                int ldd, const BatchMsg& M, int nB, GQ float* obase) {
+  const int NBB = (nB + 15) >> 4;
+  if (NBB == 1)
+    tree_bwd_stream_blocks<BR, 1>(P, rowoff, t, Dl, ldd, M, nB, obase);
+  else if (NBB == 2)
+    tree_bwd_stream_blocks<BR, 2>(P, rowoff, t, Dl, ldd, M, nB, obase);
+  else if (NBB == 3)
+    tree_bwd_stream_blocks<BR, 3>(P, rowoff, t, Dl, ldd, M, nB, obase);
+  else
+    tree_bwd_stream_blocks<BR, 4>(P, rowoff, t, Dl, ldd, M, nB, obase);
+}
+
+// The update of a streamed tile: as tree_update_from_pend, in passes of 8 waves
+// x TREE_GU (16-row, 64-column) units, each pass re-reading the pending list;
+// the optimizer step goes to the parameter array in HBM.
+__device__ __noinline__ void tree_update_stream(GQ float* P, LDSQ float* bl, const GQ NodeDev* ndp, Tile t, const GQ float* pend,
+                                                unsigned count, unsigned tstep, const LDSQ int* rowmap, float gb) {
+  const GQ NodeDev& nd = *ndp;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  const int NRB = t.Rp >> 4, Rp = t.Rp, Cp = amp_round16(t.Cl), stride = Rp + Cp, CM = (Cp + 63) >> 6, NU = NRB * CM;
+  const v4f zero = {0.f, 0.f, 0.f, 0.f};
+  const OptCoef o = opt_coef(nd, tstep);
+  const float inv = nd.mean ? 1.f / (float)count : 1.f;
+  constexpr int NH = 4;
+  for (int u0 = 0; u0 < NU; u0 += 8 * TREE_GU) {
+    v4f g[TREE_GU][4];
+    int aoff[TREE_GU], xoff[TREE_GU];
+    bool xin[TREE_GU];
+#pragma unroll
+    for (int u = 0; u < TREE_GU; ++u) {
+      const int id = u0 + wave + 8 * u < NU ? u0 + wave + 8 * u : 0, cm = id / NRB, rb = id - cm * NRB, lc = cm * 64 + 4 * i;
+      aoff[u] = rb * 16 + i;
+      xin[u] = lc < Cp;
+      xoff[u] = Rp + (xin[u] ? lc : 0);
+#pragma unroll
+      for (int v = 0; v < 4; ++v) g[u][v] = zero;
+    }
+    for (unsigned k0 = 0; k0 < count; k0 += 4 * NH) {
+      float a[NH][TREE_GU];
+      v4f x[NH][TREE_GU];
+#pragma unroll
+      for (int h = 0; h < NH; ++h) {
+        const unsigned k = k0 + 4 * h + q;
+        const bool kin = k < count;
+        const GQ float* e = pend + (long long)(kin ? k : count - 1) * stride;
+#pragma unroll
+        for (int u = 0; u < TREE_GU; ++u) {
+          const float av = e[aoff[u]];
+          const v4f xv = *(const GQ v4f*)(e + xoff[u]);
+          a[h][u] = kin ? av : 0.f;
+          x[h][u] = xin[u] ? xv : zero;
+        }
+      }
+      asm volatile("" : "+v"(x[0][0]), "+v"(x[0][1]), "+v"(x[0][2]), "+v"(x[0][3]), "+v"(x[1][0]), "+v"(x[1][1]), "+v"(x[1][2]),
+                        "+v"(x[1][3]), "+v"(x[2][0]), "+v"(x[2][1]), "+v"(x[2][2]), "+v"(x[2][3]), "+v"(x[3][0]), "+v"(x[3][1]),
+                        "+v"(x[3][2]), "+v"(x[3][3]));
+#pragma unroll
+      for (int h = 0; h < NH; ++h)
+#pragma unroll
+        for (int u = 0; u < TREE_GU; ++u) {
+          g[u][0] = MFMA(a[h][u], x[h][u].x, g[u][0]);
+          g[u][1] = MFMA(a[h][u], x[h][u].y, g[u][1]);
+          g[u][2] = MFMA(a[h][u], x[h][u].z, g[u][2]);
+          g[u][3] = MFMA(a[h][u], x[h][u].w, g[u][3]);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < TREE_GU; ++u) {
+      const int id = u0 + wave + 8 * u, cm = id / NRB, rb = id - cm * NRB, lc = cm * 64 + 4 * i;
+      if (id < NU && lc < t.Cl) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int nr = rowmap[rb * 16 + 4 * q + e];
+          if (nr >= 0) {
+            const long long gi = (long long)nr * t.C + lc;
+            GQ v4f* wp = (GQ v4f*)(P + gi);
+            v4f wv = *wp;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) wv[v] = opt_apply(o, wv[v], g[u][v][e] * inv, nd.M, nd.V, gi + v);
+            *wp = wv;
+          }
+        }
+      }
+    }
+  }
+  if ((int)threadIdx.x < t.R && nd.has_bias) {
+    const int r = threadIdx.x;
+    bl[r] = opt_apply(o, bl[r], gb * inv, nd.M, nd.V, (long long)nd.rows * t.C + rowmap[r]);
+  }
+}
+
 // ------------------------------------------------------------ leaf / branch cells
 // BR = false: rows [i; o; u] over the embedding.
 // BR = true : rows [i; f_l; f_r; o; u] over [h_l; h_r].
 // NRBT / NCGT: the tile's 16-row blocks / 16-column groups when known at compile time, else 0.
-template <bool BR, int NRBT, int NCGT>
+// STREAM: the tile's weights stay in HBM (worker aux = 1) instead of LDS.
+template <bool BR, int NRBT, int NCGT, bool STREAM>
 __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
   const GQ NodeDev& nd = D->node[W->node];
@@ -559,17 +756,26 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
   const int R = t.R, H = B.H, Hp = B.Hp, nu = t.nu, u0 = t.u0, KB = W->kb;
   const int ldy = amp_ldrow(R);
   Lds L{lds};
-  float* Wg = L.take(t.Rp * t.ldw);
+  float* Wg = L.take(STREAM ? 0 : t.Rp * t.ldw);
   float* bg = L.take(t.Rp);
   LDSQ float* Wl = (LDSQ float*)Wg;
   LDSQ float* bl = (LDSQ float*)bg;
   const int yfloats = KB * ldy;
   LDSQ float* Y = (LDSQ float*)L.take(yfloats);   // forward: pre-activations; backward: deltas
   // node row of a tile row / node column of an LDS column (-1 = padding)
-  const int CMW = ((amp_round16(t.Cl) + 63) >> 6) << 6;
+  const int CMW = STREAM ? 0 : ((amp_round16(t.Cl) + 63) >> 6) << 6;
   LDSQ int* rowmap = (LDSQ int*)L.take(t.Rp);
   LDSQ int* colmap = (LDSQ int*)L.take(CMW);
-  tile_load(nd, t, Wg, bg);
+  LDSQ int* rowoff = (LDSQ int*)L.take(STREAM ? t.Rp : 0);   // streamed weights: node row * cols
+  GQ float* ndP = (GQ float*)nd.P;
+  if (STREAM) {
+    for (int i = threadIdx.x; i < t.Rp; i += AMP_THREADS) {
+      rowoff[i] = i < R ? t.grow(i) * t.C : 0;
+      bl[i] = (i < R && nd.has_bias) ? ndP[(long long)nd.rows * t.C + t.grow(i)] : 0.f;
+    }
+  } else {
+    tile_load(nd, t, Wg, bg);
+  }
   for (int i = threadIdx.x; i < yfloats; i += AMP_THREADS) Y[i] = 0.f;
   for (int i = threadIdx.x; i < t.Rp; i += AMP_THREADS) rowmap[i] = i < R ? t.grow(i) : -1;
   for (int i = threadIdx.x; i < CMW; i += AMP_THREADS) colmap[i] = t.ncol(i);
@@ -619,7 +825,10 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
     PHASE(0);
     // ---------------- forward messages of the batch
     if (nF > 0) {
-      tree_fwd_mfma<BR, NRBT, NCGT>(Wl, t, bl, xbase, M, nF, Y);
+      if (STREAM)
+        tree_fwd_stream<BR>(ndP, rowoff, t, bl, xbase, M, nF, Y, ldy);
+      else
+        tree_fwd_mfma<BR, NRBT, NCGT>(Wl, t, bl, xbase, M, nF, Y);
       lds_barrier();
       PHASE(1);
       for (int i = threadIdx.x; i < nF * nu; i += AMP_THREADS) {
@@ -736,7 +945,10 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
       if ((int)threadIdx.x < R)
         for (int k = 0; k < nB; ++k) accb += Y[k * ldy + threadIdx.x];
       PHASE(4);
-      tree_bwd_mfma<BR, NRBT, NCGT>(Wl, t, Y, M, nB, obase);
+      if (STREAM)
+        tree_bwd_stream<BR>(ndP, rowoff, t, Y, ldy, M, nB, obase);
+      else
+        tree_bwd_mfma<BR, NRBT, NCGT>(Wl, t, Y, M, nB, obase);
       PHASE(5);
     }
     // every wave's HBM stores have landed before wave 0 publishes the batch
@@ -762,7 +974,10 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
     if ((int)count >= nd.muf) {
       // the node's own update (Section 3): optimizer step on the LDS weights with the accumulated gradient
       tstep++;
-      tree_update_from_pend<NRBT, NCGT>(Wl, bl, &nd, t, pend, count, tstep, rowmap, colmap, accb);
+      if (STREAM)
+        tree_update_stream(ndP, bl, &nd, t, pend, count, tstep, rowmap, accb);
+      else
+        tree_update_from_pend<NRBT, NCGT>(Wl, bl, &nd, t, pend, count, tstep, rowmap, colmap, accb);
       accb = 0.f;
       count = 0;
       LOG(W->node, 2, 0, 0);
@@ -770,7 +985,12 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
     lds_barrier();
     PHASE(7);
   }
-  tile_store(nd, t, Wg, bg);
+  if (STREAM) {
+    __syncthreads();
+    if ((int)threadIdx.x < R && nd.has_bias) ndP[(long long)nd.rows * t.C + t.grow(threadIdx.x)] = bl[threadIdx.x];
+  } else {
+    tile_store(nd, t, Wg, bg);
+  }
   if ((int)threadIdx.x < R && nd.has_bias) ndG[(long long)nd.rows * t.C + t.grow(threadIdx.x)] = accb;
   if (threadIdx.x == 0) {
     W->wstate[0] = count;

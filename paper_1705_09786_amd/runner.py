@@ -21,7 +21,8 @@ class Trainer:
     """Owns a torch uint8 tensor as device arena and an Amp context in it."""
 
     def __init__(self, model: str, dims: dict, params, max_active_keys: int, max_len: int, max_edges: int,
-                 max_instances: int, arena_bytes: int = 1 << 30, tiles: dict | None = None, device: str = "cuda:0"):
+                 max_instances: int, arena_bytes: int = 1 << 30, tiles: dict | None = None, device: str = "cuda:0",
+                 in_hbm=()):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the AMP path has no CPU fallback")
@@ -34,6 +35,8 @@ class Trainer:
         self.amp.build(model, dims)
         for node, n in (tiles or {}).items():
             self.amp.set_tiles(node, n)
+        for node in in_hbm:
+            self.amp.set_weights_in_hbm(node, True)
         self.amp.finalize(max_active_keys, max_len, max_edges, max_instances)
         for k, v in enumerate(params):
             self.amp.set_params(k, v)

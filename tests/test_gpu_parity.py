@@ -85,6 +85,34 @@ def test_tree_replay_parity(dims, tiles, mak, muf, lmuf, opt, n):
     compare(g, rt, len(data))
 
 
+TREE_HBM = dict(vocab=97, emb=40, hidden=36, n_class=5)
+
+
+@pytest.mark.parametrize("tiles,mak,muf,opt,n", [({1: 2, 2: 3}, 8, 3, SGD, 64), ({1: 1, 2: 2}, 16, 5, ADAM, 64)])
+def test_tree_weights_in_hbm_replay_parity(tiles, mak, muf, opt, n):
+    """Leaf and branch tiles that read their rows from HBM as they go and update them in place (the mode for
+    cells too large for LDS), at sizes the checker replays in seconds: several tiles, ragged last row block."""
+    dims = TREE_HBM
+    data = synth.make_tree(n, 23, dims)
+    fp = synth.init_params("tree", dims, 8)
+    g = gpu_train("tree", dims, fp, data, mak, muf, opt, tiles=tiles, lookup_muf=7, in_hbm=(1, 2))
+    check_controller_log(g["logs"], mak, len(data))
+    rt = oracle_replay("tree", dims, fp, data, g["logs"], muf, opt, lookup_muf=7)
+    compare(g, rt, len(data))
+
+
+def test_tree_hidden_1024_replay_parity():
+    """The scale-up shape (hidden = embedding = 1024, weights streamed from HBM, leaf / branch split over 8 / 16
+    workgroups as the benchmark runs it) on a handful of trees the checker can still replay."""
+    dims = synth.DEFAULT_DIMS["tree_big"]
+    data = synth.make_tree(6, 31, dims, min_leaves=2, max_leaves=12)
+    fp = synth.init_params("tree", dims, 8)
+    g = gpu_train("tree", dims, fp, data, 4, 5, SGD, tiles={1: 8, 2: 16}, lookup_muf=9, arena_bytes=3 << 30)
+    check_controller_log(g["logs"], 4, len(data))
+    rt = oracle_replay("tree", dims, fp, data, g["logs"], 5, SGD, lookup_muf=9)
+    compare(g, rt, len(data))
+
+
 def test_tree_edge_shapes():
     """Single-leaf trees (the root is a leaf), two leaves, the maximum size,
     left and right combs, with repeated tokens inside a tree."""

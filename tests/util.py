@@ -19,9 +19,9 @@ def f32(x):
 
 
 def gpu_train(model, dims, fp, data, mak, muf, opt, epochs=1, log=True, tiles=None, watchdog=5.0,
-              arena_bytes=1 << 30, lookup_muf=None):
+              arena_bytes=1 << 30, lookup_muf=None, in_hbm=()):
     ml, me = runner.max_len_of(model, data)
-    tr = runner.Trainer(model, dims, fp, mak, ml, me, len(data), arena_bytes=arena_bytes, tiles=tiles)
+    tr = runner.Trainer(model, dims, fp, mak, ml, me, len(data), arena_bytes=arena_bytes, tiles=tiles, in_hbm=in_hbm)
     a = tr.amp
     a.set_watchdog(watchdog)
     a.set_min_update_frequency(-1, muf)
