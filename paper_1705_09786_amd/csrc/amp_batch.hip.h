@@ -153,7 +153,7 @@ __device__ __noinline__ void mfma_rows(const LDSQ float* Wl, int ldw, int NRB, i
     const v4f b4 = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
     *(LDSQ v4f*)(Y + (nb * 16 + i) * ldy + rb * 16 + 4 * q) = acc0 + acc1 + b4;
   }
-  __syncthreads();
+  lds_barrier();
 }
 
 // DX[j][c] = sum_r W[r][c] D[j][r]   (M = weight columns, N = messages, K = weight rows)
@@ -176,7 +176,7 @@ __device__ __noinline__ void mfma_cols(const LDSQ float* Wl, int ldw, int NRB, i
     }
     *(LDSQ v4f*)(DX + (nb * 16 + i) * ldx + cb * 16 + 4 * q) = acc0 + acc1;
   }
-  __syncthreads();
+  lds_barrier();
 }
 
 // ---------------------------------------------------------------- pending gradients

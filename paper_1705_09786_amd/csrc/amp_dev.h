@@ -118,6 +118,13 @@ struct DataDev {
   const int* etype;
   const int* tcount;       // [n_inst][8] directed edges per edge type
   const int* tnode;        // tree: [nodes][4] = left, right, parent*2+side (-1 root), label; indexed like left
+  // graph adjacency, precomputed per instance (N nodes, E directed edges, T edge types):
+  const int* inoff;        // [tok_off[i] + i + v], v = 0..N: start of node v's incoming edges in inedge (relative to edge_off[i])
+  const int* inedge;       // [edge_off[i] + .]: incoming edges grouped by destination, ascending edge index inside a group
+  const int* tstart;       // [i][9]: start of each type's block in tedge / tsk (prefix sums of tcount)
+  const int* tedge;        // [edge_off[i] + tstart[c] + k]: k-th edge of type c, ascending edge index
+  const int* tsoff;        // [T * (tok_off[i] + i) + c * (N + 1) + v]: start of the type-c edges leaving node v, in tsk
+  const int* tsk;          // [edge_off[i] + tstart[c] + .]: positions k (rows of the type-c group) grouped by source node
 };
 
 struct AmpDev {

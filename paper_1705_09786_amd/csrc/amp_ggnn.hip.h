@@ -6,51 +6,60 @@
 // edge linear (Group by edge type), all graph nodes for the GRU nodes (the
 // final Group over nodes), so each node sees one forward and one backward
 // message per instance and propagation step and performs a small
-// (rows x cols) x (k rows) product.  Broadcast / Ungroup / Flatmap / Group /
-// sum between them are index arithmetic over the instance's edge list plus
-// arrival counters.
+// (rows x cols) x (k rows) product on the matrix cores.  Broadcast / Ungroup /
+// Flatmap / Group / sum between them are index arithmetic over adjacency
+// tables the host prepared per instance (incoming edges by destination, a
+// type's edges in ascending order, a type's edges by source), plus arrival
+// counters.  Sums over a variable number of parts (messages into a node,
+// gradients back to a source node, Bcast backward) are formed by the worker
+// that consumes them, always in the same order: ascending edge index; edge
+// types ascending, then update gate, reset gate, candidate.
 //
 // Slot storage (s = slot, it = step, v = graph node, e = directed edge):
 //   buf[0]  Hm  [s][S+1][N][H]  node states before each step (Hm[.][0] = lookup output)
-//   buf[1]  A   [s][S][N][H]    aggregated messages (GRU input)
+//   buf[1]  A   [s][S][N][H]    aggregated messages (GRU input), recorded by the update gate
 //   buf[2]  Z   [s][S][N][H]    update gate
 //   buf[3]  Rr  [s][S][N][H]    reset gate
 //   buf[4]  Ht  [s][S][N][H]    candidate state
 //   buf[5]  Msg [s][E][H]       per-edge messages of the running step
-//   buf[6]  gH  [s][N][H]       gradient w.r.t. the states leaving the running step
+//   buf[6]  gH  [s][N][H]       gradient w.r.t. the final states (from the readout)
 //   buf[7]  dZ  [s][N][H]       pre-activation gradient for the update-gate node
 //   buf[8]  dR  [s][N][H]       pre-activation gradient for the reset-gate node
 //   buf[9]  dA  [s][3][N][H]    gradient w.r.t. A from candidate / update / reset nodes
 //   buf[10] dHp [s][3][N][H]    gradient w.r.t. h from the same three
 //   buf[11] dHe [s][T][N][H]    gradient w.r.t. h through the edges, per edge type
-//   buf[12] dAs [s][N][H]       summed gradient w.r.t. A
 //   buf[13] cnt [s][8] (int)    arrival counters
 #pragma once
 
 struct GView {
   int inst, N, E;
-  const int *type, *src, *dst, *et, *tcount;
+  const GQ int *type, *src, *dst, *tcount, *inoff, *inedge, *tstart, *tedge, *tsoff, *tsk;
   float target;
 };
 
 __device__ __forceinline__ GView g_view(const GQ AmpDev* D, unsigned seq) {
   GView v;
   v.inst = seq % D->data.n_inst;
-  const int to = D->data.tok_off[v.inst], eo = D->data.edge_off[v.inst];
-  v.N = D->data.tok_off[v.inst + 1] - to;
-  v.E = D->data.edge_off[v.inst + 1] - eo;
-  v.type = D->data.tok + to;
-  v.src = D->data.src + eo;
-  v.dst = D->data.dst + eo;
-  v.et = D->data.etype + eo;
-  v.tcount = D->data.tcount + v.inst * 8;
-  v.target = D->data.target[v.inst];
+  const int to = ((const GQ int*)D->data.tok_off)[v.inst], eo = ((const GQ int*)D->data.edge_off)[v.inst];
+  v.N = ((const GQ int*)D->data.tok_off)[v.inst + 1] - to;
+  v.E = ((const GQ int*)D->data.edge_off)[v.inst + 1] - eo;
+  v.type = (const GQ int*)D->data.tok + to;
+  v.src = (const GQ int*)D->data.src + eo;
+  v.dst = (const GQ int*)D->data.dst + eo;
+  v.tcount = (const GQ int*)D->data.tcount + v.inst * 8;
+  v.inoff = (const GQ int*)D->data.inoff + to + v.inst;
+  v.inedge = (const GQ int*)D->data.inedge + eo;
+  v.tstart = (const GQ int*)D->data.tstart + v.inst * 9;
+  v.tedge = (const GQ int*)D->data.tedge + eo;
+  v.tsoff = (const GQ int*)D->data.tsoff + (long long)D->n_edge_types * (to + v.inst);
+  v.tsk = (const GQ int*)D->data.tsk + eo;
+  v.target = ((const GQ float*)D->data.target)[v.inst];
   return v;
 }
 
 struct GBufs {
-  float *Hm, *A, *Z, *Rr, *Ht, *Msg, *gH, *dZ, *dR, *dA, *dHp, *dHe, *dAs;
-  int* cnt;
+  GQ float *Hm, *A, *Z, *Rr, *Ht, *Msg, *gH, *dZ, *dR, *dA, *dHp, *dHe;
+  GQ int* cnt;
   int H, N, Em, S, T;
   __device__ __forceinline__ long long st(int s, int it) const { return ((long long)s * S + it) * N * H; }
   __device__ __forceinline__ long long hm(int s, int it) const { return ((long long)s * (S + 1) + it) * N * H; }
@@ -59,20 +68,19 @@ struct GBufs {
 
 __device__ __forceinline__ GBufs g_bufs(const GQ AmpDev* D) {
   GBufs b;
-  b.Hm = (float*)D->buf[0];
-  b.A = (float*)D->buf[1];
-  b.Z = (float*)D->buf[2];
-  b.Rr = (float*)D->buf[3];
-  b.Ht = (float*)D->buf[4];
-  b.Msg = (float*)D->buf[5];
-  b.gH = (float*)D->buf[6];
-  b.dZ = (float*)D->buf[7];
-  b.dR = (float*)D->buf[8];
-  b.dA = (float*)D->buf[9];
-  b.dHp = (float*)D->buf[10];
-  b.dHe = (float*)D->buf[11];
-  b.dAs = (float*)D->buf[12];
-  b.cnt = (int*)D->buf[13];
+  b.Hm = (GQ float*)D->buf[0];
+  b.A = (GQ float*)D->buf[1];
+  b.Z = (GQ float*)D->buf[2];
+  b.Rr = (GQ float*)D->buf[3];
+  b.Ht = (GQ float*)D->buf[4];
+  b.Msg = (GQ float*)D->buf[5];
+  b.gH = (GQ float*)D->buf[6];
+  b.dZ = (GQ float*)D->buf[7];
+  b.dR = (GQ float*)D->buf[8];
+  b.dA = (GQ float*)D->buf[9];
+  b.dHp = (GQ float*)D->buf[10];
+  b.dHe = (GQ float*)D->buf[11];
+  b.cnt = (GQ int*)D->buf[13];
   b.H = D->hidden;
   b.N = D->max_len;
   b.Em = D->max_edges;
@@ -100,16 +108,73 @@ __device__ __forceinline__ void g_post_edges(const GQ AmpDev* D, const GView& v,
     if (v.tcount[c] > 0) ring_post(D->ring[GR_EDGE0 + c], MSG_MAKE(backward, s, it));
 }
 
+// Gradient w.r.t. element i of the states that entered a step whose backward
+// pass has finished: Bcast / Flatmap backward over the edge types present
+// (ascending), the update gate, the reset gate and the candidate.
+__device__ __forceinline__ float g_state_gradient(const GBufs& B, const GView& v, int s, int i) {
+  const long long NH = (long long)B.N * B.H;
+  const GQ float* he = B.dHe + (long long)s * B.T * NH + i;
+  const GQ float* hp = B.dHp + (long long)s * 3 * NH + i;
+  float a = 0.f;
+  for (int c = 0; c < B.T; ++c)
+    if (v.tcount[c] > 0) a += he[c * NH];
+  a += hp[NH] + hp[2 * NH];
+  a += hp[0];
+  return a;
+}
+
+// LDS pieces every dense graph worker carves: weight tile, bias, row / column maps for the update.
+struct GTile {
+  float *Wg, *bg;
+  LDSQ float *Wl, *bl;
+  LDSQ int *rowmap, *colmap;
+};
+
+__device__ __forceinline__ GTile g_tile_setup(Lds& L, const GQ NodeDev& nd, const Tile& t) {
+  GTile g;
+  g.Wg = L.take(t.Rp * t.ldw);
+  g.bg = L.take(t.Rp);
+  g.Wl = (LDSQ float*)g.Wg;
+  g.bl = (LDSQ float*)g.bg;
+  const int CMW = ((amp_round16(t.Cl) + 63) >> 6) << 6;
+  g.rowmap = (LDSQ int*)L.take(t.Rp);
+  g.colmap = (LDSQ int*)L.take(CMW);
+  tile_load(nd, t, g.Wg, g.bg);
+  for (int i = threadIdx.x; i < t.Rp; i += AMP_THREADS) g.rowmap[i] = i < t.R ? t.grow(i) : -1;
+  for (int i = threadIdx.x; i < CMW; i += AMP_THREADS) g.colmap[i] = t.ncol(i);
+  return g;
+}
+
+// Appends K (delta, input) rows held in LDS to the worker's pending list in HBM and adds the delta rows to the
+// bias gradient of row threadIdx.x.
+__device__ __forceinline__ void g_pend_append(GQ float* pend, int Rp, int stride, unsigned first, const LDSQ float* Dl, int ldd,
+                                              int R, const LDSQ float* X, int ldx, int C, int K, float& gb) {
+  for (int i = threadIdx.x; i < K * stride; i += AMP_THREADS) {
+    const int k = i / stride, j = i - k * stride;
+    float v = 0.f;
+    if (j < Rp) {
+      if (j < R) v = Dl[k * ldd + j];
+    } else if (j - Rp < C) {
+      v = X[k * ldx + j - Rp];
+    }
+    pend[(long long)(first + k) * stride + j] = v;
+  }
+  if ((int)threadIdx.x < R)
+    for (int k = 0; k < K; ++k) gb += Dl[k * ldd + threadIdx.x];
+}
+
 // Counts one gradient (a grouped message of K rows already appended to the
 // pending list) and updates when min_update_frequency is reached.
 __device__ __forceinline__ void g_count_and_update(const GQ AmpDev* D, const GQ WorkerDev* W, const GQ NodeDev& nd, const Tile& t,
-                                                   float* Wl, float* bl, const Pend& pd, unsigned& count,
-                                                   unsigned& nrows, unsigned& tstep, int K, float* stage) {
+                                                   const GTile& g, const GQ float* pend, unsigned& count, unsigned& nrows,
+                                                   unsigned& tstep, int K, float& gb) {
   count++;
   nrows += K;
   if ((int)count >= nd.muf) {
     tstep++;
-    mfma_update((LDSQ float*)Wl, (LDSQ float*)bl, &nd, t, pd.base, pd.stride, count, nrows, tstep, (LDSQ float*)stage);
+    __syncthreads();   // the appended rows of every wave are in HBM
+    tree_update_from_pend<0, 0>(g.Wl, g.bl, &nd, t, pend, nrows, count, tstep, g.rowmap, g.colmap, gb);
+    gb = 0.f;
     count = 0;
     nrows = 0;
     LOG(W->node, 2, 0, 0);
@@ -122,8 +187,11 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
   const GQ NodeDev& lk = D->node[0];
   const GBufs B = g_bufs(D);
   const int H = B.H, V = D->n_node_types;
-  float* El = lds;
-  for (int i = threadIdx.x; i < V * H; i += AMP_THREADS) El[i] = lk.P[i];
+  LDSQ float* El = (LDSQ float*)lds;
+  LDSQ float* gt = El + ((V * H + 3) & ~3);   // [N][H] gradient w.r.t. the lookup's output
+  GQ float* lkP = (GQ float*)lk.P;
+  GQ float* lkG = (GQ float*)lk.G;
+  for (int i = threadIdx.x; i < V * H; i += AMP_THREADS) El[i] = lkP[i];
   __syncthreads();
   const GQ RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
@@ -133,7 +201,7 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
     const unsigned seq = D->slot_seq[s];
     const GView v = g_view(D, seq);
     if (!(code & MSG_DIR_B)) {
-      float* h0 = B.Hm + B.hm(s, 0);
+      GQ float* h0 = B.Hm + B.hm(s, 0);
       for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) {
         const int n = i / H, j = i - n * H;
         h0[i] = El[v.type[n] * H + j];
@@ -147,9 +215,10 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
       continue;
     }
     // backward: scatter-add the rows into the table's accumulator, node by node
-    const float* g = B.gH + B.sl(s);
+    for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) gt[i] = g_state_gradient(B, v, s, i);
+    lds_barrier();
     for (int j = threadIdx.x; j < H; j += AMP_THREADS)
-      for (int n = 0; n < v.N; ++n) lk.G[v.type[n] * H + j] += g[n * H + j];
+      for (int n = 0; n < v.N; ++n) lkG[v.type[n] * H + j] += gt[n * H + j];
     LOG(0, 1, seq, 0);
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -161,8 +230,8 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
       tstep++;
       const float sc = lk.lr * (lk.mean ? 1.f / (float)count : 1.f);
       for (int i = threadIdx.x; i < V * H; i += AMP_THREADS) {
-        El[i] -= sc * lk.G[i];
-        lk.G[i] = 0.f;
+        El[i] -= sc * lkG[i];
+        lkG[i] = 0.f;
       }
       __syncthreads();
       count = 0;
@@ -170,7 +239,7 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < V * H; i += AMP_THREADS) lk.P[i] = El[i];
+  for (int i = threadIdx.x; i < V * H; i += AMP_THREADS) lkP[i] = El[i];
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;
@@ -184,125 +253,98 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
   const Pend pd = make_pend(W, t);
+  GQ float* pend = (GQ float*)pd.base;
   const int H = B.H, ctype = W->aux, Ep = amp_round16(B.Em), Hs = amp_ldrow(H);
   const int NRB = t.Rp >> 4, NCG = amp_round16(H) >> 4;
   Lds L{lds};
-  float* Wl = L.take(t.Rp * t.ldw);
-  float* bl = L.take(t.Rp);
-  const int xfloats = Ep * Hs > UPD_STAGE * pd.stride ? Ep * Hs : UPD_STAGE * pd.stride;
-  float* X = L.take(xfloats);     // inputs h_src; later the products W^T delta; staging at updates
-  float* Y = L.take(Ep * Hs);     // outputs / deltas
-  float* acc = L.take(B.N * H);
-  int* elist = (int*)L.take(B.Em);
-  tile_load(nd, t, Wl, bl);
-  for (int i = threadIdx.x; i < xfloats; i += AMP_THREADS) X[i] = 0.f;
-  for (int i = threadIdx.x; i < Ep * Hs; i += AMP_THREADS) Y[i] = 0.f;
+  const GTile g = g_tile_setup(L, nd, t);
+  LDSQ float* X = (LDSQ float*)L.take(Ep * Hs);     // inputs h_src; later the products W^T delta
+  LDSQ float* Y = (LDSQ float*)L.take(Ep * Hs);     // outputs / deltas
+  for (int i = threadIdx.x; i < Ep * Hs; i += AMP_THREADS) X[i] = Y[i] = 0.f;
+  GQ float* ndG = (GQ float*)nd.G;
+  float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
   __syncthreads();
   const GQ RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
-  __shared__ int s_k, s_last, s_lastb;
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
     const unsigned seq = D->slot_seq[s];
     const GView v = g_view(D, seq);
-    // edges of this type, ascending (Group orders its rows by edge index)
-    if (threadIdx.x == 0) {
-      int k = 0;
-      for (int e = 0; e < v.E; ++e)
-        if (v.et[e] == ctype) elist[k++] = e;
-      s_k = k;
-    }
-    __syncthreads();
-    const int K = s_k, NB = (K + 15) >> 4;
-    const float* h = B.Hm + B.hm(s, it);
+    const int K = v.tcount[ctype], NB = (K + 15) >> 4;
+    const GQ int* te = v.tedge + v.tstart[ctype];   // edges of this type, ascending (Group orders its rows by edge index)
+    const GQ float* h = B.Hm + B.hm(s, it);
+    const int nact = g_active_types(v, B.T);
     for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
       const int k = i / Hs, j = i - k * Hs;
-      X[i] = j < H ? h[v.src[elist[k]] * H + j] : 0.f;   // padding columns of a used row are zero
+      X[i] = j < H ? h[v.src[te[k]] * H + j] : 0.f;   // padding columns of a used row are zero
     }
-    __syncthreads();
-    const int nact = g_active_types(v, B.T);
     if (!(code & MSG_DIR_B)) {
-      mfma_rows((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)bl, (LDSQ float*)X, Hs, NB, (LDSQ float*)Y, Hs);
-      float* msg = B.Msg + (long long)s * B.Em * H;
+      lds_barrier();
+      mfma_rows(g.Wl, t.ldw, NRB, NCG, g.bl, X, Hs, NB, Y, Hs);
+      GQ float* msg = B.Msg + (long long)s * B.Em * H;
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
         const int k = i / H, j = i - k * H;
-        msg[elist[k] * H + j] = Y[k * Hs + j];
+        msg[te[k] * H + j] = Y[k * Hs + j];
       }
       LOG(W->node, 0, seq, it);
       __syncthreads();
       if (threadIdx.x == 0) {
         fence_release();
-        s_last = join_arrive(B.cnt + s * 8 + 0, nact);
-      }
-      __syncthreads();
-      if (s_last) {
-        // Ungroup, regroup by target node, sum: a_v = sum over incoming edges in edge order
-        float* A = B.A + B.st(s, it);
-        for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) {
-          const int n = i / H, j = i - n * H;
-          float a = 0.f;
-          for (int e = 0; e < v.E; ++e)
-            if (v.dst[e] == n) a += msg[e * H + j];
-          A[i] = a;
-        }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-          fence_release();
+        // the last type to arrive completes the step's messages; Ungroup, regrouping by target node and the sum are the GRU nodes' part
+        if (join_arrive(B.cnt + s * 8 + 0, nact)) {
           ring_post(D->ring[GR_GZ(D)], MSG_MAKE(0, s, it));
           ring_post(D->ring[GR_GR(D)], MSG_MAKE(0, s, it));
         }
       }
       continue;
     }
-    // ---- backward: delta_e = dA[dst(e)]; dh_src(e) += W^T delta_e; one gradient for the group
-    const float* dAs = B.dAs + B.sl(s);
-    for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
-      const int k = i / Hs, j = i - k * Hs;
-      Y[i] = j < H ? dAs[v.dst[elist[k]] * H + j] : 0.f;
+    // ---- backward: delta_e = dA[dst(e)] (Bcast backward on A: (update + reset) + candidate); one gradient for the group
+    {
+      const long long NH = (long long)B.N * H;
+      const GQ float* dA = B.dA + (long long)s * 3 * NH;
+      for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
+        const int k = i / Hs, j = i - k * Hs;
+        float d = 0.f;
+        if (j < H) {
+          const long long o = (long long)v.dst[te[k]] * H + j;
+          d = (dA[NH + o] + dA[2 * NH + o]) + dA[o];
+        }
+        Y[i] = d;
+      }
     }
-    for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) acc[i] = 0.f;
-    __syncthreads();
+    lds_barrier();
     LOG(W->node, 1, seq, it);
-    pend_append(pd, nrows, Y, Hs, H, X, Hs, H, K);
-    __syncthreads();
-    mfma_cols((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)Y, Hs, NB, (LDSQ float*)X, Hs);
-    for (int j = threadIdx.x; j < H; j += AMP_THREADS)
-      for (int k = 0; k < K; ++k) acc[v.src[elist[k]] * H + j] += X[k * Hs + j];
-    __syncthreads();
-    float* dHe = B.dHe + ((long long)s * B.T + ctype) * B.N * H;
-    for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) dHe[i] = acc[i];
+    g_pend_append(pend, pd.Rp, pd.stride, nrows, Y, Hs, H, X, Hs, H, K, gb);
+    lds_barrier();
+    mfma_cols(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Hs);
+    // dh_src += W^T delta_e: per source node, its edges of this type in ascending order
+    {
+      GQ float* dHe = B.dHe + ((long long)s * B.T + ctype) * B.N * H;
+      const GQ int* so = v.tsoff + ctype * (v.N + 1);
+      const GQ int* sk = v.tsk + v.tstart[ctype];
+      for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) {
+        const int n = i / H, j = i - n * H;
+        float a = 0.f;
+        for (int p = so[n]; p < so[n + 1]; ++p) a += X[sk[p] * Hs + j];
+        dHe[i] = a;
+      }
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
       fence_release();
-      s_lastb = join_arrive(B.cnt + s * 8 + 3, nact);
-    }
-    __syncthreads();
-    if (s_lastb) {
-      // Flatmap / Bcast backward: total gradient w.r.t. the states entering this step
-      float* gH = B.gH + B.sl(s);
-      const float* dHp = B.dHp + (long long)s * 3 * B.N * H;
-      const float* all = B.dHe + (long long)s * B.T * B.N * H;
-      for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) {
-        float a = 0.f;
-        for (int c = 0; c < B.T; ++c)
-          if (v.tcount[c] > 0) a += all[(long long)c * B.N * H + i];
-        a += dHp[B.N * H + i] + dHp[2 * B.N * H + i];
-        a += dHp[i];
-        gH[i] = a;
-      }
-      __syncthreads();
-      if (threadIdx.x == 0) {
-        fence_release();
+      if (join_arrive(B.cnt + s * 8 + 3, nact)) {
         if (it > 0)
           ring_post(D->ring[GR_GH(D)], MSG_MAKE(1, s, it - 1));
         else
           ring_post(D->ring[GR_LOOKUP], MSG_MAKE(1, s, 0));
       }
     }
-    g_count_and_update(D, W, nd, t, Wl, bl, pd, count, nrows, tstep, K, X);
+    g_count_and_update(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
+    lds_barrier();
   }
-  tile_store(nd, t, Wl, bl);
+  tile_store(nd, t, g.Wg, g.bg);
+  if ((int)threadIdx.x < t.R) ndG[(long long)nd.rows * t.C + threadIdx.x] = gb;
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;
@@ -317,38 +359,45 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
   const Pend pd = make_pend(W, t);
+  GQ float* pend = (GQ float*)pd.base;
   const int H = B.H, C = 2 * H, Np = amp_round16(B.N), which = W->aux, Hs = amp_ldrow(H), Cs = amp_ldrow(C);
   const int NRB = t.Rp >> 4, NCG = amp_round16(C) >> 4;
   Lds L{lds};
-  float* Wl = L.take(t.Rp * t.ldw);
-  float* bl = L.take(t.Rp);
-  const int xfloats = Np * Cs > UPD_STAGE * pd.stride ? Np * Cs : UPD_STAGE * pd.stride;
-  float* X = L.take(xfloats);     // inputs; later W^T delta; staging at updates
-  float* Y = L.take(Np * Hs);
-  float* DX = X;
-  tile_load(nd, t, Wl, bl);
-  for (int i = threadIdx.x; i < xfloats; i += AMP_THREADS) X[i] = 0.f;
+  const GTile g = g_tile_setup(L, nd, t);
+  LDSQ float* X = (LDSQ float*)L.take(Np * Cs);     // inputs; later W^T delta
+  LDSQ float* Y = (LDSQ float*)L.take(Np * Hs);
+  for (int i = threadIdx.x; i < Np * Cs; i += AMP_THREADS) X[i] = 0.f;
   for (int i = threadIdx.x; i < Np * Hs; i += AMP_THREADS) Y[i] = 0.f;
+  GQ float* ndG = (GQ float*)nd.G;
+  float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
   __syncthreads();
   const GQ RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
-  __shared__ int s_last;
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
     const unsigned seq = D->slot_seq[s];
     const GView v = g_view(D, seq);
-    const int K = v.N;
-    const float* A = B.A + B.st(s, it);
-    const float* h = B.Hm + B.hm(s, it);
-    for (int i = threadIdx.x; i < K * Cs; i += AMP_THREADS) {
-      const int k = i / Cs, c = i - k * Cs;
-      X[i] = c < H ? A[k * H + c] : c < C ? h[k * H + c - H] : 0.f;   // padding columns of a used row are zero
-    }
-    __syncthreads();
-    float* outp = (which == 0 ? B.Z : B.Rr) + B.st(s, it);
+    const int K = v.N, NB = (K + 15) >> 4;
+    GQ float* A = B.A + B.st(s, it);
+    const GQ float* h = B.Hm + B.hm(s, it);
+    GQ float* outp = (which == 0 ? B.Z : B.Rr) + B.st(s, it);
     if (!(code & MSG_DIR_B)) {
-      mfma_rows((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)bl, (LDSQ float*)X, Cs, (K + 15) >> 4, (LDSQ float*)Y, Hs);
+      // Ungroup, regroup by target node, sum: a_v = sum over incoming edges in edge order
+      const GQ float* msg = B.Msg + (long long)s * B.Em * H;
+      for (int i = threadIdx.x; i < K * Cs; i += AMP_THREADS) {
+        const int k = i / Cs, c = i - k * Cs;
+        float x = 0.f;   // padding columns of a used row are zero
+        if (c < H) {
+          for (int p = v.inoff[k]; p < v.inoff[k + 1]; ++p) x += msg[v.inedge[p] * H + c];
+          if (which == 0) A[k * H + c] = x;   // the recorded activation, read again by all three GRU nodes
+        } else if (c < C) {
+          x = h[k * H + c - H];
+        }
+        X[i] = x;
+      }
+      lds_barrier();
+      mfma_rows(g.Wl, t.ldw, NRB, NCG, g.bl, X, Cs, NB, Y, Hs);
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) outp[i] = sigmoidf_(Y[(i / H) * Hs + i % H]);
       LOG(W->node, 0, seq, it);
       __syncthreads();
@@ -358,46 +407,40 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       }
       continue;
     }
-    const float* dpre = (which == 0 ? B.dZ : B.dR) + B.sl(s);
+    const GQ float* dpre = (which == 0 ? B.dZ : B.dR) + B.sl(s);
+    for (int i = threadIdx.x; i < K * Cs; i += AMP_THREADS) {
+      const int k = i / Cs, c = i - k * Cs;
+      X[i] = c < H ? A[k * H + c] : c < C ? h[k * H + c - H] : 0.f;
+    }
     for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
       const int k = i / Hs, j = i - k * Hs;
       Y[i] = j < H ? dpre[k * H + j] : 0.f;
     }
-    __syncthreads();
+    lds_barrier();
     LOG(W->node, 1, seq, it);
-    pend_append(pd, nrows, Y, Hs, H, X, Cs, C, K);
-    __syncthreads();
-    mfma_cols((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)Y, Hs, (K + 15) >> 4, (LDSQ float*)DX, Cs);
-    float* dA = B.dA + ((long long)s * 3 + 1 + which) * B.N * H;
-    float* dHp = B.dHp + ((long long)s * 3 + 1 + which) * B.N * H;
+    g_pend_append(pend, pd.Rp, pd.stride, nrows, Y, Hs, H, X, Cs, C, K, gb);
+    lds_barrier();
+    mfma_cols(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Cs);
+    GQ float* dA = B.dA + ((long long)s * 3 + 1 + which) * B.N * H;
+    GQ float* dHp = B.dHp + ((long long)s * 3 + 1 + which) * B.N * H;
     for (int i = threadIdx.x; i < K * C; i += AMP_THREADS) {
       const int k = i / C, c = i - k * C;
       if (c < H)
-        dA[k * H + c] = DX[k * Cs + c];
+        dA[k * H + c] = X[k * Cs + c];
       else
-        dHp[k * H + c - H] = DX[k * Cs + c];
+        dHp[k * H + c - H] = X[k * Cs + c];
     }
     __syncthreads();
     if (threadIdx.x == 0) {
       fence_release();
-      s_last = join_arrive(B.cnt + s * 8 + 2, 2);
+      // both gates done: back through sum / Group to the edge types
+      if (join_arrive(B.cnt + s * 8 + 2, 2)) g_post_edges(D, v, s, it, true);
     }
-    __syncthreads();
-    if (s_last) {
-      // Bcast backward on A: (update + reset) + candidate, then back through sum / Group to the edges
-      const float* all = B.dA + (long long)s * 3 * B.N * H;
-      float* dAs = B.dAs + B.sl(s);
-      for (int i = threadIdx.x; i < K * H; i += AMP_THREADS)
-        dAs[i] = (all[B.N * H + i] + all[2 * B.N * H + i]) + all[i];
-      __syncthreads();
-      if (threadIdx.x == 0) {
-        fence_release();
-        g_post_edges(D, v, s, it, true);
-      }
-    }
-    g_count_and_update(D, W, nd, t, Wl, bl, pd, count, nrows, tstep, K, X);
+    g_count_and_update(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
+    lds_barrier();
   }
-  tile_store(nd, t, Wl, bl);
+  tile_store(nd, t, g.Wg, g.bg);
+  if ((int)threadIdx.x < t.R) ndG[(long long)nd.rows * t.C + threadIdx.x] = gb;
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;
@@ -412,18 +455,18 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
   const Pend pd = make_pend(W, t);
+  GQ float* pend = (GQ float*)pd.base;
   const int H = B.H, C = 2 * H, Np = amp_round16(B.N), Hs = amp_ldrow(H), Cs = amp_ldrow(C);
   const int NRB = t.Rp >> 4, NCG = amp_round16(C) >> 4;
   Lds L{lds};
-  float* Wl = L.take(t.Rp * t.ldw);
-  float* bl = L.take(t.Rp);
-  const int xfloats = Np * Cs > UPD_STAGE * pd.stride ? Np * Cs : UPD_STAGE * pd.stride;
-  float* X = L.take(xfloats);     // inputs; later W^T delta; staging at updates
-  float* Y = L.take(Np * Hs);
-  float* DX = X;
-  tile_load(nd, t, Wl, bl);
-  for (int i = threadIdx.x; i < xfloats; i += AMP_THREADS) X[i] = 0.f;
+  const GTile g = g_tile_setup(L, nd, t);
+  LDSQ float* X = (LDSQ float*)L.take(Np * Cs);     // inputs; later W^T delta
+  LDSQ float* Y = (LDSQ float*)L.take(Np * Hs);
+  LDSQ float* gt = (LDSQ float*)L.take(B.N * H);    // gradient w.r.t. the states leaving the step
+  for (int i = threadIdx.x; i < Np * Cs; i += AMP_THREADS) X[i] = 0.f;
   for (int i = threadIdx.x; i < Np * Hs; i += AMP_THREADS) Y[i] = 0.f;
+  GQ float* ndG = (GQ float*)nd.G;
+  float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
   __syncthreads();
   const GQ RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
@@ -432,20 +475,20 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
     const unsigned seq = D->slot_seq[s];
     const GView v = g_view(D, seq);
-    const int K = v.N;
-    const float* A = B.A + B.st(s, it);
-    const float* h = B.Hm + B.hm(s, it);
-    const float* Z = B.Z + B.st(s, it);
-    const float* Rr = B.Rr + B.st(s, it);
-    float* Ht = B.Ht + B.st(s, it);
+    const int K = v.N, NB = (K + 15) >> 4;
+    const GQ float* A = B.A + B.st(s, it);
+    const GQ float* h = B.Hm + B.hm(s, it);
+    const GQ float* Z = B.Z + B.st(s, it);
+    const GQ float* Rr = B.Rr + B.st(s, it);
+    GQ float* Ht = B.Ht + B.st(s, it);
     for (int i = threadIdx.x; i < K * Cs; i += AMP_THREADS) {
       const int k = i / Cs, c = i - k * Cs;
       X[i] = c < H ? A[k * H + c] : c < C ? Rr[k * H + c - H] * h[k * H + c - H] : 0.f;
     }
-    __syncthreads();
     if (!(code & MSG_DIR_B)) {
-      mfma_rows((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)bl, (LDSQ float*)X, Cs, (K + 15) >> 4, (LDSQ float*)Y, Hs);
-      float* hn = B.Hm + B.hm(s, it + 1);
+      lds_barrier();
+      mfma_rows(g.Wl, t.ldw, NRB, NCG, g.bl, X, Cs, NB, Y, Hs);
+      GQ float* hn = B.Hm + B.hm(s, it + 1);
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
         const float ht = tanhf(Y[(i / H) * Hs + i % H]), z = Z[i];
         Ht[i] = ht;
@@ -463,28 +506,35 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
       continue;
     }
     // backward through blend, tanh, the candidate linear and r*h
-    const float* gH = B.gH + B.sl(s);
-    float* dZ = B.dZ + B.sl(s);
-    float* dR = B.dR + B.sl(s);
-    for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
-      const float g = gH[i], z = Z[i], ht = Ht[i];
-      dZ[i] = g * (ht - h[i]) * z * (1.f - z);
-      Y[(i / H) * Hs + i % H] = g * z * (1.f - ht * ht);
+    {
+      const GQ float* gH = B.gH + B.sl(s);
+      GQ float* dZ = B.dZ + B.sl(s);
+      const bool from_readout = it + 1 == B.S;
+      for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
+        const float gg = from_readout ? gH[i] : g_state_gradient(B, v, s, i);
+        const float z = Z[i], ht = Ht[i];
+        gt[i] = gg;
+        dZ[i] = gg * (ht - h[i]) * z * (1.f - z);
+        Y[(i / H) * Hs + i % H] = gg * z * (1.f - ht * ht);
+      }
+      for (int i = threadIdx.x; i < K * (Hs - H); i += AMP_THREADS) Y[(i / (Hs - H)) * Hs + H + i % (Hs - H)] = 0.f;
     }
-    for (int i = threadIdx.x; i < K * (Hs - H); i += AMP_THREADS) Y[(i / (Hs - H)) * Hs + H + i % (Hs - H)] = 0.f;
-    __syncthreads();
+    lds_barrier();
     LOG(W->node, 1, seq, it);
-    pend_append(pd, nrows, Y, Hs, H, X, Cs, C, K);
-    __syncthreads();
-    mfma_cols((LDSQ float*)Wl, t.ldw, NRB, NCG, (LDSQ float*)Y, Hs, (K + 15) >> 4, (LDSQ float*)DX, Cs);
-    float* dA = B.dA + (long long)s * 3 * B.N * H;
-    float* dHp = B.dHp + (long long)s * 3 * B.N * H;
-    for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
-      const int k = i / H, j = i - k * H;
-      const float drh = DX[k * Cs + H + j], r = Rr[i], z = Z[i];
-      dA[i] = DX[k * Cs + j];
-      dR[i] = drh * h[i] * r * (1.f - r);
-      dHp[i] = drh * r + gH[i] * (1.f - z);
+    g_pend_append(pend, pd.Rp, pd.stride, nrows, Y, Hs, H, X, Cs, C, K, gb);
+    lds_barrier();
+    mfma_cols(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Cs);
+    {
+      GQ float* dA = B.dA + (long long)s * 3 * B.N * H;
+      GQ float* dHp = B.dHp + (long long)s * 3 * B.N * H;
+      GQ float* dR = B.dR + B.sl(s);
+      for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
+        const int k = i / H, j = i - k * H;
+        const float drh = X[k * Cs + H + j], r = Rr[i], z = Z[i];
+        dA[i] = X[k * Cs + j];
+        dR[i] = drh * h[i] * r * (1.f - r);
+        dHp[i] = drh * r + gt[i] * (1.f - z);
+      }
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -492,9 +542,11 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
       ring_post(D->ring[GR_GZ(D)], MSG_MAKE(1, s, it));
       ring_post(D->ring[GR_GR(D)], MSG_MAKE(1, s, it));
     }
-    g_count_and_update(D, W, nd, t, Wl, bl, pd, count, nrows, tstep, K, X);
+    g_count_and_update(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
+    lds_barrier();
   }
-  tile_store(nd, t, Wl, bl);
+  tile_store(nd, t, g.Wg, g.bg);
+  if ((int)threadIdx.x < t.R) ndG[(long long)nd.rows * t.C + threadIdx.x] = gb;
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;
@@ -515,6 +567,7 @@ __device__ __noinline__ void role_g_readout(const GQ AmpDev* D, const GQ WorkerD
   float* pooled = L.take(H);
   float* red = L.take(AMP_THREADS);
   tile_load(nd, t, Wl, bl);
+  GQ float* ndG = (GQ float*)nd.G;
   const GQ RingDev& mine = D->ring[W->ring];
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
@@ -522,7 +575,7 @@ __device__ __noinline__ void role_g_readout(const GQ AmpDev* D, const GQ WorkerD
     const int s = MSG_SLOT(code);
     const unsigned seq = D->slot_seq[s];
     const GView v = g_view(D, seq);
-    const float* h = B.Hm + B.hm(s, B.S);
+    const GQ float* h = B.Hm + B.hm(s, B.S);
     for (int j = threadIdx.x; j < H; j += AMP_THREADS) {
       float a = 0.f;
       for (int n = 0; n < v.N; ++n) a += h[n * H + j];
@@ -541,8 +594,8 @@ __device__ __noinline__ void role_g_readout(const GQ AmpDev* D, const GQ WorkerD
     const float d = yhat - v.target;
     LOG(W->node, 0, seq, 0);
     if (threadIdx.x == 0) {
-      D->loss_out[seq - D->first_seq] = 0.5f * d * d;
-      D->yhat_out[seq - D->first_seq] = yhat;
+      ((GQ float*)D->loss_out)[seq - D->first_seq] = 0.5f * d * d;
+      ((GQ float*)D->yhat_out)[seq - D->first_seq] = yhat;
     }
     if (!D->train) {
       __syncthreads();
@@ -553,10 +606,10 @@ __device__ __noinline__ void role_g_readout(const GQ AmpDev* D, const GQ WorkerD
       continue;
     }
     LOG(W->node, 1, seq, 0);
-    float* gH = B.gH + B.sl(s);
+    GQ float* gH = B.gH + B.sl(s);
     for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) gH[i] = d * Wl[i % H];
-    for (int j = threadIdx.x; j < H; j += AMP_THREADS) nd.G[j] += d * pooled[j];
-    if (threadIdx.x == 0) nd.G[H] += d;
+    for (int j = threadIdx.x; j < H; j += AMP_THREADS) ndG[j] += d * pooled[j];
+    if (threadIdx.x == 0) ndG[H] += d;
     __syncthreads();
     if (threadIdx.x == 0) {
       fence_release();

@@ -48,6 +48,7 @@ struct InstSet {
   std::vector<float> x, target;
   std::vector<int> tok_off{0}, tok, lab_off{0}, lab, node_off{0}, left, right, parent, edge_off{0}, src, dst, etype, tcount;
   std::vector<int> tnode;   // tree: left, right, parent code, label per node
+  std::vector<int> inoff, inedge, tstart, tedge, tsoff, tsk;   // graph adjacency (see DataDev)
   bool dirty = true;
   size_t n() const { return keys.size(); }
   void clear() { *this = InstSet(); }
@@ -161,7 +162,7 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
     w.kb = 64;
     return r4(c->max_mak) + AMP_TREE_LOOKUP_MAX_MUF;
   }
-  if (w.role == ROLE_G_LOOKUP) return r4((size_t)c->dims.n_node_types * c->dims.hidden);
+  if (w.role == ROLE_G_LOOKUP) return r4((size_t)c->dims.n_node_types * c->dims.hidden) + r4((size_t)c->max_len * c->dims.hidden);
   const HostNode& n = c->nodes[w.node];
   const size_t R = tile_rows(c, w), C = n.cols, Rp = amp_round16((int)R), ldw = amp_ldrow(n.cl());
   const size_t stride = pend_stride(c, w), wfl = r4(Rp * ldw) + r4(Rp);
@@ -203,13 +204,16 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
     }
     case ROLE_G_EDGE: {
       const size_t H = c->dims.hidden, Ep = amp_round16(c->max_edges), Hs = amp_ldrow((int)H);
-      f = wfl + r4(std::max(Ep * Hs, UPD_STAGE_HOST * stride)) + r4(Ep * Hs) + r4((size_t)c->max_len * H) + r4(c->max_edges);
+      if ((Rp / 16) * ((amp_round16((int)C) + 63) / 64) > 32) return 0;   // the update's register accumulator
+      f = wfl + r4(Rp) + (size_t)(amp_round16((int)C) + 63) / 64 * 64 + 2 * r4(Ep * Hs);
       break;
     }
     case ROLE_G_GATE:
     case ROLE_G_CAND: {
       const size_t H = c->dims.hidden, Np = amp_round16(c->max_len), Hs = amp_ldrow((int)H), Cs = amp_ldrow((int)(2 * H));
-      f = wfl + r4(std::max(Np * Cs, UPD_STAGE_HOST * stride)) + r4(Np * Hs);
+      if ((Rp / 16) * ((amp_round16((int)C) + 63) / 64) > 32) return 0;
+      f = wfl + r4(Rp) + (size_t)(amp_round16((int)C) + 63) / 64 * 64 + r4(Np * Cs) + r4(Np * Hs);
+      if (w.role == ROLE_G_CAND) f += r4((size_t)c->max_len * H);
       break;
     }
     case ROLE_G_READOUT:
@@ -676,6 +680,42 @@ int amp_submit(amp_ctx* c, int which, uint64_t key, const amp_instance* in) {
         int tc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         for (int e = 0; e < E; ++e) tc[in->etype[e]]++;
         S.tcount.insert(S.tcount.end(), tc, tc + 8);
+        // adjacency tables: incoming edges by destination; per type, the edges in ascending order and
+        // their group positions by source node
+        const int T = d.n_edge_types;
+        int ts[9] = {0};
+        for (int k = 0; k < 8; ++k) ts[k + 1] = ts[k] + tc[k];
+        S.tstart.insert(S.tstart.end(), ts, ts + 9);
+        std::vector<int> io(N + 1, 0), ie(E), te(E), tso((size_t)T * (N + 1), 0), tk(E), pos(E);
+        for (int e = 0; e < E; ++e) io[in->dst[e] + 1]++;
+        for (int v = 0; v < N; ++v) io[v + 1] += io[v];
+        {
+          std::vector<int> fill(io.begin(), io.end() - 1);
+          for (int e = 0; e < E; ++e) ie[fill[in->dst[e]]++] = e;
+        }
+        {
+          int fill[8];
+          for (int k = 0; k < 8; ++k) fill[k] = ts[k];
+          for (int e = 0; e < E; ++e) {
+            pos[e] = fill[in->etype[e]] - ts[in->etype[e]];
+            te[fill[in->etype[e]]++] = e;
+          }
+        }
+        for (int e = 0; e < E; ++e) tso[(size_t)in->etype[e] * (N + 1) + in->src[e] + 1]++;
+        for (int k = 0; k < T; ++k)
+          for (int v = 0; v < N; ++v) tso[(size_t)k * (N + 1) + v + 1] += tso[(size_t)k * (N + 1) + v];
+        {
+          std::vector<int> fill(tso);
+          for (int e = 0; e < E; ++e) {   // ascending e = ascending position inside its type
+            const int k = in->etype[e];
+            tk[ts[k] + fill[(size_t)k * (N + 1) + in->src[e]]++] = pos[e];
+          }
+        }
+        S.inoff.insert(S.inoff.end(), io.begin(), io.end());
+        S.inedge.insert(S.inedge.end(), ie.begin(), ie.end());
+        S.tedge.insert(S.tedge.end(), te.begin(), te.end());
+        S.tsoff.insert(S.tsoff.end(), tso.begin(), tso.end());
+        S.tsk.insert(S.tsk.end(), tk.begin(), tk.end());
       }
       S.target.push_back(in->target);
       break;
@@ -785,6 +825,12 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   if ((r = upload(c, off, S.etype, (const void**)&dd.etype))) return r;
   if ((r = upload(c, off, S.tcount, (const void**)&dd.tcount))) return r;
   if ((r = upload(c, off, S.tnode, (const void**)&dd.tnode))) return r;
+  if ((r = upload(c, off, S.inoff, (const void**)&dd.inoff))) return r;
+  if ((r = upload(c, off, S.inedge, (const void**)&dd.inedge))) return r;
+  if ((r = upload(c, off, S.tstart, (const void**)&dd.tstart))) return r;
+  if ((r = upload(c, off, S.tedge, (const void**)&dd.tedge))) return r;
+  if ((r = upload(c, off, S.tsoff, (const void**)&dd.tsoff))) return r;
+  if ((r = upload(c, off, S.tsk, (const void**)&dd.tsk))) return r;
   auto take = [&](size_t bytes) -> size_t {
     size_t o = off;
     off = align_up(off + bytes);

@@ -449,10 +449,11 @@ __device__ __forceinline__ void tree_bwd_mfma(const LDSQ float* Wl, const Tile& 
 // rb + NRB * cm = wave + 8 u; its four 16 x 16 tiles take the columns
 // cm * 64 + 4 i + v, v = 0..3, so that one 16-byte fetch of an input feeds all
 // four.  Lane (i, q) ends up with G[rb*16 + 4q + e][cm*64 + 4i + v] in g[u][v][e].
-// gb = the accumulated bias gradient of tile row threadIdx.x.
+// gb = the accumulated bias gradient of tile row threadIdx.x; n_grad = the
+// number of gradients (messages) behind the count pending rows.
 template <int NRBT, int NCGT>
 __device__ __noinline__ void tree_update_from_pend(LDSQ float* Wl, LDSQ float* bl, const GQ NodeDev* ndp, Tile t,
-                                                   const GQ float* pend, unsigned count, unsigned tstep,
+                                                   const GQ float* pend, unsigned count, unsigned n_grad, unsigned tstep,
                                                    const LDSQ int* rowmap, const LDSQ int* colmap, float gb) {
   const TreeShape<NRBT, NCGT> sh(t);
   const GQ NodeDev& nd = *ndp;
@@ -460,7 +461,7 @@ __device__ __noinline__ void tree_update_from_pend(LDSQ float* Wl, LDSQ float* b
   const int NRB = sh.NRB, Rp = NRB * 16, Cp = sh.NCG * 16, stride = Rp + Cp, CM = (Cp + 63) >> 6, NU = NRB * CM;
   const v4f zero = {0.f, 0.f, 0.f, 0.f};
   const OptCoef o = opt_coef(nd, tstep);
-  const float inv = nd.mean ? 1.f / (float)count : 1.f;
+  const float inv = nd.mean ? 1.f / (float)n_grad : 1.f;
   v4f g[TREE_GU][4];
   int aoff[TREE_GU], xoff[TREE_GU];
   bool xin[TREE_GU];
@@ -977,7 +978,7 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
       if (STREAM)
         tree_update_stream(ndP, bl, &nd, t, pend, count, tstep, rowmap, accb);
       else
-        tree_update_from_pend<NRBT, NCGT>(Wl, bl, &nd, t, pend, count, tstep, rowmap, colmap, accb);
+        tree_update_from_pend<NRBT, NCGT>(Wl, bl, &nd, t, pend, count, count, tstep, rowmap, colmap, accb);
       accb = 0.f;
       count = 0;
       LOG(W->node, 2, 0, 0);
