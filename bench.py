@@ -29,6 +29,10 @@ from paper_1705_09786_amd import costmodel, synth  # noqa: E402
 CLOCK_HZ = 2.4e9
 LDS_BYTES_PER_CLK_PER_CU = 128
 N_CU = 256
+FP32_MFMA_PEAK = 157.3e12          # whole chip, dense fp32 matrix
+# HBM bytes per launch of the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a copy of
+# known size (profiles/amp_persistent_treelstm_h150_8544trees.md); only quoted for exactly that configuration.
+MEASURED_HBM_BYTES_PER_LAUNCH = {(3, 64, 50, 8544): 49.8e9}
 
 DEFAULTS = {
     # cfg: mak, muf, lookup muf, optimizer
@@ -109,6 +113,9 @@ def main():
     ap.add_argument("--muf", type=int, default=None)
     ap.add_argument("--n", type=int, default=None, help="instances (default: the config's full set)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, run one device-to-device copy of this many MiB (the kernel of "
+                         "known traffic that rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported" % args.gpus, file=sys.stderr)
@@ -116,6 +123,18 @@ def main():
     import torch
     from paper_1705_09786_amd import binding as B
     from paper_1705_09786_amd import runner
+
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        a = torch.empty(n, dtype=torch.uint8, device="cuda:0")
+        b = torch.empty_like(a)
+        a.zero_()
+        torch.cuda.synchronize()
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "copies": 3}))
+        return
 
     cfg = dict(DEFAULTS[args.config])
     if args.mak:
@@ -125,7 +144,8 @@ def main():
     model, dims, data = synth.workload(args.config, n=args.n)
     fp = synth.init_params(model, dims, 100 + args.config)
     ml, me = runner.max_len_of(model, data)
-    tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=4 << 30)
+    tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=(12 if args.config == 5 else 4) << 30,
+                        tiles=cfg.get("tiles"))
     a = tr.amp
     a.set_min_update_frequency(-1, cfg["muf"])
     if cfg["lmuf"]:
@@ -158,23 +178,34 @@ def main():
         lds_bytes = sum(costmodel.visit_cost(W[k])["weight_bytes"] * v[k] for k in v)
         flops = sum(costmodel.visit_cost(W[k])["flops"] * v[k] for k in v)
     n_workers = a.num_workers()
-    peak = n_workers * LDS_BYTES_PER_CLK_PER_CU * CLOCK_HZ / 1e9
-    achieved = lds_bytes / kern / 1e9
+    # Bound of the dominant (only) kernel.  Batch-1 cells with LDS-resident weights (configs 1-3): LDS bandwidth
+    # of the occupied CUs, algorithmic bytes = one read of W per forward and per backward visit.  Grouped rows
+    # (config 4) and the streamed scale-up cell (config 5): the fp32 matrix rate of the occupied CUs.
+    if args.config in (4, 5):
+        peak_chip = FP32_MFMA_PEAK / 1e12
+        achieved = flops / kern / 1e12
+        unit, bound = "TFLOP/s", "mfma"
+    else:
+        peak_chip = N_CU * LDS_BYTES_PER_CLK_PER_CU * CLOCK_HZ / 1e9
+        achieved = lds_bytes / kern / 1e9
+        unit, bound = "GB/s", "lds"
+    peak = peak_chip * n_workers / N_CU
     out = {
         "metric": "trained instances/sec", "value": value, "unit": "instances/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * wall / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": NAMES[args.config], "model": model, "instances": n, "max_active_keys": cfg["mak"],
+        "config": {"workload": NAMES[args.config], "instances": n, "max_active_keys": cfg["mak"],
                    "min_update_frequency": cfg["muf"], "lookup_min_update_frequency": cfg["lmuf"],
                    "optimizer": cfg["opt"][0], "workgroups": n_workers},
         "kernel_ms_per_step": 1e3 * kern,
         "kernel_instances_per_s": n / kern,
         "train_loss": stats["mean_loss"], "train_accuracy": stats["accuracy"],
-        "roofline": {"bound": "lds", "achieved": achieved, "peak": peak, "unit": "GB/s", "frac": achieved / peak,
-                     "traffic": None, "occupied_cus": n_workers,
-                     "peak_whole_chip": N_CU * LDS_BYTES_PER_CLK_PER_CU * CLOCK_HZ / 1e9,
-                     "frac_whole_chip": achieved / (N_CU * LDS_BYTES_PER_CLK_PER_CU * CLOCK_HZ / 1e9),
-                     "algorithmic_flops_per_s": flops / kern},
+        "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+                     "traffic": MEASURED_HBM_BYTES_PER_LAUNCH.get((args.config, cfg["mak"], cfg["muf"], n)),
+                     "traffic_unit": "HBM bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, separate runs)",
+                     "kernel": "amp_persistent", "occupied_cus": n_workers,
+                     "peak_whole_chip": peak_chip, "frac_whole_chip": achieved / peak_chip,
+                     "algorithmic_flops_per_s": flops / kern, "algorithmic_lds_bytes_per_s": lds_bytes / kern},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(model, dims, fp, data, cfg)
