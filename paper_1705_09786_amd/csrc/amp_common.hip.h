@@ -64,7 +64,11 @@ __device__ __forceinline__ void raise_abort(const GQ AmpDev* D, unsigned code, u
 // [2] batches taken, [3] last phase boundary, [4..11] ticks per phase (role-specific).
 #define AMP_NSTAT 12
 __shared__ unsigned long long s_stat[AMP_NSTAT];
-// Thread 0 charges the time since the previous boundary to phase i.
+// Thread 0 charges the time since the previous boundary to phase i.  Compiled in only with -DAMP_PHASE_STATS:
+// eight clock reads per batch cost about 3 % of a tile worker's time.
+#ifndef AMP_PHASE_STATS
+#define PHASE(i) do {} while (0)
+#else
 #define PHASE(i)                                             \
   do {                                                       \
     if (threadIdx.x == 0) {                                  \
@@ -73,6 +77,7 @@ __shared__ unsigned long long s_stat[AMP_NSTAT];
       s_stat[3] = now_;                                      \
     }                                                        \
   } while (0)
+#endif
 
 // Whole workgroup.  Waits for the entry with ticket `head` of ring r; returns
 // false when the run is over (done flag, abort flag, or this wait exceeded
