@@ -40,7 +40,7 @@ DEFAULTS = {
     2: dict(mak=16, muf=16, lmuf=16, opt=("sgd", dict(lr=0.05))),
     3: dict(mak=64, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.05))),
     4: dict(mak=32, muf=20, lmuf=20, opt=("adam", dict(lr=0.001))),
-    5: dict(mak=128, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.02)), tiles={1: 8, 2: 16}),
+    5: dict(mak=128, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.02)), tiles={1: 16, 2: 32}),
 }
 NAMES = {1: "mlp_64-128-128-10_1024inst", 2: "rnn_h128_len4-32_10000seq",
          3: "treelstm_h150_e300_2-60leaves_8544trees", 4: "ggnn_h100_4steps_9-29nodes_20000graphs",

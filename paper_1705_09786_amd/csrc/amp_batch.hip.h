@@ -14,7 +14,7 @@
 // HBM; when the node updates, the accumulated gradient
 //     G = sum_k delta_k (x) input_k      (k in arrival order)
 // is formed block by block in registers and goes straight into the optimizer
-// step on the LDS-resident weights.
+// step on the weights (tree_update_from_pend, tree_update_stream).
 #pragma once
 
 #define KB_MAX 64
@@ -194,87 +194,4 @@ __device__ __forceinline__ Pend make_pend(const GQ WorkerDev* W, const Tile& t) 
   p.Cp = amp_round16(t.Cl);
   p.stride = p.Rp + p.Cp;
   return p;
-}
-
-// Appends K pairs held in LDS (delta rows stride ldd, input rows stride ldx) as entries first..first+K-1.
-__device__ __forceinline__ void pend_append(const Pend& p, unsigned first, const float* Dl, int ldd, int R,
-                                            const float* X, int ldx, int C, int K) {
-  for (int i = threadIdx.x; i < K * p.stride; i += AMP_THREADS) {
-    const int k = i / p.stride, j = i - k * p.stride;
-    float v = 0.f;
-    if (j < p.Rp) {
-      if (j < R) v = Dl[k * ldd + j];
-    } else if (j - p.Rp < C) {
-      v = X[k * ldx + j - p.Rp];
-    }
-    p.base[(long long)(first + k) * p.stride + j] = v;
-  }
-}
-
-// The node's update from `count` pending pairs: G = sum_k delta_k (x) input_k
-// formed in 16 x 16 register tiles on the matrix cores (M = rows, N = columns,
-// K = pending index, in arrival order), then the optimizer step on the LDS
-// weights.  `stage` is LDS for UPD_STAGE entries.  Wave w owns tiles w, w+8, ...
-#define UPD_STAGE 8
-#define UPD_TILES 16
-__device__ __noinline__ void mfma_update(LDSQ float* Wl, LDSQ float* bl, const GQ NodeDev* ndp, Tile t, const float* pend,
-                                         int stride, unsigned n_grad, unsigned count, unsigned tstep,
-                                         LDSQ float* stage) {
-  // n_grad = gradients (messages) accumulated, count = pending rows (a grouped message has several)
-  const GQ NodeDev& nd = *ndp;
-  const OptCoef o = opt_coef(nd, tstep);
-  const float inv = nd.mean ? 1.f / (float)n_grad : 1.f;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
-  const int NRB = t.Rp >> 4, NCB = (stride - t.Rp) >> 4, T = NRB * NCB;
-  __syncthreads();
-  for (int pass0 = 0; pass0 < T; pass0 += 8 * UPD_TILES) {
-    v4f acc[UPD_TILES];
-#pragma unroll
-    for (int ti = 0; ti < UPD_TILES; ++ti) acc[ti] = (v4f){0.f, 0.f, 0.f, 0.f};
-    float accb = 0.f;   // bias gradient of row threadIdx.x (first pass only)
-    for (unsigned k0 = 0; k0 < count; k0 += UPD_STAGE) {
-      const int kc = count - k0 < (unsigned)UPD_STAGE ? (int)(count - k0) : UPD_STAGE;
-      const v4f* src = (const v4f*)(pend + (long long)k0 * stride);
-      for (int j = threadIdx.x; j < (UPD_STAGE * stride) >> 2; j += AMP_THREADS)
-        ((LDSQ v4f*)stage)[j] = j < (kc * stride) >> 2 ? src[j] : (v4f){0.f, 0.f, 0.f, 0.f};
-      __syncthreads();
-#pragma unroll
-      for (int ti = 0; ti < UPD_TILES; ++ti) {
-        const int tl = pass0 + wave + 8 * ti;
-        if (tl < T) {
-          const int rb = tl / NCB, cb = tl - rb * NCB;
-#pragma unroll
-          for (int k4 = 0; k4 < UPD_STAGE / 4; ++k4) {
-            const LDSQ float* e = stage + (4 * k4 + q) * stride;
-            acc[ti] = MFMA(e[rb * 16 + i], e[t.Rp + cb * 16 + i], acc[ti]);
-          }
-        }
-      }
-      if (pass0 == 0 && (int)threadIdx.x < t.R)
-        for (int k = 0; k < kc; ++k) accb += stage[k * stride + threadIdx.x];
-      __syncthreads();
-    }
-#pragma unroll
-    for (int ti = 0; ti < UPD_TILES; ++ti) {
-      const int tl = pass0 + wave + 8 * ti;
-      if (tl < T) {
-        const int rb = tl / NCB, cb = tl - rb * NCB;
-        const int lc = cb * 16 + i, c = t.ncol(lc);
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const int r = rb * 16 + 4 * q + v;
-          if (r < t.R && c >= 0) {
-            const long long gi = (long long)t.grow(r) * t.C + c;
-            Wl[r * t.ldw + lc] = opt_apply(o, Wl[r * t.ldw + lc], acc[ti][v] * inv, nd.M, nd.V, gi);
-          }
-        }
-      }
-    }
-    if (pass0 == 0 && nd.has_bias && (int)threadIdx.x < t.R) {
-      const int r = threadIdx.x;
-      const long long gi = (long long)nd.rows * t.C + t.grow(r);
-      bl[r] = opt_apply(o, bl[r], accb * inv, nd.M, nd.V, gi);
-    }
-  }
-  __syncthreads();
 }

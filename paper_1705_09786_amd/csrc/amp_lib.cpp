@@ -21,7 +21,6 @@ extern "C" hipError_t amp_launch(const AmpDev* dev, int n_workers, hipStream_t s
 namespace {
 
 constexpr size_t NSTAT = 12;
-constexpr size_t UPD_STAGE_HOST = 8;   // entries staged per step of an update (UPD_STAGE in the kernels)
 
 struct HostNode {
   std::string name;
@@ -177,7 +176,7 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
         // weights stay in HBM: rows must be 16-byte aligned and unpadded
         if (c->dims.hidden % 4 || c->dims.emb % 4) return 0;
         for (w.kb = 64; w.kb >= 16; w.kb -= 16) {
-          f = r4(Rp) + r4((size_t)w.kb * ldy) + 2 * r4(Rp);
+          f = r4(Rp) + r4((size_t)w.kb * ldy) + 2 * r4(Rp) + 2 * 64 * 68;
           if (f <= avail) break;
         }
         if (w.kb < 16) return 0;

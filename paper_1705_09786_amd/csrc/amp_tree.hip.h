@@ -554,97 +554,209 @@ __device__ __noinline__ void tree_update_from_pend(LDSQ float* Wl, LDSQ float* b
 // 16-row block, whose results are dropped or meet a zero delta.
 #define TREE_SG 10        // 16-column groups of input and weights held in registers at once
 
-// Y[j][r] = b[r] + sum_c W[r][c] x_j[c]; wave item = (16 messages, 16 weight rows).
-template <bool BR>
-__device__ __forceinline__ void tree_fwd_stream(const GQ float* P, const LDSQ int* rowoff, const Tile& t, const LDSQ float* bl,
-                                                const GQ float* xbase, const BatchMsg& M, int nF, LDSQ float* Y, int ldy) {
+// Y[j][r] = b[r] + sum_c W[r][c] x_j[c] as a K-chunked product: the batch's inputs go through LDS 64 columns
+// at a time (Xs, two buffers of kb rows x 68 floats, fetched once per chunk by the whole workgroup), every wave
+// owns up to three 16-row blocks of the weights for all message blocks, and both the next chunk's inputs and the
+// next chunk's weight rows are fetched while the matrix cores work on the present chunk.
+#define TREE_XC 64        // columns per chunk
+#define TREE_XS (TREE_XC + 4)
+
+template <bool BR, int NBF>
+__device__ __forceinline__ void tree_fwd_stream_blocks(const GQ float* P, const LDSQ int* rowoff, const Tile& t,
+                                                       const LDSQ float* bl, const GQ float* xbase, const BatchMsg& M, int nF,
+                                                       LDSQ float* Y, int ldy, LDSQ float* Xs) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
-  const int NRB = t.Rp >> 4, NCG = amp_round16(t.Cl) >> 4, NBF = (nF + 15) >> 4;
+  const int NRB = t.Rp >> 4, NCH = (t.Cl + TREE_XC - 1) / TREE_XC;
   const v4f zero = {0.f, 0.f, 0.f, 0.f};
-  for (int item = wave; item < NBF * NRB; item += AMP_THREADS / 64) {
-    const int rb = item % NRB, nb = item / NRB;
-    int mi = nb * 16 + i;
-    if (mi > nF - 1) mi = nF - 1;
+  constexpr int NX = NBF > 2 ? 2 : 1;   // staging passes of 32 messages
+  // staging role of this thread: message row sm (+ 32 per pass), 16-byte piece sp of the chunk
+  const int sm = threadIdx.x >> 4, sp = (threadIdx.x & 15) << 2;
+  const GQ float* xp0[NX];
+  const GQ float* xp1[NX];
+#pragma unroll
+  for (int a = 0; a < NX; ++a) {
+    int mi = sm + 32 * a;
+    if (mi > nF - 1) mi = nF - 1;   // rows beyond the batch repeat its last message; their results are dropped
     const int m = M.fidx[mi];
-    const GQ float* p0 = xbase + M.off0[m] + 4 * q;
-    const GQ float* p1 = xbase + M.off1[m] + 4 * q - t.segp;
-    const GQ float* wrow = P + rowoff[rb * 16 + i] + 4 * q;
-    v4f acc[4] = {zero, zero, zero, zero};
-    for (int c0 = 0; c0 < NCG; c0 += TREE_SG) {
-      v4f x[TREE_SG], w[TREE_SG];
+    xp0[a] = xbase + M.off0[m] + sp;
+    xp1[a] = xbase + M.off1[m] + sp - t.segp;
+  }
+  auto xfetch = [&](int ch, int a) -> v4f {
+    const int lc = ch * TREE_XC + sp;
+    const bool in = lc < t.Cl;
+    const v4f v = *(const GQ v4f*)(in ? (BR && lc >= t.segp ? xp1[a] : xp0[a]) + ch * TREE_XC : xp0[a]);
+    return in ? v : zero;
+  };
+  for (int r0 = 0; r0 < NRB; r0 += 24) {
+    // this wave's row blocks: r0 + wave, + 8, + 16 (a block beyond the tile repeats the last one and is not stored)
+    const GQ float* wrow[3];
 #pragma unroll
-      for (int g = 0; g < TREE_SG; ++g) {
-        const int lc = (c0 + g) * 16 + 4 * q;
-        const bool in = lc < t.Cl;
-        const v4f xv = *(const GQ v4f*)(in ? (BR && lc >= t.segp ? p1 : p0) + (c0 + g) * 16 : p0);
-        const v4f wv = *(const GQ v4f*)(in ? wrow + (c0 + g) * 16 : wrow);
-        x[g] = in ? xv : zero;
-        w[g] = wv;
+    for (int j = 0; j < 3; ++j) {
+      const int rb = r0 + wave + 8 * j < NRB ? r0 + wave + 8 * j : NRB - 1;
+      wrow[j] = P + rowoff[rb * 16 + i] + 4 * q;
+    }
+    auto wfetch = [&](int ch, int j, int g) -> v4f {
+      const int lc = ch * TREE_XC + g * 16 + 4 * q;
+      return *(const GQ v4f*)(lc < t.Cl ? wrow[j] + ch * TREE_XC + g * 16 : wrow[j]);   // beyond the input: x is zero
+    };
+    v4f acc[3][NBF];
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+#pragma unroll
+      for (int nb = 0; nb < NBF; ++nb) acc[j][nb] = zero;
+    v4f wa[3][4], wb[3][4], xr[NX];
+    // prologue: chunk 0
+#pragma unroll
+    for (int a = 0; a < NX; ++a) xr[a] = xfetch(0, a);
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) wa[j][g] = wfetch(0, j, g);
+    lds_barrier();   // the previous pass has finished with Xs
+#pragma unroll
+    for (int a = 0; a < NX; ++a) *(LDSQ v4f*)(Xs + (sm + 32 * a) * TREE_XS + sp) = xr[a];
+    lds_barrier();
+    for (int ch = 0; ch < NCH; ch += 2) {
+      // ---- even chunk: operands wa, Xs buffer 0; fetch chunk ch + 1 into wb / xr
+#pragma unroll
+      for (int a = 0; a < NX; ++a) xr[a] = xfetch(ch + 1, a);
+#pragma unroll
+      for (int j = 0; j < 3; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) wb[j][g] = wfetch(ch + 1, j, g);
+      asm volatile("" ::: "memory");   // the fetches are issued before the products below start
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        v4f x[NBF];
+#pragma unroll
+        for (int nb = 0; nb < NBF; ++nb) x[nb] = *(const LDSQ v4f*)(Xs + (nb * 16 + i) * TREE_XS + g * 16 + 4 * q);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)   // component-major: consecutive products go to different accumulators
+#pragma unroll
+          for (int j = 0; j < 3; ++j)
+#pragma unroll
+            for (int nb = 0; nb < NBF; ++nb) acc[j][nb] = MFMA(wa[j][g][e], x[nb][e], acc[j][nb]);
       }
-      asm volatile("" : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]),
-                        "+v"(x[8]), "+v"(x[9]), "+v"(w[0]), "+v"(w[1]), "+v"(w[2]), "+v"(w[3]), "+v"(w[4]), "+v"(w[5]),
-                        "+v"(w[6]), "+v"(w[7]), "+v"(w[8]), "+v"(w[9]));
 #pragma unroll
-      for (int g = 0; g < TREE_SG; ++g) {
-        acc[0] = MFMA(w[g].x, x[g].x, acc[0]);
-        acc[1] = MFMA(w[g].y, x[g].y, acc[1]);
-        acc[2] = MFMA(w[g].z, x[g].z, acc[2]);
-        acc[3] = MFMA(w[g].w, x[g].w, acc[3]);
+      for (int a = 0; a < NX; ++a) *(LDSQ v4f*)(Xs + 64 * TREE_XS + (sm + 32 * a) * TREE_XS + sp) = xr[a];
+      lds_barrier();
+      if (ch + 1 >= NCH) break;
+      // ---- odd chunk: operands wb, Xs buffer 1; fetch chunk ch + 2 into wa / xr
+#pragma unroll
+      for (int a = 0; a < NX; ++a) xr[a] = xfetch(ch + 2, a);
+#pragma unroll
+      for (int j = 0; j < 3; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) wa[j][g] = wfetch(ch + 2, j, g);
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        v4f x[NBF];
+#pragma unroll
+        for (int nb = 0; nb < NBF; ++nb)
+          x[nb] = *(const LDSQ v4f*)(Xs + 64 * TREE_XS + (nb * 16 + i) * TREE_XS + g * 16 + 4 * q);
+#pragma unroll
+        for (int e = 0; e < 4; ++e)   // component-major: consecutive products go to different accumulators
+#pragma unroll
+          for (int j = 0; j < 3; ++j)
+#pragma unroll
+            for (int nb = 0; nb < NBF; ++nb) acc[j][nb] = MFMA(wb[j][g][e], x[nb][e], acc[j][nb]);
+      }
+#pragma unroll
+      for (int a = 0; a < NX; ++a) *(LDSQ v4f*)(Xs + (sm + 32 * a) * TREE_XS + sp) = xr[a];
+      lds_barrier();
+    }
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const int rb = r0 + wave + 8 * j;
+      if (rb < NRB) {
+        const v4f b4 = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
+#pragma unroll
+        for (int nb = 0; nb < NBF; ++nb) *(LDSQ v4f*)(Y + (nb * 16 + i) * ldy + rb * 16 + 4 * q) = acc[j][nb] + b4;
       }
     }
-    const v4f b4 = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
-    *(LDSQ v4f*)(Y + (nb * 16 + i) * ldy + rb * 16 + 4 * q) = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + b4;
   }
 }
 
-// dx_j[c] = sum_r W[r][c] delta_j[r]; wave item = 16 weight columns for all NBB message blocks,
-// the tile's rows taken TREE_SG 16-row blocks at a time.
+template <bool BR>
+__device__ __forceinline__ void tree_fwd_stream(const GQ float* P, const LDSQ int* rowoff, const Tile& t, const LDSQ float* bl,
+                                                const GQ float* xbase, const BatchMsg& M, int nF, LDSQ float* Y, int ldy,
+                                                LDSQ float* Xs) {
+  const int NBF = (nF + 15) >> 4;
+  if (NBF == 1)
+    tree_fwd_stream_blocks<BR, 1>(P, rowoff, t, bl, xbase, M, nF, Y, ldy, Xs);
+  else if (NBF == 2)
+    tree_fwd_stream_blocks<BR, 2>(P, rowoff, t, bl, xbase, M, nF, Y, ldy, Xs);
+  else if (NBF == 3)
+    tree_fwd_stream_blocks<BR, 3>(P, rowoff, t, bl, xbase, M, nF, Y, ldy, Xs);
+  else
+    tree_fwd_stream_blocks<BR, 4>(P, rowoff, t, bl, xbase, M, nF, Y, ldy, Xs);
+}
+
+// dx_j[c] = sum_r W[r][c] delta_j[r]; a wave owns every 8th group of 16 weight columns for all NBB message
+// blocks and walks the tile's rows TREE_SG 16-row blocks at a time, fetching the next stretch of weight
+// columns (two register buffers) while the matrix cores work on the present one.
 template <bool BR, int NBB>
 __device__ __forceinline__ void tree_bwd_stream_blocks(const GQ float* P, const LDSQ int* rowoff, const Tile& t,
                                                        const LDSQ float* Dl, int ldd, const BatchMsg& M, int nB, GQ float* obase) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
   const int NRB = t.Rp >> 4, NCG = amp_round16(t.Cl) >> 4;
+  const int NGC = (NRB + TREE_SG - 1) / TREE_SG;                 // row stretches per column group
+  const int ncb = wave < NCG ? (NCG - wave + 7) >> 3 : 0;        // column groups of this wave
+  const int T = ncb * NGC;
   const v4f zero = {0.f, 0.f, 0.f, 0.f};
-  for (int cb = wave; cb < NCG; cb += AMP_THREADS / 64) {
-    const int lc = cb * 16 + 4 * q;
+  const LDSQ float* dp = Dl + i * ldd + 4 * q;
+  auto afetch = [&](int it, float (&a)[TREE_SG][4]) {
+    const int cb = wave + 8 * (it / NGC), g0 = (it % NGC) * TREE_SG;
     const int col = cb * 16 + i < t.Cl ? cb * 16 + i : 0;
-    const LDSQ float* dp = Dl + i * ldd + 4 * q;
-    v4f acc[NBB][2];
 #pragma unroll
-    for (int nb = 0; nb < NBB; ++nb) acc[nb][0] = acc[nb][1] = zero;
-    for (int g0 = 0; g0 < NRB; g0 += TREE_SG) {
-      float a[TREE_SG][4];
+    for (int g = 0; g < TREE_SG; ++g) {
+      const int gg = g0 + g < NRB ? g0 + g : NRB - 1;
 #pragma unroll
-      for (int g = 0; g < TREE_SG; ++g) {
-        const int gg = g0 + g < NRB ? g0 + g : NRB - 1;
+      for (int v = 0; v < 4; ++v) a[g][v] = P[rowoff[gg * 16 + 4 * q + v] + col];
+    }
+  };
+  v4f acc[NBB][2];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) a[g][v] = P[rowoff[gg * 16 + 4 * q + v] + col];
-      }
+  for (int nb = 0; nb < NBB; ++nb) acc[nb][0] = acc[nb][1] = zero;
+  auto work = [&](int it, float (&a)[TREE_SG][4]) {
+    const int cb = wave + 8 * (it / NGC), gc = it % NGC, g0 = gc * TREE_SG;
 #pragma unroll
-      for (int g = 0; g < TREE_SG; ++g)
-        asm volatile("" : "+v"(a[g][0]), "+v"(a[g][1]), "+v"(a[g][2]), "+v"(a[g][3]));
+    for (int g = 0; g < TREE_SG; ++g)
+      if (g0 + g < NRB) {
 #pragma unroll
-      for (int g = 0; g < TREE_SG; ++g)
-        if (g0 + g < NRB) {
-#pragma unroll
-          for (int nb = 0; nb < NBB; ++nb) {
-            const v4f d = *(const LDSQ v4f*)(dp + nb * 16 * ldd + 16 * (g0 + g));
-            acc[nb][0] = MFMA(a[g][0], d.x, acc[nb][0]);
-            acc[nb][1] = MFMA(a[g][1], d.y, acc[nb][1]);
-            acc[nb][0] = MFMA(a[g][2], d.z, acc[nb][0]);
-            acc[nb][1] = MFMA(a[g][3], d.w, acc[nb][1]);
-          }
+        for (int nb = 0; nb < NBB; ++nb) {
+          const v4f d = *(const LDSQ v4f*)(dp + nb * 16 * ldd + 16 * (g0 + g));
+          acc[nb][0] = MFMA(a[g][0], d.x, acc[nb][0]);
+          acc[nb][1] = MFMA(a[g][1], d.y, acc[nb][1]);
+          acc[nb][0] = MFMA(a[g][2], d.z, acc[nb][0]);
+          acc[nb][1] = MFMA(a[g][3], d.w, acc[nb][1]);
         }
-    }
+      }
+    if (gc == NGC - 1) {
+      const int lc = cb * 16 + 4 * q;
 #pragma unroll
-    for (int nb = 0; nb < NBB; ++nb) {
-      const int mi = nb * 16 + i;
-      if (mi < nB && lc < t.Cl) {
-        const int m = M.bidx[mi];
-        GQ float* o = (BR && lc >= t.segp) ? obase + M.dst1[m] + (lc - t.segp) : obase + M.dst0[m] + lc;
-        *(GQ v4f*)o = acc[nb][0] + acc[nb][1];
+      for (int nb = 0; nb < NBB; ++nb) {
+        const int mi = nb * 16 + i;
+        if (mi < nB && lc < t.Cl) {
+          const int m = M.bidx[mi];
+          GQ float* o = (BR && lc >= t.segp) ? obase + M.dst1[m] + (lc - t.segp) : obase + M.dst0[m] + lc;
+          *(GQ v4f*)o = acc[nb][0] + acc[nb][1];
+        }
+        acc[nb][0] = acc[nb][1] = zero;
       }
     }
+  };
+  float a0[TREE_SG][4], a1[TREE_SG][4];
+  if (T > 0) afetch(0, a0);
+  for (int it = 0; it < T; it += 2) {
+    if (it + 1 < T) afetch(it + 1, a1);
+    asm volatile("" ::: "memory");   // the fetches are issued before the products below start
+    work(it, a0);
+    if (it + 1 >= T) break;
+    if (it + 2 < T) afetch(it + 2, a0);
+    asm volatile("" ::: "memory");
+    work(it + 1, a1);
   }
 }
 
@@ -768,6 +880,7 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
   LDSQ int* rowmap = (LDSQ int*)L.take(t.Rp);
   LDSQ int* colmap = (LDSQ int*)L.take(CMW);
   LDSQ int* rowoff = (LDSQ int*)L.take(STREAM ? t.Rp : 0);   // streamed weights: node row * cols
+  LDSQ float* Xs = (LDSQ float*)L.take(STREAM ? 2 * 64 * TREE_XS : 0);   // streamed weights: input chunks
   GQ float* ndP = (GQ float*)nd.P;
   if (STREAM) {
     for (int i = threadIdx.x; i < t.Rp; i += AMP_THREADS) {
@@ -827,7 +940,7 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
     // ---------------- forward messages of the batch
     if (nF > 0) {
       if (STREAM)
-        tree_fwd_stream<BR>(ndP, rowoff, t, bl, xbase, M, nF, Y, ldy);
+        tree_fwd_stream<BR>(ndP, rowoff, t, bl, xbase, M, nF, Y, ldy, Xs);
       else
         tree_fwd_mfma<BR, NRBT, NCGT>(Wl, t, bl, xbase, M, nF, Y);
       lds_barrier();
