@@ -145,6 +145,18 @@ int amp_set_tiles(amp_ctx *ctx, int node_id, int n_tiles);
  * branch nodes only. */
 int amp_set_weights_in_hbm(amp_ctx *ctx, int node_id, int on);
 
+/* Replicas (Section 5: data parallelism inside the IR).  Every parameterized
+ * node is replicated n_replicas times and a Cond on the instance number sends
+ * instance i (in submit order) to replica i mod n_replicas, so that n_replicas
+ * copies of the whole pipeline train side by side, each with max_active_keys
+ * instances in flight; at the end of every epoch each node's parameters are
+ * set to the mean over its replicas (optimizer slots are not shared).  1
+ * (default) = no replication.  Workers x replicas must not exceed the CUs.
+ * Evaluation uses the first replica.  Event records and worker statistics
+ * list replica 0's workers first, then replica 1's, ...; `seq` counts
+ * admissions per replica.  Only before amp_finalize. */
+int amp_set_replicas(amp_ctx *ctx, int n_replicas);
+
 /* Validates the graph, places nodes on workgroups and lays out the arena for
  * at most max_active_keys instances in flight, each at most max_instance_len
  * long (time steps, tree leaves, or graph nodes) with at most max_edges

@@ -830,3 +830,42 @@ def pump_ggnn(rt, seq, inst):
 
 BUILDERS = {"mlp": build_mlp, "rnn": build_rnn, "tree": build_tree, "ggnn": build_ggnn}
 PUMPS = {"mlp": pump_mlp, "rnn": pump_rnn, "tree": pump_tree, "ggnn": pump_ggnn}
+
+
+# ---------------------------------------------------------------------------
+# replicas (Section 5, "Interaction with data parallelism and replicas")
+# ---------------------------------------------------------------------------
+def average_replicas(runtimes):
+    """End-of-epoch replica synchronisation: the parameters of every replicated
+    node become the mean over its replicas.  Accumulators, counts and
+    optimizer slots stay with their replica."""
+    for nodes in zip(*[rt.ppt for rt in runtimes]):
+        for name in nodes[0].P:
+            mean = sum(n.P[name] for n in nodes) / float(len(nodes))
+            for n in nodes:
+                n.P[name] = mean.copy()
+
+
+def replica_subsets(instances, n_replicas):
+    """The Cond in front of the replicas routes on the instance number:
+    instance i (in submit order) goes to replica i mod n_replicas."""
+    return [instances[r::n_replicas] for r in range(n_replicas)]
+
+
+def run_replicas(runtimes, instances, mak, epochs=1):
+    """Own-schedule training with every parameterized node replicated: the
+    replicas train side by side on their share of the instances, each with
+    `mak` instances in flight, and are averaged after every epoch.  Returns
+    the per-instance losses in submit order, epoch by epoch."""
+    R = len(runtimes)
+    parts = replica_subsets(instances, R)
+    done = [0] * R
+    out = []
+    for _ in range(epochs):
+        per = []
+        for r, rt in enumerate(runtimes):
+            per.append(rt.run(parts[r], mak=mak, epochs=1, first_seq=done[r]))
+            done[r] += len(parts[r])
+        average_replicas(runtimes)
+        out += [per[i % R][i // R] for i in range(len(instances))]
+    return out

@@ -62,6 +62,7 @@ SIGNATURES = {
     "amp_build_ggnn": (ct.c_int, [_ctxp, ct.POINTER(ModelDims)]),
     "amp_set_tiles": (ct.c_int, [_ctxp, ct.c_int, ct.c_int]),
     "amp_set_weights_in_hbm": (ct.c_int, [_ctxp, ct.c_int, ct.c_int]),
+    "amp_set_replicas": (ct.c_int, [_ctxp, ct.c_int]),
     "amp_finalize": (ct.c_int, [_ctxp, ct.c_int, ct.c_int, ct.c_int, ct.c_size_t]),
     "amp_set_max_active_keys": (ct.c_int, [_ctxp, ct.c_int]),
     "amp_set_min_update_frequency": (ct.c_int, [_ctxp, ct.c_int, ct.c_int]),
@@ -187,6 +188,9 @@ class Amp:
     def set_tiles(self, node, n):
         self._chk(self.L.amp_set_tiles(self.h, node, n))
 
+    def set_replicas(self, n):
+        self._chk(self.L.amp_set_replicas(self.h, n))
+
     def set_weights_in_hbm(self, node, on=True):
         self._chk(self.L.amp_set_weights_in_hbm(self.h, node, int(on)))
 
@@ -276,7 +280,7 @@ class Amp:
         n = ct.c_size_t()
         self._chk(self.L.amp_get_worker_stats(self.h, wf, ms, nd, nw, ct.byref(n), bt, ph))
         return [dict(node=nd[i], wait_fraction=wf[i], messages=ms[i], batches=bt[i],
-                     phases=[ph[8 * i + j] for j in range(8)]) for i in range(nw)]
+                     phases=[ph[8 * i + j] for j in range(8)]) for i in range(min(nw, n.value))]
 
     def get_staleness_hist(self, nbins=16):
         bins = (ct.c_uint64 * nbins)()

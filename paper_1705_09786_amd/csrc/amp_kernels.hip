@@ -406,9 +406,11 @@ __device__ __noinline__ void role_rnn_out(const GQ AmpDev* D, const GQ WorkerDev
 #include "amp_ggnn.hip.h"
 
 // ============================================================ entry
-extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const AmpDev* Dp) {
-  const GQ AmpDev* D = (const GQ AmpDev*)Dp;
-  const GQ WorkerDev* W = &D->worker[blockIdx.x];
+extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const AmpDev* Dp, int workers_per_replica) {
+  // replica r = blocks [r * workers_per_replica, (r + 1) * workers_per_replica), each with its own descriptor
+  const int replica = blockIdx.x / workers_per_replica, wi = blockIdx.x - replica * workers_per_replica;
+  const GQ AmpDev* D = (const GQ AmpDev*)Dp + replica;
+  const GQ WorkerDev* W = &D->worker[wi];
   long long t_begin = 0;
   if (threadIdx.x == 0) {
     s_logn = 0;
@@ -455,7 +457,7 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
   }
 }
 
-extern "C" hipError_t amp_launch(const AmpDev* dev, int n_workers, hipStream_t stream) {
+extern "C" hipError_t amp_launch(const AmpDev* devs, int n_replicas, int workers_per_replica, hipStream_t stream) {
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)amp_persistent, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -463,6 +465,24 @@ extern "C" hipError_t amp_launch(const AmpDev* dev, int n_workers, hipStream_t s
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(amp_persistent, dim3(n_workers), dim3(AMP_THREADS), AMP_DYN_LDS_BYTES, stream, dev);
+  hipLaunchKernelGGL(amp_persistent, dim3(n_replicas * workers_per_replica), dim3(AMP_THREADS), AMP_DYN_LDS_BYTES, stream, devs,
+                     workers_per_replica);
+  return hipGetLastError();
+}
+
+// End-of-epoch synchronisation of replicas (Section 5): every replica's copy of a node's parameters becomes
+// the mean over the replicas, summed in replica order.
+__global__ void amp_average_kernel(float* p0, size_t stride_floats, int n_replicas, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float s = 0.f;
+  for (int r = 0; r < n_replicas; ++r) s += p0[(size_t)r * stride_floats + i];
+  s /= (float)n_replicas;
+  for (int r = 0; r < n_replicas; ++r) p0[(size_t)r * stride_floats + i] = s;
+}
+
+extern "C" hipError_t amp_average(float* p0, size_t stride_floats, int n_replicas, size_t n, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(amp_average_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p0, stride_floats, n_replicas, n);
   return hipGetLastError();
 }

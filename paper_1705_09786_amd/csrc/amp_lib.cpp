@@ -16,7 +16,8 @@
 #include "../../include/amp.h"
 #include "amp_dev.h"
 
-extern "C" hipError_t amp_launch(const AmpDev* dev, int n_workers, hipStream_t stream);
+extern "C" hipError_t amp_launch(const AmpDev* devs, int n_replicas, int workers_per_replica, hipStream_t stream);
+extern "C" hipError_t amp_average(float* p0, size_t stride_floats, int n_replicas, size_t n, hipStream_t stream);
 
 namespace {
 
@@ -77,6 +78,10 @@ struct amp_ctx {
   size_t buf_bytes[AMP_MAX_BUFS] = {0};
   long long buf_stride[AMP_MAX_BUFS] = {0};
   bool state_zeroed = false;
+  int replicas = 1, last_replicas = 1;
+  size_t rep_stride = 0;                              // bytes from one replica's static region to the next
+  std::vector<unsigned> rep_admitted;                 // admissions so far, per replica
+  std::vector<std::vector<amp_event>> launch_events;  // per worker, while a training call runs
   // results of the last train
   std::vector<float> last_loss;
   std::vector<int> last_correct;
@@ -84,7 +89,6 @@ struct amp_ctx {
   double last_seconds = 0;
   std::vector<unsigned long long> last_stats;   // NSTAT per worker
   uint64_t last_npred = 0;
-  unsigned total_admitted = 0;
   std::string err;
 };
 
@@ -327,6 +331,14 @@ int amp_set_weights_in_hbm(amp_ctx* c, int node_id, int on) {
   return AMP_OK;
 }
 
+int amp_set_replicas(amp_ctx* c, int n_replicas) {
+  if (!c) return AMP_EINVAL;
+  if (!c->model || c->finalized) return fail(c, AMP_ESTATE, "set_replicas: only between build and finalize");
+  if (n_replicas < 1 || n_replicas > 64) return fail(c, AMP_EINVAL, "set_replicas: 1..64 replicas");
+  c->replicas = n_replicas;
+  return AMP_OK;
+}
+
 int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_edges, size_t max_instances) {
   if (!c) return AMP_EINVAL;
   if (!c->model) return fail(c, AMP_ESTATE, "finalize: no model graph built");
@@ -398,6 +410,8 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     nrings = (int)c->workers.size();
   }
   if (c->workers.size() > AMP_MAX_WORKERS) return fail(c, AMP_EUNSUPPORTED, "finalize: too many workers");
+  if (c->workers.size() * (size_t)c->replicas > 256)
+    return fail(c, AMP_EUNSUPPORTED, "finalize: %zu workers x %d replicas exceed 256 workgroups", c->workers.size(), c->replicas);
   for (HostWorker& w : c->workers) {
     if ((w.role == ROLE_TREE_LEAF || w.role == ROLE_TREE_BRANCH) && c->nodes[w.node].in_hbm) w.aux = 1;
     size_t need = lds_floats(c, w) * 4;
@@ -418,7 +432,6 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     off = align_up(off + bytes);
     return o;
   };
-  c->off_dev = take(sizeof(AmpDev));
   c->off_ctl = take(64);
   c->off_clock = take(64);
   c->off_slot_seq = take(sizeof(unsigned) * c->max_mak);
@@ -489,9 +502,13 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     buf(12, N * H);
     buf(13, 8);
   }
-  c->static_end = off;
-  if (off > c->arena_bytes)
-    return fail(c, AMP_ENOMEM, "finalize: arena of %zu bytes is too small, %zu needed before instances", c->arena_bytes, off);
+  // every replica owns a copy of all of the above, rep_stride bytes apart
+  c->rep_stride = align_up(off, 4096);
+  c->static_end = c->rep_stride * (size_t)c->replicas;
+  c->rep_admitted.assign(c->replicas, 0);
+  if (c->static_end > c->arena_bytes)
+    return fail(c, AMP_ENOMEM, "finalize: arena of %zu bytes is too small, %zu needed before instances", c->arena_bytes,
+                c->static_end);
   c->finalized = true;
   c->state_zeroed = false;
   return AMP_OK;
@@ -542,22 +559,23 @@ int amp_set_gradient_mean(amp_ctx* c, int mean) {
 }
 
 int amp_num_nodes(amp_ctx* c) { return c ? (int)c->nodes.size() : AMP_EINVAL; }
-int amp_num_workers(amp_ctx* c) { return c ? (int)c->workers.size() : AMP_EINVAL; }
+int amp_num_workers(amp_ctx* c) { return c ? (int)c->workers.size() * c->replicas : AMP_EINVAL; }
 
 int amp_get_worker_stats(amp_ctx* c, double* wait_fraction, uint64_t* messages, int32_t* node_of_worker, size_t cap,
                          size_t* n, uint64_t* batches, double* phase_fraction) {
   if (!c) return AMP_EINVAL;
-  if (n) *n = c->workers.size();
+  const size_t wpr = c->workers.size(), nw = c->last_stats.size() / NSTAT;   // workers of the last call
+  if (n) *n = nw ? nw : wpr * c->replicas;
   if (c->last_stats.empty()) return fail(c, AMP_ESTATE, "get_worker_stats: nothing run yet");
-  if (cap < c->workers.size()) return fail(c, AMP_ENOMEM, "get_worker_stats: %zu entries needed", c->workers.size());
-  for (size_t w = 0; w < c->workers.size(); ++w) {
+  if (cap < nw) return fail(c, AMP_ENOMEM, "get_worker_stats: %zu entries needed", nw);
+  for (size_t w = 0; w < nw; ++w) {
     const unsigned long long* s = &c->last_stats[NSTAT * w];
     if (wait_fraction) wait_fraction[w] = s[3] ? (double)s[0] / (double)s[3] : 0.0;
     if (messages) messages[w] = s[1];
     if (batches) batches[w] = s[2];
     if (phase_fraction)
-      for (int i = 0; i < 8; ++i) phase_fraction[8 * w + i] = getenv("AMP_RAW_PHASES") ? (double)s[4 + i] : s[3] ? (double)s[4 + i] / (double)s[3] : 0.0;
-    if (node_of_worker) node_of_worker[w] = c->workers[w].node;
+      for (int i = 0; i < 8; ++i) phase_fraction[8 * w + i] = s[3] ? (double)s[4 + i] / (double)s[3] : 0.0;
+    if (node_of_worker) node_of_worker[w] = c->workers[w % wpr].node;
   }
   return AMP_OK;
 }
@@ -765,46 +783,45 @@ int upload(amp_ctx* c, size_t& off, const std::vector<T>& v, const void** dst) {
   return AMP_OK;
 }
 
-int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
-  InstSet& S = c->sets[which];
-  if (S.n() == 0) return fail(c, AMP_ESTATE, "no instances submitted");
-  if (c->model == AMP_MODEL_TREE && c->nodes[0].muf > AMP_TREE_LOOKUP_MAX_MUF)
-    return fail(c, AMP_EUNSUPPORTED, "the tree lookup supports min_update_frequency up to %d", AMP_TREE_LOOKUP_MAX_MUF);
-  for (const HostNode& n : c->nodes)
-    if (n.name != "lookup" && n.muf > AMP_DENSE_MAX_MUF)
-      return fail(c, AMP_EUNSUPPORTED, "dense nodes support min_update_frequency up to %d", AMP_DENSE_MAX_MUF);
-  const size_t n_total = S.n() * (size_t)epochs;
-  if (n_total >= 0xffffffffull) return fail(c, AMP_EINVAL, "too many admissions for one call");
-  int dev_id = 0;
-  HIPCHK(c, hipGetDevice(&dev_id));
-  hipDeviceProp_t prop;
-  HIPCHK(c, hipGetDeviceProperties(&prop, dev_id));
-  if ((int)c->workers.size() > prop.multiProcessorCount)
-    return fail(c, AMP_EUNSUPPORTED, "%zu workers do not fit %d compute units", c->workers.size(), prop.multiProcessorCount);
+template <class T>
+void copy_range(std::vector<T>& dst, const std::vector<T>& src, size_t lo, size_t hi) {
+  if (hi > lo) dst.insert(dst.end(), src.begin() + lo, src.begin() + hi);
+}
 
-  if (!c->state_zeroed) {
-    // accumulators, optimizer slots, per-worker counters start at zero
-    for (HostNode& n : c->nodes) {
-      HIPCHK(c, hipMemsetAsync(c->arena + n.off_G, 0, n.count() * 4, c->stream));
-      HIPCHK(c, hipMemsetAsync(c->arena + n.off_M, 0, n.count() * 4, c->stream));
-      HIPCHK(c, hipMemsetAsync(c->arena + n.off_V, 0, n.count() * 4, c->stream));
-    }
-    for (HostWorker& w : c->workers) HIPCHK(c, hipMemsetAsync(c->arena + w.off_state, 0, 64, c->stream));
-    for (int i = 0; i < AMP_MAX_BUFS; ++i)
-      if (c->buf_bytes[i]) HIPCHK(c, hipMemsetAsync(c->arena + c->off_buf[i], 0, c->buf_bytes[i], c->stream));
-    c->state_zeroed = true;
+// Appends instance i of S to D (all flattened arrays, adjacency tables included).
+void append_instance(const amp_ctx* c, InstSet& D, const InstSet& S, size_t i) {
+  const size_t T = (size_t)c->dims.n_edge_types;
+  if (!S.x.empty()) copy_range(D.x, S.x, i * c->dims.d_in, (i + 1) * c->dims.d_in);
+  D.target.push_back(S.target[i]);
+  const size_t t0 = S.tok_off[i], t1 = S.tok_off[i + 1], l0 = S.lab_off[i], l1 = S.lab_off[i + 1];
+  const size_t n0 = S.node_off[i], n1 = S.node_off[i + 1], e0 = S.edge_off[i], e1 = S.edge_off[i + 1];
+  copy_range(D.tok, S.tok, t0, t1);
+  copy_range(D.lab, S.lab, l0, l1);
+  copy_range(D.left, S.left, n0, n1);
+  copy_range(D.right, S.right, n0, n1);
+  copy_range(D.parent, S.parent, n0, n1);
+  if (!S.tnode.empty()) copy_range(D.tnode, S.tnode, 4 * n0, 4 * n1);
+  copy_range(D.src, S.src, e0, e1);
+  copy_range(D.dst, S.dst, e0, e1);
+  copy_range(D.etype, S.etype, e0, e1);
+  if (!S.tcount.empty()) {
+    const size_t N = t1 - t0;
+    copy_range(D.tcount, S.tcount, 8 * i, 8 * i + 8);
+    copy_range(D.tstart, S.tstart, 9 * i, 9 * i + 9);
+    copy_range(D.inoff, S.inoff, t0 + i, t0 + i + N + 1);
+    copy_range(D.inedge, S.inedge, e0, e1);
+    copy_range(D.tedge, S.tedge, e0, e1);
+    copy_range(D.tsoff, S.tsoff, T * (t0 + i), T * (t0 + i) + T * (N + 1));
+    copy_range(D.tsk, S.tsk, e0, e1);
   }
-  for (HostNode& n : c->nodes)
-    if (n.dirty) {
-      HIPCHK(c, hipMemcpyAsync(c->arena + n.off_P, n.params.data(), n.count() * 4, hipMemcpyHostToDevice, c->stream));
-      n.dirty = false;
-    }
+  D.tok_off.push_back((int)D.tok.size());
+  D.lab_off.push_back((int)D.lab.size());
+  D.node_off.push_back((int)D.left.size());
+  D.edge_off.push_back((int)D.src.size());
+  D.keys.push_back(S.keys[i]);
+}
 
-  // ---- per-call region: instance set, results, event record
-  AmpDev D;
-  std::memset(&D, 0, sizeof D);
-  size_t off = c->static_end;
-  DataDev& dd = D.data;
+int upload_set(amp_ctx* c, size_t& off, const InstSet& S, DataDev& dd) {
   dd.n_inst = (int)S.n();
   dd.n_x = c->dims.d_in;
   int r;
@@ -830,181 +847,288 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   if ((r = upload(c, off, S.tedge, (const void**)&dd.tedge))) return r;
   if ((r = upload(c, off, S.tsoff, (const void**)&dd.tsoff))) return r;
   if ((r = upload(c, off, S.tsk, (const void**)&dd.tsk))) return r;
+  return AMP_OK;
+}
+
+// Everything replica r owns in the static part of the arena lies rep_stride bytes after replica r - 1's.
+char* rep_ptr(const amp_ctx* c, int r, size_t off) { return c->arena + (size_t)r * c->rep_stride + off; }
+
+// One launch: every replica trains (or evaluates) `epochs` passes over its own instance set.
+// losses / correct: per replica, per admission of this launch.
+int launch_once(amp_ctx* c, const std::vector<const InstSet*>& sets, int epochs, bool train,
+                std::vector<std::vector<float>>& losses, std::vector<std::vector<int>>& correct, double& seconds) {
+  const int R = (int)sets.size();
+  const size_t wpr = c->workers.size();
+  size_t off = c->static_end;
   auto take = [&](size_t bytes) -> size_t {
     size_t o = off;
     off = align_up(off + bytes);
     return o;
   };
-  const size_t off_loss = take(n_total * 4), off_correct = take(n_total * 4), off_yhat = take(n_total * 4);
+  std::vector<AmpDev> Ds(R);
+  std::vector<size_t> off_loss(R), off_correct(R), off_yhat(R), n_total(R), off_stats(R);
+  std::vector<std::vector<size_t>> off_log(R, std::vector<size_t>(wpr)), off_logn(R, std::vector<size_t>(wpr));
   const size_t log_cap = train ? c->log_cap : 0;
-  std::vector<size_t> off_log(c->workers.size()), off_logn(c->workers.size());
-  for (size_t w = 0; w < c->workers.size(); ++w) {
-    off_log[w] = take(8 * std::max<size_t>(log_cap, 1));
-    off_logn[w] = take(64);
-  }
-  const size_t off_stats = take(8 * NSTAT * c->workers.size());
-  if (off > c->arena_bytes) return fail(c, AMP_ENOMEM, "arena of %zu bytes is too small, %zu needed", c->arena_bytes, off);
-  HIPCHK(c, hipMemsetAsync(c->arena + off_loss, 0, off - off_loss, c->stream));
+  const size_t off_devs = take(sizeof(AmpDev) * R);
+  for (int r = 0; r < R; ++r) {
+    AmpDev& D = Ds[r];
+    std::memset(&D, 0, sizeof D);
+    if (int rc = upload_set(c, off, *sets[r], D.data)) return rc;
+    n_total[r] = sets[r]->n() * (size_t)epochs;
+    const size_t zero_from = off;
+    off_loss[r] = take(n_total[r] * 4);
+    off_correct[r] = take(n_total[r] * 4);
+    off_yhat[r] = take(n_total[r] * 4);
+    for (size_t w = 0; w < wpr; ++w) {
+      off_log[r][w] = take(8 * std::max<size_t>(log_cap, 1));
+      off_logn[r][w] = take(64);
+    }
+    off_stats[r] = take(8 * NSTAT * wpr);
+    if (off > c->arena_bytes) return fail(c, AMP_ENOMEM, "arena of %zu bytes is too small, %zu needed", c->arena_bytes, off);
+    HIPCHK(c, hipMemsetAsync(c->arena + zero_from, 0, off - zero_from, c->stream));
 
-  // ---- device descriptor
-  for (size_t i = 0; i < c->off_ring_ent.size(); ++i) {
-    D.ring[i].ent = (unsigned long long*)(c->arena + c->off_ring_ent[i]);
-    D.ring[i].tail = (unsigned*)(c->arena + c->off_ring_tail[i]);
-    D.ring[i].mask = c->ring_cap - 1;
-    HIPCHK(c, hipMemsetAsync(D.ring[i].ent, 0, 8 * (size_t)c->ring_cap, c->stream));
-    HIPCHK(c, hipMemsetAsync(D.ring[i].tail, 0, 64, c->stream));
+    for (size_t i = 0; i < c->off_ring_ent.size(); ++i) {
+      D.ring[i].ent = (unsigned long long*)rep_ptr(c, r, c->off_ring_ent[i]);
+      D.ring[i].tail = (unsigned*)rep_ptr(c, r, c->off_ring_tail[i]);
+      D.ring[i].mask = c->ring_cap - 1;
+      HIPCHK(c, hipMemsetAsync(D.ring[i].ent, 0, 8 * (size_t)c->ring_cap, c->stream));
+      HIPCHK(c, hipMemsetAsync(D.ring[i].tail, 0, 64, c->stream));
+    }
+    for (size_t i = 0; i < c->nodes.size(); ++i) {
+      const HostNode& n = c->nodes[i];
+      NodeDev& nd = D.node[i];
+      nd.P = (float*)rep_ptr(c, r, n.off_P);
+      nd.G = (float*)rep_ptr(c, r, n.off_G);
+      nd.M = (float*)rep_ptr(c, r, n.off_M);
+      nd.V = (float*)rep_ptr(c, r, n.off_V);
+      nd.rows = n.rows;
+      nd.cols = n.cols;
+      nd.has_bias = n.has_bias;
+      nd.muf = n.muf;
+      nd.opt = n.opt;
+      nd.mean = c->mean;
+      nd.nblocks = n.nblocks;
+      nd.block = n.block;
+      nd.lr = n.op.lr;
+      nd.mom = n.op.momentum;
+      nd.b1 = n.op.beta1;
+      nd.b2 = n.op.beta2;
+      nd.eps = n.op.eps;
+      nd.seg = n.seg ? n.seg : n.cols;
+      nd.segp = n.seg ? n.segp : n.cols;
+    }
+    for (size_t i = 0; i < wpr; ++i) {
+      const HostWorker& w = c->workers[i];
+      WorkerDev& wd = D.worker[i];
+      wd.role = w.role;
+      wd.node = w.node;
+      wd.tile = w.tile;
+      wd.ntiles = w.ntiles;
+      wd.u0 = w.u0;
+      wd.nu = w.nu;
+      wd.ring = w.ring;
+      wd.aux = w.aux;
+      wd.wstate = (unsigned*)rep_ptr(c, r, w.off_state);
+      wd.log = (unsigned long long*)(c->arena + off_log[r][i]);
+      wd.log_n = (unsigned*)(c->arena + off_logn[r][i]);
+      wd.log_cap = (unsigned)log_cap;
+      wd.stats = (unsigned long long*)(c->arena + off_stats[r]) + NSTAT * i;
+      wd.pend = w.pend_bytes ? (float*)rep_ptr(c, r, w.off_pend) : nullptr;
+      wd.kb = w.kb;
+    }
+    D.model = c->model;
+    D.n_workers = (int)wpr;
+    D.n_nodes = (int)c->nodes.size();
+    D.mak = c->mak;
+    D.d_in = c->dims.d_in;
+    D.hidden = c->dims.hidden;
+    D.n_class = c->dims.n_class;
+    D.vocab = c->dims.vocab;
+    D.emb = c->dims.emb;
+    D.n_node_types = c->dims.n_node_types;
+    D.n_edge_types = c->dims.n_edge_types;
+    D.n_steps = c->dims.n_steps;
+    D.max_len = c->max_len;
+    D.max_edges = c->max_edges;
+    D.train = train ? 1 : 0;
+    if (c->model == AMP_MODEL_TREE) {
+      D.tiles_leaf = c->nodes[1].tiles;
+      D.tiles_branch = c->nodes[2].tiles;
+    }
+    D.n_total = (unsigned)n_total[r];
+    D.first_seq = train ? c->rep_admitted[r] : 0;
+    D.ctl = (unsigned*)rep_ptr(c, r, c->off_ctl);
+    D.slot_seq = (unsigned*)rep_ptr(c, r, c->off_slot_seq);
+    D.smeta = (int*)rep_ptr(c, r, c->off_smeta);
+    D.loss_out = (float*)(c->arena + off_loss[r]);
+    D.correct_out = (int*)(c->arena + off_correct[r]);
+    D.yhat_out = (float*)(c->arena + off_yhat[r]);
+    D.clock = (unsigned long long*)rep_ptr(c, r, c->off_clock);
+    D.watchdog_ticks = (long long)(c->watchdog_s * 1.0e8);   // wall_clock64 counts at 100 MHz
+    for (int i = 0; i < AMP_MAX_BUFS; ++i) {
+      D.buf[i] = c->buf_bytes[i] ? rep_ptr(c, r, c->off_buf[i]) : nullptr;
+      D.stride[i] = c->buf_stride[i];
+    }
+    HIPCHK(c, hipMemsetAsync(D.ctl, 0, 64, c->stream));
+    HIPCHK(c, hipMemsetAsync(D.clock, 0, 64, c->stream));
   }
-  for (size_t i = 0; i < c->nodes.size(); ++i) {
-    const HostNode& n = c->nodes[i];
-    NodeDev& nd = D.node[i];
-    nd.P = (float*)(c->arena + n.off_P);
-    nd.G = (float*)(c->arena + n.off_G);
-    nd.M = (float*)(c->arena + n.off_M);
-    nd.V = (float*)(c->arena + n.off_V);
-    nd.rows = n.rows;
-    nd.cols = n.cols;
-    nd.has_bias = n.has_bias;
-    nd.muf = n.muf;
-    nd.opt = n.opt;
-    nd.mean = c->mean;
-    nd.nblocks = n.nblocks;
-    nd.block = n.block;
-    nd.lr = n.op.lr;
-    nd.mom = n.op.momentum;
-    nd.b1 = n.op.beta1;
-    nd.b2 = n.op.beta2;
-    nd.eps = n.op.eps;
-    nd.seg = n.seg ? n.seg : n.cols;
-    nd.segp = n.seg ? n.segp : n.cols;
-  }
-  for (size_t i = 0; i < c->workers.size(); ++i) {
-    const HostWorker& w = c->workers[i];
-    WorkerDev& wd = D.worker[i];
-    wd.role = w.role;
-    wd.node = w.node;
-    wd.tile = w.tile;
-    wd.ntiles = w.ntiles;
-    wd.u0 = w.u0;
-    wd.nu = w.nu;
-    wd.ring = w.ring;
-    wd.aux = w.aux;
-    wd.wstate = (unsigned*)(c->arena + w.off_state);
-    wd.log = (unsigned long long*)(c->arena + off_log[i]);
-    wd.log_n = (unsigned*)(c->arena + off_logn[i]);
-    wd.log_cap = (unsigned)log_cap;
-    wd.stats = (unsigned long long*)(c->arena + off_stats) + NSTAT * i;
-    wd.pend = w.pend_bytes ? (float*)(c->arena + w.off_pend) : nullptr;
-    wd.kb = w.kb;
-  }
-  D.model = c->model;
-  D.n_workers = (int)c->workers.size();
-  D.n_nodes = (int)c->nodes.size();
-  D.mak = c->mak;
-  D.d_in = c->dims.d_in;
-  D.hidden = c->dims.hidden;
-  D.n_class = c->dims.n_class;
-  D.vocab = c->dims.vocab;
-  D.emb = c->dims.emb;
-  D.n_node_types = c->dims.n_node_types;
-  D.n_edge_types = c->dims.n_edge_types;
-  D.n_steps = c->dims.n_steps;
-  D.max_len = c->max_len;
-  D.max_edges = c->max_edges;
-  D.train = train ? 1 : 0;
-  if (c->model == AMP_MODEL_TREE) {
-    D.tiles_leaf = c->nodes[1].tiles;
-    D.tiles_branch = c->nodes[2].tiles;
-  }
-  D.n_total = (unsigned)n_total;
-  D.first_seq = train ? c->total_admitted : 0;
-  D.ctl = (unsigned*)(c->arena + c->off_ctl);
-  D.slot_seq = (unsigned*)(c->arena + c->off_slot_seq);
-  D.smeta = (int*)(c->arena + c->off_smeta);
-  D.loss_out = (float*)(c->arena + off_loss);
-  D.correct_out = (int*)(c->arena + off_correct);
-  D.yhat_out = (float*)(c->arena + off_yhat);
-  D.clock = (unsigned long long*)(c->arena + c->off_clock);
-  D.watchdog_ticks = (long long)(c->watchdog_s * 1.0e8);   // wall_clock64 counts at 100 MHz
-  for (int i = 0; i < AMP_MAX_BUFS; ++i) {
-    D.buf[i] = c->buf_bytes[i] ? c->arena + c->off_buf[i] : nullptr;
-    D.stride[i] = c->buf_stride[i];
-  }
-  HIPCHK(c, hipMemsetAsync(D.ctl, 0, 64, c->stream));
-  HIPCHK(c, hipMemsetAsync(D.clock, 0, 64, c->stream));
-  HIPCHK(c, hipMemcpyAsync(c->arena + c->off_dev, &D, sizeof D, hipMemcpyHostToDevice, c->stream));
+  HIPCHK(c, hipMemcpyAsync(c->arena + off_devs, Ds.data(), sizeof(AmpDev) * R, hipMemcpyHostToDevice, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
 
   hipEvent_t e0, e1;
   HIPCHK(c, hipEventCreate(&e0));
   HIPCHK(c, hipEventCreate(&e1));
   HIPCHK(c, hipEventRecord(e0, c->stream));
-  HIPCHK(c, amp_launch((const AmpDev*)(c->arena + c->off_dev), (int)c->workers.size(), c->stream));
+  HIPCHK(c, amp_launch((const AmpDev*)(c->arena + off_devs), R, (int)wpr, c->stream));
   HIPCHK(c, hipEventRecord(e1, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
   float ms = 0;
   HIPCHK(c, hipEventElapsedTime(&ms, e0, e1));
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
+  seconds += ms * 1e-3;
 
-  unsigned ctl[4] = {0, 0, 0, 0};
-  HIPCHK(c, hipMemcpy(ctl, D.ctl, sizeof ctl, hipMemcpyDeviceToHost));
-  if (ctl[0]) {
-    const char* why = ctl[0] == ABORT_WATCHDOG ? "a worker waited longer than the watchdog allows"
-                      : ctl[0] == ABORT_LOG_FULL ? "event record full"
-                                                 : "inconsistent state";
-    c->state_zeroed = false;   // device state is unreliable after an aborted run
-    for (HostNode& n : c->nodes) n.dirty = true;
-    return fail(c, AMP_EDEVICE, "kernel stopped itself: %s (worker %u)", why, ctl[2]);
+  for (int r = 0; r < R; ++r) {
+    unsigned ctl[4] = {0, 0, 0, 0};
+    HIPCHK(c, hipMemcpy(ctl, Ds[r].ctl, sizeof ctl, hipMemcpyDeviceToHost));
+    if (ctl[0]) {
+      const char* why = ctl[0] == ABORT_WATCHDOG ? "a worker waited longer than the watchdog allows"
+                        : ctl[0] == ABORT_LOG_FULL ? "event record full"
+                                                   : "inconsistent state";
+      c->state_zeroed = false;   // device state is unreliable after an aborted run
+      for (HostNode& n : c->nodes) n.dirty = true;
+      return fail(c, AMP_EDEVICE, "kernel stopped itself: %s (replica %d, worker %u)", why, r, ctl[2]);
+    }
   }
-  c->last_stats.assign(NSTAT * c->workers.size(), 0);
-  HIPCHK(c, hipMemcpy(c->last_stats.data(), c->arena + off_stats, 8 * NSTAT * c->workers.size(), hipMemcpyDeviceToHost));
-  std::vector<float> loss(n_total);
-  std::vector<int> correct(n_total);
-  HIPCHK(c, hipMemcpy(loss.data(), D.loss_out, n_total * 4, hipMemcpyDeviceToHost));
-  HIPCHK(c, hipMemcpy(correct.data(), D.correct_out, n_total * 4, hipMemcpyDeviceToHost));
-  uint64_t npred = 0;
-  if (c->model == AMP_MODEL_TREE)
-    for (int e = 0; e < epochs; ++e) npred += S.lab.size();
-  else
-    npred = n_total;
-  if (train) {
-    c->last_loss.swap(loss);
-    c->last_correct.swap(correct);
-    c->last_seconds = ms * 1e-3;
-    c->last_npred = npred;
-    c->total_admitted += (unsigned)n_total;
-    c->last_events.clear();
+  c->last_stats.assign(NSTAT * wpr * R, 0);
+  for (int r = 0; r < R; ++r) {
+    HIPCHK(c, hipMemcpy(c->last_stats.data() + NSTAT * wpr * r, c->arena + off_stats[r], 8 * NSTAT * wpr, hipMemcpyDeviceToHost));
+    const size_t base = losses[r].size();
+    losses[r].resize(base + n_total[r]);
+    correct[r].resize(base + n_total[r]);
+    HIPCHK(c, hipMemcpy(losses[r].data() + base, Ds[r].loss_out, n_total[r] * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(correct[r].data() + base, Ds[r].correct_out, n_total[r] * 4, hipMemcpyDeviceToHost));
+    if (train) c->rep_admitted[r] += (unsigned)n_total[r];
     if (log_cap) {
       std::vector<unsigned long long> raw(log_cap);
-      for (size_t w = 0; w < c->workers.size(); ++w) {
+      for (size_t w = 0; w < wpr; ++w) {
         unsigned n = 0;
-        HIPCHK(c, hipMemcpy(&n, c->arena + off_logn[w], 4, hipMemcpyDeviceToHost));
+        HIPCHK(c, hipMemcpy(&n, c->arena + off_logn[r][w], 4, hipMemcpyDeviceToHost));
         if (n > log_cap) n = (unsigned)log_cap;
-        if (n) HIPCHK(c, hipMemcpy(raw.data(), c->arena + off_log[w], 8 * (size_t)n, hipMemcpyDeviceToHost));
+        if (n) HIPCHK(c, hipMemcpy(raw.data(), c->arena + off_log[r][w], 8 * (size_t)n, hipMemcpyDeviceToHost));
         for (unsigned i = 0; i < n; ++i) {
           amp_event e;
-          e.worker = (uint16_t)w;
+          e.worker = (uint16_t)(r * wpr + w);
           e.kind = (uint8_t)((raw[i] >> 28) & 0xf);
           e.node = (uint8_t)((raw[i] >> 20) & 0xff);
           e.local = (uint32_t)(raw[i] & 0xfffff);
           e.seq = (uint32_t)(raw[i] >> 32);
-          c->last_events.push_back(e);
+          c->launch_events[r * wpr + w].push_back(e);
         }
       }
     }
+  }
+  return AMP_OK;
+}
+
+int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
+  InstSet& S = c->sets[which];
+  if (S.n() == 0) return fail(c, AMP_ESTATE, "no instances submitted");
+  if (c->model == AMP_MODEL_TREE && c->nodes[0].muf > AMP_TREE_LOOKUP_MAX_MUF)
+    return fail(c, AMP_EUNSUPPORTED, "the tree lookup supports min_update_frequency up to %d", AMP_TREE_LOOKUP_MAX_MUF);
+  for (const HostNode& n : c->nodes)
+    if (n.name != "lookup" && n.muf > AMP_DENSE_MAX_MUF)
+      return fail(c, AMP_EUNSUPPORTED, "dense nodes support min_update_frequency up to %d", AMP_DENSE_MAX_MUF);
+  if (S.n() * (size_t)epochs >= 0xffffffffull) return fail(c, AMP_EINVAL, "too many admissions for one call");
+  // evaluation runs on the first replica alone: after a training call all replicas hold the same parameters
+  const int R = train ? c->replicas : 1;
+  const size_t wpr = c->workers.size();
+  if (S.n() < (size_t)R) return fail(c, AMP_EINVAL, "fewer instances (%zu) than replicas (%d)", S.n(), R);
+  int dev_id = 0;
+  HIPCHK(c, hipGetDevice(&dev_id));
+  hipDeviceProp_t prop;
+  HIPCHK(c, hipGetDeviceProperties(&prop, dev_id));
+  if ((int)(wpr * c->replicas) > prop.multiProcessorCount)
+    return fail(c, AMP_EUNSUPPORTED, "%zu workers do not fit %d compute units", wpr * c->replicas, prop.multiProcessorCount);
+
+  if (!c->state_zeroed) {
+    // accumulators, optimizer slots, per-worker counters start at zero
+    for (int r = 0; r < c->replicas; ++r) {
+      for (HostNode& n : c->nodes) {
+        HIPCHK(c, hipMemsetAsync(rep_ptr(c, r, n.off_G), 0, n.count() * 4, c->stream));
+        HIPCHK(c, hipMemsetAsync(rep_ptr(c, r, n.off_M), 0, n.count() * 4, c->stream));
+        HIPCHK(c, hipMemsetAsync(rep_ptr(c, r, n.off_V), 0, n.count() * 4, c->stream));
+      }
+      for (HostWorker& w : c->workers) HIPCHK(c, hipMemsetAsync(rep_ptr(c, r, w.off_state), 0, 64, c->stream));
+      for (int i = 0; i < AMP_MAX_BUFS; ++i)
+        if (c->buf_bytes[i]) HIPCHK(c, hipMemsetAsync(rep_ptr(c, r, c->off_buf[i]), 0, c->buf_bytes[i], c->stream));
+    }
+    c->state_zeroed = true;
+  }
+  for (HostNode& n : c->nodes)
+    if (n.dirty) {
+      for (int r = 0; r < c->replicas; ++r)
+        HIPCHK(c, hipMemcpyAsync(rep_ptr(c, r, n.off_P), n.params.data(), n.count() * 4, hipMemcpyHostToDevice, c->stream));
+      n.dirty = false;
+    }
+
+  // replica r trains on instances r, r + R, r + 2R, ... of the set, in that order
+  std::vector<InstSet> parts;
+  std::vector<const InstSet*> sets;
+  if (R == 1) {
+    sets.push_back(&S);
+  } else {
+    parts.resize(R);
+    for (size_t i = 0; i < S.n(); ++i) append_instance(c, parts[i % R], S, i);
+    for (int r = 0; r < R; ++r) sets.push_back(&parts[r]);
+  }
+  std::vector<std::vector<float>> losses(R);
+  std::vector<std::vector<int>> correct(R);
+  double seconds = 0;
+  c->launch_events.assign(wpr * R, std::vector<amp_event>());
+  // with replicas the parameters are averaged at the end of every epoch (Section 5), hence one launch per epoch
+  const int launches = R > 1 ? epochs : 1, per_launch = R > 1 ? 1 : epochs;
+  for (int l = 0; l < launches; ++l) {
+    if (int rc = launch_once(c, sets, per_launch, train, losses, correct, seconds)) return rc;
+    if (R > 1)
+      for (HostNode& n : c->nodes)
+        HIPCHK(c, amp_average((float*)rep_ptr(c, 0, n.off_P), c->rep_stride / 4, R, n.count(), c->stream));
+  }
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+
+  // results in submit order, epoch by epoch
+  const size_t n = S.n(), n_total = n * (size_t)epochs;
+  std::vector<float> loss(n_total);
+  std::vector<int> corr(n_total);
+  for (int e = 0; e < epochs; ++e)
+    for (size_t i = 0; i < n; ++i) {
+      const size_t r = i % R, j = i / R;
+      loss[e * n + i] = losses[r][(size_t)e * sets[r]->n() + j];
+      corr[e * n + i] = correct[r][(size_t)e * sets[r]->n() + j];
+    }
+  uint64_t npred = c->model == AMP_MODEL_TREE ? (uint64_t)S.lab.size() * epochs : n_total;
+  if (train) {
+    c->last_loss.swap(loss);
+    c->last_correct.swap(corr);
+    c->last_seconds = seconds;
+    c->last_npred = npred;
+    c->last_events.clear();
+    for (auto& v : c->launch_events) c->last_events.insert(c->last_events.end(), v.begin(), v.end());
+    c->last_replicas = R;
   } else if (ev) {
     double sl = 0;
     uint64_t sc = 0;
     for (size_t i = 0; i < n_total; ++i) {
       sl += loss[i];
-      sc += correct[i];
+      sc += corr[i];
     }
     ev->mean_loss = sl / (double)n_total;
     ev->accuracy = c->model == AMP_MODEL_GGNN ? 0.0 : (double)sc / (double)npred;
     ev->n_instances = n_total;
     ev->n_predictions = npred;
-    ev->seconds = ms * 1e-3;
+    ev->seconds = seconds;
   }
+  c->launch_events.clear();
   return AMP_OK;
 }
 
@@ -1063,11 +1187,12 @@ int amp_get_staleness_hist(amp_ctx* c, uint64_t* bins, size_t nbins) {
   if (c->last_events.empty()) return fail(c, AMP_ESTATE, "get_staleness_hist: no event record (amp_set_event_log)");
   std::fill(bins, bins + nbins, 0);
   // per node: updates so far, and the value at each pending forward
-  const size_t nn = c->nodes.size();
+  const size_t nn1 = c->nodes.size(), wpr = c->workers.size(), nn = nn1 * (size_t)c->last_replicas;
   std::vector<uint64_t> updates(nn, 0);
   std::vector<std::vector<std::pair<uint64_t, uint64_t>>> pending(nn);   // (key, updates at forward)
-  for (const amp_event& e : c->last_events) {
-    if (e.worker == 0 || e.node >= nn) continue;
+  for (amp_event e : c->last_events) {
+    if (e.worker % wpr == 0 || e.node >= nn1) continue;
+    e.node = (uint8_t)(e.node + nn1 * (e.worker / wpr));   // every replica has its own copy of the node
     const uint64_t key = ((uint64_t)e.seq << 20) | e.local;
     if (e.kind == AMP_EV_U) {
       updates[e.node]++;

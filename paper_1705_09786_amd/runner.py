@@ -22,7 +22,7 @@ class Trainer:
 
     def __init__(self, model: str, dims: dict, params, max_active_keys: int, max_len: int, max_edges: int,
                  max_instances: int, arena_bytes: int = 1 << 30, tiles: dict | None = None, device: str = "cuda:0",
-                 in_hbm=()):
+                 in_hbm=(), replicas: int = 1):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the AMP path has no CPU fallback")
@@ -35,6 +35,8 @@ class Trainer:
         self.amp.build(model, dims)
         for node, n in (tiles or {}).items():
             self.amp.set_tiles(node, n)
+        if replicas != 1:
+            self.amp.set_replicas(replicas)
         for node in in_hbm:
             self.amp.set_weights_in_hbm(node, True)
         self.amp.finalize(max_active_keys, max_len, max_edges, max_instances)

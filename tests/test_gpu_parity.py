@@ -7,7 +7,9 @@ import pytest
 from oracle import direct
 from paper_1705_09786_amd import synth
 
-from util import check_controller_log, compare, gpu_train, oracle_replay
+from oracle import amp as oamp
+
+from util import check_controller_log, compare, gpu_train, named_logs, oracle_replay, oracle_runtime, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -192,3 +194,48 @@ def test_eval_matches_direct_forward(cfg, n, nv):
     assert ev2["accuracy"] == ev["accuracy"]
     # and training can continue afterwards
     a.train(1)
+
+
+@pytest.mark.parametrize("cfg,dims,R,mak,muf,lmuf,opt,n", [
+    (1, None, 4, 4, 3, None, SGD, 203),
+    (3, TREE_ODD, 3, 8, 3, 5, SGD, 50),
+    (4, GG_ODD, 2, 6, 4, 4, ADAM, 41),
+])
+def test_replicas_replay_parity(cfg, dims, R, mak, muf, lmuf, opt, n):
+    """Every parameterized node replicated R times, instance i routed to replica i mod R, parameters averaged
+    after each epoch (Section 5).  Two epochs as two training calls: each replica's record is replayed by a
+    checker runtime of its own on its share of the instances, then the runtimes are averaged, twice."""
+    from paper_1705_09786_amd import runner
+    if cfg == 1:
+        model, dims, data = synth.workload(1, n=n)
+    elif cfg == 3:
+        model, data = "tree", synth.make_tree(n, 27, dims, max_leaves=20)
+    else:
+        model, data = "ggnn", synth.make_ggnn(n, 28, dims)[0]
+    fp = synth.init_params(model, dims, 12)
+    g = gpu_train(model, dims, fp, data, mak, muf, opt, lookup_muf=lmuf, replicas=R, tiles={1: 2, 2: 3} if cfg == 3 else None)
+    a = g["trainer"].amp
+    wpr = a.num_workers() // R
+    rts = [oracle_runtime(model, dims, fp, muf, opt, lookup_muf=lmuf) for _ in range(R)]
+    parts = oamp.replica_subsets(data, R)
+    done = [0] * R
+    losses_gpu = g["losses"]
+    logs = g["logs"]
+    for epoch in range(2):
+        if epoch == 1:
+            a.train(1)
+            logs = a.get_event_log()
+            losses_gpu = a.get_instance_losses().astype(np.float64)
+        for r in range(R):
+            check = logs[r * wpr]
+            assert [e[2] for e in check if e[1] == "A"] == list(range(done[r], done[r] + len(parts[r])))
+            rts[r].replay(parts[r], named_logs(model, dims, logs[r * wpr + 1:(r + 1) * wpr]), first_seq=done[r])
+        oamp.average_replicas(rts)
+        params = g["trainer"].params()
+        for k, node in enumerate(rts[0].ppt):
+            assert rel_err(params[k], oamp.C.pack_node(node.P)) <= 1e-5, (epoch, node.name)
+        ref = np.array([rts[i % R].loss[done[i % R] + i // R] for i in range(len(data))])
+        le = np.abs(losses_gpu - ref) / np.maximum(np.abs(ref), 1.0)
+        assert le.max() <= 1e-5, (epoch, int(le.argmax()), float(le.max()))
+        for r in range(R):
+            done[r] += len(parts[r])

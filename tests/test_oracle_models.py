@@ -379,3 +379,42 @@ def test_replay_refuses_illegal_logs():
     bad[2] = [e for e in bad[2] if not (e[1] in "FB" and e[2] == 5)]
     with pytest.raises(RuntimeError):
         fresh().replay(data, bad)
+
+
+def test_replicas_with_one_update_per_epoch_equal_full_batch_sgd():
+    """Section 5: replicas are data parallelism.  If every replica makes exactly one update per epoch, from the
+    mean gradient of its (equally large) share, the average of the replicas is plain SGD on the mean gradient of
+    the whole set -- computed here by the direct trainer, which knows nothing of messages or replicas."""
+    model, dims, data = synth.workload(1, n=24)
+    fp = synth.init_params(model, dims, 3)
+    R, lr, epochs = 3, 0.1, 2
+    rts = []
+    for _ in range(R):
+        rt = amp.Runtime(model, dims, fp)
+        rt.set_muf(len(data) // R)
+        rt.set_optimizer(kind="sgd", lr=lr)
+        rts.append(rt)
+    losses = amp.run_replicas(rts, data, mak=2, epochs=epochs)
+    P = direct.unpack(model, dims, fp)
+    ref = []
+    for _ in range(epochs):
+        ref += direct.train(model, dims, P, data, lr=lr, batch=len(data))
+    assert np.allclose(losses, ref, rtol=1e-12, atol=1e-12)
+    for rt in rts:
+        for k, node in enumerate(rt.ppt):
+            for name in node.P:
+                assert np.allclose(node.P[name], P[k][name], rtol=1e-12, atol=1e-14), (k, name)
+
+
+def test_replica_routing_and_average():
+    data = list(range(10))
+    assert amp.replica_subsets(data, 3) == [[0, 3, 6, 9], [1, 4, 7], [2, 5, 8]]
+    model, dims, _ = synth.workload(1, n=1)
+    rts = [amp.Runtime(model, dims, synth.init_params(model, dims, s)) for s in (1, 2, 3, 4)]
+    before = [[{k: v.copy() for k, v in n.P.items()} for n in rt.ppt] for rt in rts]
+    amp.average_replicas(rts)
+    for k in range(len(rts[0].ppt)):
+        for name in rts[0].ppt[k].P:
+            want = (before[0][k][name] + before[1][k][name] + before[2][k][name] + before[3][k][name]) / 4.0
+            for rt in rts:
+                assert np.allclose(rt.ppt[k].P[name], want, rtol=0, atol=1e-15)

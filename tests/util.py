@@ -19,9 +19,10 @@ def f32(x):
 
 
 def gpu_train(model, dims, fp, data, mak, muf, opt, epochs=1, log=True, tiles=None, watchdog=5.0,
-              arena_bytes=1 << 30, lookup_muf=None, in_hbm=()):
+              arena_bytes=1 << 30, lookup_muf=None, in_hbm=(), replicas=1):
     ml, me = runner.max_len_of(model, data)
-    tr = runner.Trainer(model, dims, fp, mak, ml, me, len(data), arena_bytes=arena_bytes, tiles=tiles, in_hbm=in_hbm)
+    tr = runner.Trainer(model, dims, fp, mak, ml, me, len(data), arena_bytes=arena_bytes, tiles=tiles, in_hbm=in_hbm,
+                        replicas=replicas)
     a = tr.amp
     a.set_watchdog(watchdog)
     a.set_min_update_frequency(-1, muf)
@@ -38,6 +39,25 @@ def gpu_train(model, dims, fp, data, mak, muf, opt, epochs=1, log=True, tiles=No
     out = dict(params=tr.params(), losses=a.get_instance_losses().astype(np.float64), stats=a.get_loss(),
                logs=a.get_event_log() if log else None, trainer=tr)
     return out
+
+
+def oracle_runtime(model, dims, fp, muf, opt, lookup_muf=None):
+    names = [sh[0] for sh in synth.param_shapes(model, dims)]
+    rt = oamp.Runtime(model, dims, fp)
+    rt.set_muf(muf)
+    if lookup_muf is not None:
+        rt.set_muf(lookup_muf, "lookup")
+    kw = {k: (f32(v) if isinstance(v, float) else v) for k, v in opt.items()}
+    rt.set_optimizer(**kw)
+    if "lookup" in names:
+        rt.set_optimizer("lookup", kind="sgd", lr=kw["lr"])
+    return rt
+
+
+def named_logs(model, dims, logs):
+    """Worker logs (controller's excluded) with node ids turned into node names."""
+    names = [sh[0] for sh in synth.param_shapes(model, dims)]
+    return [[(names[n], k, s, l) for (n, k, s, l) in w] for w in logs]
 
 
 def oracle_replay(model, dims, fp, data, logs, muf, opt, lookup_muf=None):
