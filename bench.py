@@ -212,7 +212,7 @@ def main():
     # Beside the headline (one copy of the model, as the configuration names it): the paper's own way to use more
     # of the machine -- every parameterized node replicated, instances dealt round-robin to the replicas, parameters
     # averaged at the end of each epoch (Section 5).  A different training procedure, so reported apart from `value`.
-    R = args.replicas if args.replicas is not None else min(240 // n_workers, len(data) // (4 * cfg["mak"]))
+    R = args.replicas if args.replicas is not None else min(64, 240 // n_workers, len(data) // (4 * cfg["mak"]))
     if R > 1:
         tr.close()
         tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=24 << 30, tiles=cfg.get("tiles"),

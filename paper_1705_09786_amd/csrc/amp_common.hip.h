@@ -213,20 +213,23 @@ __device__ __forceinline__ void gemv_cols(const float* Wl, int ldw, int R, int C
 // lr = g * nu + j  <->  node row g * block + u0 + j.
 struct Tile {
   int R, C, ldw, nu, u0, block, nblocks, Rp;
-  int seg, segp, Cl;   // column segments (see NodeDev); Cl = padded column count
+  int seg, segp, seg0, Cl;   // column segments (see NodeDev); Cl = padded column count
   __device__ __forceinline__ int grow(int lr) const {
     const int g = lr / nu;
     return g * block + u0 + (lr - g * nu);
   }
   // LDS column of node column c
   __device__ __forceinline__ int lcol(int c) const {
-    const int sg = c / seg;
-    return sg * segp + (c - sg * seg);
+    if (c < seg0) return c;
+    const int sg = (c - seg0) / seg;
+    return (sg + 1) * segp + (c - seg0 - sg * seg);
   }
   // node column of LDS column lc, -1 for a padding column
   __device__ __forceinline__ int ncol(int lc) const {
     const int sg = lc / segp, o = lc - sg * segp;
-    return (lc < Cl && o < seg) ? sg * seg + o : -1;
+    if (lc >= Cl) return -1;
+    if (sg == 0) return o < seg0 ? o : -1;
+    return o < seg ? seg0 + (sg - 1) * seg + o : -1;
   }
 };
 
@@ -240,7 +243,8 @@ __device__ __forceinline__ Tile make_tile(const GQ NodeDev& nd, const GQ WorkerD
   t.C = nd.cols;
   t.seg = nd.seg;
   t.segp = nd.segp;
-  t.Cl = (nd.cols / nd.seg) * nd.segp;
+  t.seg0 = nd.seg0;
+  t.Cl = ((nd.cols - nd.seg0) / nd.seg + 1) * nd.segp;
   t.ldw = amp_ldrow(t.Cl);
   t.Rp = amp_round16(t.R);
   return t;

@@ -81,9 +81,10 @@ struct NodeDev {
   int opt, mean, nblocks, block;   // rows = nblocks * block (gate blocks)
   float lr, mom, b1, b2, eps;
   // Column layout of the node's LDS tile and pending inputs: the cols columns
-  // form cols / seg segments of seg columns, each padded to segp (a multiple
-  // of 4) so that a segment can be fetched from its own 16-byte aligned row.
-  int seg, segp, pad;
+  // form a first segment of seg0 columns and (cols - seg0) / seg more of seg
+  // columns, each padded to segp (a multiple of 4) so that a segment can be
+  // fetched from its own 16-byte aligned row.
+  int seg, segp, seg0;
 };
 
 struct WorkerDev {
@@ -139,7 +140,7 @@ struct AmpDev {
   unsigned n_total, first_seq;
   unsigned* ctl;              // [0] abort code, [1] done, [2] abort detail
   unsigned* slot_seq;         // [mak] admission number held by each slot
-  int* smeta;                 // [mak][4] written at admission: admission number, length, node offset, token offset
+  int* smeta;                 // [mak][4] written at admission: admission number, length, node offset (RNN: instance), token offset
   float* loss_out;            // [n_total] summed loss of each admission
   int* correct_out;           // [n_total]
   float* yhat_out;            // [n_total] (GGNN prediction)

@@ -94,6 +94,16 @@ __device__ __noinline__ void role_ctrl(const GQ AmpDev* D, const GQ WorkerDev* W
           const unsigned t = ring_reserve(D->ring[1], L);
           for (int l = 0; l < L; ++l) ring_put(D->ring[1], t + l, MSG_MAKE(0, s, l));
         } else {
+          if (D->model == 2) {
+            // RNN: admission number, length, instance, token offset
+            const int inst = seq % D->data.n_inst;
+            const int toff = D->data.tok_off[inst];
+            int* sm = D->smeta + 4 * s;
+            sm[0] = (int)seq;
+            sm[1] = D->data.tok_off[inst + 1] - toff;
+            sm[2] = inst;
+            sm[3] = toff;
+          }
           fence_release();
           ring_post(D->ring[1], MSG_MAKE(0, s, 0));
         }
@@ -218,191 +228,9 @@ __device__ __noinline__ void role_mlp_lin(const GQ AmpDev* D, const GQ WorkerDev
   }
 }
 
-// ============================================================ RNN
-// The cell worker hosts the lookup table and the recurrent cell (Figure 2):
-// Concat(embedding, h) -> Linear-1 -> tanh -> Isu(t+1) -> Cond(end?) is one
-// forward event; the loop edge is a message to itself.
-// Slot storage: buf[0]=hs[mak][max_len][H] cell outputs, buf[1]=es[mak][max_len][E]
-// embeddings recorded at forward time, buf[2]=dh[mak][H] gradient w.r.t. the
-// hidden state travelling down the loop.
-__device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDev* W) {
-  float* lds = amp_lds;
-  const GQ NodeDev& nd = D->node[1];
-  const GQ NodeDev& lk = D->node[0];
-  const Tile t = make_tile(nd, W);
-  const int H = t.R, C = t.C, E = D->emb, V = D->vocab, TM = D->max_len;
-  Lds L{lds};
-  float* Wl = L.take(t.Rp * t.ldw);
-  float* bl = L.take(t.Rp);
-  float* El = L.take(V * E);
-  float* xs = L.take(C);
-  float* ys = L.take(H);
-  float* ds = L.take(H);
-  float* dx = L.take(C);
-  float* part = L.take(8 * (H > C ? H : C));
-  tile_load(nd, t, Wl, bl);
-  for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) El[i] = lk.P[i];
-  __syncthreads();
-  float* hs = (float*)D->buf[0];
-  float* es = (float*)D->buf[1];
-  float* dh = (float*)D->buf[2];
-  const GQ RingDev& mine = D->ring[W->ring];
-  const GQ RingDev& out = D->ring[W->ring + 1];
-  unsigned head = 0, code;
-  unsigned count = W->wstate[0], tstep = W->wstate[1], lcount = W->wstate[2], lstep = W->wstate[3];
-  while (wait_msg(D, mine, head, s_ctl, code)) {
-    const int s = MSG_SLOT(code), tt = MSG_LOCAL(code);
-    const unsigned seq = D->slot_seq[s];
-    const int inst = seq % D->data.n_inst;
-    const int toff = D->data.tok_off[inst];
-    const int T = D->data.tok_off[inst + 1] - toff;
-    const int tok = D->data.tok[toff + tt];
-    float* h_t = hs + ((long long)s * TM + tt) * H;
-    float* e_t = es + ((long long)s * TM + tt) * E;
-    if (!(code & MSG_DIR_B)) {
-      for (int c = threadIdx.x; c < C; c += AMP_THREADS) {
-        float v;
-        if (c < E) {
-          v = El[tok * E + c];
-          e_t[c] = v;
-        } else {
-          v = tt == 0 ? 0.f : h_t[c - E - H];   // previous step's output
-        }
-        xs[c] = v;
-      }
-      __syncthreads();
-      gemv_rows(Wl, t.ldw, H, C, bl, xs, part, ys);
-      for (int r = threadIdx.x; r < H; r += AMP_THREADS) h_t[r] = tanhf(ys[r]);
-      LOG(0, 0, seq, tt);
-      LOG(1, 0, seq, tt);
-      __syncthreads();
-      if (threadIdx.x == 0) {
-        fence_release();
-        if (tt + 1 < T)
-          ring_post(mine, MSG_MAKE(0, s, tt + 1));
-        else
-          ring_post(out, MSG_MAKE(0, s, 0));
-      }
-      continue;
-    }
-    // backward through step tt
-    for (int c = threadIdx.x; c < C; c += AMP_THREADS) xs[c] = c < E ? e_t[c] : (tt == 0 ? 0.f : h_t[c - E - H]);
-    for (int r = threadIdx.x; r < H; r += AMP_THREADS) {
-      const float y = h_t[r];
-      ds[r] = dh[(long long)s * H + r] * (1.f - y * y);
-    }
-    __syncthreads();
-    LOG(1, 1, seq, tt);
-    gemv_cols(Wl, t.ldw, H, C, ds, part, dx);
-    for (int c = threadIdx.x; c < C; c += AMP_THREADS) {
-      if (c < E) {
-        float* g = lk.G + (long long)tok * E + c;
-        *g += dx[c];
-      } else {
-        dh[(long long)s * H + c - E] = dx[c];
-      }
-    }
-    tile_accumulate(nd, t, ds, xs);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      fence_release();
-      if (tt > 0)
-        ring_post(mine, MSG_MAKE(1, s, tt - 1));
-      else
-        ring_post(D->ring[0], MSG_MAKE(1, s, 0));
-    }
-    count_and_update(D, W, nd, t, Wl, bl, count, tstep);
-    LOG(0, 1, seq, tt);
-    lcount++;
-    if ((int)lcount >= lk.muf) {
-      // lookup update: plain SGD over the whole (small) table
-      lstep++;
-      __syncthreads();
-      const float sc = lk.lr * (lk.mean ? 1.f / (float)lcount : 1.f);
-      for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) {
-        El[i] -= sc * lk.G[i];
-        lk.G[i] = 0.f;
-      }
-      __syncthreads();
-      lcount = 0;
-      LOG(0, 2, 0, 0);
-    }
-  }
-  tile_store(nd, t, Wl, bl);
-  for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) lk.P[i] = El[i];
-  if (threadIdx.x == 0) {
-    W->wstate[0] = count;
-    W->wstate[1] = tstep;
-    W->wstate[2] = lcount;
-    W->wstate[3] = lstep;
-  }
-}
-
-// Output layer + softmax loss of the RNN: forward and backward in one event.
-__device__ __noinline__ void role_rnn_out(const GQ AmpDev* D, const GQ WorkerDev* W) {
-  float* lds = amp_lds;
-  const GQ NodeDev& nd = D->node[2];
-  const Tile t = make_tile(nd, W);
-  const int R = t.R, C = t.C, TM = D->max_len;
-  Lds L{lds};
-  float* Wl = L.take(t.Rp * t.ldw);
-  float* bl = L.take(t.Rp);
-  float* xs = L.take(C);
-  float* ys = L.take(R);
-  float* ds = L.take(R);
-  float* dx = L.take(C);
-  float* part = L.take(8 * (R > C ? R : C));
-  tile_load(nd, t, Wl, bl);
-  const float* hs = (const float*)D->buf[0];
-  float* dh = (float*)D->buf[2];
-  const GQ RingDev& mine = D->ring[W->ring];
-  const GQ RingDev& cell = D->ring[W->ring - 1];
-  unsigned head = 0, code;
-  unsigned count = W->wstate[0], tstep = W->wstate[1];
-  while (wait_msg(D, mine, head, s_ctl, code)) {
-    const int s = MSG_SLOT(code);
-    const unsigned seq = D->slot_seq[s];
-    const int inst = seq % D->data.n_inst;
-    const int T = D->data.tok_off[inst + 1] - D->data.tok_off[inst];
-    const float* x = hs + ((long long)s * TM + (T - 1)) * C;
-    for (int c = threadIdx.x; c < C; c += AMP_THREADS) xs[c] = x[c];
-    __syncthreads();
-    gemv_rows(Wl, t.ldw, R, C, bl, xs, part, ys);
-    LOG(2, 0, seq, 0);
-    const int label = D->data.lab[D->data.lab_off[inst]];
-    softmax_xent_wave0(ys, R, label, ds, &s_loss, &s_pred);
-    if (threadIdx.x == 0) {
-      D->loss_out[seq - D->first_seq] = s_loss;
-      D->correct_out[seq - D->first_seq] = s_pred == label;
-    }
-    if (!D->train) {
-      __syncthreads();
-      if (threadIdx.x == 0) {
-        fence_release();
-        ring_post(D->ring[0], MSG_MAKE(1, s, 0));
-      }
-      continue;
-    }
-    LOG(2, 1, seq, 0);
-    gemv_cols(Wl, t.ldw, R, C, ds, part, dx);
-    for (int c = threadIdx.x; c < C; c += AMP_THREADS) dh[(long long)s * C + c] = dx[c];
-    tile_accumulate(nd, t, ds, xs);
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      fence_release();
-      ring_post(cell, MSG_MAKE(1, s, T - 1));
-    }
-    count_and_update(D, W, nd, t, Wl, bl, count, tstep);
-  }
-  tile_store(nd, t, Wl, bl);
-  if (threadIdx.x == 0) {
-    W->wstate[0] = count;
-    W->wstate[1] = tstep;
-  }
-}
-
 #include "amp_batch.hip.h"
 #include "amp_tree.hip.h"
+#include "amp_rnn.hip.h"
 #include "amp_ggnn.hip.h"
 
 // ============================================================ entry
@@ -421,7 +249,13 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
   switch (W->role) {
     case ROLE_CTRL: role_ctrl(D, W); break;
     case ROLE_MLP_LIN: role_mlp_lin(D, W); break;
-    case ROLE_RNN_CELL: role_rnn_cell(D, W); break;
+    case ROLE_RNN_CELL:
+      // hidden = emb = 128 (8 row blocks, 16 column groups) has products with fixed trip counts
+      if (D->node[1].rows == 128 && D->node[1].cols == 256 && D->node[1].seg0 == 128)
+        role_rnn_cell<8, 16>(D, W);
+      else
+        role_rnn_cell<0, 0>(D, W);
+      break;
     case ROLE_RNN_OUT: role_rnn_out(D, W); break;
     case ROLE_TREE_LOOKUP: role_tree_lookup(D, W); break;
     case ROLE_TREE_LEAF:

@@ -28,8 +28,9 @@ struct HostNode {
   int rows = 0, cols = 0, has_bias = 0, nblocks = 1, block = 0;
   int muf = 1, opt = AMP_OPT_SGD, tiles = 1;
   int in_hbm = 0;           // tiles read the weights from HBM even if they would fit LDS
-  int seg = 0, segp = 0;    // column segments of the LDS layout (0 = one unpadded segment)
-  int cl() const { return seg ? (cols / seg) * segp : cols; }
+  int seg = 0, segp = 0, seg0 = 0;   // column segments of the LDS layout (seg 0 = one unpadded segment; seg0 0 = seg)
+  int first_seg() const { return seg0 ? seg0 : seg; }
+  int cl() const { return seg ? ((cols - first_seg()) / seg + 1) * segp : cols; }
   amp_opt_params op{0.1f, 0.9f, 0.9f, 0.999f, 1e-8f};
   std::vector<float> params;
   bool dirty = true;        // host copy newer than device copy
@@ -172,6 +173,7 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
   if (R > AMP_THREADS) return 0;
   size_t f = 0;
   switch (w.role) {
+    case ROLE_RNN_CELL:
     case ROLE_TREE_LEAF:
     case ROLE_TREE_BRANCH: {
       // the largest batch (a multiple of 16 messages) whose pre-activation rows fit beside the weights
@@ -222,9 +224,8 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
     case ROLE_G_READOUT:
       f = wfl + r4(c->dims.hidden) + AMP_THREADS;
       break;
-    default:   // MLP / RNN workers
+    default:   // MLP layers, RNN output layer
       f = wfl + r4(C) + r4(R) + r4(R) + r4(C) + r4(8 * std::max(R, C));
-      if (w.role == ROLE_RNN_CELL) f += r4((size_t)c->dims.vocab * c->dims.emb);
   }
   return f <= avail ? f : 0;
 }
@@ -268,6 +269,10 @@ int amp_build_rnn(amp_ctx* c, const amp_model_dims* d) {
   c->dims = *d;
   c->nodes = {make_node("lookup", d->vocab, d->emb, 0), make_node("cell", d->hidden, d->emb + d->hidden, 1),
               make_node("out", d->n_class, d->hidden, 1)};
+  // the cell's input is Concat(embedding, h): two column segments with a common padded width
+  c->nodes[1].seg0 = d->emb;
+  c->nodes[1].seg = d->hidden;
+  c->nodes[1].segp = amp_round4(std::max(d->emb, d->hidden));
   return AMP_OK;
 }
 
@@ -468,9 +473,13 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
   if (c->model == AMP_MODEL_MLP) {
     for (int i = 0; i < 4; ++i) buf(i, H);
   } else if (c->model == AMP_MODEL_RNN) {
-    buf(0, (size_t)c->max_len * H);
-    buf(1, (size_t)c->max_len * c->dims.emb);
-    buf(2, H);
+    const size_t SP = c->nodes[1].segp;
+    buf(0, ((size_t)c->max_len + 1) * SP);
+    buf(1, (size_t)c->max_len * SP);
+    buf(2, SP);
+    c->buf_stride[3] = 0;
+    c->buf_bytes[3] = 4 * 64 * SP;
+    c->off_buf[3] = take(c->buf_bytes[3]);
   } else if (c->model == AMP_MODEL_TREE) {
     const size_t L = c->max_len, N2 = 2 * L - 1, E = c->dims.emb, Ep = amp_round4(c->dims.emb), Hp = amp_round4(c->dims.hidden);
     const size_t TL = c->nodes[1].tiles, TB = c->nodes[2].tiles;
@@ -916,6 +925,7 @@ int launch_once(amp_ctx* c, const std::vector<const InstSet*>& sets, int epochs,
       nd.eps = n.op.eps;
       nd.seg = n.seg ? n.seg : n.cols;
       nd.segp = n.seg ? n.segp : n.cols;
+      nd.seg0 = n.seg ? n.first_seg() : n.cols;
     }
     for (size_t i = 0; i < wpr; ++i) {
       const HostWorker& w = c->workers[i];

@@ -46,7 +46,15 @@ def test_mlp_mak1_is_synchronous_sgd():
         assert np.linalg.norm(g["params"][k] - refv) / np.linalg.norm(refv) <= 1e-5
 
 
-@pytest.mark.parametrize("mak,muf,opt,n", [(1, 1, SGD, 200), (16, 1, SGD, 600), (16, 7, ADAM, 600)])
+# The recurrent model under Adam at lr = 0.002 is a chaotic training run: the checker's own result moves by O(1)
+# when its initial parameters are perturbed by 1e-7 (relative), so no fp32 implementation can follow it to 1e-5.
+# At lr = 5e-4 over 300 sequences the same perturbation stays at 1e-7 (the CPU suite checks this), and that
+# is the setting the recurrent Adam case uses.
+RNN_ADAM = dict(kind="adam", lr=0.0005, beta1=0.9, beta2=0.999, eps=1e-6)
+
+
+@pytest.mark.parametrize("mak,muf,opt,n", [(1, 1, SGD, 200), (16, 1, SGD, 600), (16, 7, SGD, 600), (4, 3, RNN_ADAM, 300),
+                                           (16, 7, RNN_ADAM, 300)])
 def test_rnn_replay_parity(mak, muf, opt, n):
     model, dims, data = synth.workload(2, n=n)
     fp = synth.init_params(model, dims, 6)
