@@ -30,9 +30,11 @@ CLOCK_HZ = 2.4e9
 LDS_BYTES_PER_CLK_PER_CU = 128
 N_CU = 256
 FP32_MFMA_PEAK = 157.3e12          # whole chip, dense fp32 matrix
-# HBM bytes per launch of the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a copy of
-# known size (profiles/amp_persistent_treelstm_h150_8544trees.md); only quoted for exactly that configuration.
-MEASURED_HBM_BYTES_PER_LAUNCH = {(3, 64, 50, 8544): 49.8e9}
+# HBM bytes per launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a copy of known size (the summaries
+# under profiles/); only quoted for exactly the configuration (workload, max_active_keys, min_update_frequency,
+# instances) that was profiled.
+MEASURED_HBM_BYTES_PER_LAUNCH = {(3, 64, 50, 8544): 49.8e9, (2, 16, 16, 10000): 2.34e9, (4, 32, 20, 20000): 46.8e9,
+                                 (5, 128, 50, 8544): 2.39e12}
 
 DEFAULTS = {
     # cfg: mak, muf, lookup muf, optimizer
