@@ -122,43 +122,89 @@ __device__ __forceinline__ int wait_batch(const GQ AmpDev* D, const GQ RingDev& 
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_16x16x4f32((a), (b), (c), 0, 0, 0)
 
 // Y[j][r] = b[r] + sum_c W[r][c] X[j][c]   (M = weight rows, N = messages, K = columns)
-__device__ __noinline__ void mfma_rows(const LDSQ float* Wl, int ldw, int NRB, int NCG, const LDSQ float* bl,
-                                       const LDSQ float* X, int ldx, int NB, LDSQ float* Y, int ldy) {
+// Generic shape: one (row block, message block) item per wave at a time.
+__device__ __noinline__ void mfma_rows_any(const LDSQ float* Wl, int ldw, int NRB, int NCG, const LDSQ float* bl,
+                                           const LDSQ float* X, int ldx, int NB, LDSQ float* Y, int ldy) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
   for (int item = wave; item < NRB * NB; item += AMP_THREADS / 64) {
     const int rb = item % NRB, nb = item / NRB;
     const LDSQ float* wp = Wl + (rb * 16 + i) * ldw + 4 * q;
     const LDSQ float* xp = X + (nb * 16 + i) * ldx + 4 * q;
     v4f acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-    int g = 0;
-    for (; g + 1 < NCG; g += 2) {
-      const v4f w0 = *(const LDSQ v4f*)(wp + 16 * g), x0 = *(const LDSQ v4f*)(xp + 16 * g);
-      const v4f w1 = *(const LDSQ v4f*)(wp + 16 * g + 16), x1 = *(const LDSQ v4f*)(xp + 16 * g + 16);
-      acc0 = MFMA(w0.x, x0.x, acc0);
-      acc1 = MFMA(w1.x, x1.x, acc1);
-      acc0 = MFMA(w0.y, x0.y, acc0);
-      acc1 = MFMA(w1.y, x1.y, acc1);
-      acc0 = MFMA(w0.z, x0.z, acc0);
-      acc1 = MFMA(w1.z, x1.z, acc1);
-      acc0 = MFMA(w0.w, x0.w, acc0);
-      acc1 = MFMA(w1.w, x1.w, acc1);
-    }
-    if (g < NCG) {
+    for (int g = 0; g < NCG; ++g) {
       const v4f w0 = *(const LDSQ v4f*)(wp + 16 * g), x0 = *(const LDSQ v4f*)(xp + 16 * g);
       acc0 = MFMA(w0.x, x0.x, acc0);
-      acc0 = MFMA(w0.y, x0.y, acc0);
+      acc1 = MFMA(w0.y, x0.y, acc1);
       acc0 = MFMA(w0.z, x0.z, acc0);
-      acc0 = MFMA(w0.w, x0.w, acc0);
+      acc1 = MFMA(w0.w, x0.w, acc1);
     }
     const v4f b4 = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
     *(LDSQ v4f*)(Y + (nb * 16 + i) * ldy + rb * 16 + 4 * q) = acc0 + acc1 + b4;
   }
+}
+
+// Fixed shape (NRB row blocks, NCG column groups, NB message blocks known at compile time): a wave owns row
+// block rb for all message blocks, so a weight operand is read once for NB products and the unrolled loop keeps
+// 2 NB (4 for NB = 1) independent accumulators going.
+template <int NRB, int NCG, int NB>
+__device__ __forceinline__ void mfma_rows_fixed(const LDSQ float* Wl, int ldw, const LDSQ float* bl, const LDSQ float* X, int ldx,
+                                                LDSQ float* Y, int ldy) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  constexpr int NA = NB == 1 ? 4 : 2;
+  const v4f zero = {0.f, 0.f, 0.f, 0.f};
+  for (int rb = wave; rb < NRB; rb += AMP_THREADS / 64) {
+    const LDSQ float* wp = Wl + (rb * 16 + i) * ldw + 4 * q;
+    const LDSQ float* xp = X + i * ldx + 4 * q;
+    v4f acc[NB][NA];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int a = 0; a < NA; ++a) acc[nb][a] = zero;
+#pragma unroll
+    for (int g = 0; g < NCG; ++g) {
+      const v4f w = *(const LDSQ v4f*)(wp + 16 * g);
+      v4f x[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) x[nb] = *(const LDSQ v4f*)(xp + nb * 16 * ldx + 16 * g);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        acc[nb][0] = MFMA(w.x, x[nb].x, acc[nb][0]);
+        acc[nb][1] = MFMA(w.y, x[nb].y, acc[nb][1]);
+      }
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        acc[nb][NA == 4 ? 2 : 0] = MFMA(w.z, x[nb].z, acc[nb][NA == 4 ? 2 : 0]);
+        acc[nb][NA == 4 ? 3 : 1] = MFMA(w.w, x[nb].w, acc[nb][NA == 4 ? 3 : 1]);
+      }
+    }
+    const v4f b4 = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      v4f r = acc[nb][0] + acc[nb][1] + b4;
+      if (NA == 4) r += acc[nb][2] + acc[nb][3];
+      *(LDSQ v4f*)(Y + (nb * 16 + i) * ldy + rb * 16 + 4 * q) = r;
+    }
+  }
+}
+
+// NRBT / NCGT = 0: shape known only at run time.  Ends with a barrier.
+template <int NRBT, int NCGT>
+__device__ __forceinline__ void mfma_rows(const LDSQ float* Wl, int ldw, int NRB, int NCG, const LDSQ float* bl,
+                                          const LDSQ float* X, int ldx, int NB, LDSQ float* Y, int ldy) {
+  if (NRBT && NB == 1)
+    mfma_rows_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 1>(Wl, ldw, bl, X, ldx, Y, ldy);
+  else if (NRBT && NB == 2)
+    mfma_rows_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 2>(Wl, ldw, bl, X, ldx, Y, ldy);
+  else if (NRBT && NB == 3)
+    mfma_rows_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 3>(Wl, ldw, bl, X, ldx, Y, ldy);
+  else
+    mfma_rows_any(Wl, ldw, NRB, NCG, bl, X, ldx, NB, Y, ldy);
   lds_barrier();
 }
 
 // DX[j][c] = sum_r W[r][c] D[j][r]   (M = weight columns, N = messages, K = weight rows)
-__device__ __noinline__ void mfma_cols(const LDSQ float* Wl, int ldw, int NRB, int NCG, const LDSQ float* Dl, int ldd,
-                                       int NB, LDSQ float* DX, int ldx) {
+__device__ __noinline__ void mfma_cols_any(const LDSQ float* Wl, int ldw, int NRB, int NCG, const LDSQ float* Dl, int ldd,
+                                           int NB, LDSQ float* DX, int ldx) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
   for (int item = wave; item < NCG * NB; item += AMP_THREADS / 64) {
     const int cb = item % NCG, nb = item / NCG;
@@ -176,6 +222,61 @@ __device__ __noinline__ void mfma_cols(const LDSQ float* Wl, int ldw, int NRB, i
     }
     *(LDSQ v4f*)(DX + (nb * 16 + i) * ldx + cb * 16 + 4 * q) = acc0 + acc1;
   }
+}
+
+// Fixed shape: a wave owns column group cb for all message blocks.
+template <int NRB, int NCG, int NB>
+__device__ __forceinline__ void mfma_cols_fixed(const LDSQ float* Wl, int ldw, const LDSQ float* Dl, int ldd, LDSQ float* DX,
+                                                int ldx) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  constexpr int NA = NB == 1 ? 4 : 2;
+  const v4f zero = {0.f, 0.f, 0.f, 0.f};
+  for (int cb = wave; cb < NCG; cb += AMP_THREADS / 64) {
+    const LDSQ float* wp = Wl + (4 * q) * ldw + cb * 16 + i;
+    const LDSQ float* dp = Dl + i * ldd + 4 * q;
+    v4f acc[NB][NA];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int a = 0; a < NA; ++a) acc[nb][a] = zero;
+#pragma unroll
+    for (int g = 0; g < NRB; ++g) {
+      v4f d[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) d[nb] = *(const LDSQ v4f*)(dp + nb * 16 * ldd + 16 * g);
+      const LDSQ float* w = wp + 16 * g * ldw;
+      const float w0 = w[0], w1 = w[ldw], w2 = w[2 * ldw], w3 = w[3 * ldw];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        acc[nb][0] = MFMA(w0, d[nb].x, acc[nb][0]);
+        acc[nb][1] = MFMA(w1, d[nb].y, acc[nb][1]);
+      }
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        acc[nb][NA == 4 ? 2 : 0] = MFMA(w2, d[nb].z, acc[nb][NA == 4 ? 2 : 0]);
+        acc[nb][NA == 4 ? 3 : 1] = MFMA(w3, d[nb].w, acc[nb][NA == 4 ? 3 : 1]);
+      }
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      v4f r = acc[nb][0] + acc[nb][1];
+      if (NA == 4) r += acc[nb][2] + acc[nb][3];
+      *(LDSQ v4f*)(DX + (nb * 16 + i) * ldx + cb * 16 + 4 * q) = r;
+    }
+  }
+}
+
+template <int NRBT, int NCGT>
+__device__ __forceinline__ void mfma_cols(const LDSQ float* Wl, int ldw, int NRB, int NCG, const LDSQ float* Dl, int ldd,
+                                          int NB, LDSQ float* DX, int ldx) {
+  if (NRBT && NB == 1)
+    mfma_cols_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 1>(Wl, ldw, Dl, ldd, DX, ldx);
+  else if (NRBT && NB == 2)
+    mfma_cols_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 2>(Wl, ldw, Dl, ldd, DX, ldx);
+  else if (NRBT && NB == 3)
+    mfma_cols_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 3>(Wl, ldw, Dl, ldd, DX, ldx);
+  else
+    mfma_cols_any(Wl, ldw, NRB, NCG, Dl, ldd, NB, DX, ldx);
   lds_barrier();
 }
 

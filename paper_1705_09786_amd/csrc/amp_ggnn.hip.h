@@ -96,30 +96,40 @@ __device__ __forceinline__ GBufs g_bufs(const GQ AmpDev* D) {
 #define GR_GH(D) (4 + (D)->n_edge_types)
 #define GR_RO(D) (5 + (D)->n_edge_types)
 
-__device__ __forceinline__ int g_active_types(const GView& v, int T) {
-  int n = 0;
-  for (int c = 0; c < T; ++c) n += v.tcount[c] > 0;
-  return n;
+// Bit c set when the graph has edges of type c (at most 8 types).
+__device__ __forceinline__ unsigned g_present_types(const GView& v, int T) {
+  unsigned m = 0;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) m |= (c < T && v.tcount[c < T ? c : 0] > 0) ? 1u << c : 0u;
+  return m;
 }
 
-// Sends one message per edge type that occurs in the graph.  ONE thread, after a release fence.
-__device__ __forceinline__ void g_post_edges(const GQ AmpDev* D, const GView& v, int s, int it, bool backward) {
-  for (int c = 0; c < D->n_edge_types; ++c)
-    if (v.tcount[c] > 0) ring_post(D->ring[GR_EDGE0 + c], MSG_MAKE(backward, s, it));
+// Sends one message per edge type that occurs in the graph: lane c of the calling wave posts to type c's ring.
+// Whole wave, after a release fence.
+__device__ __forceinline__ void g_post_edges(const GQ AmpDev* D, unsigned present, int s, int it, bool backward) {
+  const int c = threadIdx.x & 63;
+  if (c < 8 && ((present >> c) & 1u)) ring_post(D->ring[GR_EDGE0 + c], MSG_MAKE(backward, s, it));
 }
 
 // Gradient w.r.t. element i of the states that entered a step whose backward
 // pass has finished: Bcast / Flatmap backward over the edge types present
 // (ascending), the update gate, the reset gate and the candidate.
-__device__ __forceinline__ float g_state_gradient(const GBufs& B, const GView& v, int s, int i) {
+// `present` = g_present_types(): bit c set when the graph has edges of type c.  All loads are unconditional
+// (an absent type reads type 0's row and drops it) so that they are in flight together.
+__device__ __forceinline__ float g_state_gradient(const GBufs& B, unsigned present, int s, int i) {
   const long long NH = (long long)B.N * B.H;
   const GQ float* he = B.dHe + (long long)s * B.T * NH + i;
   const GQ float* hp = B.dHp + (long long)s * 3 * NH + i;
+  float e[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) e[c] = he[((present >> c) & 1u) ? c * NH : 0];
+  const float p0 = hp[0], p1 = hp[NH], p2 = hp[2 * NH];
   float a = 0.f;
-  for (int c = 0; c < B.T; ++c)
-    if (v.tcount[c] > 0) a += he[c * NH];
-  a += hp[NH] + hp[2 * NH];
-  a += hp[0];
+#pragma unroll
+  for (int c = 0; c < 8; ++c)
+    if ((present >> c) & 1u) a += e[c];
+  a += p1 + p2;
+  a += p0;
   return a;
 }
 
@@ -165,6 +175,7 @@ __device__ __forceinline__ void g_pend_append(GQ float* pend, int Rp, int stride
 
 // Counts one gradient (a grouped message of K rows already appended to the
 // pending list) and updates when min_update_frequency is reached.
+template <int NRBT, int NCGT>
 __device__ __forceinline__ void g_count_and_update(const GQ AmpDev* D, const GQ WorkerDev* W, const GQ NodeDev& nd, const Tile& t,
                                                    const GTile& g, const GQ float* pend, unsigned& count, unsigned& nrows,
                                                    unsigned& tstep, int K, float& gb) {
@@ -173,7 +184,7 @@ __device__ __forceinline__ void g_count_and_update(const GQ AmpDev* D, const GQ 
   if ((int)count >= nd.muf) {
     tstep++;
     __syncthreads();   // the appended rows of every wave are in HBM
-    tree_update_from_pend<0, 0>(g.Wl, g.bl, &nd, t, pend, nrows, count, tstep, g.rowmap, g.colmap, gb);
+    tree_update_from_pend<NRBT, NCGT>(g.Wl, g.bl, &nd, t, pend, nrows, count, tstep, g.rowmap, g.colmap, gb);
     gb = 0.f;
     count = 0;
     nrows = 0;
@@ -200,6 +211,7 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
     const int s = MSG_SLOT(code);
     const unsigned seq = D->slot_seq[s];
     const GView v = g_view(D, seq);
+    const unsigned present = g_present_types(v, B.T);
     if (!(code & MSG_DIR_B)) {
       GQ float* h0 = B.Hm + B.hm(s, 0);
       for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) {
@@ -208,14 +220,14 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
       }
       LOG(0, 0, seq, 0);
       __syncthreads();
-      if (threadIdx.x == 0) {
+      if (threadIdx.x < 64) {
         fence_release();
-        g_post_edges(D, v, s, 0, false);
+        g_post_edges(D, present, s, 0, false);
       }
       continue;
     }
     // backward: scatter-add the rows into the table's accumulator, node by node
-    for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) gt[i] = g_state_gradient(B, v, s, i);
+    for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) gt[i] = g_state_gradient(B, present, s, i);
     lds_barrier();
     for (int j = threadIdx.x; j < H; j += AMP_THREADS)
       for (int n = 0; n < v.N; ++n) lkG[v.type[n] * H + j] += gt[n * H + j];
@@ -247,6 +259,7 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
 }
 
 // ---------------------------------------------------------------- edge linear of type c
+template <int NRBT, int NCGT>
 __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
   const GQ NodeDev& nd = D->node[W->node];
@@ -274,14 +287,14 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
     const int K = v.tcount[ctype], NB = (K + 15) >> 4;
     const GQ int* te = v.tedge + v.tstart[ctype];   // edges of this type, ascending (Group orders its rows by edge index)
     const GQ float* h = B.Hm + B.hm(s, it);
-    const int nact = g_active_types(v, B.T);
+    const int nact = __popc(g_present_types(v, B.T));
     for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
       const int k = i / Hs, j = i - k * Hs;
       X[i] = j < H ? h[v.src[te[k]] * H + j] : 0.f;   // padding columns of a used row are zero
     }
     if (!(code & MSG_DIR_B)) {
       lds_barrier();
-      mfma_rows(g.Wl, t.ldw, NRB, NCG, g.bl, X, Hs, NB, Y, Hs);
+      mfma_rows<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, g.bl, X, Hs, NB, Y, Hs);
       GQ float* msg = B.Msg + (long long)s * B.Em * H;
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
         const int k = i / H, j = i - k * H;
@@ -317,7 +330,7 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
     LOG(W->node, 1, seq, it);
     g_pend_append(pend, pd.Rp, pd.stride, nrows, Y, Hs, H, X, Hs, H, K, gb);
     lds_barrier();
-    mfma_cols(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Hs);
+    mfma_cols<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Hs);
     // dh_src += W^T delta_e: per source node, its edges of this type in ascending order
     {
       GQ float* dHe = B.dHe + ((long long)s * B.T + ctype) * B.N * H;
@@ -340,7 +353,7 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
           ring_post(D->ring[GR_LOOKUP], MSG_MAKE(1, s, 0));
       }
     }
-    g_count_and_update(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
+    g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
     lds_barrier();
   }
   tile_store(nd, t, g.Wg, g.bg);
@@ -353,6 +366,7 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
 }
 
 // ---------------------------------------------------------------- GRU gate nodes (aux 0: update z, aux 1: reset r)
+template <int NRBT, int NCGT>
 __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
   const GQ NodeDev& nd = D->node[W->node];
@@ -397,7 +411,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
         X[i] = x;
       }
       lds_barrier();
-      mfma_rows(g.Wl, t.ldw, NRB, NCG, g.bl, X, Cs, NB, Y, Hs);
+      mfma_rows<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, g.bl, X, Cs, NB, Y, Hs);
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) outp[i] = sigmoidf_(Y[(i / H) * Hs + i % H]);
       LOG(W->node, 0, seq, it);
       __syncthreads();
@@ -420,7 +434,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
     LOG(W->node, 1, seq, it);
     g_pend_append(pend, pd.Rp, pd.stride, nrows, Y, Hs, H, X, Cs, C, K, gb);
     lds_barrier();
-    mfma_cols(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Cs);
+    mfma_cols<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Cs);
     GQ float* dA = B.dA + ((long long)s * 3 + 1 + which) * B.N * H;
     GQ float* dHp = B.dHp + ((long long)s * 3 + 1 + which) * B.N * H;
     for (int i = threadIdx.x; i < K * C; i += AMP_THREADS) {
@@ -431,12 +445,14 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
         dHp[k * H + c - H] = X[k * Cs + c];
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
+    if (threadIdx.x < 64) {
       fence_release();
       // both gates done: back through sum / Group to the edge types
-      if (join_arrive(B.cnt + s * 8 + 2, 2)) g_post_edges(D, v, s, it, true);
+      int go = 0;
+      if (threadIdx.x == 0) go = join_arrive(B.cnt + s * 8 + 2, 2);
+      if (__shfl(go, 0)) g_post_edges(D, g_present_types(v, B.T), s, it, true);
     }
-    g_count_and_update(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
+    g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
     lds_barrier();
   }
   tile_store(nd, t, g.Wg, g.bg);
@@ -449,6 +465,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
 }
 
 // ---------------------------------------------------------------- GRU candidate node + blend + loop control
+template <int NRBT, int NCGT>
 __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
   const GQ NodeDev& nd = D->node[W->node];
@@ -475,19 +492,23 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
     const unsigned seq = D->slot_seq[s];
     const GView v = g_view(D, seq);
+    const unsigned present = g_present_types(v, B.T);
     const int K = v.N, NB = (K + 15) >> 4;
     const GQ float* A = B.A + B.st(s, it);
     const GQ float* h = B.Hm + B.hm(s, it);
     const GQ float* Z = B.Z + B.st(s, it);
     const GQ float* Rr = B.Rr + B.st(s, it);
     GQ float* Ht = B.Ht + B.st(s, it);
+    PHASE(0);
     for (int i = threadIdx.x; i < K * Cs; i += AMP_THREADS) {
       const int k = i / Cs, c = i - k * Cs;
       X[i] = c < H ? A[k * H + c] : c < C ? Rr[k * H + c - H] * h[k * H + c - H] : 0.f;
     }
     if (!(code & MSG_DIR_B)) {
       lds_barrier();
-      mfma_rows(g.Wl, t.ldw, NRB, NCG, g.bl, X, Cs, NB, Y, Hs);
+      PHASE(1);
+      mfma_rows<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, g.bl, X, Cs, NB, Y, Hs);
+      PHASE(2);
       GQ float* hn = B.Hm + B.hm(s, it + 1);
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
         const float ht = tanhf(Y[(i / H) * Hs + i % H]), z = Z[i];
@@ -496,13 +517,14 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
       }
       LOG(W->node, 0, seq, it);
       __syncthreads();
-      if (threadIdx.x == 0) {
+      if (threadIdx.x < 64) {
         fence_release();
         if (it + 1 < B.S)
-          g_post_edges(D, v, s, it + 1, false);
-        else
+          g_post_edges(D, present, s, it + 1, false);
+        else if (threadIdx.x == 0)
           ring_post(D->ring[GR_RO(D)], MSG_MAKE(0, s, 0));
       }
+      PHASE(3);
       continue;
     }
     // backward through blend, tanh, the candidate linear and r*h
@@ -511,7 +533,7 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
       GQ float* dZ = B.dZ + B.sl(s);
       const bool from_readout = it + 1 == B.S;
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
-        const float gg = from_readout ? gH[i] : g_state_gradient(B, v, s, i);
+        const float gg = from_readout ? gH[i] : g_state_gradient(B, present, s, i);
         const float z = Z[i], ht = Ht[i];
         gt[i] = gg;
         dZ[i] = gg * (ht - h[i]) * z * (1.f - z);
@@ -520,10 +542,13 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
       for (int i = threadIdx.x; i < K * (Hs - H); i += AMP_THREADS) Y[(i / (Hs - H)) * Hs + H + i % (Hs - H)] = 0.f;
     }
     lds_barrier();
+    PHASE(4);
     LOG(W->node, 1, seq, it);
     g_pend_append(pend, pd.Rp, pd.stride, nrows, Y, Hs, H, X, Cs, C, K, gb);
     lds_barrier();
-    mfma_cols(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Cs);
+    PHASE(5);
+    mfma_cols<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Cs);
+    PHASE(6);
     {
       GQ float* dA = B.dA + (long long)s * 3 * B.N * H;
       GQ float* dHp = B.dHp + (long long)s * 3 * B.N * H;
@@ -542,8 +567,9 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
       ring_post(D->ring[GR_GZ(D)], MSG_MAKE(1, s, it));
       ring_post(D->ring[GR_GR(D)], MSG_MAKE(1, s, it));
     }
-    g_count_and_update(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
+    g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
     lds_barrier();
+    PHASE(7);
   }
   tile_store(nd, t, g.Wg, g.bg);
   if ((int)threadIdx.x < t.R) ndG[(long long)nd.rows * t.C + threadIdx.x] = gb;

@@ -277,9 +277,19 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
     }
     case ROLE_TREE_OUT: role_tree_out(D, W); break;
     case ROLE_G_LOOKUP: role_g_lookup(D, W); break;
-    case ROLE_G_EDGE: role_g_edge(D, W); break;
-    case ROLE_G_GATE: role_g_gate(D, W); break;
-    case ROLE_G_CAND: role_g_cand(D, W); break;
+    // hidden size 97..112 (7 row blocks; 7 / 13 column groups) has products with fixed trip counts
+    case ROLE_G_EDGE:
+      if (amp_round16(D->hidden) == 112) role_g_edge<7, 7>(D, W);
+      else role_g_edge<0, 0>(D, W);
+      break;
+    case ROLE_G_GATE:
+      if (amp_round16(D->hidden) == 112 && amp_round16(2 * D->hidden) == 208) role_g_gate<7, 13>(D, W);
+      else role_g_gate<0, 0>(D, W);
+      break;
+    case ROLE_G_CAND:
+      if (amp_round16(D->hidden) == 112 && amp_round16(2 * D->hidden) == 208) role_g_cand<7, 13>(D, W);
+      else role_g_cand<0, 0>(D, W);
+      break;
     case ROLE_G_READOUT: role_g_readout(D, W); break;
     default: break;
   }
