@@ -238,6 +238,18 @@ def main():
                              "kernel_instances_per_s": n * args.steps / rk, "workgroups": R * n_workers,
                              "max_active_keys_per_replica": cfg["mak"], "parameter_averaging": "end of every epoch",
                              "roofline_frac_whole_chip": rach / peak_chip, "train_loss": a.get_loss()["mean_loss"]}
+    # The published peaks above are what `roofline.peak` quotes; the rates this chip actually reaches on the two
+    # access patterns (a worker-shaped workgroup streaming 16-byte LDS reads on every CU; a grid-wide streaming sum
+    # over 2 GiB of HBM) are measured beside them.
+    tr.close()
+    buf = torch.zeros(2 << 30, dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    lds_cu, hbm = B.measure_peaks(buf.data_ptr(), buf.numel(), torch.cuda.current_stream().cuda_stream)
+    del buf
+    out["measured_peaks"] = {"lds_read_GBps_per_cu": lds_cu / 1e9, "lds_read_fraction_of_nominal": lds_cu / (
+        LDS_BYTES_PER_CLK_PER_CU * CLOCK_HZ), "hbm_read_GBps": hbm / 1e9, "hbm_read_fraction_of_nominal": hbm / 8e12}
+    if bound == "lds":
+        out["roofline"]["frac_of_measured_lds_rate"] = achieved / (lds_cu / 1e9 * n_workers)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(model, dims, fp, data, cfg)
     print(json.dumps(out))

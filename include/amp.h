@@ -223,6 +223,19 @@ int amp_get_worker_stats(amp_ctx *ctx, double *wait_fraction, uint64_t *messages
                          size_t cap, size_t *n, uint64_t *batches, double *phase_fraction);
 const char *amp_last_error(amp_ctx *ctx);
 
+/* Measures the two rates the workers' rooflines are quoted against (Section
+ * 3 / Appendix C argue from the cost of loading the weights): the LDS read
+ * rate of one worker-shaped workgroup (512 threads, 16-byte reads) per
+ * compute unit with every compute unit busy, in bytes/s per CU, and the HBM
+ * read rate of a streaming sum over dev_buf, in bytes/s.  dev_buf: device
+ * memory, 256-byte aligned, at least 64 MiB (use more than the 256 MiB last
+ * level cache for an HBM figure), initialised by the caller with finite
+ * floats, not written.  Needs no context; blocks until both launches on
+ * hip_stream have finished.  AMP_EINVAL for bad arguments, AMP_EDEVICE when
+ * a launch fails. */
+int amp_measure_peaks(void *dev_buf, size_t bytes, void *hip_stream, double *lds_bytes_per_s_per_cu,
+                      double *hbm_read_bytes_per_s);
+
 #ifdef __cplusplus
 }
 #endif

@@ -88,6 +88,8 @@ SIGNATURES = {
                                         ct.c_size_t, ct.POINTER(ct.c_size_t), ct.POINTER(ct.c_uint64),
                                         ct.POINTER(ct.c_double)]),
     "amp_last_error": (ct.c_char_p, [_ctxp]),
+    "amp_measure_peaks": (ct.c_int, [ct.c_void_p, ct.c_size_t, ct.c_void_p, ct.POINTER(ct.c_double),
+                                     ct.POINTER(ct.c_double)]),
 }
 
 _lib = None
@@ -105,6 +107,15 @@ def lib():
             fn.restype, fn.argtypes = res, args
         _lib = l
     return _lib
+
+
+def measure_peaks(dev_ptr: int, nbytes: int, stream: int = 0):
+    """(LDS bytes/s per CU, HBM read bytes/s) measured on the current device; dev_ptr = device buffer of nbytes."""
+    a, b = ct.c_double(), ct.c_double()
+    rc = lib().amp_measure_peaks(ct.c_void_p(dev_ptr), nbytes, ct.c_void_p(stream), ct.byref(a), ct.byref(b))
+    if rc != 0:
+        raise RuntimeError("amp_measure_peaks failed with code %d" % rc)
+    return a.value, b.value
 
 
 class AmpError(RuntimeError):

@@ -330,3 +330,98 @@ extern "C" hipError_t amp_average(float* p0, size_t stride_floats, int n_replica
   hipLaunchKernelGGL(amp_average_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p0, stride_floats, n_replicas, n);
   return hipGetLastError();
 }
+
+// ============================================================ peak micro-benchmarks
+// What the roofline fractions are measured against can itself be measured: the
+// LDS read rate of one workgroup per CU shaped like a worker (512 threads,
+// 16-byte reads, several independent reads in flight), and the HBM read rate
+// of a grid-wide streaming sum.
+extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_peak_lds_kernel(int iters, float* sink) {
+  LDSQ float* l = (LDSQ float*)amp_lds;
+  const int nfl = AMP_DYN_LDS_BYTES / 4;
+  for (int i = threadIdx.x; i < nfl; i += AMP_THREADS) l[i] = (float)(i & 7);
+  __syncthreads();
+  // each thread walks the whole LDS in 16-byte steps, eight reads per round
+  const int nv = nfl / 4;   // 16-byte groups
+  v4f a[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) a[k] = (v4f){0.f, 0.f, 0.f, 0.f};
+  int pos = threadIdx.x;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      a[k] += *(const LDSQ v4f*)(l + 4 * pos);
+      pos += AMP_THREADS;
+      if (pos >= nv) pos -= nv;
+    }
+  }
+  v4f r = a[0];
+#pragma unroll
+  for (int k = 1; k < 8; ++k) r += a[k];
+  if (r.x + r.y + r.z + r.w == -1.f) sink[0] = r.x;   // never true: keeps the reads alive
+}
+
+extern "C" __global__ void __launch_bounds__(256) amp_peak_hbm_kernel(const v4f* src, size_t n16, float* sink) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  v4f a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0, a2 = a0, a3 = a0;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    a0 += src[i];
+    a1 += src[i + stride];
+    a2 += src[i + 2 * stride];
+    a3 += src[i + 3 * stride];
+  }
+  for (; i < n16; i += stride) a0 += src[i];
+  const v4f r = a0 + a1 + a2 + a3;
+  if (r.x + r.y + r.z + r.w == -1.2345f) sink[0] = r.x;
+}
+
+// Launches the LDS benchmark on n_wg workgroups (one per CU: the dynamic LDS
+// size allows no second one) and returns the seconds the timed launch took
+// and the bytes it read per workgroup.
+extern "C" hipError_t amp_peak_lds_launch(int n_wg, int iters, float* sink, hipStream_t stream, double* seconds,
+                                          double* bytes_per_wg) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)amp_peak_lds_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       AMP_DYN_LDS_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipEvent_t t0, t1;
+  hipError_t e;
+  if ((e = hipEventCreate(&t0)) != hipSuccess) return e;
+  if ((e = hipEventCreate(&t1)) != hipSuccess) return e;
+  hipLaunchKernelGGL(amp_peak_lds_kernel, dim3(n_wg), dim3(AMP_THREADS), AMP_DYN_LDS_BYTES, stream, iters / 8 + 1, sink);   // warm-up
+  hipEventRecord(t0, stream);
+  hipLaunchKernelGGL(amp_peak_lds_kernel, dim3(n_wg), dim3(AMP_THREADS), AMP_DYN_LDS_BYTES, stream, iters, sink);
+  hipEventRecord(t1, stream);
+  if ((e = hipEventSynchronize(t1)) != hipSuccess) return e;
+  float ms = 0.f;
+  hipEventElapsedTime(&ms, t0, t1);
+  hipEventDestroy(t0);
+  hipEventDestroy(t1);
+  *seconds = ms * 1e-3;
+  *bytes_per_wg = (double)iters * 8.0 * AMP_THREADS * 16.0;
+  return hipGetLastError();
+}
+
+extern "C" hipError_t amp_peak_hbm_launch(const void* src, size_t bytes, float* sink, hipStream_t stream, double* seconds) {
+  hipEvent_t t0, t1;
+  hipError_t e;
+  if ((e = hipEventCreate(&t0)) != hipSuccess) return e;
+  if ((e = hipEventCreate(&t1)) != hipSuccess) return e;
+  const size_t n16 = bytes / 16;
+  const int grid = 256 * 16;
+  hipLaunchKernelGGL(amp_peak_hbm_kernel, dim3(grid), dim3(256), 0, stream, (const v4f*)src, n16, sink);   // warm-up
+  hipEventRecord(t0, stream);
+  hipLaunchKernelGGL(amp_peak_hbm_kernel, dim3(grid), dim3(256), 0, stream, (const v4f*)src, n16, sink);
+  hipEventRecord(t1, stream);
+  if ((e = hipEventSynchronize(t1)) != hipSuccess) return e;
+  float ms = 0.f;
+  hipEventElapsedTime(&ms, t0, t1);
+  hipEventDestroy(t0);
+  hipEventDestroy(t1);
+  *seconds = ms * 1e-3;
+  return hipGetLastError();
+}

@@ -17,6 +17,9 @@
 #include "amp_dev.h"
 
 extern "C" hipError_t amp_launch(const AmpDev* devs, int n_replicas, int workers_per_replica, hipStream_t stream);
+extern "C" hipError_t amp_peak_lds_launch(int n_wg, int iters, float* sink, hipStream_t stream, double* seconds,
+                                          double* bytes_per_wg);
+extern "C" hipError_t amp_peak_hbm_launch(const void* src, size_t bytes, float* sink, hipStream_t stream, double* seconds);
 extern "C" hipError_t amp_average(float* p0, size_t stride_floats, int n_replicas, size_t n, hipStream_t stream);
 
 namespace {
@@ -249,6 +252,24 @@ int amp_create(amp_ctx** out, void* dev_arena, size_t arena_bytes, void* hip_str
 void amp_destroy(amp_ctx* ctx) { delete ctx; }
 
 const char* amp_last_error(amp_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int amp_measure_peaks(void* dev_buf, size_t bytes, void* hip_stream, double* lds_bytes_per_s_per_cu,
+                      double* hbm_read_bytes_per_s) {
+  if (!dev_buf || bytes < (64u << 20) || ((uintptr_t)dev_buf & 255) || !lds_bytes_per_s_per_cu || !hbm_read_bytes_per_s)
+    return AMP_EINVAL;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  int dev_id = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev_id) != hipSuccess || hipGetDeviceProperties(&prop, dev_id) != hipSuccess) return AMP_EDEVICE;
+  double sec = 0, per_wg = 0;
+  // the first float of the buffer doubles as the kernels' (never written) sink
+  if (amp_peak_lds_launch(prop.multiProcessorCount, 20000, (float*)dev_buf, stream, &sec, &per_wg) != hipSuccess || sec <= 0)
+    return AMP_EDEVICE;
+  *lds_bytes_per_s_per_cu = per_wg / sec;
+  if (amp_peak_hbm_launch(dev_buf, bytes, (float*)dev_buf, stream, &sec) != hipSuccess || sec <= 0) return AMP_EDEVICE;
+  *hbm_read_bytes_per_s = (double)(bytes / 16 * 16) / sec;
+  return AMP_OK;
+}
 
 int amp_build_mlp(amp_ctx* c, const amp_model_dims* d) {
   if (int r = check_build(c, d)) return r;
