@@ -1,0 +1,74 @@
+"""Asynchrony sweep (Section 6, "Asynchrony", Figure 7): an 8-replica RNN on a
+synthetic list-reduction task, trained for every (max_active_keys,
+min_update_frequency) pair of a grid until it reaches 96 % validation
+accuracy; reports the epochs (data) and the device time that took, and the
+training rate.
+
+    python -m paper_1705_09786_amd.sweep [--replicas 8] [--max-epochs 40] [--out sweep.json]
+
+The paper's list-reduction dataset is not available; the stand-in is the
+"max" reduction of `synth.make_rnn` (lists of 2..10 tokens, label = largest
+token value scaled to 10 classes), which this RNN learns within a few epochs.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+from . import binding as B
+from . import runner, synth
+
+TARGET = 0.96
+MAKS = (1, 2, 4, 8, 16, 32, 64)
+MUFS = (1, 4, 16, 64, 256)
+
+
+def run_one(data, valid, dims, fp, replicas, mak, muf, lr, max_epochs):
+    ml, _ = runner.max_len_of("rnn", data + valid)
+    tr = runner.Trainer("rnn", dims, fp, mak, ml, 0, len(data), arena_bytes=2 << 30, replicas=replicas)
+    a = tr.amp
+    a.set_min_update_frequency(-1, muf)
+    a.set_optimizer(-1, B.OPT_ADAM, lr=lr)
+    tr.submit_all(data)
+    tr.submit_all(valid, which=1)
+    seconds, reached, acc = 0.0, None, 0.0
+    for ep in range(1, max_epochs + 1):
+        a.train(1)
+        seconds += a.get_loss()["seconds"]
+        acc = a.eval()["accuracy"]
+        if acc >= TARGET:
+            reached = ep
+            break
+    tr.close()
+    epochs = reached if reached is not None else max_epochs
+    return dict(max_active_keys=mak, min_update_frequency=muf, converged=reached is not None, epochs=epochs,
+                device_seconds=seconds, instances_per_s=len(data) * epochs / seconds, valid_accuracy=acc)
+
+
+def main(argv=None):
+    ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
+    ap.add_argument("--replicas", type=int, default=8)
+    ap.add_argument("--max-epochs", type=int, default=40)
+    ap.add_argument("--lr", type=float, default=0.001)
+    ap.add_argument("--instances", type=int, default=10000)
+    ap.add_argument("--out", default=None, help="also write the table to this JSON file")
+    args = ap.parse_args(argv)
+    dims = synth.DEFAULT_DIMS["rnn"]
+    data = synth.make_rnn(args.instances, synth.BASE_SEED + 20, dims, 2, 10, reduction="max")
+    valid = synth.make_rnn(1000, synth.BASE_SEED + 1020, dims, 2, 10, reduction="max")
+    fp = synth.init_params("rnn", dims, 102)
+    rows = []
+    for mak in MAKS:
+        for muf in MUFS:
+            r = run_one(data, valid, dims, fp, args.replicas, mak, muf, args.lr, args.max_epochs)
+            rows.append(r)
+            print(json.dumps(r), flush=True)
+    if args.out:
+        with open(args.out, "w") as f:
+            json.dump(dict(replicas=args.replicas, target_accuracy=TARGET, lr=args.lr, rows=rows), f, indent=1)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
