@@ -283,6 +283,17 @@ class Amp:
             logs[e.worker].append((e.node, EV_NAMES[e.kind], e.seq, e.local))
         return logs
 
+    def get_event_array(self):
+        """The same record as one numpy structured array (fields worker, node, kind, seq, local), for long runs."""
+        import numpy as np
+        n = ct.c_size_t()
+        self._chk(self.L.amp_get_event_log(self.h, None, 0, ct.byref(n)))
+        buf = (Event * max(n.value, 1))()
+        self._chk(self.L.amp_get_event_log(self.h, buf, n.value, ct.byref(n)))
+        dt = np.dtype([("worker", np.uint16), ("node", np.uint8), ("kind", np.uint8), ("seq", np.uint32),
+                       ("local", np.uint32)])
+        return np.frombuffer(buf, dtype=dt, count=n.value).copy()
+
     def get_worker_stats(self):
         """List per worker of dict(node, wait_fraction, messages)."""
         nw = self.num_workers()

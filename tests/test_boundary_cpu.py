@@ -114,3 +114,34 @@ def test_malformed_trees_and_graphs():
         bad = dict(ok)
         bad.update(patch)
         expect(B.AMP_EINVAL, g.submit, bad)
+
+
+def test_replica_and_weight_placement_setters():
+    a = new_ctx()
+    expect(B.AMP_ESTATE, a.set_replicas, 2)                            # before build
+    expect(B.AMP_ESTATE, a.set_weights_in_hbm, 1, True)
+    a.build("tree", dict(vocab=11, emb=8, hidden=6, n_class=3))
+    expect(B.AMP_EINVAL, a.set_replicas, 0)
+    expect(B.AMP_EINVAL, a.set_replicas, 65)
+    expect(B.AMP_EINVAL, a.set_weights_in_hbm, 9, True)                # no such node
+    expect(B.AMP_EUNSUPPORTED, a.set_weights_in_hbm, 0, True)          # the lookup
+    expect(B.AMP_EUNSUPPORTED, a.set_weights_in_hbm, 3, True)          # the output layer
+    expect(B.AMP_EUNSUPPORTED, a.set_weights_in_hbm, 1, True)          # hidden 6 is no multiple of 4
+    a.set_replicas(3)
+    a.finalize(4, 5, 0, 10)
+    expect(B.AMP_ESTATE, a.set_replicas, 2)                            # after finalize
+    assert a.num_workers() == 3 * (1 + 1 + 5 + 8 + 1)                  # controller, lookup, leaf / branch tiles, output
+    b = new_ctx()
+    b.build("mlp", dict(d_in=5, hidden=4, n_class=3))
+    expect(B.AMP_EUNSUPPORTED, b.set_weights_in_hbm, 1, True)          # only the tree cells
+    c = new_ctx()
+    c.build("tree", dict(vocab=11, emb=8, hidden=6, n_class=3))
+    c.set_replicas(17)
+    expect(B.AMP_EUNSUPPORTED, c.finalize, 4, 5, 0, 10)                # 17 x 16 workers exceed 256 workgroups
+
+
+def test_measure_peaks_needs_a_buffer():
+    import ctypes as ct
+    x, y = ct.c_double(), ct.c_double()
+    assert B.lib().amp_measure_peaks(None, 1 << 30, None, ct.byref(x), ct.byref(y)) == B.AMP_EINVAL
+    assert B.lib().amp_measure_peaks(ct.c_void_p(4096), 1 << 20, None, ct.byref(x), ct.byref(y)) == B.AMP_EINVAL

@@ -1,0 +1,93 @@
+"""GPU, at the benchmark's full sizes and in the launch configuration bench.py times (same workload, tiles,
+max_active_keys, update thresholds): outputs the checker can compute one by one on a sample, and properties of
+the event record that hold at any size."""
+import numpy as np
+import pytest
+
+import bench
+from oracle import direct
+from paper_1705_09786_amd import binding as B
+from paper_1705_09786_amd import runner, synth
+
+pytestmark = pytest.mark.gpu
+
+OPT_KIND = {"sgd": B.OPT_SGD, "momentum": B.OPT_MOMENTUM, "adam": B.OPT_ADAM}
+
+
+def _trainer(cfgi, lr=None, log=False):
+    cfg = bench.DEFAULTS[cfgi]
+    model, dims, data = synth.workload(cfgi)
+    fp = synth.init_params(model, dims, 100 + cfgi)
+    ml, me = runner.max_len_of(model, data)
+    tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=(12 if cfgi == 5 else 4) << 30,
+                        tiles=cfg.get("tiles"))
+    a = tr.amp
+    a.set_watchdog(20.0)
+    a.set_min_update_frequency(-1, cfg["muf"])
+    if cfg["lmuf"]:
+        a.set_min_update_frequency(0, cfg["lmuf"])
+    kw = dict(cfg["opt"][1])
+    if lr is not None:
+        kw["lr"] = lr
+    a.set_optimizer(-1, OPT_KIND[cfg["opt"][0]], **kw)
+    if log:
+        a.set_event_log(8 * (2 * ml + 2) * len(data) + 1024)
+    tr.submit_all(data)
+    return cfg, model, dims, data, fp, tr
+
+
+@pytest.mark.parametrize("cfgi,sample", [(1, 64), (2, 48), (3, 32), (4, 32), (5, 3)])
+def test_full_size_run_with_zero_step_equals_plain_forward(cfgi, sample):
+    """With a zero learning rate every update leaves the parameters where they are, so whatever the schedule each
+    instance's loss is the plain forward loss under the initial parameters (the checker's direct forward, on a
+    seeded sample), and the parameters come back bit-identical after a full epoch of forward, backward, gradient
+    accumulation and updates."""
+    cfg, model, dims, data, fp, tr = _trainer(cfgi, lr=0.0)
+    a = tr.amp
+    a.train(1)
+    losses = a.get_instance_losses()
+    assert losses.shape == (len(data),) and np.isfinite(losses).all()
+    for k, p in enumerate(tr.params()):
+        assert np.array_equal(p, fp[k]), "node %d changed under a zero step" % k
+    P = direct.unpack(model, dims, fp)
+    rng = np.random.Generator(np.random.Philox(900 + cfgi))
+    for i in rng.choice(len(data), size=sample, replace=False):
+        ref, _ = direct.evaluate(model, dims, P, [data[i]])
+        assert abs(losses[i] - ref) <= 1e-5 * max(1.0, abs(ref)), (int(i), float(losses[i]), ref)
+    tr.close()
+
+
+@pytest.mark.parametrize("cfgi", [1, 2, 3])
+def test_full_size_event_record_invariants(cfgi):
+    """Training as the benchmark does, with the event record on: at most max_active_keys instances active, every
+    instance admitted once in submit order and retired; at every node each forward event is answered by exactly
+    one backward event with the same key, and an update follows exactly min_update_frequency backward events."""
+    cfg, model, dims, data, fp, tr = _trainer(cfgi, log=True)
+    a = tr.amp
+    a.train(1)
+    ev = a.get_event_array()
+    n = len(data)
+    F, Bk, U, A, R = 0, 1, 2, 3, 4
+    ctrl = ev[ev["worker"] == 0]
+    delta = np.where(ctrl["kind"] == A, 1, -1)
+    assert set(np.unique(ctrl["kind"])) == {A, R}
+    active = np.cumsum(delta)
+    assert active.min() >= 0 and active.max() <= cfg["mak"] and active[-1] == 0
+    assert np.array_equal(ctrl["seq"][ctrl["kind"] == A], np.arange(n, dtype=np.uint32))
+    assert np.array_equal(np.sort(ctrl["seq"][ctrl["kind"] == R]), np.arange(n, dtype=np.uint32))
+    names = [sh[0] for sh in synth.param_shapes(model, dims)]
+    work = ev[ev["worker"] != 0]
+    for node, name in enumerate(names):
+        e = work[work["node"] == node]
+        muf = cfg["lmuf"] if (name == "lookup" and cfg["lmuf"]) else cfg["muf"]
+        key = e["seq"].astype(np.uint64) << np.uint64(32) | e["local"].astype(np.uint64)
+        kf, kb = np.sort(key[e["kind"] == F]), np.sort(key[e["kind"] == Bk])
+        assert len(kf) > 0 and np.array_equal(kf, kb), name
+        assert len(np.unique(kf)) == len(kf), name
+        # backward events seen before each update, in the order the node's worker recorded them
+        isb = np.cumsum(e["kind"] == Bk)
+        at_u = isb[e["kind"] == U]
+        assert len(at_u) == len(kb) // muf, (name, len(at_u), len(kb), muf)
+        assert np.array_equal(at_u, muf * np.arange(1, len(at_u) + 1)), name
+    assert np.isfinite(a.get_instance_losses()).all()
+    tr.close()

@@ -75,6 +75,20 @@ def test_rnn_edge_lengths():
     compare(g, rt, len(data))
 
 
+@pytest.mark.parametrize("dims,opt", [(dict(vocab=13, emb=50, hidden=37, n_class=7), SGD),
+                                      (dict(vocab=13, emb=20, hidden=44, n_class=7), RNN_ADAM),
+                                      (dict(vocab=5, emb=128, hidden=64, n_class=3), SGD)])
+def test_rnn_unequal_and_odd_sizes(dims, opt):
+    """Embedding and hidden size differ (the cell's two input segments have their own widths), sizes that are
+    no multiples of 4 or 16, and an embedding as wide as the padded segment next to a narrower hidden state."""
+    data = synth.make_rnn(150, 31, dims, min_len=1, max_len=12)
+    fp = synth.init_params("rnn", dims, 7)
+    g = gpu_train("rnn", dims, fp, data, 8, 3, opt)
+    check_controller_log(g["logs"], 8, len(data))
+    rt = oracle_replay("rnn", dims, fp, data, g["logs"], 3, opt)
+    compare(g, rt, len(data))
+
+
 TREE_SMALLVOCAB = dict(vocab=64, emb=300, hidden=150, n_class=5)
 TREE_ODD = dict(vocab=97, emb=50, hidden=37, n_class=5)
 
