@@ -983,6 +983,23 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
     }
     // ---------------- backward messages of the batch
     if (nB > 0) {
+      // The (delta, input) pairs join the pending gradients: entry = [delta (Rp) | input in LDS column layout (Cp)].
+      // The input part depends on nothing computed here: its first four 16-byte groups per thread are fetched now,
+      // so that they travel while the deltas are formed, and stored afterwards.
+      const int perx = pd.Cp >> 2, totalx = nB * perx;
+      v4f xv[4];
+      GQ float* xd[4];
+      bool xin[4];
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const int idx = threadIdx.x + a * AMP_THREADS;
+        const int ii = idx < totalx ? idx : totalx - 1;
+        const int k = ii / perx, lc = (ii - k * perx) << 2, m = M.bidx[k];
+        xin[a] = lc < t.Cl;
+        xd[a] = idx < totalx ? pend + (long long)(count + k) * pd.stride + pd.Rp + lc : nullptr;
+        xv[a] = *(const GQ v4f*)(xbase + (xin[a] ? ((BR && lc >= t.segp) ? M.off1[m] + lc - t.segp : M.off0[m] + lc) : M.off0[m]));
+      }
+      asm volatile("" ::: "memory");   // the fetches are issued before the loads below
       // delta rows (tile order [gate][unit], zero beyond R) into Y
       for (int i = threadIdx.x; i < nB * (ldy - R); i += AMP_THREADS) {
         const int k = i / (ldy - R), r = R + i - k * (ldy - R);
@@ -1029,31 +1046,21 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
       }
       lds_barrier();
       PHASE(3);
-      // the (delta, input) pairs join the pending gradients: entry = [delta (Rp) | input in LDS column layout (Cp)];
-      // four 16-byte groups per thread are in flight at a time
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+        if (xd[a]) *(GQ v4f*)xd[a] = xin[a] ? xv[a] : (v4f){0.f, 0.f, 0.f, 0.f};
+      // the rest of the input parts (batches of more than 4 x 512 groups), then the delta parts from LDS
+      for (int idx = threadIdx.x + 4 * AMP_THREADS; idx < totalx; idx += AMP_THREADS) {
+        const int k = idx / perx, lc = (idx - k * perx) << 2, m = M.bidx[k];
+        const bool in = lc < t.Cl;
+        const v4f xr = *(const GQ v4f*)(xbase + (in ? ((BR && lc >= t.segp) ? M.off1[m] + lc - t.segp : M.off0[m] + lc) : M.off0[m]));
+        *(GQ v4f*)(pend + (long long)(count + k) * pd.stride + pd.Rp + lc) = in ? xr : (v4f){0.f, 0.f, 0.f, 0.f};
+      }
       {
-        const int per = pd.stride >> 2, total = nB * per;
-        for (int i0 = threadIdx.x; i0 < total; i0 += 4 * AMP_THREADS) {
-          v4f v[4];
-          GQ float* dstp[4];
-#pragma unroll
-          for (int a = 0; a < 4; ++a) {
-            const int idx = i0 + a * AMP_THREADS;
-            const int ii = idx < total ? idx : total - 1;
-            const int k = ii / per, j = (ii - k * per) << 2, m = M.bidx[k];
-            dstp[a] = idx < total ? pend + (long long)(count + k) * pd.stride + j : nullptr;
-            if (j < pd.Rp) {
-              v[a] = *(const LDSQ v4f*)(Y + k * ldy + j);   // ldy >= Rp, zero beyond R
-            } else {
-              const int lc = j - pd.Rp;
-              const bool in = lc < t.Cl;
-              const v4f xv = *(const GQ v4f*)(xbase + (in ? ((BR && lc >= t.segp) ? M.off1[m] + lc - t.segp : M.off0[m] + lc) : M.off0[m]));
-              v[a] = in ? xv : (v4f){0.f, 0.f, 0.f, 0.f};
-            }
-          }
-#pragma unroll
-          for (int a = 0; a < 4; ++a)
-            if (dstp[a]) *(GQ v4f*)dstp[a] = v[a];
+        const int perd = pd.Rp >> 2, totald = nB * perd;
+        for (int idx = threadIdx.x; idx < totald; idx += AMP_THREADS) {
+          const int k = idx / perd, j = (idx - k * perd) << 2;
+          *(GQ v4f*)(pend + (long long)(count + k) * pd.stride + j) = *(const LDSQ v4f*)(Y + k * ldy + j);   // ldy >= Rp, zero beyond R
         }
       }
       if ((int)threadIdx.x < R)
