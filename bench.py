@@ -7,9 +7,10 @@ one amp_train epoch.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--mak 64]
 
-The default workload is BASELINE config 3 (binary Tree-LSTM, 8,544 random
-trees, hidden 150, 300-d embeddings, max_active_keys 64), the configuration
-the metric names first; --config 1, 2 select the MLP and RNN workloads.
+The default workload is number 3 (binary Tree-LSTM, 8,544 random trees,
+hidden 150, 300-d embeddings, max_active_keys 64), the configuration the
+metric is quoted on; --config 1, 2, 4, 5 select the MLP, RNN, GGNN and
+hidden-1024 Tree-LSTM workloads.
 """
 from __future__ import annotations
 

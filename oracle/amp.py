@@ -27,7 +27,7 @@ Two drivers:
               events in an order recorded elsewhere (one ordered list per
               worker), and refuses orders that are not legal AMP executions.
 
-Readings of points the paper leaves open (each is listed in the design doc):
+Readings of points the paper leaves open:
 the backward pass uses the node's present parameters (only the activation is
 recorded); "exceeds the threshold" means count >= min_update_frequency; the
 applied gradient is the mean of the accumulated ones; one backward message is

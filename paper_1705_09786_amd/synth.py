@@ -281,7 +281,8 @@ def make_ggnn(n: int, seed: int, dims: dict | None = None, min_nodes: int = 9,
 # the five named workloads
 # --------------------------------------------------------------------------
 def workload(cfg: int, n: int | None = None, valid: bool = False):
-    """(model, dims, instances) for BASELINE config index cfg (1-based)."""
+    """(model, dims, instances) of benchmark workload cfg (1 MLP, 2 RNN, 3 Tree-LSTM, 4 GGNN, 5 Tree-LSTM with
+    hidden = embedding = 1024)."""
     seed = BASE_SEED + cfg + (1000 if valid else 0)
     if cfg == 1:
         d = DEFAULT_DIMS["mlp"]

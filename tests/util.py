@@ -7,7 +7,7 @@ from oracle import direct
 from paper_1705_09786_amd import binding as B
 from paper_1705_09786_amd import runner, synth
 
-# Tolerance (relative), as the benchmark spec fixes it for fp32 against the
+# Tolerance (relative) for fp32 results against the
 # float64 checker: parameters per tensor in the 2-norm, losses per instance.
 RTOL = 1e-5
 
