@@ -38,8 +38,8 @@ __shared__ int s_n;
 // leading run that is ready, cut so that at most `room` backward messages
 // (those for which is_b(code) holds) are in it.  Returns the batch size, 0
 // when the run is over.  s_codes / s_n are LDS.
-template <class IsB>
-__device__ __forceinline__ int wait_batch(const GQ AmpDev* D, const GQ RingDev& r, unsigned& head, int kmax, int room, unsigned* s_codes,
+template <class R, class IsB>
+__device__ __forceinline__ int wait_batch(const GQ AmpDev* D, const R& r, unsigned& head, int kmax, int room, unsigned* s_codes,
                           int* s_n, IsB is_b) {
   if (threadIdx.x < 64) {
     const int lane = threadIdx.x;
@@ -290,7 +290,7 @@ struct Pend {
 
 __device__ __forceinline__ Pend make_pend(const GQ WorkerDev* W, const Tile& t) {
   Pend p;
-  p.base = W->pend;
+  p.base = (float*)uni_gq<float>(W->pend);
   p.Rp = t.Rp;
   p.Cp = amp_round16(t.Cl);
   p.stride = p.Rp + p.Cp;

@@ -38,18 +38,29 @@ __device__ __forceinline__ void lds_barrier() {
 }
 
 // ---------------------------------------------------------------- rings
+// A ring's descriptor held in (scalar) registers for the life of a worker: posting through it needs no fetch of
+// the descriptor from HBM in front of the atomic.
+struct Ring {
+  GQ unsigned long long* ent;
+  GQ unsigned* tail;
+  unsigned mask;
+};
+
 // Called by ONE thread, after a release fence that covers the payload.
-__device__ __forceinline__ void ring_post(const GQ RingDev& r, unsigned code) {
+template <class R>
+__device__ __forceinline__ void ring_post(const R& r, unsigned code) {
   unsigned t = __hip_atomic_fetch_add((GQ unsigned*)r.tail, 1u, __ATOMIC_RELAXED, AGENT);
   unsigned long long e = ((unsigned long long)(t + 1u) << 32) | code;
   __hip_atomic_store((GQ unsigned long long*)&r.ent[t & r.mask], e, __ATOMIC_RELAXED, AGENT);
 }
 
 // Reserves n consecutive tickets; entry i is published with ring_put.
-__device__ __forceinline__ unsigned ring_reserve(const GQ RingDev& r, unsigned n) {
+template <class R>
+__device__ __forceinline__ unsigned ring_reserve(const R& r, unsigned n) {
   return __hip_atomic_fetch_add((GQ unsigned*)r.tail, n, __ATOMIC_RELAXED, AGENT);
 }
-__device__ __forceinline__ void ring_put(const GQ RingDev& r, unsigned ticket, unsigned code) {
+template <class R>
+__device__ __forceinline__ void ring_put(const R& r, unsigned ticket, unsigned code) {
   unsigned long long e = ((unsigned long long)(ticket + 1u) << 32) | code;
   __hip_atomic_store((GQ unsigned long long*)&r.ent[ticket & r.mask], e, __ATOMIC_RELAXED, AGENT);
 }
@@ -79,11 +90,37 @@ __shared__ unsigned long long s_stat[AMP_NSTAT];
   } while (0)
 #endif
 
+// A value known to be the same in every lane, moved to a scalar register: addresses derived from it need no
+// vector registers (a worker's per-message pointers would otherwise be spilled to scratch memory and reloaded,
+// at L2 latency, in front of every phase).
+__device__ __forceinline__ unsigned uni(unsigned v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ float uni(float v) { return __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(v))); }
+__device__ __forceinline__ long long uni(long long v) {
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)((unsigned long long)v >> 32));
+  return (long long)(((unsigned long long)hi << 32) | lo);
+}
+// The descriptors in HBM are read with vector loads (the compiler cannot prove them unwritten), which leaves every
+// base pointer in a pair of vector registers; these put them back into scalar ones.
+template <class T>
+__device__ __forceinline__ GQ T* uni_gq(const void* p) {
+  return (GQ T*)(unsigned long long)uni((long long)(unsigned long long)p);
+}
+
+__device__ __forceinline__ Ring ring_regs(const GQ AmpDev* D, int idx) {
+  Ring r;
+  r.ent = uni_gq<unsigned long long>(D->ring[idx].ent);
+  r.tail = uni_gq<unsigned>(D->ring[idx].tail);
+  r.mask = uni(D->ring[idx].mask);
+  return r;
+}
+
 // Whole workgroup.  Waits for the entry with ticket `head` of ring r; returns
 // false when the run is over (done flag, abort flag, or this wait exceeded
 // the watchdog, which raises the abort flag so that every workgroup leaves).
 // s_ctl: two words of LDS.
-__device__ __forceinline__ bool wait_msg(const GQ AmpDev* D, const GQ RingDev& r, unsigned& head, unsigned* s_ctl, unsigned& code) {
+template <class R>
+__device__ __forceinline__ bool wait_msg(const GQ AmpDev* D, const R& r, unsigned& head, unsigned* s_ctl, unsigned& code) {
   if (threadIdx.x == 0) {
     const unsigned want = head + 1u;
     GQ unsigned long long* slot = (GQ unsigned long long*)&r.ent[head & r.mask];
@@ -116,23 +153,30 @@ __device__ __forceinline__ bool wait_msg(const GQ AmpDev* D, const GQ RingDev& r
     s_ctl[1] = stop;
   }
   __syncthreads();
-  code = s_ctl[0];
-  const bool ok = s_ctl[1] == 0u;
-  __syncthreads();
+  // the same for every lane: kept in scalar registers, and so is everything derived from it
+  code = uni(s_ctl[0]);
+  const bool ok = uni(s_ctl[1]) == 0u;
+  lds_barrier();
   if (ok) head++;
   return ok;
 }
 
 // ---------------------------------------------------------------- event record
+// The worker's record buffer and its capacity, copied into LDS when the kernel starts (s_log_cap = 0 when the
+// record is off or this worker is not its node's first tile): an event costs no descriptor fetch from HBM.
+__shared__ unsigned long long* s_log_ptr;
+__shared__ unsigned s_log_cap;
+
 __device__ __forceinline__ void log_event(const GQ AmpDev* D, const GQ WorkerDev* W, unsigned* s_logn, int node, int kind,
                                           unsigned seq, unsigned local) {
-  if (W->log_cap == 0) return;
+  const unsigned cap = s_log_cap;
+  if (cap == 0) return;
   unsigned n = *s_logn;
-  if (n >= W->log_cap) {
+  if (n >= cap) {
     raise_abort(D, ABORT_LOG_FULL, blockIdx.x);
     return;
   }
-  W->log[n] = ((unsigned long long)seq << 32) | ((unsigned)kind << 28) | ((unsigned)node << 20) | (local & 0xfffffu);
+  ((GQ unsigned long long*)s_log_ptr)[n] = ((unsigned long long)seq << 32) | ((unsigned)kind << 28) | ((unsigned)node << 20) | (local & 0xfffffu);
   *s_logn = n + 1;
 }
 
@@ -235,16 +279,16 @@ struct Tile {
 
 __device__ __forceinline__ Tile make_tile(const GQ NodeDev& nd, const GQ WorkerDev* W) {
   Tile t;
-  t.nu = W->nu;
-  t.u0 = W->u0;
-  t.block = nd.block;
-  t.nblocks = nd.nblocks;
-  t.R = nd.nblocks * W->nu;
-  t.C = nd.cols;
-  t.seg = nd.seg;
-  t.segp = nd.segp;
-  t.seg0 = nd.seg0;
-  t.Cl = ((nd.cols - nd.seg0) / nd.seg + 1) * nd.segp;
+  t.nu = uni(W->nu);
+  t.u0 = uni(W->u0);
+  t.block = uni(nd.block);
+  t.nblocks = uni(nd.nblocks);
+  t.R = t.nblocks * t.nu;
+  t.C = uni(nd.cols);
+  t.seg = uni(nd.seg);
+  t.segp = uni(nd.segp);
+  t.seg0 = uni(nd.seg0);
+  t.Cl = ((t.C - t.seg0) / t.seg + 1) * t.segp;
   t.ldw = amp_ldrow(t.Cl);
   t.Rp = amp_round16(t.R);
   return t;

@@ -37,23 +37,52 @@ struct GView {
   float target;
 };
 
-__device__ __forceinline__ GView g_view(const GQ AmpDev* D, unsigned seq) {
+// The instance set's arrays, read once per worker into scalar registers.
+struct GData {
+  const GQ int *tok_off, *edge_off, *tok, *src, *dst, *tcount, *inoff, *inedge, *tstart, *tedge, *tsoff, *tsk;
+  const GQ float* target;
+  const GQ unsigned* slot_seq;
+  int n_inst, T;
+};
+
+__device__ __forceinline__ GData g_data(const GQ AmpDev* D) {
+  GData d;
+  d.tok_off = uni_gq<int>(D->data.tok_off);
+  d.edge_off = uni_gq<int>(D->data.edge_off);
+  d.tok = uni_gq<int>(D->data.tok);
+  d.src = uni_gq<int>(D->data.src);
+  d.dst = uni_gq<int>(D->data.dst);
+  d.tcount = uni_gq<int>(D->data.tcount);
+  d.inoff = uni_gq<int>(D->data.inoff);
+  d.inedge = uni_gq<int>(D->data.inedge);
+  d.tstart = uni_gq<int>(D->data.tstart);
+  d.tedge = uni_gq<int>(D->data.tedge);
+  d.tsoff = uni_gq<int>(D->data.tsoff);
+  d.tsk = uni_gq<int>(D->data.tsk);
+  d.target = uni_gq<float>(D->data.target);
+  d.slot_seq = uni_gq<unsigned>(D->slot_seq);
+  d.n_inst = uni(D->data.n_inst);
+  d.T = uni(D->n_edge_types);
+  return d;
+}
+
+__device__ __forceinline__ GView g_view(const GData& d, unsigned seq) {
   GView v;
-  v.inst = seq % D->data.n_inst;
-  const int to = ((const GQ int*)D->data.tok_off)[v.inst], eo = ((const GQ int*)D->data.edge_off)[v.inst];
-  v.N = ((const GQ int*)D->data.tok_off)[v.inst + 1] - to;
-  v.E = ((const GQ int*)D->data.edge_off)[v.inst + 1] - eo;
-  v.type = (const GQ int*)D->data.tok + to;
-  v.src = (const GQ int*)D->data.src + eo;
-  v.dst = (const GQ int*)D->data.dst + eo;
-  v.tcount = (const GQ int*)D->data.tcount + v.inst * 8;
-  v.inoff = (const GQ int*)D->data.inoff + to + v.inst;
-  v.inedge = (const GQ int*)D->data.inedge + eo;
-  v.tstart = (const GQ int*)D->data.tstart + v.inst * 9;
-  v.tedge = (const GQ int*)D->data.tedge + eo;
-  v.tsoff = (const GQ int*)D->data.tsoff + (long long)D->n_edge_types * (to + v.inst);
-  v.tsk = (const GQ int*)D->data.tsk + eo;
-  v.target = ((const GQ float*)D->data.target)[v.inst];
+  v.inst = seq % d.n_inst;
+  const int to = uni(d.tok_off[v.inst]), eo = uni(d.edge_off[v.inst]);
+  v.N = uni(d.tok_off[v.inst + 1]) - to;
+  v.E = uni(d.edge_off[v.inst + 1]) - eo;
+  v.type = d.tok + to;
+  v.src = d.src + eo;
+  v.dst = d.dst + eo;
+  v.tcount = d.tcount + v.inst * 8;
+  v.inoff = d.inoff + to + v.inst;
+  v.inedge = d.inedge + eo;
+  v.tstart = d.tstart + v.inst * 9;
+  v.tedge = d.tedge + eo;
+  v.tsoff = d.tsoff + (long long)d.T * (to + v.inst);
+  v.tsk = d.tsk + eo;
+  v.target = uni(d.target[v.inst]);
   return v;
 }
 
@@ -68,24 +97,24 @@ struct GBufs {
 
 __device__ __forceinline__ GBufs g_bufs(const GQ AmpDev* D) {
   GBufs b;
-  b.Hm = (GQ float*)D->buf[0];
-  b.A = (GQ float*)D->buf[1];
-  b.Z = (GQ float*)D->buf[2];
-  b.Rr = (GQ float*)D->buf[3];
-  b.Ht = (GQ float*)D->buf[4];
-  b.Msg = (GQ float*)D->buf[5];
-  b.gH = (GQ float*)D->buf[6];
-  b.dZ = (GQ float*)D->buf[7];
-  b.dR = (GQ float*)D->buf[8];
-  b.dA = (GQ float*)D->buf[9];
-  b.dHp = (GQ float*)D->buf[10];
-  b.dHe = (GQ float*)D->buf[11];
-  b.cnt = (GQ int*)D->buf[13];
-  b.H = D->hidden;
-  b.N = D->max_len;
-  b.Em = D->max_edges;
-  b.S = D->n_steps;
-  b.T = D->n_edge_types;
+  b.Hm = uni_gq<float>(D->buf[0]);
+  b.A = uni_gq<float>(D->buf[1]);
+  b.Z = uni_gq<float>(D->buf[2]);
+  b.Rr = uni_gq<float>(D->buf[3]);
+  b.Ht = uni_gq<float>(D->buf[4]);
+  b.Msg = uni_gq<float>(D->buf[5]);
+  b.gH = uni_gq<float>(D->buf[6]);
+  b.dZ = uni_gq<float>(D->buf[7]);
+  b.dR = uni_gq<float>(D->buf[8]);
+  b.dA = uni_gq<float>(D->buf[9]);
+  b.dHp = uni_gq<float>(D->buf[10]);
+  b.dHe = uni_gq<float>(D->buf[11]);
+  b.cnt = uni_gq<int>(D->buf[13]);
+  b.H = uni(D->hidden);
+  b.N = uni(D->max_len);
+  b.Em = uni(D->max_edges);
+  b.S = uni(D->n_steps);
+  b.T = uni(D->n_edge_types);
   return b;
 }
 
@@ -96,19 +125,40 @@ __device__ __forceinline__ GBufs g_bufs(const GQ AmpDev* D) {
 #define GR_GH(D) (4 + (D)->n_edge_types)
 #define GR_RO(D) (5 + (D)->n_edge_types)
 
+// The rings a graph worker posts to, read once.  `edge` is per lane: lane c (mod 8) holds the ring of edge type c.
+struct GRings {
+  Ring ctl, lookup, gz, gr, gh, ro, edge;
+};
+
+__device__ __forceinline__ GRings g_rings(const GQ AmpDev* D) {
+  GRings r;
+  const int T = uni(D->n_edge_types);
+  r.ctl = ring_regs(D, 0);
+  r.lookup = ring_regs(D, GR_LOOKUP);
+  r.gz = ring_regs(D, 2 + T);
+  r.gr = ring_regs(D, 3 + T);
+  r.gh = ring_regs(D, 4 + T);
+  r.ro = ring_regs(D, 5 + T);
+  const int c = (threadIdx.x & 7) < T ? (threadIdx.x & 7) : 0;
+  r.edge.ent = (GQ unsigned long long*)D->ring[GR_EDGE0 + c].ent;
+  r.edge.tail = (GQ unsigned*)D->ring[GR_EDGE0 + c].tail;
+  r.edge.mask = D->ring[GR_EDGE0 + c].mask;
+  return r;
+}
+
 // Bit c set when the graph has edges of type c (at most 8 types).
 __device__ __forceinline__ unsigned g_present_types(const GView& v, int T) {
   unsigned m = 0;
 #pragma unroll
   for (int c = 0; c < 8; ++c) m |= (c < T && v.tcount[c < T ? c : 0] > 0) ? 1u << c : 0u;
-  return m;
+  return uni(m);
 }
 
 // Sends one message per edge type that occurs in the graph: lane c of the calling wave posts to type c's ring.
 // Whole wave, after a release fence.
-__device__ __forceinline__ void g_post_edges(const GQ AmpDev* D, unsigned present, int s, int it, bool backward) {
+__device__ __forceinline__ void g_post_edges(const GRings& R, unsigned present, int s, int it, bool backward) {
   const int c = threadIdx.x & 63;
-  if (c < 8 && ((present >> c) & 1u)) ring_post(D->ring[GR_EDGE0 + c], MSG_MAKE(backward, s, it));
+  if (c < 8 && ((present >> c) & 1u)) ring_post(R.edge, MSG_MAKE(backward, s, it));
 }
 
 // Gradient w.r.t. element i of the states that entered a step whose backward
@@ -181,7 +231,7 @@ __device__ __forceinline__ void g_count_and_update(const GQ AmpDev* D, const GQ 
                                                    unsigned& tstep, int K, float& gb) {
   count++;
   nrows += K;
-  if ((int)count >= nd.muf) {
+  if ((int)count >= uni(nd.muf)) {
     tstep++;
     __syncthreads();   // the appended rows of every wave are in HBM
     tree_update_from_pend<NRBT, NCGT>(g.Wl, g.bl, &nd, t, pend, nrows, count, tstep, g.rowmap, g.colmap, gb);
@@ -197,6 +247,8 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
   float* lds = amp_lds;
   const GQ NodeDev& lk = D->node[0];
   const GBufs B = g_bufs(D);
+  const GData gd = g_data(D);
+  const GRings rg = g_rings(D);
   const int H = B.H, V = D->n_node_types;
   LDSQ float* El = (LDSQ float*)lds;
   LDSQ float* gt = El + ((V * H + 3) & ~3);   // [N][H] gradient w.r.t. the lookup's output
@@ -204,13 +256,13 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
   GQ float* lkG = (GQ float*)lk.G;
   for (int i = threadIdx.x; i < V * H; i += AMP_THREADS) El[i] = lkP[i];
   __syncthreads();
-  const GQ RingDev& mine = D->ring[W->ring];
+  const Ring mine = ring_regs(D, uni(W->ring));
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code);
-    const unsigned seq = D->slot_seq[s];
-    const GView v = g_view(D, seq);
+    const unsigned seq = uni(gd.slot_seq[s]);
+    const GView v = g_view(gd, seq);
     const unsigned present = g_present_types(v, B.T);
     if (!(code & MSG_DIR_B)) {
       GQ float* h0 = B.Hm + B.hm(s, 0);
@@ -222,7 +274,7 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
       __syncthreads();
       if (threadIdx.x < 64) {
         fence_release();
-        g_post_edges(D, present, s, 0, false);
+        g_post_edges(rg, present, s, 0, false);
       }
       continue;
     }
@@ -235,7 +287,7 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
     __syncthreads();
     if (threadIdx.x == 0) {
       fence_release();
-      ring_post(D->ring[0], MSG_MAKE(1, s, 0));
+      ring_post(rg.ctl, MSG_MAKE(1, s, 0));
     }
     count++;
     if ((int)count >= lk.muf) {
@@ -265,6 +317,8 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
   const GQ NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
+  const GData gd = g_data(D);
+  const GRings rg = g_rings(D);
   const Pend pd = make_pend(W, t);
   GQ float* pend = (GQ float*)pd.base;
   const int H = B.H, ctype = W->aux, Ep = amp_round16(B.Em), Hs = amp_ldrow(H);
@@ -277,15 +331,15 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
   GQ float* ndG = (GQ float*)nd.G;
   float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
   __syncthreads();
-  const GQ RingDev& mine = D->ring[W->ring];
+  const Ring mine = ring_regs(D, uni(W->ring));
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
-    const unsigned seq = D->slot_seq[s];
-    const GView v = g_view(D, seq);
-    const int K = v.tcount[ctype], NB = (K + 15) >> 4;
-    const GQ int* te = v.tedge + v.tstart[ctype];   // edges of this type, ascending (Group orders its rows by edge index)
+    const unsigned seq = uni(gd.slot_seq[s]);
+    const GView v = g_view(gd, seq);
+    const int K = uni(v.tcount[ctype]), NB = (K + 15) >> 4;
+    const GQ int* te = v.tedge + uni(v.tstart[ctype]);   // edges of this type, ascending (Group orders its rows by edge index)
     const GQ float* h = B.Hm + B.hm(s, it);
     const int nact = __popc(g_present_types(v, B.T));
     for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
@@ -306,8 +360,8 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
         fence_release();
         // the last type to arrive completes the step's messages; Ungroup, regrouping by target node and the sum are the GRU nodes' part
         if (join_arrive(B.cnt + s * 8 + 0, nact)) {
-          ring_post(D->ring[GR_GZ(D)], MSG_MAKE(0, s, it));
-          ring_post(D->ring[GR_GR(D)], MSG_MAKE(0, s, it));
+          ring_post(rg.gz, MSG_MAKE(0, s, it));
+          ring_post(rg.gr, MSG_MAKE(0, s, it));
         }
       }
       continue;
@@ -335,7 +389,7 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
     {
       GQ float* dHe = B.dHe + ((long long)s * B.T + ctype) * B.N * H;
       const GQ int* so = v.tsoff + ctype * (v.N + 1);
-      const GQ int* sk = v.tsk + v.tstart[ctype];
+      const GQ int* sk = v.tsk + uni(v.tstart[ctype]);
       for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) {
         const int n = i / H, j = i - n * H;
         float a = 0.f;
@@ -348,9 +402,9 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
       fence_release();
       if (join_arrive(B.cnt + s * 8 + 3, nact)) {
         if (it > 0)
-          ring_post(D->ring[GR_GH(D)], MSG_MAKE(1, s, it - 1));
+          ring_post(rg.gh, MSG_MAKE(1, s, it - 1));
         else
-          ring_post(D->ring[GR_LOOKUP], MSG_MAKE(1, s, 0));
+          ring_post(rg.lookup, MSG_MAKE(1, s, 0));
       }
     }
     g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
@@ -372,6 +426,8 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
   const GQ NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
+  const GData gd = g_data(D);
+  const GRings rg = g_rings(D);
   const Pend pd = make_pend(W, t);
   GQ float* pend = (GQ float*)pd.base;
   const int H = B.H, C = 2 * H, Np = amp_round16(B.N), which = W->aux, Hs = amp_ldrow(H), Cs = amp_ldrow(C);
@@ -385,13 +441,13 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
   GQ float* ndG = (GQ float*)nd.G;
   float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
   __syncthreads();
-  const GQ RingDev& mine = D->ring[W->ring];
+  const Ring mine = ring_regs(D, uni(W->ring));
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
-    const unsigned seq = D->slot_seq[s];
-    const GView v = g_view(D, seq);
+    const unsigned seq = uni(gd.slot_seq[s]);
+    const GView v = g_view(gd, seq);
     const int K = v.N, NB = (K + 15) >> 4;
     GQ float* A = B.A + B.st(s, it);
     const GQ float* h = B.Hm + B.hm(s, it);
@@ -417,7 +473,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       __syncthreads();
       if (threadIdx.x == 0) {
         fence_release();
-        if (join_arrive(B.cnt + s * 8 + 1, 2)) ring_post(D->ring[GR_GH(D)], MSG_MAKE(0, s, it));
+        if (join_arrive(B.cnt + s * 8 + 1, 2)) ring_post(rg.gh, MSG_MAKE(0, s, it));
       }
       continue;
     }
@@ -450,7 +506,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       // both gates done: back through sum / Group to the edge types
       int go = 0;
       if (threadIdx.x == 0) go = join_arrive(B.cnt + s * 8 + 2, 2);
-      if (__shfl(go, 0)) g_post_edges(D, g_present_types(v, B.T), s, it, true);
+      if (__shfl(go, 0)) g_post_edges(rg, g_present_types(v, B.T), s, it, true);
     }
     g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
     lds_barrier();
@@ -471,6 +527,8 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
   const GQ NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
+  const GData gd = g_data(D);
+  const GRings rg = g_rings(D);
   const Pend pd = make_pend(W, t);
   GQ float* pend = (GQ float*)pd.base;
   const int H = B.H, C = 2 * H, Np = amp_round16(B.N), Hs = amp_ldrow(H), Cs = amp_ldrow(C);
@@ -485,13 +543,13 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
   GQ float* ndG = (GQ float*)nd.G;
   float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
   __syncthreads();
-  const GQ RingDev& mine = D->ring[W->ring];
+  const Ring mine = ring_regs(D, uni(W->ring));
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
-    const unsigned seq = D->slot_seq[s];
-    const GView v = g_view(D, seq);
+    const unsigned seq = uni(gd.slot_seq[s]);
+    const GView v = g_view(gd, seq);
     const unsigned present = g_present_types(v, B.T);
     const int K = v.N, NB = (K + 15) >> 4;
     const GQ float* A = B.A + B.st(s, it);
@@ -520,9 +578,9 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
       if (threadIdx.x < 64) {
         fence_release();
         if (it + 1 < B.S)
-          g_post_edges(D, present, s, it + 1, false);
+          g_post_edges(rg, present, s, it + 1, false);
         else if (threadIdx.x == 0)
-          ring_post(D->ring[GR_RO(D)], MSG_MAKE(0, s, 0));
+          ring_post(rg.ro, MSG_MAKE(0, s, 0));
       }
       PHASE(3);
       continue;
@@ -564,8 +622,8 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
     __syncthreads();
     if (threadIdx.x == 0) {
       fence_release();
-      ring_post(D->ring[GR_GZ(D)], MSG_MAKE(1, s, it));
-      ring_post(D->ring[GR_GR(D)], MSG_MAKE(1, s, it));
+      ring_post(rg.gz, MSG_MAKE(1, s, it));
+      ring_post(rg.gr, MSG_MAKE(1, s, it));
     }
     g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
     lds_barrier();
@@ -586,6 +644,8 @@ __device__ __noinline__ void role_g_readout(const GQ AmpDev* D, const GQ WorkerD
   const GQ NodeDev& nd = D->node[W->node];
   const Tile t = make_tile(nd, W);
   const GBufs B = g_bufs(D);
+  const GData gd = g_data(D);
+  const GRings rg = g_rings(D);
   const int H = B.H;
   Lds L{lds};
   float* Wl = L.take(t.Rp * t.ldw);
@@ -594,13 +654,13 @@ __device__ __noinline__ void role_g_readout(const GQ AmpDev* D, const GQ WorkerD
   float* red = L.take(AMP_THREADS);
   tile_load(nd, t, Wl, bl);
   GQ float* ndG = (GQ float*)nd.G;
-  const GQ RingDev& mine = D->ring[W->ring];
+  const Ring mine = ring_regs(D, uni(W->ring));
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code);
-    const unsigned seq = D->slot_seq[s];
-    const GView v = g_view(D, seq);
+    const unsigned seq = uni(gd.slot_seq[s]);
+    const GView v = g_view(gd, seq);
     const GQ float* h = B.Hm + B.hm(s, B.S);
     for (int j = threadIdx.x; j < H; j += AMP_THREADS) {
       float a = 0.f;
@@ -627,7 +687,7 @@ __device__ __noinline__ void role_g_readout(const GQ AmpDev* D, const GQ WorkerD
       __syncthreads();
       if (threadIdx.x == 0) {
         fence_release();
-        ring_post(D->ring[0], MSG_MAKE(1, s, 0));
+        ring_post(rg.ctl, MSG_MAKE(1, s, 0));
       }
       continue;
     }
@@ -639,7 +699,7 @@ __device__ __noinline__ void role_g_readout(const GQ AmpDev* D, const GQ WorkerD
     __syncthreads();
     if (threadIdx.x == 0) {
       fence_release();
-      ring_post(D->ring[GR_GH(D)], MSG_MAKE(1, s, B.S - 1));
+      ring_post(rg.gh, MSG_MAKE(1, s, B.S - 1));
     }
     count_and_update(D, W, nd, t, Wl, bl, count, tstep);
   }

@@ -33,7 +33,7 @@ __shared__ int s_pred;
 
 #define LOG(node, kind, seq, local)                                         \
   do {                                                                      \
-    if (threadIdx.x == 0 && W->tile == 0) log_event(D, W, &s_logn, node, kind, seq, local); \
+    if (threadIdx.x == 0) log_event(D, W, &s_logn, node, kind, seq, local); \
   } while (0)
 
 // ============================================================ controller
@@ -242,6 +242,8 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
   long long t_begin = 0;
   if (threadIdx.x == 0) {
     s_logn = 0;
+    s_log_cap = W->tile == 0 ? W->log_cap : 0u;
+    s_log_ptr = W->log;
     for (int i = 0; i < AMP_NSTAT; ++i) s_stat[i] = 0;
     t_begin = wall_clock64();
   }
@@ -393,14 +395,14 @@ extern "C" hipError_t amp_peak_lds_launch(int n_wg, int iters, float* sink, hipS
   if ((e = hipEventCreate(&t0)) != hipSuccess) return e;
   if ((e = hipEventCreate(&t1)) != hipSuccess) return e;
   hipLaunchKernelGGL(amp_peak_lds_kernel, dim3(n_wg), dim3(AMP_THREADS), AMP_DYN_LDS_BYTES, stream, iters / 8 + 1, sink);   // warm-up
-  hipEventRecord(t0, stream);
+  (void)hipEventRecord(t0, stream);
   hipLaunchKernelGGL(amp_peak_lds_kernel, dim3(n_wg), dim3(AMP_THREADS), AMP_DYN_LDS_BYTES, stream, iters, sink);
-  hipEventRecord(t1, stream);
+  (void)hipEventRecord(t1, stream);
   if ((e = hipEventSynchronize(t1)) != hipSuccess) return e;
   float ms = 0.f;
-  hipEventElapsedTime(&ms, t0, t1);
-  hipEventDestroy(t0);
-  hipEventDestroy(t1);
+  (void)hipEventElapsedTime(&ms, t0, t1);
+  (void)hipEventDestroy(t0);
+  (void)hipEventDestroy(t1);
   *seconds = ms * 1e-3;
   *bytes_per_wg = (double)iters * 8.0 * AMP_THREADS * 16.0;
   return hipGetLastError();
@@ -414,14 +416,14 @@ extern "C" hipError_t amp_peak_hbm_launch(const void* src, size_t bytes, float* 
   const size_t n16 = bytes / 16;
   const int grid = 256 * 16;
   hipLaunchKernelGGL(amp_peak_hbm_kernel, dim3(grid), dim3(256), 0, stream, (const v4f*)src, n16, sink);   // warm-up
-  hipEventRecord(t0, stream);
+  (void)hipEventRecord(t0, stream);
   hipLaunchKernelGGL(amp_peak_hbm_kernel, dim3(grid), dim3(256), 0, stream, (const v4f*)src, n16, sink);
-  hipEventRecord(t1, stream);
+  (void)hipEventRecord(t1, stream);
   if ((e = hipEventSynchronize(t1)) != hipSuccess) return e;
   float ms = 0.f;
-  hipEventElapsedTime(&ms, t0, t1);
-  hipEventDestroy(t0);
-  hipEventDestroy(t1);
+  (void)hipEventElapsedTime(&ms, t0, t1);
+  (void)hipEventDestroy(t0);
+  (void)hipEventDestroy(t1);
   *seconds = ms * 1e-3;
   return hipGetLastError();
 }

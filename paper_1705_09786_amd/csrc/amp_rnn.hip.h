@@ -25,12 +25,12 @@ struct RnnBufs {
 
 __device__ __forceinline__ RnnBufs rnn_bufs(const GQ AmpDev* D) {
   RnnBufs b;
-  b.hs = (GQ float*)D->buf[0];
-  b.es = (GQ float*)D->buf[1];
-  b.dh = (GQ float*)D->buf[2];
-  b.de = (GQ float*)D->buf[3];
-  b.SP = D->node[1].segp;
-  b.TM = D->max_len;
+  b.hs = uni_gq<float>(D->buf[0]);
+  b.es = uni_gq<float>(D->buf[1]);
+  b.dh = uni_gq<float>(D->buf[2]);
+  b.de = uni_gq<float>(D->buf[3]);
+  b.SP = uni(D->node[1].segp);
+  b.TM = uni(D->max_len);
   return b;
 }
 
@@ -60,16 +60,17 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
   for (int i = threadIdx.x; i < yfloats; i += AMP_THREADS) Y[i] = 0.f;
   for (int i = threadIdx.x; i < t.Rp; i += AMP_THREADS) rowmap[i] = i < R ? t.grow(i) : -1;
   for (int i = threadIdx.x; i < CMW; i += AMP_THREADS) colmap[i] = t.ncol(i);
-  GQ float* ndG = (GQ float*)nd.G;
-  GQ float* lkP = (GQ float*)lk.P;
-  GQ float* lkG = (GQ float*)lk.G;
+  GQ float* ndG = uni_gq<float>(nd.G);
+  GQ float* lkP = uni_gq<float>(lk.P);
+  GQ float* lkG = uni_gq<float>(lk.G);
   // bias gradient of row threadIdx.x accumulated since the last update (rests in HBM between launches)
   float accb = ((int)threadIdx.x < R && nd.has_bias) ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
   BatchMsg& M = s_M;
   __syncthreads();
-  const GQ RingDev& mine = D->ring[W->ring];
-  const GQ RingDev& out = D->ring[W->ring + 1];
-  const GQ int* tokens = (const GQ int*)D->data.tok;
+  const Ring mine = ring_regs(D, uni(W->ring)), out = ring_regs(D, uni(W->ring) + 1), ctl = ring_regs(D, 0);
+  const GQ int* tokens = uni_gq<int>(D->data.tok);
+  const GQ int* smeta = uni_gq<int>(D->smeta);
+  const int nd_muf = uni(nd.muf), lk_muf = uni(lk.muf);
   // both input segments are addressed from hs, both gradient segments from dh
   const GQ float* xbase = B.hs;
   GQ float* obase = B.dh;
@@ -81,7 +82,7 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
   unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1], lcount = W->wstate[2], lstep = W->wstate[3];
   for (;;) {
-    const int room_c = nd.muf - (int)count, room_l = lk.muf - (int)lcount;
+    const int room_c = nd_muf - (int)count, room_l = lk_muf - (int)lcount;
     const int n = wait_batch(D, mine, head, KB, room_c < room_l ? room_c : room_l, s_codes, &s_n, code_is_b);
     if (n == 0) break;
     if (threadIdx.x < 64) {
@@ -91,7 +92,7 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
       if (in) {
         const unsigned code = s_codes[k];
         const int s = MSG_SLOT(code), tt = MSG_LOCAL(code);
-        const v4i sm = *(const GQ v4i*)(D->smeta + 4 * s);   // admission number, length, -, token offset
+        const v4i sm = *(const GQ v4i*)(smeta + 4 * s);   // admission number, length, -, token offset
         isb = code_is_b(code);
         M.s[k] = s;
         M.n[k] = tt;
@@ -117,16 +118,17 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
         M.nB = __popcll(mb);
       }
       // every message is an event of both hosted nodes: lookup then cell going forward, cell then lookup going back
-      if (W->log_cap) {
+      if (s_log_cap) {
         const unsigned base = s_logn;
-        if (base + 2u * (unsigned)n > W->log_cap) {
+        GQ unsigned long long* logp = (GQ unsigned long long*)s_log_ptr;
+        if (base + 2u * (unsigned)n > s_log_cap) {
           if (k == 0) raise_abort(D, ABORT_LOG_FULL, blockIdx.x);
         } else {
           if (in) {
             const unsigned long long tail = ((unsigned long long)M.seq[k] << 32) | ((unsigned)M.n[k] & 0xfffffu);
             const unsigned long long dirb = (unsigned long long)(isb ? 1 : 0) << 28;
-            W->log[base + 2 * k] = tail | dirb | ((isb ? 1ull : 0ull) << 20);
-            W->log[base + 2 * k + 1] = tail | dirb | ((isb ? 0ull : 1ull) << 20);
+            logp[base + 2 * k] = tail | dirb | ((isb ? 1ull : 0ull) << 20);
+            logp[base + 2 * k + 1] = tail | dirb | ((isb ? 0ull : 1ull) << 20);
           }
           if (k == 0) s_logn = base + 2u * (unsigned)n;
         }
@@ -231,14 +233,14 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
           if (tt > 0)
             ring_post(mine, MSG_MAKE(1, s, tt - 1));
           else
-            ring_post(D->ring[0], MSG_MAKE(1, s, 0));
+            ring_post(ctl, MSG_MAKE(1, s, 0));
         }
       }
     }
     PHASE(6);
     count += nB;
     lcount += nB;
-    if ((int)count >= nd.muf) {
+    if ((int)count >= nd_muf) {
       // the cell's own update (Section 3)
       tstep++;
       tree_update_from_pend<NRBT, NCGT>(Wl, bl, &nd, t, pend, count, count, tstep, rowmap, colmap, accb);
@@ -246,7 +248,7 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
       count = 0;
       LOG(1, 2, 0, 0);
     }
-    if ((int)lcount >= lk.muf) {
+    if ((int)lcount >= lk_muf) {
       // the lookup's update: plain SGD over the whole (small) table
       lstep++;
       const float sc = lk.lr * (lk.mean ? 1.f / (float)lcount : 1.f);

@@ -41,22 +41,22 @@ struct TreeBufs {
 
 __device__ __forceinline__ TreeBufs tree_bufs(const GQ AmpDev* D) {
   TreeBufs b;
-  b.xin = (GQ float*)D->buf[0];
-  b.hc = (GQ float*)D->buf[1];
-  b.gate = (GQ float*)D->buf[2];
-  b.gout = (GQ float*)D->buf[3];
-  b.gpar = (GQ float*)D->buf[4];
-  b.gc = (GQ float*)D->buf[5];
-  b.gx = (GQ float*)D->buf[6];
-  b.cnt = (GQ int*)D->buf[7];
-  b.H = D->hidden;
-  b.Hp = amp_round4(D->hidden);
-  b.E = D->emb;
-  b.Ep = amp_round4(D->emb);
-  b.Lmax = D->max_len;
-  b.NNmax = 2 * D->max_len - 1;
-  b.TL = D->tiles_leaf;
-  b.TB = D->tiles_branch;
+  b.xin = uni_gq<float>(D->buf[0]);
+  b.hc = uni_gq<float>(D->buf[1]);
+  b.gate = uni_gq<float>(D->buf[2]);
+  b.gout = uni_gq<float>(D->buf[3]);
+  b.gpar = uni_gq<float>(D->buf[4]);
+  b.gc = uni_gq<float>(D->buf[5]);
+  b.gx = uni_gq<float>(D->buf[6]);
+  b.cnt = uni_gq<int>(D->buf[7]);
+  b.H = uni(D->hidden);
+  b.Hp = amp_round4(b.H);
+  b.E = uni(D->emb);
+  b.Ep = amp_round4(b.E);
+  b.Lmax = uni(D->max_len);
+  b.NNmax = 2 * b.Lmax - 1;
+  b.TL = uni(D->tiles_leaf);
+  b.TB = uni(D->tiles_branch);
   return b;
 }
 
@@ -68,17 +68,42 @@ __device__ __forceinline__ TreeBufs tree_bufs(const GQ AmpDev* D) {
 
 __device__ __forceinline__ bool code_is_b(unsigned c) { return (c & MSG_DIR_B) != 0; }
 
+// What a worker keeps of its descriptor and of the rings it posts to, read once (into scalar registers).
+struct WorkerRegs {
+  int node, tile, ntiles, kb, train;
+  unsigned log_cap;
+  GQ unsigned long long* log;
+  Ring ctl, lookup, leaf, branch, out;   // the tree model's rings
+};
+
+__device__ __forceinline__ WorkerRegs worker_regs(const GQ AmpDev* D, const GQ WorkerDev* W) {
+  WorkerRegs w;
+  w.node = uni(W->node);
+  w.tile = uni(W->tile);
+  w.ntiles = uni(W->ntiles);
+  w.kb = uni(W->kb);
+  w.train = uni(D->train);
+  w.log_cap = uni(W->log_cap);
+  w.log = uni_gq<unsigned long long>(W->log);
+  w.ctl = ring_regs(D, 0);
+  w.lookup = ring_regs(D, 1);
+  w.leaf = ring_regs(D, 2);
+  w.branch = ring_regs(D, 3);
+  w.out = ring_regs(D, 4);
+  return w;
+}
+
 
 // What the controller wrote for slot s at admission: admission number, leaves, node offset, token offset.
-__device__ __forceinline__ v4i tree_slot(const GQ AmpDev* D, int s) { return *(const GQ v4i*)(D->smeta + 4 * s); }
+__device__ __forceinline__ v4i tree_slot(const GQ int* smeta, int s) { return *(const GQ v4i*)(smeta + 4 * s); }
 // left, right, parent * 2 + side (-1 for the root), label of node n of the instance whose nodes start at noff
-__device__ __forceinline__ v4i tree_node(const GQ AmpDev* D, int noff, int n) {
-  return *(const GQ v4i*)(D->data.tnode + 4 * (long long)(noff + n));
+__device__ __forceinline__ v4i tree_node(const GQ int* tnode, int noff, int n) {
+  return *(const GQ v4i*)(tnode + 4 * (long long)(noff + n));
 }
 
 // Wave 0, all 64 lanes, after lanes k < n have written M.aux[k]: positions of
 // the batch's forward and backward messages, and the event record (tile 0 only).
-__device__ __forceinline__ void batch_split_and_log(const GQ AmpDev* D, const GQ WorkerDev* W, BatchMsg& M, int n, int node,
+__device__ __forceinline__ void batch_split_and_log(const GQ AmpDev* D, const WorkerRegs& W, BatchMsg& M, int n, int node,
                                                     bool both_kinds) {
   const int k = threadIdx.x;   // < 64
   const bool in = k < n, isb = in && M.aux[k] != 0;
@@ -90,19 +115,19 @@ __device__ __forceinline__ void batch_split_and_log(const GQ AmpDev* D, const GQ
     M.nF = __popcll(mf);
     M.nB = __popcll(mb);
   }
-  if (W->log_cap && W->tile == 0) {
+  if (W.log_cap && W.tile == 0) {
     // both_kinds: every message is a forward event followed by a backward event (output layer in training)
     const unsigned per = both_kinds ? 2u : 1u, base = s_logn;
-    if (base + per * (unsigned)n > W->log_cap) {
+    if (base + per * (unsigned)n > W.log_cap) {
       if (k == 0) raise_abort(D, ABORT_LOG_FULL, blockIdx.x);
     } else {
       if (in) {
         const unsigned long long tail = ((unsigned long long)M.seq[k] << 32) | ((unsigned)node << 20) | ((unsigned)M.n[k] & 0xfffffu);
         if (both_kinds) {
-          W->log[base + 2 * k] = tail;
-          W->log[base + 2 * k + 1] = tail | (1ull << 28);
+          W.log[base + 2 * k] = tail;
+          W.log[base + 2 * k + 1] = tail | (1ull << 28);
         } else {
-          W->log[base + k] = tail | ((unsigned long long)(isb ? 1 : 0) << 28);
+          W.log[base + k] = tail | ((unsigned long long)(isb ? 1 : 0) << 28);
         }
       }
       if (k == 0) s_logn = base + per * (unsigned)n;
@@ -113,21 +138,25 @@ __device__ __forceinline__ void batch_split_and_log(const GQ AmpDev* D, const GQ
 // A tile has finished its units of node n: when all tiles have, the node's
 // [h; c] goes to the output layer and, through Isu / Concat, to its parent,
 // which fires once both children are there.  One lane, after a release fence.
-__device__ __forceinline__ void tree_node_part_done(const GQ AmpDev* D, const TreeBufs& B, int s, int n, int parent_code, int ntiles) {
+__device__ __forceinline__ void tree_node_part_done(const WorkerRegs& W, const TreeBufs& B, int s, int n, int parent_code) {
   GQ int* c = B.cnt + B.node(s, n) * 4;
-  if (!join_arrive(c + 0, ntiles)) return;
-  ring_post(D->ring[TR_OUT], MSG_MAKE(0, s, n));
+  if (!join_arrive(c + 0, W.ntiles)) return;
+  ring_post(W.out, MSG_MAKE(0, s, n));
   if (parent_code < 0) return;
   const int p = parent_code >> 1;
-  if (join_arrive(B.cnt + B.node(s, p) * 4 + 1, 2)) ring_post(D->ring[TR_BRANCH], MSG_MAKE(0, s, p));
+  if (join_arrive(B.cnt + B.node(s, p) * 4 + 1, 2)) ring_post(W.branch, MSG_MAKE(0, s, p));
 }
 
 // One gradient part for node n has been written: Bcast's backward waits for
 // the output layer's part and (unless n is the root) every parent tile's.
-__device__ __forceinline__ void tree_grad_part_done(const GQ AmpDev* D, const TreeBufs& B, int s, int n, bool is_root, bool is_leaf) {
+__device__ __forceinline__ void tree_grad_part_done(const WorkerRegs& W, const TreeBufs& B, int s, int n, bool is_root, bool is_leaf) {
   const int expect = is_root ? 1 : 1 + B.TB;
-  if (join_arrive(B.cnt + B.node(s, n) * 4 + 2, expect))
-    ring_post(D->ring[is_leaf ? TR_LEAF : TR_BRANCH], MSG_MAKE(1, s, n));
+  if (join_arrive(B.cnt + B.node(s, n) * 4 + 2, expect)) {
+    if (is_leaf)
+      ring_post(W.leaf, MSG_MAKE(1, s, n));
+    else
+      ring_post(W.branch, MSG_MAKE(1, s, n));
+  }
 }
 
 // ------------------------------------------------------------ lookup
@@ -135,12 +164,14 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
   float* lds = amp_lds;
   const GQ NodeDev& lk = D->node[0];
   const TreeBufs B = tree_bufs(D);
-  const int E = B.E, Ep = B.Ep, KB = W->kb, E4 = E >> 2;
+  const WorkerRegs wr = worker_regs(D, W);
+  const int E = B.E, Ep = B.Ep, KB = wr.kb, E4 = E >> 2, lk_muf = uni(lk.muf);
+  const GQ int* smeta = uni_gq<int>(D->smeta);
   int* left_cnt = (int*)lds;                  // [mak] leaves not yet answered
   int* pend_tok = left_cnt + ((D->mak + 3) & ~3);
   for (int i = threadIdx.x; i < D->mak; i += AMP_THREADS) left_cnt[i] = 0;
   BatchMsg& M = s_M;
-  const GQ RingDev& mine = D->ring[W->ring];
+  const Ring mine = ring_regs(D, uni(W->ring));
   unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   GQ int* keep = (GQ int*)D->buf[10];
@@ -150,14 +181,14 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
   for (unsigned k = threadIdx.x; k < count; k += AMP_THREADS) pend_tok[k] = keep[k];
   __syncthreads();
   for (;;) {
-    const int n = wait_batch(D, mine, head, KB, lk.muf - (int)count, s_codes, &s_n, code_is_b);
+    const int n = wait_batch(D, mine, head, KB, lk_muf - (int)count, s_codes, &s_n, code_is_b);
     if (n == 0) break;
     if (threadIdx.x < 64) {
       const int k = threadIdx.x;
       if (k < n) {
         const unsigned code = s_codes[k];
         const int s = MSG_SLOT(code), l = MSG_LOCAL(code);
-        const v4i sm = tree_slot(D, s);
+        const v4i sm = tree_slot(smeta, s);
         M.s[k] = s;
         M.n[k] = l;
         M.seq[k] = (unsigned)sm.x;
@@ -165,7 +196,7 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
         M.aux[k] = code_is_b(code);
         if (!code_is_b(code) && l == 0) left_cnt[s] = sm.y;
       }
-      batch_split_and_log(D, W, M, n, 0, false);
+      batch_split_and_log(D, wr, M, n, 0, false);
       // backward message k is the b-th gradient of the batch: remember its token
       const bool isb = k < n && M.aux[k] != 0;
       const unsigned long long mb = __ballot(isb);
@@ -208,14 +239,14 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
       const int k = threadIdx.x;
       if (k < n) {
         if (!M.aux[k]) {
-          ring_post(D->ring[TR_LEAF], MSG_MAKE(0, M.s[k], M.n[k]));
-        } else if (D->train) {
-          if (atomicSub(&left_cnt[M.s[k]], 1) == 1) ring_post(D->ring[0], MSG_MAKE(1, M.s[k], 0));
+          ring_post(wr.leaf, MSG_MAKE(0, M.s[k], M.n[k]));
+        } else if (wr.train) {
+          if (atomicSub(&left_cnt[M.s[k]], 1) == 1) ring_post(wr.ctl, MSG_MAKE(1, M.s[k], 0));
         }
       }
     }
     count += M.nB;
-    if ((int)count >= lk.muf) {
+    if ((int)count >= lk_muf) {
       // SGD on the touched rows: each waiting gradient row is subtracted from its
       // token's row, in arrival order (rows never touched have a zero gradient)
       tstep++;
@@ -866,7 +897,10 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
   const TreeBufs B = tree_bufs(D);
   const Pend pd = make_pend(W, t);
   GQ float* pend = (GQ float*)pd.base;
-  const int R = t.R, H = B.H, Hp = B.Hp, nu = t.nu, u0 = t.u0, KB = W->kb;
+  const WorkerRegs wr = worker_regs(D, W);
+  const int R = t.R, H = B.H, Hp = B.Hp, nu = t.nu, u0 = t.u0, KB = wr.kb, nd_muf = uni(nd.muf);
+  const GQ int* smeta = uni_gq<int>(D->smeta);
+  const GQ int* tnode = uni_gq<int>(D->data.tnode);
   const int ldy = amp_ldrow(R);
   Lds L{lds};
   float* Wg = L.take(STREAM ? 0 : t.Rp * t.ldw);
@@ -881,7 +915,7 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
   LDSQ int* colmap = (LDSQ int*)L.take(CMW);
   LDSQ int* rowoff = (LDSQ int*)L.take(STREAM ? t.Rp : 0);   // streamed weights: node row * cols
   LDSQ float* Xs = (LDSQ float*)L.take(STREAM ? 2 * 64 * TREE_XS : 0);   // streamed weights: input chunks
-  GQ float* ndP = (GQ float*)nd.P;
+  GQ float* ndP = uni_gq<float>(nd.P);
   if (STREAM) {
     for (int i = threadIdx.x; i < t.Rp; i += AMP_THREADS) {
       rowoff[i] = i < R ? t.grow(i) * t.C : 0;
@@ -895,25 +929,25 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
   for (int i = threadIdx.x; i < CMW; i += AMP_THREADS) colmap[i] = t.ncol(i);
   __syncthreads();
   // bias gradient of tile row threadIdx.x accumulated since the last update (rests in HBM between launches)
-  GQ float* ndG = (GQ float*)nd.G;
+  GQ float* ndG = uni_gq<float>(nd.G);
   float accb = ((int)threadIdx.x < R && nd.has_bias) ? ndG[(long long)nd.rows * t.C + t.grow(threadIdx.x)] : 0.f;
   BatchMsg& M = s_M;
   __syncthreads();
-  const GQ RingDev& mine = D->ring[W->ring];
+  const Ring mine = ring_regs(D, uni(W->ring));
   const GQ float* xbase = BR ? B.hc : B.xin;
   GQ float* obase = BR ? B.gpar : B.gx;
   unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   for (;;) {
-    const int n = wait_batch(D, mine, head, KB, nd.muf - (int)count, s_codes, &s_n, code_is_b);
+    const int n = wait_batch(D, mine, head, KB, nd_muf - (int)count, s_codes, &s_n, code_is_b);
     if (n == 0) break;
     if (threadIdx.x < 64) {
       const int k = threadIdx.x;
       if (k < n) {
         const unsigned code = s_codes[k];
         const int s = MSG_SLOT(code), nn = MSG_LOCAL(code);
-        const v4i sm = tree_slot(D, s);
-        const v4i tn = tree_node(D, sm.z, nn);
+        const v4i sm = tree_slot(smeta, s);
+        const v4i tn = tree_node(tnode, sm.z, nn);
         M.s[k] = s;
         M.n[k] = nn;
         M.seq[k] = (unsigned)sm.x;
@@ -925,14 +959,14 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
         if (BR) {
           M.off0[k] = (int)(B.node(s, tn.x) * 2 * Hp);
           M.off1[k] = (int)(B.node(s, tn.y) * 2 * Hp);
-          M.dst0[k] = (int)((B.node(s, tn.x) * B.TB + W->tile) * Hp);
-          M.dst1[k] = (int)((B.node(s, tn.y) * B.TB + W->tile) * Hp);
+          M.dst0[k] = (int)((B.node(s, tn.x) * B.TB + wr.tile) * Hp);
+          M.dst1[k] = (int)((B.node(s, tn.y) * B.TB + wr.tile) * Hp);
         } else {
           M.off0[k] = M.off1[k] = (int)(B.leaf(s, nn) * B.Ep);
-          M.dst0[k] = M.dst1[k] = (int)((B.leaf(s, nn) * B.TL + W->tile) * B.Ep);
+          M.dst0[k] = M.dst1[k] = (int)((B.leaf(s, nn) * B.TL + wr.tile) * B.Ep);
         }
       }
-      batch_split_and_log(D, W, M, n, W->node, false);
+      batch_split_and_log(D, wr, M, n, wr.node, false);
     }
     lds_barrier();
     const int nF = M.nF, nB = M.nB;
@@ -1081,18 +1115,18 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
       if (k < n) {
         const int s = M.s[k], nn = M.n[k];
         if (!M.aux[k]) {
-          tree_node_part_done(D, B, s, nn, M.par[k], W->ntiles);
+          tree_node_part_done(wr, B, s, nn, M.par[k]);
         } else if (BR) {
-          tree_grad_part_done(D, B, s, M.a[k], false, M.a[k] < M.L[k]);
-          tree_grad_part_done(D, B, s, M.b[k], false, M.b[k] < M.L[k]);
+          tree_grad_part_done(wr, B, s, M.a[k], false, M.a[k] < M.L[k]);
+          tree_grad_part_done(wr, B, s, M.b[k], false, M.b[k] < M.L[k]);
         } else {
-          if (join_arrive(B.cnt + B.node(s, nn) * 4 + 3, B.TL)) ring_post(D->ring[TR_LOOKUP], MSG_MAKE(1, s, nn));
+          if (join_arrive(B.cnt + B.node(s, nn) * 4 + 3, B.TL)) ring_post(wr.lookup, MSG_MAKE(1, s, nn));
         }
       }
     }
     PHASE(6);
     count += nB;
-    if ((int)count >= nd.muf) {
+    if ((int)count >= nd_muf) {
       // the node's own update (Section 3): optimizer step on the LDS weights with the accumulated gradient
       tstep++;
       if (STREAM)
@@ -1131,7 +1165,10 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
   const GQ NodeDev& nd = D->node[3];
   const Tile t = make_tile(nd, W);
   const TreeBufs B = tree_bufs(D);
-  const int R = t.R, C = t.C, H = B.H, Hp = B.Hp, KB = W->kb, ldw = t.ldw;
+  const WorkerRegs wr = worker_regs(D, W);
+  const int R = t.R, C = t.C, H = B.H, Hp = B.Hp, KB = wr.kb, ldw = t.ldw, nd_muf = uni(nd.muf);
+  const GQ int* smeta = uni_gq<int>(D->smeta);
+  const GQ int* tnode = uni_gq<int>(D->data.tnode);
   Lds L{lds};
   float* Wg = L.take(t.Rp * t.ldw);
   float* bg = L.take(t.Rp);
@@ -1157,11 +1194,11 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
   gb = (int)threadIdx.x < R ? ndG[R * C + threadIdx.x] : 0.f;
   BatchMsg& M = s_M;
   __syncthreads();
-  const GQ RingDev& mine = D->ring[W->ring];
+  const Ring mine = ring_regs(D, uni(W->ring));
   unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   for (;;) {
-    const int room = D->train ? nd.muf - (int)count : KB_MAX;
+    const int room = wr.train ? nd_muf - (int)count : KB_MAX;
     const int n = wait_batch(D, mine, head, KB, room, s_codes, &s_n, [](unsigned) { return true; });
     if (n == 0) break;
     if (threadIdx.x < 64) {
@@ -1169,8 +1206,8 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
       if (k < n) {
         const unsigned code = s_codes[k];
         const int s = MSG_SLOT(code), nn = MSG_LOCAL(code);
-        const v4i sm = tree_slot(D, s);
-        const v4i tn = tree_node(D, sm.z, nn);
+        const v4i sm = tree_slot(smeta, s);
+        const v4i tn = tree_node(tnode, sm.z, nn);
         M.s[k] = s;
         M.n[k] = nn;
         M.seq[k] = (unsigned)sm.x;
@@ -1181,7 +1218,7 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
         M.off0[k] = (int)(B.node(s, nn) * 2 * Hp);
         M.dst0[k] = (int)(B.node(s, nn) * H);
       }
-      batch_split_and_log(D, W, M, n, 3, D->train != 0);
+      batch_split_and_log(D, wr, M, n, 3, wr.train != 0);
     }
     lds_barrier();
     for (int idx = threadIdx.x; idx < n * (Hp >> 2); idx += AMP_THREADS) {
@@ -1253,13 +1290,13 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
       fence_release();
       const int k = threadIdx.x;
       if (k < n) {
-        if (!D->train) {
+        if (!wr.train) {
           if (atomicAdd((int*)&done_cnt[M.s[k]], 1) + 1 == 2 * M.L[k] - 1) {
             done_cnt[M.s[k]] = 0;
-            ring_post(D->ring[0], MSG_MAKE(1, M.s[k], 0));
+            ring_post(wr.ctl, MSG_MAKE(1, M.s[k], 0));
           }
         } else {
-          tree_grad_part_done(D, B, M.s[k], M.n[k], M.par[k] < 0, M.n[k] < M.L[k]);
+          tree_grad_part_done(wr, B, M.s[k], M.n[k], M.par[k] < 0, M.n[k] < M.L[k]);
         }
       }
     }
