@@ -160,12 +160,22 @@ __device__ __forceinline__ void mfma_rows_fixed(const LDSQ float* Wl, int ldw, c
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int a = 0; a < NA; ++a) acc[nb][a] = zero;
+    // operands of column group g + 1 are fetched from LDS before the products of group g are issued
+    v4f w = *(const LDSQ v4f*)wp, x[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) x[nb] = *(const LDSQ v4f*)(xp + nb * 16 * ldx);
 #pragma unroll
     for (int g = 0; g < NCG; ++g) {
-      const v4f w = *(const LDSQ v4f*)(wp + 16 * g);
-      v4f x[NB];
+      v4f wn = w, xn[NB];
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) x[nb] = *(const LDSQ v4f*)(xp + nb * 16 * ldx + 16 * g);
+      for (int nb = 0; nb < NB; ++nb) xn[nb] = x[nb];
+      if (g + 1 < NCG) {
+        wn = *(const LDSQ v4f*)(wp + 16 * (g + 1));
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) xn[nb] = *(const LDSQ v4f*)(xp + nb * 16 * ldx + 16 * (g + 1));
+        // the fetches above are issued before this point, the products below (which need acc[0][0]) after it
+        asm volatile("" : "+v"(acc[0][0]) : : "memory");
+      }
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         acc[nb][0] = MFMA(w.x, x[nb].x, acc[nb][0]);
@@ -176,6 +186,9 @@ __device__ __forceinline__ void mfma_rows_fixed(const LDSQ float* Wl, int ldw, c
         acc[nb][NA == 4 ? 2 : 0] = MFMA(w.z, x[nb].z, acc[nb][NA == 4 ? 2 : 0]);
         acc[nb][NA == 4 ? 3 : 1] = MFMA(w.w, x[nb].w, acc[nb][NA == 4 ? 3 : 1]);
       }
+      w = wn;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) x[nb] = xn[nb];
     }
     const v4f b4 = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
 #pragma unroll
@@ -239,13 +252,27 @@ __device__ __forceinline__ void mfma_cols_fixed(const LDSQ float* Wl, int ldw, c
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
       for (int a = 0; a < NA; ++a) acc[nb][a] = zero;
+    // operands of row block g + 1 are fetched from LDS before the products of block g are issued
+    v4f d[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) d[nb] = *(const LDSQ v4f*)(dp + nb * 16 * ldd);
+    float w0 = wp[0], w1 = wp[ldw], w2 = wp[2 * ldw], w3 = wp[3 * ldw];
 #pragma unroll
     for (int g = 0; g < NRB; ++g) {
-      v4f d[NB];
+      v4f dn[NB];
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) d[nb] = *(const LDSQ v4f*)(dp + nb * 16 * ldd + 16 * g);
-      const LDSQ float* w = wp + 16 * g * ldw;
-      const float w0 = w[0], w1 = w[ldw], w2 = w[2 * ldw], w3 = w[3 * ldw];
+      for (int nb = 0; nb < NB; ++nb) dn[nb] = d[nb];
+      float n0 = w0, n1 = w1, n2 = w2, n3 = w3;
+      if (g + 1 < NRB) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) dn[nb] = *(const LDSQ v4f*)(dp + nb * 16 * ldd + 16 * (g + 1));
+        const LDSQ float* w = wp + 16 * (g + 1) * ldw;
+        n0 = w[0];
+        n1 = w[ldw];
+        n2 = w[2 * ldw];
+        n3 = w[3 * ldw];
+        asm volatile("" : "+v"(acc[0][0]) : : "memory");
+      }
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
         acc[nb][0] = MFMA(w0, d[nb].x, acc[nb][0]);
@@ -256,6 +283,12 @@ __device__ __forceinline__ void mfma_cols_fixed(const LDSQ float* Wl, int ldw, c
         acc[nb][NA == 4 ? 2 : 0] = MFMA(w2, d[nb].z, acc[nb][NA == 4 ? 2 : 0]);
         acc[nb][NA == 4 ? 3 : 1] = MFMA(w3, d[nb].w, acc[nb][NA == 4 ? 3 : 1]);
       }
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) d[nb] = dn[nb];
+      w0 = n0;
+      w1 = n1;
+      w2 = n2;
+      w3 = n3;
     }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {

@@ -17,8 +17,10 @@
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-// The workgroup's dynamic LDS; every role carves its buffers out of it.
-extern __shared__ float amp_lds[];
+// The workgroup's dynamic LDS; every role carves its buffers out of it.  The alignment matters: the dynamic part
+// starts where the static variables end, and a base that is only 8-byte aligned makes every 16-byte LDS access of
+// the workers a split one (measured: the grouped-row product then takes 7 us instead of 3.1 us).
+extern __shared__ __attribute__((aligned(256))) float amp_lds[];
 
 __device__ __forceinline__ unsigned ld_u32(const unsigned* p) {
   return __hip_atomic_load((const GQ unsigned*)p, __ATOMIC_RELAXED, AGENT);
