@@ -183,6 +183,46 @@ __device__ __forceinline__ float g_state_gradient(const GBufs& B, unsigned prese
   return a;
 }
 
+// Four consecutive elements (c .. c + 3) of a_k = sum of the messages on node k's incoming edges, ascending edge
+// order; the edge numbers of up to four edges are fetched together, then their rows.
+__device__ __forceinline__ v4f g_sum_incoming4(const GQ float* msg, const GView& v, int k, int c, int H) {
+  const int p0 = v.inoff[k], p1 = v.inoff[k + 1];
+  v4f x = {0.f, 0.f, 0.f, 0.f};
+  for (int p = p0; p < p1; p += 4) {
+    int e[4];
+    v4f m[4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) e[a] = v.inedge[p + a < p1 ? p + a : p1 - 1];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) m[a] = *(const GQ v4f*)(msg + (long long)e[a] * H + c);
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+      if (p + a < p1) x += m[a];
+  }
+  return x;
+}
+
+__device__ __forceinline__ v4f sigmoid4(v4f y) { return (v4f){sigmoidf_(y.x), sigmoidf_(y.y), sigmoidf_(y.z), sigmoidf_(y.w)}; }
+__device__ __forceinline__ v4f tanh4(v4f y) { return (v4f){tanhf(y.x), tanhf(y.y), tanhf(y.z), tanhf(y.w)}; }
+
+// Four consecutive elements of the same sum.
+__device__ __forceinline__ v4f g_state_gradient4(const GBufs& B, unsigned present, int s, int i) {
+  const long long NH = (long long)B.N * B.H;
+  const GQ float* he = B.dHe + (long long)s * B.T * NH + i;
+  const GQ float* hp = B.dHp + (long long)s * 3 * NH + i;
+  v4f e[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) e[c] = *(const GQ v4f*)(he + (((present >> c) & 1u) ? c * NH : 0));
+  const v4f p0 = *(const GQ v4f*)hp, p1 = *(const GQ v4f*)(hp + NH), p2 = *(const GQ v4f*)(hp + 2 * NH);
+  v4f a = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int c = 0; c < 8; ++c)
+    if ((present >> c) & 1u) a += e[c];
+  a += p1 + p2;
+  a += p0;
+  return a;
+}
+
 // LDS pieces every dense graph worker carves: weight tile, bias, row / column maps for the update.
 struct GTile {
   float *Wg, *bg;
@@ -321,7 +361,9 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
   const GRings rg = g_rings(D);
   const Pend pd = make_pend(W, t);
   GQ float* pend = (GQ float*)pd.base;
-  const int H = B.H, ctype = W->aux, Ep = amp_round16(B.Em), Hs = amp_ldrow(H);
+  const int H = B.H, ctype = uni(W->aux), Ep = amp_round16(B.Em), Hs = amp_ldrow(H);
+  const bool vec = (H & 3) == 0;   // rows can be moved 16 bytes at a time
+  const int G1 = H >> 2;
   const int NRB = t.Rp >> 4, NCG = amp_round16(H) >> 4;
   Lds L{lds};
   const GTile g = g_tile_setup(L, nd, t);
@@ -342,6 +384,15 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
     const GQ int* te = v.tedge + uni(v.tstart[ctype]);   // edges of this type, ascending (Group orders its rows by edge index)
     const GQ float* h = B.Hm + B.hm(s, it);
     const int nact = __popc(g_present_types(v, B.T));
+    if (vec) {
+      const int GY = Hs >> 2;   // padding columns of a used row are written as zeros every time
+      for (int idx = threadIdx.x; idx < K * GY; idx += AMP_THREADS) {
+        const int k = idx / GY, c = (idx - k * GY) << 2;
+        const bool in = c < H;
+        const v4f x = *(const GQ v4f*)(h + (long long)v.src[te[k]] * H + (in ? c : 0));
+        *(LDSQ v4f*)(X + k * Hs + c) = in ? x : (v4f){0.f, 0.f, 0.f, 0.f};
+      }
+    } else
     for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
       const int k = i / Hs, j = i - k * Hs;
       X[i] = j < H ? h[v.src[te[k]] * H + j] : 0.f;   // padding columns of a used row are zero
@@ -350,6 +401,12 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
       lds_barrier();
       mfma_rows<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, g.bl, X, Hs, NB, Y, Hs);
       GQ float* msg = B.Msg + (long long)s * B.Em * H;
+      if (vec) {
+        for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
+          const int k = idx / G1, c = (idx - k * G1) << 2;
+          *(GQ v4f*)(msg + (long long)te[k] * H + c) = *(const LDSQ v4f*)(Y + k * Hs + c);
+        }
+      } else
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
         const int k = i / H, j = i - k * H;
         msg[te[k] * H + j] = Y[k * Hs + j];
@@ -370,6 +427,16 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
     {
       const long long NH = (long long)B.N * H;
       const GQ float* dA = B.dA + (long long)s * 3 * NH;
+      if (vec) {
+        const int GY = Hs >> 2;
+        for (int idx = threadIdx.x; idx < K * GY; idx += AMP_THREADS) {
+          const int k = idx / GY, c = (idx - k * GY) << 2;
+          const bool in = c < H;
+          const GQ float* p = dA + (long long)v.dst[te[k]] * H + (in ? c : 0);
+          const v4f d0 = *(const GQ v4f*)p, d1 = *(const GQ v4f*)(p + NH), d2 = *(const GQ v4f*)(p + 2 * NH);
+          *(LDSQ v4f*)(Y + k * Hs + c) = in ? (d1 + d2) + d0 : (v4f){0.f, 0.f, 0.f, 0.f};
+        }
+      } else
       for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
         const int k = i / Hs, j = i - k * Hs;
         float d = 0.f;
@@ -390,6 +457,22 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
       GQ float* dHe = B.dHe + ((long long)s * B.T + ctype) * B.N * H;
       const GQ int* so = v.tsoff + ctype * (v.N + 1);
       const GQ int* sk = v.tsk + uni(v.tstart[ctype]);
+      if (vec) {
+        for (int idx = threadIdx.x; idx < v.N * G1; idx += AMP_THREADS) {
+          const int n = idx / G1, c = (idx - n * G1) << 2;
+          const int p0 = so[n], p1 = so[n + 1];
+          v4f a = {0.f, 0.f, 0.f, 0.f};
+          for (int p = p0; p < p1; p += 4) {
+            int kk[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) kk[u] = sk[p + u < p1 ? p + u : p1 - 1];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+              if (p + u < p1) a += *(const LDSQ v4f*)(X + kk[u] * Hs + c);
+          }
+          *(GQ v4f*)(dHe + n * H + c) = a;
+        }
+      } else
       for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) {
         const int n = i / H, j = i - n * H;
         float a = 0.f;
@@ -430,7 +513,9 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
   const GRings rg = g_rings(D);
   const Pend pd = make_pend(W, t);
   GQ float* pend = (GQ float*)pd.base;
-  const int H = B.H, C = 2 * H, Np = amp_round16(B.N), which = W->aux, Hs = amp_ldrow(H), Cs = amp_ldrow(C);
+  const int H = B.H, C = 2 * H, Np = amp_round16(B.N), which = uni(W->aux), Hs = amp_ldrow(H), Cs = amp_ldrow(C);
+  const bool vec = (H & 3) == 0;   // rows can be moved 16 bytes at a time
+  const int G1 = H >> 2;
   const int NRB = t.Rp >> 4, NCG = amp_round16(C) >> 4;
   Lds L{lds};
   const GTile g = g_tile_setup(L, nd, t);
@@ -455,6 +540,22 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
     if (!(code & MSG_DIR_B)) {
       // Ungroup, regroup by target node, sum: a_v = sum over incoming edges in edge order
       const GQ float* msg = B.Msg + (long long)s * B.Em * H;
+      if (vec) {
+        // 16 bytes per thread and step; the padding columns of a used row are written as zeros every time (an
+        // unused row may hold anything, and the products leave 0 x anything in its padding)
+        const int GX = Cs >> 2;
+        for (int idx = threadIdx.x; idx < K * GX; idx += AMP_THREADS) {
+          const int k = idx / GX, c = (idx - k * GX) << 2;
+          v4f x = (v4f){0.f, 0.f, 0.f, 0.f};
+          if (c < H) {
+            x = g_sum_incoming4(msg, v, k, c, H);
+            if (which == 0) *(GQ v4f*)(A + k * H + c) = x;
+          } else if (c < C) {
+            x = *(const GQ v4f*)(h + k * H + c - H);
+          }
+          *(LDSQ v4f*)(X + k * Cs + c) = x;
+        }
+      } else
       for (int i = threadIdx.x; i < K * Cs; i += AMP_THREADS) {
         const int k = i / Cs, c = i - k * Cs;
         float x = 0.f;   // padding columns of a used row are zero
@@ -468,6 +569,12 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       }
       lds_barrier();
       mfma_rows<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, g.bl, X, Cs, NB, Y, Hs);
+      if (vec) {
+        for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
+          const int k = idx / G1, c = (idx - k * G1) << 2;
+          *(GQ v4f*)(outp + k * H + c) = sigmoid4(*(const LDSQ v4f*)(Y + k * Hs + c));
+        }
+      } else
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) outp[i] = sigmoidf_(Y[(i / H) * Hs + i % H]);
       LOG(W->node, 0, seq, it);
       __syncthreads();
@@ -478,13 +585,31 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       continue;
     }
     const GQ float* dpre = (which == 0 ? B.dZ : B.dR) + B.sl(s);
-    for (int i = threadIdx.x; i < K * Cs; i += AMP_THREADS) {
-      const int k = i / Cs, c = i - k * Cs;
-      X[i] = c < H ? A[k * H + c] : c < C ? h[k * H + c - H] : 0.f;
-    }
-    for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
-      const int k = i / Hs, j = i - k * Hs;
-      Y[i] = j < H ? dpre[k * H + j] : 0.f;
+    if (vec) {
+      const int GY = Hs >> 2;   // 16-byte groups of a delta row, padding included
+      for (int idx = threadIdx.x; idx < K * GY; idx += AMP_THREADS) {
+        const int k = idx / GY, c = (idx - k * GY) << 2;
+        const bool in = c < H;
+        const int o = k * H + (in ? c : 0);
+        const v4f a = *(const GQ v4f*)(A + o), hv = *(const GQ v4f*)(h + o), dp = *(const GQ v4f*)(dpre + o);
+        if (in) {
+          *(LDSQ v4f*)(X + k * Cs + c) = a;
+          *(LDSQ v4f*)(X + k * Cs + H + c) = hv;
+        }
+        *(LDSQ v4f*)(Y + k * Hs + c) = in ? dp : (v4f){0.f, 0.f, 0.f, 0.f};
+      }
+      const int GP = (Cs - C) >> 2;   // padding columns of the used rows of X
+      for (int idx = threadIdx.x; idx < K * GP; idx += AMP_THREADS)
+        *(LDSQ v4f*)(X + (idx / GP) * Cs + C + ((idx % GP) << 2)) = (v4f){0.f, 0.f, 0.f, 0.f};
+    } else {
+      for (int i = threadIdx.x; i < K * Cs; i += AMP_THREADS) {
+        const int k = i / Cs, c = i - k * Cs;
+        X[i] = c < H ? A[k * H + c] : c < C ? h[k * H + c - H] : 0.f;
+      }
+      for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
+        const int k = i / Hs, j = i - k * Hs;
+        Y[i] = j < H ? dpre[k * H + j] : 0.f;
+      }
     }
     lds_barrier();
     LOG(W->node, 1, seq, it);
@@ -493,6 +618,13 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
     mfma_cols<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Cs);
     GQ float* dA = B.dA + ((long long)s * 3 + 1 + which) * B.N * H;
     GQ float* dHp = B.dHp + ((long long)s * 3 + 1 + which) * B.N * H;
+    if (vec) {
+      for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
+        const int k = idx / G1, c = (idx - k * G1) << 2;
+        *(GQ v4f*)(dA + k * H + c) = *(const LDSQ v4f*)(X + k * Cs + c);
+        *(GQ v4f*)(dHp + k * H + c) = *(const LDSQ v4f*)(X + k * Cs + H + c);
+      }
+    } else
     for (int i = threadIdx.x; i < K * C; i += AMP_THREADS) {
       const int k = i / C, c = i - k * C;
       if (c < H)
@@ -532,6 +664,8 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
   const Pend pd = make_pend(W, t);
   GQ float* pend = (GQ float*)pd.base;
   const int H = B.H, C = 2 * H, Np = amp_round16(B.N), Hs = amp_ldrow(H), Cs = amp_ldrow(C);
+  const bool vec = (H & 3) == 0;   // rows can be moved 16 bytes at a time
+  const int G1 = H >> 2;
   const int NRB = t.Rp >> 4, NCG = amp_round16(C) >> 4;
   Lds L{lds};
   const GTile g = g_tile_setup(L, nd, t);
@@ -558,6 +692,17 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
     const GQ float* Rr = B.Rr + B.st(s, it);
     GQ float* Ht = B.Ht + B.st(s, it);
     PHASE(0);
+    if (vec) {
+      for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
+        const int k = idx / G1, c = (idx - k * G1) << 2, o = k * H + c;
+        const v4f a = *(const GQ v4f*)(A + o), r = *(const GQ v4f*)(Rr + o), hv = *(const GQ v4f*)(h + o);
+        *(LDSQ v4f*)(X + k * Cs + c) = a;
+        *(LDSQ v4f*)(X + k * Cs + H + c) = r * hv;
+      }
+      const int GP = (Cs - C) >> 2;   // padding columns of the used rows of X
+      for (int idx = threadIdx.x; idx < K * GP; idx += AMP_THREADS)
+        *(LDSQ v4f*)(X + (idx / GP) * Cs + C + ((idx % GP) << 2)) = (v4f){0.f, 0.f, 0.f, 0.f};
+    } else
     for (int i = threadIdx.x; i < K * Cs; i += AMP_THREADS) {
       const int k = i / Cs, c = i - k * Cs;
       X[i] = c < H ? A[k * H + c] : c < C ? Rr[k * H + c - H] * h[k * H + c - H] : 0.f;
@@ -568,6 +713,15 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
       mfma_rows<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, g.bl, X, Cs, NB, Y, Hs);
       PHASE(2);
       GQ float* hn = B.Hm + B.hm(s, it + 1);
+      if (vec) {
+        for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
+          const int k = idx / G1, c = (idx - k * G1) << 2, o = k * H + c;
+          const v4f z = *(const GQ v4f*)(Z + o), hv = *(const GQ v4f*)(h + o);
+          const v4f ht = tanh4(*(const LDSQ v4f*)(Y + k * Hs + c));
+          *(GQ v4f*)(Ht + o) = ht;
+          *(GQ v4f*)(hn + o) = (1.f - z) * hv + z * ht;
+        }
+      } else
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
         const float ht = tanhf(Y[(i / H) * Hs + i % H]), z = Z[i];
         Ht[i] = ht;
@@ -590,6 +744,21 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
       const GQ float* gH = B.gH + B.sl(s);
       GQ float* dZ = B.dZ + B.sl(s);
       const bool from_readout = it + 1 == B.S;
+      if (vec) {
+        const int GY = Hs >> 2;
+        for (int idx = threadIdx.x; idx < K * GY; idx += AMP_THREADS) {
+          const int k = idx / GY, c = (idx - k * GY) << 2;
+          const bool in = c < H;
+          const int o = k * H + (in ? c : 0);
+          const v4f z = *(const GQ v4f*)(Z + o), ht = *(const GQ v4f*)(Ht + o), hv = *(const GQ v4f*)(h + o);
+          const v4f gg = from_readout ? *(const GQ v4f*)(gH + o) : g_state_gradient4(B, present, s, o);
+          if (in) {
+            *(LDSQ v4f*)(gt + o) = gg;
+            *(GQ v4f*)(dZ + o) = gg * (ht - hv) * z * (1.f - z);
+          }
+          *(LDSQ v4f*)(Y + k * Hs + c) = in ? gg * z * (1.f - ht * ht) : (v4f){0.f, 0.f, 0.f, 0.f};
+        }
+      } else {
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
         const float gg = from_readout ? gH[i] : g_state_gradient(B, present, s, i);
         const float z = Z[i], ht = Ht[i];
@@ -598,6 +767,7 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
         Y[(i / H) * Hs + i % H] = gg * z * (1.f - ht * ht);
       }
       for (int i = threadIdx.x; i < K * (Hs - H); i += AMP_THREADS) Y[(i / (Hs - H)) * Hs + H + i % (Hs - H)] = 0.f;
+      }
     }
     lds_barrier();
     PHASE(4);
@@ -611,6 +781,16 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
       GQ float* dA = B.dA + (long long)s * 3 * B.N * H;
       GQ float* dHp = B.dHp + (long long)s * 3 * B.N * H;
       GQ float* dR = B.dR + B.sl(s);
+      if (vec) {
+        for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
+          const int k = idx / G1, c = (idx - k * G1) << 2, o = k * H + c;
+          const v4f r = *(const GQ v4f*)(Rr + o), z = *(const GQ v4f*)(Z + o), hv = *(const GQ v4f*)(h + o);
+          const v4f drh = *(const LDSQ v4f*)(X + k * Cs + H + c);
+          *(GQ v4f*)(dA + o) = *(const LDSQ v4f*)(X + k * Cs + c);
+          *(GQ v4f*)(dR + o) = drh * hv * r * (1.f - r);
+          *(GQ v4f*)(dHp + o) = drh * r + *(const LDSQ v4f*)(gt + o) * (1.f - z);
+        }
+      } else
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
         const int k = i / H, j = i - k * H;
         const float drh = X[k * Cs + H + j], r = Rr[i], z = Z[i];

@@ -19,7 +19,11 @@ SGD = dict(kind="sgd", lr=0.05)
 # single such element is enough to exceed 1e-5 in the norm.  The replay cases therefore use eps = 1e-6, which keeps
 # the optimizer's own amplification of rounding noise below the tolerance; the checker's Adam is pinned with the
 # customary eps against torch.optim.Adam in the CPU suite.
-ADAM = dict(kind="adam", lr=0.002, beta1=0.9, beta2=0.999, eps=1e-6)
+# The step size is 5e-4: at 2e-3 several of these short training runs amplify a 1e-7 perturbation of the
+# initial parameters 5..10 times in the checker itself (and the recurrent and graph models far more), which
+# leaves fp32 rounding too little room under 1e-5; each run has its own event order, so a case close to the
+# limit fails now and then.
+ADAM = dict(kind="adam", lr=0.0005, beta1=0.9, beta2=0.999, eps=1e-6)
 
 
 @pytest.mark.parametrize("mak,muf,opt", [(1, 1, SGD), (4, 1, SGD), (4, 3, ADAM), (8, 5, dict(kind="momentum", lr=0.02, momentum=0.9))])
@@ -50,7 +54,7 @@ def test_mlp_mak1_is_synchronous_sgd():
 # when its initial parameters are perturbed by 1e-7 (relative), so no fp32 implementation can follow it to 1e-5.
 # At lr = 5e-4 over 300 sequences the same perturbation stays at 1e-7 (the CPU suite checks this), and that
 # is the setting the recurrent Adam case uses.
-RNN_ADAM = dict(kind="adam", lr=0.0005, beta1=0.9, beta2=0.999, eps=1e-6)
+RNN_ADAM = dict(ADAM)
 # an update every 3 gradients amplifies more: the same check asks for lr = 2e-4 there
 RNN_ADAM_MUF3 = dict(RNN_ADAM, lr=0.0002)
 
@@ -164,8 +168,8 @@ GG_ODD = dict(n_node_types=5, hidden=37, n_edge_types=3, n_steps=3)
 
 # The graph model under Adam at lr = 0.002 trains at the edge of stability: repeated runs (each with its own
 # event order) put the worst per-graph loss between 2e-6 and 4e-5 off the checker while the parameters agree to
-# 1e-6, whatever eps is; at lr = 0.001 the worst loss difference is below 1e-6 in every run.
-G_ADAM = dict(ADAM, lr=0.001)
+# 1e-6, whatever eps is; at lr = 0.001 and below the worst loss difference is below 1e-6 in every run.
+G_ADAM = dict(ADAM)
 
 
 @pytest.mark.parametrize("mak,muf,opt,n", [(1, 1, dict(kind="sgd", lr=0.01), 40), (32, 20, G_ADAM, 300), (8, 3, MOM, 150)])
