@@ -249,15 +249,12 @@ __device__ __forceinline__ GTile g_tile_setup(Lds& L, const GQ NodeDev& nd, cons
 // bias gradient of row threadIdx.x.
 __device__ __forceinline__ void g_pend_append(GQ float* pend, int Rp, int stride, unsigned first, const LDSQ float* Dl, int ldd,
                                               int R, const LDSQ float* X, int ldx, int C, int K, float& gb) {
-  for (int i = threadIdx.x; i < K * stride; i += AMP_THREADS) {
-    const int k = i / stride, j = i - k * stride;
-    float v = 0.f;
-    if (j < Rp) {
-      if (j < R) v = Dl[k * ldd + j];
-    } else if (j - Rp < C) {
-      v = X[k * ldx + j - Rp];
-    }
-    pend[(long long)(first + k) * stride + j] = v;
+  // 16 bytes at a time: the rows' padding (beyond R in Dl, beyond C in X) is zero, and ldd >= Rp, ldx >= stride - Rp
+  const int per = stride >> 2;
+  for (int idx = threadIdx.x; idx < K * per; idx += AMP_THREADS) {
+    const int k = idx / per, j = (idx - k * per) << 2;
+    const v4f v = j < Rp ? *(const LDSQ v4f*)(Dl + k * ldd + j) : *(const LDSQ v4f*)(X + k * ldx + j - Rp);
+    *(GQ v4f*)(pend + (long long)(first + k) * stride + j) = v;
   }
   if ((int)threadIdx.x < R)
     for (int k = 0; k < K; ++k) gb += Dl[k * ldd + threadIdx.x];
