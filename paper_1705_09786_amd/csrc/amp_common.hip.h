@@ -189,8 +189,8 @@ __device__ __forceinline__ void log_event(const GQ AmpDev* D, const GQ WorkerDev
 
 // y[r] = b[r] + sum_c Wl[r][c] * x[c].  Thread (p, r) sums the p-th column
 // chunk of row r; partials meet in `part` (>= P * R floats).  All threads.
-__device__ __forceinline__ void gemv_rows(const float* Wl, int ldw, int R, int C, const float* bl, const float* x, float* part,
-                          float* y) {
+__device__ __forceinline__ void gemv_rows(const LDSQ float* Wl, int ldw, int R, int C, const LDSQ float* bl, const LDSQ float* x,
+                                          LDSQ float* part, LDSQ float* y) {
   int P = AMP_THREADS / R;
   if (P < 1) P = 1;
   if (P > 8) P = 8;
@@ -200,7 +200,7 @@ __device__ __forceinline__ void gemv_rows(const float* Wl, int ldw, int R, int C
     const int c0 = p * chunk;
     int c1 = c0 + chunk;
     if (c1 > C) c1 = C;
-    const float* w = Wl + r * ldw;
+    const LDSQ float* w = Wl + r * ldw;
     float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
     int c = c0;
     for (; c + 3 < c1; c += 4) {
@@ -212,18 +212,19 @@ __device__ __forceinline__ void gemv_rows(const float* Wl, int ldw, int R, int C
     for (; c < c1; ++c) s0 = fmaf(w[c], x[c], s0);
     part[p * R + r] = (s0 + s1) + (s2 + s3);
   }
-  __syncthreads();
+  lds_barrier();
   for (int r = threadIdx.x; r < R; r += AMP_THREADS) {
     float s = bl ? bl[r] : 0.f;
     for (int p = 0; p < P; ++p) s += part[p * R + r];
     y[r] = s;
   }
-  __syncthreads();
+  lds_barrier();
 }
 
 // dx[c] = sum_r Wl[r][c] * d[r].  Thread (p, c) sums the p-th row chunk of
 // column c.  `part` >= P * C floats.  All threads.
-__device__ __forceinline__ void gemv_cols(const float* Wl, int ldw, int R, int C, const float* d, float* part, float* dx) {
+__device__ __forceinline__ void gemv_cols(const LDSQ float* Wl, int ldw, int R, int C, const LDSQ float* d, LDSQ float* part,
+                                          LDSQ float* dx) {
   int P = AMP_THREADS / C;
   if (P < 1) P = 1;
   if (P > 8) P = 8;
@@ -233,7 +234,7 @@ __device__ __forceinline__ void gemv_cols(const float* Wl, int ldw, int R, int C
     const int r0 = p * chunk;
     int r1 = r0 + chunk;
     if (r1 > R) r1 = R;
-    const float* w = Wl + c;
+    const LDSQ float* w = Wl + c;
     float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
     int r = r0;
     for (; r + 3 < r1; r += 4) {
@@ -245,13 +246,13 @@ __device__ __forceinline__ void gemv_cols(const float* Wl, int ldw, int R, int C
     for (; r < r1; ++r) s0 = fmaf(w[r * ldw], d[r], s0);
     part[p * C + c] = (s0 + s1) + (s2 + s3);
   }
-  __syncthreads();
+  lds_barrier();
   for (int c = threadIdx.x; c < C; c += AMP_THREADS) {
     float s = 0.f;
     for (int p = 0; p < P; ++p) s += part[p * C + c];
     dx[c] = s;
   }
-  __syncthreads();
+  lds_barrier();
 }
 
 // ---------------------------------------------------------------- tiles
@@ -331,6 +332,17 @@ __device__ __forceinline__ void tile_accumulate(const GQ NodeDev& nd, const Tile
     for (int lr = threadIdx.x; lr < t.R; lr += AMP_THREADS) nd.G[(long long)nd.rows * t.C + t.grow(lr)] += d[lr];
 }
 
+// The same with the accumulator in LDS (Gl laid out like the weight tile, gbl like the bias): x must be padded
+// with zeros up to ldw.
+__device__ __forceinline__ void tile_accumulate_lds(const Tile& t, LDSQ float* Gl, LDSQ float* gbl, const LDSQ float* d,
+                                                    const LDSQ float* x) {
+  for (int i = threadIdx.x; i < t.R * t.ldw; i += AMP_THREADS) {
+    const int lr = i / t.ldw, c = i - lr * t.ldw;
+    Gl[i] = fmaf(d[lr], x[c], Gl[i]);
+  }
+  for (int lr = threadIdx.x; lr < t.R; lr += AMP_THREADS) gbl[lr] += d[lr];
+}
+
 // One optimizer step on a value held in LDS (w) with slots in HBM.
 struct OptCoef {
   float lr, mom, b1, b2, eps, c1, c2;  // c1 = 1/(1-b1^t), c2 = 1/(1-b2^t)
@@ -353,9 +365,7 @@ __device__ __forceinline__ OptCoef opt_coef(const GQ NodeDev& nd, unsigned tstep
   return o;
 }
 
-__device__ __forceinline__ float opt_apply(const OptCoef& o, float w, float g, float* Mp, float* Vp, long long gi) {
-  GQ float* M = (GQ float*)Mp;
-  GQ float* V = (GQ float*)Vp;
+__device__ __forceinline__ float opt_apply(const OptCoef& o, float w, float g, GQ float* M, GQ float* V, long long gi) {
   if (o.kind == 0) return w - o.lr * g;
   if (o.kind == 1) {
     const float m = fmaf(o.mom, M[gi], g);
@@ -367,6 +377,10 @@ __device__ __forceinline__ float opt_apply(const OptCoef& o, float w, float g, f
   M[gi] = m;
   V[gi] = v;
   return w - o.lr * (m * o.c1) / (sqrtf(v * o.c2) + o.eps);
+}
+
+__device__ __forceinline__ float opt_apply(const OptCoef& o, float w, float g, float* Mp, float* Vp, long long gi) {
+  return opt_apply(o, w, g, (GQ float*)Mp, (GQ float*)Vp, gi);
 }
 
 // Applies the node's optimizer to the tile with the accumulated gradient

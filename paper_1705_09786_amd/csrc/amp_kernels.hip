@@ -143,41 +143,69 @@ __device__ __forceinline__ void count_and_update(const GQ AmpDev* D, const GQ Wo
 // Worker for linear layer `aux` (0..2) with its ReLU fused; the last layer
 // also hosts the softmax loss, which turns the forward message round.
 // Slot storage: buf[0]=act1, buf[1]=act2 (post-ReLU outputs), buf[2]=grad
-// w.r.t. act1, buf[3]=grad w.r.t. act2.
+// w.r.t. act1, buf[3]=grad w.r.t. act2.  Weights, bias and the gradient
+// accumulator (same layout) stay in LDS for the life of the launch; the
+// accumulator rests in HBM between launches.
 __device__ __noinline__ void role_mlp_lin(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
-  const GQ NodeDev& nd = D->node[W->node];
+  const GQ NodeDev& nd = D->node[uni(W->node)];
   const Tile t = make_tile(nd, W);
-  const int R = t.R, C = t.C, li = W->aux;
+  const int R = t.R, C = t.C, li = uni(W->aux), ldw = t.ldw, muf = uni(nd.muf), train = uni(D->train);
   const bool first = li == 0, last = li == 2;
   Lds L{lds};
-  float* Wl = L.take(t.Rp * t.ldw);
-  float* bl = L.take(t.Rp);
-  float* xs = L.take(C);
-  float* ys = L.take(R);
-  float* ds = L.take(R);
-  float* dx = L.take(C);
-  float* part = L.take(8 * (R > C ? R : C));
-  tile_load(nd, t, Wl, bl);
-  const float* act_in = first ? nullptr : (const float*)D->buf[li - 1];
-  float* act_out = last ? nullptr : (float*)D->buf[li];
-  const float* g_in = last ? nullptr : (const float*)D->buf[2 + li];
-  float* g_out = first ? nullptr : (float*)D->buf[2 + li - 1];
-  const GQ RingDev& mine = D->ring[W->ring];
-  const GQ RingDev& next = D->ring[W->ring + 1];   // unused by the last layer
-  const GQ RingDev& prev = D->ring[W->ring - 1];   // the controller for the first layer
+  float* Wg = L.take(t.Rp * ldw);
+  float* bg = L.take(t.Rp);
+  LDSQ float* Wl = (LDSQ float*)Wg;
+  LDSQ float* bl = (LDSQ float*)bg;
+  LDSQ float* Gl = (LDSQ float*)L.take(t.Rp * ldw);
+  LDSQ float* gbl = (LDSQ float*)L.take(t.Rp);
+  LDSQ float* xs = (LDSQ float*)L.take(ldw);
+  LDSQ float* ys = (LDSQ float*)L.take(R);
+  LDSQ float* ds = (LDSQ float*)L.take(R);
+  LDSQ float* dx = (LDSQ float*)L.take(C);
+  LDSQ float* part = (LDSQ float*)L.take(8 * (R > C ? R : C));
+  tile_load(nd, t, Wg, bg);
+  GQ float* ndG = uni_gq<float>(nd.G);
+  GQ float* ndM = uni_gq<float>(nd.M);
+  GQ float* ndV = uni_gq<float>(nd.V);
+  const long long boff = (long long)uni(nd.rows) * C;
+  const int has_bias = uni(nd.has_bias);
+  for (int i = threadIdx.x; i < t.Rp * ldw; i += AMP_THREADS) {
+    const int lr = i / ldw, c = i - lr * ldw;
+    Gl[i] = (lr < R && c < C) ? ndG[(long long)lr * C + c] : 0.f;
+  }
+  for (int i = threadIdx.x; i < t.Rp; i += AMP_THREADS) gbl[i] = (i < R && has_bias) ? ndG[boff + i] : 0.f;
+  for (int i = threadIdx.x; i < ldw; i += AMP_THREADS) xs[i] = 0.f;
+  __syncthreads();
+  const GQ float* act_in = first ? nullptr : uni_gq<float>(D->buf[li - 1]);
+  GQ float* act_out = last ? nullptr : uni_gq<float>(D->buf[li]);
+  const GQ float* g_in = last ? nullptr : uni_gq<float>(D->buf[2 + li]);
+  GQ float* g_out = first ? nullptr : uni_gq<float>(D->buf[2 + li - 1]);
+  const GQ float* datax = uni_gq<float>(D->data.x);
+  const GQ int* lab = uni_gq<int>(D->data.lab);
+  const GQ int* lab_off = uni_gq<int>(D->data.lab_off);
+  const GQ unsigned* slot_seq = uni_gq<unsigned>(D->slot_seq);
+  GQ float* loss_out = uni_gq<float>(D->loss_out);
+  GQ int* correct_out = uni_gq<int>(D->correct_out);
+  const int n_inst = uni(D->data.n_inst);
+  const unsigned first_seq = uni(D->first_seq);
+  const int ring = uni(W->ring);
+  const Ring mine = ring_regs(D, ring), next = ring_regs(D, last ? ring : ring + 1), prev = ring_regs(D, ring - 1), ctl = ring_regs(D, 0);
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code);
-    const unsigned seq = D->slot_seq[s];
-    const int inst = seq % D->data.n_inst;
-    const float* x = first ? D->data.x + (long long)inst * C : act_in + (long long)s * C;
+    const unsigned seq = uni(slot_seq[s]);
+    const int inst = seq % n_inst;
+    const GQ float* x = first ? datax + (long long)inst * C : act_in + (long long)s * C;
     bool backward = (code & MSG_DIR_B) != 0;
     for (int c = threadIdx.x; c < C; c += AMP_THREADS) xs[c] = x[c];
-    __syncthreads();
+    if (backward)
+      for (int r = threadIdx.x; r < R; r += AMP_THREADS)
+        ds[r] = act_out[(long long)s * R + r] > 0.f ? g_in[(long long)s * R + r] : 0.f;
+    lds_barrier();
     if (!backward) {
-      gemv_rows(Wl, t.ldw, R, C, bl, xs, part, ys);
+      gemv_rows(Wl, ldw, R, C, bl, xs, part, ys);
       LOG(W->node, 0, seq, 0);
       if (!last) {
         for (int r = threadIdx.x; r < R; r += AMP_THREADS) act_out[(long long)s * R + r] = fmaxf(ys[r], 0.f);
@@ -188,40 +216,65 @@ __device__ __noinline__ void role_mlp_lin(const GQ AmpDev* D, const GQ WorkerDev
         }
         continue;
       }
-      const int label = D->data.lab[D->data.lab_off[inst]];
-      softmax_xent_wave0(ys, R, label, ds, &s_loss, &s_pred);
+      const int label = lab[lab_off[inst]];
+      softmax_xent_wave0((float*)ys, R, label, (float*)ds, &s_loss, &s_pred);
       if (threadIdx.x == 0) {
-        D->loss_out[seq - D->first_seq] = s_loss;
-        D->correct_out[seq - D->first_seq] = s_pred == label;
+        loss_out[seq - first_seq] = s_loss;
+        correct_out[seq - first_seq] = s_pred == label;
       }
-      if (!D->train) {
+      if (!train) {
         __syncthreads();
         if (threadIdx.x == 0) {
           fence_release();
-          ring_post(D->ring[0], MSG_MAKE(1, s, 0));
+          ring_post(ctl, MSG_MAKE(1, s, 0));
         }
         continue;
       }
       backward = true;   // the loss layer starts backpropagation
-    } else {
-      for (int r = threadIdx.x; r < R; r += AMP_THREADS)
-        ds[r] = act_out[(long long)s * R + r] > 0.f ? g_in[(long long)s * R + r] : 0.f;
-      __syncthreads();
     }
     LOG(W->node, 1, seq, 0);
     if (!first) {
-      gemv_cols(Wl, t.ldw, R, C, ds, part, dx);
+      gemv_cols(Wl, ldw, R, C, ds, part, dx);
       for (int c = threadIdx.x; c < C; c += AMP_THREADS) g_out[(long long)s * C + c] = dx[c];
     }
-    tile_accumulate(nd, t, ds, xs);
+    // every wave's HBM stores have landed before thread 0 publishes
     __syncthreads();
     if (threadIdx.x == 0) {
       fence_release();
       ring_post(prev, MSG_MAKE(1, s, 0));
     }
-    count_and_update(D, W, nd, t, Wl, bl, count, tstep);
+    tile_accumulate_lds(t, Gl, gbl, ds, xs);
+    count++;
+    if ((int)count >= muf) {
+      // the node's own update (Section 3) from the accumulator in LDS
+      tstep++;
+      lds_barrier();
+      const OptCoef o = opt_coef(nd, tstep);
+      const float inv = nd.mean ? 1.f / (float)count : 1.f;
+      for (int i = threadIdx.x; i < R * ldw; i += AMP_THREADS) {
+        const int lr = i / ldw, c = i - lr * ldw;
+        if (c < C) {
+          Wl[i] = opt_apply(o, Wl[i], Gl[i] * inv, ndM, ndV, (long long)lr * C + c);
+          Gl[i] = 0.f;
+        }
+      }
+      if (has_bias)
+        for (int lr = threadIdx.x; lr < R; lr += AMP_THREADS) {
+          bl[lr] = opt_apply(o, bl[lr], gbl[lr] * inv, ndM, ndV, boff + lr);
+          gbl[lr] = 0.f;
+        }
+      count = 0;
+      LOG(W->node, 2, 0, 0);
+    }
+    lds_barrier();
   }
-  tile_store(nd, t, Wl, bl);
+  tile_store(nd, t, Wg, bg);
+  for (int i = threadIdx.x; i < R * ldw; i += AMP_THREADS) {
+    const int lr = i / ldw, c = i - lr * ldw;
+    if (c < C) ndG[(long long)lr * C + c] = Gl[i];
+  }
+  if (has_bias)
+    for (int lr = threadIdx.x; lr < R; lr += AMP_THREADS) ndG[boff + lr] = gbl[lr];
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;

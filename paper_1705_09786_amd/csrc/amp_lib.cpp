@@ -227,7 +227,10 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
     case ROLE_G_READOUT:
       f = wfl + r4(c->dims.hidden) + AMP_THREADS;
       break;
-    default:   // MLP layers, RNN output layer
+    case ROLE_MLP_LIN:   // weights and a gradient accumulator of the same layout
+      f = 2 * wfl + r4(ldw) + r4(R) + r4(R) + r4(C) + r4(8 * std::max(R, C));
+      break;
+    default:   // RNN output layer
       f = wfl + r4(C) + r4(R) + r4(R) + r4(C) + r4(8 * std::max(R, C));
   }
   return f <= avail ? f : 0;

@@ -300,7 +300,7 @@ __device__ __noinline__ void role_rnn_out(const GQ AmpDev* D, const GQ WorkerDev
     const GQ float* x = B.hs + B.hrow(s, T);
     for (int c = threadIdx.x; c < C; c += AMP_THREADS) xs[c] = x[c];
     __syncthreads();
-    gemv_rows(Wl, t.ldw, R, C, bl, xs, part, ys);
+    gemv_rows((LDSQ float*)Wl, t.ldw, R, C, (LDSQ float*)bl, (LDSQ float*)xs, (LDSQ float*)part, (LDSQ float*)ys);
     LOG(2, 0, seq, 0);
     const int label = D->data.lab[D->data.lab_off[inst]];
     softmax_xent_wave0(ys, R, label, ds, &s_loss, &s_pred);
@@ -317,7 +317,7 @@ __device__ __noinline__ void role_rnn_out(const GQ AmpDev* D, const GQ WorkerDev
       continue;
     }
     LOG(2, 1, seq, 0);
-    gemv_cols(Wl, t.ldw, R, C, ds, part, dx);
+    gemv_cols((LDSQ float*)Wl, t.ldw, R, C, (LDSQ float*)ds, (LDSQ float*)part, (LDSQ float*)dx);
     for (int c = threadIdx.x; c < C; c += AMP_THREADS) B.dh[(long long)s * B.SP + c] = dx[c];
     tile_accumulate(nd, t, ds, xs);
     __syncthreads();
