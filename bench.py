@@ -34,8 +34,7 @@ FP32_MFMA_PEAK = 157.3e12          # whole chip, dense fp32 matrix
 # HBM bytes per launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a copy of known size (the summaries
 # under profiles/); only quoted for exactly the configuration (workload, max_active_keys, min_update_frequency,
 # instances) that was profiled.
-MEASURED_HBM_BYTES_PER_LAUNCH = {(3, 64, 50, 8544): 47.3e9, (2, 16, 16, 10000): 2.34e9, (4, 32, 20, 20000): 43.9e9,
-                                 (5, 128, 50, 8544): 2.22e12}
+MEASURED_HBM_BYTES_PER_LAUNCH = {(3, 64, 50, 8544): 47.3e9, (2, 16, 16, 10000): 2.34e9, (4, 32, 20, 20000): 43.9e9}
 
 DEFAULTS = {
     # cfg: mak, muf, lookup muf, optimizer
@@ -43,7 +42,7 @@ DEFAULTS = {
     2: dict(mak=16, muf=16, lmuf=16, opt=("sgd", dict(lr=0.05))),
     3: dict(mak=64, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.05))),
     4: dict(mak=32, muf=20, lmuf=20, opt=("adam", dict(lr=0.001))),
-    5: dict(mak=128, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.02)), tiles={1: 16, 2: 32}),
+    5: dict(mak=128, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.02)), tiles={1: 16, 2: 64}),
 }
 NAMES = {1: "mlp_64-128-128-10_1024inst", 2: "rnn_h128_len4-32_10000seq",
          3: "treelstm_h150_e300_2-60leaves_8544trees", 4: "ggnn_h100_4steps_9-29nodes_20000graphs",
@@ -149,7 +148,7 @@ def main():
     model, dims, data = synth.workload(args.config, n=args.n)
     fp = synth.init_params(model, dims, 100 + args.config)
     ml, me = runner.max_len_of(model, data)
-    tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=(12 if args.config == 5 else 4) << 30,
+    tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=(20 if args.config == 5 else 4) << 30,
                         tiles=cfg.get("tiles"))
     a = tr.amp
     a.set_min_update_frequency(-1, cfg["muf"])
@@ -218,7 +217,7 @@ def main():
     R = args.replicas if args.replicas is not None else min(64, 240 // n_workers, len(data) // (4 * cfg["mak"]))
     if R > 1:
         tr.close()
-        tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=24 << 30, tiles=cfg.get("tiles"),
+        tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=(48 if args.config == 5 else 24) << 30, tiles=cfg.get("tiles"),
                             replicas=R)
         a = tr.amp
         a.set_min_update_frequency(-1, cfg["muf"])

@@ -133,7 +133,7 @@ int amp_build_ggnn(amp_ctx *ctx, const amp_model_dims *dims);
 
 /* Splits a heavy node's rows over `n_tiles` workgroups that run in lockstep
  * (Section 5.1: a linear layer can be split into tiles computed in
- * parallel).  1..32 tiles.  Only before amp_finalize; TREE leaf / branch
+ * parallel).  1..64 tiles.  Only before amp_finalize; TREE leaf / branch
  * nodes only. */
 int amp_set_tiles(amp_ctx *ctx, int node_id, int n_tiles);
 /* Where a tiled node keeps its weights during a launch.  0 (default): in the

@@ -5,7 +5,7 @@
 #include <stdint.h>
 
 #define AMP_MAX_NODES 16
-#define AMP_MAX_WORKERS 64
+#define AMP_MAX_WORKERS 128
 #define AMP_MAX_BUFS 24
 #define AMP_THREADS 512
 #define AMP_LDS_BYTES 163840   // 160 KB per workgroup on gfx950

@@ -342,8 +342,8 @@ int amp_set_tiles(amp_ctx* c, int node_id, int n_tiles) {
   if (node_id < 0 || node_id >= (int)c->nodes.size()) return fail(c, AMP_EINVAL, "set_tiles: no node %d", node_id);
   if (c->model != AMP_MODEL_TREE || (node_id != 1 && node_id != 2))
     return fail(c, AMP_EUNSUPPORTED, "set_tiles: only the tree model's leaf and branch nodes can be tiled");
-  if (n_tiles < 1 || n_tiles > 32 || n_tiles > c->nodes[node_id].block)
-    return fail(c, AMP_EINVAL, "set_tiles: n_tiles must be in 1..min(32, hidden)");
+  if (n_tiles < 1 || n_tiles > 64 || n_tiles > c->nodes[node_id].block)
+    return fail(c, AMP_EINVAL, "set_tiles: n_tiles must be in 1..min(64, hidden)");
   c->nodes[node_id].tiles = n_tiles;
   return AMP_OK;
 }

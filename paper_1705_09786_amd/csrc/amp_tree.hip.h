@@ -592,10 +592,12 @@ __device__ __noinline__ void tree_update_from_pend(LDSQ float* Wl, LDSQ float* b
 #define TREE_XC 64        // columns per chunk
 #define TREE_XS (TREE_XC + 4)
 
-template <bool BR, int NBF>
-__device__ __forceinline__ void tree_fwd_stream_blocks(const GQ float* P, const LDSQ int* rowoff, const Tile& t,
-                                                       const LDSQ float* bl, const GQ float* xbase, const BatchMsg& M, int nF,
-                                                       LDSQ float* Y, int ldy, LDSQ float* Xs) {
+// NJ = 16-row blocks a wave owns in this pass (blocks r0 + wave, + 8, ...); a wave whose last block lies beyond the
+// tile skips that block's fetches and products.
+template <bool BR, int NBF, int NJ>
+__device__ __forceinline__ void tree_fwd_stream_pass(const GQ float* P, const LDSQ int* rowoff, const Tile& t,
+                                                     const LDSQ float* bl, const GQ float* xbase, const BatchMsg& M, int nF,
+                                                     LDSQ float* Y, int ldy, LDSQ float* Xs, int r0) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
   const int NRB = t.Rp >> 4, NCH = (t.Cl + TREE_XC - 1) / TREE_XC;
   const v4f zero = {0.f, 0.f, 0.f, 0.f};
@@ -618,11 +620,12 @@ __device__ __forceinline__ void tree_fwd_stream_blocks(const GQ float* P, const 
     const v4f v = *(const GQ v4f*)(in ? (BR && lc >= t.segp ? xp1[a] : xp0[a]) + ch * TREE_XC : xp0[a]);
     return in ? v : zero;
   };
-  for (int r0 = 0; r0 < NRB; r0 += 24) {
-    // this wave's row blocks: r0 + wave, + 8, + 16 (a block beyond the tile repeats the last one and is not stored)
-    const GQ float* wrow[3];
+  {
+    // this wave's row blocks: r0 + wave, + 8, ...; only the last can lie beyond the tile
+    const bool last_in = r0 + wave + 8 * (NJ - 1) < NRB;
+    const GQ float* wrow[NJ];
 #pragma unroll
-    for (int j = 0; j < 3; ++j) {
+    for (int j = 0; j < NJ; ++j) {
       const int rb = r0 + wave + 8 * j < NRB ? r0 + wave + 8 * j : NRB - 1;
       wrow[j] = P + rowoff[rb * 16 + i] + 4 * q;
     }
@@ -630,19 +633,19 @@ __device__ __forceinline__ void tree_fwd_stream_blocks(const GQ float* P, const 
       const int lc = ch * TREE_XC + g * 16 + 4 * q;
       return *(const GQ v4f*)(lc < t.Cl ? wrow[j] + ch * TREE_XC + g * 16 : wrow[j]);   // beyond the input: x is zero
     };
-    v4f acc[3][NBF];
+    v4f acc[NJ][NBF];
 #pragma unroll
-    for (int j = 0; j < 3; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int nb = 0; nb < NBF; ++nb) acc[j][nb] = zero;
-    v4f wa[3][4], wb[3][4], xr[NX];
+    v4f wa[NJ][4], wb[NJ][4], xr[NX];
     // prologue: chunk 0
 #pragma unroll
     for (int a = 0; a < NX; ++a) xr[a] = xfetch(0, a);
 #pragma unroll
-    for (int j = 0; j < 3; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) wa[j][g] = wfetch(0, j, g);
+      for (int g = 0; g < 4; ++g) wa[j][g] = (j < NJ - 1 || last_in) ? wfetch(0, j, g) : zero;
     lds_barrier();   // the previous pass has finished with Xs
 #pragma unroll
     for (int a = 0; a < NX; ++a) *(LDSQ v4f*)(Xs + (sm + 32 * a) * TREE_XS + sp) = xr[a];
@@ -652,9 +655,9 @@ __device__ __forceinline__ void tree_fwd_stream_blocks(const GQ float* P, const 
 #pragma unroll
       for (int a = 0; a < NX; ++a) xr[a] = xfetch(ch + 1, a);
 #pragma unroll
-      for (int j = 0; j < 3; ++j)
+      for (int j = 0; j < NJ; ++j)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) wb[j][g] = wfetch(ch + 1, j, g);
+        for (int g = 0; g < 4; ++g) wb[j][g] = (j < NJ - 1 || last_in) ? wfetch(ch + 1, j, g) : zero;
       asm volatile("" ::: "memory");   // the fetches are issued before the products below start
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -664,9 +667,15 @@ __device__ __forceinline__ void tree_fwd_stream_blocks(const GQ float* P, const 
 #pragma unroll
         for (int e = 0; e < 4; ++e)   // component-major: consecutive products go to different accumulators
 #pragma unroll
-          for (int j = 0; j < 3; ++j)
+          for (int j = 0; j < NJ - 1; ++j)
 #pragma unroll
             for (int nb = 0; nb < NBF; ++nb) acc[j][nb] = MFMA(wa[j][g][e], x[nb][e], acc[j][nb]);
+        if (last_in) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int nb = 0; nb < NBF; ++nb) acc[NJ - 1][nb] = MFMA(wa[NJ - 1][g][e], x[nb][e], acc[NJ - 1][nb]);
+        }
       }
 #pragma unroll
       for (int a = 0; a < NX; ++a) *(LDSQ v4f*)(Xs + 64 * TREE_XS + (sm + 32 * a) * TREE_XS + sp) = xr[a];
@@ -676,9 +685,9 @@ __device__ __forceinline__ void tree_fwd_stream_blocks(const GQ float* P, const 
 #pragma unroll
       for (int a = 0; a < NX; ++a) xr[a] = xfetch(ch + 2, a);
 #pragma unroll
-      for (int j = 0; j < 3; ++j)
+      for (int j = 0; j < NJ; ++j)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) wa[j][g] = wfetch(ch + 2, j, g);
+        for (int g = 0; g < 4; ++g) wa[j][g] = (j < NJ - 1 || last_in) ? wfetch(ch + 2, j, g) : zero;
       asm volatile("" ::: "memory");
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -689,16 +698,22 @@ __device__ __forceinline__ void tree_fwd_stream_blocks(const GQ float* P, const 
 #pragma unroll
         for (int e = 0; e < 4; ++e)   // component-major: consecutive products go to different accumulators
 #pragma unroll
-          for (int j = 0; j < 3; ++j)
+          for (int j = 0; j < NJ - 1; ++j)
 #pragma unroll
             for (int nb = 0; nb < NBF; ++nb) acc[j][nb] = MFMA(wb[j][g][e], x[nb][e], acc[j][nb]);
+        if (last_in) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int nb = 0; nb < NBF; ++nb) acc[NJ - 1][nb] = MFMA(wb[NJ - 1][g][e], x[nb][e], acc[NJ - 1][nb]);
+        }
       }
 #pragma unroll
       for (int a = 0; a < NX; ++a) *(LDSQ v4f*)(Xs + (sm + 32 * a) * TREE_XS + sp) = xr[a];
       lds_barrier();
     }
 #pragma unroll
-    for (int j = 0; j < 3; ++j) {
+    for (int j = 0; j < NJ; ++j) {
       const int rb = r0 + wave + 8 * j;
       if (rb < NRB) {
         const v4f b4 = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
@@ -706,6 +721,22 @@ __device__ __forceinline__ void tree_fwd_stream_blocks(const GQ float* P, const 
         for (int nb = 0; nb < NBF; ++nb) *(LDSQ v4f*)(Y + (nb * 16 + i) * ldy + rb * 16 + 4 * q) = acc[j][nb] + b4;
       }
     }
+  }
+}
+
+template <bool BR, int NBF>
+__device__ __forceinline__ void tree_fwd_stream_blocks(const GQ float* P, const LDSQ int* rowoff, const Tile& t,
+                                                       const LDSQ float* bl, const GQ float* xbase, const BatchMsg& M, int nF,
+                                                       LDSQ float* Y, int ldy, LDSQ float* Xs) {
+  const int NRB = t.Rp >> 4;
+  for (int r0 = 0; r0 < NRB; r0 += 24) {
+    const int left = NRB - r0;
+    if (left > 16)
+      tree_fwd_stream_pass<BR, NBF, 3>(P, rowoff, t, bl, xbase, M, nF, Y, ldy, Xs, r0);
+    else if (left > 8)
+      tree_fwd_stream_pass<BR, NBF, 2>(P, rowoff, t, bl, xbase, M, nF, Y, ldy, Xs, r0);
+    else
+      tree_fwd_stream_pass<BR, NBF, 1>(P, rowoff, t, bl, xbase, M, nF, Y, ldy, Xs, r0);
   }
 }
 

@@ -19,7 +19,7 @@ def _trainer(cfgi, lr=None, log=False):
     model, dims, data = synth.workload(cfgi)
     fp = synth.init_params(model, dims, 100 + cfgi)
     ml, me = runner.max_len_of(model, data)
-    tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=(12 if cfgi == 5 else 4) << 30,
+    tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=(20 if cfgi == 5 else 4) << 30,
                         tiles=cfg.get("tiles"))
     a = tr.amp
     a.set_watchdog(20.0)

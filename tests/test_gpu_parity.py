@@ -132,12 +132,12 @@ def test_tree_weights_in_hbm_replay_parity(tiles, mak, muf, opt, n):
 
 
 def test_tree_hidden_1024_replay_parity():
-    """The scale-up shape (hidden = embedding = 1024, weights streamed from HBM, leaf / branch split over 16 / 32
+    """The scale-up shape (hidden = embedding = 1024, weights streamed from HBM, leaf / branch split over 16 / 64
     workgroups as the benchmark runs it) on a handful of trees the checker can still replay."""
     dims = synth.DEFAULT_DIMS["tree_big"]
     data = synth.make_tree(6, 31, dims, min_leaves=2, max_leaves=12)
     fp = synth.init_params("tree", dims, 8)
-    g = gpu_train("tree", dims, fp, data, 4, 5, SGD, tiles={1: 16, 2: 32}, lookup_muf=9, arena_bytes=3 << 30)
+    g = gpu_train("tree", dims, fp, data, 4, 5, SGD, tiles={1: 16, 2: 64}, lookup_muf=9, arena_bytes=3 << 30)
     check_controller_log(g["logs"], 4, len(data))
     rt = oracle_replay("tree", dims, fp, data, g["logs"], 5, SGD, lookup_muf=9)
     compare(g, rt, len(data))
