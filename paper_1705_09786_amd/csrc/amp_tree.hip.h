@@ -583,7 +583,6 @@ __device__ __noinline__ void tree_update_from_pend(LDSQ float* Wl, LDSQ float* b
 // HBM / L2 as they go, and the update writes them back in place.  rowoff[lr] =
 // (node row of tile row lr) * cols, row 0 for the padding rows of the last
 // 16-row block, whose results are dropped or meet a zero delta.
-#define TREE_SG 10        // 16-column groups of input and weights held in registers at once
 
 // Y[j][r] = b[r] + sum_c W[r][c] x_j[c] as a K-chunked product: the batch's inputs go through LDS 64 columns
 // at a time (Xs, two buffers of kb rows x 68 floats, fetched once per chunk by the whole workgroup), every wave
@@ -755,61 +754,73 @@ __device__ __forceinline__ void tree_fwd_stream(const GQ float* P, const LDSQ in
     tree_fwd_stream_blocks<BR, 4>(P, rowoff, t, bl, xbase, M, nF, Y, ldy, Xs);
 }
 
-// dx_j[c] = sum_r W[r][c] delta_j[r]; a wave owns every 8th group of 16 weight columns for all NBB message
-// blocks and walks the tile's rows TREE_SG 16-row blocks at a time, fetching the next stretch of weight
-// columns (two register buffers) while the matrix cores work on the present one.
+// dx_j[c] = sum_r W[r][c] delta_j[r].  A wave owns every 8th block of 64 weight columns for all NBB message
+// blocks.  For a (16-row block, 64-column block) unit lane (i, q) fetches rows 4q .. 4q+3 of the block at columns
+// 4i .. 4i+3 -- 16 bytes per fetch, 256 contiguous bytes per row across the 16 lanes -- and component e of those
+// fetches is the weight operand of output tile e, whose 16 columns are 4m + e: one fetch feeds four products, and
+// a lane ends up with 16 consecutive columns of its message's input gradient.  The rows are walked TREE_SR blocks
+// at a time with two register buffers, the next stretch in flight while the matrix cores work on the present one.
+#define TREE_SR 4
 template <bool BR, int NBB>
 __device__ __forceinline__ void tree_bwd_stream_blocks(const GQ float* P, const LDSQ int* rowoff, const Tile& t,
                                                        const LDSQ float* Dl, int ldd, const BatchMsg& M, int nB, GQ float* obase) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
-  const int NRB = t.Rp >> 4, NCG = amp_round16(t.Cl) >> 4;
-  const int NGC = (NRB + TREE_SG - 1) / TREE_SG;                 // row stretches per column group
-  const int ncb = wave < NCG ? (NCG - wave + 7) >> 3 : 0;        // column groups of this wave
+  const int NRB = t.Rp >> 4, CM = (amp_round16(t.Cl) + 63) >> 6;
+  const int NGC = (NRB + TREE_SR - 1) / TREE_SR;                 // row stretches per column block
+  const int ncb = wave < CM ? (CM - wave + 7) >> 3 : 0;           // column blocks of this wave
   const int T = ncb * NGC;
   const v4f zero = {0.f, 0.f, 0.f, 0.f};
   const LDSQ float* dp = Dl + i * ldd + 4 * q;
-  auto afetch = [&](int it, float (&a)[TREE_SG][4]) {
-    const int cb = wave + 8 * (it / NGC), g0 = (it % NGC) * TREE_SG;
-    const int col = cb * 16 + i < t.Cl ? cb * 16 + i : 0;
+  auto afetch = [&](int it, v4f (&a)[TREE_SR][4]) {
+    const int cb = wave + 8 * (it / NGC), g0 = (it % NGC) * TREE_SR;
+    const int col = cb * 64 + 4 * i < t.Cl ? cb * 64 + 4 * i : 0;
 #pragma unroll
-    for (int g = 0; g < TREE_SG; ++g) {
+    for (int g = 0; g < TREE_SR; ++g) {
       const int gg = g0 + g < NRB ? g0 + g : NRB - 1;
 #pragma unroll
-      for (int v = 0; v < 4; ++v) a[g][v] = P[rowoff[gg * 16 + 4 * q + v] + col];
+      for (int sx = 0; sx < 4; ++sx) a[g][sx] = *(const GQ v4f*)(P + rowoff[gg * 16 + 4 * q + sx] + col);
     }
   };
-  v4f acc[NBB][2];
+  v4f acc[NBB][4];
 #pragma unroll
-  for (int nb = 0; nb < NBB; ++nb) acc[nb][0] = acc[nb][1] = zero;
-  auto work = [&](int it, float (&a)[TREE_SG][4]) {
-    const int cb = wave + 8 * (it / NGC), gc = it % NGC, g0 = gc * TREE_SG;
+  for (int nb = 0; nb < NBB; ++nb)
 #pragma unroll
-    for (int g = 0; g < TREE_SG; ++g)
+    for (int e = 0; e < 4; ++e) acc[nb][e] = zero;
+  auto work = [&](int it, v4f (&a)[TREE_SR][4]) {
+    const int cb = wave + 8 * (it / NGC), gc = it % NGC, g0 = gc * TREE_SR;
+#pragma unroll
+    for (int g = 0; g < TREE_SR; ++g)
       if (g0 + g < NRB) {
 #pragma unroll
         for (int nb = 0; nb < NBB; ++nb) {
           const v4f d = *(const LDSQ v4f*)(dp + nb * 16 * ldd + 16 * (g0 + g));
-          acc[nb][0] = MFMA(a[g][0], d.x, acc[nb][0]);
-          acc[nb][1] = MFMA(a[g][1], d.y, acc[nb][1]);
-          acc[nb][0] = MFMA(a[g][2], d.z, acc[nb][0]);
-          acc[nb][1] = MFMA(a[g][3], d.w, acc[nb][1]);
+#pragma unroll
+          for (int sx = 0; sx < 4; ++sx)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[nb][e] = MFMA(a[g][sx][e], d[sx], acc[nb][e]);
         }
       }
     if (gc == NGC - 1) {
-      const int lc = cb * 16 + 4 * q;
 #pragma unroll
       for (int nb = 0; nb < NBB; ++nb) {
         const int mi = nb * 16 + i;
-        if (mi < nB && lc < t.Cl) {
+        if (mi < nB) {
           const int m = M.bidx[mi];
-          GQ float* o = (BR && lc >= t.segp) ? obase + M.dst1[m] + (lc - t.segp) : obase + M.dst0[m] + lc;
-          *(GQ v4f*)o = acc[nb][0] + acc[nb][1];
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int lc = cb * 64 + 16 * q + 4 * v;
+            if (lc < t.Cl) {
+              GQ float* o = (BR && lc >= t.segp) ? obase + M.dst1[m] + (lc - t.segp) : obase + M.dst0[m] + lc;
+              *(GQ v4f*)o = (v4f){acc[nb][0][v], acc[nb][1][v], acc[nb][2][v], acc[nb][3][v]};
+            }
+          }
         }
-        acc[nb][0] = acc[nb][1] = zero;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[nb][e] = zero;
       }
     }
   };
-  float a0[TREE_SG][4], a1[TREE_SG][4];
+  v4f a0[TREE_SR][4], a1[TREE_SR][4];
   if (T > 0) afetch(0, a0);
   for (int it = 0; it < T; it += 2) {
     if (it + 1 < T) afetch(it + 1, a1);
