@@ -1090,6 +1090,13 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
           const GQ float* gp = B.gpar + nn * B.TB * Hp + u;
           float p = 0.f;
           int q = 0;
+          for (; q + 15 < B.TB; q += 16) {   // sixteen parts in flight at a time, added in tile order
+            float pp[16];
+#pragma unroll
+            for (int a = 0; a < 16; ++a) pp[a] = gp[(q + a) * Hp];
+#pragma unroll
+            for (int a = 0; a < 16; ++a) p += pp[a];
+          }
           for (; q + 3 < B.TB; q += 4) {
             const float p0 = gp[q * Hp], p1 = gp[(q + 1) * Hp], p2 = gp[(q + 2) * Hp], p3 = gp[(q + 3) * Hp];
             p = (((p + p0) + p1) + p2) + p3;
