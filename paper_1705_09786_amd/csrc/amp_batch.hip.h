@@ -34,15 +34,16 @@ __shared__ BatchMsg s_M;
 __shared__ unsigned s_codes[KB_MAX];
 __shared__ int s_n;
 
-// Wave 0 looks at up to kmax consecutive ring entries at once and takes the
-// leading run that is ready, cut so that at most `room` backward messages
-// (those for which is_b(code) holds) are in it.  Returns the batch size, 0
-// when the run is over.  s_codes / s_n are LDS.
+// One whole wave (any one) looks at up to kmax consecutive ring entries at once
+// and takes the leading run that is ready, cut so that at most `room` backward
+// messages (those for which is_b(code) holds) are in it.  Leaves the codes in
+// s_codes and the batch size in *s_n (0 when the run is over) and returns it;
+// no barrier.  s_codes / s_n are LDS.
 template <class R, class IsB>
-__device__ __forceinline__ int wait_batch(const GQ AmpDev* D, const R& r, unsigned& head, int kmax, int room, unsigned* s_codes,
-                          int* s_n, IsB is_b) {
-  if (threadIdx.x < 64) {
-    const int lane = threadIdx.x;
+__device__ __forceinline__ int poll_batch(const GQ AmpDev* D, const R& r, unsigned head, int kmax, int room, unsigned* s_codes,
+                                          int* s_n, IsB is_b) {
+  {
+    const int lane = threadIdx.x & 63;
     const unsigned ticket = head + lane;
     GQ unsigned long long* slot = (GQ unsigned long long*)&r.ent[ticket & r.mask];
     const long long t0 = wall_clock64();
@@ -102,6 +103,14 @@ __device__ __forceinline__ int wait_batch(const GQ AmpDev* D, const R& r, unsign
       s_stat[3] = now;
     }
   }
+  return *s_n;
+}
+
+// The same by wave 0 for the whole workgroup: ends with a barrier and advances head.
+template <class R, class IsB>
+__device__ __forceinline__ int wait_batch(const GQ AmpDev* D, const R& r, unsigned& head, int kmax, int room, unsigned* s_codes,
+                                          int* s_n, IsB is_b) {
+  if (threadIdx.x < 64) poll_batch(D, r, head, kmax, room, s_codes, s_n, is_b);
   lds_barrier();
   const int n = *s_n;
   head += n;

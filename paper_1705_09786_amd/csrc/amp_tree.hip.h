@@ -101,11 +101,11 @@ __device__ __forceinline__ v4i tree_node(const GQ int* tnode, int noff, int n) {
   return *(const GQ v4i*)(tnode + 4 * (long long)(noff + n));
 }
 
-// Wave 0, all 64 lanes, after lanes k < n have written M.aux[k]: positions of
-// the batch's forward and backward messages, and the event record (tile 0 only).
+// One wave, all 64 lanes (k = lane), after lanes k < n have written M.aux[k]: positions
+// of the batch's forward and backward messages, and the event record (tile 0 only).
 __device__ __forceinline__ void batch_split_and_log(const GQ AmpDev* D, const WorkerRegs& W, BatchMsg& M, int n, int node,
                                                     bool both_kinds) {
-  const int k = threadIdx.x;   // < 64
+  const int k = threadIdx.x & 63;
   const bool in = k < n, isb = in && M.aux[k] != 0;
   const unsigned long long mb = __ballot(isb), mf = __ballot(in && !isb);
   const unsigned long long lt = (1ull << k) - 1ull;
@@ -980,11 +980,13 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
   GQ float* obase = BR ? B.gpar : B.gx;
   unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
-  for (;;) {
-    const int n = wait_batch(D, mine, head, KB, nd_muf - (int)count, s_codes, &s_n, code_is_b);
-    if (n == 0) break;
-    if (threadIdx.x < 64) {
-      const int k = threadIdx.x;
+  // Wave 1 takes the next batch from the ring and decodes it while wave 0 is still publishing the present one
+  // (wave 0 keeps what its joins need in registers, so the batch's LDS record is free from the publish barrier on).
+  const int wave = threadIdx.x >> 6;
+  auto take_batch = [&](int room) {
+    const int n = poll_batch(D, mine, head, KB, room, s_codes, &s_n, code_is_b);
+    if (n > 0) {
+      const int k = threadIdx.x & 63;
       if (k < n) {
         const unsigned code = s_codes[k];
         const int s = MSG_SLOT(code), nn = MSG_LOCAL(code);
@@ -1010,7 +1012,13 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
       }
       batch_split_and_log(D, wr, M, n, wr.node, false);
     }
-    lds_barrier();
+  };
+  if (wave == 1) take_batch(nd_muf - (int)count);
+  lds_barrier();
+  for (;;) {
+    const int n = s_n;
+    if (n == 0) break;
+    head += n;
     const int nF = M.nF, nB = M.nB;
     PHASE(0);
     // ---------------- forward messages of the batch
@@ -1155,21 +1163,31 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
         tree_bwd_mfma<BR, NRBT, NCGT>(Wl, t, Y, M, nB, obase);
       PHASE(5);
     }
+    // what lane k of wave 0 needs of message k for its joins, before the batch's record is given up
+    int js = 0, jn = 0, jaux = 0, jpar = 0, ja = 0, jb = 0, jL = 0;
+    if (threadIdx.x < 64 && (int)threadIdx.x < n) {
+      const int k = threadIdx.x;
+      js = M.s[k];
+      jn = M.n[k];
+      jaux = M.aux[k];
+      jpar = M.par[k];
+      ja = M.a[k];
+      jb = M.b[k];
+      jL = M.L[k];
+    }
     // every wave's HBM stores have landed before wave 0 publishes the batch
     __syncthreads();
     // ---------------- joins and posts, one lane per message
     if (threadIdx.x < 64) {
       fence_release();
-      const int k = threadIdx.x;
-      if (k < n) {
-        const int s = M.s[k], nn = M.n[k];
-        if (!M.aux[k]) {
-          tree_node_part_done(wr, B, s, nn, M.par[k]);
+      if ((int)threadIdx.x < n) {
+        if (!jaux) {
+          tree_node_part_done(wr, B, js, jn, jpar);
         } else if (BR) {
-          tree_grad_part_done(wr, B, s, M.a[k], false, M.a[k] < M.L[k]);
-          tree_grad_part_done(wr, B, s, M.b[k], false, M.b[k] < M.L[k]);
+          tree_grad_part_done(wr, B, js, ja, false, ja < jL);
+          tree_grad_part_done(wr, B, js, jb, false, jb < jL);
         } else {
-          if (join_arrive(B.cnt + B.node(s, nn) * 4 + 3, B.TL)) ring_post(wr.lookup, MSG_MAKE(1, s, nn));
+          if (join_arrive(B.cnt + B.node(js, jn) * 4 + 3, B.TL)) ring_post(wr.lookup, MSG_MAKE(1, js, jn));
         }
       }
     }
@@ -1184,8 +1202,10 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
         tree_update_from_pend<NRBT, NCGT>(Wl, bl, &nd, t, pend, count, count, tstep, rowmap, colmap, accb);
       accb = 0.f;
       count = 0;
-      LOG(W->node, 2, 0, 0);
+      // recorded by the wave that records the next batch's events, so that the update comes first
+      if (threadIdx.x == 64) log_event(D, W, &s_logn, wr.node, 2, 0, 0);
     }
+    if (wave == 1) take_batch(nd_muf - (int)count);
     lds_barrier();
     PHASE(7);
   }
