@@ -117,43 +117,47 @@ __device__ __forceinline__ Ring ring_regs(const GQ AmpDev* D, int idx) {
   return r;
 }
 
-// Whole workgroup.  Waits for the entry with ticket `head` of ring r; returns
-// false when the run is over (done flag, abort flag, or this wait exceeded
-// the watchdog, which raises the abort flag so that every workgroup leaves).
+// ONE thread.  Waits for the entry with ticket `head` of ring r and leaves its code in s_ctl[0] and a stop flag
+// in s_ctl[1] (run over: done flag, abort flag, or this wait exceeded the watchdog, which raises the abort flag so
+// that every workgroup leaves).  No barrier.
+template <class R>
+__device__ __forceinline__ void poll_msg(const GQ AmpDev* D, const R& r, unsigned head, unsigned* s_ctl) {
+  const unsigned want = head + 1u;
+  GQ unsigned long long* slot = (GQ unsigned long long*)&r.ent[head & r.mask];
+  const long long t0 = wall_clock64();
+  unsigned stop = 0, spins = 0;
+  unsigned long long e;
+  for (;;) {
+    e = __hip_atomic_load(slot, __ATOMIC_RELAXED, AGENT);
+    if ((unsigned)(e >> 32) == want) break;
+    if ((++spins & 7u) == 0u) {
+      if (ld_u32(&D->ctl[0]) | ld_u32(&D->ctl[1])) {
+        // done is only raised once nothing is in flight; re-check the slot once
+        e = __hip_atomic_load(slot, __ATOMIC_RELAXED, AGENT);
+        if ((unsigned)(e >> 32) == want && ld_u32(&D->ctl[0]) == 0u) break;
+        stop = 1;
+        break;
+      }
+      if (wall_clock64() - t0 > D->watchdog_ticks) {
+        raise_abort(D, ABORT_WATCHDOG, blockIdx.x);
+        stop = 1;
+        break;
+      }
+    }
+    __builtin_amdgcn_s_sleep(1);
+  }
+  if (!stop) fence_acquire();
+  s_stat[0] += (unsigned long long)(wall_clock64() - t0);
+  s_stat[1] += 1ull - stop;
+  s_ctl[0] = (unsigned)e;
+  s_ctl[1] = stop;
+}
+
+// Whole workgroup: thread 0 polls, everybody gets the code; returns false when the run is over.
 // s_ctl: two words of LDS.
 template <class R>
 __device__ __forceinline__ bool wait_msg(const GQ AmpDev* D, const R& r, unsigned& head, unsigned* s_ctl, unsigned& code) {
-  if (threadIdx.x == 0) {
-    const unsigned want = head + 1u;
-    GQ unsigned long long* slot = (GQ unsigned long long*)&r.ent[head & r.mask];
-    const long long t0 = wall_clock64();
-    unsigned stop = 0, spins = 0;
-    unsigned long long e;
-    for (;;) {
-      e = __hip_atomic_load(slot, __ATOMIC_RELAXED, AGENT);
-      if ((unsigned)(e >> 32) == want) break;
-      if ((++spins & 7u) == 0u) {
-        if (ld_u32(&D->ctl[0]) | ld_u32(&D->ctl[1])) {
-          // done is only raised once nothing is in flight; re-check the slot once
-          e = __hip_atomic_load(slot, __ATOMIC_RELAXED, AGENT);
-          if ((unsigned)(e >> 32) == want && ld_u32(&D->ctl[0]) == 0u) break;
-          stop = 1;
-          break;
-        }
-        if (wall_clock64() - t0 > D->watchdog_ticks) {
-          raise_abort(D, ABORT_WATCHDOG, blockIdx.x);
-          stop = 1;
-          break;
-        }
-      }
-      __builtin_amdgcn_s_sleep(1);
-    }
-    if (!stop) fence_acquire();
-    s_stat[0] += (unsigned long long)(wall_clock64() - t0);
-    s_stat[1] += 1ull - stop;
-    s_ctl[0] = (unsigned)e;
-    s_ctl[1] = stop;
-  }
+  if (threadIdx.x == 0) poll_msg(D, r, head, s_ctl);
   __syncthreads();
   // the same for every lane: kept in scalar registers, and so is everything derived from it
   code = uni(s_ctl[0]);

@@ -371,9 +371,15 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
   float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
   __syncthreads();
   const Ring mine = ring_regs(D, uni(W->ring));
-  unsigned head = 0, code;
+  unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
-  while (wait_msg(D, mine, head, s_ctl, code)) {
+  // Thread 64 (wave 1) waits for the next message while wave 0 publishes the present one.
+  if (threadIdx.x == 64) poll_msg(D, mine, head, s_ctl);
+  lds_barrier();
+  for (;;) {
+    const unsigned code = uni(s_ctl[0]);
+    if (uni(s_ctl[1]) != 0u) break;
+    head++;
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
     const unsigned seq = uni(gd.slot_seq[s]);
     const GView v = g_view(gd, seq);
@@ -418,8 +424,7 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
           ring_post(rg.gr, MSG_MAKE(0, s, it));
         }
       }
-      continue;
-    }
+    } else {
     // ---- backward: delta_e = dA[dst(e)] (Bcast backward on A: (update + reset) + candidate); one gradient for the group
     {
       const long long NH = (long long)B.N * H;
@@ -488,6 +493,8 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
       }
     }
     g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
+    }
+    if (threadIdx.x == 64) poll_msg(D, mine, head, s_ctl);
     lds_barrier();
   }
   tile_store(nd, t, g.Wg, g.bg);
@@ -524,9 +531,15 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
   float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
   __syncthreads();
   const Ring mine = ring_regs(D, uni(W->ring));
-  unsigned head = 0, code;
+  unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
-  while (wait_msg(D, mine, head, s_ctl, code)) {
+  // Thread 64 (wave 1) waits for the next message while wave 0 publishes the present one.
+  if (threadIdx.x == 64) poll_msg(D, mine, head, s_ctl);
+  lds_barrier();
+  for (;;) {
+    const unsigned code = uni(s_ctl[0]);
+    if (uni(s_ctl[1]) != 0u) break;
+    head++;
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
     const unsigned seq = uni(gd.slot_seq[s]);
     const GView v = g_view(gd, seq);
@@ -579,8 +592,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
         fence_release();
         if (join_arrive(B.cnt + s * 8 + 1, 2)) ring_post(rg.gh, MSG_MAKE(0, s, it));
       }
-      continue;
-    }
+    } else {
     const GQ float* dpre = (which == 0 ? B.dZ : B.dR) + B.sl(s);
     if (vec) {
       const int GY = Hs >> 2;   // 16-byte groups of a delta row, padding included
@@ -638,6 +650,8 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       if (__shfl(go, 0)) g_post_edges(rg, g_present_types(v, B.T), s, it, true);
     }
     g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
+    }
+    if (threadIdx.x == 64) poll_msg(D, mine, head, s_ctl);
     lds_barrier();
   }
   tile_store(nd, t, g.Wg, g.bg);
@@ -675,9 +689,15 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
   float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
   __syncthreads();
   const Ring mine = ring_regs(D, uni(W->ring));
-  unsigned head = 0, code;
+  unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
-  while (wait_msg(D, mine, head, s_ctl, code)) {
+  // Thread 64 (wave 1) waits for the next message while wave 0 publishes the present one.
+  if (threadIdx.x == 64) poll_msg(D, mine, head, s_ctl);
+  lds_barrier();
+  for (;;) {
+    const unsigned code = uni(s_ctl[0]);
+    if (uni(s_ctl[1]) != 0u) break;
+    head++;
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
     const unsigned seq = uni(gd.slot_seq[s]);
     const GView v = g_view(gd, seq);
@@ -734,8 +754,7 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
           ring_post(rg.ro, MSG_MAKE(0, s, 0));
       }
       PHASE(3);
-      continue;
-    }
+    } else {
     // backward through blend, tanh, the candidate linear and r*h
     {
       const GQ float* gH = B.gH + B.sl(s);
@@ -803,8 +822,9 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
       ring_post(rg.gr, MSG_MAKE(1, s, it));
     }
     g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
+    }
+    if (threadIdx.x == 64) poll_msg(D, mine, head, s_ctl);
     lds_barrier();
-    PHASE(7);
   }
   tile_store(nd, t, g.Wg, g.bg);
   if ((int)threadIdx.x < t.R) ndG[(long long)nd.rows * t.C + threadIdx.x] = gb;
