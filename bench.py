@@ -117,7 +117,7 @@ def main():
     ap.add_argument("--n", type=int, default=None, help="instances (default: the config's full set)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--replicas", type=int, default=None,
-                    help="replicas for the extra 'replicated' measurement (default: as many as fit 240 workgroups; 1 = skip)")
+                    help="replicas for the extra 'replicated' measurement (default: as many whole replicas as fit each 32-CU XCD; 1 = skip)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run one device-to-device copy of this many MiB (the kernel of "
                          "known traffic that rocprofv3's FETCH_SIZE / WRITE_SIZE readings are scaled by)")
@@ -215,7 +215,8 @@ def main():
     # Beside the headline (one copy of the model, as the configuration names it): the paper's own way to use more
     # of the machine -- every parameterized node replicated, instances dealt round-robin to the replicas, parameters
     # averaged at the end of each epoch (Section 5).  A different training procedure, so reported apart from `value`.
-    R = args.replicas if args.replicas is not None else min(64, 240 // n_workers, len(data) // (4 * cfg["mak"]))
+    fit = 8 * (32 // n_workers) if n_workers <= 32 else 240 // n_workers   # whole replicas per 32-CU XCD
+    R = args.replicas if args.replicas is not None else min(64, fit, len(data) // (4 * cfg["mak"]))
     if R > 1:
         tr.close()
         tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=(48 if args.config == 5 else 24) << 30, tiles=cfg.get("tiles"),

@@ -547,6 +547,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
     GQ float* A = B.A + B.st(s, it);
     const GQ float* h = B.Hm + B.hm(s, it);
     GQ float* outp = (which == 0 ? B.Z : B.Rr) + B.st(s, it);
+    PHASE(0);
     if (!(code & MSG_DIR_B)) {
       // Ungroup, regroup by target node, sum: a_v = sum over incoming edges in edge order
       const GQ float* msg = B.Msg + (long long)s * B.Em * H;
@@ -578,7 +579,9 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
         X[i] = x;
       }
       lds_barrier();
+      PHASE(1);
       mfma_rows<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, g.bl, X, Cs, NB, Y, Hs);
+      PHASE(2);
       if (vec) {
         for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
           const int k = idx / G1, c = (idx - k * G1) << 2;
@@ -592,6 +595,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
         fence_release();
         if (join_arrive(B.cnt + s * 8 + 1, 2)) ring_post(rg.gh, MSG_MAKE(0, s, it));
       }
+      PHASE(3);
     } else {
     const GQ float* dpre = (which == 0 ? B.dZ : B.dR) + B.sl(s);
     if (vec) {
@@ -621,10 +625,13 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       }
     }
     lds_barrier();
+    PHASE(4);
     LOG(W->node, 1, seq, it);
     g_pend_append(pend, pd.Rp, pd.stride, nrows, Y, Hs, H, X, Cs, C, K, gb);
     lds_barrier();
+    PHASE(5);
     mfma_cols<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Cs);
+    PHASE(6);
     GQ float* dA = B.dA + ((long long)s * 3 + 1 + which) * B.N * H;
     GQ float* dHp = B.dHp + ((long long)s * 3 + 1 + which) * B.N * H;
     if (vec) {
@@ -650,6 +657,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       if (__shfl(go, 0)) g_post_edges(rg, g_present_types(v, B.T), s, it, true);
     }
     g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
+    PHASE(7);
     }
     if (threadIdx.x == 64) poll_msg(D, mine, head, s_ctl);
     lds_barrier();

@@ -287,9 +287,22 @@ __device__ __noinline__ void role_mlp_lin(const GQ AmpDev* D, const GQ WorkerDev
 #include "amp_ggnn.hip.h"
 
 // ============================================================ entry
-extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const AmpDev* Dp, int workers_per_replica) {
-  // replica r = blocks [r * workers_per_replica, (r + 1) * workers_per_replica), each with its own descriptor
-  const int replica = blockIdx.x / workers_per_replica, wi = blockIdx.x - replica * workers_per_replica;
+extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const AmpDev* Dp, int workers_per_replica,
+                                                                         int n_replicas, int xcd_packed) {
+  // Every replica has its own descriptor.  Plain mapping: replica r = blocks [r * workers_per_replica, (r + 1) *
+  // workers_per_replica).  Packed mapping: workgroups are dealt to the 8 XCDs round-robin by their index, so block
+  // b lands on XCD b % 8; all workers of a replica take blocks of one residue, replicas x, x + 8, ... share XCD x,
+  // and a replica's rings, stash and joins stay in one L2.  Blocks without a worker leave at once.
+  int replica, wi;
+  if (xcd_packed) {
+    const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
+    replica = x + 8 * (j / workers_per_replica);
+    wi = j % workers_per_replica;
+    if (replica >= n_replicas) return;
+  } else {
+    replica = blockIdx.x / workers_per_replica;
+    wi = blockIdx.x - replica * workers_per_replica;
+  }
   const GQ AmpDev* D = (const GQ AmpDev*)Dp + replica;
   const GQ WorkerDev* W = &D->worker[wi];
   long long t_begin = 0;
@@ -364,8 +377,15 @@ extern "C" hipError_t amp_launch(const AmpDev* devs, int n_replicas, int workers
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(amp_persistent, dim3(n_replicas * workers_per_replica), dim3(AMP_THREADS), AMP_DYN_LDS_BYTES, stream, devs,
-                     workers_per_replica);
+  // One XCD has 32 CUs: the packed mapping needs the replicas that share an XCD to fit it.  Measured: replicas
+  // gain from staying inside one L2 (15 Tree-LSTM replicas 184k -> 256k trees/s); a single pipeline of many
+  // workers is faster spread over all eight L2s (16 workers 28.5k against 25.5k packed), one of few workers
+  // faster packed (the 4-worker MLP 52k -> 55k instances/s).
+  const int per_xcd = (n_replicas + 7) / 8;
+  const bool packed = per_xcd * workers_per_replica <= 32 && (n_replicas > 1 || workers_per_replica <= 8);
+  const int grid = packed ? 8 * per_xcd * workers_per_replica : n_replicas * workers_per_replica;
+  hipLaunchKernelGGL(amp_persistent, dim3(grid), dim3(AMP_THREADS), AMP_DYN_LDS_BYTES, stream, devs, workers_per_replica,
+                     n_replicas, packed ? 1 : 0);
   return hipGetLastError();
 }
 
