@@ -53,9 +53,18 @@ struct InstSet {
   std::vector<int> tok_off{0}, tok, lab_off{0}, lab, node_off{0}, left, right, parent, edge_off{0}, src, dst, etype, tcount;
   std::vector<int> tnode;   // tree: left, right, parent code, label per node
   std::vector<int> inoff, inedge, tstart, tedge, tsoff, tsk;   // graph adjacency (see DataDev)
-  bool dirty = true;
+  bool dirty = true;   // host copy newer than what the arena holds
   size_t n() const { return keys.size(); }
   void clear() { *this = InstSet(); }
+};
+
+// An instance set as it lies in the arena, dealt to R replicas: kept from call to call until the set changes.
+struct Resident {
+  bool valid = false;
+  int R = 0;
+  size_t begin = 0, end = 0;
+  std::vector<DataDev> dd;   // per replica
+  std::vector<size_t> n;     // instances per replica
 };
 
 }  // namespace
@@ -73,10 +82,12 @@ struct amp_ctx {
   size_t max_instances = 0, log_cap = 0;
   double watchdog_s = 20.0;
   InstSet sets[2];
+  Resident resident[2];
   // arena layout
   size_t static_end = 0;   // everything below is laid out at finalize
   size_t off_dev = 0, off_ctl = 0, off_slot_seq = 0, off_clock = 0, off_smeta = 0;
   std::vector<size_t> off_ring_ent, off_ring_tail;
+  size_t sync_end = 0;   // [0, sync_end) of a replica's region: stop word, clock, slot tables, rings -- zero at every launch
   unsigned ring_cap = 0;
   size_t off_buf[AMP_MAX_BUFS] = {0};
   size_t buf_bytes[AMP_MAX_BUFS] = {0};
@@ -473,6 +484,7 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     c->off_ring_ent[r] = take(8 * (size_t)c->ring_cap);
     c->off_ring_tail[r] = take(64);
   }
+  c->sync_end = off;
   for (HostNode& n : c->nodes) {
     const size_t b = n.count() * 4;
     n.off_P = take(b);
@@ -886,13 +898,39 @@ int upload_set(amp_ctx* c, size_t& off, const InstSet& S, DataDev& dd) {
 // Everything replica r owns in the static part of the arena lies rep_stride bytes after replica r - 1's.
 char* rep_ptr(const amp_ctx* c, int r, size_t off) { return c->arena + (size_t)r * c->rep_stride + off; }
 
+// Puts set S into the arena at `begin`, dealt to R replicas: replica r gets instances r, r + R, r + 2R, ...
+int make_resident(amp_ctx* c, const InstSet& S, int R, size_t begin, Resident& res) {
+  res.valid = false;
+  res.R = R;
+  res.begin = begin;
+  res.dd.assign(R, DataDev());
+  res.n.assign(R, 0);
+  size_t off = begin;
+  if (R == 1) {
+    if (int rc = upload_set(c, off, S, res.dd[0])) return rc;
+    res.n[0] = S.n();
+  } else {
+    std::vector<InstSet> parts(R);
+    for (size_t i = 0; i < S.n(); ++i) append_instance(c, parts[i % R], S, i);
+    for (int r = 0; r < R; ++r) {
+      if (int rc = upload_set(c, off, parts[r], res.dd[r])) return rc;
+      res.n[r] = parts[r].n();
+    }
+    // the copies above read pageable host memory: they have left `parts` before it goes away
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+  }
+  res.end = off;
+  res.valid = true;
+  return AMP_OK;
+}
+
 // One launch: every replica trains (or evaluates) `epochs` passes over its own instance set.
-// losses / correct: per replica, per admission of this launch.
-int launch_once(amp_ctx* c, const std::vector<const InstSet*>& sets, int epochs, bool train,
+// losses / correct: per replica, per admission of this launch.  Launch outputs lie from `out_begin` on.
+int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, bool train,
                 std::vector<std::vector<float>>& losses, std::vector<std::vector<int>>& correct, double& seconds) {
-  const int R = (int)sets.size();
+  const int R = res.R;
   const size_t wpr = c->workers.size();
-  size_t off = c->static_end;
+  size_t off = out_begin;
   auto take = [&](size_t bytes) -> size_t {
     size_t o = off;
     off = align_up(off + bytes);
@@ -903,29 +941,34 @@ int launch_once(amp_ctx* c, const std::vector<const InstSet*>& sets, int epochs,
   std::vector<std::vector<size_t>> off_log(R, std::vector<size_t>(wpr)), off_logn(R, std::vector<size_t>(wpr));
   const size_t log_cap = train ? c->log_cap : 0;
   const size_t off_devs = take(sizeof(AmpDev) * R);
+  // what the host reads after every launch lies together: one copy brings it back
+  const size_t res_begin = off;
+  for (int r = 0; r < R; ++r) {
+    n_total[r] = res.n[r] * (size_t)epochs;
+    off_loss[r] = take(n_total[r] * 4);
+    off_correct[r] = take(n_total[r] * 4);
+    off_stats[r] = take(8 * NSTAT * wpr);
+  }
+  const size_t res_end = off;
+  for (int r = 0; r < R; ++r) {
+    off_yhat[r] = take(n_total[r] * 4);
+    for (size_t w = 0; w < wpr; ++w) off_logn[r][w] = take(64);
+  }
+  const size_t zero_end = off;
+  for (int r = 0; r < R; ++r)
+    for (size_t w = 0; w < wpr; ++w) off_log[r][w] = take(8 * std::max<size_t>(log_cap, 1));
+  if (off > c->arena_bytes) return fail(c, AMP_ENOMEM, "arena of %zu bytes is too small, %zu needed", c->arena_bytes, off);
+  HIPCHK(c, hipMemsetAsync(c->arena + res_begin, 0, zero_end - res_begin, c->stream));
   for (int r = 0; r < R; ++r) {
     AmpDev& D = Ds[r];
     std::memset(&D, 0, sizeof D);
-    if (int rc = upload_set(c, off, *sets[r], D.data)) return rc;
-    n_total[r] = sets[r]->n() * (size_t)epochs;
-    const size_t zero_from = off;
-    off_loss[r] = take(n_total[r] * 4);
-    off_correct[r] = take(n_total[r] * 4);
-    off_yhat[r] = take(n_total[r] * 4);
-    for (size_t w = 0; w < wpr; ++w) {
-      off_log[r][w] = take(8 * std::max<size_t>(log_cap, 1));
-      off_logn[r][w] = take(64);
-    }
-    off_stats[r] = take(8 * NSTAT * wpr);
-    if (off > c->arena_bytes) return fail(c, AMP_ENOMEM, "arena of %zu bytes is too small, %zu needed", c->arena_bytes, off);
-    HIPCHK(c, hipMemsetAsync(c->arena + zero_from, 0, off - zero_from, c->stream));
-
+    D.data = res.dd[r];
+    // stop word, clock, slot tables and every ring of this replica
+    HIPCHK(c, hipMemsetAsync(rep_ptr(c, r, 0), 0, c->sync_end, c->stream));
     for (size_t i = 0; i < c->off_ring_ent.size(); ++i) {
       D.ring[i].ent = (unsigned long long*)rep_ptr(c, r, c->off_ring_ent[i]);
       D.ring[i].tail = (unsigned*)rep_ptr(c, r, c->off_ring_tail[i]);
       D.ring[i].mask = c->ring_cap - 1;
-      HIPCHK(c, hipMemsetAsync(D.ring[i].ent, 0, 8 * (size_t)c->ring_cap, c->stream));
-      HIPCHK(c, hipMemsetAsync(D.ring[i].tail, 0, 64, c->stream));
     }
     for (size_t i = 0; i < c->nodes.size(); ++i) {
       const HostNode& n = c->nodes[i];
@@ -1003,8 +1046,6 @@ int launch_once(amp_ctx* c, const std::vector<const InstSet*>& sets, int epochs,
       D.buf[i] = c->buf_bytes[i] ? rep_ptr(c, r, c->off_buf[i]) : nullptr;
       D.stride[i] = c->buf_stride[i];
     }
-    HIPCHK(c, hipMemsetAsync(D.ctl, 0, 64, c->stream));
-    HIPCHK(c, hipMemsetAsync(D.clock, 0, 64, c->stream));
   }
   HIPCHK(c, hipMemcpyAsync(c->arena + off_devs, Ds.data(), sizeof(AmpDev) * R, hipMemcpyHostToDevice, c->stream));
   HIPCHK(c, hipStreamSynchronize(c->stream));
@@ -1022,26 +1063,28 @@ int launch_once(amp_ctx* c, const std::vector<const InstSet*>& sets, int epochs,
   (void)hipEventDestroy(e1);
   seconds += ms * 1e-3;
 
-  for (int r = 0; r < R; ++r) {
-    unsigned ctl[4] = {0, 0, 0, 0};
-    HIPCHK(c, hipMemcpy(ctl, Ds[r].ctl, sizeof ctl, hipMemcpyDeviceToHost));
-    if (ctl[0]) {
-      const char* why = ctl[0] == ABORT_WATCHDOG ? "a worker waited longer than the watchdog allows"
-                        : ctl[0] == ABORT_LOG_FULL ? "event record full"
-                                                   : "inconsistent state";
+  std::vector<unsigned> ctl(4 * (size_t)R);
+  HIPCHK(c, hipMemcpy2D(ctl.data(), 16, rep_ptr(c, 0, c->off_ctl), c->rep_stride, 16, R, hipMemcpyDeviceToHost));
+  for (int r = 0; r < R; ++r)
+    if (ctl[4 * r]) {
+      const unsigned why_code = ctl[4 * r];
+      const char* why = why_code == ABORT_WATCHDOG ? "a worker waited longer than the watchdog allows"
+                        : why_code == ABORT_LOG_FULL ? "event record full"
+                                                     : "inconsistent state";
       c->state_zeroed = false;   // device state is unreliable after an aborted run
       for (HostNode& n : c->nodes) n.dirty = true;
-      return fail(c, AMP_EDEVICE, "kernel stopped itself: %s (replica %d, worker %u)", why, r, ctl[2]);
+      return fail(c, AMP_EDEVICE, "kernel stopped itself: %s (replica %d, worker %u)", why, r, ctl[4 * r + 2]);
     }
-  }
+  std::vector<char> back(res_end - res_begin);
+  HIPCHK(c, hipMemcpy(back.data(), c->arena + res_begin, back.size(), hipMemcpyDeviceToHost));
   c->last_stats.assign(NSTAT * wpr * R, 0);
   for (int r = 0; r < R; ++r) {
-    HIPCHK(c, hipMemcpy(c->last_stats.data() + NSTAT * wpr * r, c->arena + off_stats[r], 8 * NSTAT * wpr, hipMemcpyDeviceToHost));
+    std::memcpy(c->last_stats.data() + NSTAT * wpr * r, back.data() + (off_stats[r] - res_begin), 8 * NSTAT * wpr);
     const size_t base = losses[r].size();
     losses[r].resize(base + n_total[r]);
     correct[r].resize(base + n_total[r]);
-    HIPCHK(c, hipMemcpy(losses[r].data() + base, Ds[r].loss_out, n_total[r] * 4, hipMemcpyDeviceToHost));
-    HIPCHK(c, hipMemcpy(correct[r].data() + base, Ds[r].correct_out, n_total[r] * 4, hipMemcpyDeviceToHost));
+    std::memcpy(losses[r].data() + base, back.data() + (off_loss[r] - res_begin), n_total[r] * 4);
+    std::memcpy(correct[r].data() + base, back.data() + (off_correct[r] - res_begin), n_total[r] * 4);
     if (train) c->rep_admitted[r] += (unsigned)n_total[r];
     if (log_cap) {
       std::vector<unsigned long long> raw(log_cap);
@@ -1106,16 +1149,16 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
       n.dirty = false;
     }
 
-  // replica r trains on instances r, r + R, r + 2R, ... of the set, in that order
-  std::vector<InstSet> parts;
-  std::vector<const InstSet*> sets;
-  if (R == 1) {
-    sets.push_back(&S);
-  } else {
-    parts.resize(R);
-    for (size_t i = 0; i < S.n(); ++i) append_instance(c, parts[i % R], S, i);
-    for (int r = 0; r < R; ++r) sets.push_back(&parts[r]);
+  // The set stays in the arena from call to call: the training set first, the evaluation set behind it.
+  Resident& res = c->resident[which];
+  const Resident& other = c->resident[1 - which];
+  const size_t begin = which == 1 && other.valid ? other.end : c->static_end;
+  if (S.dirty || !res.valid || res.R != R || res.begin != begin) {
+    if (which == 0) c->resident[1].valid = false;
+    if (int rc = make_resident(c, S, R, begin, res)) return rc;
+    S.dirty = false;
   }
+  const size_t out_begin = std::max(res.end, other.valid ? other.end : (size_t)0);
   std::vector<std::vector<float>> losses(R);
   std::vector<std::vector<int>> correct(R);
   double seconds = 0;
@@ -1123,7 +1166,7 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   // with replicas the parameters are averaged at the end of every epoch (Section 5), hence one launch per epoch
   const int launches = R > 1 ? epochs : 1, per_launch = R > 1 ? 1 : epochs;
   for (int l = 0; l < launches; ++l) {
-    if (int rc = launch_once(c, sets, per_launch, train, losses, correct, seconds)) return rc;
+    if (int rc = launch_once(c, res, out_begin, per_launch, train, losses, correct, seconds)) return rc;
     if (R > 1)
       for (HostNode& n : c->nodes)
         HIPCHK(c, amp_average((float*)rep_ptr(c, 0, n.off_P), c->rep_stride / 4, R, n.count(), c->stream));
@@ -1137,8 +1180,8 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   for (int e = 0; e < epochs; ++e)
     for (size_t i = 0; i < n; ++i) {
       const size_t r = i % R, j = i / R;
-      loss[e * n + i] = losses[r][(size_t)e * sets[r]->n() + j];
-      corr[e * n + i] = correct[r][(size_t)e * sets[r]->n() + j];
+      loss[e * n + i] = losses[r][(size_t)e * res.n[r] + j];
+      corr[e * n + i] = correct[r][(size_t)e * res.n[r] + j];
     }
   uint64_t npred = c->model == AMP_MODEL_TREE ? (uint64_t)S.lab.size() * epochs : n_total;
   if (train) {
