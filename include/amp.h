@@ -167,6 +167,25 @@ int amp_finalize(amp_ctx *ctx, int max_active_keys, int max_instance_len, int ma
 /* max_active_keys: number of instances in flight (Section 3); 1..the value
  * given to amp_finalize. */
 int amp_set_max_active_keys(amp_ctx *ctx, int mak);
+/* How the controller admits instances (Appendix B, MNIST: the greedy schedule
+ * lets gradients go stale at a high max_active_keys and a better one would
+ * remove that sensitivity).
+ *   AMP_ADMIT_GREEDY (default): a new instance whenever fewer than
+ *     max_active_keys are in flight.
+ *   AMP_ADMIT_BOUNDED: the number in flight is a limit of its own in
+ *     1..max_active_keys.  It starts at 1, grows by one with every instance
+ *     that retires having seen at most max_staleness updates per worker
+ *     (updates applied by all workers during the instance's life, divided by
+ *     the number of workers) and shrinks by one with every instance that saw
+ *     more.  max_staleness >= 0; 0 keeps one instance in flight once any
+ *     update has been applied.  Evaluation always admits greedily.
+ * amp_get_admission reports, for the last amp_train call's last launch, the
+ * largest number of instances that were in flight and the limit at the end
+ * (largest over the replicas); either pointer may be NULL. */
+#define AMP_ADMIT_GREEDY 0
+#define AMP_ADMIT_BOUNDED 1
+int amp_set_admission(amp_ctx *ctx, int policy, double max_staleness);
+int amp_get_admission(amp_ctx *ctx, int *max_in_flight, int *final_limit);
 /* min_update_frequency of a node (-1 = all): the node updates as soon as it
  * has accumulated this many gradients (Section 3); >= 1. */
 int amp_set_min_update_frequency(amp_ctx *ctx, int node_id, int muf);

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libamp.so")
 
 AMP_OK, AMP_EINVAL, AMP_ESTATE, AMP_ENOMEM, AMP_EFULL, AMP_EDEVICE, AMP_EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 MODEL_MLP, MODEL_RNN, MODEL_TREE, MODEL_GGNN = 1, 2, 3, 4
+ADMIT_GREEDY, ADMIT_BOUNDED = 0, 1
 OPT_SGD, OPT_MOMENTUM, OPT_ADAM = 0, 1, 2
 EV_NAMES = "FBUAR"
 
@@ -77,6 +78,8 @@ SIGNATURES = {
     "amp_clear_instances": (ct.c_int, [_ctxp, ct.c_int]),
     "amp_set_event_log": (ct.c_int, [_ctxp, ct.c_size_t]),
     "amp_set_watchdog": (ct.c_int, [_ctxp, ct.c_double]),
+    "amp_set_admission": (ct.c_int, [_ctxp, ct.c_int, ct.c_double]),
+    "amp_get_admission": (ct.c_int, [_ctxp, ct.POINTER(ct.c_int), ct.POINTER(ct.c_int)]),
     "amp_train": (ct.c_int, [_ctxp, ct.c_int]),
     "amp_eval": (ct.c_int, [_ctxp, ct.POINTER(EvalResult)]),
     "amp_get_loss": (ct.c_int, [_ctxp, ct.POINTER(ct.c_double), ct.POINTER(ct.c_double),
@@ -247,6 +250,14 @@ class Amp:
 
     def set_event_log(self, n):
         self._chk(self.L.amp_set_event_log(self.h, n))
+
+    def set_admission(self, policy, max_staleness=0.0):
+        self._chk(self.L.amp_set_admission(self.h, policy, max_staleness))
+
+    def get_admission(self):
+        a, b = ct.c_int(0), ct.c_int(0)
+        self._chk(self.L.amp_get_admission(self.h, ct.byref(a), ct.byref(b)))
+        return dict(max_in_flight=a.value, final_limit=b.value)
 
     def set_watchdog(self, seconds):
         self._chk(self.L.amp_set_watchdog(self.h, seconds))

@@ -440,6 +440,11 @@ __device__ __forceinline__ void softmax_xent_wave0(const float* z, int n, int la
   __syncthreads();
 }
 
+// ONE thread, at every update a worker applies: the controller's staleness-bounded admission reads this count.
+__device__ __forceinline__ void note_update(const GQ AmpDev* D) {
+  if (D->admit_bounded) __hip_atomic_fetch_add((GQ unsigned*)&D->ctl[3], 1u, __ATOMIC_RELAXED, AGENT);
+}
+
 // Arrival counter of a join: returns true for the arrival that completes
 // `expect` parts; that caller resets the counter (the slot is not reused
 // before the instance has retired) and may then post.  ONE thread, after a

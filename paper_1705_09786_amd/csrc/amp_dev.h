@@ -138,7 +138,10 @@ struct AmpDev {
   int max_len, max_edges, train, pad0;
   int tiles_leaf, tiles_branch;
   unsigned n_total, first_seq;
-  unsigned* ctl;              // [0] abort code, [1] done, [2] abort detail
+  int admit_bounded, n_updaters;  // staleness-bounded admission on / workers that apply updates
+  float max_staleness;            // its bound: updates per worker during an instance's life
+  unsigned* ctl;              // [0] abort code, [1] done, [2] abort detail, [3] updates applied by all workers,
+                              // [4] largest number of instances in flight, [5] admission limit at the end
   unsigned* slot_seq;         // [mak] admission number held by each slot
   int* smeta;                 // [mak][4] written at admission: admission number, length, node offset (RNN: instance), token offset
   float* loss_out;            // [n_total] summed loss of each admission

@@ -270,6 +270,7 @@ __device__ __forceinline__ void g_count_and_update(const GQ AmpDev* D, const GQ 
   nrows += K;
   if ((int)count >= uni(nd.muf)) {
     tstep++;
+    if (threadIdx.x == 0) note_update(D);
     __syncthreads();   // the appended rows of every wave are in HBM
     tree_update_from_pend<NRBT, NCGT>(g.Wl, g.bl, &nd, t, pend, nrows, count, tstep, g.rowmap, g.colmap, gb);
     gb = 0.f;
@@ -329,6 +330,7 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
     count++;
     if ((int)count >= lk.muf) {
       tstep++;
+      if (threadIdx.x == 0) note_update(D);
       const float sc = lk.lr * (lk.mean ? 1.f / (float)count : 1.f);
       for (int i = threadIdx.x; i < V * H; i += AMP_THREADS) {
         El[i] -= sc * lkG[i];

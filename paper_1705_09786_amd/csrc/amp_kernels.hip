@@ -70,15 +70,25 @@ __device__ __noinline__ void role_ctrl(const GQ AmpDev* D, const GQ WorkerDev* W
     int nfree = mak;
     for (int i = 0; i < mak; ++i) freelist[i] = mak - 1 - i;
     unsigned next = 0, retired = 0, head = 0;
-    int active = 0;
+    int active = 0, max_active = 0;
+    // Admission.  Greedy: a new instance whenever fewer than max_active_keys are in flight -- at a high
+    // max_active_keys the gradients then go stale and training can become unstable (Appendix B, MNIST, which asks
+    // for a better schedule).  Staleness-bounded: the number in flight is a limit of its own, between 1 and
+    // max_active_keys, which starts at 1, grows by one with every instance that retires having seen at most
+    // max_staleness updates per worker during its life, and shrinks by one with every instance that saw more.
+    const bool bounded = D->admit_bounded != 0;
+    unsigned* upd_at = (unsigned*)(freelist + mak);   // [slot] updates applied so far when the slot's instance was admitted
+    int limit = bounded ? 1 : mak;
+    const float per_worker = 1.f / (float)(D->n_updaters > 0 ? D->n_updaters : 1);
     const unsigned n_total = D->n_total;
     const GQ RingDev& mine = D->ring[W->ring];
     D->clock[0] = wall_clock64();
     bool ok = true;
     while (retired < n_total && ok) {
-      while (active < mak && next < n_total) {
+      while (active < limit && next < n_total) {
         const int s = freelist[--nfree];
         const unsigned seq = D->first_seq + next;
+        if (bounded) upd_at[s] = ld_u32(&D->ctl[3]);
         D->slot_seq[s] = seq;
         log_event(D, W, &s_logn, 0, 3, seq, 0);
         if (D->model == 3) {
@@ -109,6 +119,7 @@ __device__ __noinline__ void role_ctrl(const GQ AmpDev* D, const GQ WorkerDev* W
         }
         next++;
         active++;
+        if (active > max_active) max_active = active;
       }
       unsigned code;
       ok = ctrl_wait(D, mine, head, code);
@@ -118,9 +129,18 @@ __device__ __noinline__ void role_ctrl(const GQ AmpDev* D, const GQ WorkerDev* W
         freelist[nfree++] = s;
         active--;
         retired++;
+        if (bounded) {
+          const float seen = (float)(ld_u32(&D->ctl[3]) - upd_at[s]) * per_worker;
+          if (seen > D->max_staleness)
+            limit = limit > 1 ? limit - 1 : 1;
+          else
+            limit = limit < mak ? limit + 1 : mak;
+        }
       }
     }
     D->clock[1] = wall_clock64();
+    D->ctl[4] = (unsigned)max_active;
+    D->ctl[5] = (unsigned)limit;
     fence_release();
     __hip_atomic_store((GQ unsigned*)&D->ctl[1], 1u, __ATOMIC_RELAXED, AGENT);
   }
@@ -133,6 +153,7 @@ __device__ __forceinline__ void count_and_update(const GQ AmpDev* D, const GQ Wo
   count++;
   if ((int)count >= nd.muf) {
     tstep++;
+    if (threadIdx.x == 0) note_update(D);
     tile_update(nd, t, Wl, bl, count, tstep);
     count = 0;
     LOG(W->node, 2, 0, 0);
@@ -248,6 +269,7 @@ __device__ __noinline__ void role_mlp_lin(const GQ AmpDev* D, const GQ WorkerDev
     if ((int)count >= muf) {
       // the node's own update (Section 3) from the accumulator in LDS
       tstep++;
+      if (threadIdx.x == 0) note_update(D);
       lds_barrier();
       const OptCoef o = opt_coef(nd, tstep);
       const float inv = nd.mean ? 1.f / (float)count : 1.f;

@@ -81,6 +81,9 @@ struct amp_ctx {
   int max_mak = 0, mak = 1, max_len = 0, max_edges = 0, mean = 1;
   size_t max_instances = 0, log_cap = 0;
   double watchdog_s = 20.0;
+  int admit_bounded = 0;         // staleness-bounded admission
+  double max_staleness = 0;
+  int last_max_in_flight = 0, last_limit = 0;   // of the last training launch, largest over the replicas
   InstSet sets[2];
   Resident resident[2];
   // arena layout
@@ -175,7 +178,7 @@ size_t rows_per_message(const amp_ctx* c, const HostWorker& w) {
 size_t lds_floats(const amp_ctx* c, HostWorker& w) {
   const size_t avail = AMP_DYN_LDS_BYTES / 4;
   w.kb = 1;
-  if (w.role == ROLE_CTRL) return r4(c->max_mak);
+  if (w.role == ROLE_CTRL) return r4(2 * c->max_mak);   // free slots, update count at admission
   if (w.role == ROLE_TREE_LOOKUP) {
     w.kb = 64;
     return r4(c->max_mak) + AMP_TREE_LOOKUP_MAX_MUF;
@@ -806,6 +809,22 @@ int amp_set_event_log(amp_ctx* c, size_t events_per_worker) {
   return AMP_OK;
 }
 
+int amp_set_admission(amp_ctx* c, int policy, double max_staleness) {
+  if (!c) return AMP_EINVAL;
+  if (policy != AMP_ADMIT_GREEDY && policy != AMP_ADMIT_BOUNDED) return fail(c, AMP_EINVAL, "unknown admission policy %d", policy);
+  if (policy == AMP_ADMIT_BOUNDED && !(max_staleness >= 0)) return fail(c, AMP_EINVAL, "max_staleness must be >= 0");
+  c->admit_bounded = policy == AMP_ADMIT_BOUNDED;
+  c->max_staleness = max_staleness;
+  return AMP_OK;
+}
+
+int amp_get_admission(amp_ctx* c, int* max_in_flight, int* final_limit) {
+  if (!c) return AMP_EINVAL;
+  if (max_in_flight) *max_in_flight = c->last_max_in_flight;
+  if (final_limit) *final_limit = c->last_limit;
+  return AMP_OK;
+}
+
 int amp_set_watchdog(amp_ctx* c, double seconds) {
   if (!c) return AMP_EINVAL;
   if (!(seconds > 0) || seconds > 600) return fail(c, AMP_EINVAL, "watchdog must be in (0, 600] seconds");
@@ -1032,6 +1051,9 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
       D.tiles_leaf = c->nodes[1].tiles;
       D.tiles_branch = c->nodes[2].tiles;
     }
+    D.admit_bounded = train ? c->admit_bounded : 0;
+    D.max_staleness = (float)c->max_staleness;
+    D.n_updaters = (int)wpr - 1;   // every worker but the controller applies updates
     D.n_total = (unsigned)n_total[r];
     D.first_seq = train ? c->rep_admitted[r] : 0;
     D.ctl = (unsigned*)rep_ptr(c, r, c->off_ctl);
@@ -1063,18 +1085,24 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
   (void)hipEventDestroy(e1);
   seconds += ms * 1e-3;
 
-  std::vector<unsigned> ctl(4 * (size_t)R);
-  HIPCHK(c, hipMemcpy2D(ctl.data(), 16, rep_ptr(c, 0, c->off_ctl), c->rep_stride, 16, R, hipMemcpyDeviceToHost));
-  for (int r = 0; r < R; ++r)
-    if (ctl[4 * r]) {
-      const unsigned why_code = ctl[4 * r];
+  std::vector<unsigned> ctl(8 * (size_t)R);
+  HIPCHK(c, hipMemcpy2D(ctl.data(), 32, rep_ptr(c, 0, c->off_ctl), c->rep_stride, 32, R, hipMemcpyDeviceToHost));
+  if (train) c->last_max_in_flight = c->last_limit = 0;
+  for (int r = 0; r < R; ++r) {
+    if (train) {
+      c->last_max_in_flight = std::max(c->last_max_in_flight, (int)ctl[8 * r + 4]);
+      c->last_limit = std::max(c->last_limit, (int)ctl[8 * r + 5]);
+    }
+    if (ctl[8 * r]) {
+      const unsigned why_code = ctl[8 * r];
       const char* why = why_code == ABORT_WATCHDOG ? "a worker waited longer than the watchdog allows"
                         : why_code == ABORT_LOG_FULL ? "event record full"
                                                      : "inconsistent state";
       c->state_zeroed = false;   // device state is unreliable after an aborted run
       for (HostNode& n : c->nodes) n.dirty = true;
-      return fail(c, AMP_EDEVICE, "kernel stopped itself: %s (replica %d, worker %u)", why, r, ctl[4 * r + 2]);
+      return fail(c, AMP_EDEVICE, "kernel stopped itself: %s (replica %d, worker %u)", why, r, ctl[8 * r + 2]);
     }
+  }
   std::vector<char> back(res_end - res_begin);
   HIPCHK(c, hipMemcpy(back.data(), c->arena + res_begin, back.size(), hipMemcpyDeviceToHost));
   c->last_stats.assign(NSTAT * wpr * R, 0);

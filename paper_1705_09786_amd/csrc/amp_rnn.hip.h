@@ -243,6 +243,7 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
     if ((int)count >= nd_muf) {
       // the cell's own update (Section 3)
       tstep++;
+      if (threadIdx.x == 0) note_update(D);
       tree_update_from_pend<NRBT, NCGT>(Wl, bl, &nd, t, pend, count, count, tstep, rowmap, colmap, accb);
       accb = 0.f;
       count = 0;
@@ -251,6 +252,7 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
     if ((int)lcount >= lk_muf) {
       // the lookup's update: plain SGD over the whole (small) table
       lstep++;
+      if (threadIdx.x == 0) note_update(D);
       const float sc = lk.lr * (lk.mean ? 1.f / (float)lcount : 1.f);
       for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) {
         lkP[i] -= sc * lkG[i];

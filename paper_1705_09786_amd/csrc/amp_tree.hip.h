@@ -250,6 +250,7 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
       // SGD on the touched rows: each waiting gradient row is subtracted from its
       // token's row, in arrival order (rows never touched have a zero gradient)
       tstep++;
+      if (threadIdx.x == 0) note_update(D);
       const float sc = lk.lr * (lk.mean ? 1.f / (float)count : 1.f);
       __syncthreads();
       for (int c = threadIdx.x; c < E; c += AMP_THREADS) {
@@ -1196,6 +1197,7 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
     if ((int)count >= nd_muf) {
       // the node's own update (Section 3): optimizer step on the LDS weights with the accumulated gradient
       tstep++;
+      if (threadIdx.x == 0) note_update(D);
       if (STREAM)
         tree_update_stream(ndP, bl, &nd, t, pend, count, tstep, rowmap, accb);
       else
@@ -1374,6 +1376,7 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
       if ((int)count >= nd.muf) {
         // the node's own update (Section 3)
         tstep++;
+        if (threadIdx.x == 0) note_update(D);
         const OptCoef o = opt_coef(nd, tstep);
         const float inv = nd.mean ? 1.f / (float)count : 1.f;
 #pragma unroll

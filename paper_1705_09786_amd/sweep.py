@@ -5,6 +5,12 @@ accuracy; reports the epochs (data) and the device time that took, and the
 training rate.
 
     python -m paper_1705_09786_amd.sweep [--replicas 8] [--max-epochs 40] [--out sweep.json]
+                                         [--admission bounded --max-staleness 8] [--maks 32,64] [--mufs 1,4]
+
+With `--admission bounded` the controller keeps the number of instances in
+flight below max_active_keys whenever they would see more than
+`--max-staleness` updates per worker (Appendix B, MNIST: a better schedule
+than the greedy one); the cells then also report the largest number in flight.
 
 The paper's list-reduction dataset is not available; the stand-in is the
 "max" reduction of `synth.make_rnn` (lists of 2..10 tokens, label = largest
@@ -24,18 +30,21 @@ MAKS = (1, 2, 4, 8, 16, 32, 64)
 MUFS = (1, 4, 16, 64, 256)
 
 
-def run_one(data, valid, dims, fp, replicas, mak, muf, lr, max_epochs):
+def run_one(data, valid, dims, fp, replicas, mak, muf, lr, max_epochs, bounded=None):
     ml, _ = runner.max_len_of("rnn", data + valid)
     tr = runner.Trainer("rnn", dims, fp, mak, ml, 0, len(data), arena_bytes=2 << 30, replicas=replicas)
     a = tr.amp
     a.set_min_update_frequency(-1, muf)
     a.set_optimizer(-1, B.OPT_ADAM, lr=lr)
+    if bounded is not None:
+        a.set_admission(B.ADMIT_BOUNDED, bounded)
     tr.submit_all(data)
     tr.submit_all(valid, which=1)
-    seconds, reached, acc = 0.0, None, 0.0
+    seconds, reached, acc, in_flight = 0.0, None, 0.0, 0
     for ep in range(1, max_epochs + 1):
         a.train(1)
         seconds += a.get_loss()["seconds"]
+        in_flight = max(in_flight, a.get_admission()["max_in_flight"])
         acc = a.eval()["accuracy"]
         if acc >= TARGET:
             reached = ep
@@ -43,7 +52,8 @@ def run_one(data, valid, dims, fp, replicas, mak, muf, lr, max_epochs):
     tr.close()
     epochs = reached if reached is not None else max_epochs
     return dict(max_active_keys=mak, min_update_frequency=muf, converged=reached is not None, epochs=epochs,
-                device_seconds=seconds, instances_per_s=len(data) * epochs / seconds, valid_accuracy=acc)
+                device_seconds=seconds, instances_per_s=len(data) * epochs / seconds, valid_accuracy=acc,
+                max_in_flight=in_flight)
 
 
 def main(argv=None):
@@ -53,20 +63,28 @@ def main(argv=None):
     ap.add_argument("--lr", type=float, default=0.001)
     ap.add_argument("--instances", type=int, default=10000)
     ap.add_argument("--out", default=None, help="also write the table to this JSON file")
+    ap.add_argument("--admission", choices=("greedy", "bounded"), default="greedy")
+    ap.add_argument("--max-staleness", type=float, default=8.0, help="bound of the bounded admission (updates per worker)")
+    ap.add_argument("--maks", default=None, help="comma-separated max_active_keys values (default: the full grid)")
+    ap.add_argument("--mufs", default=None, help="comma-separated min_update_frequency values (default: the full grid)")
     args = ap.parse_args(argv)
     dims = synth.DEFAULT_DIMS["rnn"]
     data = synth.make_rnn(args.instances, synth.BASE_SEED + 20, dims, 2, 10, reduction="max")
     valid = synth.make_rnn(1000, synth.BASE_SEED + 1020, dims, 2, 10, reduction="max")
     fp = synth.init_params("rnn", dims, 102)
     rows = []
-    for mak in MAKS:
-        for muf in MUFS:
-            r = run_one(data, valid, dims, fp, args.replicas, mak, muf, args.lr, args.max_epochs)
+    maks = [int(v) for v in args.maks.split(",")] if args.maks else MAKS
+    mufs = [int(v) for v in args.mufs.split(",")] if args.mufs else MUFS
+    bounded = args.max_staleness if args.admission == "bounded" else None
+    for mak in maks:
+        for muf in mufs:
+            r = run_one(data, valid, dims, fp, args.replicas, mak, muf, args.lr, args.max_epochs, bounded)
             rows.append(r)
             print(json.dumps(r), flush=True)
     if args.out:
         with open(args.out, "w") as f:
-            json.dump(dict(replicas=args.replicas, target_accuracy=TARGET, lr=args.lr, rows=rows), f, indent=1)
+            json.dump(dict(replicas=args.replicas, target_accuracy=TARGET, lr=args.lr, admission=args.admission,
+                           max_staleness=bounded, rows=rows), f, indent=1)
     return 0
 
 

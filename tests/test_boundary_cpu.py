@@ -140,6 +140,16 @@ def test_replica_and_weight_placement_setters():
     expect(B.AMP_EUNSUPPORTED, c.finalize, 4, 5, 0, 10)                # 17 x 16 workers exceed 256 workgroups
 
 
+def test_admission_setter():
+    a = new_ctx()
+    expect(B.AMP_EINVAL, a.set_admission, 2, 1.0)                      # no such policy
+    expect(B.AMP_EINVAL, a.set_admission, B.ADMIT_BOUNDED, -1.0)
+    expect(B.AMP_EINVAL, a.set_admission, B.ADMIT_BOUNDED, float("nan"))
+    a.set_admission(B.ADMIT_BOUNDED, 0.0)
+    a.set_admission(B.ADMIT_GREEDY)
+    assert a.get_admission() == dict(max_in_flight=0, final_limit=0)   # nothing trained yet
+
+
 def test_measure_peaks_needs_a_buffer():
     import ctypes as ct
     x, y = ct.c_double(), ct.c_double()

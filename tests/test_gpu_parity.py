@@ -70,6 +70,45 @@ def test_rnn_replay_parity(mak, muf, opt, n):
     compare(g, rt, len(data))
 
 
+def max_in_flight(log):
+    active = worst = 0
+    for (_, kind, _, _) in log:
+        active += 1 if kind == "A" else -1
+        worst = max(worst, active)
+    return worst
+
+
+def test_staleness_bounded_admission():
+    """The controller's own limit on the instances in flight (Appendix B, MNIST: a better schedule than the greedy
+    one).  The event record is replayed as for any other admission order; bound 0 keeps one instance in flight and
+    so repeats the max_active_keys = 1 run bit for bit; a bound nothing reaches ends at max_active_keys."""
+    model, dims, data = synth.workload(2, n=300)
+    fp = synth.init_params(model, dims, 6)
+    seq = gpu_train(model, dims, fp, data, 1, 1, SGD)
+    for bound, lo, hi in ((0.0, 1, 1), (60.0, 2, 15), (1e9, 16, 16)):
+        g = gpu_train(model, dims, fp, data, 16, 1, SGD, max_staleness=bound)
+        check_controller_log(g["logs"], 16, len(data))
+        assert lo <= max_in_flight(g["logs"][0]) <= hi, (bound, max_in_flight(g["logs"][0]))
+        assert g["admission"]["max_in_flight"] == max_in_flight(g["logs"][0])
+        assert 1 <= g["admission"]["final_limit"] <= 16
+        rt = oracle_replay(model, dims, fp, data, g["logs"], 1, SGD)
+        compare(g, rt, len(data))
+        if bound == 0.0:
+            for a, b in zip(g["params"], seq["params"]):
+                assert np.array_equal(a, b)
+            assert np.array_equal(g["losses"], seq["losses"])
+        if bound == 1e9:
+            assert g["admission"]["final_limit"] == 16
+    # a tree run under the bound: tiles, joins and the lookup count their updates too
+    tdims = TREE_ODD
+    tdata = synth.make_tree(48, 5, tdims)
+    tfp = synth.init_params("tree", tdims, 8)
+    g = gpu_train("tree", tdims, tfp, tdata, 8, 3, SGD, tiles={1: 3, 2: 5}, lookup_muf=5, max_staleness=4.0)
+    check_controller_log(g["logs"], 8, len(tdata))
+    rt = oracle_replay("tree", tdims, tfp, tdata, g["logs"], 3, SGD, lookup_muf=5)
+    compare(g, rt, len(tdata))
+
+
 def test_rnn_edge_lengths():
     """Length-1 sequences, the maximum length, and a ragged mix."""
     dims = synth.DEFAULT_DIMS["rnn"]

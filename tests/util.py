@@ -19,12 +19,14 @@ def f32(x):
 
 
 def gpu_train(model, dims, fp, data, mak, muf, opt, epochs=1, log=True, tiles=None, watchdog=5.0,
-              arena_bytes=1 << 30, lookup_muf=None, in_hbm=(), replicas=1):
+              arena_bytes=1 << 30, lookup_muf=None, in_hbm=(), replicas=1, max_staleness=None):
     ml, me = runner.max_len_of(model, data)
     tr = runner.Trainer(model, dims, fp, mak, ml, me, len(data), arena_bytes=arena_bytes, tiles=tiles, in_hbm=in_hbm,
                         replicas=replicas)
     a = tr.amp
     a.set_watchdog(watchdog)
+    if max_staleness is not None:
+        a.set_admission(B.ADMIT_BOUNDED, max_staleness)
     a.set_min_update_frequency(-1, muf)
     if lookup_muf is not None:
         a.set_min_update_frequency(0, lookup_muf)
@@ -37,7 +39,7 @@ def gpu_train(model, dims, fp, data, mak, muf, opt, epochs=1, log=True, tiles=No
     tr.submit_all(data)
     a.train(epochs)
     out = dict(params=tr.params(), losses=a.get_instance_losses().astype(np.float64), stats=a.get_loss(),
-               logs=a.get_event_log() if log else None, trainer=tr)
+               logs=a.get_event_log() if log else None, trainer=tr, admission=a.get_admission())
     return out
 
 
