@@ -472,6 +472,84 @@ __device__ __forceinline__ void tree_bwd_mfma(const LDSQ float* Wl, const Tile& 
     tree_bwd_blocks<BR, 4, NRBT, NCGT>(Wl, t, Dl, M, nB, obase);
 }
 
+// The optimizer step on the LDS weights from the accumulators of tree_update_from_pend (layout described there).
+template <int NRBT, int NCGT>
+__device__ __forceinline__ void tree_update_apply(LDSQ float* Wl, LDSQ float* bl, const GQ NodeDev& nd, const Tile& t,
+                                                  const TreeShape<NRBT, NCGT>& sh, v4f (&g)[TREE_GU][4], unsigned n_grad,
+                                                  unsigned tstep, const LDSQ int* rowmap, const LDSQ int* colmap, float gb) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  const int NRB = sh.NRB, Cp = sh.NCG * 16, CM = (Cp + 63) >> 6, NU = NRB * CM;
+  const OptCoef o = opt_coef(nd, tstep);
+  const float inv = nd.mean ? 1.f / (float)n_grad : 1.f;
+  // optimizer step from the accumulators.  Plain SGD needs no per-element slots: padding rows and columns
+  // have a zero gradient (their delta / input entries are zero), so whole 16-byte groups are updated.
+  if (o.kind == 0) {
+    const float sc = o.lr * inv;
+#pragma unroll
+    for (int u = 0; u < TREE_GU; ++u) {
+      const int id = wave + 8 * u, cm = id / NRB, rb = id - cm * NRB, lc = cm * 64 + 4 * i;
+      if (id < NU && lc < Cp) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          LDSQ v4f* wp = (LDSQ v4f*)(Wl + (rb * 16 + 4 * q + e) * sh.ldw + lc);
+          const v4f gv = {g[u][0][e], g[u][1][e], g[u][2][e], g[u][3][e]};
+          *wp = *wp - sc * gv;
+        }
+      }
+    }
+  } else {
+    // momentum / Adam: the slots are in HBM.  A unit's sixteen elements per lane are fetched together, then stepped,
+    // then stored (a fetch behind the previous element's stores would wait for them).
+    GQ float* Mq = (GQ float*)nd.M;
+    GQ float* Vq = (GQ float*)nd.V;
+#pragma unroll
+    for (int u = 0; u < TREE_GU; ++u) {
+      const int id = wave + 8 * u, cm = id / NRB, rb = id - cm * NRB;
+      if (id < NU) {
+        long long gi[4][4];
+        float mo[4][4], vo[4][4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int nc = colmap[cm * 64 + 4 * i + v];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int nr = rowmap[rb * 16 + 4 * q + e];
+            gi[v][e] = (nr >= 0 && nc >= 0) ? (long long)nr * t.C + nc : -1;
+            const long long at = gi[v][e] >= 0 ? gi[v][e] : 0;
+            mo[v][e] = Mq[at];
+            vo[v][e] = o.kind == 2 ? Vq[at] : 0.f;
+          }
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int lc = cm * 64 + 4 * i + v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (gi[v][e] >= 0) {
+              const int r = rb * 16 + 4 * q + e;
+              const float gr = g[u][v][e] * inv, w = Wl[r * sh.ldw + lc];
+              if (o.kind == 1) {
+                const float m = fmaf(o.mom, mo[v][e], gr);
+                Mq[gi[v][e]] = m;
+                Wl[r * sh.ldw + lc] = w - o.lr * m;
+              } else {
+                const float m = fmaf(o.b1, mo[v][e], (1.f - o.b1) * gr);
+                const float vv = fmaf(o.b2, vo[v][e], (1.f - o.b2) * gr * gr);
+                Mq[gi[v][e]] = m;
+                Vq[gi[v][e]] = vv;
+                Wl[r * sh.ldw + lc] = w - o.lr * (m * o.c1) / (sqrtf(vv * o.c2) + o.eps);
+              }
+            }
+        }
+      }
+    }
+  }
+  if ((int)threadIdx.x < t.R && nd.has_bias) {
+    const int r = threadIdx.x;
+    bl[r] = opt_apply(o, bl[r], gb * inv, nd.M, nd.V, (long long)nd.rows * t.C + rowmap[r]);
+  }
+}
+
 // The node's update (Section 3) for one tile, from the `count` pending
 // (delta, input) pairs in HBM, entry k at pend + k * stride = [delta (Rp) |
 // input in LDS column layout (Cp)]:  G[r][c] = sum_k delta_k[r] x_k[c] in
@@ -492,8 +570,6 @@ __device__ __noinline__ void tree_update_from_pend(LDSQ float* Wl, LDSQ float* b
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
   const int NRB = sh.NRB, Rp = NRB * 16, Cp = sh.NCG * 16, stride = Rp + Cp, CM = (Cp + 63) >> 6, NU = NRB * CM;
   const v4f zero = {0.f, 0.f, 0.f, 0.f};
-  const OptCoef o = opt_coef(nd, tstep);
-  const float inv = nd.mean ? 1.f / (float)n_grad : 1.f;
   v4f g[TREE_GU][4];
   int aoff[TREE_GU], xoff[TREE_GU];
   bool xin[TREE_GU];
@@ -538,43 +614,7 @@ __device__ __noinline__ void tree_update_from_pend(LDSQ float* Wl, LDSQ float* b
           g[u][3] = MFMA(a[h][u], x[h][u].w, g[u][3]);
         }
   }
-  // optimizer step from the accumulators.  Plain SGD needs no per-element slots: padding rows and columns
-  // have a zero gradient (their delta / input entries are zero), so whole 16-byte groups are updated.
-  if (o.kind == 0) {
-    const float sc = o.lr * inv;
-#pragma unroll
-    for (int u = 0; u < TREE_GU; ++u) {
-      const int id = wave + 8 * u, cm = id / NRB, rb = id - cm * NRB, lc = cm * 64 + 4 * i;
-      if (id < NU && lc < Cp) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          LDSQ v4f* wp = (LDSQ v4f*)(Wl + (rb * 16 + 4 * q + e) * sh.ldw + lc);
-          const v4f gv = {g[u][0][e], g[u][1][e], g[u][2][e], g[u][3][e]};
-          *wp = *wp - sc * gv;
-        }
-      }
-    }
-  } else
-#pragma unroll
-  for (int u = 0; u < TREE_GU; ++u) {
-    const int id = wave + 8 * u, cm = id / NRB, rb = id - cm * NRB;
-    if (id < NU) {
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int lc = cm * 64 + 4 * i + v, nc = colmap[lc];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = rb * 16 + 4 * q + e, nr = rowmap[r];
-          if (nr >= 0 && nc >= 0)
-            Wl[r * sh.ldw + lc] = opt_apply(o, Wl[r * sh.ldw + lc], g[u][v][e] * inv, nd.M, nd.V, (long long)nr * t.C + nc);
-        }
-      }
-    }
-  }
-  if ((int)threadIdx.x < t.R && nd.has_bias) {
-    const int r = threadIdx.x;
-    bl[r] = opt_apply(o, bl[r], gb * inv, nd.M, nd.V, (long long)nd.rows * t.C + rowmap[r]);
-  }
+  tree_update_apply<NRBT, NCGT>(Wl, bl, nd, t, sh, g, n_grad, tstep, rowmap, colmap, gb);
 }
 
 // ------------------------------------------------------------ products of a tile whose weights stay in HBM
