@@ -1064,6 +1064,14 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
     PHASE(0);
     // ---------------- forward messages of the batch
     if (nF > 0) {
+      // the children's c of this thread's first (message, unit) pair travel while the product is formed
+      float pcl = 0.f, pcr = 0.f;
+      if (BR && (int)threadIdx.x < nF * nu) {
+        const int k = threadIdx.x / nu, m = M.fidx[k], u = u0 + (int)threadIdx.x - k * nu;
+        pcl = xbase[M.off0[m] + Hp + u];
+        pcr = xbase[M.off1[m] + Hp + u];
+        asm volatile("" ::: "memory");
+      }
       if (STREAM)
         tree_fwd_stream<BR>(ndP, rowoff, t, bl, xbase, M, nF, Y, ldy, Xs);
       else
@@ -1078,8 +1086,9 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
         GQ float* gt = B.gate + nn * 6 * H;
         float c_, o_;
         if (BR) {
-          const float cl = xbase[M.off0[m] + Hp + u];
-          const float cr = xbase[M.off1[m] + Hp + u];
+          const bool first = i == (int)threadIdx.x;
+          const float cl = first ? pcl : xbase[M.off0[m] + Hp + u];
+          const float cr = first ? pcr : xbase[M.off1[m] + Hp + u];
           const float i_ = sigmoidf_(y[j]), fl = sigmoidf_(y[nu + j]), fr = sigmoidf_(y[2 * nu + j]);
           o_ = sigmoidf_(y[3 * nu + j]);
           const float g_ = tanhf(y[4 * nu + j]);
