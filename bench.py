@@ -83,7 +83,7 @@ def ggnn_cost(dims, data):
     return nbytes, nflops
 
 
-def cpu_baseline(model, dims, fp, data, cfg, budget_s=15.0):
+def cpu_baseline(model, dims, fp, data, cfg, budget_s=30.0):
     """The CPU checker's own-schedule AMP driver, as it stands, on a prefix of
     the same workload; one thread."""
     from threadpoolctl import threadpool_limits
