@@ -14,13 +14,14 @@ pytestmark = pytest.mark.gpu
 OPT_KIND = {"sgd": B.OPT_SGD, "momentum": B.OPT_MOMENTUM, "adam": B.OPT_ADAM}
 
 
-def _trainer(cfgi, lr=None, log=False):
+def _trainer(cfgi, lr=None, log=False, replicas=1):
     cfg = bench.DEFAULTS[cfgi]
     model, dims, data = synth.workload(cfgi)
     fp = synth.init_params(model, dims, 100 + cfgi)
     ml, me = runner.max_len_of(model, data)
-    tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=(20 if cfgi == 5 else 4) << 30,
-                        tiles=cfg.get("tiles"))
+    tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data),
+                        arena_bytes=(20 if cfgi == 5 else 24 if replicas > 1 else 4) << 30, tiles=cfg.get("tiles"),
+                        replicas=replicas)
     a = tr.amp
     a.set_watchdog(20.0)
     a.set_min_update_frequency(-1, cfg["muf"])
@@ -54,6 +55,30 @@ def test_full_size_run_with_zero_step_equals_plain_forward(cfgi, sample):
     for i in rng.choice(len(data), size=sample, replace=False):
         ref, _ = direct.evaluate(model, dims, P, [data[i]])
         assert abs(losses[i] - ref) <= 1e-5 * max(1.0, abs(ref)), (int(i), float(losses[i]), ref)
+    tr.close()
+
+
+@pytest.mark.parametrize("cfgi,replicas,sample", [(3, 16, 32), (4, 24, 32)])
+def test_full_size_replicated_run_with_zero_step(cfgi, replicas, sample):
+    """The replicated launch bench.py times (whole replicas placed XCD by XCD, all 256 / 240 workgroups): with a zero
+    learning rate the average of the replicas' parameters is the initial parameters up to the rounding of the
+    averaging sum (16 equal terms added one after another), and every instance's loss -- whichever replica it went
+    to -- is the plain forward loss."""
+    cfg, model, dims, data, fp, tr = _trainer(cfgi, lr=0.0, replicas=replicas)
+    a = tr.amp
+    a.train(2)   # two launches: the second starts from the averaged parameters
+    losses = a.get_instance_losses()
+    assert losses.shape == (2 * len(data),) and np.isfinite(losses).all()
+    for k, p in enumerate(tr.params()):
+        assert np.allclose(p, fp[k], rtol=1e-6, atol=0.0), "node %d moved under a zero step" % k
+    assert a.get_admission()["max_in_flight"] <= cfg["mak"]
+    P = direct.unpack(model, dims, fp)
+    rng = np.random.Generator(np.random.Philox(950 + cfgi))
+    for i in rng.choice(len(data), size=sample, replace=False):
+        ref, _ = direct.evaluate(model, dims, P, [data[i]])
+        for e in range(2):
+            got = losses[e * len(data) + i]
+            assert abs(got - ref) <= 1e-5 * max(1.0, abs(ref)), (int(i), e, float(got), ref)
     tr.close()
 
 
