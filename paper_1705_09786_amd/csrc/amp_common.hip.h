@@ -28,11 +28,20 @@ __device__ __forceinline__ unsigned ld_u32(const unsigned* p) {
 __device__ __forceinline__ void fence_release() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
 __device__ __forceinline__ void fence_acquire() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent"); }
 
-// Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits
-// until every HBM load and store of the wave has completed (a round trip to
-// memory); between phases that hand data over through LDS this one is enough.
-// HBM data written by one wave and read by another wave of the workgroup, or
-// published to other workgroups, still needs __syncthreads().
+// The barrier in front of a post.  __syncthreads() does not wait for a wave's outstanding HBM stores (at
+// workgroup scope the compiler emits no wait for them: the waves of a workgroup share one L1), and the posting
+// wave's release fence writes back the L2 as it stands and waits for its own wave's accesses only -- a store of
+// another wave still on its way would miss the write-back and the receiver would read the old value (seen as a
+// rare wrong parameter in the parity tests).  So every wave first waits until its own stores have reached the L2.
+__device__ __forceinline__ void publish_barrier() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+}
+
+// Workgroup barrier that orders LDS accesses only; between phases that hand
+// data over through LDS this one is enough.  HBM data written by one wave and
+// read by another wave of the workgroup needs __syncthreads(); data published
+// to other workgroups needs publish_barrier().
 __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   __builtin_amdgcn_s_barrier();

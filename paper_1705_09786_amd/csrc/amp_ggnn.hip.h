@@ -309,7 +309,7 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
         h0[i] = El[v.type[n] * H + j];
       }
       LOG(0, 0, seq, 0);
-      __syncthreads();
+      publish_barrier();
       if (threadIdx.x < 64) {
         fence_release();
         g_post_edges(rg, present, s, 0, false);
@@ -322,7 +322,7 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
     for (int j = threadIdx.x; j < H; j += AMP_THREADS)
       for (int n = 0; n < v.N; ++n) lkG[v.type[n] * H + j] += gt[n * H + j];
     LOG(0, 1, seq, 0);
-    __syncthreads();
+    publish_barrier();
     if (threadIdx.x == 0) {
       fence_release();
       ring_post(rg.ctl, MSG_MAKE(1, s, 0));
@@ -417,7 +417,7 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
         msg[te[k] * H + j] = Y[k * Hs + j];
       }
       LOG(W->node, 0, seq, it);
-      __syncthreads();
+      publish_barrier();
       if (threadIdx.x == 0) {
         fence_release();
         // the last type to arrive completes the step's messages; Ungroup, regrouping by target node and the sum are the GRU nodes' part
@@ -484,7 +484,7 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
         dHe[i] = a;
       }
     }
-    __syncthreads();
+    publish_barrier();
     if (threadIdx.x == 0) {
       fence_release();
       if (join_arrive(B.cnt + s * 8 + 3, nact)) {
@@ -592,7 +592,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       } else
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) outp[i] = sigmoidf_(Y[(i / H) * Hs + i % H]);
       LOG(W->node, 0, seq, it);
-      __syncthreads();
+      publish_barrier();
       if (threadIdx.x == 0) {
         fence_release();
         if (join_arrive(B.cnt + s * 8 + 1, 2)) ring_post(rg.gh, MSG_MAKE(0, s, it));
@@ -650,7 +650,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       else
         dHp[k * H + c - H] = X[k * Cs + c];
     }
-    __syncthreads();
+    publish_barrier();
     if (threadIdx.x < 64) {
       fence_release();
       // both gates done: back through sum / Group to the edge types
@@ -755,7 +755,7 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
         hn[i] = (1.f - z) * h[i] + z * ht;
       }
       LOG(W->node, 0, seq, it);
-      __syncthreads();
+      publish_barrier();
       if (threadIdx.x < 64) {
         fence_release();
         if (it + 1 < B.S)
@@ -825,7 +825,7 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
         dHp[i] = drh * r + gt[i] * (1.f - z);
       }
     }
-    __syncthreads();
+    publish_barrier();
     if (threadIdx.x == 0) {
       fence_release();
       ring_post(rg.gz, MSG_MAKE(1, s, it));
@@ -891,7 +891,7 @@ __device__ __noinline__ void role_g_readout(const GQ AmpDev* D, const GQ WorkerD
       ((GQ float*)D->yhat_out)[seq - D->first_seq] = yhat;
     }
     if (!D->train) {
-      __syncthreads();
+      publish_barrier();
       if (threadIdx.x == 0) {
         fence_release();
         ring_post(rg.ctl, MSG_MAKE(1, s, 0));
@@ -903,7 +903,7 @@ __device__ __noinline__ void role_g_readout(const GQ AmpDev* D, const GQ WorkerD
     for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) gH[i] = d * Wl[i % H];
     for (int j = threadIdx.x; j < H; j += AMP_THREADS) ndG[j] += d * pooled[j];
     if (threadIdx.x == 0) ndG[H] += d;
-    __syncthreads();
+    publish_barrier();
     if (threadIdx.x == 0) {
       fence_release();
       ring_post(rg.gh, MSG_MAKE(1, s, B.S - 1));

@@ -230,7 +230,7 @@ __device__ __noinline__ void role_mlp_lin(const GQ AmpDev* D, const GQ WorkerDev
       LOG(W->node, 0, seq, 0);
       if (!last) {
         for (int r = threadIdx.x; r < R; r += AMP_THREADS) act_out[(long long)s * R + r] = fmaxf(ys[r], 0.f);
-        __syncthreads();
+        publish_barrier();
         if (threadIdx.x == 0) {
           fence_release();
           ring_post(next, MSG_MAKE(0, s, 0));
@@ -244,7 +244,7 @@ __device__ __noinline__ void role_mlp_lin(const GQ AmpDev* D, const GQ WorkerDev
         correct_out[seq - first_seq] = s_pred == label;
       }
       if (!train) {
-        __syncthreads();
+        publish_barrier();
         if (threadIdx.x == 0) {
           fence_release();
           ring_post(ctl, MSG_MAKE(1, s, 0));
@@ -259,7 +259,7 @@ __device__ __noinline__ void role_mlp_lin(const GQ AmpDev* D, const GQ WorkerDev
       for (int c = threadIdx.x; c < C; c += AMP_THREADS) g_out[(long long)s * C + c] = dx[c];
     }
     // every wave's HBM stores have landed before thread 0 publishes
-    __syncthreads();
+    publish_barrier();
     if (threadIdx.x == 0) {
       fence_release();
       ring_post(prev, MSG_MAKE(1, s, 0));

@@ -217,7 +217,7 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
         }
     }
     // every wave's HBM stores have landed before wave 0 publishes the batch
-    __syncthreads();
+    publish_barrier();
     PHASE(5);
     if (threadIdx.x < 64) {
       fence_release();
@@ -311,7 +311,7 @@ __device__ __noinline__ void role_rnn_out(const GQ AmpDev* D, const GQ WorkerDev
       D->correct_out[seq - D->first_seq] = s_pred == label;
     }
     if (!D->train) {
-      __syncthreads();
+      publish_barrier();
       if (threadIdx.x == 0) {
         fence_release();
         ring_post(D->ring[0], MSG_MAKE(1, s, 0));
@@ -322,7 +322,7 @@ __device__ __noinline__ void role_rnn_out(const GQ AmpDev* D, const GQ WorkerDev
     gemv_cols((LDSQ float*)Wl, t.ldw, R, C, (LDSQ float*)ds, (LDSQ float*)part, (LDSQ float*)dx);
     for (int c = threadIdx.x; c < C; c += AMP_THREADS) B.dh[(long long)s * B.SP + c] = dx[c];
     tile_accumulate(nd, t, ds, xs);
-    __syncthreads();
+    publish_barrier();
     if (threadIdx.x == 0) {
       fence_release();
       ring_post(cell, MSG_MAKE(1, s, T - 1));

@@ -233,7 +233,7 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
         }
       }
     }
-    __syncthreads();
+    publish_barrier();
     if (threadIdx.x < 64) {
       fence_release();
       const int k = threadIdx.x;
@@ -1226,7 +1226,7 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
       jL = M.L[k];
     }
     // every wave's HBM stores have landed before wave 0 publishes the batch
-    __syncthreads();
+    publish_barrier();
     // ---------------- joins and posts, one lane per message
     if (threadIdx.x < 64) {
       fence_release();
@@ -1405,7 +1405,7 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
         for (int k = 0; k < n; ++k) gb += zbuf[k * 64 + threadIdx.x];
     }
     // every wave's HBM stores have landed before wave 0 publishes the batch
-    __syncthreads();
+    publish_barrier();
     if (threadIdx.x < 64) {
       fence_release();
       const int k = threadIdx.x;
