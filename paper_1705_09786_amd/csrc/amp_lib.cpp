@@ -195,7 +195,7 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
     case ROLE_TREE_BRANCH: {
       // the largest batch (a multiple of 16 messages) whose pre-activation rows fit beside the weights
       const size_t ldy = amp_ldrow((int)R);
-      if (w.aux) {
+      if (w.aux && w.role != ROLE_RNN_CELL) {
         // weights stay in HBM: rows must be 16-byte aligned and unpadded
         if (c->dims.hidden % 4 || c->dims.emb % 4) return 0;
         for (w.kb = 64; w.kb >= 16; w.kb -= 16) {
@@ -207,11 +207,19 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
       }
       // the update's register accumulator holds 8 waves x 4 (16-row, 64-column) units
       if ((Rp / 16) * ((amp_round16(n.cl()) + 63) / 64) > 32) return 0;
-      for (w.kb = 64; w.kb >= 16; w.kb -= 16) {
+      // a sequence has one message in flight, so the recurrent cell never sees more than max_active_keys at once
+      const int kb_top = w.role == ROLE_RNN_CELL ? std::min(64, amp_round16(c->max_mak)) : 64;
+      for (w.kb = kb_top; w.kb >= 16; w.kb -= 16) {
         f = wfl + r4((size_t)w.kb * ldy) + r4(Rp) + (size_t)(amp_round16(n.cl()) + 63) / 64 * 64;
         if (f <= avail) break;
       }
       if (w.kb < 16) return 0;
+      if (w.role == ROLE_RNN_CELL) {
+        // the lookup's gradient accumulator beside the cell's weights, if it fits (worker aux = 1)
+        const size_t lkg = r4((size_t)c->dims.vocab * c->dims.emb);
+        w.aux = f + lkg <= avail ? 1 : 0;
+        if (w.aux) f += lkg;
+      }
       break;
     }
     case ROLE_TREE_OUT: {

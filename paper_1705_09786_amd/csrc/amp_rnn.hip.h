@@ -56,6 +56,10 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
   const int CMW = ((amp_round16(t.Cl) + 63) >> 6) << 6;
   LDSQ int* rowmap = (LDSQ int*)L.take(t.Rp);
   LDSQ int* colmap = (LDSQ int*)L.take(CMW);
+  // The lookup's accumulated gradient (vocab x emb) stays in LDS when the host found room for it (worker aux = 1):
+  // adding a batch's rows to it in HBM is a fetch and a store behind each other in every batch with backward messages.
+  const bool g_lds = uni(W->aux) != 0;
+  LDSQ float* Gk = (LDSQ float*)L.take(g_lds ? V * E : 0);
   tile_load(nd, t, Wg, bg);
   for (int i = threadIdx.x; i < yfloats; i += AMP_THREADS) Y[i] = 0.f;
   for (int i = threadIdx.x; i < t.Rp; i += AMP_THREADS) rowmap[i] = i < R ? t.grow(i) : -1;
@@ -63,6 +67,8 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
   GQ float* ndG = uni_gq<float>(nd.G);
   GQ float* lkP = uni_gq<float>(lk.P);
   GQ float* lkG = uni_gq<float>(lk.G);
+  if (g_lds)
+    for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) Gk[i] = lkG[i];
   // bias gradient of row threadIdx.x accumulated since the last update (rests in HBM between launches)
   float accb = ((int)threadIdx.x < R && nd.has_bias) ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
   BatchMsg& M = s_M;
@@ -189,6 +195,19 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
       tree_bwd_mfma<true, NRBT, NCGT>(Wl, t, Y, M, nB, obase);
       // the lookup's gradient: rows of de added to their tokens' rows in arrival order
       __syncthreads();
+      if (g_lds) {
+        // column c of every row belongs to thread c: no other thread touches it
+        for (int c = threadIdx.x; c < E; c += AMP_THREADS)
+          for (int k0 = 0; k0 < nB; k0 += 16) {
+            const int kc = nB - k0 < 16 ? nB - k0 : 16;
+            float d[16];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) d[k] = B.de[(k < kc ? k0 + k : k0) * SP + c];
+#pragma unroll
+            for (int k = 0; k < 16; ++k)
+              if (k < kc) Gk[M.a[M.bidx[k0 + k]] * E + c] += d[k];
+          }
+      } else
       for (int c = threadIdx.x; c < E; c += AMP_THREADS)
         for (int k0 = 0; k0 < nB; k0 += 16) {
           // sixteen rows at a time, all fetches in flight together; a token seen earlier in the chunk continues
@@ -254,10 +273,16 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
       lstep++;
       if (threadIdx.x == 0) note_update(D);
       const float sc = lk.lr * (lk.mean ? 1.f / (float)lcount : 1.f);
-      for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) {
-        lkP[i] -= sc * lkG[i];
-        lkG[i] = 0.f;
-      }
+      if (g_lds)
+        for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) {
+          lkP[i] -= sc * Gk[i];
+          Gk[i] = 0.f;
+        }
+      else
+        for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) {
+          lkP[i] -= sc * lkG[i];
+          lkG[i] = 0.f;
+        }
       lcount = 0;
       LOG(0, 2, 0, 0);
     }
@@ -265,6 +290,8 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
     PHASE(7);
   }
   tile_store(nd, t, Wg, bg);
+  if (g_lds)
+    for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) lkG[i] = Gk[i];
   if ((int)threadIdx.x < R && nd.has_bias) ndG[(long long)nd.rows * t.C + threadIdx.x] = accb;
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
