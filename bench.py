@@ -34,8 +34,8 @@ FP32_MFMA_PEAK = 157.3e12          # whole chip, dense fp32 matrix
 # HBM bytes per launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a copy of known size (the summaries
 # under profiles/); only quoted for exactly the configuration (workload, max_active_keys, min_update_frequency,
 # instances) that was profiled.
-MEASURED_HBM_BYTES_PER_LAUNCH = {(3, 64, 50, 8544): 48.1e9, (2, 16, 16, 10000): 2.33e9, (4, 32, 20, 20000): 43.9e9,
-                                 (5, 128, 50, 8544): 2.60e12}
+MEASURED_HBM_BYTES_PER_LAUNCH = {(3, 64, 50, 8544): 47.1e9, (2, 16, 16, 10000): 1.90e9, (4, 32, 20, 20000): 43.8e9,
+                                 (5, 128, 50, 8544): 2.59e12}
 
 DEFAULTS = {
     # cfg: mak, muf, lookup muf, optimizer
