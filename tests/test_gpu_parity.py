@@ -144,6 +144,7 @@ TREE_ODD = dict(vocab=97, emb=50, hidden=37, n_class=5)
     (synth.DEFAULT_DIMS["tree"], None, 64, 7, 333, ADAM, 96),
     (TREE_ODD, {1: 3, 2: 5}, 8, 3, 5, SGD, 64),
     (TREE_ODD, {1: 1, 2: 1}, 8, 3, 5, ADAM, 64),
+    (TREE_ODD, {1: 2, 2: 3}, 8, 4, 5, dict(kind="momentum", lr=0.02, momentum=0.9), 64),
 ])
 def test_tree_replay_parity(dims, tiles, mak, muf, lmuf, opt, n):
     data = synth.make_tree(n, 21, dims)
