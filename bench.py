@@ -34,14 +34,17 @@ FP32_MFMA_PEAK = 157.3e12          # whole chip, dense fp32 matrix
 # HBM bytes per launch, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a copy of known size (the summaries
 # under profiles/); only quoted for exactly the configuration (workload, max_active_keys, min_update_frequency,
 # instances) that was profiled.
-MEASURED_HBM_BYTES_PER_LAUNCH = {(3, 64, 50, 8544): 47.1e9, (2, 16, 16, 10000): 1.90e9, (4, 32, 20, 20000): 43.8e9,
+MEASURED_HBM_BYTES_PER_LAUNCH = {(3, 64, 50, 8544): 70.5e9, (2, 16, 16, 10000): 1.90e9, (4, 32, 20, 20000): 43.8e9,
                                  (5, 128, 50, 8544): 2.59e12}
 
 DEFAULTS = {
     # cfg: mak, muf, lookup muf, optimizer
     1: dict(mak=4, muf=1, lmuf=None, opt=("sgd", dict(lr=0.05))),
     2: dict(mak=16, muf=16, lmuf=16, opt=("sgd", dict(lr=0.05))),
-    3: dict(mak=64, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.05))),
+    # 8 leaf + 16 branch tiles: the single model's best rate (37k trees/s on 27 workgroups); the fewest tiles that
+    # fit LDS (5 + 8, 16 workgroups, 30k trees/s) use each CU better and are what the replicated run packs two per XCD
+    3: dict(mak=64, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.05)), tiles={1: 8, 2: 16}, replica_tiles={1: 5, 2: 8},
+            replica_workers=16),
     4: dict(mak=32, muf=20, lmuf=20, opt=("adam", dict(lr=0.001))),
     5: dict(mak=128, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.02)), tiles={1: 16, 2: 64}),
 }
@@ -201,7 +204,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": NAMES[args.config], "instances": n, "max_active_keys": cfg["mak"],
                    "min_update_frequency": cfg["muf"], "lookup_min_update_frequency": cfg["lmuf"],
-                   "optimizer": cfg["opt"][0], "workgroups": n_workers},
+                   "optimizer": cfg["opt"][0], "workgroups": n_workers,
+                   "tiles": {"leaf": cfg["tiles"][1], "branch": cfg["tiles"][2]} if cfg.get("tiles") else None},
         "kernel_ms_per_step": 1e3 * kern,
         "kernel_instances_per_s": n / kern,
         "train_loss": stats["mean_loss"], "train_accuracy": stats["accuracy"],
@@ -215,12 +219,15 @@ def main():
     # Beside the headline (one copy of the model, as the configuration names it): the paper's own way to use more
     # of the machine -- every parameterized node replicated, instances dealt round-robin to the replicas, parameters
     # averaged at the end of each epoch (Section 5).  A different training procedure, so reported apart from `value`.
-    fit = 8 * (32 // n_workers) if n_workers <= 32 else 240 // n_workers   # whole replicas per 32-CU XCD
+    rep_tiles = cfg.get("replica_tiles", cfg.get("tiles"))
+    rep_workers = cfg.get("replica_workers", n_workers)
+    fit = 8 * (32 // rep_workers) if rep_workers <= 32 else 240 // rep_workers   # whole replicas per 32-CU XCD
     R = args.replicas if args.replicas is not None else min(64, fit, len(data) // (4 * cfg["mak"]))
     if R > 1:
         tr.close()
-        tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=(48 if args.config == 5 else 24) << 30, tiles=cfg.get("tiles"),
+        tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=(48 if args.config == 5 else 24) << 30, tiles=rep_tiles,
                             replicas=R)
+        assert tr.amp.num_workers() == R * rep_workers
         a = tr.amp
         a.set_min_update_frequency(-1, cfg["muf"])
         if cfg["lmuf"]:
@@ -237,7 +244,7 @@ def main():
         rk = a.get_loss()["seconds"]
         rach = (flops if bound == "mfma" else lds_bytes) * args.steps / rk / (1e12 if bound == "mfma" else 1e9)
         out["replicated"] = {"replicas": R, "value": n * args.steps / rwall, "unit": "instances/s",
-                             "kernel_instances_per_s": n * args.steps / rk, "workgroups": R * n_workers,
+                             "kernel_instances_per_s": n * args.steps / rk, "workgroups": R * rep_workers,
                              "max_active_keys_per_replica": cfg["mak"], "parameter_averaging": "end of every epoch",
                              "roofline_frac_whole_chip": rach / peak_chip, "train_loss": a.get_loss()["mean_loss"]}
     # The published peaks above are what `roofline.peak` quotes; the rates this chip actually reaches on the two

@@ -31,8 +31,8 @@ __device__ __forceinline__ void fence_acquire() { __builtin_amdgcn_fence(__ATOMI
 // The barrier in front of a post.  __syncthreads() does not wait for a wave's outstanding HBM stores (at
 // workgroup scope the compiler emits no wait for them: the waves of a workgroup share one L1), and the posting
 // wave's release fence writes back the L2 as it stands and waits for its own wave's accesses only -- a store of
-// another wave still on its way would miss the write-back and the receiver would read the old value (seen as a
-// rare wrong parameter in the parity tests).  So every wave first waits until its own stores have reached the L2.
+// another wave still on its way would miss the write-back and the receiver would read the old value.  So every
+// wave first waits until its own stores have reached the L2.
 __device__ __forceinline__ void publish_barrier() {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();

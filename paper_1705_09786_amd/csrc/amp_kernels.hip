@@ -350,17 +350,22 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
     case ROLE_TREE_LOOKUP: role_tree_lookup(D, W); break;
     case ROLE_TREE_LEAF:
     case ROLE_TREE_BRANCH: {
-      // the benchmark shape (six 16-row blocks, nineteen 16-column groups per tile) has its own instantiation
+      // hidden 150 / embedding 300 (nineteen 16-column groups) split into tiles of six, four or three 16-row blocks
+      // (5 + 8 tiles, the fewest that fit LDS; 8 leaf tiles; 16 branch tiles) has instantiations with fixed trip counts
       const GQ NodeDev& nd = D->node[W->node];
       const int rp = amp_round16(nd.nblocks * W->nu), cl = (nd.cols / nd.seg) * nd.segp;
-      const bool fixed = rp == 96 && amp_round16(cl) == 304;
+      const bool c19 = amp_round16(cl) == 304;
       if (W->role == ROLE_TREE_LEAF) {
         if (W->aux) role_tree_cell<false, 0, 0, true>(D, W);
-        else if (fixed) role_tree_cell<false, 6, 19, false>(D, W);
+        else if (c19 && rp == 96) role_tree_cell<false, 6, 19, false>(D, W);
+        else if (c19 && rp == 64) role_tree_cell<false, 4, 19, false>(D, W);
+        else if (c19 && rp == 48) role_tree_cell<false, 3, 19, false>(D, W);
         else role_tree_cell<false, 0, 0, false>(D, W);
       } else {
         if (W->aux) role_tree_cell<true, 0, 0, true>(D, W);
-        else if (fixed) role_tree_cell<true, 6, 19, false>(D, W);
+        else if (c19 && rp == 96) role_tree_cell<true, 6, 19, false>(D, W);
+        else if (c19 && rp == 64) role_tree_cell<true, 4, 19, false>(D, W);
+        else if (c19 && rp == 48) role_tree_cell<true, 3, 19, false>(D, W);
         else role_tree_cell<true, 0, 0, false>(D, W);
       }
       break;

@@ -20,7 +20,8 @@ def _trainer(cfgi, lr=None, log=False, replicas=1):
     fp = synth.init_params(model, dims, 100 + cfgi)
     ml, me = runner.max_len_of(model, data)
     tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data),
-                        arena_bytes=(20 if cfgi == 5 else 24 if replicas > 1 else 4) << 30, tiles=cfg.get("tiles"),
+                        arena_bytes=(20 if cfgi == 5 else 24 if replicas > 1 else 4) << 30,
+                        tiles=cfg.get("replica_tiles", cfg.get("tiles")) if replicas > 1 else cfg.get("tiles"),
                         replicas=replicas)
     a = tr.amp
     a.set_watchdog(20.0)

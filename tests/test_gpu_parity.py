@@ -26,7 +26,10 @@ SGD = dict(kind="sgd", lr=0.05)
 ADAM = dict(kind="adam", lr=0.0005, beta1=0.9, beta2=0.999, eps=1e-6)
 
 
-@pytest.mark.parametrize("mak,muf,opt", [(1, 1, SGD), (4, 1, SGD), (4, 3, ADAM), (8, 5, dict(kind="momentum", lr=0.02, momentum=0.9))])
+# Momentum 0.9 at lr = 0.02 is an unstable training run on this task (losses spike to twice their initial value):
+# under some event orders the checker's own replay, started 1e-7 away, ends 8 % away -- and so does the GPU.  At
+# lr = 0.005 the same replay stays at 1e-7 (checked on the CPU in test_oracle_models.py).
+@pytest.mark.parametrize("mak,muf,opt", [(1, 1, SGD), (4, 1, SGD), (4, 3, ADAM), (8, 5, dict(kind="momentum", lr=0.005, momentum=0.9))])
 def test_mlp_replay_parity(mak, muf, opt):
     model, dims, data = synth.workload(1)
     fp = synth.init_params(model, dims, 5)
@@ -142,9 +145,10 @@ TREE_ODD = dict(vocab=97, emb=50, hidden=37, n_class=5)
     (TREE_SMALLVOCAB, None, 1, 1, 1, SGD, 16),
     (synth.DEFAULT_DIMS["tree"], None, 16, 50, 1000, SGD, 96),
     (synth.DEFAULT_DIMS["tree"], None, 64, 7, 333, ADAM, 96),
+    (synth.DEFAULT_DIMS["tree"], {1: 8, 2: 16}, 32, 50, 1000, SGD, 96),   # the benchmark's tiling: tiles of 4 and 3 row blocks
     (TREE_ODD, {1: 3, 2: 5}, 8, 3, 5, SGD, 64),
     (TREE_ODD, {1: 1, 2: 1}, 8, 3, 5, ADAM, 64),
-    (TREE_ODD, {1: 2, 2: 3}, 8, 4, 5, dict(kind="momentum", lr=0.02, momentum=0.9), 64),
+    (TREE_ODD, {1: 2, 2: 3}, 8, 4, 5, dict(kind="momentum", lr=0.005, momentum=0.9), 64),
 ])
 def test_tree_replay_parity(dims, tiles, mak, muf, lmuf, opt, n):
     data = synth.make_tree(n, 21, dims)

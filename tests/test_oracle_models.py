@@ -441,3 +441,23 @@ def test_rnn_adam_parity_setting_is_well_conditioned(mak, muf, lr):
         res.append([amp.C.pack_node(n.P) for n in rt.ppt])
     for a, b in zip(*res):
         assert np.linalg.norm(a - b) / np.linalg.norm(a) < 1e-6
+
+
+def test_mlp_momentum_parity_setting_is_well_conditioned():
+    """The same for the MLP's momentum case (max_active_keys 8, min_update_frequency 5, momentum 0.9): at lr = 0.02
+    the training run is unstable (losses spike to twice their initial value) and, under some event orders the GPU
+    takes, a 1e-7 perturbation of the checker's own initial parameters ends 8 % away; at lr = 0.005 it stays at
+    1e-7, and that is what the parity case uses."""
+    model, dims, data = synth.workload(1)
+    fp = synth.init_params(model, dims, 5)
+    rng = np.random.default_rng(1)
+    fp2 = [(p * (1 + 1e-7 * rng.standard_normal(p.shape))).astype(np.float32) for p in fp]
+    res = []
+    for f in (fp, fp2):
+        rt = amp.Runtime(model, dims, f)
+        rt.set_muf(5)
+        rt.set_optimizer(kind="momentum", lr=float(np.float32(0.005)), momentum=float(np.float32(0.9)))
+        rt.run(data, 8)
+        res.append([amp.C.pack_node(n.P) for n in rt.ppt])
+    for a, b in zip(*res):
+        assert np.linalg.norm(a - b) / np.linalg.norm(a) < 1e-6

@@ -83,16 +83,15 @@ def rel_err(a, b):
 
 
 def compare(gpu, rt, n_adm, tol=RTOL):
-    worst = 0.0
-    for k, node in enumerate(rt.ppt):
-        ref = oamp.C.pack_node(node.P)
-        e = rel_err(gpu["params"][k], ref)
-        worst = max(worst, e)
-        assert e <= tol, ("params", node.name, e)
+    errs = {node.name: rel_err(gpu["params"][k], oamp.C.pack_node(node.P)) for k, node in enumerate(rt.ppt)}
     ref_loss = np.array([rt.loss[s] for s in range(n_adm)])
     le = np.abs(gpu["losses"] - ref_loss) / np.maximum(np.abs(ref_loss), 1.0)
-    assert le.max() <= tol, ("loss", int(le.argmax()), float(le.max()))
-    return worst, float(le.max())
+    off = np.flatnonzero(le > tol)
+    # everything a failure needs in one message: every tensor's error and where the losses part ways
+    report = dict(params=errs, loss_max=float(le.max()), first_loss_off=int(off[0]) if len(off) else None, n_loss_off=len(off))
+    assert max(errs.values()) <= tol, report
+    assert le.max() <= tol, report
+    return max(errs.values()), float(le.max())
 
 
 def check_controller_log(logs, mak, n_adm):
