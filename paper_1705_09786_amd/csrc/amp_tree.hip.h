@@ -180,11 +180,13 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
   const GQ int* tokens = (const GQ int*)D->data.tok;
   for (unsigned k = threadIdx.x; k < count; k += AMP_THREADS) pend_tok[k] = keep[k];
   __syncthreads();
-  for (;;) {
-    const int n = wait_batch(D, mine, head, KB, lk_muf - (int)count, s_codes, &s_n, code_is_b);
-    if (n == 0) break;
-    if (threadIdx.x < 64) {
-      const int k = threadIdx.x;
+  // Wave 1 takes and decodes the next batch while wave 0 is still publishing the present one (wave 0 keeps what its
+  // posts need in registers, so the batch's LDS record is free from the publish barrier on).
+  const int wave = threadIdx.x >> 6;
+  auto take_batch = [&](int room) {
+    const int n = poll_batch(D, mine, head, KB, room, s_codes, &s_n, code_is_b);
+    if (n > 0) {
+      const int k = threadIdx.x & 63;
       if (k < n) {
         const unsigned code = s_codes[k];
         const int s = MSG_SLOT(code), l = MSG_LOCAL(code);
@@ -206,7 +208,14 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
         pend_tok[count + b] = M.a[k];
       }
     }
-    lds_barrier();
+  };
+  if (wave == 1) take_batch(lk_muf - (int)count);
+  lds_barrier();
+  for (;;) {
+    const int n = s_n;
+    if (n == 0) break;
+    head += n;
+    const int nB = M.nB;
     if ((E & 3) == 0) {
       // forward: table row -> xin; backward: sum of the leaf tiles' partials -> pending gradient row
       for (int idx = threadIdx.x; idx < n * E4; idx += AMP_THREADS) {
@@ -216,7 +225,14 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
         } else {
           const GQ float* gx = B.gx + B.leaf(M.s[k], M.n[k]) * B.TL * Ep + c;
           v4f a = {0.f, 0.f, 0.f, 0.f};
-          for (int t = 0; t < B.TL; ++t) a += *(const GQ v4f*)(gx + t * Ep);
+          for (int t0 = 0; t0 < B.TL; t0 += 16) {   // sixteen parts in flight at a time, added in tile order
+            v4f p[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) p[u] = *(const GQ v4f*)(gx + (t0 + u < B.TL ? t0 + u : B.TL - 1) * Ep);
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+              if (t0 + u < B.TL) a += p[u];
+          }
           *(GQ v4f*)(prow + (long long)(count + M.b[k]) * E + c) = a;
         }
       }
@@ -233,19 +249,25 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
         }
       }
     }
+    // what lane k of wave 0 needs of message k for its post, before the batch's record is given up
+    int js = 0, jn = 0, jaux = 0;
+    if (threadIdx.x < 64 && (int)threadIdx.x < n) {
+      js = M.s[threadIdx.x];
+      jn = M.n[threadIdx.x];
+      jaux = M.aux[threadIdx.x];
+    }
     publish_barrier();
     if (threadIdx.x < 64) {
       fence_release();
-      const int k = threadIdx.x;
-      if (k < n) {
-        if (!M.aux[k]) {
-          ring_post(wr.leaf, MSG_MAKE(0, M.s[k], M.n[k]));
+      if ((int)threadIdx.x < n) {
+        if (!jaux) {
+          ring_post(wr.leaf, MSG_MAKE(0, js, jn));
         } else if (wr.train) {
-          if (atomicSub(&left_cnt[M.s[k]], 1) == 1) ring_post(wr.ctl, MSG_MAKE(1, M.s[k], 0));
+          if (atomicSub(&left_cnt[js], 1) == 1) ring_post(wr.ctl, MSG_MAKE(1, js, 0));
         }
       }
     }
-    count += M.nB;
+    count += nB;
     if ((int)count >= lk_muf) {
       // SGD on the touched rows: each waiting gradient row is subtracted from its
       // token's row, in arrival order (rows never touched have a zero gradient)
@@ -279,9 +301,12 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
         }
       }
       count = 0;
-      if (threadIdx.x == 0) log_event(D, W, &s_logn, 0, 2, 0, 0);
+      lds_barrier();   // every wave has finished with the token list before wave 1 starts the next one
+      // recorded by the wave that records the next batch's events, so that the update comes first
+      if (threadIdx.x == 64) log_event(D, W, &s_logn, 0, 2, 0, 0);
     }
-    __syncthreads();
+    if (wave == 1) take_batch(lk_muf - (int)count);
+    lds_barrier();
   }
   __syncthreads();
   if (threadIdx.x == 0) {
