@@ -129,9 +129,24 @@ class NPT(Node):
         super().__init__(name)
         self.fwd, self.bwd = fwd, bwd
         self.stash = {}
+        # A transform with a kink at zero (ReLU) takes a yes / no decision on every input element, and an input
+        # within rounding of zero can fall either way in another precision or summation order.  With kink_tau set,
+        # every decision on an input with |x| < kink_tau is listed in `kinks` as (state, element), and the ones
+        # named in `flip` are recorded the other way round for the backward pass (the output, within kink_tau
+        # of zero either way, is left as it is).  Parity tests use this to accept either decision.
+        self.kink_tau = None
+        self.kinks = []
+        self.flip = set()
 
     def forward(self, rt, port, msg):
         y, cache = self.fwd(msg.payload)
+        if self.kink_tau is not None:
+            x = np.asarray(msg.payload)
+            for i in np.flatnonzero(np.abs(x) < self.kink_tau):
+                self.kinks.append((msg.state, int(i)))
+                if (msg.state, int(i)) in self.flip:
+                    cache = np.array(cache, copy=True)
+                    cache[i] = self.kink_tau if x[i] <= 0 else -self.kink_tau
         self.stash[msg.state] = cache
         rt.emit_fwd(self, 0, Msg(y, msg.state))
 

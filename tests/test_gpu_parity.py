@@ -9,7 +9,7 @@ from paper_1705_09786_amd import synth
 
 from oracle import amp as oamp
 
-from util import check_controller_log, compare, gpu_train, named_logs, oracle_replay, oracle_runtime, rel_err
+from util import check_controller_log, compare, compare_up_to_relu_decisions, gpu_train, named_logs, oracle_replay, oracle_runtime, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -26,17 +26,16 @@ SGD = dict(kind="sgd", lr=0.05)
 ADAM = dict(kind="adam", lr=0.0005, beta1=0.9, beta2=0.999, eps=1e-6)
 
 
-# Momentum 0.9 at lr = 0.02 is an unstable training run on this task (losses spike to twice their initial value):
-# under some event orders the checker's own replay, started 1e-7 away, ends 8 % away -- and so does the GPU.  At
-# lr = 0.005 the same replay stays at 1e-7 (checked on the CPU in test_oracle_models.py).
+# Momentum 0.9 at lr = 0.02 is an unstable training run on this task (losses spike to twice their initial value);
+# at lr = 0.005 a 1e-7 perturbation stays at 1e-7 (checked on the CPU in test_oracle_models.py).  The MLP's ReLUs
+# make one more thing necessary: see compare_up_to_relu_decisions.
 @pytest.mark.parametrize("mak,muf,opt", [(1, 1, SGD), (4, 1, SGD), (4, 3, ADAM), (8, 5, dict(kind="momentum", lr=0.005, momentum=0.9))])
 def test_mlp_replay_parity(mak, muf, opt):
     model, dims, data = synth.workload(1)
     fp = synth.init_params(model, dims, 5)
     g = gpu_train(model, dims, fp, data, mak, muf, opt)
     check_controller_log(g["logs"], mak, len(data))
-    rt = oracle_replay(model, dims, fp, data, g["logs"], muf, opt)
-    compare(g, rt, len(data))
+    compare_up_to_relu_decisions(model, dims, fp, data, g, muf, opt)
 
 
 def test_mlp_mak1_is_synchronous_sgd():

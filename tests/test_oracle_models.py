@@ -445,9 +445,8 @@ def test_rnn_adam_parity_setting_is_well_conditioned(mak, muf, lr):
 
 def test_mlp_momentum_parity_setting_is_well_conditioned():
     """The same for the MLP's momentum case (max_active_keys 8, min_update_frequency 5, momentum 0.9): at lr = 0.02
-    the training run is unstable (losses spike to twice their initial value) and, under some event orders the GPU
-    takes, a 1e-7 perturbation of the checker's own initial parameters ends 8 % away; at lr = 0.005 it stays at
-    1e-7, and that is what the parity case uses."""
+    the training run is unstable (losses spike to twice their initial value); at lr = 0.005, which the parity
+    case uses, a 1e-7 perturbation stays at 1e-7."""
     model, dims, data = synth.workload(1)
     fp = synth.init_params(model, dims, 5)
     rng = np.random.default_rng(1)
@@ -461,3 +460,33 @@ def test_mlp_momentum_parity_setting_is_well_conditioned():
         res.append([amp.C.pack_node(n.P) for n in rt.ppt])
     for a, b in zip(*res):
         assert np.linalg.norm(a - b) / np.linalg.norm(a) < 1e-6
+
+
+def test_relu_decision_hook():
+    """The checker's ReLU lists its decisions on inputs within kink_tau of zero and records the ones named in
+    `flip` the other way round for the backward pass; everything else is untouched."""
+    class Catch:
+        def __init__(self):
+            self.f, self.b = [], []
+
+        def emit_fwd(self, node, port, msg):
+            self.f.append(msg.payload)
+
+        def emit_bwd(self, node, port, msg):
+            self.b.append(msg.payload)
+
+    x = np.array([1e-9, -1e-9, 0.5, -0.5])
+    dy = np.array([2.0, 3.0, 4.0, 5.0])
+    for flip, want in ((set(), [2.0, 0.0, 4.0, 0.0]), ({((7,), 0)}, [0.0, 0.0, 4.0, 0.0]), ({((7,), 1)}, [2.0, 3.0, 4.0, 0.0])):
+        node = amp.NPT("relu1", amp.C.relu_fwd, amp.C.relu_bwd)
+        node.kink_tau, node.flip = 1e-6, flip
+        rt = Catch()
+        node.forward(rt, 0, amp.Msg(x, (7,)))
+        node.backward(rt, 0, amp.Msg(dy, (7,)))
+        assert node.kinks == [((7,), 0), ((7,), 1)]
+        assert np.array_equal(rt.f[0], np.maximum(x, 0.0))
+        assert np.array_equal(rt.b[0], np.array(want))
+    plain = amp.NPT("relu1", amp.C.relu_fwd, amp.C.relu_bwd)
+    rt = Catch()
+    plain.forward(rt, 0, amp.Msg(x, (7,)))
+    assert plain.kinks == []

@@ -62,9 +62,14 @@ def named_logs(model, dims, logs):
     return [[(names[n], k, s, l) for (n, k, s, l) in w] for w in logs]
 
 
-def oracle_replay(model, dims, fp, data, logs, muf, opt, lookup_muf=None):
+def oracle_replay(model, dims, fp, data, logs, muf, opt, lookup_muf=None, kink_tau=None, flips=()):
     names = [sh[0] for sh in synth.param_shapes(model, dims)]
     rt = oamp.Runtime(model, dims, fp)
+    if kink_tau is not None:
+        for node in rt.nodes:
+            if isinstance(node, oamp.NPT) and node.name.startswith("relu"):
+                node.kink_tau = kink_tau
+                node.flip = {(state, i) for (name, state, i) in flips if name == node.name}
     rt.set_muf(muf)
     if lookup_muf is not None:
         rt.set_muf(lookup_muf, "lookup")
@@ -107,3 +112,33 @@ def check_controller_log(logs, mak, n_adm):
         assert 0 <= active <= mak
     assert adm == list(range(n_adm))
     assert active == 0
+
+
+# |pre-activation| below which a ReLU decision may fall either way: a 128-term fp32 dot product of O(1) terms is
+# good to about 1e-6 absolute, and the kernel sums in another order than the checker.
+RELU_TAU = 3e-6
+
+
+def compare_up_to_relu_decisions(model, dims, fp, data, gpu, muf, opt, max_flips=6):
+    """Replay parity for a model with ReLUs.  A pre-activation within rounding of zero is a yes / no decision that
+    fp32 on the GPU and fp64 in the checker may take differently; the whole gradient of that unit then differs and
+    no tolerance covers it.  Both decisions are correct, so the check is: some assignment of the (few) decisions
+    the checker itself marks as ambiguous (|x| < RELU_TAU) reproduces the GPU's result to the usual tolerance.  The
+    search is greedy: replay, and while the results differ, reverse the ambiguous decision closest before the
+    first instance whose loss differs."""
+    flips = []
+    report = None
+    for _ in range(max_flips + 1):
+        rt = oracle_replay(model, dims, fp, data, gpu["logs"], muf, opt, kink_tau=RELU_TAU, flips=flips)
+        try:
+            return compare(gpu, rt, len(data)) + (len(flips),)
+        except AssertionError as e:
+            report = e.args[0]
+        kinks = [(node.name, state, i) for node in rt.nodes if isinstance(node, oamp.NPT) for (state, i) in node.kinks]
+        cands = [k for k in kinks if k not in flips]
+        first = report["first_loss_off"] if report["first_loss_off"] is not None else len(data)
+        before = [k for k in cands if k[1][0] <= first]
+        if not before:
+            break
+        flips.append(max(before, key=lambda k: k[1][0]))
+    raise AssertionError(dict(report, ambiguous_relu_decisions_reversed=flips))
