@@ -222,7 +222,7 @@ def main():
     rep_tiles = cfg.get("replica_tiles", cfg.get("tiles"))
     rep_workers = cfg.get("replica_workers", n_workers)
     fit = 8 * (32 // rep_workers) if rep_workers <= 32 else 240 // rep_workers   # whole replicas per 32-CU XCD
-    R = args.replicas if args.replicas is not None else min(64, fit, len(data) // (4 * cfg["mak"]))
+    R = args.replicas if args.replicas is not None else min(128, fit, len(data) // (4 * cfg["mak"]))
     if R > 1:
         tr.close()
         tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=(48 if args.config == 5 else 24) << 30, tiles=rep_tiles,

@@ -151,7 +151,8 @@ int amp_set_weights_in_hbm(amp_ctx *ctx, int node_id, int on);
  * copies of the whole pipeline train side by side, each with max_active_keys
  * instances in flight; at the end of every epoch each node's parameters are
  * set to the mean over its replicas (optimizer slots are not shared).  1
- * (default) = no replication.  Workers x replicas must not exceed the CUs.
+ * (default) = no replication; at most 128.  Workers x replicas must not exceed
+ * the CUs.
  * Evaluation uses the first replica.  Event records and worker statistics
  * list replica 0's workers first, then replica 1's, ...; `seq` counts
  * admissions per replica.  Only before amp_finalize. */

@@ -385,7 +385,7 @@ int amp_set_weights_in_hbm(amp_ctx* c, int node_id, int on) {
 int amp_set_replicas(amp_ctx* c, int n_replicas) {
   if (!c) return AMP_EINVAL;
   if (!c->model || c->finalized) return fail(c, AMP_ESTATE, "set_replicas: only between build and finalize");
-  if (n_replicas < 1 || n_replicas > 64) return fail(c, AMP_EINVAL, "set_replicas: 1..64 replicas");
+  if (n_replicas < 1 || n_replicas > 128) return fail(c, AMP_EINVAL, "set_replicas: 1..128 replicas");
   c->replicas = n_replicas;
   return AMP_OK;
 }

@@ -122,7 +122,7 @@ def test_replica_and_weight_placement_setters():
     expect(B.AMP_ESTATE, a.set_weights_in_hbm, 1, True)
     a.build("tree", dict(vocab=11, emb=8, hidden=6, n_class=3))
     expect(B.AMP_EINVAL, a.set_replicas, 0)
-    expect(B.AMP_EINVAL, a.set_replicas, 65)
+    expect(B.AMP_EINVAL, a.set_replicas, 129)
     expect(B.AMP_EINVAL, a.set_weights_in_hbm, 9, True)                # no such node
     expect(B.AMP_EUNSUPPORTED, a.set_weights_in_hbm, 0, True)          # the lookup
     expect(B.AMP_EUNSUPPORTED, a.set_weights_in_hbm, 3, True)          # the output layer
