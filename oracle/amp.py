@@ -435,6 +435,7 @@ class Runtime:
         self.pending_sources = {}
         self.retired = []
         self.loss, self.correct, self.npred, self.yhat = {}, {}, {}, {}
+        self.max_staleness, self.limit, self.updates_at = None, 1, {}
 
     # ---- graph construction helpers
     def add(self, node):
@@ -536,18 +537,36 @@ class Runtime:
             self.active -= 1
             self.retired.append(seq)
             self.events.append(("controller", "R", (seq, 0)))
+            if self.max_staleness is not None:
+                # staleness-bounded admission: the limit on the instances in flight moves by one with every
+                # retirement, up if the instance saw at most max_staleness updates per parameterized node
+                # during its life, down otherwise
+                seen = (sum(n.n_updates for n in self.ppt) - self.updates_at.pop(seq)) / float(len(self.ppt))
+                if seen > self.max_staleness:
+                    self.limit = max(1, self.limit - 1)
+                else:
+                    self.limit += 1
 
     # ---- driver 1: own schedule
-    def run(self, instances, mak, epochs=1, first_seq=0):
+    def run(self, instances, mak, epochs=1, first_seq=0, max_staleness=None):
         """Train on `instances` in order, `epochs` times; returns the list of
-        per-instance losses in admission order."""
+        per-instance losses in admission order.  The controller is the greedy
+        one (a new instance whenever fewer than mak are in flight) unless
+        max_staleness is given: then the number in flight has a limit of its
+        own in 1..mak, starting at 1 (Appendix B, MNIST, asks for a schedule
+        that keeps gradients from going stale at a high max_active_keys)."""
         self.instances = instances
         self.parked = None
         self.auto_update = True
+        self.max_staleness = max_staleness
+        self.limit = 1
+        self.updates_at = {}
         total = first_seq + len(instances) * epochs
         nxt = first_seq
         while True:
-            while self.active < mak and nxt < total:
+            while self.active < (mak if max_staleness is None else min(mak, self.limit)) and nxt < total:
+                if max_staleness is not None:
+                    self.updates_at[nxt] = sum(n.n_updates for n in self.ppt)
                 self.admit(nxt)
                 nxt += 1
             assert self.active <= mak

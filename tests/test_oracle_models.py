@@ -490,3 +490,33 @@ def test_relu_decision_hook():
     rt = Catch()
     plain.forward(rt, 0, amp.Msg(x, (7,)))
     assert plain.kinks == []
+
+
+def test_staleness_bounded_admission_in_the_checker():
+    """The controller's own limit on the instances in flight (Appendix B, MNIST).  Bound 0 keeps one instance in
+    flight once an update has happened and so repeats the max_active_keys = 1 run exactly; a bound nothing reaches
+    lets the limit rise to max_active_keys; in between the limit settles below max_active_keys and the measured
+    gradient staleness (Section 3) stays below the greedy controller's."""
+    model, dims, data = synth.workload(2, n=60)
+    fp = synth.init_params(model, dims, 6)
+
+    def run(mak, bound):
+        rt = amp.Runtime(model, dims, fp)
+        rt.set_muf(1)
+        rt.set_optimizer(kind="sgd", lr=0.05)
+        losses = rt.run(data, mak, max_staleness=bound)
+        worst = max(max(v) for v in rt.staleness().values() if v)
+        return rt, losses, worst
+
+    seq, seq_losses, _ = run(1, None)
+    b0, b0_losses, _ = run(16, 0.0)
+    assert b0.max_active_seen == 1 and b0_losses == seq_losses
+    for a, b in zip(seq.ppt, b0.ppt):
+        for k in a.P:
+            assert np.array_equal(a.P[k], b.P[k])
+    greedy, _, greedy_stale = run(16, None)
+    free, _, _ = run(16, 1e9)
+    assert greedy.max_active_seen == 16 and free.max_active_seen == 16 and free.limit >= 16
+    mid, _, mid_stale = run(16, 40.0)
+    assert 1 < mid.max_active_seen < 16
+    assert mid_stale < greedy_stale
