@@ -44,7 +44,7 @@ enum amp_status {
   AMP_EUNSUPPORTED = -6  /* valid request that this build cannot run */
 };
 
-/* The four model graphs of Sections 2 and 5 (Figures 2 and 4a). */
+/* The four model graphs of Sections 2, 4 and 6 (Figures 2 and 4a; the experiments' MLP and Tree-LSTM). */
 enum amp_model { AMP_MODEL_MLP = 1, AMP_MODEL_RNN = 2, AMP_MODEL_TREE = 3, AMP_MODEL_GGNN = 4 };
 
 /* Sizes of a model; fields a model does not use are ignored.
@@ -132,7 +132,7 @@ int amp_build_treelstm(amp_ctx *ctx, const amp_model_dims *dims);
 int amp_build_ggnn(amp_ctx *ctx, const amp_model_dims *dims);
 
 /* Splits a heavy node's rows over `n_tiles` workgroups that run in lockstep
- * (Section 5.1: a linear layer can be split into tiles computed in
+ * (Section 5: a linear layer can be split into tiles computed in
  * parallel).  1..64 tiles.  Only before amp_finalize; TREE leaf / branch
  * nodes only. */
 int amp_set_tiles(amp_ctx *ctx, int node_id, int n_tiles);

@@ -651,7 +651,7 @@ def _lookup(rt, flat, rows, cols, logkey=None):
 
 def build_mlp(rt, d, fp):
     """Controller -> Linear -> ReLU -> Linear -> ReLU -> Linear -> loss
-    (Section 5, MLP)."""
+    (Section 6, MLP paragraph)."""
     l1 = _lin(rt, "lin1", fp[0], d["hidden"], d["d_in"])
     l2 = _lin(rt, "lin2", fp[1], d["hidden"], d["hidden"])
     l3 = _lin(rt, "lin3", fp[2], d["n_class"], d["hidden"])
@@ -714,7 +714,7 @@ def _parent_tables(inst):
 
 def build_tree(rt, d, fp):
     """Binary Tree-LSTM with separate leaf and branch cells and a label at
-    every node (Section 5).  State = (instance, tree node).  A node's [h; c]
+    every node (Section 6, Tree-LSTM paragraph).  State = (instance, tree node).  A node's [h; c]
     is broadcast to the output layer and towards its parent, where the two
     children are concatenated, keyed on (instance, parent)."""
     H = d["hidden"]

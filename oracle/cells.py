@@ -10,10 +10,10 @@ where P is a dict of float64 arrays.  A payload is a vector, or a k-row matrix
 when several messages were grouped into one (Section 4, aggregation); a
 grouped payload yields one gradient, the sum over its rows.
 
-The paper gives the structure of the cells (Sections 2, 5 and Appendix C) but
+The paper gives the structure of the cells (Sections 2, 6 and Appendix C) but
 not their equations; the equations below are the standard ones for a linear
 layer, a tanh RNN, the binary Tree-LSTM split into a leaf and a branch cell
-(Section 5, Tree-LSTM paragraph) and the gated graph network's per-edge-type
+(Section 6, Tree-LSTM paragraph) and the gated graph network's per-edge-type
 linear message plus GRU update (Section 4 GNN description, Appendix C).
 """
 from __future__ import annotations

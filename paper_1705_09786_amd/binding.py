@@ -14,6 +14,8 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libamp.so")
+# the same sources built with -DAMP_STRICT_JOIN (explicitly ordered join completion), for attribution runs
+LIB_STRICT_PATH = os.path.join(_HERE, "libamp_strict.so")
 
 AMP_OK, AMP_EINVAL, AMP_ESTATE, AMP_ENOMEM, AMP_EFULL, AMP_EDEVICE, AMP_EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
 MODEL_MLP, MODEL_RNN, MODEL_TREE, MODEL_GGNN = 1, 2, 3, 4
@@ -95,21 +97,21 @@ SIGNATURES = {
                                      ct.POINTER(ct.c_double)]),
 }
 
-_lib = None
+_libs = {}
 
 
-def lib():
-    """The loaded C library (raises if it has not been built)."""
-    global _lib
-    if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise RuntimeError("libamp.so is not built: run `python -m paper_1705_09786_amd.build`")
-        l = ct.CDLL(LIB_PATH)
+def lib(strict: bool = False):
+    """The loaded C library (raises if it has not been built); strict = the build with ordered joins."""
+    if strict not in _libs:
+        path = LIB_STRICT_PATH if strict else LIB_PATH
+        if not os.path.exists(path):
+            raise RuntimeError("%s is not built: run `python -m paper_1705_09786_amd.build`" % os.path.basename(path))
+        l = ct.CDLL(path)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(l, name)
             fn.restype, fn.argtypes = res, args
-        _lib = l
-    return _lib
+        _libs[strict] = l
+    return _libs[strict]
 
 
 def measure_peaks(dev_ptr: int, nbytes: int, stream: int = 0):
@@ -171,8 +173,8 @@ class Amp:
     """One context of the C library.  `arena` is a device pointer (int) to
     `arena_bytes` bytes owned by the caller; `stream` a hipStream_t (int)."""
 
-    def __init__(self, arena: int, arena_bytes: int, stream: int = 0):
-        self.L = lib()
+    def __init__(self, arena: int, arena_bytes: int, stream: int = 0, strict: bool = False):
+        self.L = lib(strict)
         self.h = _ctxp()
         rc = self.L.amp_create(ct.byref(self.h), ct.c_void_p(arena), arena_bytes, ct.c_void_p(stream))
         if rc:

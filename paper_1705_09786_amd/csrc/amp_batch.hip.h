@@ -43,6 +43,9 @@ template <class R, class IsB>
 __device__ __forceinline__ int poll_batch(const GQ AmpDev* D, const R& r, unsigned head, int kmax, int room, unsigned* s_codes,
                                           int* s_n, IsB is_b) {
   {
+    // a node whose carried gradient count already reaches its threshold (the host refuses to lower a threshold that
+    // far) still cuts at the first backward message, so the pending list never grows past its end
+    if (room < 1) room = 1;
     const int lane = threadIdx.x & 63;
     const unsigned ticket = head + lane;
     GQ unsigned long long* slot = (GQ unsigned long long*)&r.ent[ticket & r.mask];

@@ -463,11 +463,28 @@ __device__ __forceinline__ void note_update(const GQ AmpDev* D) {
 // invalidates its caches before it reads.  (A fence here would be one more
 // L2 write-back and invalidation per join, and an XCD's L2 serves those one
 // at a time, 55-70 ns each: measured with 32 workgroups on one XCD.)
+//
+// That shortcut leans on how gfx950 implements agent-scope release (an L2
+// write-back that completes before the writer's atomic is issued); the HIP
+// memory model itself gives the receiver no happens-before edge to the other
+// parts' writes.  Built with -DAMP_STRICT_JOIN the completing arrival makes the
+// edge explicit: its read-modify-write acquires (and so synchronises with every
+// earlier arrival's release fence through the counter's release sequence) and a
+// release fence precedes the post.  The two builds must give the same results;
+// a parity test runs both.
 __device__ __forceinline__ bool join_arrive(GQ int* counter, int expect) {
+#ifdef AMP_STRICT_JOIN
+  const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_ACQ_REL, AGENT);
+  if (old + 1 != expect) return false;
+  __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, AGENT);
+  fence_release();
+  return true;
+#else
   const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, AGENT);
   if (old + 1 != expect) return false;
   __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, AGENT);
   return true;
+#endif
 }
 
 __device__ __forceinline__ bool join_arrive(int* counter, int expect) { return join_arrive((GQ int*)counter, expect); }

@@ -17,7 +17,7 @@
 // multiple of 16 floats plus, if needed, 4 more so that stride/4 is odd: rows
 // are then 16-byte aligned and both row-wise 16-byte reads and column-wise
 // 4-byte reads spread evenly over the LDS banks.
-#if defined(__HIPCC__) || defined(__CUDACC__)
+#if defined(__HIPCC__)
 #define AMP_HD __host__ __device__
 #else
 #define AMP_HD

@@ -130,6 +130,9 @@ int fail(amp_ctx* c, int code, const char* fmt, ...) {
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 
+// Everything replica r owns in the static part of the arena lies rep_stride bytes after replica r - 1's.
+char* rep_ptr(const amp_ctx* c, int r, size_t off) { return c->arena + (size_t)r * c->rep_stride + off; }
+
 HostNode make_node(const char* name, int rows, int cols, int has_bias, int nblocks = 1) {
   HostNode n;
   n.name = name;
@@ -583,6 +586,27 @@ int amp_set_min_update_frequency(amp_ctx* c, int node_id, int muf) {
   if (!c->model) return fail(c, AMP_ESTATE, "set_min_update_frequency: build a model first");
   if (muf < 1) return fail(c, AMP_EINVAL, "min_update_frequency must be >= 1");
   if (node_id < -1 || node_id >= (int)c->nodes.size()) return fail(c, AMP_EINVAL, "no node %d", node_id);
+  if (c->finalized && c->state_zeroed) {
+    // Gradients accumulated by earlier training calls stay with their node (Section 3: a node updates when its
+    // own count reaches the threshold).  A threshold at or below a carried count would have had to fire already:
+    // refuse it rather than let the count run past the threshold (and the pending-gradient list past its end).
+    for (int r = 0; r < c->replicas; ++r)
+      for (const HostWorker& w : c->workers) {
+        if (w.node < 0) continue;
+        unsigned st[4] = {0, 0, 0, 0};
+        HIPCHK(c, hipMemcpyAsync(st, rep_ptr(c, r, w.off_state), sizeof st, hipMemcpyDeviceToHost, c->stream));
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        // word 0: gradients held by the worker's node; word 2: by the lookup the recurrent cell's worker hosts
+        const int held[2] = {w.node, w.role == ROLE_RNN_CELL ? 0 : -1};
+        const unsigned cnt[2] = {st[0], st[2]};
+        for (int k = 0; k < 2; ++k)
+          if (held[k] >= 0 && (node_id < 0 || node_id == held[k]) && cnt[k] >= (unsigned)muf)
+            return fail(c, AMP_ESTATE,
+                        "set_min_update_frequency: node %d (%s) holds %u accumulated gradients; a threshold of %d would "
+                        "already have been reached -- choose a larger one, or train until the node has updated",
+                        held[k], c->nodes[held[k]].name.c_str(), cnt[k], muf);
+      }
+  }
   for (int i = 0; i < (int)c->nodes.size(); ++i)
     if (node_id < 0 || node_id == i) c->nodes[i].muf = muf;
   return AMP_OK;
@@ -921,9 +945,6 @@ int upload_set(amp_ctx* c, size_t& off, const InstSet& S, DataDev& dd) {
   if ((r = upload(c, off, S.tsk, (const void**)&dd.tsk))) return r;
   return AMP_OK;
 }
-
-// Everything replica r owns in the static part of the arena lies rep_stride bytes after replica r - 1's.
-char* rep_ptr(const amp_ctx* c, int r, size_t off) { return c->arena + (size_t)r * c->rep_stride + off; }
 
 // Puts set S into the arena at `begin`, dealt to R replicas: replica r gets instances r, r + R, r + 2R, ...
 int make_resident(amp_ctx* c, const InstSet& S, int R, size_t begin, Resident& res) {
@@ -1303,19 +1324,19 @@ int amp_get_staleness_hist(amp_ctx* c, uint64_t* bins, size_t nbins) {
   const size_t nn1 = c->nodes.size(), wpr = c->workers.size(), nn = nn1 * (size_t)c->last_replicas;
   std::vector<uint64_t> updates(nn, 0);
   std::vector<std::vector<std::pair<uint64_t, uint64_t>>> pending(nn);   // (key, updates at forward)
-  for (amp_event e : c->last_events) {
+  for (const amp_event& e : c->last_events) {
     if (e.worker % wpr == 0 || e.node >= nn1) continue;
-    e.node = (uint8_t)(e.node + nn1 * (e.worker / wpr));   // every replica has its own copy of the node
+    const size_t node = e.node + nn1 * (e.worker / wpr);   // every replica has its own copy of the node
     const uint64_t key = ((uint64_t)e.seq << 20) | e.local;
     if (e.kind == AMP_EV_U) {
-      updates[e.node]++;
+      updates[node]++;
     } else if (e.kind == AMP_EV_F) {
-      pending[e.node].push_back({key, updates[e.node]});
+      pending[node].push_back({key, updates[node]});
     } else if (e.kind == AMP_EV_B) {
-      auto& p = pending[e.node];
+      auto& p = pending[node];
       for (size_t i = 0; i < p.size(); ++i)
         if (p[i].first == key) {
-          const uint64_t st = updates[e.node] - p[i].second;
+          const uint64_t st = updates[node] - p[i].second;
           bins[std::min<uint64_t>(st, nbins - 1)]++;
           p[i] = p.back();
           p.pop_back();

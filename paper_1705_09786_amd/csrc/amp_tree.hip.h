@@ -1,4 +1,4 @@
-// Tree-LSTM workers (Section 5, Tree-LSTM paragraph): lookup, leaf cell,
+// Tree-LSTM workers (Section 6, Tree-LSTM paragraph): lookup, leaf cell,
 // branch cell, output layer with a softmax loss at every tree node.
 //
 // Leaf and branch cells are split over several workgroups ("tiles", Section

@@ -22,7 +22,7 @@ class Trainer:
 
     def __init__(self, model: str, dims: dict, params, max_active_keys: int, max_len: int, max_edges: int,
                  max_instances: int, arena_bytes: int = 1 << 30, tiles: dict | None = None, device: str = "cuda:0",
-                 in_hbm=(), replicas: int = 1):
+                 in_hbm=(), replicas: int = 1, strict: bool = False):
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the AMP path has no CPU fallback")
@@ -30,7 +30,7 @@ class Trainer:
         self.arena = torch.empty(arena_bytes + 256, dtype=torch.uint8, device=device)
         ptr = (self.arena.data_ptr() + 255) // 256 * 256
         stream = torch.cuda.current_stream(self.arena.device).cuda_stream
-        self.amp = B.Amp(ptr, arena_bytes, stream)
+        self.amp = B.Amp(ptr, arena_bytes, stream, strict=strict)
         self.model, self.dims = model, dims
         self.amp.build(model, dims)
         for node, n in (tiles or {}).items():

@@ -1,6 +1,6 @@
 """Seeded synthetic workloads and initial parameters.
 
-Stand-ins for the datasets the paper trains on (Section 5: MNIST, list
+Stand-ins for the datasets the paper trains on (Section 6: MNIST, list
 reduction, Stanford Sentiment Treebank, QM9), which are not available here.
 Shapes and sizes follow the paper's experiment descriptions; the items
 themselves are generated.  Everything is drawn from a counter-based Philox

@@ -81,7 +81,7 @@ def fused_tree_lstm(W, b, x, hl, cl, hr, cr):
 
 
 def test_leaf_branch_split_equals_fused_cell():
-    """Section 5: the leaf cell is the full cell with zero hidden states, the
+    """Section 6 (Tree-LSTM paragraph): the leaf cell is the full cell with zero hidden states, the
     branch cell is the full cell with zero input; they share no weights."""
     H, D = 3, 4
     W = RNG.standard_normal((5 * H, D + 2 * H))
