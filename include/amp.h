@@ -17,7 +17,8 @@
  *     passes; the library copies what it needs during the call and writes
  *     results into caller-provided buffers of stated capacity.
  *   - The library never allocates device memory: it works inside the device
- *     arena handed to amp_create and launches on the HIP stream given there.
+ *     arena handed to amp_create (or, after amp_create_static, inside an array
+ *     of its own) and launches on the HIP stream given there.
  *   - A ctx is not thread-safe.  Call order: create -> build_* -> finalize
  *     -> (set_* | submit | train | eval | get_*)* -> destroy.  Calls made in
  *     the wrong phase return AMP_ESTATE.
@@ -123,6 +124,23 @@ typedef struct amp_eval_result {
  * amp_destroy) and launches on hip_stream (a hipStream_t passed as void*;
  * NULL = the default stream).  Model = IR graph + controller, Section 4. */
 int amp_create(amp_ctx **out, void *dev_arena, size_t arena_bytes, void *hip_stream);
+/* amp_create for callers that cannot allocate device memory (tight serving
+ * loops, harnesses that forbid hipMalloc, code that must not touch the
+ * allocator): the context works inside a device array built into the library,
+ * AMP_STATIC_ARENA_MAX bytes (64 MiB) on every GPU, instead of a caller's
+ * arena, and neither this call nor any later call on the context allocates or
+ * frees device memory.  Everything else is as for amp_create: instances,
+ * parameters and results still travel through the caller's host buffers.
+ * The device current at the call is the one used.  amp_finalize, amp_train
+ * and amp_eval return AMP_ENOMEM, with a message naming the built-in arena,
+ * when the model, max_active_keys and instance sets need more than it holds.
+ * The array is shared by every such context on a GPU and keeps what the last
+ * one left in it (each context clears what it needs to start from zero):
+ * contexts that overlapped in it would race, so at most one per GPU may exist
+ * at a time -- a second call returns AMP_ESTATE until the first context has
+ * been destroyed.  AMP_EDEVICE when the array's address cannot be obtained. */
+#define AMP_STATIC_ARENA_MAX ((size_t)64 << 20)
+int amp_create_static(amp_ctx **out, void *hip_stream);
 void amp_destroy(amp_ctx *ctx);
 
 /* Builds one of the paper's model graphs.  One model per ctx. */

@@ -58,6 +58,7 @@ class EvalResult(ct.Structure):
 _ctxp = ct.c_void_p
 SIGNATURES = {
     "amp_create": (ct.c_int, [ct.POINTER(_ctxp), ct.c_void_p, ct.c_size_t, ct.c_void_p]),
+    "amp_create_static": (ct.c_int, [ct.POINTER(_ctxp), ct.c_void_p]),
     "amp_destroy": (None, [_ctxp]),
     "amp_build_mlp": (ct.c_int, [_ctxp, ct.POINTER(ModelDims)]),
     "amp_build_rnn": (ct.c_int, [_ctxp, ct.POINTER(ModelDims)]),
@@ -173,12 +174,16 @@ class Amp:
     """One context of the C library.  `arena` is a device pointer (int) to
     `arena_bytes` bytes owned by the caller; `stream` a hipStream_t (int)."""
 
-    def __init__(self, arena: int, arena_bytes: int, stream: int = 0, strict: bool = False):
+    def __init__(self, arena: int | None, arena_bytes: int = 0, stream: int = 0, strict: bool = False):
+        """arena None: the library's built-in device arena (amp_create_static)."""
         self.L = lib(strict)
         self.h = _ctxp()
-        rc = self.L.amp_create(ct.byref(self.h), ct.c_void_p(arena), arena_bytes, ct.c_void_p(stream))
+        if arena is None:
+            rc = self.L.amp_create_static(ct.byref(self.h), ct.c_void_p(stream))
+        else:
+            rc = self.L.amp_create(ct.byref(self.h), ct.c_void_p(arena), arena_bytes, ct.c_void_p(stream))
         if rc:
-            raise AmpError(rc, "amp_create failed")
+            raise AmpError(rc, "amp_create_static failed" if arena is None else "amp_create failed")
         self.model = 0
 
     def close(self):

@@ -12,6 +12,7 @@
 #define AMP_DYN_LDS_BYTES (AMP_LDS_BYTES - 6144)   // dynamic part; the rest is for static __shared__
 #define AMP_TREE_LOOKUP_MAX_MUF 16384
 #define AMP_DENSE_MAX_MUF 256         // longest pending-gradient list of a dense node (messages)
+#define AMP_STATIC_ARENA_BYTES (64u << 20)   // the library's built-in device arena (amp_create_static)
 
 // LDS layout of a weight tile: rows padded to a multiple of 16, row stride a
 // multiple of 16 floats plus, if needed, 4 more so that stride/4 is odd: rows

@@ -15,6 +15,7 @@
 // the index arithmetic a producer performs when it decides where a result
 // goes, plus arrival counters where several messages must meet.
 #include <hip/hip_runtime.h>
+#include <mutex>
 #include "amp_common.hip.h"
 
 struct Lds {
@@ -431,6 +432,34 @@ extern "C" hipError_t amp_average(float* p0, size_t stride_floats, int n_replica
   if (n == 0) return hipSuccess;
   hipLaunchKernelGGL(amp_average_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p0, stride_floats, n_replicas, n);
   return hipGetLastError();
+}
+
+// ============================================================ built-in arena
+// Device memory that exists without any allocation call: amp_create_static hands it to a context in place of a
+// caller-provided arena.  Every GPU the library's code object is loaded on holds its own copy, at its own address,
+// until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the address it
+// returns (looked up once per device, with that device current) is what kernels, copies and clears are given.
+static __device__ __align__(256) unsigned char scratch[AMP_STATIC_ARENA_BYTES];
+
+extern "C" hipError_t amp_static_arena(void** ptr, size_t* bytes) {
+  constexpr int MAX_DEV = 64;
+  static std::mutex mu;
+  static void* addr[MAX_DEV] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEV) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!addr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p || ((uintptr_t)p & 255)) return hipErrorInvalidSymbol;
+    addr[dev] = p;
+  }
+  *ptr = addr[dev];
+  *bytes = AMP_STATIC_ARENA_BYTES;
+  return hipSuccess;
 }
 
 // ============================================================ peak micro-benchmarks

@@ -10,6 +10,7 @@
 #include <cstdio>
 #include <cstring>
 #include <cstdlib>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -21,6 +22,7 @@ extern "C" hipError_t amp_peak_lds_launch(int n_wg, int iters, float* sink, hipS
                                           double* bytes_per_wg);
 extern "C" hipError_t amp_peak_hbm_launch(const void* src, size_t bytes, float* sink, hipStream_t stream, double* seconds);
 extern "C" hipError_t amp_average(float* p0, size_t stride_floats, int n_replicas, size_t n, hipStream_t stream);
+extern "C" hipError_t amp_static_arena(void** ptr, size_t* bytes);
 
 namespace {
 
@@ -73,6 +75,7 @@ struct amp_ctx {
   char* arena = nullptr;
   size_t arena_bytes = 0;
   hipStream_t stream = nullptr;
+  int static_dev = -1;   // >= 0: the arena is the library's built-in one on this device (amp_create_static)
   int model = 0;
   amp_model_dims dims{};
   std::vector<HostNode> nodes;
@@ -129,6 +132,11 @@ int fail(amp_ctx* c, int code, const char* fmt, ...) {
   } while (0)
 
 size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+static_assert(AMP_STATIC_ARENA_MAX == AMP_STATIC_ARENA_BYTES, "the header states the built-in arena's size");
+const char* arena_name(const amp_ctx* c) {
+  return c->static_dev >= 0 ? "the library's built-in arena (amp_create_static)" : "the arena";
+}
 
 // Everything replica r owns in the static part of the arena lies rep_stride bytes after replica r - 1's.
 char* rep_ptr(const amp_ctx* c, int r, size_t off) { return c->arena + (size_t)r * c->rep_stride + off; }
@@ -277,7 +285,39 @@ int amp_create(amp_ctx** out, void* dev_arena, size_t arena_bytes, void* hip_str
   return AMP_OK;
 }
 
-void amp_destroy(amp_ctx* ctx) { delete ctx; }
+// One context at a time may use a device's built-in arena.
+static std::mutex g_static_mu;
+static bool g_static_in_use[64] = {};
+
+int amp_create_static(amp_ctx** out, void* hip_stream) {
+  if (!out) return AMP_EINVAL;
+  *out = nullptr;
+  void* ptr = nullptr;
+  size_t bytes = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return AMP_EDEVICE;
+  if (amp_static_arena(&ptr, &bytes) != hipSuccess) return AMP_EDEVICE;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (g_static_in_use[dev]) return AMP_ESTATE;
+    g_static_in_use[dev] = true;
+  }
+  amp_ctx* c = new amp_ctx();
+  c->arena = (char*)ptr;
+  c->arena_bytes = bytes;
+  c->stream = (hipStream_t)hip_stream;
+  c->static_dev = dev;
+  *out = c;
+  return AMP_OK;
+}
+
+void amp_destroy(amp_ctx* ctx) {
+  if (ctx && ctx->static_dev >= 0) {
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    g_static_in_use[ctx->static_dev] = false;
+  }
+  delete ctx;
+}
 
 const char* amp_last_error(amp_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
@@ -566,8 +606,8 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
   c->static_end = c->rep_stride * (size_t)c->replicas;
   c->rep_admitted.assign(c->replicas, 0);
   if (c->static_end > c->arena_bytes)
-    return fail(c, AMP_ENOMEM, "finalize: arena of %zu bytes is too small, %zu needed before instances", c->arena_bytes,
-                c->static_end);
+    return fail(c, AMP_ENOMEM, "finalize: %s of %zu bytes is too small, %zu needed before instances", arena_name(c),
+                c->arena_bytes, c->static_end);
   c->finalized = true;
   c->state_zeroed = false;
   return AMP_OK;
@@ -872,7 +912,7 @@ namespace {
 template <class T>
 int upload(amp_ctx* c, size_t& off, const std::vector<T>& v, const void** dst) {
   const size_t bytes = std::max<size_t>(v.size() * sizeof(T), 4);
-  if (off + bytes > c->arena_bytes) return fail(c, AMP_ENOMEM, "arena too small for the instance set (%zu bytes more needed)", bytes);
+  if (off + bytes > c->arena_bytes) return fail(c, AMP_ENOMEM, "%s is too small for the instance set (%zu bytes more needed)", arena_name(c), bytes);
   *dst = c->arena + off;
   if (!v.empty()) HIPCHK(c, hipMemcpyAsync(c->arena + off, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice, c->stream));
   off = align_up(off + bytes);
@@ -1005,7 +1045,7 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
   const size_t zero_end = off;
   for (int r = 0; r < R; ++r)
     for (size_t w = 0; w < wpr; ++w) off_log[r][w] = take(8 * std::max<size_t>(log_cap, 1));
-  if (off > c->arena_bytes) return fail(c, AMP_ENOMEM, "arena of %zu bytes is too small, %zu needed", c->arena_bytes, off);
+  if (off > c->arena_bytes) return fail(c, AMP_ENOMEM, "%s of %zu bytes is too small, %zu needed", arena_name(c), c->arena_bytes, off);
   HIPCHK(c, hipMemsetAsync(c->arena + res_begin, 0, zero_end - res_begin, c->stream));
   for (int r = 0; r < R; ++r) {
     AmpDev& D = Ds[r];
