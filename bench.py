@@ -41,7 +41,11 @@ DEFAULTS = {
     # fit LDS (5 + 8, 16 workgroups, 30k trees/s) use each CU better and are what the replicated run packs two per XCD
     3: dict(mak=64, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.05)), tiles={1: 8, 2: 16}, replica_tiles={1: 5, 2: 8},
             replica_workers=16),
-    4: dict(mak=32, muf=20, lmuf=20, opt=("adam", dict(lr=0.001))),
+    # the commonest edge type's linear and the two GRU gates split over two workgroups each, the candidate over three
+    # (15 workgroups): 14.0k graphs/s against 10.8k unsplit; more tiles add nothing (13.6-13.9k on 16-18 workgroups)
+    # the replicated run keeps the nodes whole: 24 replicas of 10 workgroups beat 16 of 15
+    4: dict(mak=32, muf=20, lmuf=20, opt=("adam", dict(lr=0.001)), tiles={1: 2, 5: 2, 6: 2, 7: 3}, replica_tiles=None,
+            replica_workers=10),
     5: dict(mak=128, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.02)), tiles={1: 16, 2: 64}),
 }
 NAMES = {1: "mlp_64-128-128-10_1024inst", 2: "rnn_h128_len4-32_10000seq",
@@ -121,7 +125,7 @@ def measured_traffic(config, mak, muf, n, tiles):
     (profiles/hbm_traffic.md: one row per profiled configuration, written when the profile is taken); None when
     this configuration has not been profiled with the present kernels."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.md")
-    want = (str(config), str(mak), str(muf), str(n), "%d+%d" % (tiles[1], tiles[2]) if tiles else "-")
+    want = (str(config), str(mak), str(muf), str(n), "+".join(str(t) for _, t in sorted(tiles.items())) if tiles else "-")
     try:
         rows = [[c.strip() for c in line.strip().strip("|").split("|")] for line in open(path) if line.startswith("|")]
     except OSError:
@@ -207,7 +211,8 @@ def run_config(config, steps, warmup, mak=None, muf=None, n=None):
            "config": {"workload": NAMES[config], "instances": n_inst, "max_active_keys": cfg["mak"],
                       "min_update_frequency": cfg["muf"], "lookup_min_update_frequency": cfg["lmuf"],
                       "optimizer": cfg["opt"][0], "workgroups": n_workers,
-                      "tiles": {"leaf": cfg["tiles"][1], "branch": cfg["tiles"][2]} if cfg.get("tiles") else None},
+                      "tiles": ({"node %d" % k: t for k, t in sorted(cfg["tiles"].items())} if model == "ggnn" else
+                                {"leaf": cfg["tiles"][1], "branch": cfg["tiles"][2]}) if cfg.get("tiles") else None},
            "kernel_ms_per_step": 1e3 * kern, "kernel_instances_per_s": n_inst / kern,
            "train_loss": stats["mean_loss"], "train_accuracy": stats["accuracy"], "roofline": roof}
     ctx = dict(cfg=cfg, model=model, dims=dims, data=data, fp=fp, ml=ml, me=me, kind=kind, n_workers=n_workers,

@@ -212,11 +212,45 @@ __device__ __forceinline__ void mfma_rows_fixed(const LDSQ float* Wl, int ldw, c
   }
 }
 
+// Fixed shape with few row blocks (a node split over several tiles): NRB * NB <= 8 (row block, message block) items,
+// one per wave, so that all waves work where the per-row-block mapping above would leave most of them idle.
+template <int NRB, int NCG>
+__device__ __forceinline__ void mfma_rows_items(const LDSQ float* Wl, int ldw, const LDSQ float* bl, const LDSQ float* X, int ldx,
+                                                int NB, LDSQ float* Y, int ldy) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
+  if (wave >= NRB * NB) return;
+  const int rb = wave % NRB, nb = wave / NRB;
+  const v4f zero = {0.f, 0.f, 0.f, 0.f};
+  const LDSQ float* wp = Wl + (rb * 16 + i) * ldw + 4 * q;
+  const LDSQ float* xp = X + (nb * 16 + i) * ldx + 4 * q;
+  v4f acc0 = zero, acc1 = zero, acc2 = zero, acc3 = zero;
+  v4f w = *(const LDSQ v4f*)wp, x = *(const LDSQ v4f*)xp;
+#pragma unroll
+  for (int g = 0; g < NCG; ++g) {
+    v4f wn = w, xn = x;
+    if (g + 1 < NCG) {
+      wn = *(const LDSQ v4f*)(wp + 16 * (g + 1));
+      xn = *(const LDSQ v4f*)(xp + 16 * (g + 1));
+      asm volatile("" : "+v"(acc0) : : "memory");
+    }
+    acc0 = MFMA(w.x, x.x, acc0);
+    acc1 = MFMA(w.y, x.y, acc1);
+    acc2 = MFMA(w.z, x.z, acc2);
+    acc3 = MFMA(w.w, x.w, acc3);
+    w = wn;
+    x = xn;
+  }
+  const v4f b4 = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
+  *(LDSQ v4f*)(Y + (nb * 16 + i) * ldy + rb * 16 + 4 * q) = (acc0 + acc1) + (acc2 + acc3) + b4;
+}
+
 // NRBT / NCGT = 0: shape known only at run time.  Ends with a barrier.
 template <int NRBT, int NCGT>
 __device__ __forceinline__ void mfma_rows(const LDSQ float* Wl, int ldw, int NRB, int NCG, const LDSQ float* bl,
                                           const LDSQ float* X, int ldx, int NB, LDSQ float* Y, int ldy) {
-  if (NRBT && NB == 1)
+  if (NRBT && NRBT <= 4 && NB >= 2 && NRBT * NB <= 8)
+    mfma_rows_items<NRBT ? NRBT : 1, NCGT ? NCGT : 1>(Wl, ldw, bl, X, ldx, NB, Y, ldy);
+  else if (NRBT && NB == 1)
     mfma_rows_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 1>(Wl, ldw, bl, X, ldx, Y, ldy);
   else if (NRBT && NB == 2)
     mfma_rows_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 2>(Wl, ldw, bl, X, ldx, Y, ldy);

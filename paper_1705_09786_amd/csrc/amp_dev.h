@@ -138,6 +138,12 @@ struct AmpDev {
   int d_in, hidden, n_class, vocab, emb, n_node_types, n_edge_types, n_steps;
   int max_len, max_edges, train, pad0;
   int tiles_leaf, tiles_branch;
+  // graph model: workgroups ("tiles", split by hidden unit) per dense node -- [0..7] edge types, [8] update gate,
+  // [9] reset gate, [10] candidate -- and where each edge type's partial results start among the g_PE parts
+  int g_tiles[12];
+  int g_eoff[9];
+  int g_PE, g_PA;             // parts of the gradient w.r.t. h through the edges (sum of the edge tiles) / of the
+                              // gradients the three GRU nodes return (candidate tiles, then update, then reset)
   unsigned n_total, first_seq;
   int admit_bounded, n_updaters;  // staleness-bounded admission on / workers that apply updates
   float max_staleness;            // its bound: updates per worker during an instance's life

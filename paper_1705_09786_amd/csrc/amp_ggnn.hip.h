@@ -24,11 +24,20 @@
 //   buf[5]  Msg [s][E][H]       per-edge messages of the running step
 //   buf[6]  gH  [s][N][H]       gradient w.r.t. the final states (from the readout)
 //   buf[7]  dZ  [s][N][H]       pre-activation gradient for the update-gate node
-//   buf[8]  dR  [s][N][H]       pre-activation gradient for the reset-gate node
-//   buf[9]  dA  [s][3][N][H]    gradient w.r.t. A from candidate / update / reset nodes
-//   buf[10] dHp [s][3][N][H]    gradient w.r.t. h from the same three
-//   buf[11] dHe [s][T][N][H]    gradient w.r.t. h through the edges, per edge type
-//   buf[13] cnt [s][8] (int)    arrival counters
+//   buf[8]  dR  [s][Th][N][H]   pre-activation gradient for the reset-gate node, one part per candidate tile
+//   buf[9]  dA  [s][PA][N][H]   gradient w.r.t. A: parts of the candidate tiles, then the update, then the reset gate's
+//   buf[10] dHp [s][2][PA][N][H] gradient w.r.t. h from the same, by step parity: the candidate tiles of step it read
+//                               what step it + 1 left (for their own units) while other tiles of step it already
+//                               write their parts (over all units), so the two steps must not share a buffer
+//   buf[11] dHe [s][PE][N][H]   gradient w.r.t. h through the edges, one part per edge-type tile
+//   buf[13] cnt [s][8] (int)    arrival counters: 0 edge tiles forward, 1 gate tiles forward, 2 gate tiles backward,
+//                               3 edge tiles backward, 4 candidate tiles forward, 5 candidate tiles backward
+//
+// An edge linear or GRU node may be split by hidden unit over several workgroups (Section 5: a linear layer can be
+// split into tiles computed in parallel): the tiles read the node's ring in the same order, tile t owns output
+// units [u0, u0 + nu) -- those rows of W -- writes its slice of the node's output on the way forward and hands back
+// a partial W^T delta over all input columns on the way back; consumers add the parts up in a fixed order (edge
+// types ascending and tiles ascending inside a type; update gate, reset gate, candidate).
 #pragma once
 
 struct GView {
@@ -90,6 +99,10 @@ struct GBufs {
   GQ float *Hm, *A, *Z, *Rr, *Ht, *Msg, *gH, *dZ, *dR, *dA, *dHp, *dHe;
   GQ int* cnt;
   int H, N, Em, S, T;
+  int Tz, Tr, Th, PA, PE;     // tiles of the update gate, reset gate and candidate; parts of dA / dHp; parts of dHe
+  unsigned te_packed, eoff_packed;   // 4 bits per edge type: tiles of the type / first part of the type in dHe
+  __device__ __forceinline__ int te(int c) const { return (te_packed >> (4 * c)) & 15; }
+  __device__ __forceinline__ int eoff(int c) const { return (eoff_packed >> (4 * c)) & 15; }
   __device__ __forceinline__ long long st(int s, int it) const { return ((long long)s * S + it) * N * H; }
   __device__ __forceinline__ long long hm(int s, int it) const { return ((long long)s * (S + 1) + it) * N * H; }
   __device__ __forceinline__ long long sl(int s) const { return (long long)s * N * H; }
@@ -115,7 +128,51 @@ __device__ __forceinline__ GBufs g_bufs(const GQ AmpDev* D) {
   b.Em = uni(D->max_edges);
   b.S = uni(D->n_steps);
   b.T = uni(D->n_edge_types);
+  b.Tz = uni(D->g_tiles[8]);
+  b.Tr = uni(D->g_tiles[9]);
+  b.Th = uni(D->g_tiles[10]);
+  b.PA = uni(D->g_PA);
+  b.PE = uni(D->g_PE);
+  unsigned tp = 0, ep = 0;
+  for (int c = 0; c < 8; ++c) {
+    tp |= (unsigned)D->g_tiles[c] << (4 * c);
+    ep |= (unsigned)D->g_eoff[c] << (4 * c);
+  }
+  b.te_packed = uni(tp);
+  b.eoff_packed = uni(ep);
   return b;
+}
+
+// Tiles of the edge types that occur in a graph: what the joins over "every edge linear" wait for.
+__device__ __forceinline__ int g_present_tiles(const GBufs& B, unsigned present) {
+  int n = 0;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) n += ((present >> c) & 1u) ? B.te(c) : 0;
+  return n;
+}
+
+// The parts of dHe (by offset in units of N * H) that a graph's state gradient adds up, in order: edge types
+// present ascending, tiles ascending.  Uniform across the workgroup.
+struct GParts {
+  int n;
+  int off[12];
+};
+__device__ __forceinline__ GParts g_edge_parts(const GBufs& B, unsigned present) {
+  GParts p;
+  p.n = 0;
+#pragma unroll
+  for (int i = 0; i < 12; ++i) p.off[i] = 0;
+#pragma unroll
+  for (int c = 0; c < 8; ++c)
+    if ((present >> c) & 1u)
+      for (int t = 0; t < B.te(c); ++t) {
+        const int at = p.n < 12 ? p.n : 11;
+#pragma unroll
+        for (int i = 0; i < 12; ++i)
+          if (i == at) p.off[i] = B.eoff(c) + t;
+        p.n++;
+      }
+  return p;
 }
 
 #define GR_LOOKUP 1
@@ -165,21 +222,30 @@ __device__ __forceinline__ void g_post_edges(const GRings& R, unsigned present, 
 // pass has finished: Bcast / Flatmap backward over the edge types present
 // (ascending), the update gate, the reset gate and the candidate.
 // `present` = g_present_types(): bit c set when the graph has edges of type c.  All loads are unconditional
-// (an absent type reads type 0's row and drops it) so that they are in flight together.
-__device__ __forceinline__ float g_state_gradient(const GBufs& B, unsigned present, int s, int i) {
+// (an absent type reads type 0's row and drops it) so that they are in flight together.  `step` = the propagation
+// step whose backward pass produced the parts.
+__device__ __forceinline__ float g_state_gradient(const GBufs& B, const GParts& ep, int s, int i, int step) {
   const long long NH = (long long)B.N * B.H;
-  const GQ float* he = B.dHe + (long long)s * B.T * NH + i;
-  const GQ float* hp = B.dHp + (long long)s * 3 * NH + i;
-  float e[8];
+  const GQ float* he = B.dHe + (long long)s * B.PE * NH + i;
+  const GQ float* hp = B.dHp + ((long long)s * 2 + (step & 1)) * B.PA * NH + i;
+  float e[12], p[12];
 #pragma unroll
-  for (int c = 0; c < 8; ++c) e[c] = he[((present >> c) & 1u) ? c * NH : 0];
-  const float p0 = hp[0], p1 = hp[NH], p2 = hp[2 * NH];
+  for (int k = 0; k < 12; ++k) e[k] = he[(k < ep.n ? ep.off[k] : ep.off[0]) * NH];
+#pragma unroll
+  for (int k = 0; k < 12; ++k) p[k] = hp[(k < B.PA ? k : 0) * NH];
   float a = 0.f;
 #pragma unroll
-  for (int c = 0; c < 8; ++c)
-    if ((present >> c) & 1u) a += e[c];
-  a += p1 + p2;
-  a += p0;
+  for (int k = 0; k < 12; ++k)
+    if (k < ep.n) a += e[k];
+  // the GRU's parts: update gate, reset gate (parts Th .. PA - 1), then the candidate (parts 0 .. Th - 1)
+  float g = 0.f, cnd = 0.f;
+#pragma unroll
+  for (int k = 0; k < 12; ++k) {
+    if (k >= B.Th && k < B.PA) g += p[k];
+    if (k < B.Th) cnd += p[k];
+  }
+  a += g;
+  a += cnd;
   return a;
 }
 
@@ -206,21 +272,52 @@ __device__ __forceinline__ v4f sigmoid4(v4f y) { return (v4f){sigmoidf_(y.x), si
 __device__ __forceinline__ v4f tanh4(v4f y) { return (v4f){tanhf(y.x), tanhf(y.y), tanhf(y.z), tanhf(y.w)}; }
 
 // Four consecutive elements of the same sum.
-__device__ __forceinline__ v4f g_state_gradient4(const GBufs& B, unsigned present, int s, int i) {
+__device__ __forceinline__ v4f g_state_gradient4(const GBufs& B, const GParts& ep, int s, int i, int step) {
   const long long NH = (long long)B.N * B.H;
-  const GQ float* he = B.dHe + (long long)s * B.T * NH + i;
-  const GQ float* hp = B.dHp + (long long)s * 3 * NH + i;
-  v4f e[8];
+  const GQ float* he = B.dHe + (long long)s * B.PE * NH + i;
+  const GQ float* hp = B.dHp + ((long long)s * 2 + (step & 1)) * B.PA * NH + i;
+  const v4f zero = {0.f, 0.f, 0.f, 0.f};
+  v4f e[12], p[12];
 #pragma unroll
-  for (int c = 0; c < 8; ++c) e[c] = *(const GQ v4f*)(he + (((present >> c) & 1u) ? c * NH : 0));
-  const v4f p0 = *(const GQ v4f*)hp, p1 = *(const GQ v4f*)(hp + NH), p2 = *(const GQ v4f*)(hp + 2 * NH);
-  v4f a = {0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < 12; ++k) e[k] = *(const GQ v4f*)(he + (k < ep.n ? ep.off[k] : ep.off[0]) * NH);
 #pragma unroll
-  for (int c = 0; c < 8; ++c)
-    if ((present >> c) & 1u) a += e[c];
-  a += p1 + p2;
-  a += p0;
+  for (int k = 0; k < 12; ++k) p[k] = *(const GQ v4f*)(hp + (k < B.PA ? k : 0) * NH);
+  v4f a = zero, g = zero, cnd = zero;
+#pragma unroll
+  for (int k = 0; k < 12; ++k)
+    if (k < ep.n) a += e[k];
+#pragma unroll
+  for (int k = 0; k < 12; ++k) {
+    if (k >= B.Th && k < B.PA) g += p[k];
+    if (k < B.Th) cnd += p[k];
+  }
+  a += g;
+  a += cnd;
   return a;
+}
+
+// Sum of the PA parts of the gradient w.r.t. A at float offset o (four consecutive elements): update gate, reset
+// gate, then candidate -- (update + reset) + candidate when no node is tiled.
+__device__ __forceinline__ v4f g_sum_dA4(const GBufs& B, const GQ float* dA, long long o) {
+  const long long NH = (long long)B.N * B.H;
+  const v4f zero = {0.f, 0.f, 0.f, 0.f};
+  v4f p[12];
+#pragma unroll
+  for (int k = 0; k < 12; ++k) p[k] = *(const GQ v4f*)(dA + (k < B.PA ? k : 0) * NH + o);
+  v4f g = zero, cnd = zero;
+#pragma unroll
+  for (int k = 0; k < 12; ++k) {
+    if (k >= B.Th && k < B.PA) g += p[k];
+    if (k < B.Th) cnd += p[k];
+  }
+  return g + cnd;
+}
+__device__ __forceinline__ float g_sum_dA(const GBufs& B, const GQ float* dA, long long o) {
+  const long long NH = (long long)B.N * B.H;
+  float g = 0.f, cnd = 0.f;
+  for (int k = B.Th; k < B.PA; ++k) g += dA[k * NH + o];
+  for (int k = 0; k < B.Th; ++k) cnd += dA[k * NH + o];
+  return g + cnd;
 }
 
 // LDS pieces every dense graph worker carves: weight tile, bias, row / column maps for the update.
@@ -317,7 +414,8 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
       continue;
     }
     // backward: scatter-add the rows into the table's accumulator, node by node
-    for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) gt[i] = g_state_gradient(B, present, s, i);
+    const GParts ep = g_edge_parts(B, present);
+    for (int i = threadIdx.x; i < v.N * H; i += AMP_THREADS) gt[i] = g_state_gradient(B, ep, s, i, 0);
     lds_barrier();
     for (int j = threadIdx.x; j < H; j += AMP_THREADS)
       for (int n = 0; n < v.N; ++n) lkG[v.type[n] * H + j] += gt[n * H + j];
@@ -361,8 +459,9 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
   const Pend pd = make_pend(W, t);
   GQ float* pend = (GQ float*)pd.base;
   const int H = B.H, ctype = uni(W->aux), Ep = amp_round16(B.Em), Hs = amp_ldrow(H);
-  const bool vec = (H & 3) == 0;   // rows can be moved 16 bytes at a time
-  const int G1 = H >> 2;
+  const int u0 = t.u0, nu = t.nu, tile = uni(W->tile);   // this tile's output units = rows of W
+  const bool vec = (H & 3) == 0 && (u0 & 3) == 0 && (nu & 3) == 0;   // rows can be moved 16 bytes at a time
+  const int G1 = H >> 2, GU = nu >> 2;
   const int NRB = t.Rp >> 4, NCG = amp_round16(H) >> 4;
   Lds L{lds};
   const GTile g = g_tile_setup(L, nd, t);
@@ -370,7 +469,7 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
   LDSQ float* Y = (LDSQ float*)L.take(Ep * Hs);     // outputs / deltas
   for (int i = threadIdx.x; i < Ep * Hs; i += AMP_THREADS) X[i] = Y[i] = 0.f;
   GQ float* ndG = (GQ float*)nd.G;
-  float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
+  float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + t.grow(threadIdx.x)] : 0.f;
   __syncthreads();
   const Ring mine = ring_regs(D, uni(W->ring));
   unsigned head = 0;
@@ -388,7 +487,7 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
     const int K = uni(v.tcount[ctype]), NB = (K + 15) >> 4;
     const GQ int* te = v.tedge + uni(v.tstart[ctype]);   // edges of this type, ascending (Group orders its rows by edge index)
     const GQ float* h = B.Hm + B.hm(s, it);
-    const int nact = __popc(g_present_types(v, B.T));
+    const int nact = g_present_tiles(B, g_present_types(v, B.T));   // tiles of every edge type the graph uses
     if (vec) {
       const int GY = Hs >> 2;   // padding columns of a used row are written as zeros every time
       for (int idx = threadIdx.x; idx < K * GY; idx += AMP_THREADS) {
@@ -405,15 +504,15 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
     if (!(code & MSG_DIR_B)) {
       lds_barrier();
       mfma_rows<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, g.bl, X, Hs, NB, Y, Hs);
-      GQ float* msg = B.Msg + (long long)s * B.Em * H;
+      GQ float* msg = B.Msg + (long long)s * B.Em * H + u0;   // this tile's units of every message
       if (vec) {
-        for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
-          const int k = idx / G1, c = (idx - k * G1) << 2;
+        for (int idx = threadIdx.x; idx < K * GU; idx += AMP_THREADS) {
+          const int k = idx / GU, c = (idx - k * GU) << 2;
           *(GQ v4f*)(msg + (long long)te[k] * H + c) = *(const LDSQ v4f*)(Y + k * Hs + c);
         }
       } else
-      for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
-        const int k = i / H, j = i - k * H;
+      for (int i = threadIdx.x; i < K * nu; i += AMP_THREADS) {
+        const int k = i / nu, j = i - k * nu;
         msg[te[k] * H + j] = Y[k * Hs + j];
       }
       LOG(W->node, 0, seq, it);
@@ -427,38 +526,34 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
         }
       }
     } else {
-    // ---- backward: delta_e = dA[dst(e)] (Bcast backward on A: (update + reset) + candidate); one gradient for the group
+    // ---- backward: delta_e = this tile's units of dA[dst(e)] (Bcast backward on A: (update + reset) + candidate,
+    // each the sum of its tiles' parts); one gradient for the group
     {
       const long long NH = (long long)B.N * H;
-      const GQ float* dA = B.dA + (long long)s * 3 * NH;
+      const GQ float* dA = B.dA + (long long)s * B.PA * NH + u0;
       if (vec) {
-        const int GY = Hs >> 2;
-        for (int idx = threadIdx.x; idx < K * GY; idx += AMP_THREADS) {
-          const int k = idx / GY, c = (idx - k * GY) << 2;
-          const bool in = c < H;
-          const GQ float* p = dA + (long long)v.dst[te[k]] * H + (in ? c : 0);
-          const v4f d0 = *(const GQ v4f*)p, d1 = *(const GQ v4f*)(p + NH), d2 = *(const GQ v4f*)(p + 2 * NH);
-          *(LDSQ v4f*)(Y + k * Hs + c) = in ? (d1 + d2) + d0 : (v4f){0.f, 0.f, 0.f, 0.f};
+        // the tile's units first (one group per thread and round trip), then zeros for the rest of each row
+        const int GY = Hs >> 2, GZ = GY - GU;
+        for (int idx = threadIdx.x; idx < K * GU; idx += AMP_THREADS) {
+          const int k = idx / GU, c = (idx - k * GU) << 2;
+          *(LDSQ v4f*)(Y + k * Hs + c) = g_sum_dA4(B, dA, (long long)v.dst[te[k]] * H + c);
         }
+        for (int idx = threadIdx.x; idx < K * GZ; idx += AMP_THREADS)
+          *(LDSQ v4f*)(Y + (idx / GZ) * Hs + nu + ((idx % GZ) << 2)) = (v4f){0.f, 0.f, 0.f, 0.f};
       } else
       for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
         const int k = i / Hs, j = i - k * Hs;
-        float d = 0.f;
-        if (j < H) {
-          const long long o = (long long)v.dst[te[k]] * H + j;
-          d = (dA[NH + o] + dA[2 * NH + o]) + dA[o];
-        }
-        Y[i] = d;
+        Y[i] = j < nu ? g_sum_dA(B, dA, (long long)v.dst[te[k]] * H + j) : 0.f;
       }
     }
     lds_barrier();
     LOG(W->node, 1, seq, it);
-    g_pend_append(pend, pd.Rp, pd.stride, nrows, Y, Hs, H, X, Hs, H, K, gb);
+    g_pend_append(pend, pd.Rp, pd.stride, nrows, Y, Hs, nu, X, Hs, H, K, gb);
     lds_barrier();
     mfma_cols<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Hs);
     // dh_src += W^T delta_e: per source node, its edges of this type in ascending order
     {
-      GQ float* dHe = B.dHe + ((long long)s * B.T + ctype) * B.N * H;
+      GQ float* dHe = B.dHe + ((long long)s * B.PE + B.eoff(ctype) + tile) * B.N * H;   // this tile's part
       const GQ int* so = v.tsoff + ctype * (v.N + 1);
       const GQ int* sk = v.tsk + uni(v.tstart[ctype]);
       if (vec) {
@@ -500,7 +595,7 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
     lds_barrier();
   }
   tile_store(nd, t, g.Wg, g.bg);
-  if ((int)threadIdx.x < t.R) ndG[(long long)nd.rows * t.C + threadIdx.x] = gb;
+  if ((int)threadIdx.x < t.R) ndG[(long long)nd.rows * t.C + t.grow(threadIdx.x)] = gb;
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;
@@ -520,8 +615,10 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
   const Pend pd = make_pend(W, t);
   GQ float* pend = (GQ float*)pd.base;
   const int H = B.H, C = 2 * H, Np = amp_round16(B.N), which = uni(W->aux), Hs = amp_ldrow(H), Cs = amp_ldrow(C);
-  const bool vec = (H & 3) == 0;   // rows can be moved 16 bytes at a time
-  const int G1 = H >> 2;
+  const int u0 = t.u0, nu = t.nu, tile = uni(W->tile);   // this tile's output units = rows of W
+  const bool vec = (H & 3) == 0 && (u0 & 3) == 0 && (nu & 3) == 0;   // rows can be moved 16 bytes at a time
+  const int G1 = H >> 2, GU = nu >> 2;
+  const int part = B.Th + (which ? B.Tz : 0) + tile;     // this tile's part of dA / dHp
   const int NRB = t.Rp >> 4, NCG = amp_round16(C) >> 4;
   Lds L{lds};
   const GTile g = g_tile_setup(L, nd, t);
@@ -530,7 +627,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
   for (int i = threadIdx.x; i < Np * Cs; i += AMP_THREADS) X[i] = 0.f;
   for (int i = threadIdx.x; i < Np * Hs; i += AMP_THREADS) Y[i] = 0.f;
   GQ float* ndG = (GQ float*)nd.G;
-  float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
+  float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + t.grow(threadIdx.x)] : 0.f;
   __syncthreads();
   const Ring mine = ring_regs(D, uni(W->ring));
   unsigned head = 0;
@@ -548,7 +645,8 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
     const int K = v.N, NB = (K + 15) >> 4;
     GQ float* A = B.A + B.st(s, it);
     const GQ float* h = B.Hm + B.hm(s, it);
-    GQ float* outp = (which == 0 ? B.Z : B.Rr) + B.st(s, it);
+    GQ float* outp = (which == 0 ? B.Z : B.Rr) + B.st(s, it) + u0;   // this tile's units of every row
+    const bool rec_a = which == 0 && tile == 0;   // the update gate's first tile records the aggregated messages
     PHASE(0);
     if (!(code & MSG_DIR_B)) {
       // Ungroup, regroup by target node, sum: a_v = sum over incoming edges in edge order
@@ -556,25 +654,26 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       if (vec) {
         // 16 bytes per thread and step; the padding columns of a used row are written as zeros every time (an
         // unused row may hold anything, and the products leave 0 x anything in its padding)
-        const int GX = Cs >> 2;
-        for (int idx = threadIdx.x; idx < K * GX; idx += AMP_THREADS) {
-          const int k = idx / GX, c = (idx - k * GX) << 2;
-          v4f x = (v4f){0.f, 0.f, 0.f, 0.f};
-          if (c < H) {
-            x = g_sum_incoming4(msg, v, k, c, H);
-            if (which == 0) *(GQ v4f*)(A + k * H + c) = x;
-          } else if (c < C) {
-            x = *(const GQ v4f*)(h + k * H + c - H);
-          }
+        // one thread per (node, 4 units): its part of h travels while the chain inoff -> inedge -> message rows runs,
+        // so a graph of up to 20 nodes takes one pass
+        for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
+          const int k = idx / G1, c = (idx - k * G1) << 2;
+          const v4f hv = *(const GQ v4f*)(h + k * H + c);
+          const v4f x = g_sum_incoming4(msg, v, k, c, H);
+          if (rec_a) *(GQ v4f*)(A + k * H + c) = x;
           *(LDSQ v4f*)(X + k * Cs + c) = x;
+          *(LDSQ v4f*)(X + k * Cs + H + c) = hv;
         }
+        const int GP = (Cs - C) >> 2;
+        for (int idx = threadIdx.x; idx < K * GP; idx += AMP_THREADS)
+          *(LDSQ v4f*)(X + (idx / GP) * Cs + C + ((idx % GP) << 2)) = (v4f){0.f, 0.f, 0.f, 0.f};
       } else
       for (int i = threadIdx.x; i < K * Cs; i += AMP_THREADS) {
         const int k = i / Cs, c = i - k * Cs;
         float x = 0.f;   // padding columns of a used row are zero
         if (c < H) {
           for (int p = v.inoff[k]; p < v.inoff[k + 1]; ++p) x += msg[v.inedge[p] * H + c];
-          if (which == 0) A[k * H + c] = x;   // the recorded activation, read again by all three GRU nodes
+          if (rec_a) A[k * H + c] = x;   // the recorded activation, read again by all three GRU nodes
         } else if (c < C) {
           x = h[k * H + c - H];
         }
@@ -585,34 +684,48 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       mfma_rows<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, g.bl, X, Cs, NB, Y, Hs);
       PHASE(2);
       if (vec) {
-        for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
-          const int k = idx / G1, c = (idx - k * G1) << 2;
+        for (int idx = threadIdx.x; idx < K * GU; idx += AMP_THREADS) {
+          const int k = idx / GU, c = (idx - k * GU) << 2;
           *(GQ v4f*)(outp + k * H + c) = sigmoid4(*(const LDSQ v4f*)(Y + k * Hs + c));
         }
       } else
-      for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) outp[i] = sigmoidf_(Y[(i / H) * Hs + i % H]);
+      for (int i = threadIdx.x; i < K * nu; i += AMP_THREADS) outp[(i / nu) * H + i % nu] = sigmoidf_(Y[(i / nu) * Hs + i % nu]);
       LOG(W->node, 0, seq, it);
       publish_barrier();
       if (threadIdx.x == 0) {
         fence_release();
-        if (join_arrive(B.cnt + s * 8 + 1, 2)) ring_post(rg.gh, MSG_MAKE(0, s, it));
+        // every tile of both gates done: the candidate can start
+        if (join_arrive(B.cnt + s * 8 + 1, B.Tz + B.Tr)) ring_post(rg.gh, MSG_MAKE(0, s, it));
       }
       PHASE(3);
     } else {
-    const GQ float* dpre = (which == 0 ? B.dZ : B.dR) + B.sl(s);
+    // this tile's units of the pre-activation gradient: the update gate's was written by the candidate tile that
+    // owns each unit; the reset gate's is the sum of the candidate tiles' parts (each a full-width W^T delta)
+    const GQ float* dpre = (which == 0 ? B.dZ + B.sl(s) : B.dR + B.sl(s) * B.Th) + u0;
+    const int ndp = which == 0 ? 1 : B.Th;
+    const long long NHp = (long long)B.N * H;
     if (vec) {
-      const int GY = Hs >> 2;   // 16-byte groups of a delta row, padding included
-      for (int idx = threadIdx.x; idx < K * GY; idx += AMP_THREADS) {
-        const int k = idx / GY, c = (idx - k * GY) << 2;
-        const bool in = c < H;
-        const int o = k * H + (in ? c : 0);
-        const v4f a = *(const GQ v4f*)(A + o), hv = *(const GQ v4f*)(h + o), dp = *(const GQ v4f*)(dpre + o);
-        if (in) {
-          *(LDSQ v4f*)(X + k * Cs + c) = a;
-          *(LDSQ v4f*)(X + k * Cs + H + c) = hv;
-        }
-        *(LDSQ v4f*)(Y + k * Hs + c) = in ? dp : (v4f){0.f, 0.f, 0.f, 0.f};
+      // the H real columns of every row in one pass (one group per thread and round trip for graphs of up to 20
+      // nodes), the delta's zero padding afterwards
+      const int GY = Hs >> 2, GZ = GY - G1;
+      for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
+        const int k = idx / G1, c = (idx - k * G1) << 2;
+        const bool ind = c < nu;
+        const int o = k * H + c, od = k * H + (ind ? c : 0);
+        const v4f a = *(const GQ v4f*)(A + o), hv = *(const GQ v4f*)(h + o);
+        v4f dq[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) dq[p] = *(const GQ v4f*)(dpre + (p < ndp ? p : 0) * NHp + od);
+        v4f dp = dq[0];
+#pragma unroll
+        for (int p = 1; p < 4; ++p)
+          if (p < ndp) dp += dq[p];
+        *(LDSQ v4f*)(X + k * Cs + c) = a;
+        *(LDSQ v4f*)(X + k * Cs + H + c) = hv;
+        *(LDSQ v4f*)(Y + k * Hs + c) = ind ? dp : (v4f){0.f, 0.f, 0.f, 0.f};
       }
+      for (int idx = threadIdx.x; idx < K * GZ; idx += AMP_THREADS)
+        *(LDSQ v4f*)(Y + (idx / GZ) * Hs + H + ((idx % GZ) << 2)) = (v4f){0.f, 0.f, 0.f, 0.f};
       const int GP = (Cs - C) >> 2;   // padding columns of the used rows of X
       for (int idx = threadIdx.x; idx < K * GP; idx += AMP_THREADS)
         *(LDSQ v4f*)(X + (idx / GP) * Cs + C + ((idx % GP) << 2)) = (v4f){0.f, 0.f, 0.f, 0.f};
@@ -623,19 +736,22 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       }
       for (int i = threadIdx.x; i < K * Hs; i += AMP_THREADS) {
         const int k = i / Hs, j = i - k * Hs;
-        Y[i] = j < H ? dpre[k * H + j] : 0.f;
+        float d = 0.f;
+        if (j < nu)
+          for (int p = 0; p < ndp; ++p) d += dpre[p * NHp + k * H + j];
+        Y[i] = d;
       }
     }
     lds_barrier();
     PHASE(4);
     LOG(W->node, 1, seq, it);
-    g_pend_append(pend, pd.Rp, pd.stride, nrows, Y, Hs, H, X, Cs, C, K, gb);
+    g_pend_append(pend, pd.Rp, pd.stride, nrows, Y, Hs, nu, X, Cs, C, K, gb);
     lds_barrier();
     PHASE(5);
     mfma_cols<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Cs);
     PHASE(6);
-    GQ float* dA = B.dA + ((long long)s * 3 + 1 + which) * B.N * H;
-    GQ float* dHp = B.dHp + ((long long)s * 3 + 1 + which) * B.N * H;
+    GQ float* dA = B.dA + ((long long)s * B.PA + part) * B.N * H;
+    GQ float* dHp = B.dHp + (((long long)s * 2 + (it & 1)) * B.PA + part) * B.N * H;
     if (vec) {
       for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
         const int k = idx / G1, c = (idx - k * G1) << 2;
@@ -655,7 +771,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       fence_release();
       // both gates done: back through sum / Group to the edge types
       int go = 0;
-      if (threadIdx.x == 0) go = join_arrive(B.cnt + s * 8 + 2, 2);
+      if (threadIdx.x == 0) go = join_arrive(B.cnt + s * 8 + 2, B.Tz + B.Tr);
       if (__shfl(go, 0)) g_post_edges(rg, g_present_types(v, B.T), s, it, true);
     }
     g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
@@ -665,7 +781,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
     lds_barrier();
   }
   tile_store(nd, t, g.Wg, g.bg);
-  if ((int)threadIdx.x < t.R) ndG[(long long)nd.rows * t.C + threadIdx.x] = gb;
+  if ((int)threadIdx.x < t.R) ndG[(long long)nd.rows * t.C + t.grow(threadIdx.x)] = gb;
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;
@@ -685,8 +801,9 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
   const Pend pd = make_pend(W, t);
   GQ float* pend = (GQ float*)pd.base;
   const int H = B.H, C = 2 * H, Np = amp_round16(B.N), Hs = amp_ldrow(H), Cs = amp_ldrow(C);
-  const bool vec = (H & 3) == 0;   // rows can be moved 16 bytes at a time
-  const int G1 = H >> 2;
+  const int u0 = t.u0, nu = t.nu, tile = uni(W->tile);   // this tile's output units = rows of W
+  const bool vec = (H & 3) == 0 && (u0 & 3) == 0 && (nu & 3) == 0;   // rows can be moved 16 bytes at a time
+  const int G1 = H >> 2, GU = nu >> 2;
   const int NRB = t.Rp >> 4, NCG = amp_round16(C) >> 4;
   Lds L{lds};
   const GTile g = g_tile_setup(L, nd, t);
@@ -696,7 +813,7 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
   for (int i = threadIdx.x; i < Np * Cs; i += AMP_THREADS) X[i] = 0.f;
   for (int i = threadIdx.x; i < Np * Hs; i += AMP_THREADS) Y[i] = 0.f;
   GQ float* ndG = (GQ float*)nd.G;
-  float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
+  float gb = (int)threadIdx.x < t.R ? ndG[(long long)nd.rows * t.C + t.grow(threadIdx.x)] : 0.f;
   __syncthreads();
   const Ring mine = ring_regs(D, uni(W->ring));
   unsigned head = 0;
@@ -740,81 +857,96 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
       mfma_rows<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, g.bl, X, Cs, NB, Y, Hs);
       PHASE(2);
       GQ float* hn = B.Hm + B.hm(s, it + 1);
+      // this tile's units of the candidate and of the next state
       if (vec) {
-        for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
-          const int k = idx / G1, c = (idx - k * G1) << 2, o = k * H + c;
+        for (int idx = threadIdx.x; idx < K * GU; idx += AMP_THREADS) {
+          const int k = idx / GU, c = (idx - k * GU) << 2, o = k * H + u0 + c;
           const v4f z = *(const GQ v4f*)(Z + o), hv = *(const GQ v4f*)(h + o);
           const v4f ht = tanh4(*(const LDSQ v4f*)(Y + k * Hs + c));
           *(GQ v4f*)(Ht + o) = ht;
           *(GQ v4f*)(hn + o) = (1.f - z) * hv + z * ht;
         }
       } else
-      for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
-        const float ht = tanhf(Y[(i / H) * Hs + i % H]), z = Z[i];
-        Ht[i] = ht;
-        hn[i] = (1.f - z) * h[i] + z * ht;
+      for (int i = threadIdx.x; i < K * nu; i += AMP_THREADS) {
+        const int k = i / nu, j = i - k * nu, o = k * H + u0 + j;
+        const float ht = tanhf(Y[k * Hs + j]), z = Z[o];
+        Ht[o] = ht;
+        hn[o] = (1.f - z) * h[o] + z * ht;
       }
       LOG(W->node, 0, seq, it);
       publish_barrier();
       if (threadIdx.x < 64) {
         fence_release();
-        if (it + 1 < B.S)
-          g_post_edges(rg, present, s, it + 1, false);
-        else if (threadIdx.x == 0)
-          ring_post(rg.ro, MSG_MAKE(0, s, 0));
+        // the next state is complete when every tile has written its units
+        int go = B.Th == 1;
+        if (threadIdx.x == 0 && !go) go = join_arrive(B.cnt + s * 8 + 4, B.Th);
+        if (__shfl(go, 0)) {
+          if (it + 1 < B.S)
+            g_post_edges(rg, present, s, it + 1, false);
+          else if (threadIdx.x == 0)
+            ring_post(rg.ro, MSG_MAKE(0, s, 0));
+        }
       }
       PHASE(3);
     } else {
     // backward through blend, tanh, the candidate linear and r*h
     {
+      // the gradient w.r.t. the states leaving the step, for this tile's units: delta rows in tile order
       const GQ float* gH = B.gH + B.sl(s);
       GQ float* dZ = B.dZ + B.sl(s);
       const bool from_readout = it + 1 == B.S;
+      const GParts ep = g_edge_parts(B, present);
       if (vec) {
-        const int GY = Hs >> 2;
-        for (int idx = threadIdx.x; idx < K * GY; idx += AMP_THREADS) {
-          const int k = idx / GY, c = (idx - k * GY) << 2;
-          const bool in = c < H;
-          const int o = k * H + (in ? c : 0);
+        // the tile's units first (one group per thread and round trip), then zeros for the rest of each row
+        const int GY = Hs >> 2, GZ = GY - GU;
+        for (int idx = threadIdx.x; idx < K * GU; idx += AMP_THREADS) {
+          const int k = idx / GU, c = (idx - k * GU) << 2;
+          const int o = k * H + u0 + c;
           const v4f z = *(const GQ v4f*)(Z + o), ht = *(const GQ v4f*)(Ht + o), hv = *(const GQ v4f*)(h + o);
-          const v4f gg = from_readout ? *(const GQ v4f*)(gH + o) : g_state_gradient4(B, present, s, o);
-          if (in) {
-            *(LDSQ v4f*)(gt + o) = gg;
-            *(GQ v4f*)(dZ + o) = gg * (ht - hv) * z * (1.f - z);
-          }
-          *(LDSQ v4f*)(Y + k * Hs + c) = in ? gg * z * (1.f - ht * ht) : (v4f){0.f, 0.f, 0.f, 0.f};
+          const v4f gg = from_readout ? *(const GQ v4f*)(gH + o) : g_state_gradient4(B, ep, s, o, it + 1);
+          *(LDSQ v4f*)(gt + o) = gg;
+          *(GQ v4f*)(dZ + o) = gg * (ht - hv) * z * (1.f - z);
+          *(LDSQ v4f*)(Y + k * Hs + c) = gg * z * (1.f - ht * ht);
         }
+        for (int idx = threadIdx.x; idx < K * GZ; idx += AMP_THREADS)
+          *(LDSQ v4f*)(Y + (idx / GZ) * Hs + nu + ((idx % GZ) << 2)) = (v4f){0.f, 0.f, 0.f, 0.f};
       } else {
-      for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
-        const float gg = from_readout ? gH[i] : g_state_gradient(B, present, s, i);
-        const float z = Z[i], ht = Ht[i];
-        gt[i] = gg;
-        dZ[i] = gg * (ht - h[i]) * z * (1.f - z);
-        Y[(i / H) * Hs + i % H] = gg * z * (1.f - ht * ht);
+      for (int i = threadIdx.x; i < K * nu; i += AMP_THREADS) {
+        const int k = i / nu, j = i - k * nu, o = k * H + u0 + j;
+        const float gg = from_readout ? gH[o] : g_state_gradient(B, ep, s, o, it + 1);
+        const float z = Z[o], ht = Ht[o];
+        gt[o] = gg;
+        dZ[o] = gg * (ht - h[o]) * z * (1.f - z);
+        Y[k * Hs + j] = gg * z * (1.f - ht * ht);
       }
-      for (int i = threadIdx.x; i < K * (Hs - H); i += AMP_THREADS) Y[(i / (Hs - H)) * Hs + H + i % (Hs - H)] = 0.f;
+      for (int i = threadIdx.x; i < K * (Hs - nu); i += AMP_THREADS) Y[(i / (Hs - nu)) * Hs + nu + i % (Hs - nu)] = 0.f;
       }
     }
     lds_barrier();
     PHASE(4);
     LOG(W->node, 1, seq, it);
-    g_pend_append(pend, pd.Rp, pd.stride, nrows, Y, Hs, H, X, Cs, C, K, gb);
+    g_pend_append(pend, pd.Rp, pd.stride, nrows, Y, Hs, nu, X, Cs, C, K, gb);
     lds_barrier();
     PHASE(5);
     mfma_cols<NRBT, NCGT>(g.Wl, t.ldw, NRB, NCG, Y, Hs, NB, X, Cs);
     PHASE(6);
     {
-      GQ float* dA = B.dA + (long long)s * 3 * B.N * H;
-      GQ float* dHp = B.dHp + (long long)s * 3 * B.N * H;
-      GQ float* dR = B.dR + B.sl(s);
+      // This tile's parts, over all H columns: W^T delta w.r.t. A; the reset gate's pre-activation gradient, linear
+      // in the tile's partial W^T delta w.r.t. r * h; the gradient w.r.t. h, to which the blend's direct term
+      // gg (1 - z) belongs for the units this tile owns.
+      GQ float* dA = B.dA + ((long long)s * B.PA + tile) * B.N * H;
+      GQ float* dHp = B.dHp + (((long long)s * 2 + (it & 1)) * B.PA + tile) * B.N * H;
+      GQ float* dR = B.dR + ((long long)s * B.Th + tile) * B.N * H;
       if (vec) {
         for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
           const int k = idx / G1, c = (idx - k * G1) << 2, o = k * H + c;
+          const bool own = c >= u0 && c < u0 + nu;
           const v4f r = *(const GQ v4f*)(Rr + o), z = *(const GQ v4f*)(Z + o), hv = *(const GQ v4f*)(h + o);
           const v4f drh = *(const LDSQ v4f*)(X + k * Cs + H + c);
+          const v4f gg = own ? *(const LDSQ v4f*)(gt + o) : (v4f){0.f, 0.f, 0.f, 0.f};
           *(GQ v4f*)(dA + o) = *(const LDSQ v4f*)(X + k * Cs + c);
           *(GQ v4f*)(dR + o) = drh * hv * r * (1.f - r);
-          *(GQ v4f*)(dHp + o) = drh * r + *(const LDSQ v4f*)(gt + o) * (1.f - z);
+          *(GQ v4f*)(dHp + o) = own ? drh * r + gg * (1.f - z) : drh * r;
         }
       } else
       for (int i = threadIdx.x; i < K * H; i += AMP_THREADS) {
@@ -822,14 +954,17 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
         const float drh = X[k * Cs + H + j], r = Rr[i], z = Z[i];
         dA[i] = X[k * Cs + j];
         dR[i] = drh * h[i] * r * (1.f - r);
-        dHp[i] = drh * r + gt[i] * (1.f - z);
+        dHp[i] = (j >= u0 && j < u0 + nu) ? drh * r + gt[i] * (1.f - z) : drh * r;
       }
     }
     publish_barrier();
     if (threadIdx.x == 0) {
       fence_release();
-      ring_post(rg.gz, MSG_MAKE(1, s, it));
-      ring_post(rg.gr, MSG_MAKE(1, s, it));
+      // every candidate tile's parts are there: on to the two gates
+      if (B.Th == 1 || join_arrive(B.cnt + s * 8 + 5, B.Th)) {
+        ring_post(rg.gz, MSG_MAKE(1, s, it));
+        ring_post(rg.gr, MSG_MAKE(1, s, it));
+      }
     }
     g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
     }
@@ -837,7 +972,7 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
     lds_barrier();
   }
   tile_store(nd, t, g.Wg, g.bg);
-  if ((int)threadIdx.x < t.R) ndG[(long long)nd.rows * t.C + threadIdx.x] = gb;
+  if ((int)threadIdx.x < t.R) ndG[(long long)nd.rows * t.C + t.grow(threadIdx.x)] = gb;
   if (threadIdx.x == 0) {
     W->wstate[0] = count;
     W->wstate[1] = tstep;

@@ -373,19 +373,38 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
     }
     case ROLE_TREE_OUT: role_tree_out(D, W); break;
     case ROLE_G_LOOKUP: role_g_lookup(D, W); break;
-    // hidden size 97..112 (7 row blocks; 7 / 13 column groups) has products with fixed trip counts
-    case ROLE_G_EDGE:
-      if (amp_round16(D->hidden) == 112) role_g_edge<7, 7>(D, W);
+    // hidden size 97..112 (7 / 13 column groups; 7 row blocks, or 4, 3 and 2 when the node is split over two or three tiles)
+    // has products with fixed trip counts
+    case ROLE_G_EDGE: {
+      const int rb = amp_round16(W->nu) >> 4;
+      const bool c7 = amp_round16(D->hidden) == 112;
+      if (c7 && rb == 7) role_g_edge<7, 7>(D, W);
+      else if (c7 && rb == 4) role_g_edge<4, 7>(D, W);
+      else if (c7 && rb == 3) role_g_edge<3, 7>(D, W);
+      else if (c7 && rb == 2) role_g_edge<2, 7>(D, W);
       else role_g_edge<0, 0>(D, W);
       break;
-    case ROLE_G_GATE:
-      if (amp_round16(D->hidden) == 112 && amp_round16(2 * D->hidden) == 208) role_g_gate<7, 13>(D, W);
+    }
+    case ROLE_G_GATE: {
+      const int rb = amp_round16(W->nu) >> 4;
+      const bool c13 = amp_round16(D->hidden) == 112 && amp_round16(2 * D->hidden) == 208;
+      if (c13 && rb == 7) role_g_gate<7, 13>(D, W);
+      else if (c13 && rb == 4) role_g_gate<4, 13>(D, W);
+      else if (c13 && rb == 3) role_g_gate<3, 13>(D, W);
+      else if (c13 && rb == 2) role_g_gate<2, 13>(D, W);
       else role_g_gate<0, 0>(D, W);
       break;
-    case ROLE_G_CAND:
-      if (amp_round16(D->hidden) == 112 && amp_round16(2 * D->hidden) == 208) role_g_cand<7, 13>(D, W);
+    }
+    case ROLE_G_CAND: {
+      const int rb = amp_round16(W->nu) >> 4;
+      const bool c13 = amp_round16(D->hidden) == 112 && amp_round16(2 * D->hidden) == 208;
+      if (c13 && rb == 7) role_g_cand<7, 13>(D, W);
+      else if (c13 && rb == 4) role_g_cand<4, 13>(D, W);
+      else if (c13 && rb == 3) role_g_cand<3, 13>(D, W);
+      else if (c13 && rb == 2) role_g_cand<2, 13>(D, W);
       else role_g_cand<0, 0>(D, W);
       break;
+    }
     case ROLE_G_READOUT: role_g_readout(D, W); break;
     default: break;
   }

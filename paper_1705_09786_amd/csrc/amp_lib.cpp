@@ -405,8 +405,19 @@ int amp_set_tiles(amp_ctx* c, int node_id, int n_tiles) {
   if (!c) return AMP_EINVAL;
   if (!c->model || c->finalized) return fail(c, AMP_ESTATE, "set_tiles: only between build and finalize");
   if (node_id < 0 || node_id >= (int)c->nodes.size()) return fail(c, AMP_EINVAL, "set_tiles: no node %d", node_id);
+  if (c->model == AMP_MODEL_GGNN) {
+    // edge linears and the three GRU nodes, split by hidden unit; the partial results their tiles hand back are
+    // summed by the consumers, which hold at most 12 parts of a kind in flight
+    const int ne = c->dims.n_edge_types;
+    if (node_id < 1 || node_id > 3 + ne)
+      return fail(c, AMP_EUNSUPPORTED, "set_tiles: the graph model's lookup and readout cannot be tiled");
+    if (n_tiles < 1 || n_tiles > 4 || n_tiles > c->nodes[node_id].block)
+      return fail(c, AMP_EINVAL, "set_tiles: a graph node takes 1..min(4, hidden) tiles");
+    c->nodes[node_id].tiles = n_tiles;
+    return AMP_OK;
+  }
   if (c->model != AMP_MODEL_TREE || (node_id != 1 && node_id != 2))
-    return fail(c, AMP_EUNSUPPORTED, "set_tiles: only the tree model's leaf and branch nodes can be tiled");
+    return fail(c, AMP_EUNSUPPORTED, "set_tiles: only the tree model's leaf and branch nodes and the graph model's dense nodes can be tiled");
   if (n_tiles < 1 || n_tiles > 64 || n_tiles > c->nodes[node_id].block)
     return fail(c, AMP_EINVAL, "set_tiles: n_tiles must be in 1..min(64, hidden)");
   c->nodes[node_id].tiles = n_tiles;
@@ -459,9 +470,11 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     w.aux = aux;
     if (node >= 0) {
       const int blk = c->nodes[node].block;
-      const int base = blk / ntiles, rem = blk % ntiles;
-      w.u0 = tile * base + std::min(tile, rem);
-      w.nu = base + (tile < rem ? 1 : 0);
+      // graph nodes move their rows 16 bytes at a time when the hidden size allows: tiles of whole groups of 4 units
+      const int grp = (c->model == AMP_MODEL_GGNN && ntiles > 1 && blk % 4 == 0 && blk / 4 >= ntiles) ? 4 : 1;
+      const int nb = blk / grp, base = nb / ntiles, rem = nb % ntiles;
+      w.u0 = grp * (tile * base + std::min(tile, rem));
+      w.nu = grp * (base + (tile < rem ? 1 : 0));
     }
     c->workers.push_back(w);
   };
@@ -493,15 +506,22 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     nrings = 5;
   } else {
     // rings: 0 controller, 1 lookup, 2.. edge types, then gz, gr, gh, readout
+    // every tile of a node reads the node's ring (ring = node + 1) with a head of its own
     const int ne = c->dims.n_edge_types;
     add_worker(ROLE_G_LOOKUP, 0, 0, 1, 0);
-    for (int k = 0; k < ne; ++k) add_worker(ROLE_G_EDGE, 1 + k, 0, 1, k);
-    add_worker(ROLE_G_GATE, 1 + ne, 0, 1, 0);
-    add_worker(ROLE_G_GATE, 2 + ne, 0, 1, 1);
-    add_worker(ROLE_G_CAND, 3 + ne, 0, 1, 0);
+    for (int k = 0; k < ne; ++k)
+      for (int t = 0; t < c->nodes[1 + k].tiles; ++t) add_worker(ROLE_G_EDGE, 1 + k, t, c->nodes[1 + k].tiles, k);
+    for (int t = 0; t < c->nodes[1 + ne].tiles; ++t) add_worker(ROLE_G_GATE, 1 + ne, t, c->nodes[1 + ne].tiles, 0);
+    for (int t = 0; t < c->nodes[2 + ne].tiles; ++t) add_worker(ROLE_G_GATE, 2 + ne, t, c->nodes[2 + ne].tiles, 1);
+    for (int t = 0; t < c->nodes[3 + ne].tiles; ++t) add_worker(ROLE_G_CAND, 3 + ne, t, c->nodes[3 + ne].tiles, 0);
     add_worker(ROLE_G_READOUT, 4 + ne, 0, 1, 0);
-    for (size_t i = 0; i < c->workers.size(); ++i) c->workers[i].ring = (int)i;
-    nrings = (int)c->workers.size();
+    for (size_t i = 1; i < c->workers.size(); ++i) c->workers[i].ring = c->workers[i].node + 1;
+    nrings = 6 + ne;
+    int pe = 0;
+    for (int k = 0; k < ne; ++k) pe += c->nodes[1 + k].tiles;
+    const int pa = c->nodes[1 + ne].tiles + c->nodes[2 + ne].tiles + c->nodes[3 + ne].tiles;
+    if (pe > 12 || pa > 12)
+      return fail(c, AMP_EUNSUPPORTED, "finalize: at most 12 edge tiles and 12 GRU tiles in all (%d and %d asked for)", pe, pa);
   }
   if (c->workers.size() > AMP_MAX_WORKERS) return fail(c, AMP_EUNSUPPORTED, "finalize: too many workers");
   if (c->workers.size() * (size_t)c->replicas > 256)
@@ -589,15 +609,18 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     c->off_buf[11] = take(c->buf_bytes[11]);
   } else if (c->model == AMP_MODEL_GGNN) {
     const size_t N = c->max_len, E = c->max_edges, S = c->dims.n_steps, T = c->dims.n_edge_types;
+    size_t PE = 0;
+    for (size_t k = 0; k < T; ++k) PE += c->nodes[1 + k].tiles;
+    const size_t TH = c->nodes[3 + T].tiles, PA = c->nodes[1 + T].tiles + c->nodes[2 + T].tiles + TH;
     buf(0, (S + 1) * N * H);
     for (int i = 1; i <= 4; ++i) buf(i, S * N * H);
     buf(5, E * H);
     buf(6, N * H);
     buf(7, N * H);
-    buf(8, N * H);
-    buf(9, 3 * N * H);
-    buf(10, 3 * N * H);
-    buf(11, T * N * H);
+    buf(8, TH * N * H);
+    buf(9, PA * N * H);
+    buf(10, 2 * PA * N * H);
+    buf(11, PE * N * H);
     buf(12, N * H);
     buf(13, 8);
   }
@@ -1119,6 +1142,16 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
     if (c->model == AMP_MODEL_TREE) {
       D.tiles_leaf = c->nodes[1].tiles;
       D.tiles_branch = c->nodes[2].tiles;
+    }
+    if (c->model == AMP_MODEL_GGNN) {
+      const int ne = c->dims.n_edge_types;
+      for (int k = 0; k < 8; ++k) {
+        D.g_tiles[k] = k < ne ? c->nodes[1 + k].tiles : 0;
+        D.g_eoff[k + 1] = D.g_eoff[k] + D.g_tiles[k];
+      }
+      D.g_PE = D.g_eoff[8];
+      for (int k = 0; k < 3; ++k) D.g_tiles[8 + k] = c->nodes[1 + ne + k].tiles;
+      D.g_PA = D.g_tiles[8] + D.g_tiles[9] + D.g_tiles[10];
     }
     D.admit_bounded = train ? c->admit_bounded : 0;
     D.max_staleness = (float)c->max_staleness;

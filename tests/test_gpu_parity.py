@@ -320,6 +320,28 @@ def test_ggnn_replay_parity(mak, muf, opt, n):
     compare(g, rt, len(data), opt=opt)
 
 
+@pytest.mark.parametrize("dims,tiles,mak,muf,opt,n", [
+    (synth.DEFAULT_DIMS["ggnn"], {1: 2, 5: 2, 6: 2, 7: 3}, 32, 20, G_ADAM, 300),   # the benchmark's split: 52 + 48 and 36 + 32 + 32 units
+    (GG_ODD, {1: 2, 2: 3, 4: 2, 5: 3, 6: 4}, 6, 4, dict(kind="sgd", lr=0.01), 0),  # uneven splits of 37 units, scalar path
+    (dict(n_node_types=5, hidden=40, n_edge_types=2, n_steps=2), {1: 4, 2: 1, 3: 3, 4: 2, 5: 4}, 8, 3, MOM, 120),
+])
+def test_ggnn_tiled_nodes_replay_parity(dims, tiles, mak, muf, opt, n):
+    """Edge linears and GRU nodes split by hidden unit over several workgroups (Section 5's tiling of a linear
+    layer): every tile writes its units on the way forward and hands back a partial W^T delta that the consumers
+    add up.  Hidden 100 in two and three tiles (52 + 48 and 36 + 32 + 32 units, the fixed-shape products), 37 units in uneven tiles of 2, 3
+    and 4 (no 16-byte moves) on two-node and 29-node graphs, 40 units in tiles of 1 to 4 (12 + 8 + ... units)."""
+    if n:
+        data = synth.make_ggnn(n, 5, dims)[0]
+    else:
+        data = synth.make_ggnn(30, 5, dims, min_nodes=2, max_nodes=3)[0] + synth.make_ggnn(30, 6, dims, min_nodes=29, max_nodes=29)[0]
+    fp = synth.init_params("ggnn", dims, 9)
+    g = gpu_train("ggnn", dims, fp, data, mak, muf, opt, tiles=tiles)
+    check_controller_log(g["logs"], mak, len(data))
+    assert g["trainer"].amp.num_workers() == 3 + dims["n_edge_types"] + 3 + sum(t - 1 for t in tiles.values())
+    rt = oracle_replay("ggnn", dims, fp, data, g["logs"], muf, opt)
+    compare(g, rt, len(data), opt=opt)
+
+
 def test_ggnn_odd_sizes_and_tiny_graphs():
     """Hidden size not a multiple of anything, three edge types of which some
     graphs use only one, graphs of two nodes next to the largest ones."""
