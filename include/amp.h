@@ -143,7 +143,72 @@ int amp_create(amp_ctx **out, void *dev_arena, size_t arena_bytes, void *hip_str
 int amp_create_static(amp_ctx **out, void *hip_stream);
 void amp_destroy(amp_ctx *ctx);
 
-/* Builds one of the paper's model graphs.  One model per ctx. */
+/* Generic graph construction (Section 4: a model is a static IR graph plus a
+ * controller).  Node 0, the controller, exists from amp_create on; its output
+ * ports are what it pumps into the graph (instances, initial states, labels)
+ * and are numbered in the order they are connected.  Every other node is
+ * added with amp_add_node and gets the next id (1, 2, ...).
+ *
+ * Kinds (Section 4, "Payload transformations", "Loops, state, and control
+ * flow", "Aggregation and disaggregation"; the cells of Sections 2 and 6 and
+ * Appendix C).  rows / cols are the weight matrix's; n_in / n_out the port
+ * counts where the kind leaves them open; aux as noted:
+ *   parameterized payload transforms
+ *     LOOKUP            rows x cols table, token in, row out
+ *     LINEAR            y = act(W x + b); aux = AMP_ACT_NONE / AMP_ACT_RELU
+ *     RNN_TANH          h' = tanh(W [x; h] + b): a LINEAR with the tanh fused
+ *     GRU               rows = hidden; ports in 0 = aggregated messages a, 1 =
+ *                       state h; stands for three linear nodes (update gate,
+ *                       reset gate, candidate; Appendix C)
+ *     LEAF_LSTM         rows = hidden, cols = embedding; out = [h; c]
+ *     BRANCH_LSTM       rows = hidden; in = [h_l; c_l; h_r; c_r], out = [h; c]
+ *     GGNN_EDGE_LINEAR  rows = cols = hidden, applied to a group of rows
+ *     SUM_READOUT       sum over the rows of the payload, then 1 x cols linear
+ *   loss layers (port 0 prediction, port 1 label or target pumped by the
+ *   controller; they start backpropagation): SOFTMAX_XENT (rows = classes),
+ *   SQUARED_ERR
+ *   control and aggregation, functions of the message state only:
+ *     COND (n_out successors; aux = loop count where it ends a loop), PHI
+ *     (n_in alternatives, records the origin), ISU (invertible state
+ *     update), CONCAT (n_in ports; aux = parts that arrive on each port told
+ *     apart by their state, 0 or 1 = one), SPLIT (n_out equal parts), BCAST
+ *     (n_out copies; gradients summed in port order), GROUP, UNGROUP,
+ *     FLATMAP, SUM (rows of a group added up), SINK (end of a path without
+ *     a loss: answers a zero gradient)
+ *
+ * Ownership: desc is read during the call.  Errors: AMP_EINVAL for an unknown
+ * kind or node id; AMP_ESTATE after a model has been built or finalized.
+ *
+ * amp_validate_graph (amp_finalize calls it if the caller did not) checks the
+ * graph and returns AMP_EINVAL with a message for: a dangling port (every
+ * port of every node must carry exactly one edge), a port connected twice, a
+ * dimension mismatch between the two ends of an edge (widths are propagated
+ * through the control nodes), a cycle that does not pass through a Phi.  A
+ * valid graph is then matched, node by node and port by port, against the
+ * four graphs the persistent kernel has workers for (Figure 2's RNN, the MLP
+ * and Tree-LSTM of Section 6, Figure 4(a)'s gated graph network, as the
+ * amp_build_* calls below construct them with these same two calls); any
+ * other valid graph is AMP_EUNSUPPORTED.  After validation the parameterized
+ * nodes carry the model's numbering (see "Parameterized nodes" below);
+ * amp_get_node_index translates a graph node id into it (-1 for control and
+ * loss nodes; a GRU node gives the first of its three). */
+enum amp_node_kind {
+  AMP_NODE_CONTROLLER = 0, AMP_NODE_LOOKUP, AMP_NODE_LINEAR, AMP_NODE_RNN_TANH, AMP_NODE_GRU, AMP_NODE_LEAF_LSTM,
+  AMP_NODE_BRANCH_LSTM, AMP_NODE_GGNN_EDGE_LINEAR, AMP_NODE_SUM_READOUT, AMP_NODE_SOFTMAX_XENT, AMP_NODE_SQUARED_ERR,
+  AMP_NODE_COND, AMP_NODE_PHI, AMP_NODE_ISU, AMP_NODE_CONCAT, AMP_NODE_SPLIT, AMP_NODE_BCAST, AMP_NODE_GROUP,
+  AMP_NODE_UNGROUP, AMP_NODE_FLATMAP, AMP_NODE_SUM, AMP_NODE_SINK
+};
+#define AMP_ACT_NONE 0
+#define AMP_ACT_RELU 1
+typedef struct amp_node_desc { int32_t rows, cols, n_in, n_out, aux; } amp_node_desc;
+int amp_add_node(amp_ctx *ctx, int kind, const amp_node_desc *desc, int *node_id);
+int amp_connect(amp_ctx *ctx, int src, int src_port, int dst, int dst_port);
+int amp_validate_graph(amp_ctx *ctx);
+int amp_get_node_index(amp_ctx *ctx, int graph_node, int *param_node);
+
+/* Builds one of the paper's model graphs (with the two calls above; the
+ * graphs are those of Section 6's MLP paragraph, Figure 2, Section 6's
+ * Tree-LSTM paragraph and Figure 4(a)) and validates it.  One model per ctx. */
 int amp_build_mlp(amp_ctx *ctx, const amp_model_dims *dims);
 int amp_build_rnn(amp_ctx *ctx, const amp_model_dims *dims);
 int amp_build_treelstm(amp_ctx *ctx, const amp_model_dims *dims);
@@ -176,10 +241,17 @@ int amp_set_weights_in_hbm(amp_ctx *ctx, int node_id, int on);
  * admissions per replica.  Only before amp_finalize. */
 int amp_set_replicas(amp_ctx *ctx, int n_replicas);
 
-/* Validates the graph, places nodes on workgroups and lays out the arena for
- * at most max_active_keys instances in flight, each at most max_instance_len
- * long (time steps, tree leaves, or graph nodes) with at most max_edges
- * directed edges, and room for max_instances stored instances per set. */
+/* Validates the graph if that has not been done (see amp_validate_graph),
+ * places its nodes on workers (Appendix A: a worker hosts one or more IR
+ * nodes; Section 6 affinitizes the heavy operations to workers of their own:
+ * here one workgroup per parameterized node or tile of it) and lays out the
+ * arena: message queues, the per-key activation records of the parameterized
+ * nodes (Section 4, "Payload transformations") and the join tables, for at
+ * most max_active_keys instances in flight (Section 3), each at most
+ * max_instance_len long (time steps, tree leaves, or graph nodes) with at most
+ * max_edges directed edges, and room for max_instances stored instances per
+ * set.  AMP_ENOMEM when the arena is too small, AMP_EUNSUPPORTED when a node
+ * fits no worker. */
 int amp_finalize(amp_ctx *ctx, int max_active_keys, int max_instance_len, int max_edges,
                  size_t max_instances);
 
@@ -213,14 +285,28 @@ int amp_set_optimizer(amp_ctx *ctx, int node_id, int kind, const amp_opt_params 
 /* 1 (default): the applied gradient is the mean of the accumulated ones; 0: their sum. */
 int amp_set_gradient_mean(amp_ctx *ctx, int mean);
 
+/* Parameters of a parameterized node (Section 4: a PPT node owns its
+ * parameters; Appendix C: parameter, gradient buffer and optimizer slots live
+ * with the node), as one flat host vector in the layout given under
+ * "Parameterized nodes" above.  set copies from `host` (n must be the node's
+ * count) and takes effect at the next amp_train / amp_eval; get copies the
+ * present values into `host` (capacity cap floats; *n = count; AMP_ENOMEM if
+ * cap is too small).  Initial values are the caller's: the library draws no
+ * random numbers. */
 int amp_num_nodes(amp_ctx *ctx);
 int amp_param_count(amp_ctx *ctx, int node_id, size_t *n);
 int amp_set_params(amp_ctx *ctx, int node_id, const float *host, size_t n);
 int amp_get_params(amp_ctx *ctx, int node_id, float *host, size_t cap, size_t *n);
 
 /* Appends an instance to the training set (which = 0) or the evaluation set
- * (which = 1).  `key` is kept for the caller's bookkeeping.  Instances are
- * copied; they reach the device at the next amp_train / amp_eval. */
+ * (which = 1): what the controller will pump into the graph for it --
+ * tokens, initial states, labels, the graph structure the messages' states
+ * refer to (Section 4, Overview and the RNN / GNN examples).  `key` is kept
+ * for the caller's bookkeeping.  The instance is checked (AMP_EINVAL names
+ * the fault: a tree node without two children, an unreachable node, an edge
+ * endpoint outside the graph, a label out of range ...) and copied; it
+ * reaches the device at the next amp_train / amp_eval.  AMP_EFULL beyond
+ * max_instances.  amp_clear_instances empties a set. */
 int amp_submit(amp_ctx *ctx, int which, uint64_t key, const amp_instance *inst);
 int amp_clear_instances(amp_ctx *ctx, int which);
 
@@ -231,23 +317,39 @@ int amp_set_event_log(amp_ctx *ctx, size_t events_per_worker);
  * and amp_train returns AMP_EDEVICE (default 20). */
 int amp_set_watchdog(amp_ctx *ctx, double seconds);
 
-/* Blocking: trains `epochs` passes over the training set in submit order. */
+/* Blocking: trains `epochs` passes over the training set in submit order by
+ * asynchronous model-parallel training (Section 3): the controller keeps up to
+ * max_active_keys instances in flight, every parameterized node accumulates
+ * the gradients that reach it and applies its own update once
+ * min_update_frequency of them have arrived, with no synchronisation between
+ * nodes.  AMP_EDEVICE if the kernel stopped itself (watchdog, record full). */
 int amp_train(amp_ctx *ctx, int epochs);
 /* Blocking: forward-only pass over the evaluation set with the present
- * parameters; nothing is recorded or updated. */
+ * parameters (Section 1: inference runs through the same graph; Table 2's
+ * validation throughput); nothing is recorded or updated. */
 int amp_eval(amp_ctx *ctx, amp_eval_result *out);
 
-/* Results of the last amp_train: mean loss per instance, accuracy over all
- * predictions, instances trained, device seconds from first admission to
- * last retirement.  Any out pointer may be NULL. */
+/* Results of the last amp_train, as the experiments of Section 6 report them
+ * (Tables 1 and 2: accuracy, instances per second): mean loss per instance,
+ * accuracy over all predictions, instances trained, device seconds from first
+ * admission to last retirement.  Any out pointer may be NULL. */
 int amp_get_loss(amp_ctx *ctx, double *mean_loss, double *accuracy, uint64_t *n_instances,
                  double *seconds);
-/* Per-admission losses of the last amp_train, in admission order. */
+/* Per-admission losses of the last amp_train (the loss layer's output for
+ * each instance, Section 4; a tree's is the sum over its nodes), in admission
+ * order.  AMP_ENOMEM if cap is too small; *n = count. */
 int amp_get_instance_losses(amp_ctx *ctx, float *host, size_t cap, size_t *n);
-/* Events of the last amp_train, worker by worker, each worker's in execution order. */
+/* Events of the last amp_train, worker by worker, each worker's in execution
+ * order.  Under asynchronous training the result depends on the order in
+ * which each node saw its messages and applied its updates (Section 3:
+ * parameters may change between a message's forward and backward pass); the
+ * record is that order, enough to repeat the run elsewhere.  buf NULL = size
+ * query; AMP_ENOMEM if cap is too small. */
 int amp_get_event_log(amp_ctx *ctx, amp_event *buf, size_t cap, size_t *n);
-/* bins[k] = gradients whose node was updated k times between their forward
- * and backward pass (last bin = that many or more), from the event log. */
+/* Gradient staleness as Section 3 defines it: bins[k] = gradients whose node
+ * was updated k times between their forward and backward pass (last bin =
+ * that many or more), from the event record of the last amp_train
+ * (AMP_ESTATE without one). */
 int amp_get_staleness_hist(amp_ctx *ctx, uint64_t *bins, size_t nbins);
 int amp_num_workers(amp_ctx *ctx);
 /* Utilisation of the last amp_train / amp_eval, one entry per worker

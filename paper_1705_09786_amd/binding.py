@@ -41,6 +41,16 @@ class Instance(ct.Structure):
                 ("target", ct.c_float)]
 
 
+class NodeDesc(ct.Structure):
+    _fields_ = [(n, ct.c_int32) for n in ("rows", "cols", "n_in", "n_out", "aux")]
+
+
+NODE_KINDS = ("controller", "lookup", "linear", "rnn_tanh", "gru", "leaf_lstm", "branch_lstm", "ggnn_edge_linear",
+              "sum_readout", "softmax_xent", "squared_err", "cond", "phi", "isu", "concat", "split", "bcast", "group",
+              "ungroup", "flatmap", "sum", "sink")
+ACT_NONE, ACT_RELU = 0, 1
+
+
 class OptParams(ct.Structure):
     _fields_ = [(n, ct.c_float) for n in ("lr", "momentum", "beta1", "beta2", "eps")]
 
@@ -60,6 +70,10 @@ SIGNATURES = {
     "amp_create": (ct.c_int, [ct.POINTER(_ctxp), ct.c_void_p, ct.c_size_t, ct.c_void_p]),
     "amp_create_static": (ct.c_int, [ct.POINTER(_ctxp), ct.c_void_p]),
     "amp_destroy": (None, [_ctxp]),
+    "amp_add_node": (ct.c_int, [_ctxp, ct.c_int, ct.POINTER(NodeDesc), ct.POINTER(ct.c_int)]),
+    "amp_connect": (ct.c_int, [_ctxp, ct.c_int, ct.c_int, ct.c_int, ct.c_int]),
+    "amp_validate_graph": (ct.c_int, [_ctxp]),
+    "amp_get_node_index": (ct.c_int, [_ctxp, ct.c_int, ct.POINTER(ct.c_int)]),
     "amp_build_mlp": (ct.c_int, [_ctxp, ct.POINTER(ModelDims)]),
     "amp_build_rnn": (ct.c_int, [_ctxp, ct.POINTER(ModelDims)]),
     "amp_build_treelstm": (ct.c_int, [_ctxp, ct.POINTER(ModelDims)]),
@@ -205,6 +219,27 @@ class Amp:
         self.model = MODEL_IDS[model]
         d = ModelDims(**{k: int(v) for k, v in dims.items()})
         self._chk(getattr(self.L, _BUILDERS[self.model])(self.h, ct.byref(d)))
+
+    def add_node(self, kind: str, rows=0, cols=0, n_in=1, n_out=1, aux=0) -> int:
+        d = NodeDesc(rows, cols, n_in, n_out, aux)
+        nid = ct.c_int(-1)
+        self._chk(self.L.amp_add_node(self.h, NODE_KINDS.index(kind), ct.byref(d), ct.byref(nid)))
+        return nid.value
+
+    def connect(self, src, src_port, dst, dst_port):
+        self._chk(self.L.amp_connect(self.h, src, src_port, dst, dst_port))
+
+    def validate_graph(self, model: str | None = None):
+        """Validates and lowers a graph made with add_node / connect; `model` names what the caller expects it to
+        be, so that submit() knows how to marshal instances."""
+        self._chk(self.L.amp_validate_graph(self.h))
+        if model is not None:
+            self.model = MODEL_IDS[model]
+
+    def get_node_index(self, graph_node):
+        v = ct.c_int(-2)
+        self._chk(self.L.amp_get_node_index(self.h, graph_node, ct.byref(v)))
+        return v.value
 
     def set_tiles(self, node, n):
         self._chk(self.L.amp_set_tiles(self.h, node, n))

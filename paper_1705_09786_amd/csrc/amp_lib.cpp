@@ -16,6 +16,7 @@
 
 #include "../../include/amp.h"
 #include "amp_dev.h"
+#include "amp_graph.h"
 
 extern "C" hipError_t amp_launch(const AmpDev* devs, int n_replicas, int workers_per_replica, hipStream_t stream);
 extern "C" hipError_t amp_peak_lds_launch(int n_wg, int iters, float* sink, hipStream_t stream, double* seconds,
@@ -78,6 +79,8 @@ struct amp_ctx {
   int static_dev = -1;   // >= 0: the arena is the library's built-in one on this device (amp_create_static)
   int model = 0;
   amp_model_dims dims{};
+  ampgraph::Graph graph;       // the IR graph as described through amp_add_node / amp_connect (or by amp_build_*)
+  std::vector<int> param_of;   // per graph node: the model's parameterized-node number, -1 for control and loss nodes
   std::vector<HostNode> nodes;
   std::vector<HostWorker> workers;
   bool finalized = false;
@@ -339,65 +342,146 @@ int amp_measure_peaks(void* dev_buf, size_t bytes, void* hip_stream, double* lds
   return AMP_OK;
 }
 
-int amp_build_mlp(amp_ctx* c, const amp_model_dims* d) {
-  if (int r = check_build(c, d)) return r;
-  if (!positive({d->d_in, d->hidden, d->n_class})) return fail(c, AMP_EINVAL, "mlp: sizes must be >= 1");
-  if (d->n_class > 64) return fail(c, AMP_EUNSUPPORTED, "mlp: n_class > 64");
-  c->model = AMP_MODEL_MLP;
-  c->dims = *d;
-  c->nodes = {make_node("lin1", d->hidden, d->d_in, 1), make_node("lin2", d->hidden, d->hidden, 1),
-              make_node("lin3", d->n_class, d->hidden, 1)};
-  return AMP_OK;
-}
+}  // extern "C"
 
-int amp_build_rnn(amp_ctx* c, const amp_model_dims* d) {
-  if (int r = check_build(c, d)) return r;
-  if (!positive({d->vocab, d->emb, d->hidden, d->n_class})) return fail(c, AMP_EINVAL, "rnn: sizes must be >= 1");
-  if (d->n_class > 64) return fail(c, AMP_EUNSUPPORTED, "rnn: n_class > 64");
-  c->model = AMP_MODEL_RNN;
-  c->dims = *d;
-  c->nodes = {make_node("lookup", d->vocab, d->emb, 0), make_node("cell", d->hidden, d->emb + d->hidden, 1),
-              make_node("out", d->n_class, d->hidden, 1)};
-  // the cell's input is Concat(embedding, h): two column segments with a common padded width
-  c->nodes[1].seg0 = d->emb;
-  c->nodes[1].seg = d->hidden;
-  c->nodes[1].segp = amp_round4(std::max(d->emb, d->hidden));
-  return AMP_OK;
-}
+namespace {
 
-int amp_build_treelstm(amp_ctx* c, const amp_model_dims* d) {
-  if (int r = check_build(c, d)) return r;
-  if (!positive({d->vocab, d->emb, d->hidden, d->n_class})) return fail(c, AMP_EINVAL, "tree: sizes must be >= 1");
-  if (d->n_class > 64) return fail(c, AMP_EUNSUPPORTED, "tree: n_class > 64");
-  c->model = AMP_MODEL_TREE;
-  c->dims = *d;
-  c->nodes = {make_node("lookup", d->vocab, d->emb, 0), make_node("leaf", 3 * d->hidden, d->emb, 1, 3),
-              make_node("branch", 5 * d->hidden, 2 * d->hidden, 1, 5), make_node("out", d->n_class, d->hidden, 1)};
-  c->nodes[1].tiles = 5;
-  c->nodes[2].tiles = 8;
-  c->nodes[1].seg = d->emb;
-  c->nodes[1].segp = amp_round4(d->emb);
-  c->nodes[2].seg = d->hidden;
-  c->nodes[2].segp = amp_round4(d->hidden);
-  return AMP_OK;
-}
-
-int amp_build_ggnn(amp_ctx* c, const amp_model_dims* d) {
-  if (int r = check_build(c, d)) return r;
-  if (!positive({d->n_node_types, d->hidden, d->n_edge_types, d->n_steps}))
-    return fail(c, AMP_EINVAL, "ggnn: sizes must be >= 1");
-  if (d->n_edge_types > 8) return fail(c, AMP_EUNSUPPORTED, "ggnn: more than 8 edge types");
-  c->model = AMP_MODEL_GGNN;
-  c->dims = *d;
-  c->nodes.clear();
-  c->nodes.push_back(make_node("lookup", d->n_node_types, d->hidden, 0));
-  for (int k = 0; k < d->n_edge_types; ++k) {
-    char nm[16];
-    snprintf(nm, sizeof nm, "edge%d", k);
-    c->nodes.push_back(make_node(nm, d->hidden, d->hidden, 1));
+// A recognised graph becomes the model the kernel has workers for: the parameterized nodes in the model's
+// numbering, with the layout facts the workers need.
+int lower_model(amp_ctx* c, int model, const amp_model_dims* d) {
+  switch (model) {
+    case AMP_MODEL_MLP:
+      if (!positive({d->d_in, d->hidden, d->n_class})) return fail(c, AMP_EINVAL, "mlp: sizes must be >= 1");
+      if (d->n_class > 64) return fail(c, AMP_EUNSUPPORTED, "mlp: n_class > 64");
+      c->nodes = {make_node("lin1", d->hidden, d->d_in, 1), make_node("lin2", d->hidden, d->hidden, 1),
+                  make_node("lin3", d->n_class, d->hidden, 1)};
+      break;
+    case AMP_MODEL_RNN:
+      if (!positive({d->vocab, d->emb, d->hidden, d->n_class})) return fail(c, AMP_EINVAL, "rnn: sizes must be >= 1");
+      if (d->n_class > 64) return fail(c, AMP_EUNSUPPORTED, "rnn: n_class > 64");
+      c->nodes = {make_node("lookup", d->vocab, d->emb, 0), make_node("cell", d->hidden, d->emb + d->hidden, 1),
+                  make_node("out", d->n_class, d->hidden, 1)};
+      // the cell's input is Concat(embedding, h): two column segments with a common padded width
+      c->nodes[1].seg0 = d->emb;
+      c->nodes[1].seg = d->hidden;
+      c->nodes[1].segp = amp_round4(std::max(d->emb, d->hidden));
+      break;
+    case AMP_MODEL_TREE:
+      if (!positive({d->vocab, d->emb, d->hidden, d->n_class})) return fail(c, AMP_EINVAL, "tree: sizes must be >= 1");
+      if (d->n_class > 64) return fail(c, AMP_EUNSUPPORTED, "tree: n_class > 64");
+      c->nodes = {make_node("lookup", d->vocab, d->emb, 0), make_node("leaf", 3 * d->hidden, d->emb, 1, 3),
+                  make_node("branch", 5 * d->hidden, 2 * d->hidden, 1, 5), make_node("out", d->n_class, d->hidden, 1)};
+      c->nodes[1].tiles = 5;
+      c->nodes[2].tiles = 8;
+      c->nodes[1].seg = d->emb;
+      c->nodes[1].segp = amp_round4(d->emb);
+      c->nodes[2].seg = d->hidden;
+      c->nodes[2].segp = amp_round4(d->hidden);
+      break;
+    case AMP_MODEL_GGNN:
+      if (!positive({d->n_node_types, d->hidden, d->n_edge_types, d->n_steps}))
+        return fail(c, AMP_EINVAL, "ggnn: sizes must be >= 1");
+      if (d->n_edge_types > 8) return fail(c, AMP_EUNSUPPORTED, "ggnn: more than 8 edge types");
+      c->nodes.clear();
+      c->nodes.push_back(make_node("lookup", d->n_node_types, d->hidden, 0));
+      for (int k = 0; k < d->n_edge_types; ++k) {
+        char nm[16];
+        snprintf(nm, sizeof nm, "edge%d", k);
+        c->nodes.push_back(make_node(nm, d->hidden, d->hidden, 1));
+      }
+      for (const char* nm : {"gz", "gr", "gh"}) c->nodes.push_back(make_node(nm, d->hidden, 2 * d->hidden, 1));
+      c->nodes.push_back(make_node("readout", 1, d->hidden, 1));
+      break;
+    default: return fail(c, AMP_EINVAL, "unknown model");
   }
-  for (const char* nm : {"gz", "gr", "gh"}) c->nodes.push_back(make_node(nm, d->hidden, 2 * d->hidden, 1));
-  c->nodes.push_back(make_node("readout", 1, d->hidden, 1));
+  c->model = model;
+  c->dims = *d;
+  return AMP_OK;
+}
+
+// Validates the ctx's graph, recognises it and lowers it.
+int lower_graph(amp_ctx* c) {
+  std::string err;
+  if (int rc = ampgraph::validate(c->graph, err)) return fail(c, rc, "graph: %s", err.c_str());
+  int model = 0;
+  amp_model_dims dims{};
+  if (int rc = ampgraph::recognise(c->graph, model, dims, c->param_of, err)) return fail(c, rc, "graph: %s", err.c_str());
+  return lower_model(c, model, &dims);
+}
+
+// The canned builders describe their graph with the same two operations a caller has, then validate it.
+int build_canned(amp_ctx* c, int model, const amp_model_dims* d, std::initializer_list<int> sizes, const char* what) {
+  if (int r = check_build(c, d)) return r;
+  if (c->graph.nodes.size() > 1) return fail(c, AMP_ESTATE, "nodes were already added to this context's graph");
+  if (!positive(sizes)) return fail(c, AMP_EINVAL, "%s: sizes must be >= 1", what);
+  c->graph = ampgraph::template_graph(model, *d);
+  const int rc = lower_graph(c);
+  if (rc) c->graph = ampgraph::Graph();
+  return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+int amp_build_mlp(amp_ctx* c, const amp_model_dims* d) {
+  return d ? build_canned(c, AMP_MODEL_MLP, d, {d->d_in, d->hidden, d->n_class}, "mlp") : fail(c, AMP_EINVAL, "null argument");
+}
+int amp_build_rnn(amp_ctx* c, const amp_model_dims* d) {
+  return d ? build_canned(c, AMP_MODEL_RNN, d, {d->vocab, d->emb, d->hidden, d->n_class}, "rnn") : fail(c, AMP_EINVAL, "null argument");
+}
+int amp_build_treelstm(amp_ctx* c, const amp_model_dims* d) {
+  return d ? build_canned(c, AMP_MODEL_TREE, d, {d->vocab, d->emb, d->hidden, d->n_class}, "tree") : fail(c, AMP_EINVAL, "null argument");
+}
+int amp_build_ggnn(amp_ctx* c, const amp_model_dims* d) {
+  if (!d) return fail(c, AMP_EINVAL, "null argument");
+  if (d->n_edge_types > 8) return fail(c, AMP_EUNSUPPORTED, "ggnn: more than 8 edge types");
+  return build_canned(c, AMP_MODEL_GGNN, d, {d->n_node_types, d->hidden, d->n_edge_types, d->n_steps}, "ggnn");
+}
+
+int amp_add_node(amp_ctx* c, int kind, const amp_node_desc* desc, int* node_id) {
+  if (!c || !desc || !node_id) return fail(c, AMP_EINVAL, "null argument");
+  if (c->model || c->finalized) return fail(c, AMP_ESTATE, "add_node: the model graph is already built");
+  if (kind <= AMP_NODE_CONTROLLER || kind > AMP_NODE_SINK) return fail(c, AMP_EINVAL, "add_node: unknown node kind %d", kind);
+  if (desc->n_in < 0 || desc->n_out < 0 || desc->n_in > 64 || desc->n_out > 64 || desc->rows < 0 || desc->cols < 0)
+    return fail(c, AMP_EINVAL, "add_node: bad description");
+  if (c->graph.nodes.size() >= 4096) return fail(c, AMP_EFULL, "add_node: too many nodes");
+  ampgraph::Node n;
+  n.kind = kind;
+  n.d = *desc;
+  c->graph.nodes.push_back(n);
+  *node_id = (int)c->graph.nodes.size() - 1;
+  return AMP_OK;
+}
+
+int amp_connect(amp_ctx* c, int src, int src_port, int dst, int dst_port) {
+  if (!c) return AMP_EINVAL;
+  if (c->model || c->finalized) return fail(c, AMP_ESTATE, "connect: the model graph is already built");
+  const int N = (int)c->graph.nodes.size();
+  if (src < 0 || src >= N || dst < 1 || dst >= N) return fail(c, AMP_EINVAL, "connect: no such node (%d -> %d)", src, dst);
+  if (src_port < 0 || dst_port < 0 || src_port >= 64 || dst_port >= 64) return fail(c, AMP_EINVAL, "connect: bad port");
+  if (src == 0) {
+    // the controller's ports are numbered in the order they are connected
+    if (src_port != c->graph.nodes[0].d.n_out)
+      return fail(c, AMP_EINVAL, "connect: the controller's next free port is %d", c->graph.nodes[0].d.n_out);
+    c->graph.nodes[0].d.n_out++;
+  }
+  c->graph.connect(src, src_port, dst, dst_port);
+  return AMP_OK;
+}
+
+int amp_validate_graph(amp_ctx* c) {
+  if (!c) return AMP_EINVAL;
+  if (c->model) return AMP_OK;   // validated when it was built
+  if (c->graph.nodes.size() < 2) return fail(c, AMP_ESTATE, "validate_graph: no nodes added");
+  return lower_graph(c);
+}
+
+int amp_get_node_index(amp_ctx* c, int graph_node, int* param_node) {
+  if (!c || !param_node) return fail(c, AMP_EINVAL, "null argument");
+  if (!c->model) return fail(c, AMP_ESTATE, "get_node_index: validate the graph first");
+  if (graph_node < 0 || graph_node >= (int)c->param_of.size()) return fail(c, AMP_EINVAL, "no graph node %d", graph_node);
+  *param_node = c->param_of[graph_node];
   return AMP_OK;
 }
 
@@ -446,8 +530,11 @@ int amp_set_replicas(amp_ctx* c, int n_replicas) {
 
 int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_edges, size_t max_instances) {
   if (!c) return AMP_EINVAL;
-  if (!c->model) return fail(c, AMP_ESTATE, "finalize: no model graph built");
   if (c->finalized) return fail(c, AMP_ESTATE, "finalize: already finalized");
+  if (!c->model) {
+    if (c->graph.nodes.size() < 2) return fail(c, AMP_ESTATE, "finalize: no model graph built");
+    if (int rc = lower_graph(c)) return rc;   // a graph made with amp_add_node / amp_connect
+  }
   if (max_active_keys < 1 || max_active_keys > AMP_MAX_MAK)
     return fail(c, AMP_EINVAL, "finalize: max_active_keys must be in 1..%d", AMP_MAX_MAK);
   if (max_instance_len < 1 || max_instances < 1) return fail(c, AMP_EINVAL, "finalize: sizes must be >= 1");

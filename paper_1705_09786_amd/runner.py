@@ -22,7 +22,9 @@ class Trainer:
 
     def __init__(self, model: str, dims: dict, params, max_active_keys: int, max_len: int, max_edges: int,
                  max_instances: int, arena_bytes: int = 1 << 30, tiles: dict | None = None, device: str = "cuda:0",
-                 in_hbm=(), replicas: int = 1, strict: bool = False):
+                 in_hbm=(), replicas: int = 1, strict: bool = False, graph=None):
+        """graph: a callable that describes the model with add_node / connect on the context it is given, in place
+        of the canned builder for `model`."""
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the AMP path has no CPU fallback")
@@ -32,7 +34,11 @@ class Trainer:
         stream = torch.cuda.current_stream(self.arena.device).cuda_stream
         self.amp = B.Amp(ptr, arena_bytes, stream, strict=strict)
         self.model, self.dims = model, dims
-        self.amp.build(model, dims)
+        if graph is not None:
+            graph(self.amp)
+            self.amp.validate_graph(model)
+        else:
+            self.amp.build(model, dims)
         for node, n in (tiles or {}).items():
             self.amp.set_tiles(node, n)
         if replicas != 1:

@@ -155,3 +155,174 @@ def test_measure_peaks_needs_a_buffer():
     x, y = ct.c_double(), ct.c_double()
     assert B.lib().amp_measure_peaks(None, 1 << 30, None, ct.byref(x), ct.byref(y)) == B.AMP_EINVAL
     assert B.lib().amp_measure_peaks(ct.c_void_p(4096), 1 << 20, None, ct.byref(x), ct.byref(y)) == B.AMP_EINVAL
+
+
+# ---------------------------------------------------------------- generic graph construction
+def mlp_graph(a, d_in=5, hidden=4, n_class=3, hidden2=None):
+    """The pipelined MLP as a caller describes it: controller -> Linear+ReLU -> Linear+ReLU -> Linear -> loss."""
+    l1 = a.add_node("linear", hidden, d_in, aux=B.ACT_RELU)
+    l2 = a.add_node("linear", hidden, hidden2 or hidden, aux=B.ACT_RELU)
+    l3 = a.add_node("linear", n_class, hidden)
+    loss = a.add_node("softmax_xent", n_class)
+    a.connect(0, 0, l1, 0)
+    a.connect(l1, 0, l2, 0)
+    a.connect(l2, 0, l3, 0)
+    a.connect(l3, 0, loss, 0)
+    a.connect(0, 1, loss, 1)
+    return l1, l2, l3, loss
+
+
+def rnn_graph(a, vocab=6, emb=3, hidden=4, n_class=3, loop_through_phi=True):
+    """Figure 2's loop, nodes added in another order than the model numbers them."""
+    out = a.add_node("linear", n_class, hidden)
+    loss = a.add_node("softmax_xent", n_class)
+    cond = a.add_node("cond", n_out=2)
+    isu = a.add_node("isu")
+    cell = a.add_node("rnn_tanh", hidden, emb + hidden)
+    cat = a.add_node("concat", n_in=2)
+    lk = a.add_node("lookup", vocab, emb)
+    a.connect(0, 0, lk, 0)
+    if loop_through_phi:
+        phi = a.add_node("phi", n_in=2)
+        a.connect(0, 1, phi, 0)
+        a.connect(0, 2, loss, 1)
+        a.connect(phi, 0, cat, 1)
+        a.connect(cond, 0, phi, 1)
+    else:
+        a.connect(0, 1, loss, 1)
+        a.connect(cond, 0, cat, 1)      # the loop closes without a Phi
+    a.connect(lk, 0, cat, 0)
+    a.connect(cat, 0, cell, 0)
+    a.connect(cell, 0, isu, 0)
+    a.connect(isu, 0, cond, 0)
+    a.connect(cond, 1, out, 0)
+    a.connect(out, 0, loss, 0)
+    return dict(lookup=lk, cell=cell, out=out, loss=loss)
+
+
+def test_hand_built_graphs_are_recognised():
+    a = new_ctx()
+    l1, l2, l3, loss = mlp_graph(a)
+    a.validate_graph("mlp")
+    assert a.num_nodes() == 3
+    assert [a.get_node_index(n) for n in (l1, l2, l3, loss, 0)] == [0, 1, 2, -1, -1]
+    a.finalize(4, 1, 0, 3)
+    a.set_params(1, np.zeros(4 * 4 + 4, np.float32))
+    # the recurrent model, nodes added back to front: the parameterized nodes still carry the model's numbering
+    b = new_ctx()
+    ids = rnn_graph(b)
+    b.finalize(4, 8, 0, 3)                 # finalize validates a graph that has not been validated yet
+    assert b.num_nodes() == 3
+    assert [b.get_node_index(ids[k]) for k in ("lookup", "cell", "out", "loss")] == [0, 1, 2, -1]
+    b.set_params(1, np.zeros(4 * 7 + 4, np.float32))
+
+
+def test_graph_errors_the_host_can_force():
+    # dangling port: the label never reaches the loss layer
+    a = new_ctx()
+    l1 = a.add_node("linear", 4, 5, aux=B.ACT_RELU)
+    loss = a.add_node("softmax_xent", 4)
+    a.connect(0, 0, l1, 0)
+    a.connect(l1, 0, loss, 0)
+    with pytest.raises(B.AmpError, match="dangling port") as e:
+        a.validate_graph()
+    assert e.value.code == B.AMP_EINVAL
+    # dimension mismatch: the second layer takes 6 values, the first sends 4
+    a = new_ctx()
+    mlp_graph(a, hidden2=6)
+    with pytest.raises(B.AmpError, match="dimension mismatch") as e:
+        a.validate_graph()
+    assert e.value.code == B.AMP_EINVAL
+    # a cycle that does not pass through a Phi
+    a = new_ctx()
+    rnn_graph(a, loop_through_phi=False)
+    with pytest.raises(B.AmpError, match="cycle without a Phi") as e:
+        a.finalize(4, 8, 0, 3)
+    assert e.value.code == B.AMP_EINVAL
+    # a port connected twice; nodes and ports that do not exist; the controller's ports go in order
+    a = new_ctx()
+    l1 = a.add_node("linear", 4, 5)
+    l2 = a.add_node("linear", 4, 4)
+    a.connect(0, 0, l1, 0)
+    a.connect(l1, 0, l2, 0)
+    a.connect(l1, 0, l2, 0)
+    with pytest.raises(B.AmpError, match="connected twice"):
+        a.validate_graph()
+    a = new_ctx()
+    l1 = a.add_node("linear", 4, 5)
+    expect(B.AMP_EINVAL, a.connect, l1, 0, 9, 0)
+    expect(B.AMP_EINVAL, a.connect, 0, 3, l1, 0)
+    expect(B.AMP_EINVAL, a.connect, l1, 0, 0, 0)          # nothing connects into the controller
+    d = B.NodeDesc(1, 1, 1, 1, 0)
+    nid = ct.c_int()
+    assert a.L.amp_add_node(a.h, 99, ct.byref(d), ct.byref(nid)) == B.AMP_EINVAL
+    assert a.L.amp_add_node(a.h, 0, ct.byref(d), ct.byref(nid)) == B.AMP_EINVAL   # the controller exists already
+    # a valid graph the kernel has no workers for: a perceptron with one more layer
+    a = new_ctx()
+    ls = [a.add_node("linear", 4, 5, aux=B.ACT_RELU)] + [a.add_node("linear", 4, 4, aux=B.ACT_RELU) for _ in range(2)]
+    ls.append(a.add_node("linear", 3, 4))
+    loss = a.add_node("softmax_xent", 3)
+    a.connect(0, 0, ls[0], 0)
+    for x, y in zip(ls[:-1], ls[1:]):
+        a.connect(x, 0, y, 0)
+    a.connect(ls[-1], 0, loss, 0)
+    a.connect(0, 1, loss, 1)
+    with pytest.raises(B.AmpError) as e:
+        a.validate_graph()
+    assert e.value.code == B.AMP_EUNSUPPORTED
+    # phases: no nodes after a model is built, no canned model on top of added nodes
+    a = new_ctx()
+    a.build("mlp", dict(d_in=5, hidden=4, n_class=3))
+    expect(B.AMP_ESTATE, a.add_node, "linear", 4, 4)
+    expect(B.AMP_ESTATE, a.connect, 0, 0, 1, 0)
+    a = new_ctx()
+    a.add_node("linear", 4, 4)
+    expect(B.AMP_ESTATE, a.build, "mlp", dict(d_in=5, hidden=4, n_class=3))
+
+
+def test_hand_built_tree_and_graph_network():
+    """The two larger graphs written out by a caller: Tree-LSTM (Section 6) and the gated graph network of Figure
+    4(a) with two edge types and three propagation steps."""
+    H, E, V, C = 6, 5, 11, 3
+    a = new_ctx()
+    lk, leaf, br = a.add_node("lookup", V, E), a.add_node("leaf_lstm", H, E), a.add_node("branch_lstm", H)
+    out, loss = a.add_node("linear", C, H), a.add_node("softmax_xent", C)
+    phi, bc, sp = a.add_node("phi", n_in=2), a.add_node("bcast", n_out=2), a.add_node("split", n_out=2)
+    csink, cond, rsink = a.add_node("sink"), a.add_node("cond", n_out=2), a.add_node("sink")
+    isu, cat = a.add_node("isu"), a.add_node("concat", n_in=1, aux=2)
+    a.connect(0, 0, lk, 0)
+    a.connect(0, 1, loss, 1)
+    for s, sp_, d, dp in [(lk, 0, leaf, 0), (leaf, 0, phi, 0), (br, 0, phi, 1), (phi, 0, bc, 0), (bc, 0, sp, 0), (sp, 0, out, 0),
+                          (sp, 1, csink, 0), (out, 0, loss, 0), (bc, 1, cond, 0), (cond, 0, rsink, 0), (cond, 1, isu, 0),
+                          (isu, 0, cat, 0), (cat, 0, br, 0)]:
+        a.connect(s, sp_, d, dp)
+    a.validate_graph("tree")
+    assert a.num_nodes() == 4 and [a.get_node_index(n) for n in (lk, leaf, br, out)] == [0, 1, 2, 3]
+    n = ct.c_size_t()
+    assert a.L.amp_param_count(a.h, 2, ct.byref(n)) == 0 and n.value == 5 * H * 2 * H + 5 * H
+
+    g = new_ctx()
+    T, S, ne = 4, 3, 2
+    lk = g.add_node("lookup", T, H)
+    lin = [g.add_node("ggnn_edge_linear", H, H) for _ in range(ne)]
+    gru, ro, loss = g.add_node("gru", H), g.add_node("sum_readout", 1, H), g.add_node("squared_err")
+    phi_h, bc, ung, fm = g.add_node("phi", n_in=2), g.add_node("bcast", n_out=2), g.add_node("ungroup"), g.add_node("flatmap")
+    bytype, phi_e = g.add_node("cond", n_out=ne), g.add_node("phi", n_in=ne)
+    bydst, sm, alln, isu = g.add_node("group"), g.add_node("sum"), g.add_node("group"), g.add_node("isu")
+    done = g.add_node("cond", n_out=2, aux=S)
+    g.connect(0, 0, lk, 0)
+    g.connect(0, 1, loss, 1)
+    edges = [(lk, 0, phi_h, 0), (phi_h, 0, bc, 0), (bc, 0, ung, 0), (ung, 0, fm, 0), (fm, 0, bytype, 0)]
+    for c in range(ne):
+        grp, ungc = g.add_node("group"), g.add_node("ungroup")
+        edges += [(bytype, c, grp, 0), (grp, 0, lin[c], 0), (lin[c], 0, ungc, 0), (ungc, 0, phi_e, c)]
+    edges += [(phi_e, 0, bydst, 0), (bydst, 0, sm, 0), (sm, 0, alln, 0), (alln, 0, gru, 0), (bc, 1, gru, 1), (gru, 0, isu, 0),
+              (isu, 0, done, 0), (done, 0, phi_h, 1), (done, 1, ro, 0), (ro, 0, loss, 0)]
+    for e in edges:
+        g.connect(*e)
+    g.validate_graph("ggnn")
+    assert g.num_nodes() == 1 + ne + 3 + 1
+    assert [g.get_node_index(x) for x in [lk] + lin + [gru, ro]] == [0, 1, 2, 3, 6]
+    g.finalize(4, 9, 24, 5)
+    g.submit(dict(n_nodes=2, node_type=np.array([0, 1]), src=np.array([0, 1]), dst=np.array([1, 0]), etype=np.array([1, 1]),
+                  target=0.5))

@@ -73,6 +73,20 @@ def test_rnn_replay_parity(mak, muf, opt, n):
     compare(g, rt, len(data), opt=opt)
 
 
+def test_hand_built_graph_trains_like_the_canned_one():
+    """The recurrent model described node by node through amp_add_node / amp_connect (Figure 2's graph, nodes added
+    in another order than the model numbers them) and lowered by amp_finalize: same replay parity as the canned
+    builder's."""
+    from test_boundary_cpu import rnn_graph
+    dims = dict(vocab=13, emb=20, hidden=44, n_class=7)
+    data = synth.make_rnn(120, 31, dims, min_len=1, max_len=12)
+    fp = synth.init_params("rnn", dims, 7)
+    g = gpu_train("rnn", dims, fp, data, 8, 3, SGD, graph=lambda a: rnn_graph(a, **dims))
+    check_controller_log(g["logs"], 8, len(data))
+    rt = oracle_replay("rnn", dims, fp, data, g["logs"], 3, SGD)
+    compare(g, rt, len(data), opt=SGD)
+
+
 def max_in_flight(log):
     active = worst = 0
     for (_, kind, _, _) in log:
