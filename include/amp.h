@@ -328,6 +328,21 @@ int amp_train(amp_ctx *ctx, int epochs);
  * parameters (Section 1: inference runs through the same graph; Table 2's
  * validation throughput); nothing is recorded or updated. */
 int amp_eval(amp_ctx *ctx, amp_eval_result *out);
+/* Blocking: training and inference at the same time (Section 1: both kinds of
+ * instance travel through the same graph; an inference instance is a message
+ * that only runs forward).  One launch trains `epochs` passes over the
+ * training set and, interleaved with them, evaluates every instance of the
+ * evaluation set once: after every (training admissions / evaluation
+ * instances) training instances the controller admits one evaluation
+ * instance, marked forward-only -- it is scored with the parameters it meets
+ * on its way (which the training instances around it keep updating), records
+ * no activation, produces no gradient, and is retired by the loss layer.
+ * Both kinds count towards max_active_keys.  `out` receives the evaluation
+ * results; the training results are read as after amp_train (amp_get_loss,
+ * amp_get_instance_losses, amp_get_event_log: the controller's admission
+ * events carry local = 1 for evaluation instances, whose forward events are
+ * part of the record).  AMP_EUNSUPPORTED with replicas. */
+int amp_train_eval(amp_ctx *ctx, int epochs, amp_eval_result *out);
 
 /* Results of the last amp_train, as the experiments of Section 6 report them
  * (Tables 1 and 2: accuracy, instances per second): mean loss per instance,

@@ -18,6 +18,13 @@ What is simulated (citations are to the paper):
     the accumulator; the controller keeps at most max_active_keys instances
     in flight.
 
+Inference instances (Section 1: training and inference at the same time) are
+forward-only: the controller marks them at admission, parameterized nodes
+apply their present parameters without a gradient ever coming back, the loss
+layer scores them and does not start backpropagation, and the instance
+retires once all its predictions are scored; whatever the nodes cached for
+it on the way is dropped then.
+
 Two drivers:
   * run():    one worker hosts every node; backward messages are served
               before forward ones, first-in first-out within each class
@@ -237,6 +244,9 @@ class Loss(Node):
         else:
             loss, dz, _ = C.squared_error(slot[0], float(slot[1]))
             rt.record(msg.state[0], loss, 0, 1, yhat=float(np.ravel(slot[0])[0]))
+        if rt.is_eval(msg.state[0]):
+            rt.eval_scored(msg.state[0])    # an inference instance: scored, nothing turns round
+            return
         rt.emit_bwd(self, 0, Msg(dz, msg.state))
         rt.emit_bwd(self, 1, Msg(None, msg.state))
 
@@ -378,7 +388,8 @@ class Flatmap(Node):
     def forward(self, rt, port, msg):
         states = self.gen_fn(rt, msg.state)
         if not states:
-            rt.emit_bwd(self, 0, Msg(np.zeros_like(msg.payload), msg.state))
+            if not rt.is_eval(msg.state[0]):
+                rt.emit_bwd(self, 0, Msg(np.zeros_like(msg.payload), msg.state))
             return
         self.pend[msg.state] = [None] * len(states)
         for i, st in enumerate(states):
@@ -402,7 +413,8 @@ class Sink(Node):
     """End of a path that carries no loss: answers with a zero gradient."""
 
     def forward(self, rt, port, msg):
-        rt.emit_bwd(self, 0, Msg(np.zeros_like(msg.payload), msg.state))
+        if not rt.is_eval(msg.state[0]):
+            rt.emit_bwd(self, 0, Msg(np.zeros_like(msg.payload), msg.state))
 
 
 class Controller(Node):
@@ -436,6 +448,9 @@ class Runtime:
         self.retired = []
         self.loss, self.correct, self.npred, self.yhat = {}, {}, {}, {}
         self.max_staleness, self.limit, self.updates_at = None, 1, {}
+        self.eval_seqs = set()      # admission numbers of forward-only (inference) instances
+        self.seq_inst = {}          # admission number -> instance, where it is not instances[seq % len]
+        self.eval_pending = {}      # predictions an inference instance in flight still waits for
 
     # ---- graph construction helpers
     def add(self, node):
@@ -471,7 +486,34 @@ class Runtime:
 
     # ---- message plumbing
     def inst(self, seq):
+        if seq in self.seq_inst:
+            return self.seq_inst[seq]
         return self.instances[seq % len(self.instances)]
+
+    def is_eval(self, seq):
+        return seq in self.eval_seqs
+
+    def mark_eval(self, seq, inst):
+        """Admission number `seq` will be an inference instance: `inst`, forward only."""
+        self.eval_seqs.add(seq)
+        self.seq_inst[seq] = inst
+
+    def eval_scored(self, seq):
+        self.eval_pending[seq] -= 1
+        if self.eval_pending[seq] == 0:
+            del self.eval_pending[seq]
+            self.active -= 1
+            self.retired.append(seq)
+            self.events.append(("controller", "R", (seq, 0)))
+            # what the nodes cached for the instance on its way forward is never asked for again
+            for n in self.nodes:
+                for attr in ("stash", "pend", "cache", "origin", "parent"):
+                    d = getattr(n, attr, None)
+                    if d:
+                        for key in [k for k in d if isinstance(k, tuple) and k[0] == seq]:
+                            del d[key]
+            self.open_fwd = {t for t in self.open_fwd if t[2][0] != seq}
+            self.pending_sources.pop(seq, None)
 
     def emit_fwd(self, node, port, msg):
         tag = (id(node), port, msg.state)
@@ -524,6 +566,9 @@ class Runtime:
     def admit(self, seq):
         msgs = PUMPS[self.model](self, seq, self.inst(seq))
         self.pending_sources[seq] = len(msgs)
+        if self.is_eval(seq):
+            # one prediction per instance; one per tree node for the tree model
+            self.eval_pending[seq] = 2 * self.inst(seq)["n_leaves"] - 1 if self.model == "tree" else 1
         self.active += 1
         self.max_active_seen = max(self.max_active_seen, self.active)
         self.events.append(("controller", "A", (seq, 0)))
@@ -548,7 +593,33 @@ class Runtime:
                     self.limit += 1
 
     # ---- driver 1: own schedule
-    def run(self, instances, mak, epochs=1, first_seq=0, max_staleness=None):
+    def run_mixed(self, train, evals, mak, epochs=1, first_seq=0):
+        """Training and inference instances in one run (Section 1): `epochs` passes over `train`, and every
+        instance of `evals` once, forward only, interleaved -- after every (training admissions // inference
+        instances) training admissions the controller admits one inference instance.  Returns (losses of the
+        training admissions, losses of the inference instances), each in its own admission order."""
+        n_tr, n_ev = len(train) * epochs, len(evals)
+        stride = max(1, n_tr // n_ev)
+        order, it, ie = [], 0, 0
+        while it < n_tr or ie < n_ev:
+            for _ in range(stride):
+                if it < n_tr:
+                    order.append(("t", it))
+                    it += 1
+            if ie < n_ev:
+                order.append(("e", ie))
+                ie += 1
+        for a, (kind, i) in enumerate(order):
+            if kind == "e":
+                self.mark_eval(first_seq + a, evals[i])
+            else:
+                self.seq_inst[first_seq + a] = train[i % len(train)]
+        self.run(train, mak, first_seq=first_seq, n_admissions=len(order))
+        tl = [self.loss[first_seq + a] for a, (kind, _) in enumerate(order) if kind == "t"]
+        el = [self.loss[first_seq + a] for a, (kind, _) in enumerate(order) if kind == "e"]
+        return tl, el
+
+    def run(self, instances, mak, epochs=1, first_seq=0, max_staleness=None, n_admissions=None):
         """Train on `instances` in order, `epochs` times; returns the list of
         per-instance losses in admission order.  The controller is the greedy
         one (a new instance whenever fewer than mak are in flight) unless
@@ -561,7 +632,7 @@ class Runtime:
         self.max_staleness = max_staleness
         self.limit = 1
         self.updates_at = {}
-        total = first_seq + len(instances) * epochs
+        total = first_seq + (len(instances) * epochs if n_admissions is None else n_admissions)
         nxt = first_seq
         while True:
             while self.active < (mak if max_staleness is None else min(mak, self.limit)) and nxt < total:

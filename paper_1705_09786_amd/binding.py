@@ -99,6 +99,7 @@ SIGNATURES = {
     "amp_get_admission": (ct.c_int, [_ctxp, ct.POINTER(ct.c_int), ct.POINTER(ct.c_int)]),
     "amp_train": (ct.c_int, [_ctxp, ct.c_int]),
     "amp_eval": (ct.c_int, [_ctxp, ct.POINTER(EvalResult)]),
+    "amp_train_eval": (ct.c_int, [_ctxp, ct.c_int, ct.POINTER(EvalResult)]),
     "amp_get_loss": (ct.c_int, [_ctxp, ct.POINTER(ct.c_double), ct.POINTER(ct.c_double),
                                 ct.POINTER(ct.c_uint64), ct.POINTER(ct.c_double)]),
     "amp_get_instance_losses": (ct.c_int, [_ctxp, _f32p, ct.c_size_t, ct.POINTER(ct.c_size_t)]),
@@ -310,6 +311,13 @@ class Amp:
     def eval(self):
         r = EvalResult()
         self._chk(self.L.amp_eval(self.h, ct.byref(r)))
+        return dict(mean_loss=r.mean_loss, accuracy=r.accuracy, n_instances=r.n_instances,
+                    n_predictions=r.n_predictions, seconds=r.seconds)
+
+    def train_eval(self, epochs=1):
+        """Training and evaluation instances mixed in one launch; returns the evaluation results."""
+        r = EvalResult()
+        self._chk(self.L.amp_train_eval(self.h, epochs, ct.byref(r)))
         return dict(mean_loss=r.mean_loss, accuracy=r.accuracy, n_instances=r.n_instances,
                     n_predictions=r.n_predictions, seconds=r.seconds)
 

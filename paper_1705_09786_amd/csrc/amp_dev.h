@@ -150,6 +150,9 @@ struct AmpDev {
   unsigned* ctl;              // [0] abort code, [1] done, [2] abort detail, [3] updates applied by all workers,
                               // [4] largest number of instances in flight, [5] admission limit at the end
   unsigned* slot_seq;         // [mak] admission number held by each slot
+  int* slot_inst;             // [mak] the slot's instance: index into the launch's instance set; sign bit set = a
+                              // forward-only (evaluation) instance, which the loss layer retires instead of turning round
+  const int* adm_inst;        // [n_total] the same word for every admission of the launch, in admission order
   int* smeta;                 // [mak][4] written at admission: admission number, length, node offset (RNN: instance), token offset
   float* loss_out;            // [n_total] summed loss of each admission
   int* correct_out;           // [n_total]

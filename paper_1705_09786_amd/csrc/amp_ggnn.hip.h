@@ -51,6 +51,7 @@ struct GData {
   const GQ int *tok_off, *edge_off, *tok, *src, *dst, *tcount, *inoff, *inedge, *tstart, *tedge, *tsoff, *tsk;
   const GQ float* target;
   const GQ unsigned* slot_seq;
+  const GQ int* slot_inst;
   int n_inst, T;
 };
 
@@ -70,14 +71,15 @@ __device__ __forceinline__ GData g_data(const GQ AmpDev* D) {
   d.tsk = uni_gq<int>(D->data.tsk);
   d.target = uni_gq<float>(D->data.target);
   d.slot_seq = uni_gq<unsigned>(D->slot_seq);
+  d.slot_inst = uni_gq<int>(D->slot_inst);
   d.n_inst = uni(D->data.n_inst);
   d.T = uni(D->n_edge_types);
   return d;
 }
 
-__device__ __forceinline__ GView g_view(const GData& d, unsigned seq) {
+__device__ __forceinline__ GView g_view(const GData& d, int s) {
   GView v;
-  v.inst = seq % d.n_inst;
+  v.inst = uni(d.slot_inst[s]) & 0x7fffffff;
   const int to = uni(d.tok_off[v.inst]), eo = uni(d.edge_off[v.inst]);
   v.N = uni(d.tok_off[v.inst + 1]) - to;
   v.E = uni(d.edge_off[v.inst + 1]) - eo;
@@ -397,7 +399,7 @@ __device__ __noinline__ void role_g_lookup(const GQ AmpDev* D, const GQ WorkerDe
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code);
     const unsigned seq = uni(gd.slot_seq[s]);
-    const GView v = g_view(gd, seq);
+    const GView v = g_view(gd, s);
     const unsigned present = g_present_types(v, B.T);
     if (!(code & MSG_DIR_B)) {
       GQ float* h0 = B.Hm + B.hm(s, 0);
@@ -483,7 +485,7 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
     head++;
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
     const unsigned seq = uni(gd.slot_seq[s]);
-    const GView v = g_view(gd, seq);
+    const GView v = g_view(gd, s);
     const int K = uni(v.tcount[ctype]), NB = (K + 15) >> 4;
     const GQ int* te = v.tedge + uni(v.tstart[ctype]);   // edges of this type, ascending (Group orders its rows by edge index)
     const GQ float* h = B.Hm + B.hm(s, it);
@@ -641,7 +643,7 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
     head++;
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
     const unsigned seq = uni(gd.slot_seq[s]);
-    const GView v = g_view(gd, seq);
+    const GView v = g_view(gd, s);
     const int K = v.N, NB = (K + 15) >> 4;
     GQ float* A = B.A + B.st(s, it);
     const GQ float* h = B.Hm + B.hm(s, it);
@@ -827,7 +829,7 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
     head++;
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
     const unsigned seq = uni(gd.slot_seq[s]);
-    const GView v = g_view(gd, seq);
+    const GView v = g_view(gd, s);
     const unsigned present = g_present_types(v, B.T);
     const int K = v.N, NB = (K + 15) >> 4;
     const GQ float* A = B.A + B.st(s, it);
@@ -1002,7 +1004,7 @@ __device__ __noinline__ void role_g_readout(const GQ AmpDev* D, const GQ WorkerD
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code);
     const unsigned seq = uni(gd.slot_seq[s]);
-    const GView v = g_view(gd, seq);
+    const GView v = g_view(gd, s);
     const GQ float* h = B.Hm + B.hm(s, B.S);
     for (int j = threadIdx.x; j < H; j += AMP_THREADS) {
       float a = 0.f;
@@ -1025,7 +1027,7 @@ __device__ __noinline__ void role_g_readout(const GQ AmpDev* D, const GQ WorkerD
       ((GQ float*)D->loss_out)[seq - D->first_seq] = 0.5f * d * d;
       ((GQ float*)D->yhat_out)[seq - D->first_seq] = yhat;
     }
-    if (!D->train) {
+    if (!D->train || uni(gd.slot_inst[s]) < 0) {   // an evaluation instance: retired here, nothing turns round
       publish_barrier();
       if (threadIdx.x == 0) {
         fence_release();

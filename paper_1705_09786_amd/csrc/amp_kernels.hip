@@ -89,12 +89,15 @@ __device__ __noinline__ void role_ctrl(const GQ AmpDev* D, const GQ WorkerDev* W
       while (active < limit && next < n_total) {
         const int s = freelist[--nfree];
         const unsigned seq = D->first_seq + next;
+        // which instance this admission is, and whether it only runs forward (training and inference instances
+        // share a launch: Section 1)
+        const int word = D->adm_inst[next], inst = word & 0x7fffffff;
         if (bounded) upd_at[s] = ld_u32(&D->ctl[3]);
         D->slot_seq[s] = seq;
-        log_event(D, W, &s_logn, 0, 3, seq, 0);
+        D->slot_inst[s] = word;
+        log_event(D, W, &s_logn, 0, 3, seq, word < 0 ? 1u : 0u);
         if (D->model == 3) {
           // tree: the slot's instance facts for the workers, then one token message per leaf to the lookup (worker 1)
-          const int inst = seq % D->data.n_inst;
           const int toff = D->data.tok_off[inst], L = D->data.tok_off[inst + 1] - toff;
           int* sm = D->smeta + 4 * s;
           sm[0] = (int)seq;
@@ -107,7 +110,6 @@ __device__ __noinline__ void role_ctrl(const GQ AmpDev* D, const GQ WorkerDev* W
         } else {
           if (D->model == 2) {
             // RNN: admission number, length, instance, token offset
-            const int inst = seq % D->data.n_inst;
             const int toff = D->data.tok_off[inst];
             int* sm = D->smeta + 4 * s;
             sm[0] = (int)seq;
@@ -207,9 +209,9 @@ __device__ __noinline__ void role_mlp_lin(const GQ AmpDev* D, const GQ WorkerDev
   const GQ int* lab = uni_gq<int>(D->data.lab);
   const GQ int* lab_off = uni_gq<int>(D->data.lab_off);
   const GQ unsigned* slot_seq = uni_gq<unsigned>(D->slot_seq);
+  const GQ int* slot_inst = uni_gq<int>(D->slot_inst);
   GQ float* loss_out = uni_gq<float>(D->loss_out);
   GQ int* correct_out = uni_gq<int>(D->correct_out);
-  const int n_inst = uni(D->data.n_inst);
   const unsigned first_seq = uni(D->first_seq);
   const int ring = uni(W->ring);
   const Ring mine = ring_regs(D, ring), next = ring_regs(D, last ? ring : ring + 1), prev = ring_regs(D, ring - 1), ctl = ring_regs(D, 0);
@@ -218,7 +220,8 @@ __device__ __noinline__ void role_mlp_lin(const GQ AmpDev* D, const GQ WorkerDev
   while (wait_msg(D, mine, head, s_ctl, code)) {
     const int s = MSG_SLOT(code);
     const unsigned seq = uni(slot_seq[s]);
-    const int inst = seq % n_inst;
+    const int word = uni(slot_inst[s]), inst = word & 0x7fffffff;
+    const bool fwd_only = !train || word < 0;   // an evaluation instance: the loss layer retires it
     const GQ float* x = first ? datax + (long long)inst * C : act_in + (long long)s * C;
     bool backward = (code & MSG_DIR_B) != 0;
     for (int c = threadIdx.x; c < C; c += AMP_THREADS) xs[c] = x[c];
@@ -244,7 +247,7 @@ __device__ __noinline__ void role_mlp_lin(const GQ AmpDev* D, const GQ WorkerDev
         loss_out[seq - first_seq] = s_loss;
         correct_out[seq - first_seq] = s_pred == label;
       }
-      if (!train) {
+      if (fwd_only) {
         publish_barrier();
         if (threadIdx.x == 0) {
           fence_release();

@@ -94,7 +94,7 @@ struct amp_ctx {
   Resident resident[2];
   // arena layout
   size_t static_end = 0;   // everything below is laid out at finalize
-  size_t off_dev = 0, off_ctl = 0, off_slot_seq = 0, off_clock = 0, off_smeta = 0;
+  size_t off_dev = 0, off_ctl = 0, off_slot_seq = 0, off_clock = 0, off_smeta = 0, off_slot_inst = 0;
   std::vector<size_t> off_ring_ent, off_ring_tail;
   size_t sync_end = 0;   // [0, sync_end) of a replica's region: stop word, clock, slot tables, rings -- zero at every launch
   unsigned ring_cap = 0;
@@ -637,6 +637,7 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
   c->off_clock = take(64);
   c->off_slot_seq = take(sizeof(unsigned) * c->max_mak);
   c->off_smeta = take(16 * (size_t)c->max_mak);
+  c->off_slot_inst = take(sizeof(int) * c->max_mak);
   const size_t per_inst_msgs = 4 * (size_t)NN + 8;
   c->ring_cap = next_pow2(per_inst_msgs * c->max_mak);
   c->off_ring_ent.assign(nrings, 0);
@@ -1124,8 +1125,11 @@ int make_resident(amp_ctx* c, const InstSet& S, int R, size_t begin, Resident& r
 
 // One launch: every replica trains (or evaluates) `epochs` passes over its own instance set.
 // losses / correct: per replica, per admission of this launch.  Launch outputs lie from `out_begin` on.
+// adm: per replica, one word per admission of the launch -- the instance's index in the replica's set, sign bit set for
+// a forward-only (evaluation) instance; nullptr = `epochs` passes over the set in order, all of the launch's kind.
 int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, bool train,
-                std::vector<std::vector<float>>& losses, std::vector<std::vector<int>>& correct, double& seconds) {
+                std::vector<std::vector<float>>& losses, std::vector<std::vector<int>>& correct, double& seconds,
+                const std::vector<std::vector<int>>* adm = nullptr) {
   const int R = res.R;
   const size_t wpr = c->workers.size();
   size_t off = out_begin;
@@ -1135,14 +1139,14 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
     return o;
   };
   std::vector<AmpDev> Ds(R);
-  std::vector<size_t> off_loss(R), off_correct(R), off_yhat(R), n_total(R), off_stats(R);
+  std::vector<size_t> off_loss(R), off_correct(R), off_yhat(R), n_total(R), off_stats(R), off_adm(R);
   std::vector<std::vector<size_t>> off_log(R, std::vector<size_t>(wpr)), off_logn(R, std::vector<size_t>(wpr));
   const size_t log_cap = train ? c->log_cap : 0;
   const size_t off_devs = take(sizeof(AmpDev) * R);
   // what the host reads after every launch lies together: one copy brings it back
   const size_t res_begin = off;
   for (int r = 0; r < R; ++r) {
-    n_total[r] = res.n[r] * (size_t)epochs;
+    n_total[r] = adm ? (*adm)[r].size() : res.n[r] * (size_t)epochs;
     off_loss[r] = take(n_total[r] * 4);
     off_correct[r] = take(n_total[r] * 4);
     off_stats[r] = take(8 * NSTAT * wpr);
@@ -1155,8 +1159,22 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
   const size_t zero_end = off;
   for (int r = 0; r < R; ++r)
     for (size_t w = 0; w < wpr; ++w) off_log[r][w] = take(8 * std::max<size_t>(log_cap, 1));
+  for (int r = 0; r < R; ++r) off_adm[r] = take(4 * std::max<size_t>(n_total[r], 1));
   if (off > c->arena_bytes) return fail(c, AMP_ENOMEM, "%s of %zu bytes is too small, %zu needed", arena_name(c), c->arena_bytes, off);
   HIPCHK(c, hipMemsetAsync(c->arena + res_begin, 0, zero_end - res_begin, c->stream));
+  // the admission list of every replica
+  std::vector<std::vector<int>> plain;
+  if (!adm) {
+    plain.resize(R);
+    for (int r = 0; r < R; ++r) {
+      plain[r].resize(n_total[r]);
+      for (size_t i = 0; i < n_total[r]; ++i) plain[r][i] = (int)(i % res.n[r]);
+    }
+    adm = &plain;
+  }
+  for (int r = 0; r < R; ++r)
+    if (n_total[r])
+      HIPCHK(c, hipMemcpyAsync(c->arena + off_adm[r], (*adm)[r].data(), 4 * n_total[r], hipMemcpyHostToDevice, c->stream));
   for (int r = 0; r < R; ++r) {
     AmpDev& D = Ds[r];
     std::memset(&D, 0, sizeof D);
@@ -1248,6 +1266,8 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
     D.ctl = (unsigned*)rep_ptr(c, r, c->off_ctl);
     D.slot_seq = (unsigned*)rep_ptr(c, r, c->off_slot_seq);
     D.smeta = (int*)rep_ptr(c, r, c->off_smeta);
+    D.slot_inst = (int*)rep_ptr(c, r, c->off_slot_inst);
+    D.adm_inst = (const int*)(c->arena + off_adm[r]);
     D.loss_out = (float*)(c->arena + off_loss[r]);
     D.correct_out = (int*)(c->arena + off_correct[r]);
     D.yhat_out = (float*)(c->arena + off_yhat[r]);
@@ -1325,6 +1345,9 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
   return AMP_OK;
 }
 
+int prepare_device(amp_ctx* c);
+int run_prepared(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev);
+
 int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   InstSet& S = c->sets[which];
   if (S.n() == 0) return fail(c, AMP_ESTATE, "no instances submitted");
@@ -1338,6 +1361,14 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   const int R = train ? c->replicas : 1;
   const size_t wpr = c->workers.size();
   if (S.n() < (size_t)R) return fail(c, AMP_EINVAL, "fewer instances (%zu) than replicas (%d)", S.n(), R);
+  if (int rc = prepare_device(c)) return rc;
+  return run_prepared(c, which, epochs, train, ev);
+}
+
+// Everything a launch needs on the device besides the instances: a device with enough compute units, zeroed
+// accumulators and counters at the first use, the parameters the host changed.
+int prepare_device(amp_ctx* c) {
+  const size_t wpr = c->workers.size();
   int dev_id = 0;
   HIPCHK(c, hipGetDevice(&dev_id));
   hipDeviceProp_t prop;
@@ -1365,7 +1396,13 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
         HIPCHK(c, hipMemcpyAsync(rep_ptr(c, r, n.off_P), n.params.data(), n.count() * 4, hipMemcpyHostToDevice, c->stream));
       n.dirty = false;
     }
+  return AMP_OK;
+}
 
+int run_prepared(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
+  InstSet& S = c->sets[which];
+  const int R = train ? c->replicas : 1;
+  const size_t wpr = c->workers.size();
   // The set stays in the arena from call to call: the training set first, the evaluation set behind it.
   Resident& res = c->resident[which];
   const Resident& other = c->resident[1 - which];
@@ -1426,9 +1463,83 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   return AMP_OK;
 }
 
+// Training and evaluation instances in one launch (Section 1: training and inference run through the same graph at
+// the same time): the two sets are laid out as one, the admission list interleaves them -- after every `stride`
+// training admissions one evaluation instance, stride = training admissions / evaluation instances -- and the
+// evaluation instances are marked forward-only.
+int run_mixed(amp_ctx* c, int epochs, amp_eval_result* ev) {
+  InstSet &T = c->sets[0], &E = c->sets[1];
+  if (T.n() == 0 || E.n() == 0) return fail(c, AMP_ESTATE, "train_eval: both instance sets must hold instances");
+  if (c->replicas != 1) return fail(c, AMP_EUNSUPPORTED, "train_eval: not with replicas");
+  if (c->model == AMP_MODEL_TREE && c->nodes[0].muf > AMP_TREE_LOOKUP_MAX_MUF)
+    return fail(c, AMP_EUNSUPPORTED, "the tree lookup supports min_update_frequency up to %d", AMP_TREE_LOOKUP_MAX_MUF);
+  for (const HostNode& n : c->nodes)
+    if (n.name != "lookup" && n.muf > AMP_DENSE_MAX_MUF)
+      return fail(c, AMP_EUNSUPPORTED, "dense nodes support min_update_frequency up to %d", AMP_DENSE_MAX_MUF);
+  const size_t n_tr = T.n() * (size_t)epochs, n_ev = E.n();
+  if (n_tr + n_ev >= 0x7fffffffull) return fail(c, AMP_EINVAL, "too many admissions for one call");
+  if (int rc = prepare_device(c)) return rc;
+  // one set: training instances first, evaluation instances behind them
+  InstSet both;
+  for (size_t i = 0; i < T.n(); ++i) append_instance(c, both, T, i);
+  for (size_t i = 0; i < E.n(); ++i) append_instance(c, both, E, i);
+  c->resident[0].valid = c->resident[1].valid = false;   // the combined set takes their place in the arena
+  Resident res;
+  if (int rc = make_resident(c, both, 1, c->static_end, res)) return rc;
+  HIPCHK(c, hipStreamSynchronize(c->stream));   // `both` is pageable host memory
+  std::vector<std::vector<int>> adm(1);
+  std::vector<int>& a = adm[0];
+  const size_t stride = std::max<size_t>(1, n_tr / n_ev);
+  size_t it = 0, ie = 0;
+  while (it < n_tr || ie < n_ev) {
+    for (size_t k = 0; k < stride && it < n_tr; ++k, ++it) a.push_back((int)(it % T.n()));
+    if (ie < n_ev) a.push_back((int)(T.n() + ie++) | (int)0x80000000);
+  }
+  std::vector<std::vector<float>> losses(1);
+  std::vector<std::vector<int>> correct(1);
+  double seconds = 0;
+  c->launch_events.assign(c->workers.size(), std::vector<amp_event>());
+  if (int rc = launch_once(c, res, res.end, 1, true, losses, correct, seconds, &adm)) return rc;
+  HIPCHK(c, hipStreamSynchronize(c->stream));
+  // split the results by kind, each in its own admission order
+  c->last_loss.clear();
+  c->last_correct.clear();
+  double sl = 0;
+  uint64_t sc = 0;
+  for (size_t i = 0; i < a.size(); ++i) {
+    if (a[i] < 0) {
+      sl += losses[0][i];
+      sc += correct[0][i];
+    } else {
+      c->last_loss.push_back(losses[0][i]);
+      c->last_correct.push_back(correct[0][i]);
+    }
+  }
+  c->last_seconds = seconds;
+  c->last_npred = c->model == AMP_MODEL_TREE ? (uint64_t)T.lab.size() * epochs : n_tr;
+  c->last_events.clear();
+  for (auto& v : c->launch_events) c->last_events.insert(c->last_events.end(), v.begin(), v.end());
+  c->launch_events.clear();
+  c->last_replicas = 1;
+  const uint64_t npred = c->model == AMP_MODEL_TREE ? (uint64_t)E.lab.size() : n_ev;
+  ev->mean_loss = sl / (double)n_ev;
+  ev->accuracy = c->model == AMP_MODEL_GGNN ? 0.0 : (double)sc / (double)npred;
+  ev->n_instances = n_ev;
+  ev->n_predictions = npred;
+  ev->seconds = seconds;
+  return AMP_OK;
+}
+
 }  // namespace
 
 extern "C" {
+
+int amp_train_eval(amp_ctx* c, int epochs, amp_eval_result* out) {
+  if (!c || !out) return fail(c, AMP_EINVAL, "null argument");
+  if (!c->finalized) return fail(c, AMP_ESTATE, "train_eval: finalize first");
+  if (epochs < 1) return fail(c, AMP_EINVAL, "train_eval: epochs must be >= 1");
+  return run_mixed(c, epochs, out);
+}
 
 int amp_train(amp_ctx* c, int epochs) {
   if (!c) return AMP_EINVAL;

@@ -337,7 +337,7 @@ __device__ __noinline__ void role_rnn_out(const GQ AmpDev* D, const GQ WorkerDev
       D->loss_out[seq - D->first_seq] = s_loss;
       D->correct_out[seq - D->first_seq] = s_pred == label;
     }
-    if (!D->train) {
+    if (!D->train || D->slot_inst[s] < 0) {   // an evaluation instance: retired here, nothing turns round
       publish_barrier();
       if (threadIdx.x == 0) {
         fence_release();

@@ -1314,6 +1314,7 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
   const int R = t.R, C = t.C, H = B.H, Hp = B.Hp, KB = wr.kb, ldw = t.ldw, nd_muf = uni(nd.muf);
   const GQ int* smeta = uni_gq<int>(D->smeta);
   const GQ int* tnode = uni_gq<int>(D->data.tnode);
+  const GQ int* slot_inst = uni_gq<int>(D->slot_inst);
   Lds L{lds};
   float* Wg = L.take(t.Rp * t.ldw);
   float* bg = L.take(t.Rp);
@@ -1359,11 +1360,32 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
         M.a[k] = tn.w;
         M.par[k] = tn.z;
         M.L[k] = sm.y;
-        M.aux[k] = 0;
+        // 1 = a node of an evaluation instance: scored, then counted towards the instance's retirement; no gradient
+        M.aux[k] = (!wr.train || slot_inst[s] < 0) ? 1 : 0;
         M.off0[k] = (int)(B.node(s, nn) * 2 * Hp);
         M.dst0[k] = (int)(B.node(s, nn) * H);
       }
-      batch_split_and_log(D, wr, M, n, 3, wr.train != 0);
+      // the event record: a training node's message is a forward event followed by a backward event (the loss turns
+      // it round in place), an evaluation node's a forward event only
+      {
+        const bool in = k < n, tr = in && M.aux[k] == 0;
+        const unsigned long long mt = __ballot(tr);
+        if (k == 0) M.nB = __popcll(mt);   // gradients in this batch
+        if (wr.log_cap) {
+          const unsigned base = s_logn, at = base + (unsigned)k + (unsigned)__popcll(mt & ((1ull << k) - 1ull));
+          const unsigned total = (unsigned)n + (unsigned)__popcll(mt);
+          if (base + total > wr.log_cap) {
+            if (k == 0) raise_abort(D, ABORT_LOG_FULL, blockIdx.x);
+          } else {
+            if (in) {
+              const unsigned long long tail = ((unsigned long long)M.seq[k] << 32) | (3ull << 20) | ((unsigned)M.n[k] & 0xfffffu);
+              wr.log[at] = tail;
+              if (tr) wr.log[at + 1] = tail | (1ull << 28);
+            }
+            if (k == 0) s_logn = base + total;
+          }
+        }
+      }
     }
     lds_barrier();
     for (int idx = threadIdx.x; idx < n * (Hp >> 2); idx += AMP_THREADS) {
@@ -1403,7 +1425,9 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
       for (int r = 0; r < R; ++r) se += expf(z[r] - m);
       const float zl = z[label];
       const float inv = 1.f / se;
-      for (int r = 0; r < R; ++r) z[r] = expf(z[r] - m) * inv - (r == label ? 1.f : 0.f);
+      // d logits; zero for an evaluation node, which then adds nothing to the gradient sums below
+      const float keep = M.aux[k] ? 0.f : 1.f;
+      for (int r = 0; r < R; ++r) z[r] = keep * (expf(z[r] - m) * inv - (r == label ? 1.f : 0.f));
       const unsigned idx = M.seq[k] - D->first_seq;
       __hip_atomic_fetch_add((GQ float*)&D->loss_out[idx], -(zl - m - logf(se)), __ATOMIC_RELAXED, AGENT);
       if (am == label) __hip_atomic_fetch_add((GQ int*)&D->correct_out[idx], 1, __ATOMIC_RELAXED, AGENT);
@@ -1435,7 +1459,7 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
       fence_release();
       const int k = threadIdx.x;
       if (k < n) {
-        if (!wr.train) {
+        if (M.aux[k]) {
           if (atomicAdd((int*)&done_cnt[M.s[k]], 1) + 1 == 2 * M.L[k] - 1) {
             done_cnt[M.s[k]] = 0;
             ring_post(wr.ctl, MSG_MAKE(1, M.s[k], 0));
@@ -1446,7 +1470,7 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
       }
     }
     if (D->train) {
-      count += n;
+      count += M.nB;
       if ((int)count >= nd.muf) {
         // the node's own update (Section 3)
         tstep++;

@@ -320,8 +320,11 @@ GG_ODD = dict(n_node_types=5, hidden=37, n_edge_types=3, n_steps=3)
 
 # The graph model under Adam at lr = 0.002 trains at the edge of stability: repeated runs (each with its own
 # event order) put the worst per-graph loss between 2e-6 and 4e-5 off the checker while the parameters agree to
-# 1e-6, whatever eps is; at lr = 0.001 and below the worst loss difference is below 1e-6 in every run.
-G_ADAM = dict(ADAM)
+# 1e-6, whatever eps is.  At lr = 5e-4 the worst loss difference of a run is 2e-7 .. 1e-6 in 118 of 120 runs
+# measured (60 with each build of the join), but two runs, one with either build, reached 6e-6 and 1.3e-5: each
+# run has its own event order, and a few orders amplify the rounding differences far more than the typical one.
+# The case therefore runs at lr = 2e-4, which leaves that tail a margin under 1e-5.
+G_ADAM = dict(ADAM, lr=0.0002)
 
 
 @pytest.mark.parametrize("mak,muf,opt,n", [(1, 1, dict(kind="sgd", lr=0.01), 40), (32, 20, G_ADAM, 300), (8, 3, MOM, 150)])
@@ -402,6 +405,72 @@ def test_eval_matches_direct_forward(cfg, n, nv):
     assert ev2["accuracy"] == ev["accuracy"]
     # and training can continue afterwards
     a.train(1)
+
+
+@pytest.mark.parametrize("cfg,n,nv,mak,muf", [(1, 300, 60, 4, 3), (2, 200, 50, 8, 5), (3, 60, 24, 16, 7), (4, 120, 30, 8, 6)])
+def test_train_and_eval_instances_in_one_launch(cfg, n, nv, mak, muf):
+    """Section 1: training and inference at the same time.  One launch trains on the training set while the
+    evaluation set's instances travel through the same graph forward-only, interleaved by the controller.  The
+    event record (admissions marked as inference, the forward events of inference instances included) is replayed
+    by the checker: parameters, the training instances' losses and every inference instance's loss -- taken with
+    whatever parameters it met on the way -- must agree."""
+    from paper_1705_09786_amd import runner
+    if cfg == 3:
+        model, dims = "tree", TREE_ODD
+        data, valid = synth.make_tree(n, 21, dims, max_leaves=24), synth.make_tree(nv, 1021, dims, max_leaves=24)
+        kw = dict(tiles={1: 2, 2: 3}, lookup_muf=11)
+    else:
+        model, dims, data = synth.workload(cfg, n=n)
+        _, _, valid = synth.workload(cfg, n=nv, valid=True)
+        kw = {}
+    fp = synth.init_params(model, dims, 10 + cfg)
+    ml, me = runner.max_len_of(model, data + valid)
+    opt = dict(kind="sgd", lr=0.002 if model == "ggnn" else 0.03)
+    tr = runner.Trainer(model, dims, fp, mak, ml, me, len(data), tiles=kw.get("tiles"))
+    a = tr.amp
+    a.set_watchdog(5.0)
+    a.set_min_update_frequency(-1, muf)
+    if "lookup_muf" in kw:
+        a.set_min_update_frequency(0, kw["lookup_muf"])
+    a.set_optimizer(-1, 0, lr=opt["lr"])
+    a.set_event_log(16 * (2 * ml + 2) * max(1, dims.get("n_steps", 1)) * (len(data) + len(valid)) + 1024)
+    tr.submit_all(data)
+    tr.submit_all(valid, which=1)
+    ev = a.train_eval(1)
+    logs = a.get_event_log()
+    adm = [(seq, local) for (_, kind, seq, local) in logs[0] if kind == "A"]
+    assert len(adm) == len(data) + len(valid) and [s for s, _ in adm] == list(range(len(adm)))
+    assert sum(1 for _, e in adm if e) == len(valid)
+    check = 0
+    for (_, kind, _, _) in logs[0]:
+        check += 1 if kind == "A" else -1
+        assert 0 <= check <= mak
+    rt = oracle_runtime(model, dims, fp, muf, opt, lookup_muf=kw.get("lookup_muf"))
+    it = ie = 0
+    train_seqs, eval_seqs = [], []
+    for seq, is_eval in adm:
+        if is_eval:
+            rt.mark_eval(seq, valid[ie])
+            eval_seqs.append(seq)
+            ie += 1
+        else:
+            rt.seq_inst[seq] = data[it]
+            train_seqs.append(seq)
+            it += 1
+    # inference instances spread through the run, not bunched at either end
+    assert eval_seqs[0] < len(adm) // 3 and eval_seqs[-1] > 2 * len(adm) // 3
+    rt.replay(data, named_logs(model, dims, logs[1:]))
+    g = dict(params=tr.params(), losses=a.get_instance_losses().astype(np.float64), init=[np.asarray(v, np.float32) for v in fp])
+    compare(g, rt, len(data), opt=opt, ref_losses=[rt.loss[s] for s in train_seqs])
+    ref_eval = float(np.mean([rt.loss[s] for s in eval_seqs]))
+    assert ev["n_instances"] == len(valid)
+    assert abs(ev["mean_loss"] - ref_eval) <= 1e-5 * max(1.0, abs(ref_eval)), (ev["mean_loss"], ref_eval)
+    if model != "ggnn":
+        ref_acc = sum(rt.correct[s] for s in eval_seqs) / sum(rt.npred[s] for s in eval_seqs)
+        assert abs(ev["accuracy"] - ref_acc) < 1e-9
+    # the ordinary calls still work on the same context afterwards
+    a.train(1)
+    assert a.eval()["n_instances"] == len(valid)
 
 
 @pytest.mark.parametrize("cfg,dims,R,mak,muf,lmuf,opt,n", [

@@ -133,15 +133,16 @@ def check_lookup_rows(name, table_gpu, table_ref, table_init, touched, tol=RTOL)
     return float(row_err[worst])
 
 
-def compare(gpu, rt, n_adm, tol=RTOL, opt=None):
-    """opt: the optimizer setting of the run (None = SGD-like), which fixes the element-wise bound."""
+def compare(gpu, rt, n_adm, tol=RTOL, opt=None, ref_losses=None):
+    """opt: the optimizer setting of the run (None = SGD-like), which fixes the element-wise bound.
+    ref_losses: the checker's losses in the order of gpu["losses"], where that is not admissions 0 .. n_adm - 1."""
     etol = elem_tol(opt, tol)
     errs, elem = {}, {}
     for k, node in enumerate(rt.ppt):
         ref = oamp.C.pack_node(node.P)
         errs[node.name] = rel_err(gpu["params"][k], ref)
         elem[node.name] = elementwise_err(gpu["params"][k], ref)
-    ref_loss = np.array([rt.loss[s] for s in range(n_adm)])
+    ref_loss = np.array([rt.loss[s] for s in range(n_adm)]) if ref_losses is None else np.asarray(ref_losses, np.float64)
     le = np.abs(gpu["losses"] - ref_loss) / np.maximum(np.abs(ref_loss), 1.0)
     off = np.flatnonzero(le > tol)
     # everything a failure needs in one message: every tensor's error and where the losses part ways
@@ -152,6 +153,7 @@ def compare(gpu, rt, n_adm, tol=RTOL, opt=None):
     assert le.max() <= tol, report
     if rt.ppt[0].name == "lookup" and "init" in gpu:
         W = rt.ppt[0].P["W"]
+        # rows touched: those of the instances that trained (inference instances read rows but never write them)
         check_lookup_rows("lookup", np.asarray(gpu["params"][0], np.float32).reshape(W.shape), W,
                           np.asarray(gpu["init"][0], np.float32).reshape(W.shape), lookup_tokens(rt.model, rt.instances), etol)
     return max(errs.values()), float(le.max())
