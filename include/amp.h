@@ -313,6 +313,20 @@ int amp_clear_instances(amp_ctx *ctx, int which);
 /* Record up to events_per_worker events per worker during the next
  * amp_train calls (0 = off, the default).  Costs arena space. */
 int amp_set_event_log(amp_ctx *ctx, size_t events_per_worker);
+/* Probe for per-event comparison on runs too long for their end state to be
+ * compared (after 10^4 .. 10^5 asynchronous updates rounding differences have
+ * compounded; what a single forward or backward transform emits has not):
+ * during the next amp_train calls the kernel keeps, for every instance whose
+ * admission number is a multiple of `period`, the output payload of each cell's
+ * forward transform (a tree node's h) and of the leaf cell's backward
+ * transform (the gradient w.r.t. the leaf's embedding), up to max_entries
+ * entries (later ones are dropped); period 0 switches it off.  TREE only.
+ * amp_get_probe copies the entries of the last amp_train: each is
+ * entry_floats floats -- four 32-bit header words {kind (0 = forward output,
+ * 1 = leaf backward output), admission number, tree node, 0} followed by the
+ * payload (hidden or emb floats, zero padded).  host NULL = size query. */
+int amp_set_probe(amp_ctx *ctx, unsigned period, size_t max_entries);
+int amp_get_probe(amp_ctx *ctx, float *host, size_t cap_floats, size_t *n_entries, size_t *entry_floats);
 /* Seconds a worker may wait for a message before the kernel stops itself
  * and amp_train returns AMP_EDEVICE (default 20). */
 int amp_set_watchdog(amp_ctx *ctx, double seconds);

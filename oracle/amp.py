@@ -97,6 +97,8 @@ class PPT(Node):
         assert msg.state not in self.stash, (self.name, msg.state)
         self.stash[msg.state] = (cache, self.n_updates)
         rt.log(self, "F", msg.state)
+        if rt.probe is not None:
+            rt.probe(self.name, "F", msg.state, y)
         rt.emit_fwd(self, 0, Msg(y, msg.state))
 
     def backward(self, rt, port, msg):
@@ -112,6 +114,8 @@ class PPT(Node):
                 self.acc[k] += g[k]
         self.count += 1
         rt.log(self, "B", msg.state)
+        if rt.probe is not None:
+            rt.probe(self.name, "B", msg.state, dx)
         rt.emit_bwd(self, 0, Msg(dx, msg.state))
         if rt.auto_update and self.count >= self.muf:
             self.update(rt)
@@ -448,6 +452,7 @@ class Runtime:
         self.retired = []
         self.loss, self.correct, self.npred, self.yhat = {}, {}, {}, {}
         self.max_staleness, self.limit, self.updates_at = None, 1, {}
+        self.probe = None           # optional callback(node name, "F" | "B", state, output payload) at every PPT event
         self.eval_seqs = set()      # admission numbers of forward-only (inference) instances
         self.seq_inst = {}          # admission number -> instance, where it is not instances[seq % len]
         self.eval_pending = {}      # predictions an inference instance in flight still waits for

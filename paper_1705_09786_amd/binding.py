@@ -95,6 +95,8 @@ SIGNATURES = {
     "amp_clear_instances": (ct.c_int, [_ctxp, ct.c_int]),
     "amp_set_event_log": (ct.c_int, [_ctxp, ct.c_size_t]),
     "amp_set_watchdog": (ct.c_int, [_ctxp, ct.c_double]),
+    "amp_set_probe": (ct.c_int, [_ctxp, ct.c_uint, ct.c_size_t]),
+    "amp_get_probe": (ct.c_int, [_ctxp, _f32p, ct.c_size_t, ct.POINTER(ct.c_size_t), ct.POINTER(ct.c_size_t)]),
     "amp_set_admission": (ct.c_int, [_ctxp, ct.c_int, ct.c_double]),
     "amp_get_admission": (ct.c_int, [_ctxp, ct.POINTER(ct.c_int), ct.POINTER(ct.c_int)]),
     "amp_train": (ct.c_int, [_ctxp, ct.c_int]),
@@ -301,6 +303,18 @@ class Amp:
         a, b = ct.c_int(0), ct.c_int(0)
         self._chk(self.L.amp_get_admission(self.h, ct.byref(a), ct.byref(b)))
         return dict(max_in_flight=a.value, final_limit=b.value)
+
+    def set_probe(self, period, max_entries=0):
+        self._chk(self.L.amp_set_probe(self.h, period, max_entries))
+
+    def get_probe(self):
+        """(header int32 array [n][4] = kind, admission number, tree node, 0; payload float32 array [n][w - 4])."""
+        n, w = ct.c_size_t(), ct.c_size_t()
+        self._chk(self.L.amp_get_probe(self.h, None, 0, ct.byref(n), ct.byref(w)))
+        buf = np.zeros(max(n.value * w.value, 1), np.float32)
+        self._chk(self.L.amp_get_probe(self.h, buf.ctypes.data_as(_f32p), buf.size, ct.byref(n), ct.byref(w)))
+        e = buf[:n.value * w.value].reshape(n.value, max(w.value, 4))
+        return e[:, :4].copy().view(np.int32), e[:, 4:].copy()
 
     def set_watchdog(self, seconds):
         self._chk(self.L.amp_set_watchdog(self.h, seconds))

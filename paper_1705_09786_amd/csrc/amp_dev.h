@@ -158,6 +158,14 @@ struct AmpDev {
   int* correct_out;           // [n_total]
   float* yhat_out;            // [n_total] (GGNN prediction)
   unsigned long long* clock;  // [0] first admission, [1] last retirement (wall_clock64 ticks)
+  // Probe (tree model): output payloads of sampled events, for a per-event comparison on runs too long for their
+  // end state to be compared.  Entry = [kind (0: a cell's forward output h, 1: the leaf cell's backward output
+  // dx), admission number, tree node, 0 | payload], probe_w floats; instances with admission number % probe_period
+  // == 0 are sampled; probe_n counts the entries asked for (those beyond probe_cap are dropped).
+  float* probe;
+  unsigned* probe_n;
+  unsigned probe_cap, probe_period;
+  int probe_w, pad1;
   long long watchdog_ticks;
   void* buf[AMP_MAX_BUFS];    // model-specific per-slot storage
   long long stride[AMP_MAX_BUFS];

@@ -87,6 +87,10 @@ struct amp_ctx {
   int max_mak = 0, mak = 1, max_len = 0, max_edges = 0, mean = 1;
   size_t max_instances = 0, log_cap = 0;
   double watchdog_s = 20.0;
+  unsigned probe_period = 0;     // sample instances whose admission number is a multiple of this (0 = off)
+  size_t probe_cap = 0;          // entries the probe buffer holds
+  std::vector<float> last_probe; // entries of the last training call
+  size_t last_probe_w = 0;
   int admit_bounded = 0;         // staleness-bounded admission
   double max_staleness = 0;
   int last_max_in_flight = 0, last_limit = 0;   // of the last training launch, largest over the replicas
@@ -1008,6 +1012,28 @@ int amp_get_admission(amp_ctx* c, int* max_in_flight, int* final_limit) {
   return AMP_OK;
 }
 
+int amp_set_probe(amp_ctx* c, unsigned period, size_t max_entries) {
+  if (!c) return AMP_EINVAL;
+  if (period && c->model && c->model != AMP_MODEL_TREE) return fail(c, AMP_EUNSUPPORTED, "set_probe: the tree model only");
+  if (period && c->replicas > 1) return fail(c, AMP_EUNSUPPORTED, "set_probe: not with replicas");
+  if (period && max_entries < 1) return fail(c, AMP_EINVAL, "set_probe: max_entries must be >= 1");
+  if (max_entries > (1u << 28)) return fail(c, AMP_EINVAL, "set_probe: max_entries too large");
+  c->probe_period = period;
+  c->probe_cap = max_entries;
+  return AMP_OK;
+}
+
+int amp_get_probe(amp_ctx* c, float* host, size_t cap_floats, size_t* n_entries, size_t* entry_floats) {
+  if (!c) return AMP_EINVAL;
+  const size_t w = c->last_probe_w, n = w ? c->last_probe.size() / w : 0;
+  if (n_entries) *n_entries = n;
+  if (entry_floats) *entry_floats = w;
+  if (!host) return AMP_OK;   // size query
+  if (cap_floats < c->last_probe.size()) return fail(c, AMP_ENOMEM, "get_probe: %zu floats needed", c->last_probe.size());
+  std::memcpy(host, c->last_probe.data(), c->last_probe.size() * 4);
+  return AMP_OK;
+}
+
 int amp_set_watchdog(amp_ctx* c, double seconds) {
   if (!c) return AMP_EINVAL;
   if (!(seconds > 0) || seconds > 600) return fail(c, AMP_EINVAL, "watchdog must be in (0, 600] seconds");
@@ -1156,9 +1182,14 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
     off_yhat[r] = take(n_total[r] * 4);
     for (size_t w = 0; w < wpr; ++w) off_logn[r][w] = take(64);
   }
+  const size_t off_probe_n = take(64);
   const size_t zero_end = off;
   for (int r = 0; r < R; ++r)
     for (size_t w = 0; w < wpr; ++w) off_log[r][w] = take(8 * std::max<size_t>(log_cap, 1));
+  // the probe buffer (first replica only): entries of 4 header words and the wider of the two payloads
+  const bool probing = train && c->probe_period && c->model == AMP_MODEL_TREE;
+  const size_t probe_w = 4 + (size_t)std::max(amp_round4(c->dims.hidden), amp_round4(c->dims.emb));
+  const size_t off_probe = take(probing ? c->probe_cap * probe_w * 4 : 4);
   for (int r = 0; r < R; ++r) off_adm[r] = take(4 * std::max<size_t>(n_total[r], 1));
   if (off > c->arena_bytes) return fail(c, AMP_ENOMEM, "%s of %zu bytes is too small, %zu needed", arena_name(c), c->arena_bytes, off);
   HIPCHK(c, hipMemsetAsync(c->arena + res_begin, 0, zero_end - res_begin, c->stream));
@@ -1273,6 +1304,11 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
     D.yhat_out = (float*)(c->arena + off_yhat[r]);
     D.clock = (unsigned long long*)rep_ptr(c, r, c->off_clock);
     D.watchdog_ticks = (long long)(c->watchdog_s * 1.0e8);   // wall_clock64 counts at 100 MHz
+    D.probe = (float*)(c->arena + off_probe);
+    D.probe_n = (unsigned*)(c->arena + off_probe_n);
+    D.probe_period = probing && r == 0 ? c->probe_period : 0;
+    D.probe_cap = (unsigned)c->probe_cap;
+    D.probe_w = (int)probe_w;
     for (int i = 0; i < AMP_MAX_BUFS; ++i) {
       D.buf[i] = c->buf_bytes[i] ? rep_ptr(c, r, c->off_buf[i]) : nullptr;
       D.stride[i] = c->buf_stride[i];
@@ -1311,6 +1347,14 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
       for (HostNode& n : c->nodes) n.dirty = true;
       return fail(c, AMP_EDEVICE, "kernel stopped itself: %s (replica %d, worker %u)", why, r, ctl[8 * r + 2]);
     }
+  }
+  if (probing) {
+    unsigned asked = 0;
+    HIPCHK(c, hipMemcpy(&asked, c->arena + off_probe_n, 4, hipMemcpyDeviceToHost));
+    const size_t got = std::min<size_t>(asked, c->probe_cap), base = c->last_probe.size();
+    c->last_probe_w = probe_w;
+    c->last_probe.resize(base + got * probe_w);
+    if (got) HIPCHK(c, hipMemcpy(c->last_probe.data() + base, c->arena + off_probe, got * probe_w * 4, hipMemcpyDeviceToHost));
   }
   std::vector<char> back(res_end - res_begin);
   HIPCHK(c, hipMemcpy(back.data(), c->arena + res_begin, back.size(), hipMemcpyDeviceToHost));
@@ -1417,6 +1461,7 @@ int run_prepared(amp_ctx* c, int which, int epochs, bool train, amp_eval_result*
   std::vector<std::vector<int>> correct(R);
   double seconds = 0;
   c->launch_events.assign(wpr * R, std::vector<amp_event>());
+  if (train) c->last_probe.clear();
   // with replicas the parameters are averaged at the end of every epoch (Section 5), hence one launch per epoch
   const int launches = R > 1 ? epochs : 1, per_launch = R > 1 ? 1 : epochs;
   for (int l = 0; l < launches; ++l) {
@@ -1499,6 +1544,7 @@ int run_mixed(amp_ctx* c, int epochs, amp_eval_result* ev) {
   std::vector<std::vector<int>> correct(1);
   double seconds = 0;
   c->launch_events.assign(c->workers.size(), std::vector<amp_event>());
+  c->last_probe.clear();
   if (int rc = launch_once(c, res, res.end, 1, true, losses, correct, seconds, &adm)) return rc;
   HIPCHK(c, hipStreamSynchronize(c->stream));
   // split the results by kind, each in its own admission order

@@ -178,6 +178,10 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
   GQ float* prow = (GQ float*)D->buf[11];
   GQ float* lkP = (GQ float*)lk.P;
   const GQ int* tokens = (const GQ int*)D->data.tok;
+  GQ float* probe = uni_gq<float>(D->probe);
+  GQ unsigned* probe_n = uni_gq<unsigned>(D->probe_n);
+  const unsigned probe_period = uni(D->probe_period), probe_cap = uni(D->probe_cap);
+  const int probe_w = uni(D->probe_w);
   for (unsigned k = threadIdx.x; k < count; k += AMP_THREADS) pend_tok[k] = keep[k];
   __syncthreads();
   // Wave 1 takes and decodes the next batch while wave 0 is still publishing the present one (wave 0 keeps what its
@@ -197,6 +201,20 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
         M.a[k] = tokens[sm.w + l];
         M.aux[k] = code_is_b(code);
         if (!code_is_b(code) && l == 0) left_cnt[s] = sm.y;
+        // probe: the gradient w.r.t. this leaf's embedding (the leaf cell's backward output) of a sampled instance
+        int entry = -1;
+        if (probe_period && code_is_b(code) && (unsigned)sm.x % probe_period == 0u) {
+          const unsigned e = __hip_atomic_fetch_add(probe_n, 1u, __ATOMIC_RELAXED, AGENT);
+          if (e < probe_cap) {
+            entry = (int)e;
+            GQ int* hdr = (GQ int*)(probe + (long long)e * probe_w);
+            hdr[0] = 1;
+            hdr[1] = sm.x;
+            hdr[2] = l;
+            hdr[3] = 0;
+          }
+        }
+        M.par[k] = entry;
       }
       batch_split_and_log(D, wr, M, n, 0, false);
       // backward message k is the b-th gradient of the batch: remember its token
@@ -234,6 +252,7 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
               if (t0 + u < B.TL) a += p[u];
           }
           *(GQ v4f*)(prow + (long long)(count + M.b[k]) * E + c) = a;
+          if (M.par[k] >= 0) *(GQ v4f*)(probe + (long long)M.par[k] * probe_w + 4 + c) = a;
         }
       }
     } else {
@@ -246,6 +265,7 @@ __device__ __noinline__ void role_tree_lookup(const GQ AmpDev* D, const GQ Worke
           float a = 0.f;
           for (int t = 0; t < B.TL; ++t) a += gx[t * Ep];
           prow[(long long)(count + M.b[k]) * E + c] = a;
+          if (M.par[k] >= 0) probe[(long long)M.par[k] * probe_w + 4 + c] = a;
         }
       }
     }
@@ -1315,6 +1335,10 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
   const GQ int* smeta = uni_gq<int>(D->smeta);
   const GQ int* tnode = uni_gq<int>(D->data.tnode);
   const GQ int* slot_inst = uni_gq<int>(D->slot_inst);
+  GQ float* probe = uni_gq<float>(D->probe);
+  GQ unsigned* probe_n = uni_gq<unsigned>(D->probe_n);
+  const unsigned probe_period = uni(D->probe_period), probe_cap = uni(D->probe_cap);
+  const int probe_w = uni(D->probe_w);
   Lds L{lds};
   float* Wg = L.take(t.Rp * t.ldw);
   float* bg = L.take(t.Rp);
@@ -1364,6 +1388,20 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
         M.aux[k] = (!wr.train || slot_inst[s] < 0) ? 1 : 0;
         M.off0[k] = (int)(B.node(s, nn) * 2 * Hp);
         M.dst0[k] = (int)(B.node(s, nn) * H);
+        // probe: this node's h (its cell's forward output) if the instance is sampled
+        int entry = -1;
+        if (probe_period && (unsigned)sm.x % probe_period == 0u) {
+          const unsigned e = __hip_atomic_fetch_add(probe_n, 1u, __ATOMIC_RELAXED, AGENT);
+          if (e < probe_cap) {
+            entry = (int)e;
+            GQ int* hdr = (GQ int*)(probe + (long long)e * probe_w);
+            hdr[0] = 0;
+            hdr[1] = sm.x;
+            hdr[2] = nn;
+            hdr[3] = 0;
+          }
+        }
+        M.b[k] = entry;
       }
       // the event record: a training node's message is a forward event followed by a backward event (the loss turns
       // it round in place), an evaluation node's a forward event only
@@ -1390,7 +1428,9 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
     lds_barrier();
     for (int idx = threadIdx.x; idx < n * (Hp >> 2); idx += AMP_THREADS) {
       const int k = idx / (Hp >> 2), c = (idx - k * (Hp >> 2)) << 2;
-      *(LDSQ v4f*)(hbuf + k * Hp + c) = *(const GQ v4f*)(B.hc + M.off0[k] + c);
+      const v4f hv = *(const GQ v4f*)(B.hc + M.off0[k] + c);
+      *(LDSQ v4f*)(hbuf + k * Hp + c) = hv;
+      if (probe_period && M.b[k] >= 0) *(GQ v4f*)(probe + (long long)M.b[k] * probe_w + 4 + c) = hv;
     }
     lds_barrier();
     // logits z[k][r]
