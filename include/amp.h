@@ -390,6 +390,13 @@ int amp_num_workers(amp_ctx *ctx);
  * bottleneck.  Any out pointer may be NULL. */
 int amp_get_worker_stats(amp_ctx *ctx, double *wait_fraction, uint64_t *messages, int32_t *node_of_worker,
                          size_t cap, size_t *n, uint64_t *batches, double *phase_fraction);
+/* The accelerator die (XCC, 0..7) each worker's workgroup ran on during the
+ * last amp_train / amp_eval, in the order of amp_get_worker_stats.  The
+ * launch places the workers of one replica on one die whenever whole replicas
+ * fit its 32 compute units (Appendix A's affinitization of nodes to workers,
+ * applied to the chip's eight L2 domains); this reports where they really
+ * ran, as read from the hardware by each workgroup. */
+int amp_get_worker_placement(amp_ctx *ctx, int32_t *xcc, size_t cap, size_t *n);
 const char *amp_last_error(amp_ctx *ctx);
 
 /* Measures the two rates the workers' rooflines are quoted against (Section

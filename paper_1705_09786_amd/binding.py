@@ -110,6 +110,7 @@ SIGNATURES = {
     "amp_get_worker_stats": (ct.c_int, [_ctxp, ct.POINTER(ct.c_double), ct.POINTER(ct.c_uint64), _i32p,
                                         ct.c_size_t, ct.POINTER(ct.c_size_t), ct.POINTER(ct.c_uint64),
                                         ct.POINTER(ct.c_double)]),
+    "amp_get_worker_placement": (ct.c_int, [_ctxp, _i32p, ct.c_size_t, ct.POINTER(ct.c_size_t)]),
     "amp_last_error": (ct.c_char_p, [_ctxp]),
     "amp_measure_peaks": (ct.c_int, [ct.c_void_p, ct.c_size_t, ct.c_void_p, ct.POINTER(ct.c_double),
                                      ct.POINTER(ct.c_double)]),
@@ -378,6 +379,14 @@ class Amp:
         self._chk(self.L.amp_get_worker_stats(self.h, wf, ms, nd, nw, ct.byref(n), bt, ph))
         return [dict(node=nd[i], wait_fraction=wf[i], messages=ms[i], batches=bt[i],
                      phases=[ph[8 * i + j] for j in range(8)]) for i in range(min(nw, n.value))]
+
+    def get_worker_placement(self):
+        """The XCC (die) every worker's workgroup ran on, in worker order."""
+        nw = self.num_workers()
+        x = (ct.c_int32 * nw)()
+        n = ct.c_size_t()
+        self._chk(self.L.amp_get_worker_placement(self.h, x, nw, ct.byref(n)))
+        return list(x[:n.value])
 
     def get_staleness_hist(self, nbins=16):
         bins = (ct.c_uint64 * nbins)()

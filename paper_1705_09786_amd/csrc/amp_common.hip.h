@@ -83,8 +83,9 @@ __device__ __forceinline__ void raise_abort(const GQ AmpDev* D, unsigned code, u
 }
 
 // Per-workgroup utilisation counters: [0] ticks spent waiting for messages, [1] messages taken,
-// [2] batches taken, [3] last phase boundary, [4..11] ticks per phase (role-specific).
-#define AMP_NSTAT 12
+// [2] batches taken, [3] last phase boundary, [4..11] ticks per phase (role-specific), [12] the XCC (accelerator
+// die) the workgroup ran on.
+#define AMP_NSTAT 13
 __shared__ unsigned long long s_stat[AMP_NSTAT];
 // Thread 0 charges the time since the previous boundary to phase i.  Compiled in only with -DAMP_PHASE_STATS:
 // eight clock reads per batch cost about 3 % of a tile worker's time.

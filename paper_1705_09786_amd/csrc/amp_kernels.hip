@@ -416,6 +416,8 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
     if (W->log_cap) *W->log_n = s_logn;
     for (int i = 0; i < AMP_NSTAT; ++i) W->stats[i] = s_stat[i];
     W->stats[3] = (unsigned long long)(wall_clock64() - t_begin);
+    // which of the eight dies this workgroup ran on: hardware register XCC_ID (id 20), bits 3:0
+    W->stats[12] = (unsigned long long)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xf);
   }
 }
 

@@ -27,7 +27,7 @@ extern "C" hipError_t amp_static_arena(void** ptr, size_t* bytes);
 
 namespace {
 
-constexpr size_t NSTAT = 12;
+constexpr size_t NSTAT = 13;   // words per worker in the statistics block (AMP_NSTAT of the kernels)
 
 struct HostNode {
   std::string name;
@@ -812,6 +812,16 @@ int amp_get_worker_stats(amp_ctx* c, double* wait_fraction, uint64_t* messages, 
       for (int i = 0; i < 8; ++i) phase_fraction[8 * w + i] = s[3] ? (double)s[4 + i] / (double)s[3] : 0.0;
     if (node_of_worker) node_of_worker[w] = c->workers[w % wpr].node;
   }
+  return AMP_OK;
+}
+
+int amp_get_worker_placement(amp_ctx* c, int32_t* xcc, size_t cap, size_t* n) {
+  if (!c) return AMP_EINVAL;
+  const size_t nw = c->last_stats.size() / NSTAT;
+  if (n) *n = nw;
+  if (c->last_stats.empty()) return fail(c, AMP_ESTATE, "get_worker_placement: nothing run yet");
+  if (!xcc || cap < nw) return fail(c, AMP_ENOMEM, "get_worker_placement: %zu entries needed", nw);
+  for (size_t w = 0; w < nw; ++w) xcc[w] = (int32_t)c->last_stats[NSTAT * w + 12];
   return AMP_OK;
 }
 

@@ -83,3 +83,29 @@ def test_worker_statistics():
         if w["node"] >= 0:
             assert w["messages"] == expect[w["node"]], w
             assert 1 <= w["batches"] <= w["messages"], w
+
+
+def test_workers_run_on_the_dies_the_launch_assumes():
+    """The launch maps workgroups to the eight dies (XCDs) by their index -- block b is expected on die b % 8 -- and
+    packs each replica's workers onto one die when whole replicas fit its 32 compute units.  Every workgroup reads
+    the die it really ran on from the hardware; this checks the assumption instead of trusting it."""
+    # three replicas of a 9-worker tree pipeline (packed: replica r on die r), and a single MLP (4 workers, packed)
+    dims = dict(vocab=97, emb=50, hidden=37, n_class=5)
+    data = synth.make_tree(45, 27, dims, max_leaves=16)
+    fp = synth.init_params("tree", dims, 12)
+    g = gpu_train("tree", dims, fp, data, 6, 3, SGD, lookup_muf=5, replicas=3, tiles={1: 2, 2: 4}, log=False)
+    a = g["trainer"].amp
+    xcc = a.get_worker_placement()
+    wpr = a.num_workers() // 3
+    assert wpr == 9 and len(xcc) == 27
+    for r in range(3):
+        assert set(xcc[r * wpr:(r + 1) * wpr]) == {r}, xcc
+    model, mdims, mdata = synth.workload(1, n=64)
+    g = gpu_train(model, mdims, synth.init_params(model, mdims, 5), mdata, 4, 1, SGD, log=False)
+    assert set(g["trainer"].amp.get_worker_placement()) == {0}
+    # a single pipeline of many workers is spread over the dies: worker w = block w on die w % 8
+    dims2 = dict(vocab=200, emb=300, hidden=150, n_class=5)
+    data2 = synth.make_tree(32, 99, dims2, max_leaves=24)
+    g = gpu_train("tree", dims2, synth.init_params("tree", dims2, 3), data2, 16, 10, SGD, lookup_muf=100, log=False)
+    xcc = g["trainer"].amp.get_worker_placement()
+    assert xcc == [w % 8 for w in range(len(xcc))], xcc
