@@ -44,6 +44,10 @@ struct GView {
   int inst, N, E;
   const GQ int *type, *src, *dst, *tcount, *inoff, *inedge, *tstart, *tedge, *tsoff, *tsk;
   float target;
+  // filled by g_view_rec only: the admission number, the edge types present, and (edge workers) the number of edges
+  // of the worker's type and where they start in tedge / tsk
+  unsigned seq, present;
+  int kc, tsc;
 };
 
 // The instance set's arrays, read once per worker into scalar registers.
@@ -205,6 +209,68 @@ __device__ __forceinline__ GRings g_rings(const GQ AmpDev* D) {
   return r;
 }
 
+// The instance facts of a message, decoded once by the thread that took the message from the ring and handed to the
+// workgroup through LDS: the decode is a chain of two dependent fetches (slot -> instance -> offsets and counts),
+// which this way runs beside the publication of the previous message instead of in front of every thread's work.
+// Two records, alternating with the ring ticket: the next message's is written while the present one's is in use.
+__shared__ unsigned s_grec[2][12];
+
+// ONE thread.  ctype = the edge type whose count and start the record should carry (0 for the GRU workers).
+__device__ __forceinline__ void g_decode(const GData& d, unsigned code, int ctype, int b) {
+  const int s = MSG_SLOT(code);
+  const unsigned seq = d.slot_seq[s];
+  const int inst = d.slot_inst[s] & 0x7fffffff;
+  const int to = d.tok_off[inst], to1 = d.tok_off[inst + 1], eo = d.edge_off[inst], eo1 = d.edge_off[inst + 1];
+  const float tg = d.target[inst];
+  const v4i c0 = *(const GQ v4i*)(d.tcount + inst * 8), c1 = *(const GQ v4i*)(d.tcount + inst * 8 + 4);
+  const int tsc = d.tstart[inst * 9 + ctype];
+  const int cnt[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+  unsigned present = 0;
+  int kc = 0;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) {
+    present |= (c < d.T && cnt[c] > 0) ? 1u << c : 0u;
+    kc = c == ctype ? cnt[c] : kc;
+  }
+  unsigned* r = s_grec[b];
+  r[0] = seq;
+  r[1] = (unsigned)inst;
+  r[2] = (unsigned)to;
+  r[3] = (unsigned)(to1 - to);
+  r[4] = (unsigned)eo;
+  r[5] = (unsigned)(eo1 - eo);
+  r[6] = __float_as_uint(tg);
+  r[7] = present;
+  r[8] = (unsigned)kc;
+  r[9] = (unsigned)tsc;
+}
+
+// All threads, after the barrier that follows g_decode.
+__device__ __forceinline__ GView g_view_rec(const GData& d, int b) {
+  const unsigned* r = s_grec[b];
+  GView v;
+  v.seq = uni(r[0]);
+  v.inst = (int)uni(r[1]);
+  const int to = (int)uni(r[2]), eo = (int)uni(r[4]);
+  v.N = (int)uni(r[3]);
+  v.E = (int)uni(r[5]);
+  v.target = __uint_as_float(uni(r[6]));
+  v.present = uni(r[7]);
+  v.kc = (int)uni(r[8]);
+  v.tsc = (int)uni(r[9]);
+  v.type = d.tok + to;
+  v.src = d.src + eo;
+  v.dst = d.dst + eo;
+  v.tcount = d.tcount + v.inst * 8;
+  v.inoff = d.inoff + to + v.inst;
+  v.inedge = d.inedge + eo;
+  v.tstart = d.tstart + v.inst * 9;
+  v.tedge = d.tedge + eo;
+  v.tsoff = d.tsoff + (long long)d.T * (to + v.inst);
+  v.tsk = d.tsk + eo;
+  return v;
+}
+
 // Bit c set when the graph has edges of type c (at most 8 types).
 __device__ __forceinline__ unsigned g_present_types(const GView& v, int T) {
   unsigned m = 0;
@@ -279,19 +345,36 @@ __device__ __forceinline__ v4f g_state_gradient4(const GBufs& B, const GParts& e
   const GQ float* he = B.dHe + (long long)s * B.PE * NH + i;
   const GQ float* hp = B.dHp + ((long long)s * 2 + (step & 1)) * B.PA * NH + i;
   const v4f zero = {0.f, 0.f, 0.f, 0.f};
-  v4f e[12], p[12];
-#pragma unroll
-  for (int k = 0; k < 12; ++k) e[k] = *(const GQ v4f*)(he + (k < ep.n ? ep.off[k] : ep.off[0]) * NH);
-#pragma unroll
-  for (int k = 0; k < 12; ++k) p[k] = *(const GQ v4f*)(hp + (k < B.PA ? k : 0) * NH);
   v4f a = zero, g = zero, cnd = zero;
+  if (B.PE <= 8 && B.PA <= 4) {
+    // few parts (no node split, or only lightly): eight and four fetches in flight instead of twelve and twelve
+    v4f e[8], p[4];
 #pragma unroll
-  for (int k = 0; k < 12; ++k)
-    if (k < ep.n) a += e[k];
+    for (int k = 0; k < 8; ++k) e[k] = *(const GQ v4f*)(he + (k < ep.n ? ep.off[k] : ep.off[0]) * NH);
 #pragma unroll
-  for (int k = 0; k < 12; ++k) {
-    if (k >= B.Th && k < B.PA) g += p[k];
-    if (k < B.Th) cnd += p[k];
+    for (int k = 0; k < 4; ++k) p[k] = *(const GQ v4f*)(hp + (k < B.PA ? k : 0) * NH);
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (k < ep.n) a += e[k];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (k >= B.Th && k < B.PA) g += p[k];
+      if (k < B.Th) cnd += p[k];
+    }
+  } else {
+    v4f e[12], p[12];
+#pragma unroll
+    for (int k = 0; k < 12; ++k) e[k] = *(const GQ v4f*)(he + (k < ep.n ? ep.off[k] : ep.off[0]) * NH);
+#pragma unroll
+    for (int k = 0; k < 12; ++k) p[k] = *(const GQ v4f*)(hp + (k < B.PA ? k : 0) * NH);
+#pragma unroll
+    for (int k = 0; k < 12; ++k)
+      if (k < ep.n) a += e[k];
+#pragma unroll
+    for (int k = 0; k < 12; ++k) {
+      if (k >= B.Th && k < B.PA) g += p[k];
+      if (k < B.Th) cnd += p[k];
+    }
   }
   a += g;
   a += cnd;
@@ -303,14 +386,25 @@ __device__ __forceinline__ v4f g_state_gradient4(const GBufs& B, const GParts& e
 __device__ __forceinline__ v4f g_sum_dA4(const GBufs& B, const GQ float* dA, long long o) {
   const long long NH = (long long)B.N * B.H;
   const v4f zero = {0.f, 0.f, 0.f, 0.f};
-  v4f p[12];
-#pragma unroll
-  for (int k = 0; k < 12; ++k) p[k] = *(const GQ v4f*)(dA + (k < B.PA ? k : 0) * NH + o);
   v4f g = zero, cnd = zero;
+  if (B.PA <= 4) {
+    v4f p[4];
 #pragma unroll
-  for (int k = 0; k < 12; ++k) {
-    if (k >= B.Th && k < B.PA) g += p[k];
-    if (k < B.Th) cnd += p[k];
+    for (int k = 0; k < 4; ++k) p[k] = *(const GQ v4f*)(dA + (k < B.PA ? k : 0) * NH + o);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (k >= B.Th && k < B.PA) g += p[k];
+      if (k < B.Th) cnd += p[k];
+    }
+  } else {
+    v4f p[12];
+#pragma unroll
+    for (int k = 0; k < 12; ++k) p[k] = *(const GQ v4f*)(dA + (k < B.PA ? k : 0) * NH + o);
+#pragma unroll
+    for (int k = 0; k < 12; ++k) {
+      if (k >= B.Th && k < B.PA) g += p[k];
+      if (k < B.Th) cnd += p[k];
+    }
   }
   return g + cnd;
 }
@@ -477,19 +571,22 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
   unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
   // Thread 64 (wave 1) waits for the next message while wave 0 publishes the present one.
-  if (threadIdx.x == 64) poll_msg(D, mine, head, s_ctl);
+  if (threadIdx.x == 64) {
+    poll_msg(D, mine, head, s_ctl);
+    if (s_ctl[1] == 0u) g_decode(gd, s_ctl[0], ctype, head & 1);
+  }
   lds_barrier();
   for (;;) {
     const unsigned code = uni(s_ctl[0]);
     if (uni(s_ctl[1]) != 0u) break;
+    const GView v = g_view_rec(gd, head & 1);
     head++;
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
-    const unsigned seq = uni(gd.slot_seq[s]);
-    const GView v = g_view(gd, s);
-    const int K = uni(v.tcount[ctype]), NB = (K + 15) >> 4;
-    const GQ int* te = v.tedge + uni(v.tstart[ctype]);   // edges of this type, ascending (Group orders its rows by edge index)
+    const unsigned seq = v.seq;
+    const int K = v.kc, NB = (K + 15) >> 4;
+    const GQ int* te = v.tedge + v.tsc;   // edges of this type, ascending (Group orders its rows by edge index)
     const GQ float* h = B.Hm + B.hm(s, it);
-    const int nact = g_present_tiles(B, g_present_types(v, B.T));   // tiles of every edge type the graph uses
+    const int nact = g_present_tiles(B, v.present);   // tiles of every edge type the graph uses
     if (vec) {
       const int GY = Hs >> 2;   // padding columns of a used row are written as zeros every time
       for (int idx = threadIdx.x; idx < K * GY; idx += AMP_THREADS) {
@@ -557,7 +654,7 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
     {
       GQ float* dHe = B.dHe + ((long long)s * B.PE + B.eoff(ctype) + tile) * B.N * H;   // this tile's part
       const GQ int* so = v.tsoff + ctype * (v.N + 1);
-      const GQ int* sk = v.tsk + uni(v.tstart[ctype]);
+      const GQ int* sk = v.tsk + v.tsc;
       if (vec) {
         for (int idx = threadIdx.x; idx < v.N * G1; idx += AMP_THREADS) {
           const int n = idx / G1, c = (idx - n * G1) << 2;
@@ -593,7 +690,10 @@ __device__ __noinline__ void role_g_edge(const GQ AmpDev* D, const GQ WorkerDev*
     }
     g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
     }
-    if (threadIdx.x == 64) poll_msg(D, mine, head, s_ctl);
+    if (threadIdx.x == 64) {
+      poll_msg(D, mine, head, s_ctl);
+      if (s_ctl[1] == 0u) g_decode(gd, s_ctl[0], ctype, head & 1);
+    }
     lds_barrier();
   }
   tile_store(nd, t, g.Wg, g.bg);
@@ -635,15 +735,18 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
   unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
   // Thread 64 (wave 1) waits for the next message while wave 0 publishes the present one.
-  if (threadIdx.x == 64) poll_msg(D, mine, head, s_ctl);
+  if (threadIdx.x == 64) {
+    poll_msg(D, mine, head, s_ctl);
+    if (s_ctl[1] == 0u) g_decode(gd, s_ctl[0], 0, head & 1);
+  }
   lds_barrier();
   for (;;) {
     const unsigned code = uni(s_ctl[0]);
     if (uni(s_ctl[1]) != 0u) break;
+    const GView v = g_view_rec(gd, head & 1);
     head++;
     const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
-    const unsigned seq = uni(gd.slot_seq[s]);
-    const GView v = g_view(gd, s);
+    const unsigned seq = v.seq;
     const int K = v.N, NB = (K + 15) >> 4;
     GQ float* A = B.A + B.st(s, it);
     const GQ float* h = B.Hm + B.hm(s, it);
@@ -774,12 +877,15 @@ __device__ __noinline__ void role_g_gate(const GQ AmpDev* D, const GQ WorkerDev*
       // both gates done: back through sum / Group to the edge types
       int go = 0;
       if (threadIdx.x == 0) go = join_arrive(B.cnt + s * 8 + 2, B.Tz + B.Tr);
-      if (__shfl(go, 0)) g_post_edges(rg, g_present_types(v, B.T), s, it, true);
+      if (__shfl(go, 0)) g_post_edges(rg, v.present, s, it, true);
     }
     g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
     PHASE(7);
     }
-    if (threadIdx.x == 64) poll_msg(D, mine, head, s_ctl);
+    if (threadIdx.x == 64) {
+      poll_msg(D, mine, head, s_ctl);
+      if (s_ctl[1] == 0u) g_decode(gd, s_ctl[0], 0, head & 1);
+    }
     lds_barrier();
   }
   tile_store(nd, t, g.Wg, g.bg);
@@ -820,39 +926,95 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
   const Ring mine = ring_regs(D, uni(W->ring));
   unsigned head = 0;
   unsigned count = W->wstate[0], tstep = W->wstate[1], nrows = W->wstate[4];
-  // Thread 64 (wave 1) waits for the next message while wave 0 publishes the present one.
-  if (threadIdx.x == 64) poll_msg(D, mine, head, s_ctl);
-  lds_barrier();
-  for (;;) {
-    const unsigned code = uni(s_ctl[0]);
-    if (uni(s_ctl[1]) != 0u) break;
-    head++;
-    const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
-    const unsigned seq = uni(gd.slot_seq[s]);
-    const GView v = g_view(gd, s);
-    const unsigned present = g_present_types(v, B.T);
-    const int K = v.N, NB = (K + 15) >> 4;
+  // What a message needs in LDS before its product: X = [A; r * h] and, on the way back, the delta rows (with the
+  // gradient w.r.t. the step's output states, kept in gt, and the update gate's pre-activation gradient, written
+  // to dZ).  `nthr` threads, `tid` = this thread's number among them: the whole workgroup stages the message it is
+  // about to process; waves 1..7 alone stage the next one, if it is already waiting, while wave 0 publishes the
+  // present one (fence, join, posts) -- the two do not touch the same memory.
+  auto stage = [&](unsigned mcode, int rec, int tid, int nthr) {
+    const int s = MSG_SLOT(mcode), it = MSG_LOCAL(mcode);
+    const GView v = g_view_rec(gd, rec);
+    const int K = v.N;
     const GQ float* A = B.A + B.st(s, it);
     const GQ float* h = B.Hm + B.hm(s, it);
     const GQ float* Z = B.Z + B.st(s, it);
     const GQ float* Rr = B.Rr + B.st(s, it);
-    GQ float* Ht = B.Ht + B.st(s, it);
-    PHASE(0);
+    const GQ float* Ht = B.Ht + B.st(s, it);
     if (vec) {
-      for (int idx = threadIdx.x; idx < K * G1; idx += AMP_THREADS) {
+      for (int idx = tid; idx < K * G1; idx += nthr) {
         const int k = idx / G1, c = (idx - k * G1) << 2, o = k * H + c;
         const v4f a = *(const GQ v4f*)(A + o), r = *(const GQ v4f*)(Rr + o), hv = *(const GQ v4f*)(h + o);
         *(LDSQ v4f*)(X + k * Cs + c) = a;
         *(LDSQ v4f*)(X + k * Cs + H + c) = r * hv;
       }
       const int GP = (Cs - C) >> 2;   // padding columns of the used rows of X
-      for (int idx = threadIdx.x; idx < K * GP; idx += AMP_THREADS)
+      for (int idx = tid; idx < K * GP; idx += nthr)
         *(LDSQ v4f*)(X + (idx / GP) * Cs + C + ((idx % GP) << 2)) = (v4f){0.f, 0.f, 0.f, 0.f};
     } else
-    for (int i = threadIdx.x; i < K * Cs; i += AMP_THREADS) {
+    for (int i = tid; i < K * Cs; i += nthr) {
       const int k = i / Cs, c = i - k * Cs;
       X[i] = c < H ? A[k * H + c] : c < C ? Rr[k * H + c - H] * h[k * H + c - H] : 0.f;
     }
+    if (!(mcode & MSG_DIR_B)) return;
+    // backward through blend and tanh: the gradient w.r.t. the states leaving the step, for this tile's units;
+    // delta rows in tile order
+    const unsigned present = v.present;
+    const GQ float* gH = B.gH + B.sl(s);
+    GQ float* dZ = B.dZ + B.sl(s);
+    const bool from_readout = it + 1 == B.S;
+    const GParts ep = g_edge_parts(B, present);
+    if (vec) {
+      // the tile's units first (one group per thread and round trip), then zeros for the rest of each row
+      const int GY = Hs >> 2, GZ = GY - GU;
+      for (int idx = tid; idx < K * GU; idx += nthr) {
+        const int k = idx / GU, c = (idx - k * GU) << 2;
+        const int o = k * H + u0 + c;
+        const v4f z = *(const GQ v4f*)(Z + o), ht = *(const GQ v4f*)(Ht + o), hv = *(const GQ v4f*)(h + o);
+        const v4f gg = from_readout ? *(const GQ v4f*)(gH + o) : g_state_gradient4(B, ep, s, o, it + 1);
+        *(LDSQ v4f*)(gt + o) = gg;
+        *(GQ v4f*)(dZ + o) = gg * (ht - hv) * z * (1.f - z);
+        *(LDSQ v4f*)(Y + k * Hs + c) = gg * z * (1.f - ht * ht);
+      }
+      for (int idx = tid; idx < K * GZ; idx += nthr)
+        *(LDSQ v4f*)(Y + (idx / GZ) * Hs + nu + ((idx % GZ) << 2)) = (v4f){0.f, 0.f, 0.f, 0.f};
+    } else {
+      for (int i = tid; i < K * nu; i += nthr) {
+        const int k = i / nu, j = i - k * nu, o = k * H + u0 + j;
+        const float gg = from_readout ? gH[o] : g_state_gradient(B, ep, s, o, it + 1);
+        const float z = Z[o], ht = Ht[o];
+        gt[o] = gg;
+        dZ[o] = gg * (ht - h[o]) * z * (1.f - z);
+        Y[k * Hs + j] = gg * z * (1.f - ht * ht);
+      }
+      for (int i = tid; i < K * (Hs - nu); i += nthr) Y[(i / (Hs - nu)) * Hs + nu + i % (Hs - nu)] = 0.f;
+    }
+  };
+  // Thread 64 (wave 1) looks for the next message while the present one's stores drain; if it is there, waves 1..7
+  // stage it while wave 0 publishes the present one, otherwise thread 64 waits for it afterwards.
+  bool staged = false;
+  if (threadIdx.x == 64) {
+    poll_msg(D, mine, head, s_ctl);
+    if (s_ctl[1] == 0u) g_decode(gd, s_ctl[0], 0, head & 1);
+  }
+  lds_barrier();
+  for (;;) {
+    const unsigned code = uni(s_ctl[0]);
+    if (uni(s_ctl[1]) != 0u) break;
+    const int rec = head & 1;
+    const GView v = g_view_rec(gd, rec);
+    head++;
+    const int s = MSG_SLOT(code), it = MSG_LOCAL(code);
+    const unsigned seq = v.seq;
+    const unsigned present = v.present;
+    const int K = v.N, NB = (K + 15) >> 4;
+    const GQ float* h = B.Hm + B.hm(s, it);
+    const GQ float* Z = B.Z + B.st(s, it);
+    const GQ float* Rr = B.Rr + B.st(s, it);
+    GQ float* Ht = B.Ht + B.st(s, it);
+    PHASE(0);
+    if (!staged) stage(code, rec, threadIdx.x, AMP_THREADS);
+    bool have = false;
+    unsigned ncode = 0;
     if (!(code & MSG_DIR_B)) {
       lds_barrier();
       PHASE(1);
@@ -876,7 +1038,14 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
         hn[o] = (1.f - z) * h[o] + z * ht;
       }
       LOG(W->node, 0, seq, it);
+      if (threadIdx.x == 64) {
+        peek_msg(mine, head, s_ctl);
+        if (s_ctl[2] != 0u) g_decode(gd, s_ctl[0], 0, head & 1);
+      }
       publish_barrier();
+      have = uni(s_ctl[2]) != 0u;
+      ncode = uni(s_ctl[0]);
+      if (have && threadIdx.x >= 64) stage(ncode, head & 1, threadIdx.x - 64, AMP_THREADS - 64);
       if (threadIdx.x < 64) {
         fence_release();
         // the next state is complete when every tile has written its units
@@ -891,39 +1060,7 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
       }
       PHASE(3);
     } else {
-    // backward through blend, tanh, the candidate linear and r*h
-    {
-      // the gradient w.r.t. the states leaving the step, for this tile's units: delta rows in tile order
-      const GQ float* gH = B.gH + B.sl(s);
-      GQ float* dZ = B.dZ + B.sl(s);
-      const bool from_readout = it + 1 == B.S;
-      const GParts ep = g_edge_parts(B, present);
-      if (vec) {
-        // the tile's units first (one group per thread and round trip), then zeros for the rest of each row
-        const int GY = Hs >> 2, GZ = GY - GU;
-        for (int idx = threadIdx.x; idx < K * GU; idx += AMP_THREADS) {
-          const int k = idx / GU, c = (idx - k * GU) << 2;
-          const int o = k * H + u0 + c;
-          const v4f z = *(const GQ v4f*)(Z + o), ht = *(const GQ v4f*)(Ht + o), hv = *(const GQ v4f*)(h + o);
-          const v4f gg = from_readout ? *(const GQ v4f*)(gH + o) : g_state_gradient4(B, ep, s, o, it + 1);
-          *(LDSQ v4f*)(gt + o) = gg;
-          *(GQ v4f*)(dZ + o) = gg * (ht - hv) * z * (1.f - z);
-          *(LDSQ v4f*)(Y + k * Hs + c) = gg * z * (1.f - ht * ht);
-        }
-        for (int idx = threadIdx.x; idx < K * GZ; idx += AMP_THREADS)
-          *(LDSQ v4f*)(Y + (idx / GZ) * Hs + nu + ((idx % GZ) << 2)) = (v4f){0.f, 0.f, 0.f, 0.f};
-      } else {
-      for (int i = threadIdx.x; i < K * nu; i += AMP_THREADS) {
-        const int k = i / nu, j = i - k * nu, o = k * H + u0 + j;
-        const float gg = from_readout ? gH[o] : g_state_gradient(B, ep, s, o, it + 1);
-        const float z = Z[o], ht = Ht[o];
-        gt[o] = gg;
-        dZ[o] = gg * (ht - h[o]) * z * (1.f - z);
-        Y[k * Hs + j] = gg * z * (1.f - ht * ht);
-      }
-      for (int i = threadIdx.x; i < K * (Hs - nu); i += AMP_THREADS) Y[(i / (Hs - nu)) * Hs + nu + i % (Hs - nu)] = 0.f;
-      }
-    }
+    // backward through blend, tanh (staged above), the candidate linear and r*h
     lds_barrier();
     PHASE(4);
     LOG(W->node, 1, seq, it);
@@ -959,7 +1096,14 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
         dHp[i] = (j >= u0 && j < u0 + nu) ? drh * r + gt[i] * (1.f - z) : drh * r;
       }
     }
+    if (threadIdx.x == 64) {
+        peek_msg(mine, head, s_ctl);
+        if (s_ctl[2] != 0u) g_decode(gd, s_ctl[0], 0, head & 1);
+      }
     publish_barrier();
+    have = uni(s_ctl[2]) != 0u;
+    ncode = uni(s_ctl[0]);
+    if (have && threadIdx.x >= 64) stage(ncode, head & 1, threadIdx.x - 64, AMP_THREADS - 64);
     if (threadIdx.x == 0) {
       fence_release();
       // every candidate tile's parts are there: on to the two gates
@@ -968,10 +1112,15 @@ __device__ __noinline__ void role_g_cand(const GQ AmpDev* D, const GQ WorkerDev*
         ring_post(rg.gr, MSG_MAKE(1, s, it));
       }
     }
+    PHASE(7);
     g_count_and_update<NRBT, NCGT>(D, W, nd, t, g, pend, count, nrows, tstep, K, gb);
     }
-    if (threadIdx.x == 64) poll_msg(D, mine, head, s_ctl);
+    if (!have && threadIdx.x == 64) {
+      poll_msg(D, mine, head, s_ctl);
+      if (s_ctl[1] == 0u) g_decode(gd, s_ctl[0], 0, head & 1);
+    }
     lds_barrier();
+    staged = have;
   }
   tile_store(nd, t, g.Wg, g.bg);
   if ((int)threadIdx.x < t.R) ndG[(long long)nd.rows * t.C + t.grow(threadIdx.x)] = gb;

@@ -119,7 +119,23 @@ def test_full_size_event_record_invariants(cfgi):
     tr.close()
 
 
-def test_full_size_per_event_parity_tree():
+class Progress:
+    """The replays below take a minute or two of checker time during which the test prints nothing; a line every 20
+    seconds, written past pytest's capture, tells whoever watches the run that it is alive."""
+
+    def __init__(self, capsys, what):
+        import time
+        self.capsys, self.what, self.time, self.last, self.n = capsys, what, time, time.time(), 0
+
+    def tick(self):
+        self.n += 1
+        if self.n % 4096 == 0 and self.time.time() - self.last > 20.0:
+            self.last = self.time.time()
+            with self.capsys.disabled():
+                print("[%s: checker replay running, %d events]" % (self.what, self.n), flush=True)
+
+
+def test_full_size_per_event_parity_tree(capsys):
     """The benchmark's Tree-LSTM run itself -- 8,544 trees, its learning rate, 64 instances in flight, 8 + 16 tiles,
     about 5,000 updates per cell -- against the checker's replay of its event record.  After that many asynchronous
     updates rounding differences may have compounded in the parameters, so what single events emit is compared as
@@ -147,7 +163,10 @@ def test_full_size_per_event_parity_tree():
     rt = oracle_runtime(model, dims, fp, cfg["muf"], dict(kind="sgd", lr=cfg["opt"][1]["lr"]), lookup_muf=cfg["lmuf"])
     ref = {}
 
+    progress = Progress(capsys, "tree, 8,544 trees")
+
     def probe(name, kind, state, payload):
+        progress.tick()
         if state[0] % period:
             return
         if kind == "F" and name in ("leaf", "branch"):
@@ -178,3 +197,44 @@ def test_full_size_per_event_parity_tree():
     assert max(thirds) <= 1e-5, thirds
     assert le.max() <= 1e-5, le_thirds
     assert max(perr.values()) <= 1e-5, perr
+
+
+def test_full_size_replay_parity_ggnn(capsys):
+    """The graph workload at its full size and in the benchmark's launch shape (20,000 graphs, 32 in flight, an update
+    every 20 gradients, the edge and GRU nodes split over 2 + 2 + 2 + 3 workgroups; about 4,000 Adam updates per
+    node): the checker replays the whole event record; all 20,000 losses and the end state must agree to 1e-5.
+    The optimizer setting is the replay cases' (lr 2e-4, eps 1e-6): at the benchmark's own (lr 1e-3, eps 1e-8) this
+    training run is chaotic -- measured: the same comparison ends 30 % apart in the parameters, as it does between
+    two runs of the checker from initial values 1e-7 apart -- so that no implementation can follow another there."""
+    from oracle import amp as oamp
+    from util import named_logs, oracle_runtime, rel_err
+    cfg = bench.DEFAULTS[4]
+    model, dims, data = synth.workload(4)
+    fp = synth.init_params(model, dims, 104)
+    ml, me = runner.max_len_of(model, data)
+    opt = dict(kind="adam", lr=0.0002, beta1=0.9, beta2=0.999, eps=1e-6)
+    tr = runner.Trainer(model, dims, fp, cfg["mak"], ml, me, len(data), arena_bytes=8 << 30, tiles=cfg["tiles"])
+    a = tr.amp
+    a.set_watchdog(20.0)
+    a.set_min_update_frequency(-1, cfg["muf"])
+    a.set_optimizer(-1, B.OPT_ADAM, lr=opt["lr"], beta1=opt["beta1"], beta2=opt["beta2"], eps=opt["eps"])
+    a.set_event_log(8 * (2 * ml + 2) * dims["n_steps"] * len(data) + 1024)
+    tr.submit_all(data)
+    a.train(1)
+    logs = a.get_event_log()
+    losses = a.get_instance_losses().astype(np.float64)
+    params = tr.params()
+    assert a.num_workers() == 15
+    tr.close()
+    rt = oracle_runtime(model, dims, fp, cfg["muf"], opt)
+    progress = Progress(capsys, "graphs, 20,000")
+    rt.probe = lambda *args: progress.tick()
+    rt.replay(data, named_logs(model, dims, logs[1:]))
+    ref_loss = np.array([rt.loss[s] for s in range(len(data))])
+    le = np.abs(losses - ref_loss) / np.maximum(np.abs(ref_loss), 1.0)
+    perr = {n.name: rel_err(params[k], oamp.C.pack_node(n.P)) for k, n in enumerate(rt.ppt)}
+    q = len(data) // 4
+    print("graphs, full run: loss errors by quarter %s; parameters at the end %s"
+          % (["%.1e" % le[i * q:(i + 1) * q].max() for i in range(4)], {k: "%.1e" % v for k, v in perr.items()}))
+    assert le.max() <= 1e-5, float(le.max())       # measured 1.8e-6
+    assert max(perr.values()) <= 1e-5, perr        # measured 1.6e-6
