@@ -212,14 +212,14 @@ __device__ __forceinline__ void mfma_rows_fixed(const LDSQ float* Wl, int ldw, c
   }
 }
 
-// Fixed shape with few row blocks (a node split over several tiles): NRB * NB <= 8 (row block, message block) items,
-// one per wave, so that all waves work where the per-row-block mapping above would leave most of them idle.
+// Fixed shape with few row blocks (a node split over several tiles): (row block, message block) items dealt out to
+// the waves, so that all waves work where the per-row-block mapping above would leave most of them idle.
 template <int NRB, int NCG>
 __device__ __forceinline__ void mfma_rows_items(const LDSQ float* Wl, int ldw, const LDSQ float* bl, const LDSQ float* X, int ldx,
                                                 int NB, LDSQ float* Y, int ldy) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
-  if (wave >= NRB * NB) return;
-  const int rb = wave % NRB, nb = wave / NRB;
+  for (int item = wave; item < NRB * NB; item += AMP_THREADS / 64) {
+  const int rb = item % NRB, nb = item / NRB;
   const v4f zero = {0.f, 0.f, 0.f, 0.f};
   const LDSQ float* wp = Wl + (rb * 16 + i) * ldw + 4 * q;
   const LDSQ float* xp = X + (nb * 16 + i) * ldx + 4 * q;
@@ -242,13 +242,14 @@ __device__ __forceinline__ void mfma_rows_items(const LDSQ float* Wl, int ldw, c
   }
   const v4f b4 = *(const LDSQ v4f*)(bl + rb * 16 + 4 * q);
   *(LDSQ v4f*)(Y + (nb * 16 + i) * ldy + rb * 16 + 4 * q) = (acc0 + acc1) + (acc2 + acc3) + b4;
+  }
 }
 
 // NRBT / NCGT = 0: shape known only at run time.  Ends with a barrier.
 template <int NRBT, int NCGT>
 __device__ __forceinline__ void mfma_rows(const LDSQ float* Wl, int ldw, int NRB, int NCG, const LDSQ float* bl,
                                           const LDSQ float* X, int ldx, int NB, LDSQ float* Y, int ldy) {
-  if (NRBT && NRBT <= 4 && NB >= 2 && NRBT * NB <= 8)
+  if (NRBT && NRBT <= 4 && NB >= 2)
     mfma_rows_items<NRBT ? NRBT : 1, NCGT ? NCGT : 1>(Wl, ldw, bl, X, ldx, NB, Y, ldy);
   else if (NRBT && NB == 1)
     mfma_rows_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 1>(Wl, ldw, bl, X, ldx, Y, ldy);
@@ -256,6 +257,8 @@ __device__ __forceinline__ void mfma_rows(const LDSQ float* Wl, int ldw, int NRB
     mfma_rows_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 2>(Wl, ldw, bl, X, ldx, Y, ldy);
   else if (NRBT && NB == 3)
     mfma_rows_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 3>(Wl, ldw, bl, X, ldx, Y, ldy);
+  else if (NRBT && NB == 4)
+    mfma_rows_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 4>(Wl, ldw, bl, X, ldx, Y, ldy);
   else
     mfma_rows_any(Wl, ldw, NRB, NCG, bl, X, ldx, NB, Y, ldy);
   lds_barrier();
@@ -354,6 +357,8 @@ __device__ __forceinline__ void mfma_cols(const LDSQ float* Wl, int ldw, int NRB
     mfma_cols_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 2>(Wl, ldw, Dl, ldd, DX, ldx);
   else if (NRBT && NB == 3)
     mfma_cols_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 3>(Wl, ldw, Dl, ldd, DX, ldx);
+  else if (NRBT && NB == 4)
+    mfma_cols_fixed<NRBT ? NRBT : 1, NCGT ? NCGT : 1, 4>(Wl, ldw, Dl, ldd, DX, ldx);
   else
     mfma_cols_any(Wl, ldw, NRB, NCG, Dl, ldd, NB, DX, ldx);
   lds_barrier();

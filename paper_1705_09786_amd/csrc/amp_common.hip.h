@@ -96,7 +96,7 @@ __shared__ unsigned long long s_stat[AMP_NSTAT];
   do {                                                       \
     if (threadIdx.x == 0) {                                  \
       const unsigned long long now_ = wall_clock64();        \
-      s_stat[4 + (i)] += now_ - s_stat[3];                   \
+      if (s_stat[3]) s_stat[4 + (i)] += now_ - s_stat[3];    \
       s_stat[3] = now_;                                      \
     }                                                        \
   } while (0)

@@ -127,6 +127,8 @@ struct DataDev {
   const int* tedge;        // [edge_off[i] + tstart[c] + k]: k-th edge of type c, ascending edge index
   const int* tsoff;        // [T * (tok_off[i] + i) + c * (N + 1) + v]: start of the type-c edges leaving node v, in tsk
   const int* tsk;          // [edge_off[i] + tstart[c] + .]: positions k (rows of the type-c group) grouped by source node
+  const int* tsrc;         // [edge_off[i] + tstart[c] + k]: source node of the k-th edge of type c (= src[tedge[.]])
+  const int* tdst;         // the same for its target node
 };
 
 struct AmpDev {

@@ -55,7 +55,7 @@ struct InstSet {
   std::vector<float> x, target;
   std::vector<int> tok_off{0}, tok, lab_off{0}, lab, node_off{0}, left, right, parent, edge_off{0}, src, dst, etype, tcount;
   std::vector<int> tnode;   // tree: left, right, parent code, label per node
-  std::vector<int> inoff, inedge, tstart, tedge, tsoff, tsk;   // graph adjacency (see DataDev)
+  std::vector<int> inoff, inedge, tstart, tedge, tsoff, tsk, tsrc, tdst;   // graph adjacency (see DataDev)
   bool dirty = true;   // host copy newer than what the arena holds
   size_t n() const { return keys.size(); }
   void clear() { *this = InstSet(); }
@@ -251,17 +251,28 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
       break;
     }
     case ROLE_G_EDGE: {
+      // stacked rows of a pass (several messages): as many as fit, up to 128; at least one message's
       const size_t H = c->dims.hidden, Ep = amp_round16(c->max_edges), Hs = amp_ldrow((int)H);
       if ((Rp / 16) * ((amp_round16((int)C) + 63) / 64) > 32) return 0;   // the update's register accumulator
-      f = wfl + r4(Rp) + (size_t)(amp_round16((int)C) + 63) / 64 * 64 + 2 * r4(Ep * Hs);
+      size_t cap = std::max<size_t>(Ep, 128);
+      for (;; cap -= 16) {
+        f = wfl + r4(Rp) + (size_t)(amp_round16((int)C) + 63) / 64 * 64 + 2 * r4(cap * Hs) + r4(cap);
+        if (f <= avail || cap <= Ep) break;
+      }
+      w.kb = (int)cap;
       break;
     }
     case ROLE_G_GATE:
     case ROLE_G_CAND: {
       const size_t H = c->dims.hidden, Np = amp_round16(c->max_len), Hs = amp_ldrow((int)H), Cs = amp_ldrow((int)(2 * H));
       if ((Rp / 16) * ((amp_round16((int)C) + 63) / 64) > 32) return 0;
-      f = wfl + r4(Rp) + (size_t)(amp_round16((int)C) + 63) / 64 * 64 + r4(Np * Cs) + r4(Np * Hs);
-      if (w.role == ROLE_G_CAND) f += r4((size_t)c->max_len * H);
+      size_t cap = std::max<size_t>(Np, 64);
+      for (;; cap -= 16) {
+        f = wfl + r4(Rp) + (size_t)(amp_round16((int)C) + 63) / 64 * 64 + r4(cap * Cs) + r4(cap * Hs);
+        if (w.role == ROLE_G_CAND) f += r4(cap * H);
+        if (f <= avail || cap <= Np) break;
+      }
+      w.kb = (int)cap;
       break;
     }
     case ROLE_G_READOUT:
@@ -715,6 +726,7 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     buf(11, PE * N * H);
     buf(12, N * H);
     buf(13, 8);
+    buf(14, 16);   // slot descriptor: what the lookup found out about the instance, one 64-byte line
   }
   // every replica owns a copy of all of the above, rep_stride bytes apart
   c->rep_stride = align_up(off, 4096);
@@ -978,6 +990,10 @@ int amp_submit(amp_ctx* c, int which, uint64_t key, const amp_instance* in) {
         S.tedge.insert(S.tedge.end(), te.begin(), te.end());
         S.tsoff.insert(S.tsoff.end(), tso.begin(), tso.end());
         S.tsk.insert(S.tsk.end(), tk.begin(), tk.end());
+        for (int q = 0; q < E; ++q) {
+          S.tsrc.push_back(in->src[te[q]]);
+          S.tdst.push_back(in->dst[te[q]]);
+        }
       }
       S.target.push_back(in->target);
       break;
@@ -1096,6 +1112,8 @@ void append_instance(const amp_ctx* c, InstSet& D, const InstSet& S, size_t i) {
     copy_range(D.tedge, S.tedge, e0, e1);
     copy_range(D.tsoff, S.tsoff, T * (t0 + i), T * (t0 + i) + T * (N + 1));
     copy_range(D.tsk, S.tsk, e0, e1);
+    copy_range(D.tsrc, S.tsrc, e0, e1);
+    copy_range(D.tdst, S.tdst, e0, e1);
   }
   D.tok_off.push_back((int)D.tok.size());
   D.lab_off.push_back((int)D.lab.size());
@@ -1130,6 +1148,8 @@ int upload_set(amp_ctx* c, size_t& off, const InstSet& S, DataDev& dd) {
   if ((r = upload(c, off, S.tedge, (const void**)&dd.tedge))) return r;
   if ((r = upload(c, off, S.tsoff, (const void**)&dd.tsoff))) return r;
   if ((r = upload(c, off, S.tsk, (const void**)&dd.tsk))) return r;
+  if ((r = upload(c, off, S.tsrc, (const void**)&dd.tsrc))) return r;
+  if ((r = upload(c, off, S.tdst, (const void**)&dd.tdst))) return r;
   return AMP_OK;
 }
 
