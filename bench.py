@@ -41,10 +41,11 @@ DEFAULTS = {
     # fit LDS (5 + 8, 16 workgroups, 30k trees/s) use each CU better and are what the replicated run packs two per XCD
     3: dict(mak=64, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.05)), tiles={1: 8, 2: 16}, replica_tiles={1: 5, 2: 8},
             replica_workers=16),
-    # the commonest edge type's linear and the two GRU gates split over two workgroups each, the candidate over three
-    # (15 workgroups): 14.0k graphs/s against 10.8k unsplit; more tiles add nothing (13.6-13.9k on 16-18 workgroups)
+    # the commonest edge type's linear split over four workgroups, the two GRU gates over two each, the candidate over
+    # three (17 workgroups): 21.7k graphs/s against 12.7k unsplit and 18.7k with that linear over two; more tiles of
+    # the GRU nodes add nothing (20.8-21.4k on 18-22 workgroups)
     # the replicated run keeps the nodes whole: 24 replicas of 10 workgroups beat 16 of 15
-    4: dict(mak=32, muf=20, lmuf=20, opt=("adam", dict(lr=0.001)), tiles={1: 2, 5: 2, 6: 2, 7: 3}, replica_tiles=None,
+    4: dict(mak=32, muf=20, lmuf=20, opt=("adam", dict(lr=0.001)), tiles={1: 4, 5: 2, 6: 2, 7: 3}, replica_tiles=None,
             replica_workers=10),
     5: dict(mak=128, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.02)), tiles={1: 16, 2: 64}),
 }
