@@ -163,24 +163,6 @@ __device__ __forceinline__ void poll_msg(const GQ AmpDev* D, const R& r, unsigne
   s_ctl[1] = stop;
 }
 
-// ONE thread, never waits.  If the entry with ticket `head` of ring r is already there: acquires it and leaves its
-// code in s_ctl[0], 0 in s_ctl[1] and 1 in s_ctl[2]; otherwise only s_ctl[2] = 0.  Lets a worker find out, before
-// it publishes the present message, whether the next one can be staged meanwhile -- without ever waiting for a
-// message that the present one's publication may have to cause.  No barrier.
-template <class R>
-__device__ __forceinline__ void peek_msg(const R& r, unsigned head, unsigned* s_ctl) {
-  const unsigned long long e = __hip_atomic_load((GQ unsigned long long*)&r.ent[head & r.mask], __ATOMIC_RELAXED, AGENT);
-  if ((unsigned)(e >> 32) == head + 1u) {
-    fence_acquire();
-    s_stat[1] += 1ull;
-    s_ctl[0] = (unsigned)e;
-    s_ctl[1] = 0u;
-    s_ctl[2] = 1u;
-  } else {
-    s_ctl[2] = 0u;
-  }
-}
-
 // Whole workgroup: thread 0 polls, everybody gets the code; returns false when the run is over.
 // s_ctl: two words of LDS.
 template <class R>

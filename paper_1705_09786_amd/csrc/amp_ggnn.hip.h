@@ -48,7 +48,7 @@ struct GView {
   int inst, N, E;
   const GQ int *type, *src, *dst, *tcount, *inoff, *inedge, *tstart, *tedge, *tsoff, *tsk;
   float target;
-  // filled by g_view_rec only: the admission number, the edge types present, and (edge workers) the number of edges
+  // filled by g_view_msg only: the admission number, the edge types present, and (edge workers) the number of edges
   // of the worker's type and where they start in tedge / tsk
   unsigned seq, present;
   int kc, tsc;
