@@ -477,13 +477,14 @@ class Runtime:
 
     # ---- configuration
     def set_muf(self, muf, node=None):
+        """node: a node's name (its copies "<name>.r<k>" included), or None for every node."""
         for n in self.ppt:
-            if node is None or n.name == node:
+            if node is None or n.name == node or n.name.startswith(node + ".r"):
                 n.muf = int(muf)
 
     def set_optimizer(self, node=None, **kw):
         for n in self.ppt:
-            if node is None or n.name == node:
+            if node is None or n.name == node or n.name.startswith(node + ".r"):
                 n.opt = C.Optimizer(**kw)
 
     def params(self):
@@ -721,8 +722,8 @@ def _lin(rt, name, flat, rows, cols, logkey=None):
     return rt.add(PPT(name, C.linear_fwd, C.linear_bwd, C.unpack_node(flat, rows, cols, True), logkey))
 
 
-def _lookup(rt, flat, rows, cols, logkey=None):
-    return rt.add(PPT("lookup", C.lookup_fwd, C.lookup_bwd, C.unpack_node(flat, rows, cols, False), logkey))
+def _lookup(rt, flat, rows, cols, logkey=None, name="lookup"):
+    return rt.add(PPT(name, C.lookup_fwd, C.lookup_bwd, C.unpack_node(flat, rows, cols, False), logkey))
 
 
 def build_mlp(rt, d, fp):
@@ -748,6 +749,8 @@ def build_rnn(rt, d, fp):
     Linear-1 -> activation -> Isu(t+1) -> Cond(end?) -> back to Phi, or on to
     Linear-2 and the loss.  State = (instance, position); the length is read
     from the instance."""
+    if d.get("node_replicas", 1) > 1:
+        return build_rnn_replicated(rt, d, fp, d["node_replicas"])
     look = _lookup(rt, fp[0], d["vocab"], d["emb"])
     cell = _lin(rt, "cell", fp[1], d["hidden"], d["emb"] + d["hidden"])
     out = _lin(rt, "out", fp[2], d["n_class"], d["hidden"], logkey=lambda s: (s[0], 0))
@@ -766,6 +769,63 @@ def build_rnn(rt, d, fp):
     rt.connect(cond, 0, phi, 1)
     rt.connect(cond, 1, out, 0)
     rt.connect(out, 0, loss, 0)
+
+
+def build_rnn_replicated(rt, d, fp, R):
+    """The RNN with its heavy node replicated (Section 5): R copies of Linear-1
+    between a Cond and a Phi, the rest of the loop shared.  Each copy comes
+    with a copy of the embedding table in front of it (the two are hosted
+    together), also between a Cond and a Phi.  Both Conds route on the
+    instance: admission number mod R.  Parameterized nodes in the order
+    lookup, cell, out, then (lookup.r<k>, cell.r<k>) for k = 1 .. R - 1; every
+    copy starts from the same values."""
+    looks, cells = [None] * R, [None] * R
+    looks[0] = _lookup(rt, fp[0], d["vocab"], d["emb"])
+    cells[0] = _lin(rt, "cell", fp[1], d["hidden"], d["emb"] + d["hidden"])
+    out = _lin(rt, "out", fp[2], d["n_class"], d["hidden"], logkey=lambda s: (s[0], 0))
+    for r in range(1, R):
+        looks[r] = _lookup(rt, fp[0], d["vocab"], d["emb"], name="lookup.r%d" % r)
+        cells[r] = _lin(rt, "cell.r%d" % r, fp[1], d["hidden"], d["emb"] + d["hidden"])
+    route = lambda rt_, s: s[0] % R
+    cond_t, phi_t = rt.add(Cond("cond_tok", route)), rt.add(Phi("phi_tok"))
+    cond_c, phi_c = rt.add(Cond("cond_cell", route)), rt.add(Phi("phi_cell"))
+    phi = rt.add(Phi("phi"))
+    cat = rt.add(concat_join("concat"))
+    act = rt.add(NPT("tanh", C.tanh_fwd, C.tanh_bwd))
+    isu = rt.add(Isu("isu", lambda rt_, s: (s[0], s[1] + 1), lambda rt_, s: (s[0], s[1] - 1)))
+    cond = rt.add(Cond("cond", lambda rt_, s: 1 if s[1] == len(rt_.inst(s[0])["tokens"]) else 0))
+    loss = rt.add(Loss("loss", "xent"))
+    rt.connect(rt.ctrl, 0, cond_t, 0)
+    rt.connect(rt.ctrl, 1, phi, 0)
+    rt.connect(rt.ctrl, 2, loss, 1)
+    for r in range(R):
+        rt.connect(cond_t, r, looks[r], 0)
+        rt.connect(looks[r], 0, phi_t, r)
+        rt.connect(cond_c, r, cells[r], 0)
+        rt.connect(cells[r], 0, phi_c, r)
+    rt.connect(phi_t, 0, cat, 0)
+    rt.connect(phi, 0, cat, 1)
+    rt.chain(cat, cond_c)
+    rt.chain(phi_c, act, isu, cond)
+    rt.connect(cond, 0, phi, 1)
+    rt.connect(cond, 1, out, 0)
+    rt.connect(out, 0, loss, 0)
+
+
+def average_node_replicas(rt):
+    """End-of-epoch synchronisation of a replicated node (Section 5): the
+    parameters of a node and of its copies "<name>.r<k>" become their mean,
+    summed in copy order.  Accumulators, counts and optimizer slots stay with
+    their copy."""
+    groups = {}
+    for n in rt.ppt:
+        groups.setdefault(n.name.split(".r")[0], []).append(n)
+    for nodes in groups.values():
+        if len(nodes) > 1:
+            for name in nodes[0].P:
+                mean = sum(n.P[name] for n in nodes) / float(len(nodes))
+                for n in nodes:
+                    n.P[name] = mean.copy()
 
 
 def pump_rnn(rt, seq, inst):

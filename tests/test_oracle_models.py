@@ -634,3 +634,76 @@ def test_inference_instances_leave_training_untouched(model):
     assert busy.max_active_seen <= 5
     kinds = [k for (n, k, _) in busy.events if n == "controller"]
     assert kinds.count("A") == kinds.count("R") == 2 * len(train) + len(evals)
+
+
+# ---------------------------------------------------------------- replicas of one heavy node (Section 5)
+def _fixed_len_rnn(n, length, seed=5):
+    return synth.make_rnn(n, seed, TINY["rnn"], min_len=length, max_len=length)
+
+
+def test_node_replicas_with_one_update_per_epoch_equal_full_batch_sgd():
+    """Copies of the RNN's cell between a Cond and a Phi, the output layer shared.  If every copy makes exactly one
+    update per epoch, from the mean of the gradient messages of its (equally long) share, and so does the shared
+    layer from all of them, then after the end-of-epoch averaging the model is what plain full-batch SGD gives --
+    computed by the direct trainer, which knows nothing of messages, Cond, Phi or copies."""
+    R, n, T, lr, epochs = 3, 12, 3, 0.1, 2
+    dims = dict(TINY["rnn"], node_replicas=R)
+    fp = tiny_params("rnn", scale=1.0)
+    data = _fixed_len_rnn(n, T)
+    rt = amp.Runtime("rnn", dims, fp)
+    assert [p.name for p in rt.ppt] == ["lookup", "cell", "out", "lookup.r1", "cell.r1", "lookup.r2", "cell.r2"]
+    rt.set_optimizer(kind="sgd", lr=lr)
+    rt.set_muf(n // R * T, "lookup")
+    rt.set_muf(n // R * T, "cell")
+    rt.set_muf(n, "out")
+    P = direct.unpack("rnn", TINY["rnn"], fp)
+    losses, ref = [], []
+    for e in range(epochs):
+        losses += rt.run(data, mak=4, first_seq=e * n)
+        assert all(p.count == 0 for p in rt.ppt)          # everybody has just updated
+        amp.average_node_replicas(rt)
+        ref += direct.train("rnn", TINY["rnn"], P, data, lr=lr, batch=n)
+    assert np.allclose(losses, ref, rtol=1e-12, atol=1e-12)
+    for p in rt.ppt:
+        k = ["lookup", "cell", "out"].index(p.name.split(".r")[0])
+        for name in p.P:
+            assert np.allclose(p.P[name], P[k][name], rtol=1e-11, atol=1e-13), (p.name, name)
+
+
+def test_node_replicas_route_on_the_instance_and_stay_apart():
+    """The Conds send admission a to copy a mod R, every step of it, and its gradients come back to that copy; with
+    the shared layer frozen a copy therefore trains exactly as a model of its own on its share of the instances."""
+    R, n = 2, 8
+    dims = dict(TINY["rnn"], node_replicas=R)
+    fp = tiny_params("rnn", scale=1.0)
+    data = tiny_data("rnn", n)
+    rt = amp.Runtime("rnn", dims, fp)
+    rt.set_optimizer(kind="sgd", lr=0.05)
+    rt.set_optimizer("out", kind="sgd", lr=0.0)
+    rt.set_muf(2)
+    rt.run(data, mak=1)
+    for name, kind, key in rt.events:
+        if name.split(".r")[0] in ("lookup", "cell") and kind in ("F", "B"):
+            copy = int(name.split(".r")[1]) if ".r" in name else 0
+            assert key[0] % R == copy, (name, kind, key)
+    for r in range(R):
+        alone = amp.Runtime("rnn", TINY["rnn"], fp)
+        alone.set_optimizer(kind="sgd", lr=0.05)
+        alone.set_optimizer("out", kind="sgd", lr=0.0)
+        alone.set_muf(2)
+        alone.run(data[r::R], mak=1)
+        for base in ("lookup", "cell"):
+            mine = next(p for p in rt.ppt if p.name == (base if r == 0 else "%s.r%d" % (base, r)))
+            ref = next(p for p in alone.ppt if p.name == base)
+            for name in ref.P:
+                assert np.array_equal(mine.P[name], ref.P[name]), (r, base, name)
+
+
+def test_one_copy_is_the_plain_graph():
+    fp = tiny_params("rnn", scale=1.0)
+    data = tiny_data("rnn", 6)
+    a = amp.Runtime("rnn", TINY["rnn"], fp)
+    b = amp.Runtime("rnn", dict(TINY["rnn"], node_replicas=1), fp)
+    for rt in (a, b):
+        rt.set_muf(3)
+    assert a.run(data, mak=3) == b.run(data, mak=3)
