@@ -299,6 +299,29 @@ def main():
                              / (N_CU * LDS_BYTES_PER_CLK_PER_CU * CLOCK_HZ),
                              "train_loss": a.get_loss()["mean_loss"]}
         tr.close()
+    # The RNN is the paper's own example of a single heavy node (Section 5): copies of the cell alone between a Cond
+    # and a Phi, the output layer shared, the copies averaged at the end of each epoch; the instances in flight
+    # grow with the copies, as in the paper's table (2 copies at 4, 4 copies at 8 there).
+    if args.config == 2 and (args.replicas is None or args.replicas > 1):
+        copies = 8
+        tr = runner.Trainer(model, dims, fp, 4 * cfg["mak"], ctx["ml"], ctx["me"], len(data), arena_bytes=4 << 30,
+                            node_replicas={1: copies})
+        a = tr.amp
+        a.set_min_update_frequency(-1, cfg["muf"])
+        a.set_optimizer(-1, ctx["kind"], **cfg["opt"][1])
+        tr.submit_all(data)
+        for _ in range(args.warmup):
+            a.train(1)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        a.train(args.steps)
+        torch.cuda.synchronize()
+        cwall = time.perf_counter() - t0
+        out["cell_copies"] = {"copies": copies, "max_active_keys": 4 * cfg["mak"], "value": n * args.steps / cwall,
+                              "unit": "instances/s", "kernel_instances_per_s": n * args.steps / a.get_loss()["seconds"],
+                              "workgroups": a.num_workers(), "parameter_averaging": "end of every epoch, the copies only",
+                              "train_loss": a.get_loss()["mean_loss"]}
+        tr.close()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(model, dims, fp, data, cfg)
     # The metric names two workloads: the graph network (config 4) is measured in the same run, as an object of its

@@ -241,6 +241,25 @@ int amp_set_weights_in_hbm(amp_ctx *ctx, int node_id, int on);
  * admissions per replica.  Only before amp_finalize. */
 int amp_set_replicas(amp_ctx *ctx, int n_replicas);
 
+/* Replicas of one heavy node (Section 5: the linear layer in the body of the
+ * RNN's loop is the bottleneck, so it alone is replicated, in full, between a
+ * Cond and a Phi, and the rest of the graph is shared).  Built for the RNN
+ * model's recurrent cell, node_id 1: copy r >= 1 of the cell is node 2 + 2 r,
+ * a worker of its own with its own parameters, accumulator, update count and
+ * optimizer slots; since the cell's worker hosts the embedding table, each
+ * copy has its own table too (node 1 + 2 r).  The Cond routes on the instance:
+ * admission a is run by copy a mod n_replicas, all its steps alike, and its
+ * gradients return to that copy.  The output layer and the loss are shared
+ * and see every instance.  At the end of every training epoch the copies'
+ * parameters are set to their mean (the paper's infrequent synchronisation;
+ * its asynchronous trigger of a group synchronisation is not built).
+ * amp_set_params / amp_set_min_update_frequency / amp_set_optimizer on node 0
+ * or 1 apply to every copy; amp_get_params on them reads copy 0; the copies'
+ * own ids work too, and event records name them.  1 (default) = no copies; at
+ * most 64.  Does not combine with amp_set_replicas.  Only between the build
+ * call and amp_finalize; AMP_EUNSUPPORTED for other models or nodes. */
+int amp_set_node_replicas(amp_ctx *ctx, int node_id, int n_replicas);
+
 /* Validates the graph if that has not been done (see amp_validate_graph),
  * places its nodes on workers (Appendix A: a worker hosts one or more IR
  * nodes; Section 6 affinitizes the heavy operations to workers of their own:

@@ -81,6 +81,7 @@ SIGNATURES = {
     "amp_set_tiles": (ct.c_int, [_ctxp, ct.c_int, ct.c_int]),
     "amp_set_weights_in_hbm": (ct.c_int, [_ctxp, ct.c_int, ct.c_int]),
     "amp_set_replicas": (ct.c_int, [_ctxp, ct.c_int]),
+    "amp_set_node_replicas": (ct.c_int, [_ctxp, ct.c_int, ct.c_int]),
     "amp_finalize": (ct.c_int, [_ctxp, ct.c_int, ct.c_int, ct.c_int, ct.c_size_t]),
     "amp_set_max_active_keys": (ct.c_int, [_ctxp, ct.c_int]),
     "amp_set_min_update_frequency": (ct.c_int, [_ctxp, ct.c_int, ct.c_int]),
@@ -250,6 +251,9 @@ class Amp:
 
     def set_replicas(self, n):
         self._chk(self.L.amp_set_replicas(self.h, n))
+
+    def set_node_replicas(self, node, n):
+        self._chk(self.L.amp_set_node_replicas(self.h, node, n))
 
     def set_weights_in_hbm(self, node, on=True):
         self._chk(self.L.amp_set_weights_in_hbm(self.h, node, int(on)))

@@ -4,7 +4,7 @@
 #pragma once
 #include <stdint.h>
 
-#define AMP_MAX_NODES 16
+#define AMP_MAX_NODES 144   // the largest model: an RNN whose cell has 64 copies (3 + 2 x 63 nodes)
 #define AMP_MAX_WORKERS 128
 #define AMP_MAX_BUFS 24
 #define AMP_THREADS 512
@@ -99,6 +99,7 @@ struct WorkerDev {
   float* pend;                 // pending (delta, input) pairs of the hosted dense node
   unsigned log_cap;
   int kb;                      // largest batch this worker takes at once
+  int rep;                     // which replica of its node this worker is (node replicas, Section 5); else 0
 };
 
 // One stored instance set (training or evaluation), flattened.
@@ -167,7 +168,8 @@ struct AmpDev {
   float* probe;
   unsigned* probe_n;
   unsigned probe_cap, probe_period;
-  int probe_w, pad1;
+  int probe_w;
+  int node_replicas;          // RNN: copies of the cell between Cond and Phi; admission a goes to copy a mod node_replicas
   long long watchdog_ticks;
   void* buf[AMP_MAX_BUFS];    // model-specific per-slot storage
   long long stride[AMP_MAX_BUFS];

@@ -118,7 +118,9 @@ __device__ __noinline__ void role_ctrl(const GQ AmpDev* D, const GQ WorkerDev* W
             sm[3] = toff;
           }
           fence_release();
-          ring_post(D->ring[1], MSG_MAKE(0, s, 0));
+          // RNN with a replicated cell: the Cond in front of the copies routes on the admission number
+          const int rep = D->model == 2 ? (int)(seq % (unsigned)D->node_replicas) : 0;
+          ring_post(D->ring[rep == 0 ? 1 : 2 + rep], MSG_MAKE(0, s, 0));
         }
         next++;
         active++;

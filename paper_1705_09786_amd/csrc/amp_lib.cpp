@@ -41,12 +41,13 @@ struct HostNode {
   std::vector<float> params;
   bool dirty = true;        // host copy newer than device copy
   size_t off_P = 0, off_G = 0, off_M = 0, off_V = 0;
+  int base = -1, rep = 0;   // a replica of node `base` (Section 5); -1 = a node of its own
   size_t count() const { return (size_t)rows * cols + (has_bias ? rows : 0); }
 };
 
 struct HostWorker {
   int role, node, tile, ntiles, u0, nu, ring, aux;
-  int kb = 1;
+  int kb = 1, rep = 0;
   size_t off_state, off_pend = 0, pend_bytes = 0;
 };
 
@@ -107,6 +108,7 @@ struct amp_ctx {
   long long buf_stride[AMP_MAX_BUFS] = {0};
   bool state_zeroed = false;
   int replicas = 1, last_replicas = 1;
+  int node_replicas = 1;                              // copies of the recurrent cell between Cond and Phi (Section 5)
   size_t rep_stride = 0;                              // bytes from one replica's static region to the next
   std::vector<unsigned> rep_admitted;                 // admissions so far, per replica
   std::vector<std::vector<amp_event>> launch_events;  // per worker, while a training call runs
@@ -364,6 +366,7 @@ namespace {
 // A recognised graph becomes the model the kernel has workers for: the parameterized nodes in the model's
 // numbering, with the layout facts the workers need.
 int lower_model(amp_ctx* c, int model, const amp_model_dims* d) {
+  c->node_replicas = 1;
   switch (model) {
     case AMP_MODEL_MLP:
       if (!positive({d->d_in, d->hidden, d->n_class})) return fail(c, AMP_EINVAL, "mlp: sizes must be >= 1");
@@ -543,6 +546,27 @@ int amp_set_replicas(amp_ctx* c, int n_replicas) {
   return AMP_OK;
 }
 
+int amp_set_node_replicas(amp_ctx* c, int node_id, int n_replicas) {
+  if (!c) return AMP_EINVAL;
+  if (!c->model || c->finalized) return fail(c, AMP_ESTATE, "set_node_replicas: only between build and finalize");
+  if (c->model != AMP_MODEL_RNN || node_id != 1)
+    return fail(c, AMP_EUNSUPPORTED, "set_node_replicas: only the RNN's recurrent cell (node 1) can be replicated");
+  if (n_replicas < 1 || n_replicas > 64) return fail(c, AMP_EINVAL, "set_node_replicas: 1..64 replicas");
+  // nodes 0..2 are the model's own; a replica r >= 1 adds a copy of the cell and of the table its worker hosts
+  c->nodes.resize(3);
+  for (int r = 1; r < n_replicas; ++r)
+    for (int b = 0; b < 2; ++b) {
+      HostNode n = c->nodes[b];
+      n.name += ".r" + std::to_string(r);
+      n.base = b;
+      n.rep = r;
+      n.dirty = true;
+      c->nodes.push_back(n);
+    }
+  c->node_replicas = n_replicas;
+  return AMP_OK;
+}
+
 int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_edges, size_t max_instances) {
   if (!c) return AMP_EINVAL;
   if (c->finalized) return fail(c, AMP_ESTATE, "finalize: already finalized");
@@ -587,10 +611,15 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     for (size_t i = 0; i < c->workers.size(); ++i) c->workers[i].ring = (int)i;
     nrings = 4;
   } else if (c->model == AMP_MODEL_RNN) {
+    // rings: 0 controller, 1 cell, 2 output layer, 3.. the cell's further replicas
     add_worker(ROLE_RNN_CELL, 1, 0, 1, 0);
     add_worker(ROLE_RNN_OUT, 2, 0, 1, 0);
+    for (int r = 1; r < c->node_replicas; ++r) {
+      add_worker(ROLE_RNN_CELL, 2 + 2 * r, 0, 1, 0);
+      c->workers.back().rep = r;
+    }
     for (size_t i = 0; i < c->workers.size(); ++i) c->workers[i].ring = (int)i;
-    nrings = 3;
+    nrings = (int)c->workers.size();
   } else if (c->model == AMP_MODEL_TREE) {
     // rings: 0 controller, 1 lookup, 2 leaf (all leaf tiles), 3 branch (all branch tiles), 4 out
     add_worker(ROLE_TREE_LOOKUP, 0, 0, 1, 0);
@@ -626,6 +655,9 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
       return fail(c, AMP_EUNSUPPORTED, "finalize: at most 12 edge tiles and 12 GRU tiles in all (%d and %d asked for)", pe, pa);
   }
   if (c->workers.size() > AMP_MAX_WORKERS) return fail(c, AMP_EUNSUPPORTED, "finalize: too many workers");
+  if (c->nodes.size() > AMP_MAX_NODES) return fail(c, AMP_EUNSUPPORTED, "finalize: too many nodes");
+  if (c->node_replicas > 1 && c->replicas > 1)
+    return fail(c, AMP_EUNSUPPORTED, "finalize: replicas of a node and replicas of the whole model do not combine");
   if (c->workers.size() * (size_t)c->replicas > 256)
     return fail(c, AMP_EUNSUPPORTED, "finalize: %zu workers x %d replicas exceed 256 workgroups", c->workers.size(), c->replicas);
   for (HostWorker& w : c->workers) {
@@ -662,16 +694,22 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     c->off_ring_tail[r] = take(64);
   }
   c->sync_end = off;
+  // the parameters of a node's replicas lie behind the node's own at equal distances (one averaging launch)
+  for (size_t i = 0; i < c->nodes.size(); ++i)
+    if (c->nodes[i].base < 0) {
+      c->nodes[i].off_P = take(c->nodes[i].count() * 4);
+      for (HostNode& n : c->nodes)
+        if (n.base == (int)i) n.off_P = take(n.count() * 4);
+    }
   for (HostNode& n : c->nodes) {
     const size_t b = n.count() * 4;
-    n.off_P = take(b);
     n.off_G = take(b);
     n.off_M = take(b);
     n.off_V = take(b);
   }
   for (HostWorker& w : c->workers) {
     w.off_state = take(64);
-    if (w.node >= 0 && c->nodes[w.node].name != "lookup" && w.role != ROLE_TREE_OUT) {
+    if (w.node >= 0 && c->nodes[w.node].name.compare(0, 6, "lookup") != 0 && w.role != ROLE_TREE_OUT) {
       w.pend_bytes = pend_stride(c, w) * 4 * AMP_DENSE_MAX_MUF * rows_per_message(c, w);
       w.off_pend = take(w.pend_bytes);
     }
@@ -691,7 +729,7 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     buf(1, (size_t)c->max_len * SP);
     buf(2, SP);
     c->buf_stride[3] = 0;
-    c->buf_bytes[3] = 4 * 64 * SP;
+    c->buf_bytes[3] = 4 * 64 * SP * (size_t)c->node_replicas;   // one block per replica of the cell
     c->off_buf[3] = take(c->buf_bytes[3]);
   } else if (c->model == AMP_MODEL_TREE) {
     const size_t L = c->max_len, N2 = 2 * L - 1, E = c->dims.emb, Ep = amp_round4(c->dims.emb), Hp = amp_round4(c->dims.hidden);
@@ -775,7 +813,7 @@ int amp_set_min_update_frequency(amp_ctx* c, int node_id, int muf) {
       }
   }
   for (int i = 0; i < (int)c->nodes.size(); ++i)
-    if (node_id < 0 || node_id == i) c->nodes[i].muf = muf;
+    if (node_id < 0 || node_id == i || c->nodes[i].base == node_id) c->nodes[i].muf = muf;   // a node and its replicas
   return AMP_OK;
 }
 
@@ -785,8 +823,8 @@ int amp_set_optimizer(amp_ctx* c, int node_id, int kind, const amp_opt_params* p
   if (kind < AMP_OPT_SGD || kind > AMP_OPT_ADAM) return fail(c, AMP_EINVAL, "unknown optimizer %d", kind);
   if (node_id < -1 || node_id >= (int)c->nodes.size()) return fail(c, AMP_EINVAL, "no node %d", node_id);
   for (int i = 0; i < (int)c->nodes.size(); ++i) {
-    if (node_id >= 0 && node_id != i) continue;
-    const bool lookup = c->nodes[i].name == "lookup";
+    if (node_id >= 0 && node_id != i && c->nodes[i].base != node_id) continue;   // a node and its replicas
+    const bool lookup = c->nodes[i].name.compare(0, 6, "lookup") == 0;
     if (lookup && kind != AMP_OPT_SGD) {
       if (node_id >= 0) return fail(c, AMP_EUNSUPPORTED, "lookup nodes support SGD only");
       c->nodes[i].opt = AMP_OPT_SGD;   // "all nodes": the lookup keeps SGD with the given rate
@@ -852,6 +890,11 @@ int amp_set_params(amp_ctx* c, int node_id, const float* host, size_t n) {
     return fail(c, AMP_EINVAL, "set_params: node %d (%s) has %zu parameters, got %zu", node_id, nd.name.c_str(), nd.count(), n);
   std::memcpy(nd.params.data(), host, n * 4);
   nd.dirty = true;
+  for (HostNode& r : c->nodes)   // its replicas start from the same values
+    if (r.base == node_id) {
+      r.params = nd.params;
+      r.dirty = true;
+    }
   return AMP_OK;
 }
 
@@ -1289,6 +1332,7 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
       wd.stats = (unsigned long long*)(c->arena + off_stats[r]) + NSTAT * i;
       wd.pend = w.pend_bytes ? (float*)rep_ptr(c, r, w.off_pend) : nullptr;
       wd.kb = w.kb;
+      wd.rep = w.rep;
     }
     D.model = c->model;
     D.n_workers = (int)wpr;
@@ -1320,6 +1364,7 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
       D.g_PA = D.g_tiles[8] + D.g_tiles[9] + D.g_tiles[10];
     }
     D.admit_bounded = train ? c->admit_bounded : 0;
+    D.node_replicas = c->node_replicas;
     D.max_staleness = (float)c->max_staleness;
     D.n_updaters = (int)wpr - 1;   // every worker but the controller applies updates
     D.n_total = (unsigned)n_total[r];
@@ -1428,7 +1473,7 @@ int run(amp_ctx* c, int which, int epochs, bool train, amp_eval_result* ev) {
   if (c->model == AMP_MODEL_TREE && c->nodes[0].muf > AMP_TREE_LOOKUP_MAX_MUF)
     return fail(c, AMP_EUNSUPPORTED, "the tree lookup supports min_update_frequency up to %d", AMP_TREE_LOOKUP_MAX_MUF);
   for (const HostNode& n : c->nodes)
-    if (n.name != "lookup" && n.muf > AMP_DENSE_MAX_MUF)
+    if (n.name.compare(0, 6, "lookup") != 0 && n.muf > AMP_DENSE_MAX_MUF)
       return fail(c, AMP_EUNSUPPORTED, "dense nodes support min_update_frequency up to %d", AMP_DENSE_MAX_MUF);
   if (S.n() * (size_t)epochs >= 0xffffffffull) return fail(c, AMP_EINVAL, "too many admissions for one call");
   // evaluation runs on the first replica alone: after a training call all replicas hold the same parameters
@@ -1493,12 +1538,22 @@ int run_prepared(amp_ctx* c, int which, int epochs, bool train, amp_eval_result*
   c->launch_events.assign(wpr * R, std::vector<amp_event>());
   if (train) c->last_probe.clear();
   // with replicas the parameters are averaged at the end of every epoch (Section 5), hence one launch per epoch
-  const int launches = R > 1 ? epochs : 1, per_launch = R > 1 ? 1 : epochs;
+  const bool averaged = R > 1 || (train && c->node_replicas > 1);
+  const int launches = averaged ? epochs : 1, per_launch = averaged ? 1 : epochs;
   for (int l = 0; l < launches; ++l) {
     if (int rc = launch_once(c, res, out_begin, per_launch, train, losses, correct, seconds)) return rc;
     if (R > 1)
       for (HostNode& n : c->nodes)
         HIPCHK(c, amp_average((float*)rep_ptr(c, 0, n.off_P), c->rep_stride / 4, R, n.count(), c->stream));
+    if (train && c->node_replicas > 1)
+      // the copies of a node lie at equal distances behind it
+      for (size_t i = 0; i < c->nodes.size(); ++i) {
+        const HostNode& n = c->nodes[i];
+        int copies = 1;
+        for (const HostNode& o : c->nodes) copies += o.base == (int)i;
+        if (n.base < 0 && copies > 1)
+          HIPCHK(c, amp_average((float*)rep_ptr(c, 0, n.off_P), align_up(n.count() * 4) / 4, copies, n.count(), c->stream));
+      }
   }
   HIPCHK(c, hipStreamSynchronize(c->stream));
 
@@ -1549,7 +1604,7 @@ int run_mixed(amp_ctx* c, int epochs, amp_eval_result* ev) {
   if (c->model == AMP_MODEL_TREE && c->nodes[0].muf > AMP_TREE_LOOKUP_MAX_MUF)
     return fail(c, AMP_EUNSUPPORTED, "the tree lookup supports min_update_frequency up to %d", AMP_TREE_LOOKUP_MAX_MUF);
   for (const HostNode& n : c->nodes)
-    if (n.name != "lookup" && n.muf > AMP_DENSE_MAX_MUF)
+    if (n.name.compare(0, 6, "lookup") != 0 && n.muf > AMP_DENSE_MAX_MUF)
       return fail(c, AMP_EUNSUPPORTED, "dense nodes support min_update_frequency up to %d", AMP_DENSE_MAX_MUF);
   const size_t n_tr = T.n() * (size_t)epochs, n_ev = E.n();
   if (n_tr + n_ev >= 0x7fffffffull) return fail(c, AMP_EINVAL, "too many admissions for one call");

@@ -1,5 +1,11 @@
 // Workers of the variable-length RNN (Figure 2).
 //
+// The recurrent cell may be replicated (Section 5: copies of the heavy linear layer between a Cond and a Phi): every
+// copy is a cell worker of its own with its own parameters (node 2 + 2 r for copy r >= 1, hosting table node
+// 1 + 2 r) and its own ring (2 + r); the Cond routes on the instance -- admission a goes to copy a mod
+// node_replicas, all its steps alike, and its gradient returns to the copy that holds its activations -- and the
+// copies' parameters are averaged at the end of every epoch.  The output layer and the loss are shared.
+//
 // The cell worker hosts the lookup table and the recurrent cell:
 // Concat(embedding, h) -> Linear-1 -> tanh -> Isu(t+1) -> Cond(end?) is one
 // forward event, and the loop edge is a message to the worker's own ring.
@@ -28,7 +34,7 @@ __device__ __forceinline__ RnnBufs rnn_bufs(const GQ AmpDev* D) {
   b.hs = uni_gq<float>(D->buf[0]);
   b.es = uni_gq<float>(D->buf[1]);
   b.dh = uni_gq<float>(D->buf[2]);
-  b.de = uni_gq<float>(D->buf[3]);
+  b.de = uni_gq<float>(D->buf[3]);   // one block of 64 rows per cell worker
   b.SP = uni(D->node[1].segp);
   b.TM = uni(D->max_len);
   return b;
@@ -38,10 +44,12 @@ __device__ __forceinline__ RnnBufs rnn_bufs(const GQ AmpDev* D) {
 template <int NRBT, int NCGT>
 __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDev* W) {
   float* lds = amp_lds;
-  const GQ NodeDev& nd = D->node[1];
-  const GQ NodeDev& lk = D->node[0];
+  const int nc = uni(W->node), nl = nc - 1;   // the cell's node and the table's (1 and 0; a copy's own pair)
+  const GQ NodeDev& nd = D->node[nc];
+  const GQ NodeDev& lk = D->node[nl];
   const Tile t = make_tile(nd, W);
-  const RnnBufs B = rnn_bufs(D);
+  RnnBufs B = rnn_bufs(D);
+  B.de += (long long)uni(W->rep) * 64 * B.SP;
   const Pend pd = make_pend(W, t);
   GQ float* pend = (GQ float*)pd.base;
   const int R = t.R, H = t.R, E = D->emb, V = D->vocab, KB = W->kb, SP = B.SP;
@@ -73,7 +81,7 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
   float accb = ((int)threadIdx.x < R && nd.has_bias) ? ndG[(long long)nd.rows * t.C + threadIdx.x] : 0.f;
   BatchMsg& M = s_M;
   __syncthreads();
-  const Ring mine = ring_regs(D, uni(W->ring)), out = ring_regs(D, uni(W->ring) + 1), ctl = ring_regs(D, 0);
+  const Ring mine = ring_regs(D, uni(W->ring)), out = ring_regs(D, 2), ctl = ring_regs(D, 0);
   const GQ int* tokens = uni_gq<int>(D->data.tok);
   const GQ int* smeta = uni_gq<int>(D->smeta);
   const int nd_muf = uni(nd.muf), lk_muf = uni(lk.muf);
@@ -133,8 +141,8 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
           if (in) {
             const unsigned long long tail = ((unsigned long long)M.seq[k] << 32) | ((unsigned)M.n[k] & 0xfffffu);
             const unsigned long long dirb = (unsigned long long)(isb ? 1 : 0) << 28;
-            logp[base + 2 * k] = tail | dirb | ((isb ? 1ull : 0ull) << 20);
-            logp[base + 2 * k + 1] = tail | dirb | ((isb ? 0ull : 1ull) << 20);
+            logp[base + 2 * k] = tail | dirb | ((unsigned long long)(isb ? nc : nl) << 20);
+            logp[base + 2 * k + 1] = tail | dirb | ((unsigned long long)(isb ? nl : nc) << 20);
           }
           if (k == 0) s_logn = base + 2u * (unsigned)n;
         }
@@ -266,7 +274,7 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
       tree_update_from_pend<NRBT, NCGT>(Wl, bl, &nd, t, pend, count, count, tstep, rowmap, colmap, accb);
       accb = 0.f;
       count = 0;
-      LOG(1, 2, 0, 0);
+      LOG(nc, 2, 0, 0);
     }
     if ((int)lcount >= lk_muf) {
       // the lookup's update: plain SGD over the whole (small) table
@@ -284,7 +292,7 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
           lkG[i] = 0.f;
         }
       lcount = 0;
-      LOG(0, 2, 0, 0);
+      LOG(nl, 2, 0, 0);
     }
     __syncthreads();
     PHASE(7);
@@ -318,7 +326,7 @@ __device__ __noinline__ void role_rnn_out(const GQ AmpDev* D, const GQ WorkerDev
   float* part = L.take(8 * (R > C ? R : C));
   tile_load(nd, t, Wl, bl);
   const GQ RingDev& mine = D->ring[W->ring];
-  const GQ RingDev& cell = D->ring[W->ring - 1];
+  const int NR = D->node_replicas;
   unsigned head = 0, code;
   unsigned count = W->wstate[0], tstep = W->wstate[1];
   while (wait_msg(D, mine, head, s_ctl, code)) {
@@ -352,7 +360,9 @@ __device__ __noinline__ void role_rnn_out(const GQ AmpDev* D, const GQ WorkerDev
     publish_barrier();
     if (threadIdx.x == 0) {
       fence_release();
-      ring_post(cell, MSG_MAKE(1, s, T - 1));
+      // back to the copy of the cell that ran this instance forward (ring 1, or 2 + r for copy r >= 1)
+      const int rep = (int)(seq % (unsigned)NR);
+      ring_post(D->ring[rep == 0 ? 1 : 2 + rep], MSG_MAKE(1, s, T - 1));
     }
     count_and_update(D, W, nd, t, Wl, bl, count, tstep);
   }

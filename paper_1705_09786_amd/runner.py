@@ -22,9 +22,9 @@ class Trainer:
 
     def __init__(self, model: str, dims: dict, params, max_active_keys: int, max_len: int, max_edges: int,
                  max_instances: int, arena_bytes: int = 1 << 30, tiles: dict | None = None, device: str = "cuda:0",
-                 in_hbm=(), replicas: int = 1, strict: bool = False, graph=None):
+                 in_hbm=(), replicas: int = 1, strict: bool = False, graph=None, node_replicas: dict | None = None):
         """graph: a callable that describes the model with add_node / connect on the context it is given, in place
-        of the canned builder for `model`."""
+        of the canned builder for `model`.  node_replicas: {node: copies} of single heavy nodes (Section 5)."""
         import torch
         if not torch.cuda.is_available():
             raise RuntimeError("no GPU visible: the AMP path has no CPU fallback")
@@ -43,6 +43,8 @@ class Trainer:
             self.amp.set_tiles(node, n)
         if replicas != 1:
             self.amp.set_replicas(replicas)
+        for node, n in (node_replicas or {}).items():
+            self.amp.set_node_replicas(node, n)
         for node in in_hbm:
             self.amp.set_weights_in_hbm(node, True)
         self.amp.finalize(max_active_keys, max_len, max_edges, max_instances)

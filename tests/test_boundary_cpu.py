@@ -326,3 +326,35 @@ def test_hand_built_tree_and_graph_network():
     g.finalize(4, 9, 24, 5)
     g.submit(dict(n_nodes=2, node_type=np.array([0, 1]), src=np.array([0, 1]), dst=np.array([1, 0]), etype=np.array([1, 1]),
                   target=0.5))
+
+
+def test_node_replicas_on_the_host():
+    """Replicas of one heavy node (Section 5): built for the RNN's cell; the copies are nodes of their own that
+    follow what is set on the node they copy."""
+    rnn = dict(vocab=6, emb=3, hidden=4, n_class=3)
+    a = new_ctx()
+    expect(B.AMP_ESTATE, a.set_node_replicas, 1, 2)                    # before build
+    a.build("mlp", dict(d_in=5, hidden=4, n_class=3))
+    expect(B.AMP_EUNSUPPORTED, a.set_node_replicas, 1, 2)              # another model
+    a.close()
+    a = new_ctx()
+    a.build("rnn", rnn)
+    expect(B.AMP_EUNSUPPORTED, a.set_node_replicas, 2, 2)              # the output layer
+    expect(B.AMP_EINVAL, a.set_node_replicas, 1, 0)
+    expect(B.AMP_EINVAL, a.set_node_replicas, 1, 65)
+    a.set_node_replicas(1, 3)
+    assert a.num_nodes() == 7
+    a.set_node_replicas(1, 2)                                          # asked again: replaces the earlier copies
+    assert a.num_nodes() == 5
+    a.set_replicas(2)
+    expect(B.AMP_EUNSUPPORTED, a.finalize, 4, 5, 0, 10)                # both kinds of replica at once
+    a.set_replicas(1)
+    a.finalize(4, 5, 0, 10)
+    assert a.num_workers() == 4                                        # controller, cell, output layer, one copy
+    expect(B.AMP_ESTATE, a.set_node_replicas, 1, 2)                    # after finalize
+    fp = synth.init_params("rnn", rnn, 3)
+    a.set_params(1, fp[1])
+    assert np.array_equal(a.get_params(4), fp[1]) and np.array_equal(a.get_params(1), fp[1])   # the copy follows
+    a.set_params(4, fp[1] + 1)                                         # a copy's own id works too
+    assert np.array_equal(a.get_params(4), fp[1] + 1) and np.array_equal(a.get_params(1), fp[1])
+    a.close()

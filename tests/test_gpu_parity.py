@@ -517,3 +517,47 @@ def test_replicas_replay_parity(cfg, dims, R, mak, muf, lmuf, opt, n):
         assert le.max() <= 1e-5, (epoch, int(le.argmax()), float(le.max()))
         for r in range(R):
             done[r] += len(parts[r])
+
+
+@pytest.mark.parametrize("R,mak,muf,opt,n", [(2, 8, 5, SGD, 160), (3, 16, 7, RNN_ADAM, 240)])
+def test_rnn_replicated_cell_replay_parity(R, mak, muf, opt, n):
+    """The RNN's heavy node alone replicated (Section 5): R copies of the cell between a Cond and a Phi that route
+    on the instance, the output layer and the loss shared, the copies averaged at the end of each epoch.  Two
+    epochs as two training calls: the checker replays every worker's record (the copies are nodes of their own in
+    it), averages its copies, and must agree with the GPU on all parameters and losses."""
+    model, dims, data = synth.workload(2, n=n)
+    fp = synth.init_params(model, dims, 13)
+    g = gpu_train(model, dims, fp, data, mak, muf, opt, lookup_muf=muf, node_replicas={1: R})
+    tr = g["trainer"]
+    a = tr.amp
+    assert a.num_workers() == 3 + (R - 1) and a.num_nodes() == 3 + 2 * (R - 1)
+    rt = oracle_runtime(model, dict(dims, node_replicas=R), fp, muf, opt, lookup_muf=muf)
+    names = [p.name for p in rt.ppt]
+    assert names[:3] == ["lookup", "cell", "out"] and len(names) == a.num_nodes()
+    logs, losses = g["logs"], g["losses"]
+    for epoch in range(2):
+        if epoch == 1:
+            a.train(1)
+            logs = a.get_event_log()
+            losses = a.get_instance_losses().astype(np.float64)
+        first = epoch * n
+        assert [e[2] for e in logs[0] if e[1] == "A"] == list(range(first, first + n))
+        wl = [[(names[node], k, s, l) for (node, k, s, l) in w] for w in logs[1:]]
+        for w in wl:   # a copy only ever sees its own instances
+            for name, k, s, l in w:
+                if k in ("F", "B") and name != "out":
+                    assert s % R == (int(name.split(".r")[1]) if ".r" in name else 0), (name, k, s)
+        assert sum(1 for w in wl if w) == 1 + R    # every copy worked
+        rt.replay(data, wl, first_seq=first)
+        oamp.average_node_replicas(rt)
+        params = tr.params()
+        for k, node in enumerate(rt.ppt):
+            ref = oamp.C.pack_node(node.P)
+            assert rel_err(params[k], ref) <= 1e-5, (epoch, node.name, rel_err(params[k], ref))
+            assert elementwise_err(params[k], ref)[0] <= elem_tol(opt), (epoch, node.name)
+        for r in range(1, R):   # after the averaging the copies hold the same values, bit for bit
+            assert np.array_equal(params[1 + 2 * r], params[0]) and np.array_equal(params[2 + 2 * r], params[1])
+        ref = np.array([rt.loss[first + i] for i in range(n)])
+        le = np.abs(losses - ref) / np.maximum(np.abs(ref), 1.0)
+        assert le.max() <= 1e-5, (epoch, int(le.argmax()), float(le.max()))
+    tr.close()

@@ -32,10 +32,11 @@ def f32(x):
 
 
 def gpu_train(model, dims, fp, data, mak, muf, opt, epochs=1, log=True, tiles=None, watchdog=5.0,
-              arena_bytes=1 << 30, lookup_muf=None, in_hbm=(), replicas=1, max_staleness=None, strict=False, graph=None):
+              arena_bytes=1 << 30, lookup_muf=None, in_hbm=(), replicas=1, max_staleness=None, strict=False, graph=None,
+              node_replicas=None):
     ml, me = runner.max_len_of(model, data)
     tr = runner.Trainer(model, dims, fp, mak, ml, me, len(data), arena_bytes=arena_bytes, tiles=tiles, in_hbm=in_hbm,
-                        replicas=replicas, strict=strict, graph=graph)
+                        replicas=replicas, strict=strict, graph=graph, node_replicas=node_replicas)
     a = tr.amp
     a.set_watchdog(watchdog)
     if max_staleness is not None:
