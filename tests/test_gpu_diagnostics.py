@@ -85,6 +85,27 @@ def test_worker_statistics():
             assert 1 <= w["batches"] <= w["messages"], w
 
 
+def test_graph_workers_take_several_messages_per_pass():
+    """The graph model's dense workers count messages and passes; every message is counted once (4 steps x forward
+    and backward per graph at the GRU nodes, the same for an edge type where the graph has such edges), split
+    nodes' tiles all see every message, and with 32 graphs in flight a pass holds more than one message on average."""
+    model, dims, data = synth.workload(4, n=600)
+    fp = synth.init_params(model, dims, 5)
+    g = gpu_train(model, dims, fp, data, 32, 20, dict(kind="adam", lr=0.0002, beta1=0.9, beta2=0.999, eps=1e-6),
+                  tiles={1: 2, 5: 2, 7: 3}, log=False)
+    stats = g["trainer"].amp.get_worker_stats()
+    S, T = dims["n_steps"], dims["n_edge_types"]
+    with_type = [sum(1 for d in data if (np.asarray(d["etype"]) == c).any()) for c in range(T)]
+    dense = [w for w in stats if 1 <= w["node"] <= T + 3]
+    assert len(dense) == (T + 1) + 2 + 1 + 3
+    for w in dense:
+        graphs = with_type[w["node"] - 1] if w["node"] <= T else len(data)
+        assert w["messages"] == 2 * S * graphs, w
+        assert 1 <= w["batches"] <= w["messages"], w
+    gru = [w for w in dense if w["node"] > T]
+    assert sum(w["messages"] for w in gru) / sum(w["batches"] for w in gru) >= 1.3, gru
+
+
 def test_workers_run_on_the_dies_the_launch_assumes():
     """The launch maps workgroups to the eight dies (XCDs) by their index -- block b is expected on die b % 8 -- and
     packs each replica's workers onto one die when whole replicas fit its 32 compute units.  Every workgroup reads
