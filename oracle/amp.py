@@ -456,6 +456,8 @@ class Runtime:
         self.eval_seqs = set()      # admission numbers of forward-only (inference) instances
         self.seq_inst = {}          # admission number -> instance, where it is not instances[seq % len]
         self.eval_pending = {}      # predictions an inference instance in flight still waits for
+        self.sync_every = None      # own schedule: a synchronisation of every replicated node's copies after this many retirements
+        self.snapshots = {}         # (node name, round) -> its parameters when the round's request reached it
 
     # ---- graph construction helpers
     def add(self, node):
@@ -489,6 +491,30 @@ class Runtime:
 
     def params(self):
         return [C.pack_node(n.P) for n in self.ppt]
+
+    # ---- asynchronous synchronisation of a replicated node's copies (Section 5, last sentence)
+    def replica_group(self, node):
+        """A node and its copies "<name>.r<k>", in copy order."""
+        base = node.name.split(".r")[0]
+        return [n for n in self.ppt if n.name.split(".r")[0] == base]
+
+    def sync_snapshot(self, node, rnd):
+        """The request of round `rnd` reaches `node`: it publishes its parameters as they stand and carries on."""
+        self.snapshots[(node.name, rnd)] = {k: v.copy() for k, v in node.P.items()}
+        self.events.append((node.name, "S", (rnd, 0)))
+
+    def sync_ready(self, node, rnd):
+        return all((n.name, rnd) in self.snapshots for n in self.replica_group(node))
+
+    def sync_load(self, node, rnd):
+        """Every copy has published: `node` moves to the mean of the published values (summed in copy order) and
+        keeps what it has learned since it published its own."""
+        group = self.replica_group(node)
+        own = self.snapshots[(node.name, rnd)]
+        for k in node.P:
+            mean = sum(self.snapshots[(n.name, rnd)][k] for n in group) / float(len(group))
+            node.P[k] = mean + (node.P[k] - own[k])
+        self.events.append((node.name, "L", (rnd, 0)))
 
     # ---- message plumbing
     def inst(self, seq):
@@ -588,6 +614,15 @@ class Runtime:
             self.active -= 1
             self.retired.append(seq)
             self.events.append(("controller", "R", (seq, 0)))
+            if self.sync_every and self.parked is None and len(self.retired) % self.sync_every == 0:
+                # the controller's request reaches every copy at once on this single-worker schedule: snapshot and
+                # load follow each other directly, so the copies simply take their mean
+                rnd = len(self.retired) // self.sync_every
+                copies = [n for n in self.ppt if len(self.replica_group(n)) > 1]
+                for n in copies:
+                    self.sync_snapshot(n, rnd)
+                for n in copies:
+                    self.sync_load(n, rnd)
             if self.max_staleness is not None:
                 # staleness-bounded admission: the limit on the instances in flight moves by one with every
                 # retirement, up if the instance saw at most max_staleness updates per parameterized node
@@ -685,6 +720,14 @@ class Runtime:
                     if kind == "U":
                         node.update(self)
                         must_update.discard(name)
+                    elif kind == "S":
+                        self.sync_snapshot(node, seq)
+                    elif kind == "L":
+                        if (name, seq) not in self.snapshots:
+                            raise RuntimeError("%s loads round %d without having published" % (name, seq))
+                        if not self.sync_ready(node, seq):
+                            break          # another copy's snapshot is still to come
+                        self.sync_load(node, seq)
                     else:
                         if name in must_update:
                             raise RuntimeError("%s reached min_update_frequency but the log has no update" % name)

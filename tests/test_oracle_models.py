@@ -707,3 +707,88 @@ def test_one_copy_is_the_plain_graph():
     for rt in (a, b):
         rt.set_muf(3)
     assert a.run(data, mak=3) == b.run(data, mak=3)
+
+
+# ---------------------------------------------------------------- asynchronous synchronisation of the copies
+def _worker_logs(rt):
+    """The recorded run as per-node logs in the form the replay driver takes."""
+    logs = {}
+    for name, kind, key in rt.events:
+        if name != "controller":
+            logs.setdefault(name, []).append((name, kind) + (key if key is not None else (0, 0)))
+    return list(logs.values())
+
+
+def test_group_synchronisation_by_hand():
+    """A copy publishes its parameters when the request reaches it and carries on; once every copy has published,
+    each moves to the mean of the published values and keeps what it learned since it published."""
+    dims = dict(TINY["rnn"], node_replicas=2)
+    rt = amp.Runtime("rnn", dims, tiny_params("rnn"))
+    c0 = next(p for p in rt.ppt if p.name == "cell")
+    c1 = next(p for p in rt.ppt if p.name == "cell.r1")
+    a0, a1 = c0.P["W"].copy(), c0.P["W"] + 2.0
+    c1.P["W"] = a1.copy()
+    rt.sync_snapshot(c0, 1)
+    assert not rt.sync_ready(c0, 1)
+    rt.sync_snapshot(c1, 1)
+    assert rt.sync_ready(c0, 1) and rt.sync_ready(c1, 1)
+    c1.P["W"] = c1.P["W"] + 0.25                       # an update of copy 1 between its snapshot and its load
+    rt.sync_load(c0, 1)
+    rt.sync_load(c1, 1)
+    assert np.allclose(c0.P["W"], (a0 + a1) / 2, rtol=0, atol=1e-15)
+    assert np.allclose(c1.P["W"], (a0 + a1) / 2 + 0.25, rtol=0, atol=1e-15)
+    assert np.array_equal(c0.P["b"], c1.P["b"])        # equal before, equal after
+    look = next(p for p in rt.ppt if p.name == "lookup")
+    assert not rt.sync_ready(look, 1)                  # the tables are a group of their own
+
+
+def test_one_synchronisation_at_the_end_of_the_epoch_is_the_epoch_end_average():
+    dims = dict(TINY["rnn"], node_replicas=3)
+    fp = tiny_params("rnn", scale=1.0)
+    data = tiny_data("rnn", 9)
+    a = amp.Runtime("rnn", dims, fp)
+    b = amp.Runtime("rnn", dims, fp)
+    for rt in (a, b):
+        rt.set_muf(2)
+    a.sync_every = len(data)
+    la, lb = a.run(data, mak=3), b.run(data, mak=3)
+    amp.average_node_replicas(b)
+    assert la == lb
+    for pa, pb in zip(a.ppt, b.ppt):
+        for name in pa.P:
+            assert np.allclose(pa.P[name], pb.P[name], rtol=0, atol=1e-15), (pa.name, name)
+
+
+def test_replay_of_a_run_with_synchronisation_rounds():
+    """The replay driver takes the snapshots and loads where each copy's record has them; a load waits until every
+    copy's snapshot of the round is there, whatever the order of the records; a load without a snapshot is refused."""
+    dims = dict(TINY["rnn"], node_replicas=2)
+    fp = tiny_params("rnn", scale=1.0)
+    data = tiny_data("rnn", 8)
+
+    def fresh():
+        rt = amp.Runtime("rnn", dims, fp)
+        rt.set_muf(3)
+        return rt
+    rec = fresh()
+    rec.sync_every = 3
+    rec.run(data, mak=3)
+    logs = _worker_logs(rec)
+    assert sum(1 for log in logs for e in log if e[1] == "S") == 2 * 4       # two rounds, four replicated nodes
+    for order in (logs, logs[::-1]):
+        rt = fresh().replay(data, order)
+        for p, q in zip(rt.ppt, rec.ppt):
+            for name in p.P:
+                assert np.array_equal(p.P[name], q.P[name]), (p.name, name)
+    # copy 1 of the cell loads later, after one more of its own updates: it keeps that update on top of the mean
+    late = [list(log) for log in logs]
+    w = next(log for log in late if log[0][0] == "cell.r1")
+    i = next(k for k, e in enumerate(w) if e[1] == "L")
+    j = next(k for k in range(i + 1, len(w)) if w[k][1] == "U")
+    w.insert(j, w.pop(i))
+    rt = fresh().replay(data, late)
+    c1, r1 = next(p for p in rt.ppt if p.name == "cell.r1"), next(p for p in rec.ppt if p.name == "cell.r1")
+    assert not np.array_equal(c1.P["W"], r1.P["W"])
+    bad = [[e for e in log if not (e[0] == "cell" and e[1] == "S" and e[2] == 1)] for log in logs]
+    with pytest.raises(RuntimeError):
+        fresh().replay(data, bad)
