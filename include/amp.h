@@ -101,8 +101,10 @@ typedef struct amp_opt_params { float lr, momentum, beta1, beta2, eps; } amp_opt
  * position inside the instance: 0 for the MLP, the time step for the RNN
  * cell and lookup, the tree node for TREE nodes, the propagation step for
  * GGNN edge and GRU nodes.  Worker 0 is the controller: it records A
- * (admitted) and R (retired). */
-enum amp_event_kind { AMP_EV_F = 0, AMP_EV_B = 1, AMP_EV_U = 2, AMP_EV_A = 3, AMP_EV_R = 4 };
+ * (admitted) and R (retired).  A copy of a replicated node also records S
+ * (it published its parameters for synchronisation round `seq`) and L (it
+ * loaded the round's mean): see amp_set_group_sync. */
+enum amp_event_kind { AMP_EV_F = 0, AMP_EV_B = 1, AMP_EV_U = 2, AMP_EV_A = 3, AMP_EV_R = 4, AMP_EV_S = 5, AMP_EV_L = 6 };
 typedef struct amp_event {
   uint16_t worker;
   uint8_t node;
@@ -259,6 +261,24 @@ int amp_set_replicas(amp_ctx *ctx, int n_replicas);
  * most 64.  Does not combine with amp_set_replicas.  Only between the build
  * call and amp_finalize; AMP_EUNSUPPORTED for other models or nodes. */
 int amp_set_node_replicas(amp_ctx *ctx, int node_id, int n_replicas);
+
+/* Asynchronous synchronisation of a replicated node's copies while training
+ * runs (Section 5, last sentence: besides the end-of-epoch averaging, a
+ * message-passing protocol that triggers a synchronisation of the whole
+ * group of replicas).  After every `every_retirements` retired instances the
+ * controller sends a request message to every copy (amp_set_node_replicas);
+ * a copy that takes the request from its ring publishes its parameters as
+ * they stand and carries on with its messages; the copy whose publication
+ * completes the group sends every copy a second message, and a copy that
+ * takes that one moves its parameters to the mean of the published values
+ * (summed in copy order) plus whatever it has learned since it published.  A
+ * new round starts only when every copy has loaded the previous one.  Nothing
+ * waits: rounds still under way when the last instance retires are dropped,
+ * and the end-of-epoch averaging follows as always.  The record lists both
+ * steps (S, L) in the copies' own order, so the checker replays them.
+ * 0 (default) = never.  AMP_EINVAL if negative; without node replicas the
+ * setting has no effect.  Any time after the build call. */
+int amp_set_group_sync(amp_ctx *ctx, int every_retirements);
 
 /* Validates the graph if that has not been done (see amp_validate_graph),
  * places its nodes on workers (Appendix A: a worker hosts one or more IR

@@ -21,7 +21,7 @@ AMP_OK, AMP_EINVAL, AMP_ESTATE, AMP_ENOMEM, AMP_EFULL, AMP_EDEVICE, AMP_EUNSUPPO
 MODEL_MLP, MODEL_RNN, MODEL_TREE, MODEL_GGNN = 1, 2, 3, 4
 ADMIT_GREEDY, ADMIT_BOUNDED = 0, 1
 OPT_SGD, OPT_MOMENTUM, OPT_ADAM = 0, 1, 2
-EV_NAMES = "FBUAR"
+EV_NAMES = "FBUARSL"
 
 _f32p = ct.POINTER(ct.c_float)
 _i32p = ct.POINTER(ct.c_int32)
@@ -82,6 +82,7 @@ SIGNATURES = {
     "amp_set_weights_in_hbm": (ct.c_int, [_ctxp, ct.c_int, ct.c_int]),
     "amp_set_replicas": (ct.c_int, [_ctxp, ct.c_int]),
     "amp_set_node_replicas": (ct.c_int, [_ctxp, ct.c_int, ct.c_int]),
+    "amp_set_group_sync": (ct.c_int, [_ctxp, ct.c_int]),
     "amp_finalize": (ct.c_int, [_ctxp, ct.c_int, ct.c_int, ct.c_int, ct.c_size_t]),
     "amp_set_max_active_keys": (ct.c_int, [_ctxp, ct.c_int]),
     "amp_set_min_update_frequency": (ct.c_int, [_ctxp, ct.c_int, ct.c_int]),
@@ -254,6 +255,9 @@ class Amp:
 
     def set_node_replicas(self, node, n):
         self._chk(self.L.amp_set_node_replicas(self.h, node, n))
+
+    def set_group_sync(self, every_retirements):
+        self._chk(self.L.amp_set_group_sync(self.h, every_retirements))
 
     def set_weights_in_hbm(self, node, on=True):
         self._chk(self.L.amp_set_weights_in_hbm(self.h, node, int(on)))

@@ -86,6 +86,12 @@ __device__ __forceinline__ int poll_batch(const GQ AmpDev* D, const R& r, unsign
     }
     if (n > 0) {
       fence_acquire();
+      // a request to the worker itself (not an instance's message) is taken alone: the run is cut in front of it
+      const unsigned long long mc = __ballot(lane < n && MSG_SLOT(code) == MSG_CTL_SLOT);
+      if (mc) {
+        const int first = __builtin_ctzll(mc);
+        n = first == 0 ? 1 : first;
+      }
       // cut after the room-th backward message
       const bool b = lane < n && is_b(code);
       const unsigned long long mb = __ballot(b);

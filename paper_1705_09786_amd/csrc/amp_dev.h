@@ -33,6 +33,7 @@ AMP_HD static inline int amp_ldrow(int cols) {
 
 // Message code carried by a ring entry: [31] direction, [30:20] slot,
 // [19:0] position inside the instance.
+#define MSG_CTL_SLOT 2047u   // not an instance's slot (those are 0 .. AMP_MAX_MAK - 1): a request to the worker itself
 #define MSG_DIR_B 0x80000000u
 #define MSG_SLOT(c) (((c) >> 20) & 0x7ffu)
 #define MSG_LOCAL(c) ((c) & 0xfffffu)
@@ -78,6 +79,7 @@ struct NodeDev {
   float* G;
   float* M;
   float* V;
+  float* S;   // a replicated node's published parameters during a group synchronisation (Section 5); else null
   int rows, cols, has_bias, muf;
   int opt, mean, nblocks, block;   // rows = nblocks * block (gate blocks)
   float lr, mom, b1, b2, eps;
@@ -170,6 +172,7 @@ struct AmpDev {
   unsigned probe_cap, probe_period;
   int probe_w;
   int node_replicas;          // RNN: copies of the cell between Cond and Phi; admission a goes to copy a mod node_replicas
+  int sync_every;             // ... and a request to synchronise them after every sync_every retirements (0 = never)
   long long watchdog_ticks;
   void* buf[AMP_MAX_BUFS];    // model-specific per-slot storage
   long long stride[AMP_MAX_BUFS];

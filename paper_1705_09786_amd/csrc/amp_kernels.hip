@@ -82,6 +82,12 @@ __device__ __noinline__ void role_ctrl(const GQ AmpDev* D, const GQ WorkerDev* W
     int limit = bounded ? 1 : mak;
     const float per_worker = 1.f / (float)(D->n_updaters > 0 ? D->n_updaters : 1);
     const unsigned n_total = D->n_total;
+    // Synchronisation of a replicated node's copies (Section 5): after every sync_every retirements a request goes to
+    // every copy's ring; a new round waits until every copy has reported that it loaded the previous one.
+    const int NR = D->model == 2 ? D->node_replicas : 1;
+    const unsigned sync_every = NR > 1 ? (unsigned)D->sync_every : 0u;
+    unsigned sync_round = 0, sync_due = 0;
+    int sync_acks = NR;
     const GQ RingDev& mine = D->ring[W->ring];
     D->clock[0] = wall_clock64();
     bool ok = true;
@@ -128,7 +134,9 @@ __device__ __noinline__ void role_ctrl(const GQ AmpDev* D, const GQ WorkerDev* W
       }
       unsigned code;
       ok = ctrl_wait(D, mine, head, code);
-      if (ok) {
+      if (ok && MSG_SLOT(code) == MSG_CTL_SLOT) {
+        sync_acks++;   // a copy has loaded the round's mean
+      } else if (ok) {
         const int s = MSG_SLOT(code);
         log_event(D, W, &s_logn, 0, 4, D->slot_seq[s], 0);
         freelist[nfree++] = s;
@@ -141,6 +149,13 @@ __device__ __noinline__ void role_ctrl(const GQ AmpDev* D, const GQ WorkerDev* W
           else
             limit = limit < mak ? limit + 1 : mak;
         }
+        if (sync_every && retired % sync_every == 0u) sync_due++;
+      }
+      if (sync_due && sync_acks == NR && retired < n_total) {
+        sync_due = 0;   // requests that fell due while a round was under way merge into one
+        sync_acks = 0;
+        sync_round++;
+        for (int r = 0; r < NR; ++r) ring_post(D->ring[r == 0 ? 1 : 2 + r], MSG_MAKE(0, MSG_CTL_SLOT, sync_round << 1));
       }
     }
     D->clock[1] = wall_clock64();

@@ -42,6 +42,7 @@ struct HostNode {
   bool dirty = true;        // host copy newer than device copy
   size_t off_P = 0, off_G = 0, off_M = 0, off_V = 0;
   int base = -1, rep = 0;   // a replica of node `base` (Section 5); -1 = a node of its own
+  size_t off_S = 0;         // a replicated node's published parameters (group synchronisation); 0 = none
   size_t count() const { return (size_t)rows * cols + (has_bias ? rows : 0); }
 };
 
@@ -109,6 +110,7 @@ struct amp_ctx {
   bool state_zeroed = false;
   int replicas = 1, last_replicas = 1;
   int node_replicas = 1;                              // copies of the recurrent cell between Cond and Phi (Section 5)
+  int sync_every = 0;                                 // retirements between two synchronisation requests to them (0 = never)
   size_t rep_stride = 0;                              // bytes from one replica's static region to the next
   std::vector<unsigned> rep_admitted;                 // admissions so far, per replica
   std::vector<std::vector<amp_event>> launch_events;  // per worker, while a training call runs
@@ -567,6 +569,14 @@ int amp_set_node_replicas(amp_ctx* c, int node_id, int n_replicas) {
   return AMP_OK;
 }
 
+int amp_set_group_sync(amp_ctx* c, int every_retirements) {
+  if (!c) return AMP_EINVAL;
+  if (!c->model) return fail(c, AMP_ESTATE, "set_group_sync: build a model first");
+  if (every_retirements < 0) return fail(c, AMP_EINVAL, "set_group_sync: the interval must be >= 0");
+  c->sync_every = every_retirements;
+  return AMP_OK;
+}
+
 int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_edges, size_t max_instances) {
   if (!c) return AMP_EINVAL;
   if (c->finalized) return fail(c, AMP_ESTATE, "finalize: already finalized");
@@ -706,6 +716,17 @@ int amp_finalize(amp_ctx* c, int max_active_keys, int max_instance_len, int max_
     n.off_G = take(b);
     n.off_M = take(b);
     n.off_V = take(b);
+  }
+  // what the copies of a replicated node publish for a synchronisation round, laid out like their parameters
+  for (size_t i = 0; i < c->nodes.size(); ++i) {
+    c->nodes[i].off_S = c->nodes[i].base < 0 ? 0 : c->nodes[i].off_S;
+    bool copied = false;
+    for (const HostNode& n : c->nodes) copied = copied || n.base == (int)i;
+    if (c->nodes[i].base < 0 && copied) {
+      c->nodes[i].off_S = take(c->nodes[i].count() * 4);
+      for (HostNode& n : c->nodes)
+        if (n.base == (int)i) n.off_S = take(n.count() * 4);
+    }
   }
   for (HostWorker& w : c->workers) {
     w.off_state = take(64);
@@ -1297,6 +1318,7 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
       nd.G = (float*)rep_ptr(c, r, n.off_G);
       nd.M = (float*)rep_ptr(c, r, n.off_M);
       nd.V = (float*)rep_ptr(c, r, n.off_V);
+      nd.S = n.off_S ? (float*)rep_ptr(c, r, n.off_S) : nullptr;
       nd.rows = n.rows;
       nd.cols = n.cols;
       nd.has_bias = n.has_bias;
@@ -1365,6 +1387,7 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
     }
     D.admit_bounded = train ? c->admit_bounded : 0;
     D.node_replicas = c->node_replicas;
+    D.sync_every = train && c->node_replicas > 1 ? c->sync_every : 0;
     D.max_staleness = (float)c->max_staleness;
     D.n_updaters = (int)wpr - 1;   // every worker but the controller applies updates
     D.n_total = (unsigned)n_total[r];

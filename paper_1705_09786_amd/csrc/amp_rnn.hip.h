@@ -99,6 +99,65 @@ __device__ __noinline__ void role_rnn_cell(const GQ AmpDev* D, const GQ WorkerDe
     const int room_c = nd_muf - (int)count, room_l = lk_muf - (int)lcount;
     const int n = wait_batch(D, mine, head, KB, room_c < room_l ? room_c : room_l, s_codes, &s_n, code_is_b);
     if (n == 0) break;
+    if (MSG_SLOT(uni(s_codes[0])) == MSG_CTL_SLOT) {
+      // A request to this copy itself (always alone in its batch): a synchronisation round of the cell's copies
+      // (Section 5).  First message of a round: publish the parameters as they stand -- the cell's from LDS, the
+      // table's from HBM -- and arrive at the round's counter; the arrival that completes the group sends every copy
+      // the second message.  Second message: every copy's publication is there; move to their mean (summed in copy
+      // order) and keep what was learned since the own publication; tell the controller.
+      const unsigned rl = MSG_LOCAL(uni(s_codes[0])), rnd = rl >> 1;
+      const int NR = uni(D->node_replicas), rep = uni(W->rep);
+      GQ float* cS0 = uni_gq<float>(D->node[1].S);
+      GQ float* lS0 = uni_gq<float>(D->node[0].S);
+      const long long cstr = NR > 1 ? uni_gq<float>(D->node[4].S) - cS0 : 0, lstr = NR > 1 ? uni_gq<float>(D->node[3].S) - lS0 : 0;
+      GQ float* cS = cS0 + rep * cstr;
+      GQ float* lS = lS0 + rep * lstr;
+      const int nW = R * t.C;
+      if (!(rl & 1u)) {
+        for (int i = threadIdx.x; i < nW; i += AMP_THREADS) {
+          const int lr = i / t.C, c = i - lr * t.C;
+          cS[(long long)t.grow(lr) * t.C + c] = Wl[lr * t.ldw + t.lcol(c)];
+        }
+        if (nd.has_bias)
+          for (int lr = threadIdx.x; lr < R; lr += AMP_THREADS) cS[(long long)nd.rows * t.C + t.grow(lr)] = bl[lr];
+        for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) lS[i] = lkP[i];
+        LOG(nl, 5, rnd, 0);
+        LOG(nc, 5, rnd, 0);
+        publish_barrier();
+        if (threadIdx.x == 0) {
+          fence_release();
+          if (join_arrive((GQ int*)&D->ctl[6], NR))
+            for (int q = 0; q < NR; ++q) ring_post(D->ring[q == 0 ? 1 : 2 + q], MSG_MAKE(0, MSG_CTL_SLOT, (rnd << 1) | 1u));
+        }
+      } else {
+        const float inv = 1.f / (float)NR;
+        for (int i = threadIdx.x; i < nW; i += AMP_THREADS) {
+          const int lr = i / t.C, c = i - lr * t.C;
+          const long long gi = (long long)t.grow(lr) * t.C + c;
+          float m = 0.f;
+          for (int q = 0; q < NR; ++q) m += cS0[q * cstr + gi];
+          LDSQ float* w = Wl + lr * t.ldw + t.lcol(c);
+          *w = m * inv + (*w - cS[gi]);
+        }
+        if (nd.has_bias)
+          for (int lr = threadIdx.x; lr < R; lr += AMP_THREADS) {
+            const long long gi = (long long)nd.rows * t.C + t.grow(lr);
+            float m = 0.f;
+            for (int q = 0; q < NR; ++q) m += cS0[q * cstr + gi];
+            bl[lr] = m * inv + (bl[lr] - cS[gi]);
+          }
+        for (int i = threadIdx.x; i < V * E; i += AMP_THREADS) {
+          float m = 0.f;
+          for (int q = 0; q < NR; ++q) m += lS0[q * lstr + i];
+          lkP[i] = m * inv + (lkP[i] - lS[i]);
+        }
+        LOG(nl, 6, rnd, 0);
+        LOG(nc, 6, rnd, 0);
+        if (threadIdx.x == 0) ring_post(ctl, MSG_MAKE(1, MSG_CTL_SLOT, rnd));
+      }
+      __syncthreads();
+      continue;
+    }
     if (threadIdx.x < 64) {
       const int k = threadIdx.x;
       const bool in = k < n;

@@ -334,6 +334,7 @@ def test_node_replicas_on_the_host():
     rnn = dict(vocab=6, emb=3, hidden=4, n_class=3)
     a = new_ctx()
     expect(B.AMP_ESTATE, a.set_node_replicas, 1, 2)                    # before build
+    expect(B.AMP_ESTATE, a.set_group_sync, 10)
     a.build("mlp", dict(d_in=5, hidden=4, n_class=3))
     expect(B.AMP_EUNSUPPORTED, a.set_node_replicas, 1, 2)              # another model
     a.close()
@@ -346,6 +347,8 @@ def test_node_replicas_on_the_host():
     assert a.num_nodes() == 7
     a.set_node_replicas(1, 2)                                          # asked again: replaces the earlier copies
     assert a.num_nodes() == 5
+    expect(B.AMP_EINVAL, a.set_group_sync, -1)
+    a.set_group_sync(50)                                               # a synchronisation request every 50 retirements
     a.set_replicas(2)
     expect(B.AMP_EUNSUPPORTED, a.finalize, 4, 5, 0, 10)                # both kinds of replica at once
     a.set_replicas(1)

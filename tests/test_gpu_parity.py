@@ -519,15 +519,19 @@ def test_replicas_replay_parity(cfg, dims, R, mak, muf, lmuf, opt, n):
             done[r] += len(parts[r])
 
 
-@pytest.mark.parametrize("R,mak,muf,opt,n", [(2, 8, 5, SGD, 160), (3, 16, 7, RNN_ADAM, 240)])
-def test_rnn_replicated_cell_replay_parity(R, mak, muf, opt, n):
+@pytest.mark.parametrize("R,mak,muf,opt,n,sync", [(2, 8, 5, SGD, 160, 0), (3, 16, 7, RNN_ADAM, 240, 0),
+                                                   (2, 8, 5, SGD, 160, 25), (3, 16, 3, SGD, 240, 16)])
+def test_rnn_replicated_cell_replay_parity(R, mak, muf, opt, n, sync):
     """The RNN's heavy node alone replicated (Section 5): R copies of the cell between a Cond and a Phi that route
     on the instance, the output layer and the loss shared, the copies averaged at the end of each epoch.  Two
     epochs as two training calls: the checker replays every worker's record (the copies are nodes of their own in
-    it), averages its copies, and must agree with the GPU on all parameters and losses."""
+    it), averages its copies, and must agree with the GPU on all parameters and losses.  With sync > 0 the
+    controller also requests a synchronisation of the copies after every `sync` retirements while training runs
+    (the paper's message-passing trigger of a whole-group synchronisation): the copies' records then hold the
+    publish and load steps of every round, which the checker replays where they stand."""
     model, dims, data = synth.workload(2, n=n)
     fp = synth.init_params(model, dims, 13)
-    g = gpu_train(model, dims, fp, data, mak, muf, opt, lookup_muf=muf, node_replicas={1: R})
+    g = gpu_train(model, dims, fp, data, mak, muf, opt, lookup_muf=muf, node_replicas={1: R}, group_sync=sync)
     tr = g["trainer"]
     a = tr.amp
     assert a.num_workers() == 3 + (R - 1) and a.num_nodes() == 3 + 2 * (R - 1)
@@ -548,6 +552,14 @@ def test_rnn_replicated_cell_replay_parity(R, mak, muf, opt, n):
                 if k in ("F", "B") and name != "out":
                     assert s % R == (int(name.split(".r")[1]) if ".r" in name else 0), (name, k, s)
         assert sum(1 for w in wl if w) == 1 + R    # every copy worked
+        rounds = [sorted(s for name, k, s, l in w if k == "S" and name.startswith("cell")) for w in wl if w and w[0][0] != "out"]
+        if sync:
+            # rounds are numbered from 1 in every training call, every copy publishes in every round it takes part
+            # in, and at least half the requests that fell due were carried out (a round waits for the previous one)
+            assert all(r == list(range(1, len(r) + 1)) for r in rounds) and min(len(r) for r in rounds) >= (n // sync) // 2
+            rt.snapshots.clear()
+        else:
+            assert not any(rounds)
         rt.replay(data, wl, first_seq=first)
         oamp.average_node_replicas(rt)
         params = tr.params()

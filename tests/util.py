@@ -33,7 +33,7 @@ def f32(x):
 
 def gpu_train(model, dims, fp, data, mak, muf, opt, epochs=1, log=True, tiles=None, watchdog=5.0,
               arena_bytes=1 << 30, lookup_muf=None, in_hbm=(), replicas=1, max_staleness=None, strict=False, graph=None,
-              node_replicas=None):
+              node_replicas=None, group_sync=0):
     ml, me = runner.max_len_of(model, data)
     tr = runner.Trainer(model, dims, fp, mak, ml, me, len(data), arena_bytes=arena_bytes, tiles=tiles, in_hbm=in_hbm,
                         replicas=replicas, strict=strict, graph=graph, node_replicas=node_replicas)
@@ -41,6 +41,8 @@ def gpu_train(model, dims, fp, data, mak, muf, opt, epochs=1, log=True, tiles=No
     a.set_watchdog(watchdog)
     if max_staleness is not None:
         a.set_admission(B.ADMIT_BOUNDED, max_staleness)
+    if group_sync:
+        a.set_group_sync(group_sync)
     a.set_min_update_frequency(-1, muf)
     if lookup_muf is not None:
         a.set_min_update_frequency(0, lookup_muf)
