@@ -98,6 +98,42 @@ def test_rnn_best_accuracy_matches_checker_own_schedule():
     assert abs(max(acc_gpu) - max(acc_ref)) <= 0.005, (acc_gpu, acc_ref)
 
 
+def test_rnn_with_copies_of_the_cell_matches_checker_own_schedule():
+    """The same comparison with the heavy node replicated (Section 5): two copies of the cell behind a Cond and a
+    Phi, a synchronisation round of the copies every 500 retirements while training runs, and their average at the
+    end of every epoch -- on the HIP path and in the checker, each on its own schedule."""
+    dims = dict(vocab=20, emb=48, hidden=48, n_class=10)
+    train = synth.make_rnn(4000, 61, dims, min_len=2, max_len=10, reduction="max")
+    valid = synth.make_rnn(4000, 1061, dims, min_len=2, max_len=10, reduction="max")
+    fp = synth.init_params("rnn", dims, 44)
+    R, mak, muf, lr, epochs, sync = 2, 8, 16, 0.001, 10, 500
+    ml, me = runner.max_len_of("rnn", train + valid)
+    tr = runner.Trainer("rnn", dims, fp, mak, ml, me, len(train), node_replicas={1: R})
+    a = tr.amp
+    a.set_watchdog(10.0)
+    a.set_min_update_frequency(-1, muf)
+    a.set_optimizer(-1, OPT_KIND["adam"], lr=lr)
+    a.set_group_sync(sync)
+    tr.submit_all(train)
+    tr.submit_all(valid, which=1)
+    acc_gpu = []
+    for _ in range(epochs):
+        a.train(1)
+        acc_gpu.append(a.eval()["accuracy"])
+    rt = oracle_trainer("rnn", dict(dims, node_replicas=R), fp, muf, lr, "adam")
+    rt.sync_every = sync
+    acc_ref = []
+    for e in range(epochs):
+        rt.run(train, mak=mak, epochs=1, first_seq=e * len(train))
+        oamp.average_node_replicas(rt)
+        P = direct.unpack("rnn", dims, [oamp.C.pack_node(n.P) for n in rt.ppt[:3]])
+        acc_ref.append(direct.evaluate("rnn", dims, P, valid)[1])
+    print("rnn, 2 copies of the cell: accuracy per epoch, HIP path %s, checker %s" % (np.round(acc_gpu, 4), np.round(acc_ref, 4)))
+    assert max(acc_ref) >= 0.97, "the reference run itself did not learn"
+    assert abs(max(acc_gpu) - max(acc_ref)) <= 0.005, (acc_gpu, acc_ref)
+    tr.close()
+
+
 def test_ggnn_validation_error_matches_checker_own_schedule():
     dims = dict(n_node_types=16, hidden=24, n_edge_types=4, n_steps=4)
     train, norm = synth.make_ggnn(1000, 71, dims, min_nodes=4, max_nodes=14)
