@@ -6,6 +6,12 @@ training rate.
 
     python -m paper_1705_09786_amd.sweep [--replicas 8] [--max-epochs 40] [--out sweep.json]
                                          [--admission bounded --max-staleness 8] [--maks 32,64] [--mufs 1,4]
+                                         [--copies 8 [--group-sync 500]]
+
+`--replicas R` replicates the whole pipeline (every node R times, max_active_keys per replica); `--copies R`
+replicates the recurrent cell alone between a Cond and a Phi, as Section 5 does, with the output layer shared
+and max_active_keys counting all instances in flight; `--group-sync k` adds a synchronisation round of the
+copies after every k retirements.
 
 With `--admission bounded` the controller keeps the number of instances in
 flight below max_active_keys whenever they would see more than
@@ -30,10 +36,13 @@ MAKS = (1, 2, 4, 8, 16, 32, 64)
 MUFS = (1, 4, 16, 64, 256)
 
 
-def run_one(data, valid, dims, fp, replicas, mak, muf, lr, max_epochs, bounded=None):
+def run_one(data, valid, dims, fp, replicas, mak, muf, lr, max_epochs, bounded=None, copies=0, group_sync=0):
     ml, _ = runner.max_len_of("rnn", data + valid)
-    tr = runner.Trainer("rnn", dims, fp, mak, ml, 0, len(data), arena_bytes=2 << 30, replicas=replicas)
+    tr = runner.Trainer("rnn", dims, fp, mak, ml, 0, len(data), arena_bytes=2 << 30, replicas=1 if copies else replicas,
+                        node_replicas={1: copies} if copies else None)
     a = tr.amp
+    if group_sync:
+        a.set_group_sync(group_sync)
     a.set_min_update_frequency(-1, muf)
     a.set_optimizer(-1, B.OPT_ADAM, lr=lr)
     if bounded is not None:
@@ -59,6 +68,8 @@ def run_one(data, valid, dims, fp, replicas, mak, muf, lr, max_epochs, bounded=N
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
     ap.add_argument("--replicas", type=int, default=8)
+    ap.add_argument("--copies", type=int, default=0, help="copies of the recurrent cell alone instead of whole replicas")
+    ap.add_argument("--group-sync", type=int, default=0, help="with --copies: a synchronisation round every this many retirements")
     ap.add_argument("--max-epochs", type=int, default=40)
     ap.add_argument("--lr", type=float, default=0.001)
     ap.add_argument("--instances", type=int, default=10000)
@@ -78,12 +89,14 @@ def main(argv=None):
     bounded = args.max_staleness if args.admission == "bounded" else None
     for mak in maks:
         for muf in mufs:
-            r = run_one(data, valid, dims, fp, args.replicas, mak, muf, args.lr, args.max_epochs, bounded)
+            r = run_one(data, valid, dims, fp, args.replicas, mak, muf, args.lr, args.max_epochs, bounded, args.copies,
+                        args.group_sync)
             rows.append(r)
             print(json.dumps(r), flush=True)
     if args.out:
         with open(args.out, "w") as f:
-            json.dump(dict(replicas=args.replicas, target_accuracy=TARGET, lr=args.lr, admission=args.admission,
+            json.dump(dict(replicas=args.replicas, copies=args.copies, group_sync=args.group_sync, target_accuracy=TARGET,
+                           lr=args.lr, admission=args.admission,
                            max_staleness=bounded, rows=rows), f, indent=1)
     return 0
 
