@@ -37,9 +37,11 @@ DEFAULTS = {
     # cfg: mak, muf, lookup muf, optimizer
     1: dict(mak=4, muf=1, lmuf=None, opt=("sgd", dict(lr=0.05))),
     2: dict(mak=16, muf=16, lmuf=16, opt=("sgd", dict(lr=0.05))),
-    # 8 leaf + 16 branch tiles: the single model's best rate (37k trees/s on 27 workgroups); the fewest tiles that
-    # fit LDS (5 + 8, 16 workgroups, 30k trees/s) use each CU better and are what the replicated run packs two per XCD
-    3: dict(mak=64, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.05)), tiles={1: 8, 2: 16}, replica_tiles={1: 5, 2: 8},
+    # 10 leaf + 17 branch tiles: the single model's best rate (39.5k trees/s on 30 workgroups): 15 leaf and 9 or 8
+    # branch units per tile are 45 and 45 or 40 rows, three 16-row blocks almost full, where 8 + 16 tiles (57 and 50
+    # rows, 37k trees/s) pad to four; the fewest tiles that fit LDS (5 + 8, 16 workgroups, 30k trees/s) use each CU
+    # better and are what the replicated run packs two per XCD
+    3: dict(mak=64, muf=50, lmuf=1000, opt=("sgd", dict(lr=0.05)), tiles={1: 10, 2: 17}, replica_tiles={1: 5, 2: 8},
             replica_workers=16),
     # the commonest edge type's linear split over four workgroups, the two GRU gates over two each, the candidate over
     # three (17 workgroups): 21.7k graphs/s against 12.7k unsplit and 18.7k with that linear over two; more tiles of

@@ -136,7 +136,7 @@ class Progress:
 
 
 def test_full_size_per_event_parity_tree(capsys):
-    """The benchmark's Tree-LSTM run itself -- 8,544 trees, its learning rate, 64 instances in flight, 8 + 16 tiles,
+    """The benchmark's Tree-LSTM run itself -- 8,544 trees, its learning rate, 64 instances in flight, the benchmark's tiles,
     about 5,000 updates per cell -- against the checker's replay of its event record.  After that many asynchronous
     updates rounding differences may have compounded in the parameters, so what single events emit is compared as
     well: for every 64th instance the kernel keeps each node's forward output (h) and each leaf's backward

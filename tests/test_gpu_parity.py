@@ -159,7 +159,8 @@ TREE_ODD = dict(vocab=97, emb=50, hidden=37, n_class=5)
     (TREE_SMALLVOCAB, None, 1, 1, 1, SGD, 16),
     (synth.DEFAULT_DIMS["tree"], None, 16, 50, 1000, SGD, 96),
     (synth.DEFAULT_DIMS["tree"], None, 64, 7, 333, ADAM, 96),
-    (synth.DEFAULT_DIMS["tree"], {1: 8, 2: 16}, 32, 50, 1000, SGD, 96),   # the benchmark's tiling: tiles of 4 and 3 row blocks
+    (synth.DEFAULT_DIMS["tree"], {1: 8, 2: 16}, 32, 50, 1000, SGD, 96),   # tiles of 4 and 3 row blocks
+    (synth.DEFAULT_DIMS["tree"], {1: 10, 2: 17}, 64, 50, 1000, SGD, 96),  # the benchmark's tiling: 3 row blocks, 45 of 48 rows used
     (TREE_ODD, {1: 3, 2: 5}, 8, 3, 5, SGD, 64),
     (TREE_ODD, {1: 1, 2: 1}, 8, 3, 5, ADAM, 64),
     (TREE_ODD, {1: 2, 2: 3}, 8, 4, 5, dict(kind="momentum", lr=0.005, momentum=0.9), 64),
