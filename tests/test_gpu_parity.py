@@ -328,10 +328,10 @@ GG_ODD = dict(n_node_types=5, hidden=37, n_edge_types=3, n_steps=3)
 
 # The graph model under Adam at lr = 0.002 trains at the edge of stability: repeated runs (each with its own
 # event order) put the worst per-graph loss between 2e-6 and 4e-5 off the checker while the parameters agree to
-# 1e-6, whatever eps is.  At lr = 5e-4 the worst loss difference of a run is 2e-7 .. 1e-6 in 118 of 120 runs
-# measured (60 with each build of the join), but two runs, one with either build, reached 6e-6 and 1.3e-5: each
-# run has its own event order, and a few orders amplify the rounding differences far more than the typical one.
-# The case therefore runs at lr = 2e-4, which leaves that tail a margin under 1e-5.
+# 1e-6, whatever eps is.  At lr = 5e-4 the outcome depends on the schedule the workers happen to follow: when every
+# worker took one message at a time, 118 of 120 runs (60 with each build of the join) stayed within 1.3e-6 and two
+# reached 6e-6 and 1.3e-5; with several messages per pass the median run of 200 is 1.4e-5 off in its worst graph.
+# At lr = 2e-4 thirty runs, each with its own event order, all stayed within 4e-7: the case runs there.
 G_ADAM = dict(ADAM, lr=0.0002)
 
 
