@@ -335,7 +335,8 @@ GG_ODD = dict(n_node_types=5, hidden=37, n_edge_types=3, n_steps=3)
 G_ADAM = dict(ADAM, lr=0.0002)
 
 
-@pytest.mark.parametrize("mak,muf,opt,n", [(1, 1, dict(kind="sgd", lr=0.01), 40), (32, 20, G_ADAM, 300), (8, 3, MOM, 150)])
+@pytest.mark.parametrize("mak,muf,opt,n", [(1, 1, dict(kind="sgd", lr=0.01), 40), (32, 20, G_ADAM, 300), (8, 3, MOM, 150),
+                                           (64, 5, dict(kind="sgd", lr=0.01), 256)])   # long queues: passes of four messages
 def test_ggnn_replay_parity(mak, muf, opt, n):
     model, dims, data = synth.workload(4, n=n)
     fp = synth.init_params(model, dims, 9)
@@ -528,7 +529,9 @@ def test_replicas_replay_parity(cfg, dims, R, mak, muf, lmuf, opt, n):
 
 
 @pytest.mark.parametrize("R,mak,muf,opt,n,sync", [(2, 8, 5, SGD, 160, 0), (3, 16, 7, RNN_ADAM, 240, 0),
-                                                   (2, 8, 5, SGD, 160, 25), (3, 16, 3, SGD, 240, 16)])
+                                                   (2, 8, 5, SGD, 160, 25), (3, 16, 3, SGD, 240, 16),
+                                                   # the benchmark's `cell_copies` launch: eight copies, 64 in flight
+                                                   (8, 64, 16, SGD, 480, 0), (8, 64, 4, SGD, 480, 60)])
 def test_rnn_replicated_cell_replay_parity(R, mak, muf, opt, n, sync):
     """The RNN's heavy node alone replicated (Section 5): R copies of the cell between a Cond and a Phi that route
     on the instance, the output layer and the loss shared, the copies averaged at the end of each epoch.  Two
