@@ -233,6 +233,7 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
       const int kb_top = w.role == ROLE_RNN_CELL ? std::min(64, amp_round16(c->max_mak)) : 64;
       for (w.kb = kb_top; w.kb >= 16; w.kb -= 16) {
         f = wfl + r4((size_t)w.kb * ldy) + r4(Rp) + (size_t)(amp_round16(n.cl()) + 63) / 64 * 64;
+        if (w.role != ROLE_RNN_CELL) f += r4((size_t)w.kb * ldy);   // the tree cells keep the deltas in rows of their own
         if (f <= avail) break;
       }
       if (w.kb < 16) return 0;

@@ -1037,6 +1037,10 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
   LDSQ float* bl = (LDSQ float*)bg;
   const int yfloats = KB * ldy;
   LDSQ float* Y = (LDSQ float*)L.take(yfloats);   // forward: pre-activations; backward: deltas
+  // LDS-resident weights: the deltas have rows of their own, so that waves without a share of the forward product
+  // can form them while the others are at it
+  constexpr bool SIDE = !STREAM;
+  LDSQ float* Yd = SIDE ? (LDSQ float*)L.take(yfloats) : Y;
   // node row of a tile row / node column of an LDS column (-1 = padding)
   const int CMW = STREAM ? 0 : ((amp_round16(t.Cl) + 63) >> 6) << 6;
   LDSQ int* rowmap = (LDSQ int*)L.take(t.Rp);
@@ -1053,6 +1057,8 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
     tile_load(nd, t, Wg, bg);
   }
   for (int i = threadIdx.x; i < yfloats; i += AMP_THREADS) Y[i] = 0.f;
+  if (SIDE)
+    for (int i = threadIdx.x; i < yfloats; i += AMP_THREADS) Yd[i] = 0.f;
   for (int i = threadIdx.x; i < t.Rp; i += AMP_THREADS) rowmap[i] = i < R ? t.grow(i) : -1;
   for (int i = threadIdx.x; i < CMW; i += AMP_THREADS) colmap[i] = t.ncol(i);
   __syncthreads();
@@ -1106,6 +1112,74 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
     if (n == 0) break;
     head += n;
     const int nF = M.nF, nB = M.nB;
+    // The deltas of the batch's backward messages (tile order [gate][unit], zero beyond R) into Yd, pair i =
+    // (message, unit) by thread first + j * stride.
+    auto form_deltas = [&](int first, int stride) {
+      for (int i = first; i < nB * (ldy - R); i += stride) {
+        const int k = i / (ldy - R), r = R + i - k * (ldy - R);
+        Yd[k * ldy + r] = 0.f;
+      }
+      for (int i = first; i < nB * nu; i += stride) {
+        const int k = i / nu, j = i - k * nu, m = M.bidx[k], u = u0 + j;
+        const long long nn = B.node(M.s[m], M.n[m]);
+        const GQ float* gt = B.gate + nn * 6 * H;
+        float dh = B.gout[nn * H + u], dc = 0.f;
+        if (M.par[m] >= 0) {
+          const GQ float* gp = B.gpar + nn * B.TB * Hp + u;
+          float p = 0.f;
+          int q = 0;
+          for (; q + 15 < B.TB; q += 16) {   // sixteen parts in flight at a time, added in tile order
+            float pp[16];
+#pragma unroll
+            for (int a = 0; a < 16; ++a) pp[a] = gp[(q + a) * Hp];
+#pragma unroll
+            for (int a = 0; a < 16; ++a) p += pp[a];
+          }
+          for (; q + 3 < B.TB; q += 4) {
+            const float p0 = gp[q * Hp], p1 = gp[(q + 1) * Hp], p2 = gp[(q + 2) * Hp], p3 = gp[(q + 3) * Hp];
+            p = (((p + p0) + p1) + p2) + p3;
+          }
+          for (; q < B.TB; ++q) p += gp[q * Hp];
+          dh += p;
+          dc = B.gc[nn * H + u];
+        }
+        const float i_ = gt[u], o_ = gt[3 * H + u], g_ = gt[4 * H + u], tc = gt[5 * H + u];
+        const float dct = dc + dh * o_ * (1.f - tc * tc);
+        const float d_o = dh * tc * o_ * (1.f - o_);
+        const float d_i = dct * g_ * i_ * (1.f - i_);
+        const float d_g = dct * i_ * (1.f - g_ * g_);
+        LDSQ float* ds = Yd + k * ldy;
+        if (BR) {
+          const long long na = B.node(M.s[m], M.a[m]), nb = B.node(M.s[m], M.b[m]);
+          const float fl = gt[H + u], fr = gt[2 * H + u];
+          ds[j] = d_i;
+          ds[nu + j] = dct * xbase[M.off0[m] + Hp + u] * fl * (1.f - fl);
+          ds[2 * nu + j] = dct * xbase[M.off1[m] + Hp + u] * fr * (1.f - fr);
+          ds[3 * nu + j] = d_o;
+          ds[4 * nu + j] = d_g;
+          B.gc[na * H + u] = dct * fl;
+          B.gc[nb * H + u] = dct * fr;
+        } else {
+          ds[j] = d_i;
+          ds[nu + j] = d_o;
+          ds[2 * nu + j] = d_g;
+        }
+      }
+    };
+    // Waves without a share of the forward product (tree_fwd_mfma: a 16-message block is shared by 8, 4 or 2 waves,
+    // each taking every wpn-th 16-row block) form the deltas meanwhile.
+    int n_side = 0, side_rank = -1;
+    if (SIDE && nF > 0 && nB > 0) {
+      const TreeShape<NRBT, NCGT> sh(t);
+      const int NBF = (nF + 15) >> 4, wpn = NBF == 1 ? 8 : NBF == 2 ? 4 : 2, me = uni((int)(threadIdx.x >> 6));
+      for (int w = 0; w < AMP_THREADS / 64; ++w) {
+        const int nbw = w / wpn, subw = (w - nbw * wpn + (wpn >> 1) * (nbw & 1)) % wpn;
+        if (!(nbw < NBF && subw < sh.NRB)) {
+          if (w == me) side_rank = n_side;
+          ++n_side;
+        }
+      }
+    }
     PHASE(0);
     // ---------------- forward messages of the batch
     if (nF > 0) {
@@ -1117,6 +1191,7 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
         pcr = xbase[M.off1[m] + Hp + u];
         asm volatile("" ::: "memory");
       }
+      if (side_rank >= 0) form_deltas(side_rank * 64 + (int)(threadIdx.x & 63), n_side * 64);
       if (STREAM)
         tree_fwd_stream<BR>(ndP, rowoff, t, bl, xbase, M, nF, Y, ldy, Xs);
       else
@@ -1162,9 +1237,12 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
     }
     // ---------------- backward messages of the batch
     if (nB > 0) {
+      if (n_side == 0) form_deltas((int)threadIdx.x, AMP_THREADS);
+      lds_barrier();
+      PHASE(3);
       // The (delta, input) pairs join the pending gradients: entry = [delta (Rp) | input in LDS column layout (Cp)].
       // The input part depends on nothing computed here: its first four 16-byte groups per thread are fetched now,
-      // so that they travel while the deltas are formed, and stored afterwards.
+      // travel while the delta parts are stored and the product is formed, and are stored afterwards.
       const int perx = pd.Cp >> 2, totalx = nB * perx;
       v4f xv[4];
       GQ float* xd[4];
@@ -1178,84 +1256,41 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
         xd[a] = idx < totalx ? pend + (long long)(count + k) * pd.stride + pd.Rp + lc : nullptr;
         xv[a] = *(const GQ v4f*)(xbase + (xin[a] ? ((BR && lc >= t.segp) ? M.off1[m] + lc - t.segp : M.off0[m] + lc) : M.off0[m]));
       }
-      asm volatile("" ::: "memory");   // the fetches are issued before the loads below
-      // delta rows (tile order [gate][unit], zero beyond R) into Y
-      for (int i = threadIdx.x; i < nB * (ldy - R); i += AMP_THREADS) {
-        const int k = i / (ldy - R), r = R + i - k * (ldy - R);
-        Y[k * ldy + r] = 0.f;
-      }
-      for (int i = threadIdx.x; i < nB * nu; i += AMP_THREADS) {
-        const int k = i / nu, j = i - k * nu, m = M.bidx[k], u = u0 + j;
-        const long long nn = B.node(M.s[m], M.n[m]);
-        const GQ float* gt = B.gate + nn * 6 * H;
-        float dh = B.gout[nn * H + u], dc = 0.f;
-        if (M.par[m] >= 0) {
-          const GQ float* gp = B.gpar + nn * B.TB * Hp + u;
-          float p = 0.f;
-          int q = 0;
-          for (; q + 15 < B.TB; q += 16) {   // sixteen parts in flight at a time, added in tile order
-            float pp[16];
-#pragma unroll
-            for (int a = 0; a < 16; ++a) pp[a] = gp[(q + a) * Hp];
-#pragma unroll
-            for (int a = 0; a < 16; ++a) p += pp[a];
-          }
-          for (; q + 3 < B.TB; q += 4) {
-            const float p0 = gp[q * Hp], p1 = gp[(q + 1) * Hp], p2 = gp[(q + 2) * Hp], p3 = gp[(q + 3) * Hp];
-            p = (((p + p0) + p1) + p2) + p3;
-          }
-          for (; q < B.TB; ++q) p += gp[q * Hp];
-          dh += p;
-          dc = B.gc[nn * H + u];
-        }
-        const float i_ = gt[u], o_ = gt[3 * H + u], g_ = gt[4 * H + u], tc = gt[5 * H + u];
-        const float dct = dc + dh * o_ * (1.f - tc * tc);
-        const float d_o = dh * tc * o_ * (1.f - o_);
-        const float d_i = dct * g_ * i_ * (1.f - i_);
-        const float d_g = dct * i_ * (1.f - g_ * g_);
-        LDSQ float* ds = Y + k * ldy;
-        if (BR) {
-          const long long na = B.node(M.s[m], M.a[m]), nb = B.node(M.s[m], M.b[m]);
-          const float fl = gt[H + u], fr = gt[2 * H + u];
-          ds[j] = d_i;
-          ds[nu + j] = dct * xbase[M.off0[m] + Hp + u] * fl * (1.f - fl);
-          ds[2 * nu + j] = dct * xbase[M.off1[m] + Hp + u] * fr * (1.f - fr);
-          ds[3 * nu + j] = d_o;
-          ds[4 * nu + j] = d_g;
-          B.gc[na * H + u] = dct * fl;
-          B.gc[nb * H + u] = dct * fr;
-        } else {
-          ds[j] = d_i;
-          ds[nu + j] = d_o;
-          ds[2 * nu + j] = d_g;
+      asm volatile("" ::: "memory");   // the fetches are issued before the stores below
+      {
+        const int perd = pd.Rp >> 2, totald = nB * perd;
+        for (int idx = threadIdx.x; idx < totald; idx += AMP_THREADS) {
+          const int k = idx / perd, j = (idx - k * perd) << 2;
+          *(GQ v4f*)(pend + (long long)(count + k) * pd.stride + j) = *(const LDSQ v4f*)(Yd + k * ldy + j);   // ldy >= Rp, zero beyond R
         }
       }
-      lds_barrier();
-      PHASE(3);
+      if ((int)threadIdx.x < R) {
+        // the reads of eight messages' deltas are issued together; the sum keeps the messages' order
+        int k = 0;
+        for (; k + 7 < nB; k += 8) {
+          float y[8];
+#pragma unroll
+          for (int a = 0; a < 8; ++a) y[a] = Yd[(k + a) * ldy + threadIdx.x];
+#pragma unroll
+          for (int a = 0; a < 8; ++a) accb += y[a];
+        }
+        for (; k < nB; ++k) accb += Yd[k * ldy + threadIdx.x];
+      }
+      PHASE(4);
+      if (STREAM)
+        tree_bwd_stream<BR>(ndP, rowoff, t, Yd, ldy, M, nB, obase);
+      else
+        tree_bwd_mfma<BR, NRBT, NCGT>(Wl, t, Yd, M, nB, obase);
 #pragma unroll
       for (int a = 0; a < 4; ++a)
         if (xd[a]) *(GQ v4f*)xd[a] = xin[a] ? xv[a] : (v4f){0.f, 0.f, 0.f, 0.f};
-      // the rest of the input parts (batches of more than 4 x 512 groups), then the delta parts from LDS
+      // the rest of the input parts (batches of more than 4 x 512 groups)
       for (int idx = threadIdx.x + 4 * AMP_THREADS; idx < totalx; idx += AMP_THREADS) {
         const int k = idx / perx, lc = (idx - k * perx) << 2, m = M.bidx[k];
         const bool in = lc < t.Cl;
         const v4f xr = *(const GQ v4f*)(xbase + (in ? ((BR && lc >= t.segp) ? M.off1[m] + lc - t.segp : M.off0[m] + lc) : M.off0[m]));
         *(GQ v4f*)(pend + (long long)(count + k) * pd.stride + pd.Rp + lc) = in ? xr : (v4f){0.f, 0.f, 0.f, 0.f};
       }
-      {
-        const int perd = pd.Rp >> 2, totald = nB * perd;
-        for (int idx = threadIdx.x; idx < totald; idx += AMP_THREADS) {
-          const int k = idx / perd, j = (idx - k * perd) << 2;
-          *(GQ v4f*)(pend + (long long)(count + k) * pd.stride + j) = *(const LDSQ v4f*)(Y + k * ldy + j);   // ldy >= Rp, zero beyond R
-        }
-      }
-      if ((int)threadIdx.x < R)
-        for (int k = 0; k < nB; ++k) accb += Y[k * ldy + threadIdx.x];
-      PHASE(4);
-      if (STREAM)
-        tree_bwd_stream<BR>(ndP, rowoff, t, Y, ldy, M, nB, obase);
-      else
-        tree_bwd_mfma<BR, NRBT, NCGT>(Wl, t, Y, M, nB, obase);
       PHASE(5);
     }
     // what lane k of wave 0 needs of message k for its joins, before the batch's record is given up
@@ -1440,6 +1475,22 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
       const LDSQ float* h = hbuf + k * Hp;
       float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
       int c = 0;
+      // sixteen columns' operands are read together (rows start 16-byte aligned), then multiplied in column order
+      for (; c + 15 < C; c += 16) {
+        v4f wv[4], hv[4];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          wv[g] = *(const LDSQ v4f*)(w + c + 4 * g);
+          hv[g] = *(const LDSQ v4f*)(h + c + 4 * g);
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          a0 = fmaf(wv[g].x, hv[g].x, a0);
+          a1 = fmaf(wv[g].y, hv[g].y, a1);
+          a2 = fmaf(wv[g].z, hv[g].z, a2);
+          a3 = fmaf(wv[g].w, hv[g].w, a3);
+        }
+      }
       for (; c + 3 < C; c += 4) {
         a0 = fmaf(w[c], h[c], a0);
         a1 = fmaf(w[c + 1], h[c + 1], a1);
@@ -1487,7 +1538,18 @@ __device__ __noinline__ void role_tree_out(const GQ AmpDev* D, const GQ WorkerDe
       for (int j = 0; j < NE; ++j)
         if (er[j] >= 0) {
           float a = gacc[j];
-          for (int k = 0; k < n; ++k) a = fmaf(zbuf[k * 64 + er[j]], hbuf[k * Hp + ec[j]], a);
+          int k = 0;
+          for (; k + 7 < n; k += 8) {   // eight messages' operands are read together, then added in ring order
+            float zz[8], hh[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+              zz[q] = zbuf[(k + q) * 64 + er[j]];
+              hh[q] = hbuf[(k + q) * Hp + ec[j]];
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) a = fmaf(zz[q], hh[q], a);
+          }
+          for (; k < n; ++k) a = fmaf(zbuf[k * 64 + er[j]], hbuf[k * Hp + ec[j]], a);
           gacc[j] = a;
         }
       if ((int)threadIdx.x < R)
