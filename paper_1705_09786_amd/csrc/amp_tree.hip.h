@@ -606,46 +606,52 @@ __device__ __forceinline__ void tree_update_apply(LDSQ float* Wl, LDSQ float* bl
 // four.  Lane (i, q) ends up with G[rb*16 + 4q + e][cm*64 + 4i + v] in g[u][v][e].
 // gb = the accumulated bias gradient of tile row threadIdx.x; n_grad = the
 // number of gradients (messages) behind the count pending rows.
-// GU = units a wave holds (NU <= 8 GU), NH = groups of four pending pairs fetched per round: GU * NH = 16 fetches
-// of each kind are in flight per lane.
-template <int NRBT, int NCGT, int GU, int NH>
-__device__ __forceinline__ void tree_update_accumulate(const TreeShape<NRBT, NCGT>& sh, const GQ float* pend, unsigned count,
-                                                       v4f (&g)[TREE_GU][4]) {
-  static_assert(GU * NH == 16 && GU <= TREE_GU, "sixteen fetches per round");
+template <int NRBT, int NCGT>
+__device__ __noinline__ void tree_update_from_pend(LDSQ float* Wl, LDSQ float* bl, const GQ NodeDev* ndp, Tile t,
+                                                   const GQ float* pend, unsigned count, unsigned n_grad, unsigned tstep,
+                                                   const LDSQ int* rowmap, const LDSQ int* colmap, float gb) {
+  const TreeShape<NRBT, NCGT> sh(t);
+  const GQ NodeDev& nd = *ndp;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q = lane >> 4;
   const int NRB = sh.NRB, Rp = NRB * 16, Cp = sh.NCG * 16, stride = Rp + Cp, CM = (Cp + 63) >> 6, NU = NRB * CM;
   const v4f zero = {0.f, 0.f, 0.f, 0.f};
-  int aoff[GU], xoff[GU];
-  bool xin[GU];
+  v4f g[TREE_GU][4];
+  int aoff[TREE_GU], xoff[TREE_GU];
+  bool xin[TREE_GU];
 #pragma unroll
-  for (int u = 0; u < GU; ++u) {
+  for (int u = 0; u < TREE_GU; ++u) {
     const int id = wave + 8 * u < NU ? wave + 8 * u : 0, cm = id / NRB, rb = id - cm * NRB, lc = cm * 64 + 4 * i;
     aoff[u] = rb * 16 + i;
     xin[u] = lc < Cp;
     xoff[u] = Rp + (xin[u] ? lc : 0);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) g[u][v] = zero;
   }
+  constexpr int NH = 4;
   for (unsigned k0 = 0; k0 < count; k0 += 4 * NH) {
     // NH groups of four pending pairs per round, all fetches in flight together
-    float a[NH][GU];
-    v4f x[NH][GU];
+    float a[NH][TREE_GU];
+    v4f x[NH][TREE_GU];
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
       const unsigned k = k0 + 4 * h + q;
       const bool kin = k < count;
       const GQ float* e = pend + (long long)(kin ? k : count - 1) * stride;
 #pragma unroll
-      for (int u = 0; u < GU; ++u) {
+      for (int u = 0; u < TREE_GU; ++u) {
         const float av = e[aoff[u]];
         const v4f xv = *(const GQ v4f*)(e + xoff[u]);
         a[h][u] = kin ? av : 0.f;
         x[h][u] = xin[u] ? xv : zero;
       }
     }
-    asm volatile("" : "+v"(x[0 / GU][0 % GU]), "+v"(x[1 / GU][1 % GU]), "+v"(x[2 / GU][2 % GU]), "+v"(x[3 / GU][3 % GU]), "+v"(x[4 / GU][4 % GU]), "+v"(x[5 / GU][5 % GU]), "+v"(x[6 / GU][6 % GU]), "+v"(x[7 / GU][7 % GU]), "+v"(x[8 / GU][8 % GU]), "+v"(x[9 / GU][9 % GU]), "+v"(x[10 / GU][10 % GU]), "+v"(x[11 / GU][11 % GU]), "+v"(x[12 / GU][12 % GU]), "+v"(x[13 / GU][13 % GU]), "+v"(x[14 / GU][14 % GU]), "+v"(x[15 / GU][15 % GU]));   // all sixteen are in flight before the first product waits for one
+    asm volatile("" : "+v"(x[0][0]), "+v"(x[0][1]), "+v"(x[0][2]), "+v"(x[0][3]), "+v"(x[1][0]), "+v"(x[1][1]), "+v"(x[1][2]),
+                      "+v"(x[1][3]), "+v"(x[2][0]), "+v"(x[2][1]), "+v"(x[2][2]), "+v"(x[2][3]), "+v"(x[3][0]), "+v"(x[3][1]),
+                      "+v"(x[3][2]), "+v"(x[3][3]));
 #pragma unroll
     for (int h = 0; h < NH; ++h)
 #pragma unroll
-      for (int u = 0; u < GU; ++u)
+      for (int u = 0; u < TREE_GU; ++u)
         if (wave + 8 * u < NU) {
           g[u][0] = MFMA(a[h][u], x[h][u].x, g[u][0]);
           g[u][1] = MFMA(a[h][u], x[h][u].y, g[u][1]);
@@ -653,26 +659,6 @@ __device__ __forceinline__ void tree_update_accumulate(const TreeShape<NRBT, NCG
           g[u][3] = MFMA(a[h][u], x[h][u].w, g[u][3]);
         }
   }
-}
-
-template <int NRBT, int NCGT>
-__device__ __noinline__ void tree_update_from_pend(LDSQ float* Wl, LDSQ float* bl, const GQ NodeDev* ndp, Tile t,
-                                                   const GQ float* pend, unsigned count, unsigned n_grad, unsigned tstep,
-                                                   const LDSQ int* rowmap, const LDSQ int* colmap, float gb) {
-  const TreeShape<NRBT, NCGT> sh(t);
-  const GQ NodeDev& nd = *ndp;
-  const int NU = sh.NRB * ((sh.NCG * 16 + 63) >> 6);
-  const v4f zero = {0.f, 0.f, 0.f, 0.f};
-  v4f g[TREE_GU][4];
-#pragma unroll
-  for (int u = 0; u < TREE_GU; ++u)
-#pragma unroll
-    for (int v = 0; v < 4; ++v) g[u][v] = zero;
-  // a tile of up to sixteen units (two per wave) takes thirty-two pending pairs per round, a larger one sixteen
-  if (NU <= 16)
-    tree_update_accumulate<NRBT, NCGT, 2, 8>(sh, pend, count, g);
-  else
-    tree_update_accumulate<NRBT, NCGT, 4, 4>(sh, pend, count, g);
   tree_update_apply<NRBT, NCGT>(Wl, bl, nd, t, sh, g, n_grad, tstep, rowmap, colmap, gb);
 }
 
