@@ -377,13 +377,13 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
       const int rp = amp_round16(nd.nblocks * W->nu), cl = (nd.cols / nd.seg) * nd.segp;
       const bool c19 = amp_round16(cl) == 304;
       if (W->role == ROLE_TREE_LEAF) {
-        if (W->aux) role_tree_cell<false, 0, 0, true>(D, W);
+        if (W->aux == 1) role_tree_cell<false, 0, 0, true>(D, W);
         else if (c19 && rp == 96) role_tree_cell<false, 6, 19, false>(D, W);
         else if (c19 && rp == 64) role_tree_cell<false, 4, 19, false>(D, W);
         else if (c19 && rp == 48) role_tree_cell<false, 3, 19, false>(D, W);
         else role_tree_cell<false, 0, 0, false>(D, W);
       } else {
-        if (W->aux) role_tree_cell<true, 0, 0, true>(D, W);
+        if (W->aux == 1) role_tree_cell<true, 0, 0, true>(D, W);
         else if (c19 && rp == 96) role_tree_cell<true, 6, 19, false>(D, W);
         else if (c19 && rp == 64) role_tree_cell<true, 4, 19, false>(D, W);
         else if (c19 && rp == 48) role_tree_cell<true, 3, 19, false>(D, W);

@@ -217,7 +217,9 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
     case ROLE_TREE_BRANCH: {
       // the largest batch (a multiple of 16 messages) whose pre-activation rows fit beside the weights
       const size_t ldy = amp_ldrow((int)R);
-      if (w.aux && w.role != ROLE_RNN_CELL) {
+      // tree cells: aux 1 = the weights stay in HBM, aux 2 = LDS-resident with the deltas in rows of their own
+      if (w.role != ROLE_RNN_CELL && w.aux == 2) w.aux = 0;
+      if (w.aux == 1 && w.role != ROLE_RNN_CELL) {
         // weights stay in HBM: rows must be 16-byte aligned and unpadded
         if (c->dims.hidden % 4 || c->dims.emb % 4) return 0;
         for (w.kb = 64; w.kb >= 16; w.kb -= 16) {
@@ -233,10 +235,15 @@ size_t lds_floats(const amp_ctx* c, HostWorker& w) {
       const int kb_top = w.role == ROLE_RNN_CELL ? std::min(64, amp_round16(c->max_mak)) : 64;
       for (w.kb = kb_top; w.kb >= 16; w.kb -= 16) {
         f = wfl + r4((size_t)w.kb * ldy) + r4(Rp) + (size_t)(amp_round16(n.cl()) + 63) / 64 * 64;
-        if (w.role != ROLE_RNN_CELL) f += r4((size_t)w.kb * ldy);   // the tree cells keep the deltas in rows of their own
         if (f <= avail) break;
       }
       if (w.kb < 16) return 0;
+      // a tree cell keeps the deltas in rows of their own (waves without a share of the forward product form them
+      // meanwhile) where that costs no batch size
+      if (w.role != ROLE_RNN_CELL && f + r4((size_t)w.kb * ldy) <= avail) {
+        f += r4((size_t)w.kb * ldy);
+        w.aux = 2;
+      }
       if (w.role == ROLE_RNN_CELL) {
         // the lookup's gradient accumulator beside the cell's weights, if it fits (worker aux = 1)
         const size_t lkg = r4((size_t)c->dims.vocab * c->dims.emb);

@@ -1039,7 +1039,8 @@ __device__ __noinline__ void role_tree_cell(const GQ AmpDev* D, const GQ WorkerD
   LDSQ float* Y = (LDSQ float*)L.take(yfloats);   // forward: pre-activations; backward: deltas
   // LDS-resident weights: the deltas have rows of their own, so that waves without a share of the forward product
   // can form them while the others are at it
-  constexpr bool SIDE = !STREAM;
+  // (worker aux = 2: the host found room for them at the same batch size)
+  const bool SIDE = !STREAM && uni(W->aux) == 2;
   LDSQ float* Yd = SIDE ? (LDSQ float*)L.take(yfloats) : Y;
   // node row of a tile row / node column of an LDS column (-1 = padding)
   const int CMW = STREAM ? 0 : ((amp_round16(t.Cl) + 63) >> 6) << 6;
