@@ -44,6 +44,7 @@ AMP_HD static inline int amp_ldrow(int cols) {
 #define ABORT_WATCHDOG 1u
 #define ABORT_LOG_FULL 2u
 #define ABORT_BAD_STATE 3u
+#define ABORT_PLACEMENT 4u   // a packed launch found a workgroup on another die than its block index implies
 
 enum AmpRole {
   ROLE_CTRL = 0,

@@ -355,8 +355,26 @@ extern "C" __global__ void __launch_bounds__(AMP_THREADS) amp_persistent(const A
     s_log_ptr = W->log;
     for (int i = 0; i < AMP_NSTAT; ++i) s_stat[i] = 0;
     t_begin = wall_clock64();
+    // packed: the whole replica shares one L2 if block b really runs on die b % 8 (hardware register XCC_ID, id 20,
+    // bits 3:0); releases then skip the L2 write-back.  A workgroup that finds itself elsewhere stops the replica
+    // before it has exchanged anything.
+    s_nowb = 0;
+    if (xcd_packed) {
+      const int xcc = (int)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xf);
+      if (xcc == (int)(blockIdx.x & 7))
+        s_nowb = 1;
+      else
+        s_nowb = -1;
+    }
   }
   __syncthreads();
+  if (s_nowb < 0) {
+    if (threadIdx.x == 0) {
+      raise_abort(D, ABORT_PLACEMENT, blockIdx.x);
+      W->stats[12] = (unsigned long long)(__builtin_amdgcn_s_getreg((3 << 11) | 20) & 0xf);
+    }
+    return;
+  }
   switch (W->role) {
     case ROLE_CTRL: role_ctrl(D, W); break;
     case ROLE_MLP_LIN: role_mlp_lin(D, W); break;
@@ -447,9 +465,11 @@ extern "C" hipError_t amp_launch(const AmpDev* devs, int n_replicas, int workers
     attr_set = true;
   }
   // One XCD has 32 CUs: the packed mapping needs the replicas that share an XCD to fit it.  Measured: replicas
-  // gain from staying inside one L2 (15 Tree-LSTM replicas 184k -> 256k trees/s); a single pipeline of many
-  // workers is faster spread over all eight L2s (16 workers 28.5k against 25.5k packed), one of few workers
-  // faster packed (the 4-worker MLP 52k -> 55k instances/s).
+  // gain from staying inside one L2 (15 Tree-LSTM replicas 184k -> 256k trees/s), and again from releases without
+  // an L2 write-back, which only a packed replica can do (16 replicas 316k -> 409k trees/s); a single pipeline of
+  // many workers is faster spread over all eight L2s (30 tree workers 42.8k against 40.3k packed, 17 graph workers
+  // 21.7k against 21.3k), one of few
+  // workers faster packed (the 4-worker MLP 52k -> 55k instances/s).
   const int per_xcd = (n_replicas + 7) / 8;
   const bool packed = per_xcd * workers_per_replica <= 32 && (n_replicas > 1 || workers_per_replica <= 8);
   const int grid = packed ? 8 * per_xcd * workers_per_replica : n_replicas * workers_per_replica;

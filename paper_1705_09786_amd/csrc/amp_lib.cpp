@@ -1448,7 +1448,8 @@ int launch_once(amp_ctx* c, const Resident& res, size_t out_begin, int epochs, b
       const unsigned why_code = ctl[8 * r];
       const char* why = why_code == ABORT_WATCHDOG ? "a worker waited longer than the watchdog allows"
                         : why_code == ABORT_LOG_FULL ? "event record full"
-                                                     : "inconsistent state";
+                        : why_code == ABORT_PLACEMENT ? "a workgroup of a packed launch ran on another die than its block index implies"
+                                                      : "inconsistent state";
       c->state_zeroed = false;   // device state is unreliable after an aborted run
       for (HostNode& n : c->nodes) n.dirty = true;
       return fail(c, AMP_EDEVICE, "kernel stopped itself: %s (replica %d, worker %u)", why, r, ctl[8 * r + 2]);
