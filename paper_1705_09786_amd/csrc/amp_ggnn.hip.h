@@ -653,8 +653,18 @@ __device__ __forceinline__ void g_pend_append(GQ float* pend, int Rp, int stride
     const v4f v = j < Rp ? *(const LDSQ v4f*)(Dl + k * ldd + j) : *(const LDSQ v4f*)(X + k * ldx + j - Rp);
     *(GQ v4f*)(pend + (long long)(first + k) * stride + j) = v;
   }
-  if ((int)threadIdx.x < R)
-    for (int k = 0; k < K; ++k) gb += Dl[k * ldd + threadIdx.x];
+  if ((int)threadIdx.x < R) {
+    // eight rows' entries are read together; the sum keeps the rows' order
+    int k = 0;
+    for (; k + 7 < K; k += 8) {
+      float d[8];
+#pragma unroll
+      for (int a = 0; a < 8; ++a) d[a] = Dl[(k + a) * ldd + threadIdx.x];
+#pragma unroll
+      for (int a = 0; a < 8; ++a) gb += d[a];
+    }
+    for (; k < K; ++k) gb += Dl[k * ldd + threadIdx.x];
+  }
 }
 
 // Counts nmsg gradients (grouped messages, K rows in all, already appended to the pending list) and updates when
