@@ -237,7 +237,8 @@ int amp_set_weights_in_hbm(amp_ctx *ctx, int node_id, int on);
  * instances in flight; at the end of every epoch each node's parameters are
  * set to the mean over its replicas (optimizer slots are not shared).  1
  * (default) = no replication; at most 128.  Workers x replicas must not exceed
- * the CUs.
+ * the CUs.  When the replicas that share an XCD fit its 32 CUs, every replica
+ * is placed inside one XCD and exchanges its messages through that XCD's L2.
  * Evaluation uses the first replica.  Event records and worker statistics
  * list replica 0's workers first, then replica 1's, ...; `seq` counts
  * admissions per replica.  Only before amp_finalize. */
@@ -254,7 +255,8 @@ int amp_set_replicas(amp_ctx *ctx, int n_replicas);
  * gradients return to that copy.  The output layer and the loss are shared
  * and see every instance.  At the end of every training epoch the copies'
  * parameters are set to their mean (the paper's infrequent synchronisation;
- * its asynchronous trigger of a group synchronisation is not built).
+ * amp_set_group_sync adds its asynchronous trigger of a group
+ * synchronisation while training runs).
  * amp_set_params / amp_set_min_update_frequency / amp_set_optimizer on node 0
  * or 1 apply to every copy; amp_get_params on them reads copy 0; the copies'
  * own ids work too, and event records name them.  1 (default) = no copies; at
@@ -375,7 +377,8 @@ int amp_set_watchdog(amp_ctx *ctx, double seconds);
  * max_active_keys instances in flight, every parameterized node accumulates
  * the gradients that reach it and applies its own update once
  * min_update_frequency of them have arrived, with no synchronisation between
- * nodes.  AMP_EDEVICE if the kernel stopped itself (watchdog, record full). */
+ * nodes.  AMP_EDEVICE if the kernel stopped itself (watchdog, record full, or a
+ * launch that packs whole replicas into single XCDs found a workgroup on another die than its index implies). */
 int amp_train(amp_ctx *ctx, int epochs);
 /* Blocking: forward-only pass over the evaluation set with the present
  * parameters (Section 1: inference runs through the same graph; Table 2's
