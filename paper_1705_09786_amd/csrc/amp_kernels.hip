@@ -468,10 +468,11 @@ extern "C" hipError_t amp_launch(const AmpDev* devs, int n_replicas, int workers
   // gain from staying inside one L2 (15 Tree-LSTM replicas 184k -> 256k trees/s), and again from releases without
   // an L2 write-back, which only a packed replica can do (16 replicas 316k -> 409k trees/s); a single pipeline of
   // many workers is faster spread over all eight L2s (30 tree workers 42.8k against 40.3k packed, 17 graph workers
-  // 21.7k against 21.3k), one of few
-  // workers faster packed (the 4-worker MLP 52k -> 55k instances/s).
+  // 21.7k against 21.3k, 16 tree workers 29.5k against 28.6k), one of few
+  // workers faster packed (the 4-worker MLP 52k -> 55k instances/s; the RNN with eight copies of its cell, 10
+  // workers, 105k -> 112k sequences/s; the unsplit 10-worker graph pipeline the same either way): up to 12.
   const int per_xcd = (n_replicas + 7) / 8;
-  const bool packed = per_xcd * workers_per_replica <= 32 && (n_replicas > 1 || workers_per_replica <= 8);
+  const bool packed = per_xcd * workers_per_replica <= 32 && (n_replicas > 1 || workers_per_replica <= 12);
   const int grid = packed ? 8 * per_xcd * workers_per_replica : n_replicas * workers_per_replica;
   hipLaunchKernelGGL(amp_persistent, dim3(grid), dim3(AMP_THREADS), AMP_DYN_LDS_BYTES, stream, devs, workers_per_replica,
                      n_replicas, packed ? 1 : 0);
