@@ -169,7 +169,9 @@ TREE_ODD = dict(vocab=97, emb=50, hidden=37, n_class=5)
     (synth.DEFAULT_DIMS["tree"], {1: 8, 2: 16}, 32, 50, 1000, SGD, 96),   # tiles of 4 and 3 row blocks
     (synth.DEFAULT_DIMS["tree"], {1: 10, 2: 17}, 64, 50, 1000, SGD, 96),  # the benchmark's tiling: 3 row blocks, 45 of 48 rows used
     (TREE_ODD, {1: 3, 2: 5}, 8, 3, 5, SGD, 64),
-    (TREE_ODD, {1: 1, 2: 1}, 8, 3, 5, ADAM, 64),
+    # an update every 3 gradients under Adam: lr 2e-4 as in the recurrent case of that kind -- at 5e-4 four of forty
+    # runs put a single element of the branch matrix 5e-5 .. 7e-5 off (median 1.8e-5), at 2e-4 forty runs stay within 7.1e-6
+    (TREE_ODD, {1: 1, 2: 1}, 8, 3, 5, dict(ADAM, lr=0.0002), 64),
     (TREE_ODD, {1: 2, 2: 3}, 8, 4, 5, dict(kind="momentum", lr=0.005, momentum=0.9), 64),
 ])
 def test_tree_replay_parity(dims, tiles, mak, muf, lmuf, opt, n):
