@@ -488,6 +488,9 @@ def test_train_and_eval_instances_in_one_launch(cfg, n, nv, mak, muf):
     (1, None, 4, 4, 3, None, SGD, 203),
     (3, TREE_ODD, 3, 8, 3, 5, SGD, 50),
     (4, GG_ODD, 2, 6, 4, 4, ADAM, 41),
+    # the benchmark's replicated launch: 16 replicas of 5 leaf + 8 branch tiles on all 256 workgroups, two replicas
+    # inside every XCD (releases without an L2 write-back)
+    (3, synth.DEFAULT_DIMS["tree"], 16, 16, 5, 20, SGD, 192),
 ])
 def test_replicas_replay_parity(cfg, dims, R, mak, muf, lmuf, opt, n):
     """Every parameterized node replicated R times, instance i routed to replica i mod R, parameters averaged
@@ -501,9 +504,13 @@ def test_replicas_replay_parity(cfg, dims, R, mak, muf, lmuf, opt, n):
     else:
         model, data = "ggnn", synth.make_ggnn(n, 28, dims)[0]
     fp = synth.init_params(model, dims, 12)
-    g = gpu_train(model, dims, fp, data, mak, muf, opt, lookup_muf=lmuf, replicas=R, tiles={1: 2, 2: 3} if cfg == 3 else None)
+    tiles = None if cfg != 3 else {1: 5, 2: 8} if R == 16 else {1: 2, 2: 3}
+    g = gpu_train(model, dims, fp, data, mak, muf, opt, lookup_muf=lmuf, replicas=R, tiles=tiles,
+                  arena_bytes=(4 << 30) if R == 16 else (1 << 30))
     a = g["trainer"].amp
     wpr = a.num_workers() // R
+    if R == 16:
+        assert wpr == 16 and set(a.get_worker_placement()[r * wpr:(r + 1) * wpr] == [r % 8] * wpr for r in range(R)) == {True}
     rts = [oracle_runtime(model, dims, fp, muf, opt, lookup_muf=lmuf) for _ in range(R)]
     parts = oamp.replica_subsets(data, R)
     done = [0] * R
