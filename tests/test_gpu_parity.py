@@ -491,6 +491,8 @@ def test_train_and_eval_instances_in_one_launch(cfg, n, nv, mak, muf):
     # the benchmark's replicated launch: 16 replicas of 5 leaf + 8 branch tiles on all 256 workgroups, two replicas
     # inside every XCD (releases without an L2 write-back)
     (3, synth.DEFAULT_DIMS["tree"], 16, 16, 5, 20, SGD, 192),
+    # and the graph model's: 24 replicas of the unsplit 10-worker pipeline, three inside every XCD
+    (4, synth.DEFAULT_DIMS["ggnn"], 24, 8, 4, 4, dict(kind="sgd", lr=0.01), 192),
 ])
 def test_replicas_replay_parity(cfg, dims, R, mak, muf, lmuf, opt, n):
     """Every parameterized node replicated R times, instance i routed to replica i mod R, parameters averaged
@@ -506,11 +508,11 @@ def test_replicas_replay_parity(cfg, dims, R, mak, muf, lmuf, opt, n):
     fp = synth.init_params(model, dims, 12)
     tiles = None if cfg != 3 else {1: 5, 2: 8} if R == 16 else {1: 2, 2: 3}
     g = gpu_train(model, dims, fp, data, mak, muf, opt, lookup_muf=lmuf, replicas=R, tiles=tiles,
-                  arena_bytes=(4 << 30) if R == 16 else (1 << 30))
+                  arena_bytes=(4 << 30) if R >= 16 else (1 << 30))
     a = g["trainer"].amp
     wpr = a.num_workers() // R
-    if R == 16:
-        assert wpr == 16 and set(a.get_worker_placement()[r * wpr:(r + 1) * wpr] == [r % 8] * wpr for r in range(R)) == {True}
+    if R >= 16:
+        assert wpr == (16 if cfg == 3 else 10) and set(a.get_worker_placement()[r * wpr:(r + 1) * wpr] == [r % 8] * wpr for r in range(R)) == {True}
     rts = [oracle_runtime(model, dims, fp, muf, opt, lookup_muf=lmuf) for _ in range(R)]
     parts = oamp.replica_subsets(data, R)
     done = [0] * R
